@@ -1,0 +1,469 @@
+/*
+ * CPU oracle for DistSim's strategy evaluation.  TEST INFRASTRUCTURE ONLY.
+ *
+ * This file is the yardstick the GPU library is compared with.  It is called by
+ * the tests, by the smoke check and by the benchmark's CPU-baseline leg, and by
+ * nothing else; the product path never routes through it.  It shares no code,
+ * header, table or helper with the HIP sources.
+ *
+ * What it is: a plain priority-queue discrete-event simulation, one candidate
+ * strategy at a time, that follows DistSim's hierarchical modelling (Sec. 4.3)
+ * in the paper's order:
+ *
+ *   1. model-parallel modelling  -- every layer is mapped to its (composed)
+ *      event: one computation event when MP = 1, a computation event followed
+ *      by an all-reduce event when MP > 1 (Sec. 4.3, "Model Parallelism
+ *      Modeling").  A layer with all-to-all bytes gets one more communication
+ *      event per pass (workload extension, not in the paper).
+ *   2. pipeline modelling (Algorithm 1) -- walk the schedule S: a device takes
+ *      the next stage-task of ITS OWN ordered list as soon as it is idle and
+ *      the task's input has arrived ("data is prepared and micro-batch index is
+ *      matched"); the task's events run back to back; when it ends, the
+ *      point-to-point event towards the neighbouring stage is appended at
+ *      t + elapsed.  GPipe and Dapple (early-backward, "1F1B") orders are built
+ *      explicitly as per-device lists.
+ *   3. data-parallel modelling -- the lists are identical for every DP replica;
+ *      an all-reduce event sized by the gradient bytes is appended at the end
+ *      of each device's list (Sec. 4.3, "Data Parallelism Modeling").  With a
+ *      bucket size the gradient all-reduce is split into buckets that start as
+ *      soon as the last micro-batch's backward has produced their bytes
+ *      (extension; bucket = 0 gives the paper's single trailing event).
+ *   4. analysis -- batch (iteration) time = time of the last event; per-stage
+ *      computation / communication busy time = sum of the durations of the
+ *      events on that device's list; utilisation = busy / batch (Sec. 3.2,
+ *      Sec. 5).
+ *
+ * Only one device per pipeline stage is simulated: Algorithm 1 appends the same
+ * entries to all MP devices of a stage, and DP replicas are duplicates.
+ *
+ * Collective costs (all integer, truncating division, evaluated exactly in this
+ * order; link class k = 0 intra-node, 1 inter-node):
+ *   p2p(bytes,k)     = alpha_k + bytes / beta_k
+ *   allreduce(n,P,k) = alpha_k + (2*(n-1)*P) / (n*beta_k)      ring volume 2(N-1)P/N, Sec. 4.2
+ *   alltoall(n,P,k)  = alpha_k + ((n-1)*P) / (n*beta_k)
+ * A collective over n = 1 ranks or over 0 bytes is not an event.  Collectives
+ * are intra-node iff n <= gpus_per_node (the paper's "8 or fewer" split); a
+ * stage boundary s|s+1 is intra-node iff floor(s*tp*dp/g) == floor((s+1)*tp*dp/g)
+ * (ranks ordered tp fastest, then dp, then pp; Sec. 4.1's intra/inter attribute).
+ *
+ * Parity pins for every function here live in tests/test_oracle_*.py (closed
+ * forms, hand-worked examples in tests/golden, brute-force longest path,
+ * invariants, metamorphic relations).  Agreement with the paper's *measured*
+ * batch times (Sec. 5) is parity unpinned: it needs the authors' profiled event
+ * times and cluster traces.
+ */
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+#define ST_OK 0
+#define ST_INVALID 1
+#define ST_RANGE 2
+#define MAX_PP 64   /* interface limit of the evaluated library; larger pp is reported invalid */
+
+enum { EV_TASK_DONE = 0, EV_ARRIVE_F = 1, EV_ARRIVE_B = 2, EV_GRAD_READY = 3, EV_AR_DONE = 4 };
+
+typedef struct {
+    int64_t t;
+    int64_t seq;
+    int32_t kind, stage, mb, layer;
+} event_t;
+
+typedef struct {
+    event_t *a;
+    int64_t n, cap, seq;
+} heap_t;
+
+static int ev_less(const event_t *x, const event_t *y) {
+    if (x->t != y->t) return x->t < y->t;
+    return x->seq < y->seq;
+}
+
+static void heap_push(heap_t *h, int64_t t, int kind, int stage, int mb, int layer) {
+    if (h->n == h->cap) {
+        h->cap = h->cap ? 2 * h->cap : 1024;
+        h->a = (event_t *)realloc(h->a, (size_t)h->cap * sizeof(event_t));
+    }
+    event_t e = { t, h->seq++, kind, stage, mb, layer };
+    int64_t i = h->n++;
+    while (i > 0) {
+        int64_t p = (i - 1) / 2;
+        if (!ev_less(&e, &h->a[p])) break;
+        h->a[i] = h->a[p];
+        i = p;
+    }
+    h->a[i] = e;
+}
+
+static event_t heap_pop(heap_t *h) {
+    event_t top = h->a[0];
+    event_t e = h->a[--h->n];
+    int64_t i = 0;
+    for (;;) {
+        int64_t c = 2 * i + 1;
+        if (c >= h->n) break;
+        if (c + 1 < h->n && ev_less(&h->a[c + 1], &h->a[c])) c++;
+        if (!ev_less(&h->a[c], &e)) break;
+        h->a[i] = h->a[c];
+        i = c;
+    }
+    if (h->n > 0) h->a[i] = e;
+    return top;
+}
+
+/* ---- collective cost events ------------------------------------------------------- */
+
+typedef struct {
+    int32_t num_devices, gpus_per_node;
+    int64_t alpha[2], beta[2];
+    int64_t bucket;
+} cluster_t;
+
+static int64_t p2p_ns(const cluster_t *cl, int64_t bytes, int k) {
+    return cl->alpha[k] + (int64_t)((uint64_t)bytes / (uint64_t)cl->beta[k]);
+}
+
+static int64_t allreduce_ns(const cluster_t *cl, int64_t n, int64_t bytes) {
+    if (n <= 1 || bytes <= 0) return 0;
+    int k = n <= cl->gpus_per_node ? 0 : 1;
+    return cl->alpha[k] + (int64_t)((2ull * (uint64_t)(n - 1) * (uint64_t)bytes) / ((uint64_t)n * (uint64_t)cl->beta[k]));
+}
+
+static int64_t alltoall_ns(const cluster_t *cl, int64_t n, int64_t bytes) {
+    if (n <= 1 || bytes <= 0) return 0;
+    int k = n <= cl->gpus_per_node ? 0 : 1;
+    return cl->alpha[k] + (int64_t)(((uint64_t)(n - 1) * (uint64_t)bytes) / ((uint64_t)n * (uint64_t)cl->beta[k]));
+}
+
+/* ---- one candidate ---------------------------------------------------------------- */
+
+typedef struct {
+    int32_t L, V;
+    const int32_t *variant_tp;
+    const int64_t *fc, *bc, *fa, *ba, *act, *grad, *a2a;
+} costs_t;
+
+typedef struct {          /* per-thread scratch, grown on demand */
+    heap_t heap;
+    uint8_t *task_kind;   /* [pp][2m] 0 = forward, 1 = backward */
+    int32_t *task_mb;     /* [pp][2m] */
+    uint8_t *arrF, *arrB; /* [pp][m] input of F(s,j) / B(s,j) has arrived */
+    int64_t cap_tasks, cap_arr;
+} scratch_t;
+
+typedef struct {
+    int32_t status;
+    int64_t batch_ns, num_events;
+} result_t;
+
+static void build_schedule(int pp, int m, int sched, uint8_t *kind, int32_t *mb) {
+    for (int s = 0; s < pp; s++) {
+        uint8_t *k = kind + (int64_t)s * 2 * m;
+        int32_t *j = mb + (int64_t)s * 2 * m;
+        int n = 0;
+        if (sched == 0) {                 /* GPipe: all forwards, then all backwards, FIFO */
+            for (int i = 0; i < m; i++) { k[n] = 0; j[n++] = i; }
+            for (int i = 0; i < m; i++) { k[n] = 1; j[n++] = i; }
+        } else {                          /* Dapple / 1F1B: warm-up, one-forward-one-backward, cool-down */
+            int w = pp - 1 - s;
+            if (w > m) w = m;
+            int f = 0, b = 0;
+            for (int i = 0; i < w; i++) { k[n] = 0; j[n++] = f++; }
+            while (f < m) {
+                k[n] = 0; j[n++] = f++;
+                k[n] = 1; j[n++] = b++;
+            }
+            while (b < m) { k[n] = 1; j[n++] = b++; }
+        }
+    }
+}
+
+static void simulate_one(const costs_t *co, const cluster_t *cl,
+                         int32_t dp, int32_t tp, int32_t pp, int32_t m, int sched,
+                         const uint8_t *bnd_in /* NULL = uniform */,
+                         scratch_t *sc, result_t *res,
+                         int64_t *comp_busy, int64_t *comm_busy, double *util, /* [pp] or NULL */
+                         int64_t *tl_start, int64_t *tl_end /* [2][pp][m] or NULL */) {
+    const int L = co->L;
+    res->status = ST_INVALID;
+    res->batch_ns = INT64_MAX;
+    res->num_events = 0;
+
+    /* --- validation ("unreachable" configurations, Sec. 6) --- */
+    if (dp < 1 || tp < 1 || pp < 1 || m < 1 || (sched != 0 && sched != 1)) return;
+    if ((int64_t)dp * tp * pp != cl->num_devices) return;
+    if (pp > L || pp > MAX_PP) return;
+    int v = -1;
+    for (int i = 0; i < co->V; i++) if (co->variant_tp[i] == tp) { v = i; break; }
+    if (v < 0) return;
+    int bnd[257];
+    if (bnd_in) {
+        for (int s = 0; s <= pp; s++) bnd[s] = bnd_in[s];
+        if (bnd[0] != 0 || bnd[pp] != L) return;
+        for (int s = 0; s < pp; s++) if (bnd[s + 1] <= bnd[s]) return;
+    } else {
+        for (int s = 0; s <= pp; s++) bnd[s] = (int)(((int64_t)s * L) / pp);
+    }
+    const int64_t *fc = co->fc + (int64_t)v * L, *bc = co->bc + (int64_t)v * L;
+    const int64_t *fa = co->fa + (int64_t)v * L, *ba = co->ba + (int64_t)v * L;
+    const int64_t *act = co->act + (int64_t)v * L, *grad = co->grad + (int64_t)v * L;
+    const int64_t *a2a = co->a2a + (int64_t)v * L;
+
+    /* --- point-to-point events of every stage boundary --- */
+    int64_t pf[256], pb[256];      /* pf[s]: s -> s+1 activation; pb[s]: s -> s-1 gradient */
+    const int64_t g = cl->gpus_per_node;
+    for (int s = 0; s < pp; s++) { pf[s] = 0; pb[s] = 0; }
+    for (int s = 0; s + 1 < pp; s++) {
+        int64_t na = ((int64_t)s * tp * dp) / g, nb = ((int64_t)(s + 1) * tp * dp) / g;
+        int k = na == nb ? 0 : 1;
+        int64_t bytes = act[bnd[s + 1] - 1];
+        pf[s] = p2p_ns(cl, bytes, k);
+        pb[s + 1] = p2p_ns(cl, bytes, k);
+    }
+
+    /* --- range guard: every timestamp of the pipeline phase is below 2^53 --- */
+    {
+        unsigned __int128 t1 = 0;
+        for (int s = 0; s < pp; s++) {
+            for (int l = bnd[s]; l < bnd[s + 1]; l++) {
+                t1 += (unsigned __int128)(fc[l] + bc[l]);
+                if (tp > 1) t1 += (unsigned __int128)(fa[l] + ba[l]);
+                t1 += 2 * (unsigned __int128)alltoall_ns(cl, dp, a2a[l]);
+            }
+            t1 += (unsigned __int128)(pf[s] + pb[s]);
+        }
+        if (t1 * (unsigned __int128)m >= ((unsigned __int128)1 << 53)) { res->status = ST_RANGE; return; }
+    }
+    res->status = ST_OK;
+
+    /* --- scratch --- */
+    int64_t ntask = (int64_t)pp * 2 * m, narr = (int64_t)pp * m;
+    if (ntask > sc->cap_tasks) {
+        sc->cap_tasks = ntask;
+        sc->task_kind = (uint8_t *)realloc(sc->task_kind, (size_t)ntask);
+        sc->task_mb = (int32_t *)realloc(sc->task_mb, (size_t)ntask * sizeof(int32_t));
+    }
+    if (narr > sc->cap_arr) {
+        sc->cap_arr = narr;
+        sc->arrF = (uint8_t *)realloc(sc->arrF, (size_t)narr);
+        sc->arrB = (uint8_t *)realloc(sc->arrB, (size_t)narr);
+    }
+    memset(sc->arrF, 0, (size_t)narr);
+    memset(sc->arrB, 0, (size_t)narr);
+    build_schedule(pp, m, sched, sc->task_kind, sc->task_mb);
+
+    heap_t *h = &sc->heap;
+    h->n = 0; h->seq = 0;
+
+    int32_t next[256];
+    uint8_t busy[256];
+    int64_t cb[256], mb_[256];          /* computation / communication busy */
+    int64_t comm_free[256], acc[256];   /* DP communication stream, open bucket bytes */
+    for (int s = 0; s < pp; s++) { next[s] = 0; busy[s] = 0; cb[s] = 0; mb_[s] = 0; comm_free[s] = 0; acc[s] = 0; }
+    int64_t nev = 0, now = 0;
+    const int64_t cap = cl->bucket;
+
+/* start the next task of stage s if the device is idle and the input is there */
+#define TRY_START(s_) do {                                                              \
+        int s__ = (s_);                                                                 \
+        if (!busy[s__] && next[s__] < 2 * m) {                                          \
+            int64_t ti = (int64_t)s__ * 2 * m + next[s__];                              \
+            int kd = sc->task_kind[ti], j = sc->task_mb[ti];                            \
+            int ready = kd == 0 ? (s__ == 0 || sc->arrF[(int64_t)s__ * m + j])          \
+                                : (s__ == pp - 1 || sc->arrB[(int64_t)s__ * m + j]);    \
+            if (ready) {                                                                \
+                busy[s__] = 1;                                                          \
+                int64_t t = now;                                                        \
+                if (tl_start) tl_start[((int64_t)kd * pp + s__) * m + j] = t;           \
+                int last_bwd = (kd == 1 && next[s__] == 2 * m - 1);                     \
+                if (kd == 0) {                                                          \
+                    for (int l = bnd[s__]; l < bnd[s__ + 1]; l++) {                     \
+                        t += fc[l]; cb[s__] += fc[l];                                   \
+                        if (tp > 1) { t += fa[l]; mb_[s__] += fa[l]; }                  \
+                        int64_t x = alltoall_ns(cl, dp, a2a[l]);                        \
+                        t += x; mb_[s__] += x;                                          \
+                    }                                                                   \
+                } else {                                                                \
+                    for (int l = bnd[s__ + 1] - 1; l >= bnd[s__]; l--) {                \
+                        t += bc[l]; cb[s__] += bc[l];                                   \
+                        if (tp > 1) { t += ba[l]; mb_[s__] += ba[l]; }                  \
+                        int64_t x = alltoall_ns(cl, dp, a2a[l]);                        \
+                        t += x; mb_[s__] += x;                                          \
+                        if (last_bwd && cap > 0 && dp > 1)                              \
+                            heap_push(h, t, EV_GRAD_READY, s__, j, l);                  \
+                    }                                                                   \
+                }                                                                       \
+                heap_push(h, t, EV_TASK_DONE, s__, j, kd);                              \
+            }                                                                           \
+        }                                                                               \
+    } while (0)
+
+    for (int s = 0; s < pp; s++) TRY_START(s);       /* t = 0: start of the first stage's first event */
+
+    while (h->n > 0) {
+        event_t e = heap_pop(h);
+        now = e.t;
+        int s = e.stage;
+        switch (e.kind) {
+        case EV_TASK_DONE: {
+            int kd = e.layer, j = e.mb;
+            nev++;
+            if (tl_end) tl_end[((int64_t)kd * pp + s) * m + j] = now;
+            busy[s] = 0;
+            next[s]++;
+            if (kd == 0 && s + 1 < pp) {            /* (e_comm, t + e.elapsed, m) of Algorithm 1 */
+                heap_push(h, now + pf[s], EV_ARRIVE_F, s + 1, j, 0);
+                mb_[s] += pf[s]; nev++;
+            }
+            if (kd == 1 && s > 0) {
+                heap_push(h, now + pb[s], EV_ARRIVE_B, s - 1, j, 0);
+                mb_[s] += pb[s]; nev++;
+            }
+            if (next[s] == 2 * m && dp > 1 && cap == 0) {   /* trailing gradient all-reduce */
+                int64_t G = 0;
+                for (int l = bnd[s]; l < bnd[s + 1]; l++) G += grad[l];
+                if (G > 0) {
+                    int64_t d = allreduce_ns(cl, dp, G);
+                    heap_push(h, now + d, EV_AR_DONE, s, 0, 0);
+                    mb_[s] += d;
+                }
+            }
+            TRY_START(s);
+            break;
+        }
+        case EV_ARRIVE_F:
+            sc->arrF[(int64_t)s * m + e.mb] = 1;
+            TRY_START(s);
+            break;
+        case EV_ARRIVE_B:
+            sc->arrB[(int64_t)s * m + e.mb] = 1;
+            TRY_START(s);
+            break;
+        case EV_GRAD_READY: {                        /* bucketed, overlapped gradient all-reduce */
+            acc[s] += grad[e.layer];
+            while (acc[s] >= cap) {
+                int64_t d = allreduce_ns(cl, dp, cap);
+                int64_t st = comm_free[s] > now ? comm_free[s] : now;
+                comm_free[s] = st + d;
+                heap_push(h, comm_free[s], EV_AR_DONE, s, 0, 0);
+                mb_[s] += d;
+                acc[s] -= cap;
+            }
+            if (e.layer == bnd[s] && acc[s] > 0) {   /* the stage's first layer finishes last */
+                int64_t d = allreduce_ns(cl, dp, acc[s]);
+                int64_t st = comm_free[s] > now ? comm_free[s] : now;
+                comm_free[s] = st + d;
+                heap_push(h, comm_free[s], EV_AR_DONE, s, 0, 0);
+                mb_[s] += d;
+                acc[s] = 0;
+            }
+            break;
+        }
+        case EV_AR_DONE:
+            nev++;
+            break;
+        }
+    }
+#undef TRY_START
+
+    res->batch_ns = now;
+    res->num_events = nev;
+    for (int s = 0; s < pp; s++) {
+        if (comp_busy) comp_busy[s] = cb[s];
+        if (comm_busy) comm_busy[s] = mb_[s];
+        if (util) util[s] = now > 0 ? (double)cb[s] / (double)now : 0.0;
+    }
+}
+
+/* ---- entry points (plain C ABI for ctypes; all pointers are host memory) ---------- */
+
+/* Per-candidate outputs: status, batch_ns, num_events [C]; stage_off [C+1] is written here
+ * (exclusive prefix of pp over candidates with status 0); comp/comm/util are ragged
+ * arrays indexed stage_off[c] + s and must hold sum(pp) entries. */
+int oracle_simulate(int32_t L, int32_t V, const int32_t *variant_tp,
+                    const int64_t *fc, const int64_t *bc, const int64_t *fa, const int64_t *ba,
+                    const int64_t *act, const int64_t *grad, const int64_t *a2a,
+                    int32_t num_devices, int32_t gpus_per_node,
+                    const int64_t *alpha2, const int64_t *beta2, int64_t bucket,
+                    int64_t C, const int32_t *dp, const int32_t *tp, const int32_t *pp, const int32_t *m,
+                    const uint8_t *schedule, const int64_t *part_off, const uint8_t *part_pool,
+                    int32_t *status, int64_t *batch_ns, int64_t *num_events, int64_t *stage_off,
+                    int64_t *comp_busy, int64_t *comm_busy, double *util,
+                    int64_t *tl_start, int64_t *tl_end, int32_t nthreads) {
+    if (L < 1 || V < 1 || C < 0 || beta2[0] < 1 || beta2[1] < 1 || gpus_per_node < 1) return -1;
+    costs_t co = { L, V, variant_tp, fc, bc, fa, ba, act, grad, a2a };
+    cluster_t cl = { num_devices, gpus_per_node, { alpha2[0], alpha2[1] }, { beta2[0], beta2[1] }, bucket };
+
+    /* Each candidate is simulated into a temporary of its own; the ragged outputs are
+     * packed afterwards, once the prefix of the slot counts is known. */
+    int64_t *slots = (int64_t *)calloc((size_t)C + 1, sizeof(int64_t));
+    if (nthreads < 1) nthreads = 1;
+    int64_t **tmp_c = (int64_t **)calloc((size_t)C, sizeof(int64_t *));
+#pragma omp parallel num_threads(nthreads)
+    {
+        scratch_t sc;
+        memset(&sc, 0, sizeof sc);
+#pragma omp for schedule(dynamic, 8)
+        for (int64_t c = 0; c < C; c++) {
+            int p = pp[c];
+            int64_t *buf = NULL;
+            if (p >= 1 && p <= MAX_PP) buf = (int64_t *)malloc((size_t)p * 3 * sizeof(int64_t));
+            result_t r;
+            const uint8_t *b = part_off[c] >= 0 ? part_pool + part_off[c] : NULL;
+            simulate_one(&co, &cl, dp[c], tp[c], p, m[c], schedule[c], b, &sc, &r,
+                         buf, buf ? buf + p : NULL, buf ? (double *)(buf + 2 * p) : NULL,
+                         C == 1 ? tl_start : NULL, C == 1 ? tl_end : NULL);
+            status[c] = r.status;
+            batch_ns[c] = r.batch_ns;
+            num_events[c] = r.num_events;
+            slots[c] = r.status == ST_OK ? p : 0;
+            if (r.status != ST_OK) { free(buf); buf = NULL; }
+            tmp_c[c] = buf;
+        }
+        free(sc.heap.a); free(sc.task_kind); free(sc.task_mb); free(sc.arrF); free(sc.arrB);
+    }
+    int64_t off = 0;
+    for (int64_t c = 0; c < C; c++) {
+        stage_off[c] = off;
+        int64_t p = slots[c];
+        if (p) {
+            memcpy(comp_busy + off, tmp_c[c], (size_t)p * 8);
+            memcpy(comm_busy + off, tmp_c[c] + p, (size_t)p * 8);
+            if (util) memcpy(util + off, tmp_c[c] + 2 * p, (size_t)p * 8);
+            free(tmp_c[c]);
+        }
+        off += p;
+    }
+    stage_off[C] = off;
+    free(tmp_c);
+    free(slots);
+    return 0;
+}
+
+/* Grid-search step (Sec. 6): index of the best candidate, ties to the lowest index.
+ * objective 0: smallest batch_ns.  objective 1: smallest batch_ns / weight (time per sample),
+ * compared exactly as batch_a * w_b < batch_b * w_a.  Candidates with batch_ns == INT64_MAX
+ * (unreachable) or, for objective 1, weight <= 0 never win.  best = {index or -1, batch_ns}. */
+int oracle_search(const int64_t *batch_ns, const int64_t *weight, int64_t C, int32_t objective, int64_t *best) {
+    int64_t bi = -1;
+    for (int64_t c = 0; c < C; c++) {
+        if (batch_ns[c] == INT64_MAX) continue;
+        if (objective == 1 && weight[c] <= 0) continue;
+        if (bi < 0) { bi = c; continue; }
+        int better;
+        if (objective == 0) {
+            better = batch_ns[c] < batch_ns[bi];
+        } else {
+            unsigned __int128 l = (unsigned __int128)batch_ns[c] * (unsigned __int128)weight[bi];
+            unsigned __int128 r = (unsigned __int128)batch_ns[bi] * (unsigned __int128)weight[c];
+            better = l < r;
+        }
+        if (better) bi = c;
+    }
+    best[0] = bi;
+    best[1] = bi < 0 ? INT64_MAX : batch_ns[bi];
+    return 0;
+}
