@@ -1,0 +1,206 @@
+/*
+ * distsim.h -- C ABI of the batched DistSim strategy evaluator for AMD MI355X (gfx950).
+ *
+ * The library evaluates many candidate hybrid-parallel training strategies at once,
+ * following DistSim (arXiv 2306.08423): profiled per-layer event times are composed into
+ * per-stage events (Sec. 4.3, model-parallel modelling), the pipeline schedule is replayed
+ * with the dependency rule of Algorithm 1 (pipeline modelling), the data-parallel gradient
+ * all-reduce is appended (data-parallel modelling), and the resulting timeline is reduced
+ * to the iteration ("batch") time and per-device activity (Sec. 3.2, Sec. 5); the grid
+ * search of Sec. 6 picks the best candidate.
+ *
+ * Conventions that hold for every call
+ *  - "device pointer" = memory of the HIP device the context was created on, owned by the
+ *    caller (e.g. a PyTorch tensor).  The library never frees or reallocates caller memory
+ *    and allocates no device memory itself; everything it needs beyond the inputs and
+ *    outputs lives in distsim_events.workspace, which the caller sizes with
+ *    distsim_workspace_bytes().
+ *  - Work is enqueued on the hipStream_t passed as `hip_stream` (NULL = the default
+ *    stream); no call synchronises.  Results are valid once that stream has reached them.
+ *  - All times are int64 nanoseconds, all sizes int64 bytes.
+ *  - Return value: DISTSIM_OK, or a negative code; text via distsim_last_error().
+ *    A *candidate* that is not a valid strategy is not a call error: see `status`.
+ *  - Preconditions on table entries (not checked): 0 <= time < 2^40 ns, 0 <= bytes < 2^44,
+ *    0 <= alpha < 2^40, 1 <= beta < 2^32, 1 <= gpus_per_node.
+ */
+#ifndef DISTSIM_H
+#define DISTSIM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define DISTSIM_OK       0
+#define DISTSIM_EINVAL  (-1)   /* null pointer, negative size, unsupported shape            */
+#define DISTSIM_ERANGE  (-2)   /* a size exceeds a documented limit                          */
+#define DISTSIM_EHIP    (-3)   /* HIP runtime error                                          */
+
+#define DISTSIM_MAX_PP   64    /* pipeline stages per candidate (one 64-lane wavefront)      */
+#define DISTSIM_MAX_L    255   /* layers (partition boundaries are bytes)                    */
+#define DISTSIM_MAX_V    16    /* tensor-parallel variants in a cost table                   */
+
+#define DISTSIM_GPIPE    0     /* all forwards, then all backwards (Sec. 2.1.3)              */
+#define DISTSIM_1F1B     1     /* Dapple early backward: at most pp - s micro-batches alive  */
+
+/* per-candidate status written by distsim_build_events */
+#define DISTSIM_ST_OK       0
+#define DISTSIM_ST_INVALID  1  /* "unreachable" strategy (Sec. 6): dp*tp*pp != devices, pp > L,
+                                  pp > DISTSIM_MAX_PP, m < 1, no table variant for tp, unknown
+                                  schedule, or a partition that is not 0 = b0 < b1 < ... < bpp = L */
+#define DISTSIM_ST_RANGE    2  /* m * (sum of all stage-task and p2p durations) >= 2^53        */
+#define DISTSIM_ST_NOROOM   3  /* valid, but its stages do not fit stage_cap                    */
+
+typedef struct distsim_ctx distsim_ctx;   /* opaque; host-side state only (device id, error text, timers) */
+
+/* Create / destroy a context bound to HIP device `hip_device`.  Host memory only. */
+int         distsim_create(distsim_ctx **out, int hip_device);
+void        distsim_destroy(distsim_ctx *ctx);
+/* Text of the last error on this context; valid until the next call on it. */
+const char *distsim_last_error(const distsim_ctx *ctx);
+
+/*
+ * Profiled per-layer event times (the output of the event profiler, Sec. 4.2), one row per
+ * tensor-parallel variant: arrays are device pointers of V*L entries, entry [v*L + l].
+ * A layer of variant v is mapped to the composed event {computation, all-reduce} when
+ * variant_tp[v] > 1 and to the single computation event when it is 1 (Sec. 4.3); a layer
+ * with a2a_bytes > 0 additionally runs one all-to-all over the dp group per pass.
+ */
+typedef struct {
+    int32_t L, V;                    /* 1 <= L <= DISTSIM_MAX_L, 1 <= V <= DISTSIM_MAX_V          */
+    const int32_t *variant_tp;       /* [V] device: tensor-parallel size the row was profiled for */
+    const int64_t *fwd_comp_ns;      /* forward computation event                                 */
+    const int64_t *bwd_comp_ns;      /* backward computation event                                */
+    const int64_t *fwd_comm_ns;      /* in-layer blocking all-reduce event(s), forward            */
+    const int64_t *bwd_comm_ns;      /* same, backward                                            */
+    const int64_t *act_bytes;        /* activation sent if a stage ends after this layer          */
+    const int64_t *grad_bytes;       /* gradient bytes this layer contributes to the DP all-reduce */
+    const int64_t *a2a_bytes;        /* all-to-all payload (0 = none); may be NULL                */
+} distsim_costs;
+
+/*
+ * Simulated cluster, passed by value in host memory.  Collective events are evaluated as
+ *   p2p(P, k)       = alpha[k] + P / beta[k]
+ *   allreduce(n, P) = alpha[k] + (2 (n-1) P) / (n beta[k])     ring volume 2(N-1)P/N, Sec. 4.2
+ *   alltoall(n, P)  = alpha[k] + ((n-1) P) / (n beta[k])
+ * with truncating integer division in exactly this order; n = 1 or P = 0 means no event.
+ * Link class k: 0 = intra-node, 1 = inter-node (the communication events' attribute of
+ * Sec. 4.1).  A collective over n ranks is intra-node iff n <= gpus_per_node; the boundary
+ * between stages s and s+1 is intra-node iff floor(s tp dp / g) == floor((s+1) tp dp / g)
+ * (ranks ordered tp fastest, then dp, then pp).
+ */
+typedef struct {
+    int32_t num_devices;             /* dp*tp*pp of every valid candidate                         */
+    int32_t gpus_per_node;
+    int64_t alpha_ns[2];
+    int64_t beta_bytes_per_ns[2];    /* 1 GB/s == 1 byte/ns                                       */
+    int64_t dp_bucket_bytes;         /* 0: one all-reduce after the last backward (Sec. 4.3);
+                                        > 0: gradient buckets of this size, each issued as soon
+                                        as the last micro-batch's backward has produced it       */
+} distsim_cluster;
+
+/* Candidate strategies "xM xP xD" (Sec. 5.1) x micro-batches x schedule x partition.
+ * Struct of arrays, device pointers, C entries each. */
+typedef struct {
+    const int32_t *dp, *tp, *pp, *m;
+    const uint8_t *schedule;         /* DISTSIM_GPIPE / DISTSIM_1F1B                              */
+    const int64_t *part_off;         /* -1: uniform split, stage s owns layers [s L / pp, (s+1) L / pp);
+                                        else offset into part_pool of b0..bpp                    */
+    const uint8_t *part_pool;        /* concatenated boundaries; may be NULL if never referenced  */
+    int64_t part_pool_len;           /* entries in part_pool (offsets beyond it => invalid)       */
+} distsim_candidates;
+
+/* Columns of distsim_events.stage_tab: per pipeline stage of a candidate */
+enum {
+    DISTSIM_COL_FC = 0,   /* forward computation time of the stage's layers                       */
+    DISTSIM_COL_FA = 1,   /* forward communication time inside the stage (all-reduce, all-to-all) */
+    DISTSIM_COL_BC = 2,   /* backward computation                                                 */
+    DISTSIM_COL_BA = 3,   /* backward communication inside the stage                              */
+    DISTSIM_COL_PF = 4,   /* p2p event to stage s+1 after a forward (0 on the last stage)         */
+    DISTSIM_COL_PB = 5,   /* p2p event to stage s-1 after a backward (0 on the first stage)       */
+    DISTSIM_COL_G  = 6,   /* gradient bytes of the stage                                          */
+    DISTSIM_COL_AR = 7,   /* duration of the single trailing gradient all-reduce (0 = no event)   */
+    DISTSIM_NCOLS  = 8
+};
+
+/*
+ * The event flow of all candidates: output of distsim_build_events, input of
+ * distsim_simulate.  All pointers are caller-allocated device memory.
+ * Per-stage arrays are ragged: candidate c owns entries stage_off[c] .. stage_off[c+1]-1
+ * (pp entries if status[c] == DISTSIM_ST_OK, none otherwise).
+ */
+typedef struct {
+    int64_t  stage_cap;      /* entries available in every per-stage array                        */
+    int32_t  L, V;           /* table shape; filled in by distsim_build_events                    */
+    int32_t *status;         /* [C]                                                               */
+    int64_t *stage_off;      /* [C+1] exclusive prefix of the stage counts                        */
+    int64_t *stage_tab;      /* [DISTSIM_NCOLS][stage_cap]                                        */
+    int32_t *stage_layers;   /* [stage_cap] first layer | (one past last layer) << 8              */
+    int64_t *num_events;     /* [C] events on the pp distinct device timelines: 2 m pp stage-tasks
+                                + 2 m (pp-1) p2p + gradient all-reduce events; 0 if not OK       */
+    void    *workspace;      /* distsim_workspace_bytes() bytes, 256-byte aligned; opaque         */
+    size_t   workspace_bytes;
+} distsim_events;
+
+/* Bytes of distsim_events.workspace needed for tables of (L, V) and C candidates. */
+size_t distsim_workspace_bytes(int32_t L, int32_t V, int64_t C);
+
+/*
+ * Event-flow generation (Sec. 4.1 events -> Sec. 4.3 composed events).  For every candidate:
+ * validate, map layers to composed events, evaluate collective events, reduce the layer
+ * events of each stage (segmented sums over the layer axis) and write the stage table.
+ * Also prepares, inside the workspace, the order in which distsim_simulate visits candidates.
+ * Errors: EINVAL (null pointers, C < 0, L/V out of limits, workspace too small,
+ * stage_cap < 0), EHIP.  C == 0 is a no-op apart from stage_off[0] = 0.
+ */
+int distsim_build_events(distsim_ctx *ctx, const distsim_costs *costs, const distsim_cluster *cluster,
+                         const distsim_candidates *cand, int64_t C, distsim_events *out,
+                         void *hip_stream);
+
+/*
+ * Timeline simulation.  Replays every candidate's schedule with the rule of Algorithm 1:
+ * a stage-task starts at max(end of the previous task on the same device, end of the
+ * producing task on the neighbouring stage + its p2p event), runs for the stage's composed
+ * duration, then the gradient all-reduce event(s) follow the device's last backward.
+ * Outputs (device): batch_ns[C] = time of the last event (INT64_MAX unless status OK);
+ * comp_busy_ns / comm_busy_ns [stage_cap] = sum of the durations of the computation /
+ * communication events on each stage's device (index stage_off[c] + s); util (may be NULL)
+ * = comp_busy / batch as fp64.  `events` must come from distsim_build_events with the same
+ * cluster and C.  Errors: EINVAL, EHIP.
+ */
+int distsim_simulate(distsim_ctx *ctx, const distsim_cluster *cluster, const distsim_events *events,
+                     int64_t C, int64_t *batch_ns, int64_t *comp_busy_ns, int64_t *comm_busy_ns,
+                     double *util, void *hip_stream);
+
+/*
+ * Strategy search (Sec. 6): best[0] = index of the best candidate, best[1] = its batch_ns
+ * (device, 2 x int64).  objective 0: smallest batch_ns.  objective 1: smallest
+ * batch_ns / weight (weight[C] device, e.g. samples per iteration), compared exactly as
+ * batch_a * w_b < batch_b * w_a in 128 bits.  Ties go to the lowest index.  Candidates with
+ * batch_ns == INT64_MAX (or weight <= 0 under objective 1) never win; if none is left,
+ * best = {-1, INT64_MAX}.  `scratch` is device memory of distsim_search_scratch_bytes(C)
+ * bytes.  Errors: EINVAL, EHIP.
+ */
+size_t distsim_search_scratch_bytes(int64_t C);
+int distsim_search(distsim_ctx *ctx, const int64_t *batch_ns, const int64_t *weight, int64_t C,
+                   int objective, int64_t *best, void *scratch, void *hip_stream);
+
+/*
+ * Optional kernel timing with HIP events recorded on the caller's stream around each kernel
+ * launch.  distsim_timing_read blocks until the recorded launches have finished and returns
+ * the accumulated time and launch count of one kernel, then clears that kernel's record.
+ */
+enum {
+    DISTSIM_K_LAYER_TABLES = 0, DISTSIM_K_DECODE, DISTSIM_K_SCAN, DISTSIM_K_BINS, DISTSIM_K_SCATTER,
+    DISTSIM_K_STAGE_EVENTS, DISTSIM_K_SIM_INIT, DISTSIM_K_SIMULATE, DISTSIM_K_SEARCH, DISTSIM_K_COUNT
+};
+int distsim_timing_enable(distsim_ctx *ctx, int on);
+int distsim_timing_read(distsim_ctx *ctx, int kernel, double *total_ms, int64_t *launches);
+const char *distsim_kernel_name(int kernel);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DISTSIM_H */

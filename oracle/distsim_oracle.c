@@ -62,7 +62,8 @@
 #define ST_OK 0
 #define ST_INVALID 1
 #define ST_RANGE 2
-#define MAX_PP 64   /* interface limit of the evaluated library; larger pp is reported invalid */
+#define MAX_PP 64        /* interface limits of the evaluated library: a candidate beyond */
+#define MAX_M (1 << 16)  /* them is reported invalid                                      */
 
 enum { EV_TASK_DONE = 0, EV_ARRIVE_F = 1, EV_ARRIVE_B = 2, EV_GRAD_READY = 3, EV_AR_DONE = 4 };
 
@@ -193,7 +194,7 @@ static void simulate_one(const costs_t *co, const cluster_t *cl,
     res->num_events = 0;
 
     /* --- validation ("unreachable" configurations, Sec. 6) --- */
-    if (dp < 1 || tp < 1 || pp < 1 || m < 1 || (sched != 0 && sched != 1)) return;
+    if (dp < 1 || tp < 1 || pp < 1 || m < 1 || m > MAX_M || (sched != 0 && sched != 1)) return;
     if ((int64_t)dp * tp * pp != cl->num_devices) return;
     if (pp > L || pp > MAX_PP) return;
     int v = -1;

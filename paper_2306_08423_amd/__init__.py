@@ -1,0 +1,11 @@
+"""MI355X-native batched evaluator for DistSim's strategy search (arXiv 2306.08423).
+
+The hot path -- event-flow generation, timeline simulation, strategy search -- lives in
+hand-written HIP kernels behind the C ABI of include/distsim.h; `binding` marshals
+PyTorch device tensors into those calls.
+"""
+from .binding import (  # noqa: F401
+    Context, DeviceWorkload, DistSimError, Events, SimOutputs, EXPORTS, KERNELS, COL, LIB_PATH,
+    alloc_events, alloc_outputs, alloc_search, distsim_build_events, distsim_search, distsim_simulate,
+    load_library, upload,
+)

@@ -1,0 +1,260 @@
+"""Thin Python binding of the C ABI in include/distsim.h.
+
+Argument marshalling only: every step of the evaluation runs in the HIP kernels of
+libdistsim_hip.so.  PyTorch supplies device memory (tensors) and the stream.  There is
+no fallback: if the library is missing the import of this module's functions fails.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+from typing import Dict, Optional
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libdistsim_hip.so")
+
+EXPORTS = (
+    "distsim_create", "distsim_destroy", "distsim_last_error", "distsim_workspace_bytes",
+    "distsim_build_events", "distsim_simulate", "distsim_search_scratch_bytes", "distsim_search",
+    "distsim_timing_enable", "distsim_timing_read", "distsim_kernel_name",
+)
+
+NCOLS = 8
+COL = {"FC": 0, "FA": 1, "BC": 2, "BA": 3, "PF": 4, "PB": 5, "G": 6, "AR": 7}
+KERNELS = ("k_layer_tables", "k_decode", "k_scan", "k_bins", "k_scatter", "k_stage_events",
+           "k_sim_init", "k_simulate", "k_search")
+INT64_MAX = (1 << 63) - 1
+
+
+class _Costs(C.Structure):
+    _fields_ = [("L", C.c_int32), ("V", C.c_int32), ("variant_tp", C.c_void_p),
+                ("fwd_comp_ns", C.c_void_p), ("bwd_comp_ns", C.c_void_p),
+                ("fwd_comm_ns", C.c_void_p), ("bwd_comm_ns", C.c_void_p),
+                ("act_bytes", C.c_void_p), ("grad_bytes", C.c_void_p), ("a2a_bytes", C.c_void_p)]
+
+
+class _Cluster(C.Structure):
+    _fields_ = [("num_devices", C.c_int32), ("gpus_per_node", C.c_int32),
+                ("alpha_ns", C.c_int64 * 2), ("beta_bytes_per_ns", C.c_int64 * 2),
+                ("dp_bucket_bytes", C.c_int64)]
+
+
+class _Cand(C.Structure):
+    _fields_ = [("dp", C.c_void_p), ("tp", C.c_void_p), ("pp", C.c_void_p), ("m", C.c_void_p),
+                ("schedule", C.c_void_p), ("part_off", C.c_void_p), ("part_pool", C.c_void_p),
+                ("part_pool_len", C.c_int64)]
+
+
+class _Events(C.Structure):
+    _fields_ = [("stage_cap", C.c_int64), ("L", C.c_int32), ("V", C.c_int32),
+                ("status", C.c_void_p), ("stage_off", C.c_void_p), ("stage_tab", C.c_void_p),
+                ("stage_layers", C.c_void_p), ("num_events", C.c_void_p),
+                ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t)]
+
+
+_lib = None
+
+
+def load_library():
+    """dlopen the HIP library; raises if it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is missing: build it with paper_2306_08423_amd.build.build_library()")
+    lib = C.CDLL(LIB_PATH)
+    lib.distsim_create.argtypes = [C.POINTER(C.c_void_p), C.c_int]
+    lib.distsim_create.restype = C.c_int
+    lib.distsim_destroy.argtypes = [C.c_void_p]
+    lib.distsim_destroy.restype = None
+    lib.distsim_last_error.argtypes = [C.c_void_p]
+    lib.distsim_last_error.restype = C.c_char_p
+    lib.distsim_workspace_bytes.argtypes = [C.c_int32, C.c_int32, C.c_int64]
+    lib.distsim_workspace_bytes.restype = C.c_size_t
+    lib.distsim_build_events.argtypes = [C.c_void_p, C.POINTER(_Costs), C.POINTER(_Cluster), C.POINTER(_Cand),
+                                         C.c_int64, C.POINTER(_Events), C.c_void_p]
+    lib.distsim_build_events.restype = C.c_int
+    lib.distsim_simulate.argtypes = [C.c_void_p, C.POINTER(_Cluster), C.POINTER(_Events), C.c_int64,
+                                     C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+    lib.distsim_simulate.restype = C.c_int
+    lib.distsim_search_scratch_bytes.argtypes = [C.c_int64]
+    lib.distsim_search_scratch_bytes.restype = C.c_size_t
+    lib.distsim_search.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int, C.c_void_p,
+                                   C.c_void_p, C.c_void_p]
+    lib.distsim_search.restype = C.c_int
+    lib.distsim_timing_enable.argtypes = [C.c_void_p, C.c_int]
+    lib.distsim_timing_enable.restype = C.c_int
+    lib.distsim_timing_read.argtypes = [C.c_void_p, C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
+    lib.distsim_timing_read.restype = C.c_int
+    lib.distsim_kernel_name.argtypes = [C.c_int]
+    lib.distsim_kernel_name.restype = C.c_char_p
+    _lib = lib
+    return lib
+
+
+class DistSimError(RuntimeError):
+    pass
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _stream() -> C.c_void_p:
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+class Context:
+    """distsim_ctx bound to one HIP device."""
+
+    def __init__(self, device: int = 0):
+        self.lib = load_library()
+        self.device = torch.device("cuda", device)
+        h = C.c_void_p()
+        rc = self.lib.distsim_create(C.byref(h), device)
+        if rc != 0:
+            raise DistSimError(f"distsim_create failed ({rc})")
+        self.h = h
+
+    def close(self):
+        if getattr(self, "h", None):
+            self.lib.distsim_destroy(self.h)
+            self.h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def check(self, rc: int):
+        if rc != 0:
+            raise DistSimError(f"distsim error {rc}: {self.lib.distsim_last_error(self.h).decode()}")
+
+    def timing_enable(self, on: bool = True):
+        self.check(self.lib.distsim_timing_enable(self.h, int(on)))
+
+    def timing_read(self) -> Dict[str, tuple]:
+        out = {}
+        for k, name in enumerate(KERNELS):
+            ms, n = C.c_double(), C.c_int64()
+            self.check(self.lib.distsim_timing_read(self.h, k, C.byref(ms), C.byref(n)))
+            out[name] = (ms.value, n.value)
+        return out
+
+
+@dataclass
+class DeviceWorkload:
+    """Device-resident copy of a cost table, a cluster and a candidate list."""
+    L: int
+    V: int
+    C: int
+    costs: Dict[str, torch.Tensor]
+    cluster: Dict[str, object]
+    cand: Dict[str, torch.Tensor]
+
+    def costs_struct(self) -> _Costs:
+        c = self.costs
+        return _Costs(self.L, self.V, _ptr(c["variant_tp"]), _ptr(c["fwd_comp_ns"]), _ptr(c["bwd_comp_ns"]),
+                      _ptr(c["fwd_comm_ns"]), _ptr(c["bwd_comm_ns"]), _ptr(c["act_bytes"]), _ptr(c["grad_bytes"]),
+                      _ptr(c.get("a2a_bytes")))
+
+    def cluster_struct(self) -> _Cluster:
+        return cluster_struct(self.cluster)
+
+    def cand_struct(self) -> _Cand:
+        k = self.cand
+        pool = k["part_pool"]
+        return _Cand(_ptr(k["dp"]), _ptr(k["tp"]), _ptr(k["pp"]), _ptr(k["m"]), _ptr(k["schedule"]),
+                     _ptr(k["part_off"]), _ptr(pool) if pool.numel() else None, pool.numel())
+
+
+def cluster_struct(cl) -> _Cluster:
+    return _Cluster(int(cl["num_devices"]), int(cl["gpus_per_node"]),
+                    (C.c_int64 * 2)(*[int(x) for x in cl["alpha_ns"]]),
+                    (C.c_int64 * 2)(*[int(x) for x in cl["beta_bytes_per_ns"]]),
+                    int(cl["dp_bucket_bytes"]))
+
+
+def upload(w, device) -> DeviceWorkload:
+    """Copy a workloads.Workload (numpy, host) to the device, unchanged."""
+    dev = torch.device(device)
+    co = {k: torch.from_numpy(v).contiguous().to(dev) for k, v in w.costs.items() if hasattr(v, "dtype")}
+    ca = {k: torch.from_numpy(v).contiguous().to(dev) for k, v in w.cand.items()}
+    return DeviceWorkload(int(w.costs["L"]), int(w.costs["V"]), int(w.cand["dp"].shape[0]), co, dict(w.cluster), ca)
+
+
+@dataclass
+class Events:
+    """Caller-owned device buffers of a distsim_events plus the ctypes view of them."""
+    C: int
+    stage_cap: int
+    status: torch.Tensor
+    stage_off: torch.Tensor
+    stage_tab: torch.Tensor
+    stage_layers: torch.Tensor
+    num_events: torch.Tensor
+    workspace: torch.Tensor
+    struct: _Events
+
+
+def alloc_events(ctx: Context, L: int, V: int, Cn: int, stage_cap: int) -> Events:
+    dev = ctx.device
+    nbytes = ctx.lib.distsim_workspace_bytes(L, V, Cn)
+    if nbytes == 0:
+        raise DistSimError("distsim_workspace_bytes rejected (L, V, C)")
+    status = torch.empty(max(Cn, 1), dtype=torch.int32, device=dev)
+    stage_off = torch.empty(Cn + 1, dtype=torch.int64, device=dev)
+    cap = max(int(stage_cap), 0)
+    stage_tab = torch.empty((NCOLS, max(cap, 1)), dtype=torch.int64, device=dev)
+    stage_layers = torch.empty(max(cap, 1), dtype=torch.int32, device=dev)
+    num_events = torch.empty(max(Cn, 1), dtype=torch.int64, device=dev)
+    # torch's caching allocator hands out 512-byte aligned blocks
+    workspace = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+    st = _Events(cap, 0, 0, _ptr(status), _ptr(stage_off), _ptr(stage_tab), _ptr(stage_layers), _ptr(num_events),
+                 _ptr(workspace), nbytes)
+    return Events(Cn, cap, status, stage_off, stage_tab, stage_layers, num_events, workspace, st)
+
+
+def distsim_build_events(ctx: Context, dw: DeviceWorkload, ev: Events) -> None:
+    co, cl, ca = dw.costs_struct(), dw.cluster_struct(), dw.cand_struct()
+    ctx.check(ctx.lib.distsim_build_events(ctx.h, C.byref(co), C.byref(cl), C.byref(ca), dw.C, C.byref(ev.struct),
+                                           _stream()))
+
+
+@dataclass
+class SimOutputs:
+    batch_ns: torch.Tensor
+    comp_busy_ns: torch.Tensor
+    comm_busy_ns: torch.Tensor
+    util: Optional[torch.Tensor]
+
+
+def alloc_outputs(ctx: Context, ev: Events, util: bool = True) -> SimOutputs:
+    dev = ctx.device
+    n = max(ev.stage_cap, 1)
+    return SimOutputs(torch.empty(max(ev.C, 1), dtype=torch.int64, device=dev),
+                      torch.empty(n, dtype=torch.int64, device=dev),
+                      torch.empty(n, dtype=torch.int64, device=dev),
+                      torch.empty(n, dtype=torch.float64, device=dev) if util else None)
+
+
+def distsim_simulate(ctx: Context, cluster, ev: Events, out: SimOutputs) -> None:
+    cl = cluster_struct(cluster)
+    ctx.check(ctx.lib.distsim_simulate(ctx.h, C.byref(cl), C.byref(ev.struct), ev.C, _ptr(out.batch_ns),
+                                       _ptr(out.comp_busy_ns), _ptr(out.comm_busy_ns), _ptr(out.util), _stream()))
+
+
+def alloc_search(ctx: Context, Cn: int):
+    n = ctx.lib.distsim_search_scratch_bytes(Cn)
+    return (torch.empty(2, dtype=torch.int64, device=ctx.device),
+            torch.empty(max(n, 8), dtype=torch.uint8, device=ctx.device))
+
+
+def distsim_search(ctx: Context, batch_ns: torch.Tensor, Cn: int, best: torch.Tensor, scratch: torch.Tensor,
+                   weight: Optional[torch.Tensor] = None, objective: int = 0) -> None:
+    ctx.check(ctx.lib.distsim_search(ctx.h, _ptr(batch_ns), _ptr(weight), Cn, objective, _ptr(best), _ptr(scratch),
+                                     _stream()))

@@ -1,0 +1,286 @@
+// C ABI of the batched DistSim strategy evaluator (see include/distsim.h).
+#include <hip/hip_runtime.h>
+
+#include <cstdio>
+#include <cstring>
+#include <string>
+#include <vector>
+
+#include "distsim.h"
+#include "kernels_build.hpp"
+#include "kernels_search.hpp"
+#include "kernels_simulate.hpp"
+
+using namespace distsim;
+
+struct TimedLaunch {
+    hipEvent_t start, stop;
+};
+
+struct distsim_ctx {
+    int device = 0;
+    int num_cus = 256;
+    std::string err;
+    bool timing = false;
+    std::vector<TimedLaunch> rec[DISTSIM_K_COUNT];
+    std::vector<TimedLaunch> pool;      // recycled event pairs
+};
+
+static const char* kKernelNames[DISTSIM_K_COUNT] = {
+    "k_layer_tables", "k_decode", "k_scan", "k_bins", "k_scatter",
+    "k_stage_events", "k_sim_init", "k_simulate", "k_search",
+};
+
+static int fail(distsim_ctx* ctx, int code, const std::string& msg) {
+    if (ctx) ctx->err = msg;
+    return code;
+}
+
+#define HIP_TRY(expr)                                                                          \
+    do {                                                                                       \
+        hipError_t e_ = (expr);                                                                \
+        if (e_ != hipSuccess)                                                                  \
+            return fail(ctx, DISTSIM_EHIP, std::string(#expr) + ": " + hipGetErrorString(e_)); \
+    } while (0)
+
+namespace {
+
+// Brackets a group of launches with HIP events on the caller's stream when timing is on.
+struct Timer {
+    distsim_ctx* ctx;
+    hipStream_t stream;
+    int kid;
+    TimedLaunch tl{};
+    bool on = false;
+    Timer(distsim_ctx* c, hipStream_t s, int k) : ctx(c), stream(s), kid(k) {
+        if (!ctx->timing) return;
+        if (!ctx->pool.empty()) { tl = ctx->pool.back(); ctx->pool.pop_back(); }
+        else if (hipEventCreate(&tl.start) != hipSuccess || hipEventCreate(&tl.stop) != hipSuccess) return;
+        on = hipEventRecord(tl.start, stream) == hipSuccess;
+    }
+    ~Timer() {
+        if (!on) return;
+        (void)hipEventRecord(tl.stop, stream);
+        ctx->rec[kid].push_back(tl);
+    }
+};
+
+ClusterDev to_dev(const distsim_cluster& c) {
+    ClusterDev d;
+    d.num_devices = c.num_devices;
+    d.gpus_per_node = c.gpus_per_node;
+    d.alpha[0] = c.alpha_ns[0]; d.alpha[1] = c.alpha_ns[1];
+    d.beta[0] = c.beta_bytes_per_ns[0]; d.beta[1] = c.beta_bytes_per_ns[1];
+    d.bucket = c.dp_bucket_bytes;
+    return d;
+}
+
+bool cluster_ok(const distsim_cluster* c) {
+    return c && c->num_devices >= 1 && c->gpus_per_node >= 1 && c->alpha_ns[0] >= 0 && c->alpha_ns[1] >= 0 &&
+           c->beta_bytes_per_ns[0] >= 1 && c->beta_bytes_per_ns[1] >= 1 && c->dp_bucket_bytes >= 0;
+}
+
+// Waves that sweep the wave-items: enough to fill every SIMD, never more than one per candidate.
+int item_grid(const distsim_ctx* ctx, int64_t C) {
+    const int64_t want = (int64_t)ctx->num_cus * 8;           // blocks of 4 waves: 8 waves per SIMD
+    const int64_t need = (C + 3) / 4;
+    return (int)(need < want ? (need < 1 ? 1 : need) : want);
+}
+
+}  // namespace
+
+extern "C" {
+
+int distsim_create(distsim_ctx** out, int hip_device) {
+    if (!out) return DISTSIM_EINVAL;
+    *out = nullptr;
+    int n = 0;
+    if (hipGetDeviceCount(&n) != hipSuccess || hip_device < 0 || hip_device >= n) return DISTSIM_EHIP;
+    distsim_ctx* ctx = new distsim_ctx();
+    ctx->device = hip_device;
+    hipDeviceProp_t prop;
+    if (hipGetDeviceProperties(&prop, hip_device) == hipSuccess && prop.multiProcessorCount > 0)
+        ctx->num_cus = prop.multiProcessorCount;
+    *out = ctx;
+    return DISTSIM_OK;
+}
+
+void distsim_destroy(distsim_ctx* ctx) {
+    if (!ctx) return;
+    for (auto& v : ctx->rec) for (auto& t : v) { (void)hipEventDestroy(t.start); (void)hipEventDestroy(t.stop); }
+    for (auto& t : ctx->pool) { (void)hipEventDestroy(t.start); (void)hipEventDestroy(t.stop); }
+    delete ctx;
+}
+
+const char* distsim_last_error(const distsim_ctx* ctx) { return ctx ? ctx->err.c_str() : "null context"; }
+
+size_t distsim_workspace_bytes(int32_t L, int32_t V, int64_t C) {
+    if (L < 1 || L > DISTSIM_MAX_L || V < 1 || V > DISTSIM_MAX_V || C < 0) return 0;
+    Workspace w;
+    return carve(w, nullptr, L, V, C);
+}
+
+int distsim_build_events(distsim_ctx* ctx, const distsim_costs* costs, const distsim_cluster* cluster,
+                         const distsim_candidates* cand, int64_t C, distsim_events* out, void* hip_stream) {
+    if (!ctx) return DISTSIM_EINVAL;
+    if (!costs || !cluster || !cand || !out) return fail(ctx, DISTSIM_EINVAL, "null argument");
+    if (costs->L < 1 || costs->L > DISTSIM_MAX_L || costs->V < 1 || costs->V > DISTSIM_MAX_V)
+        return fail(ctx, DISTSIM_ERANGE, "cost table shape outside 1 <= L <= 255, 1 <= V <= 16");
+    if (C < 0 || C > 0x7fffffff) return fail(ctx, DISTSIM_ERANGE, "candidate count outside [0, 2^31)");
+    if (!cluster_ok(cluster)) return fail(ctx, DISTSIM_EINVAL, "cluster description out of range");
+    if (!costs->variant_tp || !costs->fwd_comp_ns || !costs->bwd_comp_ns || !costs->fwd_comm_ns ||
+        !costs->bwd_comm_ns || !costs->act_bytes || !costs->grad_bytes)
+        return fail(ctx, DISTSIM_EINVAL, "null cost column");
+    if (!out->stage_off || !out->workspace || out->stage_cap < 0)
+        return fail(ctx, DISTSIM_EINVAL, "events: null stage_off/workspace or negative stage_cap");
+    if (C > 0 && (!cand->dp || !cand->tp || !cand->pp || !cand->m || !cand->schedule || !cand->part_off ||
+                  !out->status || !out->num_events || (out->stage_cap > 0 && (!out->stage_tab || !out->stage_layers))))
+        return fail(ctx, DISTSIM_EINVAL, "null candidate or events array");
+    if (((uintptr_t)out->workspace & 255) != 0) return fail(ctx, DISTSIM_EINVAL, "workspace must be 256-byte aligned");
+    Workspace ws;
+    const size_t need = carve(ws, out->workspace, costs->L, costs->V, C);
+    if (out->workspace_bytes < need) return fail(ctx, DISTSIM_EINVAL, "workspace too small");
+
+    HIP_TRY(hipSetDevice(ctx->device));
+    hipStream_t st = (hipStream_t)hip_stream;
+    CostsDev co{costs->L, costs->V, costs->variant_tp, costs->fwd_comp_ns, costs->bwd_comp_ns, costs->fwd_comm_ns,
+                costs->bwd_comm_ns, costs->act_bytes, costs->grad_bytes, costs->a2a_bytes};
+    const ClusterDev cl = to_dev(*cluster);
+    CandDev ca{cand->dp, cand->tp, cand->pp, cand->m, cand->schedule, cand->part_off, cand->part_pool,
+               cand->part_pool ? cand->part_pool_len : 0};
+    EventsDev ev{out->stage_cap, out->stage_tab, out->stage_layers, out->num_events};
+    out->L = costs->L;
+    out->V = costs->V;
+
+    const int64_t nblk = (C + kScanChunk - 1) / kScanChunk;
+    const int cblocks = (int)((C + 255) / 256);
+    {
+        Timer t(ctx, st, DISTSIM_K_LAYER_TABLES);
+        hipLaunchKernelGGL(k_layer_tables, dim3(costs->V * kMaxPP), dim3(kWave), 0, st, co, cl, ws);
+        hipLaunchKernelGGL(k_clear_bins, dim3((kBins + 255) / 256), dim3(256), 0, st, ws);
+    }
+    if (C > 0) {
+        Timer t(ctx, st, DISTSIM_K_DECODE);
+        hipLaunchKernelGGL(k_decode, dim3(cblocks), dim3(256), 0, st, co, cl, ca, C, ws, out->status, out->num_events);
+    }
+    {
+        Timer t(ctx, st, DISTSIM_K_SCAN);
+        if (C > 0) hipLaunchKernelGGL(k_scan_reduce, dim3((int)nblk), dim3(kScanBlock), 0, st, ws.npp, C, ws.block_sums);
+        hipLaunchKernelGGL(k_scan_top, dim3(1), dim3(kScanBlock), 0, st, ws.block_sums, nblk);
+        // with C == 0 one block still writes stage_off[0] = block_sums[0] = 0
+        hipLaunchKernelGGL(k_scan_apply, dim3((int)(nblk > 0 ? nblk : 1)), dim3(kScanBlock), 0, st, ws.npp, C,
+                           ws.block_sums, nblk, out->stage_off);
+    }
+    {
+        Timer t(ctx, st, DISTSIM_K_BINS);
+        hipLaunchKernelGGL(k_bins, dim3(1), dim3(kBinsBlock), 0, st, ws);
+    }
+    if (C > 0) {
+        {
+            Timer t(ctx, st, DISTSIM_K_SCATTER);
+            hipLaunchKernelGGL(k_scatter, dim3(cblocks), dim3(256), 0, st, ca, C, ws, out->stage_cap, out->stage_off,
+                               out->status, out->num_events);
+        }
+        Timer t(ctx, st, DISTSIM_K_STAGE_EVENTS);
+        hipLaunchKernelGGL(k_stage_events, dim3(item_grid(ctx, C)), dim3(256), 0, st, co, cl, ca, ws, ev);
+    }
+    HIP_TRY(hipGetLastError());
+    return DISTSIM_OK;
+}
+
+int distsim_simulate(distsim_ctx* ctx, const distsim_cluster* cluster, const distsim_events* events, int64_t C,
+                     int64_t* batch_ns, int64_t* comp_busy_ns, int64_t* comm_busy_ns, double* util,
+                     void* hip_stream) {
+    if (!ctx) return DISTSIM_EINVAL;
+    if (!cluster || !events) return fail(ctx, DISTSIM_EINVAL, "null argument");
+    if (!cluster_ok(cluster)) return fail(ctx, DISTSIM_EINVAL, "cluster description out of range");
+    if (C < 0 || C > 0x7fffffff) return fail(ctx, DISTSIM_ERANGE, "candidate count outside [0, 2^31)");
+    if (C == 0) return DISTSIM_OK;
+    if (!batch_ns || !events->status || !events->workspace || !events->stage_off ||
+        (events->stage_cap > 0 && (!comp_busy_ns || !comm_busy_ns || !events->stage_tab || !events->stage_layers)))
+        return fail(ctx, DISTSIM_EINVAL, "null output or events array");
+    HIP_TRY(hipSetDevice(ctx->device));
+    hipStream_t st = (hipStream_t)hip_stream;
+    if (events->L < 1 || events->L > DISTSIM_MAX_L || events->V < 1 || events->V > DISTSIM_MAX_V)
+        return fail(ctx, DISTSIM_EINVAL, "events were not produced by distsim_build_events");
+    Workspace ws;
+    if (events->workspace_bytes < carve(ws, events->workspace, events->L, events->V, C))
+        return fail(ctx, DISTSIM_EINVAL, "workspace too small for C");
+    CostsDev co{};
+    co.L = events->L; co.V = events->V;
+    const ClusterDev cl = to_dev(*cluster);
+    EventsDev ev{events->stage_cap, events->stage_tab, events->stage_layers, events->num_events};
+    SimOut out{batch_ns, comp_busy_ns, comm_busy_ns, util};
+    {
+        Timer t(ctx, st, DISTSIM_K_SIM_INIT);
+        hipLaunchKernelGGL(k_sim_init, dim3((int)((C + 255) / 256)), dim3(256), 0, st, events->status, C, batch_ns);
+    }
+    {
+        Timer t(ctx, st, DISTSIM_K_SIMULATE);
+        hipLaunchKernelGGL(k_simulate, dim3(item_grid(ctx, C)), dim3(256), 0, st, co, cl, ws, ev, out);
+    }
+    HIP_TRY(hipGetLastError());
+    return DISTSIM_OK;
+}
+
+size_t distsim_search_scratch_bytes(int64_t C) {
+    (void)C;
+    return (size_t)kSearchMaxBlocks * sizeof(Best);
+}
+
+int distsim_search(distsim_ctx* ctx, const int64_t* batch_ns, const int64_t* weight, int64_t C, int objective,
+                   int64_t* best, void* scratch, void* hip_stream) {
+    if (!ctx) return DISTSIM_EINVAL;
+    if (!best || !scratch || (C > 0 && !batch_ns)) return fail(ctx, DISTSIM_EINVAL, "null argument");
+    if (objective != 0 && objective != 1) return fail(ctx, DISTSIM_EINVAL, "objective must be 0 or 1");
+    if (objective == 1 && C > 0 && !weight) return fail(ctx, DISTSIM_EINVAL, "objective 1 needs weights");
+    if (C < 0) return fail(ctx, DISTSIM_ERANGE, "negative candidate count");
+    HIP_TRY(hipSetDevice(ctx->device));
+    hipStream_t st = (hipStream_t)hip_stream;
+    Best* partial = (Best*)scratch;
+    int64_t nb = (C + kSearchBlock * 4 - 1) / (kSearchBlock * 4);
+    if (nb > kSearchMaxBlocks) nb = kSearchMaxBlocks;
+    if (nb < 1) nb = 1;
+    Timer t(ctx, st, DISTSIM_K_SEARCH);
+    if (objective == 0) {
+        hipLaunchKernelGGL(k_search_partial<0>, dim3((int)nb), dim3(kSearchBlock), 0, st, batch_ns, weight, C, partial);
+        hipLaunchKernelGGL(k_search_final<0>, dim3(1), dim3(kSearchBlock), 0, st, partial, (int)nb, best);
+    } else {
+        hipLaunchKernelGGL(k_search_partial<1>, dim3((int)nb), dim3(kSearchBlock), 0, st, batch_ns, weight, C, partial);
+        hipLaunchKernelGGL(k_search_final<1>, dim3(1), dim3(kSearchBlock), 0, st, partial, (int)nb, best);
+    }
+    HIP_TRY(hipGetLastError());
+    return DISTSIM_OK;
+}
+
+int distsim_timing_enable(distsim_ctx* ctx, int on) {
+    if (!ctx) return DISTSIM_EINVAL;
+    ctx->timing = on != 0;
+    return DISTSIM_OK;
+}
+
+int distsim_timing_read(distsim_ctx* ctx, int kernel, double* total_ms, int64_t* launches) {
+    if (!ctx) return DISTSIM_EINVAL;
+    if (kernel < 0 || kernel >= DISTSIM_K_COUNT || !total_ms || !launches)
+        return fail(ctx, DISTSIM_EINVAL, "bad kernel id or null output");
+    double tot = 0.0;
+    int64_t n = 0;
+    for (auto& tl : ctx->rec[kernel]) {
+        HIP_TRY(hipEventSynchronize(tl.stop));
+        float ms = 0.f;
+        HIP_TRY(hipEventElapsedTime(&ms, tl.start, tl.stop));
+        tot += ms;
+        n++;
+        ctx->pool.push_back(tl);
+    }
+    ctx->rec[kernel].clear();
+    *total_ms = tot;
+    *launches = n;
+    return DISTSIM_OK;
+}
+
+const char* distsim_kernel_name(int kernel) {
+    return kernel >= 0 && kernel < DISTSIM_K_COUNT ? kKernelNames[kernel] : "?";
+}
+
+}  // extern "C"

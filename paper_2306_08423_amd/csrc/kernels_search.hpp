@@ -1,0 +1,82 @@
+// Strategy search (Sec. 6): argmin over candidates, ties to the lowest index.
+#pragma once
+#include "device_utils.hpp"
+
+namespace distsim {
+
+struct Best {
+    int64_t idx;     // -1 = none
+    int64_t val;     // batch_ns
+    int64_t wgt;     // weight (objective 1), else 1
+};
+
+// true iff a is strictly better than b
+template <int OBJ>
+__device__ __forceinline__ bool better(const Best& a, const Best& b) {
+    if (a.idx < 0) return false;
+    if (b.idx < 0) return true;
+    if (OBJ == 0) {
+        if (a.val != b.val) return a.val < b.val;
+    } else {
+        // a.val / a.wgt < b.val / b.wgt  <=>  a.val * b.wgt < b.val * a.wgt   (128-bit exact)
+        const uint64_t lh = __umul64hi((uint64_t)a.val, (uint64_t)b.wgt), ll = (uint64_t)a.val * (uint64_t)b.wgt;
+        const uint64_t rh = __umul64hi((uint64_t)b.val, (uint64_t)a.wgt), rl = (uint64_t)b.val * (uint64_t)a.wgt;
+        if (lh != rh) return lh < rh;
+        if (ll != rl) return ll < rl;
+    }
+    return a.idx < b.idx;
+}
+
+template <int OBJ>
+__device__ __forceinline__ Best wave_best(Best a) {
+    for (int d = 1; d < kWave; d <<= 1) {
+        Best o;
+        o.idx = __shfl_xor(a.idx, d, kWave);
+        o.val = __shfl_xor(a.val, d, kWave);
+        o.wgt = __shfl_xor(a.wgt, d, kWave);
+        if (better<OBJ>(o, a)) a = o;
+    }
+    return a;
+}
+
+constexpr int kSearchBlock = 256;
+constexpr int kSearchMaxBlocks = 1024;
+
+template <int OBJ>
+__device__ __forceinline__ Best block_best(Best a) {
+    __shared__ Best sh[kSearchBlock / kWave];
+    a = wave_best<OBJ>(a);
+    if (lane_id() == 0) sh[threadIdx.x / kWave] = a;
+    __syncthreads();
+    Best r = sh[0];
+    for (int i = 1; i < kSearchBlock / kWave; i++) if (better<OBJ>(sh[i], r)) r = sh[i];
+    __syncthreads();
+    return r;
+}
+
+template <int OBJ>
+__global__ __launch_bounds__(kSearchBlock) void k_search_partial(const int64_t* __restrict__ batch_ns,
+                                                                  const int64_t* __restrict__ weight, int64_t C,
+                                                                  Best* __restrict__ partial) {
+    Best a{-1, INT64_MAX, 1};
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t c = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; c < C; c += stride) {
+        Best b{c, batch_ns[c], 1};
+        if (b.val == INT64_MAX) continue;
+        if (OBJ == 1) { b.wgt = weight[c]; if (b.wgt <= 0) continue; }
+        if (better<OBJ>(b, a)) a = b;
+    }
+    a = block_best<OBJ>(a);
+    if (threadIdx.x == 0) partial[blockIdx.x] = a;
+}
+
+template <int OBJ>
+__global__ __launch_bounds__(kSearchBlock) void k_search_final(const Best* __restrict__ partial, int n,
+                                                                int64_t* __restrict__ best) {
+    Best a{-1, INT64_MAX, 1};
+    for (int i = threadIdx.x; i < n; i += blockDim.x) if (better<OBJ>(partial[i], a)) a = partial[i];
+    a = block_best<OBJ>(a);
+    if (threadIdx.x == 0) { best[0] = a.idx; best[1] = a.idx < 0 ? INT64_MAX : a.val; }
+}
+
+}  // namespace distsim

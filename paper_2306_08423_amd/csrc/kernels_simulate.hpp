@@ -1,0 +1,136 @@
+// Timeline simulation: level-synchronous sweep of the pipeline recurrence of Algorithm 1.
+#pragma once
+#include "kernels_build.hpp"
+
+namespace distsim {
+
+struct SimOut {
+    int64_t* batch_ns;
+    int64_t* comp_busy;
+    int64_t* comm_busy;
+    double* util;       // may be null
+};
+
+__global__ __launch_bounds__(256) void k_sim_init(const int32_t* __restrict__ status, int64_t C,
+                                                  int64_t* __restrict__ batch_ns) {
+    const int64_t c = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (c < C && status[c] != 0) batch_ns[c] = INT64_MAX;
+}
+
+// Lane (g, s) of a wave-item owns stage s of one candidate and keeps a single running value:
+// the end time of the most recent stage-task on that device.  Tasks are visited in levels
+// chosen such that every dependency of a level-l task lies in a lower level:
+//   GPipe  F(s,j): s + j                         B(s,j): (m + pp - 1) + (pp - 1 - s) + j
+//   1F1B   F(s,j): s + j        (j <= w_s)       B(s,j): 2 pp - 1 - s + 2 j
+//                  s + 2 j      (j >  w_s)       w_s = min(pp - 1 - s, m) warm-up forwards
+// In that order the most recent task of the producing neighbour at the time a task runs is
+// exactly its producer (forward: F(s-1,j) on the previous lane; backward: B(s+1,j) on the next
+// lane), so the cross-stage operand is the neighbour lane's register, read with a DPP shift.
+// Times are carried as doubles: every value is an integer below 2^53 (range guard at event
+// generation), so fp64 add and max are exact and one instruction each.
+__global__ __launch_bounds__(256) void k_simulate(CostsDev co, ClusterDev cl, Workspace ws, EventsDev ev,
+                                                  SimOut out) {
+    const int lane = lane_id();
+    const int64_t wave0 = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / kWave;
+    const int64_t nwaves = ((int64_t)gridDim.x * blockDim.x) / kWave;
+    const int64_t W = ws.hdr[H_NUM_ITEMS];
+    const int64_t cap = ev.stage_cap;
+    const int L = co.L;
+    const double ninf = -__builtin_huge_val();
+
+    for (int64_t w = wave0; w < W; w += nwaves) {
+        const Item it = decode_item(ws.hdr, w);
+        const int width = 1 << it.sh;
+        const int s = lane & (width - 1);
+        const int64_t pos = it.pos0 + (lane >> it.sh);
+        int pp = 0, v = 0, m = 0, dp = 1, sched = 0;
+        int64_t off = 0, c = 0;
+        if (pos < it.class_end) {
+            const int meta = ws.s_meta[pos];
+            pp = meta & 0xff; sched = (meta >> 8) & 0xff; v = meta >> 16;
+            m = ws.s_m[pos]; dp = ws.s_dp[pos];
+            off = ws.s_off[pos]; c = ws.s_cand[pos];
+        }
+        const bool act = s < pp;
+        if (!act) m = 0;
+        const int64_t i = off + s;
+        int64_t FC = 0, FA = 0, BC = 0, BA = 0, PF = 0, PB = 0, AR = 0;
+        double pfL = ninf, pbR = ninf;      // p2p latency on the incoming edges; -inf = no edge
+        if (act) {
+            FC = ev.stage_tab[0 * cap + i]; FA = ev.stage_tab[1 * cap + i];
+            BC = ev.stage_tab[2 * cap + i]; BA = ev.stage_tab[3 * cap + i];
+            PF = ev.stage_tab[4 * cap + i]; PB = ev.stage_tab[5 * cap + i];
+            AR = ev.stage_tab[7 * cap + i];
+            if (s > 0) pfL = (double)ev.stage_tab[4 * cap + i - 1];
+            if (s + 1 < pp) pbR = (double)ev.stage_tab[5 * cap + i + 1];
+        }
+        const double Fd = (double)(FC + FA), Bd = (double)(BC + BA);
+
+        // level predicates, expressed on x = level - s
+        int wc, two_w, offB, stepB;
+        if (sched == 0) {
+            wc = m - 1; two_w = 0x7fffffff; offB = m + 2 * pp - 2 - 2 * s; stepB = 1;
+        } else {
+            int wq = pp - 1 - s; if (wq > m) wq = m;
+            wc = wq < m - 1 ? wq : m - 1; two_w = 2 * wq; offB = 2 * pp - 1 - 2 * s; stepB = 2;
+        }
+        const int spanB = m * stepB, maskB = stepB - 1, two_m = 2 * m;
+        const int nlev = wave_max_i32(act ? 2 * (m + pp - 1) : 0);
+
+        double own = 0.0;
+        int x = -s;
+        for (int lvl = 0; lvl < nlev; lvl++, x++) {
+            const double fromL = from_prev_lane(own);
+            const double fromR = from_next_lane(own);
+            const bool doF = x >= 0 && (x <= wc || ((x & 1) == 0 && x > two_w && x < two_m));
+            const int y = x - offB;
+            const bool doB = y >= 0 && y < spanB && (y & maskB) == 0;
+            const double eF = __builtin_fmax(own, fromL + pfL) + Fd;
+            const double eB = __builtin_fmax(own, fromR + pbR) + Bd;
+            own = doF ? eF : (doB ? eB : own);
+        }
+
+        // data-parallel modelling: gradient all-reduce after (or overlapped with) the last backward
+        const int64_t endB = (int64_t)own;
+        int64_t finish = endB + AR, ar_busy = AR;
+        if (act && cl.bucket > 0) {
+            finish = endB; ar_busy = 0;
+            if (dp > 1) {
+                const int lay = ev.stage_layers[i];
+                const int lo = lay & 0xff, hi = lay >> 8;
+                const size_t vr = (size_t)v * (L + 1), rr = (size_t)(v * kMaxPP + pp - 1) * (L + 1);
+                const int64_t startB = endB - (BC + BA);
+                const int64_t tot_hi = ws.pbc[vr + hi] + ws.pba[rr + hi];
+                const int64_t ar_cap = allreduce_ns(cl, dp, cl.bucket);
+                int64_t acc = 0, t = 0;
+                for (int l = hi - 1; l >= lo; l--) {
+                    const int64_t ready = startB + (tot_hi - (ws.pbc[vr + l] + ws.pba[rr + l]));
+                    acc += ws.pg[vr + l + 1] - ws.pg[vr + l];
+                    const int64_t k = acc / cl.bucket;
+                    if (k > 0) {
+                        t = (t > ready ? t : ready) + k * ar_cap;
+                        ar_busy += k * ar_cap;
+                        acc -= k * cl.bucket;
+                    }
+                    if (l == lo && acc > 0) {
+                        const int64_t d = allreduce_ns(cl, dp, acc);
+                        t = (t > ready ? t : ready) + d;
+                        ar_busy += d;
+                    }
+                }
+                finish = t > endB ? t : endB;
+            }
+        }
+        const int64_t batch = group_max(act ? finish : 0, width);
+        if (act) {
+            const int64_t comp = (int64_t)m * (FC + BC);
+            const int64_t comm = (int64_t)m * (FA + BA + PF + PB) + ar_busy;
+            out.comp_busy[i] = comp;
+            out.comm_busy[i] = comm;
+            if (out.util) out.util[i] = batch > 0 ? (double)comp / (double)batch : 0.0;
+            if (s == 0) out.batch_ns[c] = batch;
+        }
+    }
+}
+
+}  // namespace distsim

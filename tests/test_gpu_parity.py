@@ -1,0 +1,208 @@
+"""HIP path vs CPU oracle, element by element, through the C ABI.  Needs an MI355X."""
+import os
+
+import numpy as np
+import pytest
+
+from helpers import mk, mk_cluster, mk_costs
+from workloads import Workload, make_workload, subset, total_stages
+
+pytestmark = pytest.mark.gpu
+
+INT64_MAX = np.iinfo(np.int64).max
+NT = min(16, os.cpu_count() or 1)
+
+
+@pytest.fixture(scope="module")
+def H():
+    import gpu_harness
+    return gpu_harness
+
+
+def _say(msg):
+    print(msg, flush=True)
+
+
+@pytest.mark.parametrize("name", ["tiny", "tiny_b", "gpt24", "gpt48"])
+def test_full_parity_small_configs(H, oracle_mod, name):
+    _say(f"[case] full parity {name}")
+    w = make_workload(name)
+    hip = H.run_hip(w)
+    ora = oracle_mod.simulate(w, nthreads=NT)
+    H.assert_same(hip, ora, what=name)
+    assert (hip["status"] == 0).all()
+
+
+def test_tiny_golden_numbers(H):
+    _say("[case] tiny golden")
+    costs = mk_costs([1_000_000] * 4, [2_025_000] * 4, act=[4 << 20] * 4)
+    w = mk(costs, mk_cluster(2), [(1, 1, 2, 4, 1, [0, 2, 4]), (1, 1, 2, 4, 0, [0, 2, 4])])
+    hip = H.run_hip(w)
+    assert list(hip["batch_ns"]) == [30_353_884, 30_301_942]
+    assert list(hip["comp_busy_ns"]) == [24_200_000] * 4
+    assert list(hip["comm_busy_ns"]) == [103_884] * 4
+
+
+@pytest.mark.parametrize("name,nsample", [("gpt96", 6000), ("hetero64", 30000)])
+def test_sampled_parity_full_size_launch(H, oracle_mod, name, nsample):
+    """The full candidate list goes through the library in one call (the launch shape the
+    benchmark times); a seeded sample plus the extreme shapes is checked one by one."""
+    _say(f"[case] sampled parity {name}")
+    w = make_workload(name)
+    hip = H.run_hip(w)
+    rng = np.random.default_rng(123)
+    idx = set(rng.choice(w.C, nsample, replace=False).tolist())
+    work = w.cand["pp"].astype(np.int64) * w.cand["m"]
+    idx.update(np.argsort(work)[-200:].tolist())
+    idx.update(np.argsort(work)[:200].tolist())
+    idx.update(range(0, 64)); idx.update(range(w.C - 64, w.C))
+    idx = np.asarray(sorted(idx))
+    ora = oracle_mod.simulate(subset(w, idx), nthreads=NT)
+    H.assert_same(hip, ora, idx=idx, what=name)
+    # properties that hold for every candidate at any size
+    assert (hip["status"] == 0).all()
+    off = hip["stage_off"]
+    assert off[-1] == total_stages(w)
+    seg_max = np.maximum.reduceat(hip["comp_busy_ns"], off[:-1])
+    assert np.all(hip["batch_ns"] >= seg_max)
+    m, pp = w.cand["m"].astype(np.int64), w.cand["pp"].astype(np.int64)
+    assert np.all(hip["num_events"] >= 2 * m * pp + 2 * m * (pp - 1))
+
+
+def test_runs_are_deterministic(H):
+    _say("[case] determinism")
+    w = make_workload("gpt48")
+    a, b = H.run_hip(w), H.run_hip(w)
+    for k in ("status", "batch_ns", "num_events", "stage_off", "comp_busy_ns", "comm_busy_ns", "stage_tab"):
+        assert np.array_equal(a[k], b[k]), k
+    assert a["util"].tobytes() == b["util"].tobytes()
+
+
+def test_ragged_shapes_and_odd_stage_counts(H, oracle_mod):
+    """pp that is not a power of two (idle lanes inside a group), pp = 64 with many
+    micro-batches, m = 1, single stage, zero durations."""
+    _say("[case] ragged shapes")
+    rng = np.random.default_rng(77)
+    L = 96
+    costs = mk_costs(rng.integers(0, 5000, (2, L)).tolist(), rng.integers(0, 9000, (2, L)).tolist(),
+                     fa=rng.integers(0, 300, (2, L)).tolist(), ba=rng.integers(0, 300, (2, L)).tolist(),
+                     act=(rng.integers(0, 100, (2, L)) * 64).tolist(),
+                     grad=rng.integers(0, 1 << 20, (2, L)).tolist(),
+                     a2a=(rng.integers(0, 3, (2, L)) * 4096).tolist(), tps=(1, 2))
+    rows = []
+    N = 64 * 9 * 5 * 7 * 11                # 221 760: many divisors
+    for pp in (1, 2, 3, 5, 6, 7, 9, 10, 11, 12, 14, 15, 18, 20, 21, 22, 24, 28, 30, 33, 35, 36, 42, 44, 45, 55,
+               60, 63, 64, 66):
+        for tp in (1, 2):
+            if N % (pp * tp):
+                continue
+            dp = N // (pp * tp)
+            for m in (1, 2, 3, 17, 64):
+                for sc in (0, 1):
+                    bnd = None
+                    if pp <= L and (pp + m + sc) % 3 == 0:
+                        cuts = np.sort(rng.choice(np.arange(1, L), pp - 1, replace=False))
+                        bnd = [0] + cuts.tolist() + [L]
+                    rows.append((dp, tp, pp, m, sc, bnd))
+    rows.append((N // 64, 1, 64, 512, 1, None))
+    rows.append((N // 64, 1, 64, 512, 0, None))
+    for bucket in (0, 1 << 18):
+        w = mk(costs, mk_cluster(N, bucket=bucket), rows)
+        hip = H.run_hip(w)
+        ora = oracle_mod.simulate(w, nthreads=NT)
+        H.assert_same(hip, ora, what=f"ragged bucket={bucket}")
+        assert (ora["status"] == 0).sum() > 200
+    # all-zero table
+    z = mk_costs([0] * 8, [0] * 8)
+    w = mk(z, mk_cluster(4), [(1, 1, 4, 3, 1, None), (2, 1, 2, 1, 0, None), (4, 1, 1, 9, 0, None)])
+    H.assert_same(H.run_hip(w), oracle_mod.simulate(w), what="zeros")
+
+
+def test_invalid_range_and_capacity_status(H, oracle_mod):
+    _say("[case] status codes")
+    costs = mk_costs([10] * 4, [20] * 4, tps=(1,))
+    rows = [
+        (1, 1, 2, 4, 1, None), (2, 1, 2, 4, 1, None), (1, 2, 1, 4, 1, None), (1, 1, 2, 0, 1, None),
+        (1, 1, 2, 4, 1, [0, 0, 4]), (1, 1, 2, 4, 1, [0, 2, 3]), (1, 1, 2, 4, 2, None), (1, 1, 2, 4, 0, [0, 1, 4]),
+        (1, 1, 2, (1 << 16) + 1, 0, None), (-1, -1, 2, 4, 0, None), (1, 1, 0, 4, 0, None),
+    ]
+    w = mk(costs, mk_cluster(2), rows)
+    hip, ora = H.run_hip(w), oracle_mod.simulate(w)
+    H.assert_same(hip, ora, what="invalid mix")
+    assert list(hip["status"]) == [0, 1, 1, 1, 1, 1, 1, 0, 1, 1, 1]
+    assert all(hip["batch_ns"][i] == INT64_MAX for i in (1, 2, 3, 4, 5, 6, 8, 9, 10))
+    # partition offsets outside the pool
+    w2 = mk(costs, mk_cluster(2), [(1, 1, 2, 4, 1, [0, 2, 4])])
+    w2.cand["part_off"][0] = 1
+    assert H.run_hip(w2)["status"][0] == 1
+    w2.cand["part_off"][0] = -5
+    assert H.run_hip(w2)["status"][0] == 1
+    # 2^53 guard
+    big = mk_costs([1 << 48] * 4, [1 << 48] * 4)
+    w3 = mk(big, mk_cluster(2), [(1, 1, 2, 1, 1, None), (1, 1, 2, 4, 1, None), (1, 1, 2, 3, 0, None), (1, 1, 2, 5, 0, None)])
+    hip, ora = H.run_hip(w3), oracle_mod.simulate(w3)
+    H.assert_same(hip, ora, what="range")
+    assert list(hip["status"]) == [0, 2, 0, 2]
+    # not enough room: the candidates that do not fit are flagged, the others are untouched
+    w4 = mk(costs, mk_cluster(2), [(1, 1, 2, 4, 1, None)] * 5)
+    hip = H.run_hip(w4, stage_cap=7)
+    assert list(hip["status"]) == [0, 0, 0, 3, 3]
+    assert list(hip["batch_ns"][3:]) == [INT64_MAX] * 2
+    full = H.run_hip(w4)
+    assert np.array_equal(hip["batch_ns"][:3], full["batch_ns"][:3])
+    assert np.array_equal(hip["comp_busy_ns"][:6], full["comp_busy_ns"][:6])
+
+
+def test_empty_candidate_list(H):
+    _say("[case] C = 0")
+    w = mk(mk_costs([1, 2], [3, 4]), mk_cluster(2), [])
+    hip = H.run_hip(w, search=(0, None))
+    assert list(hip["stage_off"]) == [0]
+    assert hip["best"] == (-1, INT64_MAX)
+
+
+def test_search_parity(H, oracle_mod):
+    _say("[case] search")
+    w = make_workload("gpt48")
+    wgt = (w.cand["dp"].astype(np.int64) * w.cand["m"])
+    for obj in (0, 1):
+        hip = H.run_hip(w, search=(obj, wgt if obj else None))
+        want = oracle_mod.search(hip["batch_ns"], wgt if obj else None, obj)
+        assert hip["best"] == want
+    # ties, invalid entries and all-invalid, on raw arrays
+    import torch
+    import paper_2306_08423_amd as ds
+    c = H.ctx()
+    rng = np.random.default_rng(8)
+    for n in (1, 2, 63, 64, 65, 1000, 4097, 300_000):
+        b = rng.integers(1, 1 << 52, n)
+        b[rng.integers(0, n, n // 3 + 1)] = b[n // 2]
+        b[rng.random(n) < 0.1] = INT64_MAX
+        wg = rng.integers(-2, 1 << 20, n)
+        for obj in (0, 1):
+            best, scratch = ds.alloc_search(c, n)
+            ds.distsim_search(c, torch.from_numpy(b).to(c.device), n, best, scratch,
+                              weight=torch.from_numpy(wg).to(c.device), objective=obj)
+            got = tuple(int(x) for x in best.cpu().numpy())
+            assert got == oracle_mod.search(b, wg, obj), (n, obj)
+    b = np.full(100, INT64_MAX)
+    best, scratch = ds.alloc_search(c, 100)
+    ds.distsim_search(c, torch.from_numpy(b).to(c.device), 100, best, scratch)
+    assert tuple(int(x) for x in best.cpu().numpy()) == (-1, INT64_MAX)
+
+
+def test_api_errors(H):
+    _say("[case] api errors")
+    import paper_2306_08423_amd as ds
+    c = H.ctx()
+    w = make_workload("tiny")
+    dw = ds.upload(w, c.device)
+    ev = ds.alloc_events(c, dw.L, dw.V, dw.C, 4)
+    ev.struct.workspace_bytes = 16
+    with pytest.raises(ds.DistSimError, match="workspace too small"):
+        ds.distsim_build_events(c, dw, ev)
+    ev = ds.alloc_events(c, dw.L, dw.V, dw.C, 4)
+    dw.cluster["beta_bytes_per_ns"] = (0, 25)
+    with pytest.raises(ds.DistSimError, match="cluster"):
+        ds.distsim_build_events(c, dw, ev)
+    assert c.lib.distsim_workspace_bytes(300, 1, 10) == 0

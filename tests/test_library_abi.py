@@ -1,0 +1,53 @@
+"""The C-ABI library loads on a machine without a GPU and exports every symbol the header declares."""
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    txt = open(os.path.join(ROOT, "include", "distsim.h")).read()
+    txt = re.sub(r"/\*.*?\*/", "", txt, flags=re.S)
+    return sorted(set(re.findall(r"\b(distsim_[a-z_]+)\s*\(", txt)))
+
+
+def test_header_declares_the_three_calls():
+    names = _declared()
+    for n in ("distsim_build_events", "distsim_simulate", "distsim_search"):
+        assert n in names
+
+
+def test_library_exports_every_declared_symbol():
+    import paper_2306_08423_amd as ds
+    if not os.path.exists(ds.LIB_PATH):
+        from paper_2306_08423_amd.build import build_library
+        build_library()
+    lib = ds.load_library()
+    names = _declared()
+    assert len(names) >= 10
+    for n in names:
+        assert hasattr(lib, n), n
+    assert set(names) == set(ds.EXPORTS)
+
+
+def test_workspace_size_query_needs_no_gpu():
+    import paper_2306_08423_amd as ds
+    lib = ds.load_library()
+    a = lib.distsim_workspace_bytes(64, 4, 1000)
+    b = lib.distsim_workspace_bytes(64, 4, 1_000_000)
+    assert 0 < a < b
+    assert lib.distsim_workspace_bytes(0, 4, 10) == 0
+    assert lib.distsim_workspace_bytes(64, 17, 10) == 0
+    assert lib.distsim_search_scratch_bytes(10) > 0
+
+
+def test_product_package_does_not_import_the_oracle():
+    """The product path must never route through the CPU oracle."""
+    pkg = os.path.join(ROOT, "paper_2306_08423_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".hpp", ".h")):
+                txt = open(os.path.join(dirpath, f)).read()
+                assert "oracle" not in txt.lower(), os.path.join(dirpath, f)
