@@ -1,0 +1,162 @@
+#!/usr/bin/env python3
+"""Throughput of the batched strategy evaluation on one MI355X.
+
+One step = one pass of the whole hot path over one resident batch of candidates:
+distsim_build_events -> distsim_simulate -> distsim_search.  Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import hashlib
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+# fp64 add / max issue rate of the vector ALUs: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz.
+# (The published 78.6 TFLOP/s counts an FMA as two; add and max are one flop each.)
+ALU_PEAK_TFLOPS = 256 * 4 * 16 * 2.4e9 / 1e12
+HBM_PEAK_GBS = 8000.0
+FLOPS_PER_TASK = 3          # cross-stage end + p2p, max with the device's previous end, + duration
+
+
+def kernel_source_hash() -> str:
+    h = hashlib.sha256()
+    d = os.path.join(ROOT, "paper_2306_08423_amd", "csrc")
+    for f in sorted(os.listdir(d)):
+        h.update(open(os.path.join(d, f), "rb").read())
+    return h.hexdigest()[:16]
+
+
+def read_traffic(workload: str):
+    """HBM bytes per launch of k_simulate from the committed counter summary; None when the
+    kernel sources changed after the counters were taken."""
+    p = os.path.join(ROOT, "profiles", f"pmc_k_simulate_{workload}.txt")
+    if not os.path.exists(p):
+        return None
+    vals = {}
+    for line in open(p):
+        if ":" in line and not line.startswith("#"):
+            k, v = line.split(":", 1)
+            vals[k.strip()] = v.strip()
+    if vals.get("kernel_source_sha256_16") != kernel_source_hash():
+        return None
+    try:
+        return float(vals["hbm_bytes_per_launch"])
+    except (KeyError, ValueError):
+        return None
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="hetero64", help="hetero64 (default), gpt96, gpt48, gpt24")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build evaluates candidates on ONE GPU; --gpus must be 1 "
+              "(candidates would be sharded across GPUs with a 16-byte MINLOC exchange, which is not built)",
+              file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    import paper_2306_08423_amd as ds
+    from workloads import make_workload, subset, total_stages
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 3
+    w = make_workload(args.workload)
+    ctx = ds.Context(0)
+    dw = ds.upload(w, ctx.device)
+    S = total_stages(w)
+    ev = ds.alloc_events(ctx, dw.L, dw.V, dw.C, S)
+    out = ds.alloc_outputs(ctx, ev, util=True)
+    best, scratch = ds.alloc_search(ctx, dw.C)
+
+    def step():
+        ds.distsim_build_events(ctx, dw, ev)
+        ds.distsim_simulate(ctx, dw.cluster, ev, out)
+        ds.distsim_search(ctx, out.batch_ns, dw.C, best, scratch)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    ctx.timing_enable(True)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    kt = ctx.timing_read()
+    ctx.timing_enable(False)
+
+    C = dw.C
+    nev = int(ev.num_events[:C].sum().item())
+    status_ok = int((ev.status[:C] == 0).sum().item())
+    m = w.cand["m"].astype(np.int64)
+    pp = w.cand["pp"].astype(np.int64)
+    tasks = int((2 * m * pp).sum())
+    sim_ms, sim_n = kt["k_simulate"]
+    sim_avg_s = sim_ms / max(sim_n, 1) / 1e3
+    # algorithmic HBM bytes of k_simulate per launch: sorted descriptor (28 B) per candidate,
+    # 7 stage-table columns + 2 neighbour p2p words + layer range in (76 B) and comp/comm/util
+    # out (24 B) per stage, batch_ns out (8 B) per candidate
+    sim_bytes = C * (28 + 8) + S * (7 * 8 + 16 + 4 + 24)
+    roofline = {
+        "kernel": "k_simulate", "bound": "alu",
+        "achieved": FLOPS_PER_TASK * tasks / sim_avg_s / 1e12, "peak": ALU_PEAK_TFLOPS, "unit": "TFLOP/s",
+        "traffic": read_traffic(args.workload),
+        "avg_launch_ms": sim_avg_s * 1e3, "launches": sim_n,
+    }
+    roofline["frac"] = roofline["achieved"] / roofline["peak"]
+    roofline_hbm = {
+        "kernel": "k_simulate", "bound": "hbm", "achieved": sim_bytes / sim_avg_s / 1e9, "peak": HBM_PEAK_GBS,
+        "unit": "GB/s", "algorithmic_bytes_per_launch": sim_bytes,
+    }
+    roofline_hbm["frac"] = roofline_hbm["achieved"] / HBM_PEAK_GBS
+
+    cpu_baseline = None
+    parity = None
+    if not args.no_cpu_baseline:
+        import oracle
+        oracle.build()
+        ncores = min(os.cpu_count() or 1, 16)
+        ns = min(C, 100_000 if args.workload == "hetero64" else 20_000)
+        idx = np.sort(np.random.default_rng(20230608).choice(C, ns, replace=False))
+        ws = subset(w, idx)
+        oracle.simulate(subset(w, idx[:64]), nthreads=ncores)          # page the library in
+        t1 = time.perf_counter()
+        ora = oracle.simulate(ws, nthreads=ncores)
+        t_or = time.perf_counter() - t1
+        cpu_baseline = {"value": ns / t_or, "unit": "strategies/s", "cores": ncores, "kind": "oracle",
+                        "sample": f"{ns} seeded candidates of {args.workload}, {t_or:.2f} s wall",
+                        "events_per_s": int(ora["num_events"].sum()) / t_or}
+        got = out.batch_ns[:C].cpu().numpy()[idx]
+        parity = {"sampled": int(ns), "batch_ns_equal": bool(np.array_equal(got, ora["batch_ns"]))}
+
+    line = {
+        "metric": "candidate strategies simulated/sec", "value": C * args.steps / dt, "unit": "strategies/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": dt / args.steps * 1e3,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f64",
+        "data": "synthetic",
+        "config": {"workload": f"{args.workload}: {C} candidates, L={dw.L}, V={dw.V}, "
+                               f"{w.cluster['num_devices']} simulated devices, {S} stages, {tasks} stage-tasks",
+                   "candidates": C, "valid": status_ok},
+        "events_per_s": nev * args.steps / dt, "stage_tasks_per_s": tasks * args.steps / dt,
+        "kernel_ms": {k: (v[0] / max(v[1], 1)) * (v[1] / args.steps) for k, v in kt.items()},
+        "roofline": roofline, "roofline_hbm": roofline_hbm,
+        "cpu_baseline": cpu_baseline, "parity": parity,
+    }
+    print(json.dumps(line))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())
