@@ -28,6 +28,55 @@ __global__ __launch_bounds__(256) void k_sim_init(const int32_t* __restrict__ st
 // lane), so the cross-stage operand is the neighbour lane's register, read with a DPP shift.
 // Times are carried as doubles: every value is an integer below 2^53 (range guard at event
 // generation), so fp64 add and max are exact and one instruction each.
+//
+// Which lanes run a forward / backward task at a level is precomputed 32 levels at a time as
+// two per-lane bit patterns (bit 31 = first level of the chunk).  Adding a pattern to itself
+// shifts it by one level and drops the current level's bit into the carry mask, which becomes
+// the EXEC mask of the three fp64 instructions of the task: no per-level compares or selects.
+
+// bits of the chunk-relative levels a..b (inclusive), bit 31 = level 0
+__device__ __forceinline__ uint32_t level_bits(int a, int b) {
+    const bool any = a <= b && a <= 31 && b >= 0;
+    const int lo = a < 0 ? 0 : (a > 31 ? 31 : a);
+    const int hi = b > 31 ? 31 : (b < 0 ? 0 : b);
+    const uint32_t r = (0xffffffffu >> lo) & (0xffffffffu << (31 - hi));
+    return any ? r : 0u;
+}
+
+// One level for the lanes whose pattern bit is set: own = max(own, nb + lat) + dur.
+// Requires EXEC == all ones on entry (wave-uniform control flow, full wavefronts) and leaves
+// it so.  The trailing s_nop keeps two wait states between the write of `own` and the DPP
+// read that follows.
+#define DISTSIM_STEP_ONE(bits, nb, lat, dur)                                   \
+    asm volatile(                                                              \
+        "v_add_co_u32_e64 %[p], %[k], %[p], %[p]\n\t"                        \
+        "s_mov_b64 exec, %[k]\n\t"                                            \
+        "v_add_f64 %[t], %[t], %[c]\n\t"                                      \
+        "v_max_f64 %[t], %[t], %[o]\n\t"                                      \
+        "v_add_f64 %[o], %[t], %[d]\n\t"                                      \
+        "s_mov_b64 exec, -1\n\t"                                              \
+        "s_nop 0"                                                              \
+        : [o] "+v"(own), [t] "+v"(nb), [p] "+v"(bits), [k] "=&s"(kmask)       \
+        : [c] "v"(lat), [d] "v"(dur))
+
+#define DISTSIM_STEP_BOTH()                                                    \
+    asm volatile(                                                              \
+        "v_add_co_u32_e64 %[pf], %[kf], %[pf], %[pf]\n\t"                    \
+        "v_add_co_u32_e64 %[pb], %[kb], %[pb], %[pb]\n\t"                    \
+        "s_mov_b64 exec, %[kf]\n\t"                                           \
+        "v_add_f64 %[tl], %[tl], %[cl]\n\t"                                   \
+        "v_max_f64 %[tl], %[tl], %[o]\n\t"                                    \
+        "v_add_f64 %[o], %[tl], %[df]\n\t"                                    \
+        "s_mov_b64 exec, %[kb]\n\t"                                           \
+        "v_add_f64 %[tr], %[tr], %[cr]\n\t"                                   \
+        "v_max_f64 %[tr], %[tr], %[o]\n\t"                                    \
+        "v_add_f64 %[o], %[tr], %[db]\n\t"                                    \
+        "s_mov_b64 exec, -1\n\t"                                              \
+        "s_nop 0"                                                              \
+        : [o] "+v"(own), [tl] "+v"(fromL), [tr] "+v"(fromR), [pf] "+v"(PFb), [pb] "+v"(PBb),  \
+          [kf] "=&s"(kmask), [kb] "=&s"(kmask2)                               \
+        : [cl] "v"(pfL), [cr] "v"(pbR), [df] "v"(Fd), [db] "v"(Bd))
+
 __global__ __launch_bounds__(256) void k_simulate(CostsDev co, ClusterDev cl, Workspace ws, EventsDev ev,
                                                   SimOut out) {
     const int lane = lane_id();
@@ -66,28 +115,51 @@ __global__ __launch_bounds__(256) void k_simulate(CostsDev co, ClusterDev cl, Wo
         }
         const double Fd = (double)(FC + FA), Bd = (double)(BC + BA);
 
-        // level predicates, expressed on x = level - s
-        int wc, two_w, offB, stepB;
+        // level windows of this lane, expressed on x = level - s:
+        //   forward  x in [0, f1hi]  and  even x in [f2lo, f2hi]
+        //   backward x in [blo, bhi], every x (GPipe) or every second x (1F1B)
+        int f1hi, f2lo = 1, f2hi = 0, blo, bhi;
         if (sched == 0) {
-            wc = m - 1; two_w = 0x7fffffff; offB = m + 2 * pp - 2 - 2 * s; stepB = 1;
+            f1hi = m - 1;
+            blo = m + 2 * pp - 2 - 2 * s; bhi = blo + m - 1;
         } else {
             int wq = pp - 1 - s; if (wq > m) wq = m;
-            wc = wq < m - 1 ? wq : m - 1; two_w = 2 * wq; offB = 2 * pp - 1 - 2 * s; stepB = 2;
+            f1hi = wq < m - 1 ? wq : m - 1;
+            f2lo = 2 * wq + 2; f2hi = 2 * m - 2;
+            blo = 2 * pp - 1 - 2 * s; bhi = blo + 2 * m - 2;
         }
-        const int spanB = m * stepB, maskB = stepB - 1, two_m = 2 * m;
-        const int nlev = wave_max_i32(act ? 2 * (m + pp - 1) : 0);
+        const int nlev = __builtin_amdgcn_readfirstlane(wave_max_i32(act ? 2 * (m + pp - 1) : 0));
 
         double own = 0.0;
-        int x = -s;
-        for (int lvl = 0; lvl < nlev; lvl++, x++) {
-            const double fromL = from_prev_lane(own);
-            const double fromR = from_next_lane(own);
-            const bool doF = x >= 0 && (x <= wc || ((x & 1) == 0 && x > two_w && x < two_m));
-            const int y = x - offB;
-            const bool doB = y >= 0 && y < spanB && (y & maskB) == 0;
-            const double eF = __builtin_fmax(own, fromL + pfL) + Fd;
-            const double eB = __builtin_fmax(own, fromR + pbR) + Bd;
-            own = doF ? eF : (doB ? eB : own);
+        for (int l0 = 0; l0 < nlev; l0 += 32) {
+            const int x0 = l0 - s;
+            const uint32_t even_x = (x0 & 1) ? 0x55555555u : 0xaaaaaaaau;       // levels with even x
+            uint32_t PFb = level_bits(-x0, f1hi - x0) | (level_bits(f2lo - x0, f2hi - x0) & even_x);
+            uint32_t PBb = level_bits(blo - x0, bhi - x0);
+            if (sched != 0) PBb &= ((blo - x0) & 1) ? 0x55555555u : 0xaaaaaaaau;   // x - blo even
+            if (!act) { PFb = 0; PBb = 0; }
+            const bool anyF = __builtin_amdgcn_ballot_w64(PFb != 0) != 0;
+            const bool anyB = __builtin_amdgcn_ballot_w64(PBb != 0) != 0;
+            const int n = nlev - l0 < 32 ? nlev - l0 : 32;
+            uint64_t kmask, kmask2;
+            if (anyF && anyB) {
+                for (int k = 0; k < n; k++) {
+                    double fromL = from_prev_lane(own);
+                    double fromR = from_next_lane(own);
+                    DISTSIM_STEP_BOTH();
+                }
+            } else if (anyF) {
+                for (int k = 0; k < n; k++) {
+                    double fromL = from_prev_lane(own);
+                    DISTSIM_STEP_ONE(PFb, fromL, pfL, Fd);
+                }
+            } else if (anyB) {
+                for (int k = 0; k < n; k++) {
+                    double fromR = from_next_lane(own);
+                    DISTSIM_STEP_ONE(PBb, fromR, pbR, Bd);
+                }
+            }
+            (void)kmask; (void)kmask2;
         }
 
         // data-parallel modelling: gradient all-reduce after (or overlapped with) the last backward
