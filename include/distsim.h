@@ -20,8 +20,9 @@
  *  - All times are int64 nanoseconds, all sizes int64 bytes.
  *  - Return value: DISTSIM_OK, or a negative code; text via distsim_last_error().
  *    A *candidate* that is not a valid strategy is not a call error: see `status`.
- *  - Preconditions on table entries (not checked): 0 <= time < 2^40 ns, 0 <= bytes < 2^44,
- *    0 <= alpha < 2^40, 1 <= beta < 2^32, 1 <= gpus_per_node.
+ *  - Preconditions on table entries (not checked): 0 <= time < 2^40 ns, 0 <= bytes < 2^40,
+ *    0 <= alpha < 2^40, 1 <= beta < 2^32, num_devices <= 2^14, so that no product in the
+ *    collective formulas below leaves 63 bits.
  */
 #ifndef DISTSIM_H
 #define DISTSIM_H
@@ -47,9 +48,11 @@ extern "C" {
 
 /* per-candidate status written by distsim_build_events */
 #define DISTSIM_ST_OK       0
+#define DISTSIM_MAX_M    65536 /* micro-batches per candidate                                 */
 #define DISTSIM_ST_INVALID  1  /* "unreachable" strategy (Sec. 6): dp*tp*pp != devices, pp > L,
-                                  pp > DISTSIM_MAX_PP, m < 1, no table variant for tp, unknown
-                                  schedule, or a partition that is not 0 = b0 < b1 < ... < bpp = L */
+                                  pp > DISTSIM_MAX_PP, m < 1, m > DISTSIM_MAX_M, no table variant
+                                  for tp, unknown schedule, or a partition that is not
+                                  0 = b0 < b1 < ... < bpp = L                                    */
 #define DISTSIM_ST_RANGE    2  /* m * (sum of all stage-task and p2p durations) >= 2^53        */
 #define DISTSIM_ST_NOROOM   3  /* valid, but its stages do not fit stage_cap                    */
 
@@ -128,14 +131,22 @@ enum {
 /*
  * The event flow of all candidates: output of distsim_build_events, input of
  * distsim_simulate.  All pointers are caller-allocated device memory.
- * Per-stage arrays are ragged: candidate c owns entries stage_off[c] .. stage_off[c+1]-1
- * (pp entries if status[c] == DISTSIM_ST_OK, none otherwise).
+ *
+ * Per-stage arrays (stage_tab, stage_layers and the per-stage outputs of distsim_simulate)
+ * are laid out in the order in which the library visits candidates, not in the caller's
+ * order: candidate c with status[c] == DISTSIM_ST_OK owns the entries
+ * stage_pos[c] .. stage_pos[c] + pp - 1.  A candidate occupies pp rounded up to a power of
+ * two entries and candidates of equal rounded size are packed 64 entries to a wavefront, so
+ *   stage_cap >= distsim_stage_entries(C)   (= 64 C + 448, always enough), or any tighter
+ *   bound >= 64 * sum over k of ceil(n_k 2^k / 64) with n_k = candidates whose rounded pp is 2^k;
+ * candidates that do not fit get DISTSIM_ST_NOROOM.  Entries not owned by any candidate are
+ * written as zero.
  */
 typedef struct {
     int64_t  stage_cap;      /* entries available in every per-stage array                        */
     int32_t  L, V;           /* table shape; filled in by distsim_build_events                    */
     int32_t *status;         /* [C]                                                               */
-    int64_t *stage_off;      /* [C+1] exclusive prefix of the stage counts                        */
+    int64_t *stage_pos;      /* [C] first per-stage entry of the candidate, -1 if it has none     */
     int64_t *stage_tab;      /* [DISTSIM_NCOLS][stage_cap]                                        */
     int32_t *stage_layers;   /* [stage_cap] first layer | (one past last layer) << 8              */
     int64_t *num_events;     /* [C] events on the pp distinct device timelines: 2 m pp stage-tasks
@@ -143,6 +154,9 @@ typedef struct {
     void    *workspace;      /* distsim_workspace_bytes() bytes, 256-byte aligned; opaque         */
     size_t   workspace_bytes;
 } distsim_events;
+
+/* A stage_cap that is always enough for C candidates. */
+int64_t distsim_stage_entries(int64_t C);
 
 /* Bytes of distsim_events.workspace needed for tables of (L, V) and C candidates. */
 size_t distsim_workspace_bytes(int32_t L, int32_t V, int64_t C);
@@ -152,8 +166,8 @@ size_t distsim_workspace_bytes(int32_t L, int32_t V, int64_t C);
  * validate, map layers to composed events, evaluate collective events, reduce the layer
  * events of each stage (segmented sums over the layer axis) and write the stage table.
  * Also prepares, inside the workspace, the order in which distsim_simulate visits candidates.
- * Errors: EINVAL (null pointers, C < 0, L/V out of limits, workspace too small,
- * stage_cap < 0), EHIP.  C == 0 is a no-op apart from stage_off[0] = 0.
+ * Errors: EINVAL (null pointers, workspace too small, stage_cap < 0), ERANGE (C, L or V
+ * outside their limits), EHIP.  C == 0 is valid.
  */
 int distsim_build_events(distsim_ctx *ctx, const distsim_costs *costs, const distsim_cluster *cluster,
                          const distsim_candidates *cand, int64_t C, distsim_events *out,
@@ -166,8 +180,8 @@ int distsim_build_events(distsim_ctx *ctx, const distsim_costs *costs, const dis
  * duration, then the gradient all-reduce event(s) follow the device's last backward.
  * Outputs (device): batch_ns[C] = time of the last event (INT64_MAX unless status OK);
  * comp_busy_ns / comm_busy_ns [stage_cap] = sum of the durations of the computation /
- * communication events on each stage's device (index stage_off[c] + s); util (may be NULL)
- * = comp_busy / batch as fp64.  `events` must come from distsim_build_events with the same
+ * communication events on each stage's device (index stage_pos[c] + s); util (may be NULL)
+ * = comp_busy / batch as fp64; entries not owned by an OK candidate are written as zero.  `events` must come from distsim_build_events with the same
  * cluster and C.  Errors: EINVAL, EHIP.
  */
 int distsim_simulate(distsim_ctx *ctx, const distsim_cluster *cluster, const distsim_events *events,
@@ -193,7 +207,7 @@ int distsim_search(distsim_ctx *ctx, const int64_t *batch_ns, const int64_t *wei
  * the accumulated time and launch count of one kernel, then clears that kernel's record.
  */
 enum {
-    DISTSIM_K_LAYER_TABLES = 0, DISTSIM_K_DECODE, DISTSIM_K_SCAN, DISTSIM_K_BINS, DISTSIM_K_SCATTER,
+    DISTSIM_K_LAYER_TABLES = 0, DISTSIM_K_DECODE, DISTSIM_K_BINS, DISTSIM_K_SCATTER,
     DISTSIM_K_STAGE_EVENTS, DISTSIM_K_SIM_INIT, DISTSIM_K_SIMULATE, DISTSIM_K_SEARCH, DISTSIM_K_COUNT
 };
 int distsim_timing_enable(distsim_ctx *ctx, int on);

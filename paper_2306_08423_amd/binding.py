@@ -17,14 +17,14 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libdistsim_hip.so")
 
 EXPORTS = (
-    "distsim_create", "distsim_destroy", "distsim_last_error", "distsim_workspace_bytes",
+    "distsim_create", "distsim_destroy", "distsim_last_error", "distsim_workspace_bytes", "distsim_stage_entries",
     "distsim_build_events", "distsim_simulate", "distsim_search_scratch_bytes", "distsim_search",
     "distsim_timing_enable", "distsim_timing_read", "distsim_kernel_name",
 )
 
 NCOLS = 8
 COL = {"FC": 0, "FA": 1, "BC": 2, "BA": 3, "PF": 4, "PB": 5, "G": 6, "AR": 7}
-KERNELS = ("k_layer_tables", "k_decode", "k_scan", "k_bins", "k_scatter", "k_stage_events",
+KERNELS = ("k_layer_tables", "k_decode", "k_bins", "k_scatter", "k_stage_events",
            "k_sim_init", "k_simulate", "k_search")
 INT64_MAX = (1 << 63) - 1
 
@@ -50,7 +50,7 @@ class _Cand(C.Structure):
 
 class _Events(C.Structure):
     _fields_ = [("stage_cap", C.c_int64), ("L", C.c_int32), ("V", C.c_int32),
-                ("status", C.c_void_p), ("stage_off", C.c_void_p), ("stage_tab", C.c_void_p),
+                ("status", C.c_void_p), ("stage_pos", C.c_void_p), ("stage_tab", C.c_void_p),
                 ("stage_layers", C.c_void_p), ("num_events", C.c_void_p),
                 ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t)]
 
@@ -74,6 +74,8 @@ def load_library():
     lib.distsim_last_error.restype = C.c_char_p
     lib.distsim_workspace_bytes.argtypes = [C.c_int32, C.c_int32, C.c_int64]
     lib.distsim_workspace_bytes.restype = C.c_size_t
+    lib.distsim_stage_entries.argtypes = [C.c_int64]
+    lib.distsim_stage_entries.restype = C.c_int64
     lib.distsim_build_events.argtypes = [C.c_void_p, C.POINTER(_Costs), C.POINTER(_Cluster), C.POINTER(_Cand),
                                          C.c_int64, C.POINTER(_Events), C.c_void_p]
     lib.distsim_build_events.restype = C.c_int
@@ -193,7 +195,7 @@ class Events:
     C: int
     stage_cap: int
     status: torch.Tensor
-    stage_off: torch.Tensor
+    stage_pos: torch.Tensor
     stage_tab: torch.Tensor
     stage_layers: torch.Tensor
     num_events: torch.Tensor
@@ -201,22 +203,48 @@ class Events:
     struct: _Events
 
 
-def alloc_events(ctx: Context, L: int, V: int, Cn: int, stage_cap: int) -> Events:
+def stage_entries(pp) -> int:
+    """Tight stage_cap for a host-side array of stage counts: every candidate takes pp rounded
+    up to a power of two, candidates of one size class are packed 64 entries to a wavefront."""
+    import numpy as np
+    pp = np.clip(np.asarray(pp, dtype=np.int64), 1, 64)
+    width = 1 << np.ceil(np.log2(pp)).astype(np.int64)
+    total = 0
+    for k in range(7):
+        n = int((width == (64 >> k)).sum())
+        total += -(-n // (1 << k)) * 64
+    return total
+
+
+def stage_rows(status, stage_pos, pp):
+    """Host-side index helper: positions in the per-stage arrays of the stages of every OK
+    candidate, concatenated in candidate order, and the per-candidate counts."""
+    import numpy as np
+    ok = np.asarray(status) == 0
+    cnt = np.where(ok, np.asarray(pp, dtype=np.int64), 0)
+    start = np.where(ok, np.asarray(stage_pos, dtype=np.int64), 0)
+    first = np.repeat(np.cumsum(cnt) - cnt, cnt)
+    return np.repeat(start, cnt) + (np.arange(int(cnt.sum())) - first), cnt
+
+
+def alloc_events(ctx: Context, L: int, V: int, Cn: int, stage_cap: Optional[int] = None) -> Events:
     dev = ctx.device
+    if stage_cap is None:
+        stage_cap = ctx.lib.distsim_stage_entries(Cn)
     nbytes = ctx.lib.distsim_workspace_bytes(L, V, Cn)
     if nbytes == 0:
         raise DistSimError("distsim_workspace_bytes rejected (L, V, C)")
     status = torch.empty(max(Cn, 1), dtype=torch.int32, device=dev)
-    stage_off = torch.empty(Cn + 1, dtype=torch.int64, device=dev)
+    stage_pos = torch.empty(max(Cn, 1), dtype=torch.int64, device=dev)
     cap = max(int(stage_cap), 0)
     stage_tab = torch.empty((NCOLS, max(cap, 1)), dtype=torch.int64, device=dev)
     stage_layers = torch.empty(max(cap, 1), dtype=torch.int32, device=dev)
     num_events = torch.empty(max(Cn, 1), dtype=torch.int64, device=dev)
     # torch's caching allocator hands out 512-byte aligned blocks
     workspace = torch.empty(nbytes, dtype=torch.uint8, device=dev)
-    st = _Events(cap, 0, 0, _ptr(status), _ptr(stage_off), _ptr(stage_tab), _ptr(stage_layers), _ptr(num_events),
+    st = _Events(cap, 0, 0, _ptr(status), _ptr(stage_pos), _ptr(stage_tab), _ptr(stage_layers), _ptr(num_events),
                  _ptr(workspace), nbytes)
-    return Events(Cn, cap, status, stage_off, stage_tab, stage_layers, num_events, workspace, st)
+    return Events(Cn, cap, status, stage_pos, stage_tab, stage_layers, num_events, workspace, st)
 
 
 def distsim_build_events(ctx: Context, dw: DeviceWorkload, ev: Events) -> None:

@@ -60,6 +60,20 @@ __device__ __forceinline__ int64_t wave_inclusive_sum(int64_t v) {
     return v;
 }
 
+// Truncating unsigned division.  Operands below 2^53 (the usual case) go through one
+// correctly rounded fp64 division and an exact integer fix-up of the quotient; anything
+// larger takes the generic 64-bit path.
+__device__ __forceinline__ uint64_t udiv64(uint64_t num, uint64_t den) {
+    if (((num | den) >> 53) == 0) {
+        uint64_t q = (uint64_t)((double)num / (double)den);
+        int64_t r = (int64_t)(num - q * den);
+        while (r < 0) { q--; r += (int64_t)den; }
+        while (r >= (int64_t)den) { q++; r -= (int64_t)den; }
+        return q;
+    }
+    return num / den;
+}
+
 // ---- collective cost events (Sec. 4.2 ring volume; integer, truncating) ---------------
 
 struct ClusterDev {
@@ -69,17 +83,17 @@ struct ClusterDev {
 };
 
 __device__ __forceinline__ int64_t p2p_ns(const ClusterDev& cl, int64_t bytes, int k) {
-    return cl.alpha[k] + (int64_t)((uint64_t)bytes / (uint64_t)cl.beta[k]);
+    return cl.alpha[k] + (int64_t)udiv64((uint64_t)bytes, (uint64_t)cl.beta[k]);
 }
 __device__ __forceinline__ int64_t allreduce_ns(const ClusterDev& cl, int64_t n, int64_t bytes) {
     if (n <= 1 || bytes <= 0) return 0;
     const int k = n <= cl.gpus_per_node ? 0 : 1;
-    return cl.alpha[k] + (int64_t)((2ull * (uint64_t)(n - 1) * (uint64_t)bytes) / ((uint64_t)n * (uint64_t)cl.beta[k]));
+    return cl.alpha[k] + (int64_t)udiv64(2ull * (uint64_t)(n - 1) * (uint64_t)bytes, (uint64_t)n * (uint64_t)cl.beta[k]);
 }
 __device__ __forceinline__ int64_t alltoall_ns(const ClusterDev& cl, int64_t n, int64_t bytes) {
     if (n <= 1 || bytes <= 0) return 0;
     const int k = n <= cl.gpus_per_node ? 0 : 1;
-    return cl.alpha[k] + (int64_t)(((uint64_t)(n - 1) * (uint64_t)bytes) / ((uint64_t)n * (uint64_t)cl.beta[k]));
+    return cl.alpha[k] + (int64_t)udiv64((uint64_t)(n - 1) * (uint64_t)bytes, (uint64_t)n * (uint64_t)cl.beta[k]);
 }
 
 }  // namespace distsim

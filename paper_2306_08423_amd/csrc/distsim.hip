@@ -27,7 +27,7 @@ struct distsim_ctx {
 };
 
 static const char* kKernelNames[DISTSIM_K_COUNT] = {
-    "k_layer_tables", "k_decode", "k_scan", "k_bins", "k_scatter",
+    "k_layer_tables", "k_decode", "k_bins", "k_scatter",
     "k_stage_events", "k_sim_init", "k_simulate", "k_search",
 };
 
@@ -114,6 +114,8 @@ void distsim_destroy(distsim_ctx* ctx) {
 
 const char* distsim_last_error(const distsim_ctx* ctx) { return ctx ? ctx->err.c_str() : "null context"; }
 
+int64_t distsim_stage_entries(int64_t C) { return C < 0 ? 0 : C * kWave + (kClasses * kWave); }
+
 size_t distsim_workspace_bytes(int32_t L, int32_t V, int64_t C) {
     if (L < 1 || L > DISTSIM_MAX_L || V < 1 || V > DISTSIM_MAX_V || C < 0) return 0;
     Workspace w;
@@ -131,10 +133,11 @@ int distsim_build_events(distsim_ctx* ctx, const distsim_costs* costs, const dis
     if (!costs->variant_tp || !costs->fwd_comp_ns || !costs->bwd_comp_ns || !costs->fwd_comm_ns ||
         !costs->bwd_comm_ns || !costs->act_bytes || !costs->grad_bytes)
         return fail(ctx, DISTSIM_EINVAL, "null cost column");
-    if (!out->stage_off || !out->workspace || out->stage_cap < 0)
-        return fail(ctx, DISTSIM_EINVAL, "events: null stage_off/workspace or negative stage_cap");
+    if (!out->workspace || out->stage_cap < 0)
+        return fail(ctx, DISTSIM_EINVAL, "events: null workspace or negative stage_cap");
     if (C > 0 && (!cand->dp || !cand->tp || !cand->pp || !cand->m || !cand->schedule || !cand->part_off ||
-                  !out->status || !out->num_events || (out->stage_cap > 0 && (!out->stage_tab || !out->stage_layers))))
+                  !out->status || !out->num_events || !out->stage_pos ||
+                  (out->stage_cap > 0 && (!out->stage_tab || !out->stage_layers))))
         return fail(ctx, DISTSIM_EINVAL, "null candidate or events array");
     if (((uintptr_t)out->workspace & 255) != 0) return fail(ctx, DISTSIM_EINVAL, "workspace must be 256-byte aligned");
     Workspace ws;
@@ -148,11 +151,10 @@ int distsim_build_events(distsim_ctx* ctx, const distsim_costs* costs, const dis
     const ClusterDev cl = to_dev(*cluster);
     CandDev ca{cand->dp, cand->tp, cand->pp, cand->m, cand->schedule, cand->part_off, cand->part_pool,
                cand->part_pool ? cand->part_pool_len : 0};
-    EventsDev ev{out->stage_cap, out->stage_tab, out->stage_layers, out->num_events};
+    EventsDev ev{out->stage_cap, out->status, out->stage_pos, out->stage_tab, out->stage_layers, out->num_events};
     out->L = costs->L;
     out->V = costs->V;
 
-    const int64_t nblk = (C + kScanChunk - 1) / kScanChunk;
     const int cblocks = (int)((C + 255) / 256);
     {
         Timer t(ctx, st, DISTSIM_K_LAYER_TABLES);
@@ -161,15 +163,7 @@ int distsim_build_events(distsim_ctx* ctx, const distsim_costs* costs, const dis
     }
     if (C > 0) {
         Timer t(ctx, st, DISTSIM_K_DECODE);
-        hipLaunchKernelGGL(k_decode, dim3(cblocks), dim3(256), 0, st, co, cl, ca, C, ws, out->status, out->num_events);
-    }
-    {
-        Timer t(ctx, st, DISTSIM_K_SCAN);
-        if (C > 0) hipLaunchKernelGGL(k_scan_reduce, dim3((int)nblk), dim3(kScanBlock), 0, st, ws.npp, C, ws.block_sums);
-        hipLaunchKernelGGL(k_scan_top, dim3(1), dim3(kScanBlock), 0, st, ws.block_sums, nblk);
-        // with C == 0 one block still writes stage_off[0] = block_sums[0] = 0
-        hipLaunchKernelGGL(k_scan_apply, dim3((int)(nblk > 0 ? nblk : 1)), dim3(kScanBlock), 0, st, ws.npp, C,
-                           ws.block_sums, nblk, out->stage_off);
+        hipLaunchKernelGGL(k_decode, dim3(cblocks), dim3(256), 0, st, co, cl, ca, C, ws, ev);
     }
     {
         Timer t(ctx, st, DISTSIM_K_BINS);
@@ -178,8 +172,7 @@ int distsim_build_events(distsim_ctx* ctx, const distsim_costs* costs, const dis
     if (C > 0) {
         {
             Timer t(ctx, st, DISTSIM_K_SCATTER);
-            hipLaunchKernelGGL(k_scatter, dim3(cblocks), dim3(256), 0, st, ca, C, ws, out->stage_cap, out->stage_off,
-                               out->status, out->num_events);
+            hipLaunchKernelGGL(k_scatter, dim3(cblocks), dim3(256), 0, st, ca, C, ws, ev);
         }
         Timer t(ctx, st, DISTSIM_K_STAGE_EVENTS);
         hipLaunchKernelGGL(k_stage_events, dim3(item_grid(ctx, C)), dim3(256), 0, st, co, cl, ca, ws, ev);
@@ -196,7 +189,7 @@ int distsim_simulate(distsim_ctx* ctx, const distsim_cluster* cluster, const dis
     if (!cluster_ok(cluster)) return fail(ctx, DISTSIM_EINVAL, "cluster description out of range");
     if (C < 0 || C > 0x7fffffff) return fail(ctx, DISTSIM_ERANGE, "candidate count outside [0, 2^31)");
     if (C == 0) return DISTSIM_OK;
-    if (!batch_ns || !events->status || !events->workspace || !events->stage_off ||
+    if (!batch_ns || !events->status || !events->workspace ||
         (events->stage_cap > 0 && (!comp_busy_ns || !comm_busy_ns || !events->stage_tab || !events->stage_layers)))
         return fail(ctx, DISTSIM_EINVAL, "null output or events array");
     HIP_TRY(hipSetDevice(ctx->device));
@@ -209,7 +202,8 @@ int distsim_simulate(distsim_ctx* ctx, const distsim_cluster* cluster, const dis
     CostsDev co{};
     co.L = events->L; co.V = events->V;
     const ClusterDev cl = to_dev(*cluster);
-    EventsDev ev{events->stage_cap, events->stage_tab, events->stage_layers, events->num_events};
+    EventsDev ev{events->stage_cap, events->status, events->stage_pos, events->stage_tab, events->stage_layers,
+                 events->num_events};
     SimOut out{batch_ns, comp_busy_ns, comm_busy_ns, util};
     {
         Timer t(ctx, st, DISTSIM_K_SIM_INIT);

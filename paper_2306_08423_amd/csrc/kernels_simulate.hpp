@@ -82,7 +82,8 @@ __global__ __launch_bounds__(256) void k_simulate(CostsDev co, ClusterDev cl, Wo
     const int lane = lane_id();
     const int64_t wave0 = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / kWave;
     const int64_t nwaves = ((int64_t)gridDim.x * blockDim.x) / kWave;
-    const int64_t W = ws.hdr[H_NUM_ITEMS];
+    int64_t W = ws.hdr[H_NUM_ITEMS];
+    if (W * kWave > ev.stage_cap) W = ev.stage_cap / kWave;
     const int64_t cap = ev.stage_cap;
     const int L = co.L;
     const double ninf = -__builtin_huge_val();
@@ -92,27 +93,22 @@ __global__ __launch_bounds__(256) void k_simulate(CostsDev co, ClusterDev cl, Wo
         const int width = 1 << it.sh;
         const int s = lane & (width - 1);
         const int64_t pos = it.pos0 + (lane >> it.sh);
-        int pp = 0, v = 0, m = 0, dp = 1, sched = 0;
-        int64_t off = 0, c = 0;
-        if (pos < it.class_end) {
-            const int meta = ws.s_meta[pos];
-            pp = meta & 0xff; sched = (meta >> 8) & 0xff; v = meta >> 16;
-            m = ws.s_m[pos]; dp = ws.s_dp[pos];
-            off = ws.s_off[pos]; c = ws.s_cand[pos];
-        }
+        int4 dd = make_int4(0, 0, 0, 0);                   // cand, meta, m, dp
+        if (pos < it.class_end) dd = *reinterpret_cast<const int4*>(&ws.desc[pos]);
+        const int pp = dd.y & 0xff, sched = (dd.y >> 8) & 0xff, v = dd.y >> 16, dp = dd.y ? dd.w : 1;
+        const int64_t c = dd.x;
         const bool act = s < pp;
-        if (!act) m = 0;
-        const int64_t i = off + s;
-        int64_t FC = 0, FA = 0, BC = 0, BA = 0, PF = 0, PB = 0, AR = 0;
-        double pfL = ninf, pbR = ninf;      // p2p latency on the incoming edges; -inf = no edge
-        if (act) {
-            FC = ev.stage_tab[0 * cap + i]; FA = ev.stage_tab[1 * cap + i];
-            BC = ev.stage_tab[2 * cap + i]; BA = ev.stage_tab[3 * cap + i];
-            PF = ev.stage_tab[4 * cap + i]; PB = ev.stage_tab[5 * cap + i];
-            AR = ev.stage_tab[7 * cap + i];
-            if (s > 0) pfL = (double)ev.stage_tab[4 * cap + i - 1];
-            if (s + 1 < pp) pbR = (double)ev.stage_tab[5 * cap + i + 1];
-        }
+        const int m = act ? dd.z : 0;
+        const int64_t i = w * kWave + lane;
+        // rows of lanes outside a candidate are zero-filled by event generation
+        const int64_t FC = ev.stage_tab[0 * cap + i], FA = ev.stage_tab[1 * cap + i];
+        const int64_t BC = ev.stage_tab[2 * cap + i], BA = ev.stage_tab[3 * cap + i];
+        const int64_t PF = ev.stage_tab[4 * cap + i], PB = ev.stage_tab[5 * cap + i];
+        const int64_t AR = ev.stage_tab[7 * cap + i];
+        // p2p latency on the incoming edges (the neighbours' outgoing events); -inf = no edge
+        double pfL = from_prev_lane((double)PF), pbR = from_next_lane((double)PB);
+        if (!(act && s > 0)) pfL = ninf;
+        if (!(act && s + 1 < pp)) pbR = ninf;
         const double Fd = (double)(FC + FA), Bd = (double)(BC + BA);
 
         // level windows of this lane, expressed on x = level - s:
@@ -178,7 +174,7 @@ __global__ __launch_bounds__(256) void k_simulate(CostsDev co, ClusterDev cl, Wo
                 for (int l = hi - 1; l >= lo; l--) {
                     const int64_t ready = startB + (tot_hi - (ws.pbc[vr + l] + ws.pba[rr + l]));
                     acc += ws.pg[vr + l + 1] - ws.pg[vr + l];
-                    const int64_t k = acc / cl.bucket;
+                    const int64_t k = (int64_t)udiv64((uint64_t)acc, (uint64_t)cl.bucket);
                     if (k > 0) {
                         t = (t > ready ? t : ready) + k * ar_cap;
                         ar_busy += k * ar_cap;
@@ -194,14 +190,13 @@ __global__ __launch_bounds__(256) void k_simulate(CostsDev co, ClusterDev cl, Wo
             }
         }
         const int64_t batch = group_max(act ? finish : 0, width);
-        if (act) {
-            const int64_t comp = (int64_t)m * (FC + BC);
-            const int64_t comm = (int64_t)m * (FA + BA + PF + PB) + ar_busy;
-            out.comp_busy[i] = comp;
-            out.comm_busy[i] = comm;
-            if (out.util) out.util[i] = batch > 0 ? (double)comp / (double)batch : 0.0;
-            if (s == 0) out.batch_ns[c] = batch;
-        }
+        // lanes outside a candidate have m = 0 and zero rows: they store zeros
+        const int64_t comp = (int64_t)m * (FC + BC);
+        const int64_t comm = act ? (int64_t)m * (FA + BA + PF + PB) + ar_busy : 0;
+        out.comp_busy[i] = comp;
+        out.comm_busy[i] = comm;
+        if (out.util) out.util[i] = batch > 0 ? (double)comp / (double)batch : 0.0;
+        if (act && s == 0) out.batch_ns[c] = batch;
     }
 }
 

@@ -20,25 +20,27 @@ enum {
     H_WORDS = 32
 };
 
+// One candidate in visiting order (32 bytes; the first 16 are all that simulate needs).
+struct alignas(16) Desc {
+    int32_t cand;                  // index in the caller's arrays
+    int32_t meta;                  // pp | schedule << 8 | variant << 16 ; pp == 0: skip
+    int32_t m, dp;
+    int64_t poff;                  // offset of the partition in part_pool, -1 = uniform
+    int64_t spare;
+};
+
 struct Workspace {
     // layer-event prefix tables, entry [row*(L+1) + l] = sum over layers < l
     int64_t *pfc, *pbc, *pg;       // row = variant
     int64_t *pfa, *pba;            // row = variant*kMaxPP + (pp-1): in-stage communication incl. all-to-all
-    int32_t *npp;                  // [C] stages owned (0 unless status OK)
-    int32_t *key;                  // [C] ordering bin, -1 = not simulated
-    int64_t *block_sums;           // [scan blocks]
+    int64_t *p2p;                  // [(variant*L + l)*2 + link class]: p2p event of the activation after layer l
+    int32_t *key;                  // [C] ordering bin | variant << 24, -1 = not simulated
     int32_t *bin_count;            // [kBins]
     int32_t *bin_start;            // [kBins+1]
     int32_t *bin_fill;             // [kBins]
     int64_t *hdr;                  // [H_WORDS]
-    // candidates in visiting order
-    int32_t *s_cand, *s_meta, *s_m, *s_dp;   // meta = pp | schedule << 8 | variant << 16 ; pp == 0: skip
-    int64_t *s_off;
+    Desc *desc;                    // [C] candidates in visiting order
 };
-
-constexpr int kScanBlock = 256;
-constexpr int kScanItems = 8;
-constexpr int kScanChunk = kScanBlock * kScanItems;
 
 inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
@@ -54,18 +56,13 @@ inline size_t carve(Workspace& w, void* base, int32_t L, int32_t V, int64_t C) {
     w.pg = (int64_t*)take(row * V);
     w.pfa = (int64_t*)take(row * V * kMaxPP);
     w.pba = (int64_t*)take(row * V * kMaxPP);
-    w.npp = (int32_t*)take(Cc * 4);
+    w.p2p = (int64_t*)take((size_t)V * L * 2 * sizeof(int64_t));
     w.key = (int32_t*)take(Cc * 4);
-    w.block_sums = (int64_t*)take(((Cc + kScanChunk - 1) / kScanChunk + 1) * 8);
     w.bin_count = (int32_t*)take((size_t)kBins * 4);
     w.bin_start = (int32_t*)take((size_t)(kBins + 1) * 4);
     w.bin_fill = (int32_t*)take((size_t)kBins * 4);
     w.hdr = (int64_t*)take(H_WORDS * 8);
-    w.s_cand = (int32_t*)take(Cc * 4);
-    w.s_meta = (int32_t*)take(Cc * 4);
-    w.s_m = (int32_t*)take(Cc * 4);
-    w.s_dp = (int32_t*)take(Cc * 4);
-    w.s_off = (int64_t*)take(Cc * 8);
+    w.desc = (Desc*)take(Cc * sizeof(Desc));
     return off;
 }
 

@@ -6,7 +6,6 @@ import numpy as np
 import torch
 
 import paper_2306_08423_amd as ds
-from workloads import total_stages
 
 _ctx = None
 
@@ -22,10 +21,10 @@ def run_hip(w, stage_cap=None, util=True, search=None):
     """search: None or (objective, weight ndarray or None)."""
     c = ctx()
     dw = ds.upload(w, c.device)
-    cap = total_stages(w) if stage_cap is None else stage_cap
+    cap = ds.stage_entries(w.cand["pp"]) if stage_cap is None else stage_cap
     ev = ds.alloc_events(c, dw.L, dw.V, dw.C, cap)
     # poison the outputs so that untouched entries show up
-    ev.status.fill_(-7); ev.stage_off.fill_(-7); ev.num_events.fill_(-7)
+    ev.status.fill_(-7); ev.stage_pos.fill_(-7); ev.num_events.fill_(-7)
     ev.stage_tab.fill_(-7); ev.stage_layers.fill_(-7)
     ds.distsim_build_events(c, dw, ev)
     out = ds.alloc_outputs(c, ev, util=util)
@@ -43,21 +42,25 @@ def run_hip(w, stage_cap=None, util=True, search=None):
         res["best"] = tuple(int(x) for x in best.cpu().numpy())
     torch.cuda.synchronize()
     C = dw.C
-    soff = ev.stage_off.cpu().numpy()
-    n = int(soff[C])
     res.update({
         "status": ev.status.cpu().numpy()[:C],
         "num_events": ev.num_events.cpu().numpy()[:C],
-        "stage_off": soff,
-        "stage_tab": ev.stage_tab.cpu().numpy()[:, :min(n, cap)],
-        "stage_layers": ev.stage_layers.cpu().numpy()[:min(n, cap)],
+        "stage_pos": ev.stage_pos.cpu().numpy()[:C],
+        "stage_tab": ev.stage_tab.cpu().numpy()[:, :cap],
+        "stage_layers": ev.stage_layers.cpu().numpy()[:cap],
         "batch_ns": out.batch_ns.cpu().numpy()[:C],
-        "comp_busy_ns": out.comp_busy_ns.cpu().numpy()[:min(n, cap)],
-        "comm_busy_ns": out.comm_busy_ns.cpu().numpy()[:min(n, cap)],
+        "comp_busy_ns": out.comp_busy_ns.cpu().numpy()[:cap],
+        "comm_busy_ns": out.comm_busy_ns.cpu().numpy()[:cap],
+        "pp": w.cand["pp"].astype(np.int64),
     })
     if util:
-        res["util"] = out.util.cpu().numpy()[:min(n, cap)]
+        res["util"] = out.util.cpu().numpy()[:cap]
     return res
+
+
+def rows_of(hip, sel):
+    """Per-stage entries of the OK candidates among sel, in sel order."""
+    return ds.stage_rows(hip["status"][sel], hip["stage_pos"][sel], hip["pp"][sel])
 
 
 def assert_same(hip, ora, idx=None, what=""):
@@ -68,15 +71,12 @@ def assert_same(hip, ora, idx=None, what=""):
     assert np.array_equal(hip["status"][sel], ora["status"]), what + " status"
     assert np.array_equal(hip["batch_ns"][sel], ora["batch_ns"]), what + " batch_ns"
     assert np.array_equal(hip["num_events"][sel], ora["num_events"]), what + " num_events"
-    ho, oo = hip["stage_off"], ora["stage_off"]
-    cnt_h = (ho[1:] - ho[:-1])[sel]
-    cnt_o = oo[1:] - oo[:-1]
-    assert np.array_equal(cnt_h, cnt_o), what + " stage counts"
-    if idx is None:
-        assert np.array_equal(ho, oo), what + " stage_off"
-    # gather the ragged rows of the selected candidates
-    starts = ho[:-1][sel]
-    rows = np.repeat(starts, cnt_o) + (np.arange(int(cnt_o.sum())) - np.repeat(oo[:-1], cnt_o))
+    rows, cnt_h = rows_of(hip, sel)
+    oo = ora["stage_off"]
+    assert np.array_equal(cnt_h, oo[1:] - oo[:-1]), what + " stage counts"
+    if len(rows):
+        assert rows.min() >= 0 and rows.max() < len(hip["comp_busy_ns"]), what + " stage_pos range"
+        assert len(np.unique(rows)) == len(rows), what + " overlapping stage blocks"
     for key in ("comp_busy_ns", "comm_busy_ns"):
         assert np.array_equal(hip[key][rows], ora[key]), what + " " + key
     if "util" in hip:
