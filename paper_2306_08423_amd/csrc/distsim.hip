@@ -163,7 +163,8 @@ int distsim_build_events(distsim_ctx* ctx, const distsim_costs* costs, const dis
     }
     if (C > 0) {
         Timer t(ctx, st, DISTSIM_K_DECODE);
-        hipLaunchKernelGGL(k_decode, dim3(cblocks), dim3(256), 0, st, co, cl, ca, C, ws, ev);
+        hipLaunchKernelGGL(k_decode, dim3((int)((C + kDecodeChunk - 1) / kDecodeChunk)), dim3(kDecodeBlock), 0, st,
+                           co, cl, ca, C, ws, ev);
     }
     {
         Timer t(ctx, st, DISTSIM_K_BINS);

@@ -106,42 +106,69 @@ __global__ __launch_bounds__(64) void k_layer_tables(CostsDev co, ClusterDev cl,
 
 __global__ void k_clear_bins(Workspace ws) {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < kBins) { ws.bin_count[i] = 0; ws.bin_fill[i] = 0; }
+    if (i < kBins) ws.bin_count[i] = 0;
 }
 
 // ---------------------------------------------------------------------------------------
-// Candidate decoding: one thread per candidate.  Checks what can be checked in O(1) -- sizes,
-// device count, table variant, schedule, partition offset -- and files the candidate into its
-// ordering bin.  The partition itself and the 2^53 range guard are checked per stage later.
-__global__ __launch_bounds__(256) void k_decode(CostsDev co, ClusterDev cl, CandDev ca, int64_t C,
-                                                Workspace ws, EventsDev ev) {
-    const int64_t c = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (c >= C) return;
-    const int32_t dp = ca.dp[c], tp = ca.tp[c], pp = ca.pp[c], m = ca.m[c];
-    const int sched = ca.schedule[c];
-    const int64_t poff = ca.part_off[c];
-    bool ok = dp >= 1 && tp >= 1 && pp >= 1 && m >= 1 && m <= kMaxM && sched <= 1 && pp <= co.L && pp <= kMaxPP;
-    ok = ok && (int64_t)dp * tp * pp == (int64_t)cl.num_devices;
-    ok = ok && (poff == -1 || (poff >= 0 && ca.part_pool != nullptr && poff + pp + 1 <= ca.part_pool_len));
-    int v = -1;
-    if (ok) {
-        for (int i = co.V - 1; i >= 0; i--) if (co.variant_tp[i] == tp) v = i;
-        ok = v >= 0;
+// Candidate decoding.  Checks what can be checked in O(1) -- sizes, device count, table variant,
+// schedule, partition offset -- and files the candidate into its ordering bin; the partition
+// itself and the 2^53 range guard are checked per stage later.
+// A workgroup takes kDecodeChunk consecutive candidates and counts them in a histogram in LDS;
+// only the non-empty bins go to the global counters (one atomic each), which hands the
+// workgroup its base rank in every bin.  rank[c] is the candidate's position inside its bin.
+constexpr int kDecodeBlock = 1024;
+constexpr int kDecodePer = 16;
+constexpr int kDecodeChunk = kDecodeBlock * kDecodePer;
+
+__global__ __launch_bounds__(kDecodeBlock) void k_decode(CostsDev co, ClusterDev cl, CandDev ca, int64_t C,
+                                                         Workspace ws, EventsDev ev) {
+    __shared__ int32_t hist[kBins];
+    for (int b = threadIdx.x; b < kBins; b += kDecodeBlock) hist[b] = 0;
+    __syncthreads();
+    const int64_t base = (int64_t)blockIdx.x * kDecodeChunk + threadIdx.x;
+    int key[kDecodePer], rank[kDecodePer];
+#pragma unroll
+    for (int j = 0; j < kDecodePer; j++) {
+        const int64_t c = base + (int64_t)j * kDecodeBlock;
+        key[j] = -1; rank[j] = 0;
+        if (c >= C) continue;
+        const int32_t dp = ca.dp[c], tp = ca.tp[c], pp = ca.pp[c], m = ca.m[c];
+        const int sched = ca.schedule[c];
+        const int64_t poff = ca.part_off[c];
+        bool ok = dp >= 1 && tp >= 1 && pp >= 1 && m >= 1 && m <= kMaxM && sched <= 1 && pp <= co.L && pp <= kMaxPP;
+        ok = ok && (int64_t)dp * tp * pp == (int64_t)cl.num_devices;
+        ok = ok && (poff == -1 || (poff >= 0 && ca.part_pool != nullptr && poff + pp + 1 <= ca.part_pool_len));
+        int v = -1;
+        if (ok) {
+            for (int i = co.V - 1; i >= 0; i--) if (co.variant_tp[i] == tp) v = i;
+            ok = v >= 0;
+        }
+        if (ok) {
+            int k = 0;                               // class 0 = 64 lanes ... class 6 = 1 lane
+            while (k < 6 && (32 >> k) >= pp) k++;
+            const int mb = (m < kMBins ? m : kMBins) - 1;
+            const int bin = k * kBinsPerClass + sched * kMBins + (kMBins - 1 - mb);
+            rank[j] = atomicAdd(&hist[bin], 1);
+            key[j] = bin | (v << 24);
+        } else {
+            ev.num_events[c] = 0;
+            ev.stage_pos[c] = -1;
+        }
+        ev.status[c] = ok ? 0 : 1;
     }
-    int key = -1;
-    if (ok) {
-        int k = 0;                                   // class 0 = 64 lanes ... class 6 = 1 lane
-        while (k < 6 && (32 >> k) >= pp) k++;
-        const int mb = (m < kMBins ? m : kMBins) - 1;
-        key = k * kBinsPerClass + sched * kMBins + (kMBins - 1 - mb);
-        atomicAdd(&ws.bin_count[key], 1);
-        key |= v << 24;
-    } else {
-        ev.num_events[c] = 0;
-        ev.stage_pos[c] = -1;
+    __syncthreads();
+    for (int b = threadIdx.x; b < kBins; b += kDecodeBlock) {
+        const int n = hist[b];
+        if (n > 0) hist[b] = atomicAdd(&ws.bin_count[b], n);
     }
-    ev.status[c] = ok ? 0 : 1;
-    ws.key[c] = key;
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < kDecodePer; j++) {
+        const int64_t c = base + (int64_t)j * kDecodeBlock;
+        if (c >= C) continue;
+        ws.key[c] = key[j];
+        if (key[j] >= 0) ws.rank[c] = hist[key[j] & 0xffffff] + rank[j];
+    }
 }
 
 // ---------------------------------------------------------------------------------------
@@ -193,7 +220,7 @@ __global__ __launch_bounds__(256) void k_scatter(CandDev ca, int64_t C, Workspac
     if (kv < 0) return;
     const int key = kv & 0xffffff, v = kv >> 24;
     const int k = key / kBinsPerClass;
-    const int64_t pos = ws.bin_start[key] + atomicAdd(&ws.bin_fill[key], 1);
+    const int64_t pos = ws.bin_start[key] + ws.rank[c];
     const int64_t rel = pos - ws.hdr[H_CLASS_START + k];
     const int64_t item = ws.hdr[H_ITEM_START + k] + (rel >> k);
     const int64_t slot = item * kWave + ((rel & ((1 << k) - 1)) << (6 - k));

@@ -37,7 +37,7 @@ struct Workspace {
     int32_t *key;                  // [C] ordering bin | variant << 24, -1 = not simulated
     int32_t *bin_count;            // [kBins]
     int32_t *bin_start;            // [kBins+1]
-    int32_t *bin_fill;             // [kBins]
+    int32_t *rank;                 // [C] position of the candidate inside its bin
     int64_t *hdr;                  // [H_WORDS]
     Desc *desc;                    // [C] candidates in visiting order
 };
@@ -60,7 +60,7 @@ inline size_t carve(Workspace& w, void* base, int32_t L, int32_t V, int64_t C) {
     w.key = (int32_t*)take(Cc * 4);
     w.bin_count = (int32_t*)take((size_t)kBins * 4);
     w.bin_start = (int32_t*)take((size_t)(kBins + 1) * 4);
-    w.bin_fill = (int32_t*)take((size_t)kBins * 4);
+    w.rank = (int32_t*)take(Cc * 4);
     w.hdr = (int64_t*)take(H_WORDS * 8);
     w.desc = (Desc*)take(Cc * sizeof(Desc));
     return off;
