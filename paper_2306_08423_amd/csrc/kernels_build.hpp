@@ -232,7 +232,7 @@ __global__ __launch_bounds__(256) void k_scatter(CandDev ca, int64_t C, Workspac
     d.m = ca.m[c];
     d.dp = ca.dp[c];
     d.poff = ca.part_off[c];
-    d.spare = 0;
+    d.spare = ca.tp[c];
     ws.desc[pos] = d;
     ev.stage_pos[c] = room ? slot : -1;
     if (!room) { ev.status[c] = 3; ev.num_events[c] = 0; }
@@ -244,34 +244,66 @@ __global__ __launch_bounds__(256) void k_scatter(CandDev ca, int64_t C, Workspac
 // axis (segmented sums), the p2p events of its two boundaries and its gradient all-reduce are
 // evaluated, and the row is written to the stage table (64 consecutive entries per wave and
 // column).  The partition check and the 2^53 guard are group reductions over the stages.
+// The descriptor of the wave's next item and that item's partition bytes are requested one
+// iteration ahead, so that an item's own chain of dependent loads is only tables -> stores.
+struct StageWork {
+    int sh, s;
+    int64_t pos;
+    Desc d;
+    int lo, hi;
+};
+
+__device__ __forceinline__ void stage_fetch_desc(const Workspace& ws, const int64_t* hdr, int64_t w, int lane,
+                                                 StageWork& x) {
+    const Item it = decode_item(hdr, w);
+    x.sh = it.sh;
+    x.s = lane & ((1 << it.sh) - 1);
+    x.pos = it.pos0 + (lane >> it.sh);
+    x.d = Desc{};
+    if (x.pos < it.class_end) x.d = ws.desc[x.pos];
+}
+
+__device__ __forceinline__ void stage_fetch_bounds(const CandDev& ca, int L, StageWork& x) {
+    const int pp = x.d.meta & 0xff;
+    x.lo = 0; x.hi = 0;
+    if (x.s < pp) {
+        if (x.d.poff >= 0) { x.lo = ca.part_pool[x.d.poff + x.s]; x.hi = ca.part_pool[x.d.poff + x.s + 1]; }
+        else { x.lo = (int)(((int64_t)x.s * L) / pp); x.hi = (int)(((int64_t)(x.s + 1) * L) / pp); }
+    }
+}
+
 __global__ __launch_bounds__(256) void k_stage_events(CostsDev co, ClusterDev cl, CandDev ca, Workspace ws,
                                                       EventsDev ev) {
     const int lane = lane_id();
     const int64_t wave0 = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / kWave;
     const int64_t nwaves = ((int64_t)gridDim.x * blockDim.x) / kWave;
-    int64_t W = ws.hdr[H_NUM_ITEMS];
+    __shared__ int64_t hdr[H_WORDS];
+    if (threadIdx.x < H_WORDS) hdr[threadIdx.x] = ws.hdr[threadIdx.x];
+    __syncthreads();
+    int64_t W = hdr[H_NUM_ITEMS];
     if (W * kWave > ev.stage_cap) W = ev.stage_cap / kWave;       // items beyond the capacity own nothing
     const int L = co.L;
     const int64_t cap = ev.stage_cap;
+    StageWork nx{};
+    if (wave0 < W) { stage_fetch_desc(ws, hdr, wave0, lane, nx); stage_fetch_bounds(ca, L, nx); }
     for (int64_t w = wave0; w < W; w += nwaves) {
-        const Item it = decode_item(ws.hdr, w);
-        const int width = 1 << it.sh;
-        const int s = lane & (width - 1);
-        const int64_t pos = it.pos0 + (lane >> it.sh);
-        Desc d{};
-        if (pos < it.class_end) d = ws.desc[pos];
+        const StageWork cur = nx;
+        const bool more = w + nwaves < W;
+        if (more) stage_fetch_desc(ws, hdr, w + nwaves, lane, nx);
+        const int width = 1 << cur.sh;
+        const int s = cur.s;
+        const int64_t pos = cur.pos;
+        const Desc d = cur.d;
         const int pp = d.meta & 0xff, v = d.meta >> 16, m = d.m, dp = d.meta ? d.dp : 1;
         const bool act = s < pp;
         int64_t FC = 0, FA = 0, BC = 0, BA = 0, PF = 0, PB = 0, G = 0, AR = 0, nar = 0;
-        int lo = 0, hi = 0;
+        const int lo = cur.lo, hi = cur.hi;
         int bad = 0;
         // node index of this stage's first rank (ranks ordered tp fastest, then dp, then pp)
         int64_t node = 0;
         if (act) {
-            if (d.poff >= 0) { lo = ca.part_pool[d.poff + s]; hi = ca.part_pool[d.poff + s + 1]; }
-            else { lo = (int)(((int64_t)s * L) / pp); hi = (int)(((int64_t)(s + 1) * L) / pp); }
             bad = (hi <= lo) || (hi > L) || (s == 0 && lo != 0) || (s == pp - 1 && hi != L);
-            const int64_t tpdp = (int64_t)co.variant_tp[v] * dp;
+            const int64_t tpdp = d.spare * dp;       // spare holds the tensor-parallel size
             node = (int64_t)udiv64((uint64_t)s * (uint64_t)tpdp, (uint64_t)cl.gpus_per_node);
         }
         bad = (int)group_sum(bad, width);
@@ -302,12 +334,14 @@ __global__ __launch_bounds__(256) void k_stage_events(CostsDev co, ClusterDev cl
                 }
             }
         }
+        if (more) stage_fetch_bounds(ca, L, nx);
         // every timestamp of the pipeline phase is bounded by m * (all task and p2p durations)
         const uint64_t t1 = (uint64_t)group_sum(FC + FA + BC + BA + PF + PB, width);
         const bool range = __umul64hi(t1, (uint64_t)m) != 0 || t1 * (uint64_t)m >= (1ull << 53);
         nar = group_sum(nar, width);
         const bool drop = bad || range;
-        if (drop) { FC = FA = BC = BA = PF = PB = G = AR = 0; lo = hi = 0; }
+        const int lo_w = drop ? 0 : lo, hi_w = drop ? 0 : hi;
+        if (drop) { FC = FA = BC = BA = PF = PB = G = AR = 0; }
         const int64_t i = w * kWave + lane;
         ev.stage_tab[0 * cap + i] = FC;
         ev.stage_tab[1 * cap + i] = FA;
@@ -317,7 +351,7 @@ __global__ __launch_bounds__(256) void k_stage_events(CostsDev co, ClusterDev cl
         ev.stage_tab[5 * cap + i] = PB;
         ev.stage_tab[6 * cap + i] = G;
         ev.stage_tab[7 * cap + i] = AR;
-        ev.stage_layers[i] = lo | (hi << 8);
+        ev.stage_layers[i] = lo_w | (hi_w << 8);
         if (act && s == 0) {
             const int64_t c = d.cand;
             if (drop) {
