@@ -43,6 +43,39 @@ __device__ __forceinline__ uint32_t level_bits(int a, int b) {
     return any ? r : 0u;
 }
 
+__device__ __forceinline__ uint32_t shl32(uint32_t x, int n) { return n >= 32 ? 0u : x << n; }
+
+// Bitwise OR over the 64 lanes, returned as a wave-uniform value.
+__device__ __forceinline__ uint32_t wave_or_u32(uint32_t x) {
+    int v = (int)x;
+    v |= __builtin_amdgcn_update_dpp(0, v, 0xB1, 0xf, 0xf, true);     // quad_perm [1,0,3,2]
+    v |= __builtin_amdgcn_update_dpp(0, v, 0x4E, 0xf, 0xf, true);     // quad_perm [2,3,0,1]
+    v |= __builtin_amdgcn_update_dpp(0, v, 0x141, 0xf, 0xf, true);    // row_half_mirror
+    v |= __builtin_amdgcn_update_dpp(0, v, 0x140, 0xf, 0xf, true);    // row_mirror
+    return (uint32_t)(__builtin_amdgcn_readlane(v, 0) | __builtin_amdgcn_readlane(v, 16) |
+                      __builtin_amdgcn_readlane(v, 32) | __builtin_amdgcn_readlane(v, 48));
+}
+
+// Operand of a level on which lanes of one parity run forwards and the others backwards:
+// the previous lane's value for the forward lanes, the next lane's for the backward lanes,
+// fetched with one ds_bpermute per 32-bit half (byte address = 4 * source lane).
+#ifndef SIM_PAR_MODE
+#define SIM_PAR_MODE 2
+#endif
+#if SIM_PAR_MODE == 2
+__device__ __forceinline__ double from_lanes(double x, int byte_addr) {
+    const int lo = __builtin_amdgcn_ds_bpermute(byte_addr, __double2loint(x));
+    const int hi = __builtin_amdgcn_ds_bpermute(byte_addr, __double2hiint(x));
+    return __hiloint2double(hi, lo);
+}
+#else
+// byte_addr < own address: take the previous lane, else the next lane
+__device__ __forceinline__ double from_lanes(double x, int byte_addr) {
+    const double a = from_prev_lane(x), b = from_next_lane(x);
+    return byte_addr < (int)(threadIdx.x & 63) * 4 ? a : b;
+}
+#endif
+
 // One level for the lanes whose pattern bit is set: own = max(own, nb + lat) + dur.
 // Requires EXEC == all ones on entry (wave-uniform control flow, full wavefronts) and leaves
 // it so.  The trailing s_nop keeps two wait states between the write of `own` and the DPP
@@ -77,7 +110,10 @@ __device__ __forceinline__ uint32_t level_bits(int a, int b) {
           [kf] "=&s"(kmask), [kb] "=&s"(kmask2)                               \
         : [cl] "v"(pfL), [cr] "v"(pbR), [df] "v"(Fd), [db] "v"(Bd))
 
-__global__ __launch_bounds__(256) void k_simulate(CostsDev co, ClusterDev cl, Workspace ws, EventsDev ev,
+#ifndef SIM_WAVES_PER_EU
+#define SIM_WAVES_PER_EU 8
+#endif
+__global__ __launch_bounds__(256, SIM_WAVES_PER_EU) void k_simulate(CostsDev co, ClusterDev cl, Workspace ws, EventsDev ev,
                                                   SimOut out) {
     const int lane = lane_id();
     const int64_t wave0 = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / kWave;
@@ -101,15 +137,20 @@ __global__ __launch_bounds__(256) void k_simulate(CostsDev co, ClusterDev cl, Wo
         const int m = act ? dd.z : 0;
         const int64_t i = w * kWave + lane;
         // rows of lanes outside a candidate are zero-filled by event generation
-        const int64_t FC = ev.stage_tab[0 * cap + i], FA = ev.stage_tab[1 * cap + i];
-        const int64_t BC = ev.stage_tab[2 * cap + i], BA = ev.stage_tab[3 * cap + i];
-        const int64_t PF = ev.stage_tab[4 * cap + i], PB = ev.stage_tab[5 * cap + i];
-        const int64_t AR = ev.stage_tab[7 * cap + i];
-        // p2p latency on the incoming edges (the neighbours' outgoing events); -inf = no edge
-        double pfL = from_prev_lane((double)PF), pbR = from_next_lane((double)PB);
+        double Fd, Bd, pfL, pbR;
+        int64_t comp1, comm1, AR;            // per-micro-batch computation / communication, trailing all-reduce
+        {
+            const int64_t FC = ev.stage_tab[0 * cap + i], FA = ev.stage_tab[1 * cap + i];
+            const int64_t BC = ev.stage_tab[2 * cap + i], BA = ev.stage_tab[3 * cap + i];
+            const int64_t PF = ev.stage_tab[4 * cap + i], PB = ev.stage_tab[5 * cap + i];
+            AR = ev.stage_tab[7 * cap + i];
+            Fd = (double)(FC + FA); Bd = (double)(BC + BA);
+            comp1 = FC + BC; comm1 = FA + BA + PF + PB;
+            // p2p latency on the incoming edges (the neighbours' outgoing events); -inf = no edge
+            pfL = from_prev_lane((double)PF); pbR = from_next_lane((double)PB);
+        }
         if (!(act && s > 0)) pfL = ninf;
         if (!(act && s + 1 < pp)) pbR = ninf;
-        const double Fd = (double)(FC + FA), Bd = (double)(BC + BA);
 
         // level windows of this lane, expressed on x = level - s:
         //   forward  x in [0, f1hi]  and  even x in [f2lo, f2hi]
@@ -126,6 +167,17 @@ __global__ __launch_bounds__(256) void k_simulate(CostsDev co, ClusterDev cl, Wo
         }
         const int nlev = __builtin_amdgcn_readfirstlane(wave_max_i32(act ? 2 * (m + pp - 1) : 0));
 
+        // 1F1B past its warm-up runs forwards on even x and backwards on odd x.  When every
+        // candidate of the wavefront is 1F1B with one pp, a level that has both kinds therefore
+        // splits the lanes by parity, and one merged operand (previous lane for the forward
+        // lanes, next lane for the backward lanes) feeds a single task step.
+        const int ppu = __builtin_amdgcn_readfirstlane(wave_max_i32(pp));
+        const bool par_ok = SIM_PAR_MODE != 0 && width >= 2 && __builtin_amdgcn_ballot_w64(act && (sched == 0 || pp != ppu)) == 0;
+        const bool even_s = (s & 1) == 0;
+        const double latE = even_s ? pfL : pbR, durE = even_s ? Fd : Bd;     // roles on even levels
+        const double latO = even_s ? pbR : pfL, durO = even_s ? Bd : Fd;     // roles on odd levels
+        const int adrE = (even_s ? lane - 1 : lane + 1) * 4, adrO = (even_s ? lane + 1 : lane - 1) * 4;
+
         double own = 0.0;
         for (int l0 = 0; l0 < nlev; l0 += 32) {
             const int x0 = l0 - s;
@@ -134,26 +186,66 @@ __global__ __launch_bounds__(256) void k_simulate(CostsDev co, ClusterDev cl, Wo
             uint32_t PBb = level_bits(blo - x0, bhi - x0);
             if (sched != 0) PBb &= ((blo - x0) & 1) ? 0x55555555u : 0xaaaaaaaau;   // x - blo even
             if (!act) { PFb = 0; PBb = 0; }
-            const bool anyF = __builtin_amdgcn_ballot_w64(PFb != 0) != 0;
-            const bool anyB = __builtin_amdgcn_ballot_w64(PBb != 0) != 0;
-            const int n = nlev - l0 < 32 ? nlev - l0 : 32;
+            // chunk-relative level ranges in which any lane has a forward / a backward task
+            const uint32_t orF = wave_or_u32(PFb), orB = wave_or_u32(PBb);
+            if ((orF | orB) == 0) continue;
+            const int firstF = orF ? __builtin_clz(orF) : 64, lastF = orF ? 31 - __builtin_ctz(orF) : -1;
+            const int firstB = orB ? __builtin_clz(orB) : 64, lastB = orB ? 31 - __builtin_ctz(orB) : -1;
+            const int endk = (lastF > lastB ? lastF : lastB) + 1;
+            int k = firstF < firstB ? firstF : firstB;
+            PFb = shl32(PFb, k); PBb = shl32(PBb, k);            // skip the idle levels in front
             uint64_t kmask, kmask2;
-            if (anyF && anyB) {
-                for (int k = 0; k < n; k++) {
-                    double fromL = from_prev_lane(own);
-                    double fromR = from_next_lane(own);
-                    DISTSIM_STEP_BOTH();
+            while (k < endk) {
+                const bool inF = k >= firstF && k <= lastF, inB = k >= firstB && k <= lastB;
+                int e = endk;                                     // next level at which the mix changes
+                if (firstF > k && firstF < e) e = firstF;
+                if (firstB > k && firstB < e) e = firstB;
+                if (lastF + 1 > k && lastF + 1 < e) e = lastF + 1;
+                if (lastB + 1 > k && lastB + 1 < e) e = lastB + 1;
+                const int len = e - k;
+                if (inF && inB) {
+                    if (par_ok) {
+                        uint32_t Pc = PFb | PBb;
+                        int j = 0;
+                        if (((l0 + k) & 1) && j < len) {
+                            double nb = from_lanes(own, adrO);
+                            DISTSIM_STEP_ONE(Pc, nb, latO, durO);
+                            j++;
+                        }
+                        for (; j + 1 < len; j += 2) {
+                            double nb = from_lanes(own, adrE);
+                            DISTSIM_STEP_ONE(Pc, nb, latE, durE);
+                            double nb2 = from_lanes(own, adrO);
+                            DISTSIM_STEP_ONE(Pc, nb2, latO, durO);
+                        }
+                        if (j < len) {
+                            double nb = from_lanes(own, adrE);
+                            DISTSIM_STEP_ONE(Pc, nb, latE, durE);
+                        }
+                        PFb = shl32(PFb, len); PBb = shl32(PBb, len);
+                    } else {
+                        for (int j = 0; j < len; j++) {
+                            double fromL = from_prev_lane(own);
+                            double fromR = from_next_lane(own);
+                            DISTSIM_STEP_BOTH();
+                        }
+                    }
+                } else if (inF) {
+                    for (int j = 0; j < len; j++) {
+                        double fromL = from_prev_lane(own);
+                        DISTSIM_STEP_ONE(PFb, fromL, pfL, Fd);
+                    }
+                    PBb = shl32(PBb, len);
+                } else if (inB) {
+                    for (int j = 0; j < len; j++) {
+                        double fromR = from_next_lane(own);
+                        DISTSIM_STEP_ONE(PBb, fromR, pbR, Bd);
+                    }
+                    PFb = shl32(PFb, len);
+                } else {
+                    PFb = shl32(PFb, len); PBb = shl32(PBb, len);
                 }
-            } else if (anyF) {
-                for (int k = 0; k < n; k++) {
-                    double fromL = from_prev_lane(own);
-                    DISTSIM_STEP_ONE(PFb, fromL, pfL, Fd);
-                }
-            } else if (anyB) {
-                for (int k = 0; k < n; k++) {
-                    double fromR = from_next_lane(own);
-                    DISTSIM_STEP_ONE(PBb, fromR, pbR, Bd);
-                }
+                k = e;
             }
             (void)kmask; (void)kmask2;
         }
@@ -167,7 +259,7 @@ __global__ __launch_bounds__(256) void k_simulate(CostsDev co, ClusterDev cl, Wo
                 const int lay = ev.stage_layers[i];
                 const int lo = lay & 0xff, hi = lay >> 8;
                 const size_t vr = (size_t)v * (L + 1), rr = (size_t)(v * kMaxPP + pp - 1) * (L + 1);
-                const int64_t startB = endB - (BC + BA);
+                const int64_t startB = endB - (int64_t)Bd;
                 const int64_t tot_hi = ws.pbc[vr + hi] + ws.pba[rr + hi];
                 const int64_t ar_cap = allreduce_ns(cl, dp, cl.bucket);
                 int64_t acc = 0, t = 0;
@@ -191,8 +283,8 @@ __global__ __launch_bounds__(256) void k_simulate(CostsDev co, ClusterDev cl, Wo
         }
         const int64_t batch = group_max(act ? finish : 0, width);
         // lanes outside a candidate have m = 0 and zero rows: they store zeros
-        const int64_t comp = (int64_t)m * (FC + BC);
-        const int64_t comm = act ? (int64_t)m * (FA + BA + PF + PB) + ar_busy : 0;
+        const int64_t comp = (int64_t)m * comp1;
+        const int64_t comm = act ? (int64_t)m * comm1 + ar_busy : 0;
         out.comp_busy[i] = comp;
         out.comm_busy[i] = comm;
         if (out.util) out.util[i] = batch > 0 ? (double)comp / (double)batch : 0.0;
