@@ -57,6 +57,8 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="hetero64", help="hetero64 (default), gpt96, gpt48, gpt24")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--stage-table", dest="no_stage_table", action="store_false",
+                    help="also write the optional per-stage event table during event generation")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one 1 GiB device-to-device copy (known traffic, for scaling HBM counters)")
     args = ap.parse_args()
@@ -78,7 +80,7 @@ def main() -> int:
     ctx = ds.Context(0)
     dw = ds.upload(w, ctx.device)
     S = total_stages(w)
-    ev = ds.alloc_events(ctx, dw.L, dw.V, dw.C, ds.stage_entries(w.cand["pp"]))
+    ev = ds.alloc_events(ctx, dw.L, dw.V, dw.C, ds.stage_entries(w.cand["pp"]), table=not args.no_stage_table)
     out = ds.alloc_outputs(ctx, ev, util=True)
     best, scratch = ds.alloc_search(ctx, dw.C)
 
@@ -114,9 +116,9 @@ def main() -> int:
     tasks = int((2 * m * pp).sum())
     sim_ms, sim_n = kt["k_simulate"]
     sim_avg_s = sim_ms / max(sim_n, 1) / 1e3
-    # algorithmic HBM bytes of k_simulate per launch: descriptor in (16 B) and batch_ns out (8 B)
-    # per candidate; 7 stage-table columns in (56 B) and comp/comm/util out (24 B) per stage
-    sim_bytes = C * (16 + 8) + S * (7 * 8 + 24)
+    # algorithmic HBM bytes of k_simulate per launch: descriptor in (32 B), batch_ns and num_events
+    # out (16 B) per candidate; partition byte in (1 B) and comp/comm/util out (24 B) per stage
+    sim_bytes = C * (32 + 16) + S * (1 + 24)
     roofline = {
         "kernel": "k_simulate", "bound": "alu",
         "achieved": FLOPS_PER_TASK * tasks / sim_avg_s / 1e12, "peak": ALU_PEAK_TFLOPS, "unit": "TFLOP/s",

@@ -141,18 +141,28 @@ enum {
  *   bound >= 64 * sum over k of ceil(n_k 2^k / 64) with n_k = candidates whose rounded pp is 2^k;
  * candidates that do not fit get DISTSIM_ST_NOROOM.  Entries not owned by any candidate are
  * written as zero.
+ *
+ * The stage table is an optional product: the events proper are the shared layer-event tables
+ * kept in the workspace (every candidate that generates an event reuses its time, Sec. 3.2),
+ * and distsim_simulate composes them per stage itself, with the same arithmetic.  With
+ * stage_tab == NULL nothing per-stage is written by distsim_build_events; status then only
+ * reflects the checks that need no per-stage work (everything but the partition and the 2^53
+ * guard) and num_events is not yet written -- distsim_simulate completes both.
  */
 typedef struct {
     int64_t  stage_cap;      /* entries available in every per-stage array                        */
     int32_t  L, V;           /* table shape; filled in by distsim_build_events                    */
     int32_t *status;         /* [C]                                                               */
     int64_t *stage_pos;      /* [C] first per-stage entry of the candidate, -1 if it has none     */
-    int64_t *stage_tab;      /* [DISTSIM_NCOLS][stage_cap]                                        */
-    int32_t *stage_layers;   /* [stage_cap] first layer | (one past last layer) << 8              */
+    int64_t *stage_tab;      /* [DISTSIM_NCOLS][stage_cap], or NULL: do not write the table       */
+    int32_t *stage_layers;   /* [stage_cap] first layer | (one past last layer) << 8; NULL iff
+                                stage_tab is NULL                                                 */
     int64_t *num_events;     /* [C] events on the pp distinct device timelines: 2 m pp stage-tasks
                                 + 2 m (pp-1) p2p + gradient all-reduce events; 0 if not OK       */
     void    *workspace;      /* distsim_workspace_bytes() bytes, 256-byte aligned; opaque         */
     size_t   workspace_bytes;
+    distsim_costs      costs;   /* copies of the inputs' pointers, filled in by distsim_build_events: */
+    distsim_candidates cand;    /* the arrays they point to must stay alive until distsim_simulate    */
 } distsim_events;
 
 /* A stage_cap that is always enough for C candidates. */
@@ -181,7 +191,10 @@ int distsim_build_events(distsim_ctx *ctx, const distsim_costs *costs, const dis
  * Outputs (device): batch_ns[C] = time of the last event (INT64_MAX unless status OK);
  * comp_busy_ns / comm_busy_ns [stage_cap] = sum of the durations of the computation /
  * communication events on each stage's device (index stage_pos[c] + s); util (may be NULL)
- * = comp_busy / batch as fp64; entries not owned by an OK candidate are written as zero.  `events` must come from distsim_build_events with the same
+ * = comp_busy / batch as fp64; entries not owned by an OK candidate are written as zero.
+ * Also writes num_events[c], and the status of candidates whose partition is invalid or
+ * whose times would leave the 2^53 range (final values; distsim_build_events has already
+ * written the same ones if it was asked for the stage table).  `events` must come from distsim_build_events with the same
  * cluster and C.  Errors: EINVAL, EHIP.
  */
 int distsim_simulate(distsim_ctx *ctx, const distsim_cluster *cluster, const distsim_events *events,

@@ -52,7 +52,8 @@ class _Events(C.Structure):
     _fields_ = [("stage_cap", C.c_int64), ("L", C.c_int32), ("V", C.c_int32),
                 ("status", C.c_void_p), ("stage_pos", C.c_void_p), ("stage_tab", C.c_void_p),
                 ("stage_layers", C.c_void_p), ("num_events", C.c_void_p),
-                ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t)]
+                ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t),
+                ("costs", _Costs), ("cand", _Cand)]
 
 
 _lib = None
@@ -196,8 +197,8 @@ class Events:
     stage_cap: int
     status: torch.Tensor
     stage_pos: torch.Tensor
-    stage_tab: torch.Tensor
-    stage_layers: torch.Tensor
+    stage_tab: Optional[torch.Tensor]
+    stage_layers: Optional[torch.Tensor]
     num_events: torch.Tensor
     workspace: torch.Tensor
     struct: _Events
@@ -227,7 +228,9 @@ def stage_rows(status, stage_pos, pp):
     return np.repeat(start, cnt) + (np.arange(int(cnt.sum())) - first), cnt
 
 
-def alloc_events(ctx: Context, L: int, V: int, Cn: int, stage_cap: Optional[int] = None) -> Events:
+def alloc_events(ctx: Context, L: int, V: int, Cn: int, stage_cap: Optional[int] = None,
+                 table: bool = True) -> Events:
+    """table=False: no stage table is written (distsim_simulate composes the stage events itself)."""
     dev = ctx.device
     if stage_cap is None:
         stage_cap = ctx.lib.distsim_stage_entries(Cn)
@@ -237,13 +240,13 @@ def alloc_events(ctx: Context, L: int, V: int, Cn: int, stage_cap: Optional[int]
     status = torch.empty(max(Cn, 1), dtype=torch.int32, device=dev)
     stage_pos = torch.empty(max(Cn, 1), dtype=torch.int64, device=dev)
     cap = max(int(stage_cap), 0)
-    stage_tab = torch.empty((NCOLS, max(cap, 1)), dtype=torch.int64, device=dev)
-    stage_layers = torch.empty(max(cap, 1), dtype=torch.int32, device=dev)
+    stage_tab = torch.empty((NCOLS, max(cap, 1)), dtype=torch.int64, device=dev) if table else None
+    stage_layers = torch.empty(max(cap, 1), dtype=torch.int32, device=dev) if table else None
     num_events = torch.empty(max(Cn, 1), dtype=torch.int64, device=dev)
     # torch's caching allocator hands out 512-byte aligned blocks
     workspace = torch.empty(nbytes, dtype=torch.uint8, device=dev)
     st = _Events(cap, 0, 0, _ptr(status), _ptr(stage_pos), _ptr(stage_tab), _ptr(stage_layers), _ptr(num_events),
-                 _ptr(workspace), nbytes)
+                 _ptr(workspace), nbytes, _Costs(), _Cand())
     return Events(Cn, cap, status, stage_pos, stage_tab, stage_layers, num_events, workspace, st)
 
 

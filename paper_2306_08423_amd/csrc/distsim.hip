@@ -137,7 +137,7 @@ int distsim_build_events(distsim_ctx* ctx, const distsim_costs* costs, const dis
         return fail(ctx, DISTSIM_EINVAL, "events: null workspace or negative stage_cap");
     if (C > 0 && (!cand->dp || !cand->tp || !cand->pp || !cand->m || !cand->schedule || !cand->part_off ||
                   !out->status || !out->num_events || !out->stage_pos ||
-                  (out->stage_cap > 0 && (!out->stage_tab || !out->stage_layers))))
+                  ((out->stage_tab == nullptr) != (out->stage_layers == nullptr))))
         return fail(ctx, DISTSIM_EINVAL, "null candidate or events array");
     if (((uintptr_t)out->workspace & 255) != 0) return fail(ctx, DISTSIM_EINVAL, "workspace must be 256-byte aligned");
     Workspace ws;
@@ -154,6 +154,8 @@ int distsim_build_events(distsim_ctx* ctx, const distsim_costs* costs, const dis
     EventsDev ev{out->stage_cap, out->status, out->stage_pos, out->stage_tab, out->stage_layers, out->num_events};
     out->L = costs->L;
     out->V = costs->V;
+    out->costs = *costs;
+    out->cand = *cand;
 
     const int cblocks = (int)((C + 255) / 256);
     {
@@ -175,8 +177,10 @@ int distsim_build_events(distsim_ctx* ctx, const distsim_costs* costs, const dis
             Timer t(ctx, st, DISTSIM_K_SCATTER);
             hipLaunchKernelGGL(k_scatter, dim3(cblocks), dim3(256), 0, st, ca, C, ws, ev);
         }
-        Timer t(ctx, st, DISTSIM_K_STAGE_EVENTS);
-        hipLaunchKernelGGL(k_stage_events, dim3(item_grid(ctx, C)), dim3(256), 0, st, co, cl, ca, ws, ev);
+        if (out->stage_tab && out->stage_cap > 0) {
+            Timer t(ctx, st, DISTSIM_K_STAGE_EVENTS);
+            hipLaunchKernelGGL(k_stage_events, dim3(item_grid(ctx, C)), dim3(256), 0, st, co, cl, ca, ws, ev);
+        }
     }
     HIP_TRY(hipGetLastError());
     return DISTSIM_OK;
@@ -190,8 +194,8 @@ int distsim_simulate(distsim_ctx* ctx, const distsim_cluster* cluster, const dis
     if (!cluster_ok(cluster)) return fail(ctx, DISTSIM_EINVAL, "cluster description out of range");
     if (C < 0 || C > 0x7fffffff) return fail(ctx, DISTSIM_ERANGE, "candidate count outside [0, 2^31)");
     if (C == 0) return DISTSIM_OK;
-    if (!batch_ns || !events->status || !events->workspace ||
-        (events->stage_cap > 0 && (!comp_busy_ns || !comm_busy_ns || !events->stage_tab || !events->stage_layers)))
+    if (!batch_ns || !events->status || !events->num_events || !events->workspace ||
+        (events->stage_cap > 0 && (!comp_busy_ns || !comm_busy_ns)))
         return fail(ctx, DISTSIM_EINVAL, "null output or events array");
     HIP_TRY(hipSetDevice(ctx->device));
     hipStream_t st = (hipStream_t)hip_stream;
@@ -200,8 +204,14 @@ int distsim_simulate(distsim_ctx* ctx, const distsim_cluster* cluster, const dis
     Workspace ws;
     if (events->workspace_bytes < carve(ws, events->workspace, events->L, events->V, C))
         return fail(ctx, DISTSIM_EINVAL, "workspace too small for C");
-    CostsDev co{};
-    co.L = events->L; co.V = events->V;
+    const distsim_costs* cs = &events->costs;
+    const distsim_candidates* cd = &events->cand;
+    if (!cs->variant_tp || !cs->act_bytes || cs->L != events->L || cs->V != events->V)
+        return fail(ctx, DISTSIM_EINVAL, "events were not produced by distsim_build_events");
+    CostsDev co{cs->L, cs->V, cs->variant_tp, cs->fwd_comp_ns, cs->bwd_comp_ns, cs->fwd_comm_ns, cs->bwd_comm_ns,
+                cs->act_bytes, cs->grad_bytes, cs->a2a_bytes};
+    CandDev ca{cd->dp, cd->tp, cd->pp, cd->m, cd->schedule, cd->part_off, cd->part_pool,
+               cd->part_pool ? cd->part_pool_len : 0};
     const ClusterDev cl = to_dev(*cluster);
     EventsDev ev{events->stage_cap, events->status, events->stage_pos, events->stage_tab, events->stage_layers,
                  events->num_events};
@@ -212,7 +222,7 @@ int distsim_simulate(distsim_ctx* ctx, const distsim_cluster* cluster, const dis
     }
     {
         Timer t(ctx, st, DISTSIM_K_SIMULATE);
-        hipLaunchKernelGGL(k_simulate, dim3(item_grid(ctx, C)), dim3(256), 0, st, co, cl, ws, ev, out);
+        hipLaunchKernelGGL(k_simulate, dim3(item_grid(ctx, C)), dim3(256), 0, st, co, cl, ca, ws, ev, out);
     }
     HIP_TRY(hipGetLastError());
     return DISTSIM_OK;

@@ -244,6 +244,64 @@ __global__ __launch_bounds__(256) void k_scatter(CandDev ca, int64_t C, Workspac
 // axis (segmented sums), the p2p events of its two boundaries and its gradient all-reduce are
 // evaluated, and the row is written to the stage table (64 consecutive entries per wave and
 // column).  The partition check and the 2^53 guard are group reductions over the stages.
+// Per-stage composed events of one lane = (candidate, stage s).
+struct StageRow {
+    int64_t FC, FA, BC, BA;     // forward / backward computation and in-stage communication
+    int64_t PF, PB;             // p2p events towards stage s+1 / s-1
+    int64_t G;                  // gradient bytes
+};
+
+// Reduces the layer events of the lane's stage with prefix differences over the layer axis
+// (segmented sums), looks up the p2p events of its two boundaries, checks the partition and
+// applies the 2^53 guard (both are reductions over the candidate's lanes).  Every lane of the
+// wavefront must call it.  Returns 0, or the status of a candidate that must be dropped
+// (1 = not a partition, 2 = range); rows of dropped candidates and of idle lanes are zero.
+__device__ __forceinline__ int stage_row(const ClusterDev& cl, const Workspace& ws, int L, int width, int s,
+                                         int pp, int v, int m, int dp, int tp, int lo, int hi, StageRow& r) {
+    const bool act = s < pp;
+    r = StageRow{0, 0, 0, 0, 0, 0, 0};
+    int bad = 0;
+    int64_t node = 0;           // node of the stage's first rank (ranks ordered tp fastest, then dp, then pp)
+    if (act) {
+        bad = (hi <= lo) || (hi > L) || (s == 0 && lo != 0) || (s == pp - 1 && hi != L);
+        node = (int64_t)udiv64((uint64_t)s * (uint64_t)((int64_t)tp * dp), (uint64_t)cl.gpus_per_node);
+    }
+    bad = (int)group_sum(bad, width);
+    const int64_t node_next = __shfl_down(node, 1, kWave), node_prev = __shfl_up(node, 1, kWave);
+    if (act && !bad) {
+        const size_t vr = (size_t)v * (L + 1), rr = (size_t)(v * kMaxPP + pp - 1) * (L + 1);
+        r.FC = ws.pfc[vr + hi] - ws.pfc[vr + lo];
+        r.BC = ws.pbc[vr + hi] - ws.pbc[vr + lo];
+        r.FA = ws.pfa[rr + hi] - ws.pfa[rr + lo];
+        r.BA = ws.pba[rr + hi] - ws.pba[rr + lo];
+        r.G = ws.pg[vr + hi] - ws.pg[vr + lo];
+        if (s + 1 < pp) r.PF = ws.p2p[((size_t)v * L + hi - 1) * 2 + (node != node_next ? 1 : 0)];
+        if (s > 0) r.PB = ws.p2p[((size_t)v * L + lo - 1) * 2 + (node != node_prev ? 1 : 0)];
+    }
+    // every timestamp of the pipeline phase is bounded by m * (all task and p2p durations)
+    const uint64_t t1 = (uint64_t)group_sum(r.FC + r.FA + r.BC + r.BA + r.PF + r.PB, width);
+    const bool range = __umul64hi(t1, (uint64_t)m) != 0 || t1 * (uint64_t)m >= (1ull << 53);
+    const int drop = bad ? 1 : (range ? 2 : 0);
+    if (drop) r = StageRow{0, 0, 0, 0, 0, 0, 0};
+    return drop;
+}
+
+// Number of gradient all-reduce events on the stage's device (data-parallel modelling).
+__device__ __forceinline__ int64_t count_allreduce_events(const ClusterDev& cl, const Workspace& ws, int L, int v,
+                                                          int dp, int lo, int hi, int64_t G) {
+    if (dp <= 1 || G <= 0) return 0;
+    if (cl.bucket <= 0) return 1;
+    const size_t vr = (size_t)v * (L + 1);
+    int64_t acc = 0, n = 0;
+    for (int l = hi - 1; l >= lo; l--) {
+        acc += ws.pg[vr + l + 1] - ws.pg[vr + l];
+        const int64_t k = (int64_t)udiv64((uint64_t)acc, (uint64_t)cl.bucket);
+        n += k;
+        acc -= k * cl.bucket;
+    }
+    return n + (acc > 0 ? 1 : 0);
+}
+
 // The descriptor of the wave's next item and that item's partition bytes are requested one
 // iteration ahead, so that an item's own chain of dependent loads is only tables -> stores.
 struct StageWork {
@@ -272,6 +330,8 @@ __device__ __forceinline__ void stage_fetch_bounds(const CandDev& ca, int L, Sta
     }
 }
 
+// Writes the per-stage composed events of every candidate to the stage table (64 consecutive
+// entries per wavefront and column).  Optional: distsim_simulate regenerates the rows itself.
 __global__ __launch_bounds__(256) void k_stage_events(CostsDev co, ClusterDev cl, CandDev ca, Workspace ws,
                                                       EventsDev ev) {
     const int lane = lane_id();
@@ -292,72 +352,31 @@ __global__ __launch_bounds__(256) void k_stage_events(CostsDev co, ClusterDev cl
         if (more) stage_fetch_desc(ws, hdr, w + nwaves, lane, nx);
         const int width = 1 << cur.sh;
         const int s = cur.s;
-        const int64_t pos = cur.pos;
         const Desc d = cur.d;
         const int pp = d.meta & 0xff, v = d.meta >> 16, m = d.m, dp = d.meta ? d.dp : 1;
         const bool act = s < pp;
-        int64_t FC = 0, FA = 0, BC = 0, BA = 0, PF = 0, PB = 0, G = 0, AR = 0, nar = 0;
-        const int lo = cur.lo, hi = cur.hi;
-        int bad = 0;
-        // node index of this stage's first rank (ranks ordered tp fastest, then dp, then pp)
-        int64_t node = 0;
-        if (act) {
-            bad = (hi <= lo) || (hi > L) || (s == 0 && lo != 0) || (s == pp - 1 && hi != L);
-            const int64_t tpdp = d.spare * dp;       // spare holds the tensor-parallel size
-            node = (int64_t)udiv64((uint64_t)s * (uint64_t)tpdp, (uint64_t)cl.gpus_per_node);
-        }
-        bad = (int)group_sum(bad, width);
-        const int64_t node_next = __shfl_down(node, 1, kWave), node_prev = __shfl_up(node, 1, kWave);
-        if (act && !bad) {
-            const size_t vr = (size_t)v * (L + 1), rr = (size_t)(v * kMaxPP + pp - 1) * (L + 1);
-            FC = ws.pfc[vr + hi] - ws.pfc[vr + lo];
-            BC = ws.pbc[vr + hi] - ws.pbc[vr + lo];
-            FA = ws.pfa[rr + hi] - ws.pfa[rr + lo];
-            BA = ws.pba[rr + hi] - ws.pba[rr + lo];
-            G = ws.pg[vr + hi] - ws.pg[vr + lo];
-            if (s + 1 < pp) PF = ws.p2p[((size_t)v * L + hi - 1) * 2 + (node != node_next ? 1 : 0)];
-            if (s > 0) PB = ws.p2p[((size_t)v * L + lo - 1) * 2 + (node != node_prev ? 1 : 0)];
-            AR = allreduce_ns(cl, dp, G);
-            // gradient all-reduce events on this stage's device
-            if (dp > 1 && G > 0) {
-                if (cl.bucket <= 0) {
-                    nar = 1;
-                } else {
-                    int64_t acc = 0;
-                    for (int l = hi - 1; l >= lo; l--) {
-                        acc += ws.pg[vr + l + 1] - ws.pg[vr + l];
-                        const int64_t k = (int64_t)udiv64((uint64_t)acc, (uint64_t)cl.bucket);
-                        nar += k;
-                        acc -= k * cl.bucket;
-                    }
-                    if (acc > 0) nar += 1;
-                }
-            }
-        }
+        StageRow r;
+        const int drop = stage_row(cl, ws, L, width, s, pp, v, m, dp, (int)d.spare, cur.lo, cur.hi, r);
+        const int64_t AR = allreduce_ns(cl, dp, r.G);
+        int64_t nar = (act && !drop) ? count_allreduce_events(cl, ws, L, v, dp, cur.lo, cur.hi, r.G) : 0;
         if (more) stage_fetch_bounds(ca, L, nx);
-        // every timestamp of the pipeline phase is bounded by m * (all task and p2p durations)
-        const uint64_t t1 = (uint64_t)group_sum(FC + FA + BC + BA + PF + PB, width);
-        const bool range = __umul64hi(t1, (uint64_t)m) != 0 || t1 * (uint64_t)m >= (1ull << 53);
         nar = group_sum(nar, width);
-        const bool drop = bad || range;
-        const int lo_w = drop ? 0 : lo, hi_w = drop ? 0 : hi;
-        if (drop) { FC = FA = BC = BA = PF = PB = G = AR = 0; }
+        const int lo_w = drop ? 0 : cur.lo, hi_w = drop ? 0 : cur.hi;
         const int64_t i = w * kWave + lane;
-        ev.stage_tab[0 * cap + i] = FC;
-        ev.stage_tab[1 * cap + i] = FA;
-        ev.stage_tab[2 * cap + i] = BC;
-        ev.stage_tab[3 * cap + i] = BA;
-        ev.stage_tab[4 * cap + i] = PF;
-        ev.stage_tab[5 * cap + i] = PB;
-        ev.stage_tab[6 * cap + i] = G;
+        ev.stage_tab[0 * cap + i] = r.FC;
+        ev.stage_tab[1 * cap + i] = r.FA;
+        ev.stage_tab[2 * cap + i] = r.BC;
+        ev.stage_tab[3 * cap + i] = r.BA;
+        ev.stage_tab[4 * cap + i] = r.PF;
+        ev.stage_tab[5 * cap + i] = r.PB;
+        ev.stage_tab[6 * cap + i] = r.G;
         ev.stage_tab[7 * cap + i] = AR;
         ev.stage_layers[i] = lo_w | (hi_w << 8);
         if (act && s == 0) {
             const int64_t c = d.cand;
             if (drop) {
-                ev.status[c] = bad ? 1 : 2;
+                ev.status[c] = drop;
                 ev.num_events[c] = 0;
-                ws.desc[pos].meta = 0;               // simulate skips it
             } else {
                 ev.num_events[c] = 2ll * m * pp + 2ll * m * (pp - 1) + nar;
             }

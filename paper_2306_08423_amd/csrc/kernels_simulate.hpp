@@ -113,14 +113,13 @@ __device__ __forceinline__ double from_lanes(double x, int byte_addr) {
 #ifndef SIM_WAVES_PER_EU
 #define SIM_WAVES_PER_EU 8
 #endif
-__global__ __launch_bounds__(256, SIM_WAVES_PER_EU) void k_simulate(CostsDev co, ClusterDev cl, Workspace ws, EventsDev ev,
-                                                  SimOut out) {
+__global__ __launch_bounds__(256, SIM_WAVES_PER_EU) void k_simulate(CostsDev co, ClusterDev cl, CandDev ca,
+                                                                    Workspace ws, EventsDev ev, SimOut out) {
     const int lane = lane_id();
     const int64_t wave0 = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / kWave;
     const int64_t nwaves = ((int64_t)gridDim.x * blockDim.x) / kWave;
     int64_t W = ws.hdr[H_NUM_ITEMS];
     if (W * kWave > ev.stage_cap) W = ev.stage_cap / kWave;
-    const int64_t cap = ev.stage_cap;
     const int L = co.L;
     const double ninf = -__builtin_huge_val();
 
@@ -129,25 +128,36 @@ __global__ __launch_bounds__(256, SIM_WAVES_PER_EU) void k_simulate(CostsDev co,
         const int width = 1 << it.sh;
         const int s = lane & (width - 1);
         const int64_t pos = it.pos0 + (lane >> it.sh);
-        int4 dd = make_int4(0, 0, 0, 0);                   // cand, meta, m, dp
-        if (pos < it.class_end) dd = *reinterpret_cast<const int4*>(&ws.desc[pos]);
-        const int pp = dd.y & 0xff, sched = (dd.y >> 8) & 0xff, v = dd.y >> 16, dp = dd.y ? dd.w : 1;
-        const int64_t c = dd.x;
+        Desc d{};
+        if (pos < it.class_end) d = ws.desc[pos];
+        int pp = d.meta & 0xff;
+        const int sched = (d.meta >> 8) & 0xff, v = d.meta >> 16, dp = d.meta ? d.dp : 1;
+        const int64_t c = d.cand;
+        // the stage's composed events, regenerated from the layer-event tables
+        int lo = 0, hi = 0;
+        if (s < pp) {
+            if (d.poff >= 0) { lo = ca.part_pool[d.poff + s]; hi = ca.part_pool[d.poff + s + 1]; }
+            else { lo = (int)(((int64_t)s * L) / pp); hi = (int)(((int64_t)(s + 1) * L) / pp); }
+        }
+        StageRow r;
+        const int drop = stage_row(cl, ws, L, width, s, pp, v, d.m, dp, (int)d.spare, lo, hi, r);
+        if (drop) {
+            if (s == 0 && pp > 0) { ev.status[c] = drop; ev.num_events[c] = 0; out.batch_ns[c] = INT64_MAX; }
+            pp = 0;
+        }
         const bool act = s < pp;
-        const int m = act ? dd.z : 0;
+        const int m = act ? d.m : 0;
         const int64_t i = w * kWave + lane;
-        // rows of lanes outside a candidate are zero-filled by event generation
         double Fd, Bd, pfL, pbR;
         int64_t comp1, comm1, AR;            // per-micro-batch computation / communication, trailing all-reduce
+        bool has_ar;                         // the stage has gradient bytes to reduce over dp > 1 ranks
         {
-            const int64_t FC = ev.stage_tab[0 * cap + i], FA = ev.stage_tab[1 * cap + i];
-            const int64_t BC = ev.stage_tab[2 * cap + i], BA = ev.stage_tab[3 * cap + i];
-            const int64_t PF = ev.stage_tab[4 * cap + i], PB = ev.stage_tab[5 * cap + i];
-            AR = ev.stage_tab[7 * cap + i];
-            Fd = (double)(FC + FA); Bd = (double)(BC + BA);
-            comp1 = FC + BC; comm1 = FA + BA + PF + PB;
+            AR = allreduce_ns(cl, dp, r.G);
+            has_ar = act && dp > 1 && r.G > 0;
+            Fd = (double)(r.FC + r.FA); Bd = (double)(r.BC + r.BA);
+            comp1 = r.FC + r.BC; comm1 = r.FA + r.BA + r.PF + r.PB;
             // p2p latency on the incoming edges (the neighbours' outgoing events); -inf = no edge
-            pfL = from_prev_lane((double)PF); pbR = from_next_lane((double)PB);
+            pfL = from_prev_lane((double)r.PF); pbR = from_next_lane((double)r.PB);
         }
         if (!(act && s > 0)) pfL = ninf;
         if (!(act && s + 1 < pp)) pbR = ninf;
@@ -252,35 +262,34 @@ __global__ __launch_bounds__(256, SIM_WAVES_PER_EU) void k_simulate(CostsDev co,
 
         // data-parallel modelling: gradient all-reduce after (or overlapped with) the last backward
         const int64_t endB = (int64_t)own;
-        int64_t finish = endB + AR, ar_busy = AR;
-        if (act && cl.bucket > 0) {
-            finish = endB; ar_busy = 0;
-            if (dp > 1) {
-                const int lay = ev.stage_layers[i];
-                const int lo = lay & 0xff, hi = lay >> 8;
-                const size_t vr = (size_t)v * (L + 1), rr = (size_t)(v * kMaxPP + pp - 1) * (L + 1);
-                const int64_t startB = endB - (int64_t)Bd;
-                const int64_t tot_hi = ws.pbc[vr + hi] + ws.pba[rr + hi];
-                const int64_t ar_cap = allreduce_ns(cl, dp, cl.bucket);
-                int64_t acc = 0, t = 0;
-                for (int l = hi - 1; l >= lo; l--) {
-                    const int64_t ready = startB + (tot_hi - (ws.pbc[vr + l] + ws.pba[rr + l]));
-                    acc += ws.pg[vr + l + 1] - ws.pg[vr + l];
-                    const int64_t k = (int64_t)udiv64((uint64_t)acc, (uint64_t)cl.bucket);
-                    if (k > 0) {
-                        t = (t > ready ? t : ready) + k * ar_cap;
-                        ar_busy += k * ar_cap;
-                        acc -= k * cl.bucket;
-                    }
-                    if (l == lo && acc > 0) {
-                        const int64_t d = allreduce_ns(cl, dp, acc);
-                        t = (t > ready ? t : ready) + d;
-                        ar_busy += d;
-                    }
+        int64_t finish = endB + AR, ar_busy = AR, nar = has_ar ? 1 : 0;
+        if (has_ar && cl.bucket > 0) {
+            const size_t vr = (size_t)v * (L + 1), rr = (size_t)(v * kMaxPP + pp - 1) * (L + 1);
+            const int64_t startB = endB - (int64_t)Bd;
+            const int64_t tot_hi = ws.pbc[vr + hi] + ws.pba[rr + hi];
+            const int64_t ar_cap = allreduce_ns(cl, dp, cl.bucket);
+            int64_t acc = 0, t = 0;
+            ar_busy = 0; nar = 0;
+            for (int l = hi - 1; l >= lo; l--) {
+                const int64_t ready = startB + (tot_hi - (ws.pbc[vr + l] + ws.pba[rr + l]));
+                acc += ws.pg[vr + l + 1] - ws.pg[vr + l];
+                const int64_t k = (int64_t)udiv64((uint64_t)acc, (uint64_t)cl.bucket);
+                if (k > 0) {
+                    t = (t > ready ? t : ready) + k * ar_cap;
+                    ar_busy += k * ar_cap;
+                    nar += k;
+                    acc -= k * cl.bucket;
                 }
-                finish = t > endB ? t : endB;
+                if (l == lo && acc > 0) {
+                    const int64_t dlast = allreduce_ns(cl, dp, acc);
+                    t = (t > ready ? t : ready) + dlast;
+                    ar_busy += dlast;
+                    nar += 1;
+                }
             }
+            finish = t > endB ? t : endB;
         }
+        nar = group_sum(nar, width);
         const int64_t batch = group_max(act ? finish : 0, width);
         // lanes outside a candidate have m = 0 and zero rows: they store zeros
         const int64_t comp = (int64_t)m * comp1;
@@ -288,7 +297,10 @@ __global__ __launch_bounds__(256, SIM_WAVES_PER_EU) void k_simulate(CostsDev co,
         out.comp_busy[i] = comp;
         out.comm_busy[i] = comm;
         if (out.util) out.util[i] = batch > 0 ? (double)comp / (double)batch : 0.0;
-        if (act && s == 0) out.batch_ns[c] = batch;
+        if (act && s == 0) {
+            out.batch_ns[c] = batch;
+            ev.num_events[c] = 2ll * m * pp + 2ll * m * (pp - 1) + nar;
+        }
     }
 }
 

@@ -17,15 +17,16 @@ def ctx():
     return _ctx
 
 
-def run_hip(w, stage_cap=None, util=True, search=None):
+def run_hip(w, stage_cap=None, util=True, search=None, table=True):
     """search: None or (objective, weight ndarray or None)."""
     c = ctx()
     dw = ds.upload(w, c.device)
     cap = ds.stage_entries(w.cand["pp"]) if stage_cap is None else stage_cap
-    ev = ds.alloc_events(c, dw.L, dw.V, dw.C, cap)
+    ev = ds.alloc_events(c, dw.L, dw.V, dw.C, cap, table=table)
     # poison the outputs so that untouched entries show up
     ev.status.fill_(-7); ev.stage_pos.fill_(-7); ev.num_events.fill_(-7)
-    ev.stage_tab.fill_(-7); ev.stage_layers.fill_(-7)
+    if table:
+        ev.stage_tab.fill_(-7); ev.stage_layers.fill_(-7)
     ds.distsim_build_events(c, dw, ev)
     out = ds.alloc_outputs(c, ev, util=util)
     out.batch_ns.fill_(-7); out.comp_busy_ns.fill_(-7); out.comm_busy_ns.fill_(-7)
@@ -46,8 +47,6 @@ def run_hip(w, stage_cap=None, util=True, search=None):
         "status": ev.status.cpu().numpy()[:C],
         "num_events": ev.num_events.cpu().numpy()[:C],
         "stage_pos": ev.stage_pos.cpu().numpy()[:C],
-        "stage_tab": ev.stage_tab.cpu().numpy()[:, :cap],
-        "stage_layers": ev.stage_layers.cpu().numpy()[:cap],
         "batch_ns": out.batch_ns.cpu().numpy()[:C],
         "comp_busy_ns": out.comp_busy_ns.cpu().numpy()[:cap],
         "comm_busy_ns": out.comm_busy_ns.cpu().numpy()[:cap],
@@ -55,6 +54,9 @@ def run_hip(w, stage_cap=None, util=True, search=None):
     })
     if util:
         res["util"] = out.util.cpu().numpy()[:cap]
+    if table:
+        res["stage_tab"] = ev.stage_tab.cpu().numpy()[:, :cap]
+        res["stage_layers"] = ev.stage_layers.cpu().numpy()[:cap]
     return res
 
 

@@ -78,6 +78,27 @@ def test_sampled_parity_full_size_launch(H, oracle_mod, name, nsample):
     assert np.all(hip["num_events"] >= 2 * m * pp + 2 * m * (pp - 1))
 
 
+def test_without_stage_table(H, oracle_mod):
+    """stage_tab == NULL: nothing per-stage is written by event generation and simulate composes
+    the stage events itself; results, statuses and event counts must be the same."""
+    _say("[case] no stage table")
+    for name in ("gpt24", "gpt48"):
+        w = make_workload(name)
+        H.assert_same(H.run_hip(w, table=False), oracle_mod.simulate(w, nthreads=NT), what=name + " lazy")
+    costs = mk_costs([10] * 4, [20] * 4, tps=(1,))
+    rows = [(1, 1, 2, 4, 1, None), (1, 1, 2, 4, 1, [0, 0, 4]), (1, 1, 2, 4, 1, [0, 2, 3]), (1, 1, 2, 4, 0, [0, 1, 4]),
+            (2, 1, 2, 4, 1, None)]
+    w = mk(costs, mk_cluster(2), rows)
+    hip = H.run_hip(w, table=False)
+    H.assert_same(hip, oracle_mod.simulate(w), what="lazy invalid")
+    assert list(hip["status"]) == [0, 1, 1, 0, 1]
+    big = mk_costs([1 << 48] * 4, [1 << 48] * 4)
+    w3 = mk(big, mk_cluster(2), [(1, 1, 2, 1, 1, None), (1, 1, 2, 4, 1, None)])
+    hip = H.run_hip(w3, table=False)
+    H.assert_same(hip, oracle_mod.simulate(w3), what="lazy range")
+    assert list(hip["status"]) == [0, 2]
+
+
 def test_runs_are_deterministic(H):
     _say("[case] determinism")
     w = make_workload("gpt48")
