@@ -39,7 +39,8 @@ __device__ __forceinline__ int64_t group_max(int64_t v, int width) {
     return v;
 }
 __device__ __forceinline__ int64_t group_sum(int64_t v, int width) {
-    for (int d = 1; d < width; d <<= 1) v += __shfl_xor(v, d, kWave);
+    for (int d = 1; d < width; d <<= 1)
+        v += __shfl_xor(v, d, kWave);
     return v;
 }
 __device__ __forceinline__ int wave_max_i32(int v) {

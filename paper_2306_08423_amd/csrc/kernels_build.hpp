@@ -264,7 +264,9 @@ __device__ __forceinline__ int stage_row(const ClusterDev& cl, const Workspace& 
     int64_t node = 0;           // node of the stage's first rank (ranks ordered tp fastest, then dp, then pp)
     if (act) {
         bad = (hi <= lo) || (hi > L) || (s == 0 && lo != 0) || (s == pp - 1 && hi != L);
-        node = (int64_t)udiv64((uint64_t)s * (uint64_t)((int64_t)tp * dp), (uint64_t)cl.gpus_per_node);
+        // a stage of at least a node's worth of ranks starts on a node of its own
+        const int64_t tpdp = (int64_t)tp * dp;
+        node = tpdp >= cl.gpus_per_node ? s : (int64_t)udiv64((uint64_t)s * (uint64_t)tpdp, (uint64_t)cl.gpus_per_node);
     }
     bad = (int)group_sum(bad, width);
     const int64_t node_next = __shfl_down(node, 1, kWave), node_prev = __shfl_up(node, 1, kWave);

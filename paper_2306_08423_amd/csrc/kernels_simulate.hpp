@@ -59,22 +59,23 @@ __device__ __forceinline__ uint32_t wave_or_u32(uint32_t x) {
 // Operand of a level on which lanes of one parity run forwards and the others backwards:
 // the previous lane's value for the forward lanes, the next lane's for the backward lanes,
 // fetched with one ds_bpermute per 32-bit half (byte address = 4 * source lane).
-#ifndef SIM_PAR_MODE
-#define SIM_PAR_MODE 2
-#endif
-#if SIM_PAR_MODE == 2
+// On odd levels the forward lanes are the odd stages and read stage s-1, the backward lanes
+// are the even stages and read stage s+1: lanes 2k and 2k+1 read each other, which is one
+// quad permutation.
+__device__ __forceinline__ double from_pair_partner(double x) {
+    int lo = __double2loint(x), hi = __double2hiint(x);
+    lo = __builtin_amdgcn_update_dpp(0, lo, 0xB1, 0xf, 0xf, true);      // quad_perm [1,0,3,2]
+    hi = __builtin_amdgcn_update_dpp(0, hi, 0xB1, 0xf, 0xf, true);
+    return __hiloint2double(hi, lo);
+}
+// On even levels (past the warm-up) the forward lanes are the even stages and read stage s-1,
+// the backward lanes are the odd stages and read stage s+1: no single DPP pattern, so the
+// operand comes through one ds_bpermute per 32-bit half (byte address = 4 * source lane).
 __device__ __forceinline__ double from_lanes(double x, int byte_addr) {
     const int lo = __builtin_amdgcn_ds_bpermute(byte_addr, __double2loint(x));
     const int hi = __builtin_amdgcn_ds_bpermute(byte_addr, __double2hiint(x));
     return __hiloint2double(hi, lo);
 }
-#else
-// byte_addr < own address: take the previous lane, else the next lane
-__device__ __forceinline__ double from_lanes(double x, int byte_addr) {
-    const double a = from_prev_lane(x), b = from_next_lane(x);
-    return byte_addr < (int)(threadIdx.x & 63) * 4 ? a : b;
-}
-#endif
 
 // One level for the lanes whose pattern bit is set: own = max(own, nb + lat) + dur.
 // Requires EXEC == all ones on entry (wave-uniform control flow, full wavefronts) and leaves
@@ -110,10 +111,7 @@ __device__ __forceinline__ double from_lanes(double x, int byte_addr) {
           [kf] "=&s"(kmask), [kb] "=&s"(kmask2)                               \
         : [cl] "v"(pfL), [cr] "v"(pbR), [df] "v"(Fd), [db] "v"(Bd))
 
-#ifndef SIM_WAVES_PER_EU
-#define SIM_WAVES_PER_EU 8
-#endif
-__global__ __launch_bounds__(256, SIM_WAVES_PER_EU) void k_simulate(CostsDev co, ClusterDev cl, CandDev ca,
+__global__ __launch_bounds__(256, 8) void k_simulate(CostsDev co, ClusterDev cl, CandDev ca,
                                                                     Workspace ws, EventsDev ev, SimOut out) {
     const int lane = lane_id();
     const int64_t wave0 = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / kWave;
@@ -152,7 +150,7 @@ __global__ __launch_bounds__(256, SIM_WAVES_PER_EU) void k_simulate(CostsDev co,
         int64_t comp1, comm1, AR;            // per-micro-batch computation / communication, trailing all-reduce
         bool has_ar;                         // the stage has gradient bytes to reduce over dp > 1 ranks
         {
-            AR = allreduce_ns(cl, dp, r.G);
+            AR = cl.bucket > 0 ? 0 : allreduce_ns(cl, dp, r.G);
             has_ar = act && dp > 1 && r.G > 0;
             Fd = (double)(r.FC + r.FA); Bd = (double)(r.BC + r.BA);
             comp1 = r.FC + r.BC; comm1 = r.FA + r.BA + r.PF + r.PB;
@@ -182,11 +180,11 @@ __global__ __launch_bounds__(256, SIM_WAVES_PER_EU) void k_simulate(CostsDev co,
         // splits the lanes by parity, and one merged operand (previous lane for the forward
         // lanes, next lane for the backward lanes) feeds a single task step.
         const int ppu = __builtin_amdgcn_readfirstlane(wave_max_i32(pp));
-        const bool par_ok = SIM_PAR_MODE != 0 && width >= 2 && __builtin_amdgcn_ballot_w64(act && (sched == 0 || pp != ppu)) == 0;
+        const bool par_ok = width >= 2 && __builtin_amdgcn_ballot_w64(act && (sched == 0 || pp != ppu)) == 0;
         const bool even_s = (s & 1) == 0;
         const double latE = even_s ? pfL : pbR, durE = even_s ? Fd : Bd;     // roles on even levels
         const double latO = even_s ? pbR : pfL, durO = even_s ? Bd : Fd;     // roles on odd levels
-        const int adrE = (even_s ? lane - 1 : lane + 1) * 4, adrO = (even_s ? lane + 1 : lane - 1) * 4;
+        const int adrE = (even_s ? lane - 1 : lane + 1) * 4;
 
         double own = 0.0;
         for (int l0 = 0; l0 < nlev; l0 += 32) {
@@ -218,14 +216,14 @@ __global__ __launch_bounds__(256, SIM_WAVES_PER_EU) void k_simulate(CostsDev co,
                         uint32_t Pc = PFb | PBb;
                         int j = 0;
                         if (((l0 + k) & 1) && j < len) {
-                            double nb = from_lanes(own, adrO);
+                            double nb = from_pair_partner(own);
                             DISTSIM_STEP_ONE(Pc, nb, latO, durO);
                             j++;
                         }
                         for (; j + 1 < len; j += 2) {
                             double nb = from_lanes(own, adrE);
                             DISTSIM_STEP_ONE(Pc, nb, latE, durE);
-                            double nb2 = from_lanes(own, adrO);
+                            double nb2 = from_pair_partner(own);
                             DISTSIM_STEP_ONE(Pc, nb2, latO, durO);
                         }
                         if (j < len) {
