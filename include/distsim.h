@@ -102,6 +102,11 @@ typedef struct {
     int64_t dp_bucket_bytes;         /* 0: one all-reduce after the last backward (Sec. 4.3);
                                         > 0: gradient buckets of this size, each issued as soon
                                         as the last micro-batch's backward has produced it       */
+    int32_t p2p_blocking;            /* 0: the p2p event is latency on the edge to the neighbouring
+                                        stage, the sender goes on with its next task (default);
+                                        1: the sender's device is occupied for the p2p event, which
+                                        then counts as the tail of the stage-task, and the
+                                        neighbour may start when it ends                         */
 } distsim_cluster;
 
 /* Candidate strategies "xM xP xD" (Sec. 5.1) x micro-batches x schedule x partition.

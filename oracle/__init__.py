@@ -88,7 +88,7 @@ def simulate(w, nthreads: int = 1, timeline: bool = False) -> Dict[str, np.ndarr
     rc = lib.oracle_simulate(
         ctypes.c_int32(L), ctypes.c_int32(V), _p(vt), *[_p(a) for a in cols],
         ctypes.c_int32(int(cl["num_devices"])), ctypes.c_int32(int(cl["gpus_per_node"])),
-        _p(alpha), _p(beta), ctypes.c_int64(int(cl["dp_bucket_bytes"])),
+        _p(alpha), _p(beta), ctypes.c_int64(int(cl["dp_bucket_bytes"])), ctypes.c_int32(int(cl.get("p2p_blocking", 0))),
         ctypes.c_int64(C), _p(dp), _p(tp), _p(pp), _p(m), _p(sched), _p(poff), _p(pool),
         _p(status), _p(batch), _p(nev), _p(soff), _p(comp), _p(comm), _p(util),
         _p(tls), _p(tle), ctypes.c_int32(int(nthreads)))

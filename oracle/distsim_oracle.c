@@ -121,6 +121,7 @@ typedef struct {
     int32_t num_devices, gpus_per_node;
     int64_t alpha[2], beta[2];
     int64_t bucket;
+    int32_t p2p_blocking;   /* the p2p event occupies the sender: it is the tail of the stage-task */
 } cluster_t;
 
 static int64_t p2p_ns(const cluster_t *cl, int64_t bytes, int k) {
@@ -297,6 +298,10 @@ static void simulate_one(const costs_t *co, const cluster_t *cl,
                             heap_push(h, t, EV_GRAD_READY, s__, j, l);                  \
                     }                                                                   \
                 }                                                                       \
+                if (cl->p2p_blocking) {           /* the send runs on the device */     \
+                    if (kd == 0 && s__ + 1 < pp) t += pf[s__];                          \
+                    if (kd == 1 && s__ > 0) t += pb[s__];                               \
+                }                                                                       \
                 heap_push(h, t, EV_TASK_DONE, s__, j, kd);                              \
             }                                                                           \
         }                                                                               \
@@ -316,11 +321,11 @@ static void simulate_one(const costs_t *co, const cluster_t *cl,
             busy[s] = 0;
             next[s]++;
             if (kd == 0 && s + 1 < pp) {            /* (e_comm, t + e.elapsed, m) of Algorithm 1 */
-                heap_push(h, now + pf[s], EV_ARRIVE_F, s + 1, j, 0);
+                heap_push(h, now + (cl->p2p_blocking ? 0 : pf[s]), EV_ARRIVE_F, s + 1, j, 0);
                 mb_[s] += pf[s]; nev++;
             }
             if (kd == 1 && s > 0) {
-                heap_push(h, now + pb[s], EV_ARRIVE_B, s - 1, j, 0);
+                heap_push(h, now + (cl->p2p_blocking ? 0 : pb[s]), EV_ARRIVE_B, s - 1, j, 0);
                 mb_[s] += pb[s]; nev++;
             }
             if (next[s] == 2 * m && dp > 1 && cap == 0) {   /* trailing gradient all-reduce */
@@ -388,7 +393,7 @@ int oracle_simulate(int32_t L, int32_t V, const int32_t *variant_tp,
                     const int64_t *fc, const int64_t *bc, const int64_t *fa, const int64_t *ba,
                     const int64_t *act, const int64_t *grad, const int64_t *a2a,
                     int32_t num_devices, int32_t gpus_per_node,
-                    const int64_t *alpha2, const int64_t *beta2, int64_t bucket,
+                    const int64_t *alpha2, const int64_t *beta2, int64_t bucket, int32_t p2p_blocking,
                     int64_t C, const int32_t *dp, const int32_t *tp, const int32_t *pp, const int32_t *m,
                     const uint8_t *schedule, const int64_t *part_off, const uint8_t *part_pool,
                     int32_t *status, int64_t *batch_ns, int64_t *num_events, int64_t *stage_off,
@@ -396,7 +401,7 @@ int oracle_simulate(int32_t L, int32_t V, const int32_t *variant_tp,
                     int64_t *tl_start, int64_t *tl_end, int32_t nthreads) {
     if (L < 1 || V < 1 || C < 0 || beta2[0] < 1 || beta2[1] < 1 || gpus_per_node < 1) return -1;
     costs_t co = { L, V, variant_tp, fc, bc, fa, ba, act, grad, a2a };
-    cluster_t cl = { num_devices, gpus_per_node, { alpha2[0], alpha2[1] }, { beta2[0], beta2[1] }, bucket };
+    cluster_t cl = { num_devices, gpus_per_node, { alpha2[0], alpha2[1] }, { beta2[0], beta2[1] }, bucket, p2p_blocking };
 
     /* Each candidate is simulated into a temporary of its own; the ragged outputs are
      * packed afterwards, once the prefix of the slot counts is known. */

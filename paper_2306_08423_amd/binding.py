@@ -39,7 +39,7 @@ class _Costs(C.Structure):
 class _Cluster(C.Structure):
     _fields_ = [("num_devices", C.c_int32), ("gpus_per_node", C.c_int32),
                 ("alpha_ns", C.c_int64 * 2), ("beta_bytes_per_ns", C.c_int64 * 2),
-                ("dp_bucket_bytes", C.c_int64)]
+                ("dp_bucket_bytes", C.c_int64), ("p2p_blocking", C.c_int32)]
 
 
 class _Cand(C.Structure):
@@ -179,7 +179,7 @@ def cluster_struct(cl) -> _Cluster:
     return _Cluster(int(cl["num_devices"]), int(cl["gpus_per_node"]),
                     (C.c_int64 * 2)(*[int(x) for x in cl["alpha_ns"]]),
                     (C.c_int64 * 2)(*[int(x) for x in cl["beta_bytes_per_ns"]]),
-                    int(cl["dp_bucket_bytes"]))
+                    int(cl["dp_bucket_bytes"]), int(cl.get("p2p_blocking", 0)))
 
 
 def upload(w, device) -> DeviceWorkload:

@@ -72,6 +72,7 @@ ClusterDev to_dev(const distsim_cluster& c) {
     d.alpha[0] = c.alpha_ns[0]; d.alpha[1] = c.alpha_ns[1];
     d.beta[0] = c.beta_bytes_per_ns[0]; d.beta[1] = c.beta_bytes_per_ns[1];
     d.bucket = c.dp_bucket_bytes;
+    d.blocking = c.p2p_blocking != 0;
     return d;
 }
 

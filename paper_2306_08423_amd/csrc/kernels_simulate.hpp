@@ -152,10 +152,12 @@ __global__ __launch_bounds__(256, 8) void k_simulate(CostsDev co, ClusterDev cl,
         {
             AR = cl.bucket > 0 ? 0 : allreduce_ns(cl, dp, r.G);
             has_ar = act && dp > 1 && r.G > 0;
-            Fd = (double)(r.FC + r.FA); Bd = (double)(r.BC + r.BA);
             comp1 = r.FC + r.BC; comm1 = r.FA + r.BA + r.PF + r.PB;
-            // p2p latency on the incoming edges (the neighbours' outgoing events); -inf = no edge
-            pfL = from_prev_lane((double)r.PF); pbR = from_next_lane((double)r.PB);
+            // p2p on the incoming edges (the neighbours' outgoing events): latency of the edge, or,
+            // when the sender is occupied by it, part of the sender's task; -inf = no edge
+            const int64_t pf_task = cl.blocking ? r.PF : 0, pb_task = cl.blocking ? r.PB : 0;
+            Fd = (double)(r.FC + r.FA + pf_task); Bd = (double)(r.BC + r.BA + pb_task);
+            pfL = from_prev_lane((double)(r.PF - pf_task)); pbR = from_next_lane((double)(r.PB - pb_task));
         }
         if (!(act && s > 0)) pfL = ninf;
         if (!(act && s + 1 < pp)) pbR = ninf;

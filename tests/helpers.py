@@ -35,9 +35,9 @@ def mk_costs(fc, bc, fa=None, ba=None, act=None, grad=None, a2a=None, tps=(1,)):
     }
 
 
-def mk_cluster(n, g=8, alpha=(5000, 10000), beta=(200, 25), bucket=0):
+def mk_cluster(n, g=8, alpha=(5000, 10000), beta=(200, 25), bucket=0, blocking=0):
     return {"num_devices": int(n), "gpus_per_node": int(g), "alpha_ns": tuple(alpha),
-            "beta_bytes_per_ns": tuple(beta), "dp_bucket_bytes": int(bucket)}
+            "beta_bytes_per_ns": tuple(beta), "dp_bucket_bytes": int(bucket), "p2p_blocking": int(blocking)}
 
 
 def mk_cands(rows):

@@ -99,6 +99,21 @@ def test_without_stage_table(H, oracle_mod):
     assert list(hip["status"]) == [0, 2]
 
 
+def test_blocking_p2p(H, oracle_mod):
+    _say("[case] blocking p2p")
+    for name in ("gpt24", "gpt48"):
+        w = make_workload(name)
+        cl = dict(w.cluster); cl["p2p_blocking"] = 1
+        wb = Workload(name + "+blocking", w.costs, cl, w.cand)
+        H.assert_same(H.run_hip(wb), oracle_mod.simulate(wb, nthreads=NT), what=wb.name)
+    w = make_workload("gpt96")
+    rng = np.random.default_rng(5)
+    idx = np.sort(rng.choice(w.C, 3000, replace=False))
+    cl = dict(w.cluster); cl["p2p_blocking"] = 1
+    wb = Workload("gpt96+blocking", w.costs, cl, subset(w, idx).cand)
+    H.assert_same(H.run_hip(wb, table=False), oracle_mod.simulate(wb, nthreads=NT), what=wb.name)
+
+
 def test_runs_are_deterministic(H):
     _say("[case] determinism")
     w = make_workload("gpt48")

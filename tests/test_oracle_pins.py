@@ -278,6 +278,48 @@ def test_brute_force_longest_path_all_timestamps(oracle_mod):
     assert checked == 400
 
 
+def test_blocking_p2p_against_task_graph(oracle_mod):
+    """p2p_blocking = 1: the send occupies the sender, so it is the tail of the stage-task and
+    the edge to the neighbour has no latency left.  Same task graph, durations F + pf / B + pb."""
+    rng = np.random.default_rng(21)
+    L = 6
+    for trial in range(300):
+        pp = int(rng.integers(1, 5))
+        m = int(rng.integers(1, 7))
+        sched = int(rng.integers(0, 2))
+        cuts = sorted(rng.choice(np.arange(1, L), size=pp - 1, replace=False).tolist())
+        bnd = [0] + cuts + [L]
+        fc = rng.integers(0, 50, L).tolist()
+        bc = rng.integers(0, 50, L).tolist()
+        act = (rng.integers(0, 9, L) * 5).tolist()
+        dp = int(rng.choice([1, 2]))
+        costs = mk_costs(fc, bc, act=act, grad=[100] * L)
+        cl = mk_cluster(dp * pp, g=1 << 20, alpha=(2, 0), beta=(5, 1), blocking=1)
+        r = one(oracle_mod, costs, cl, (dp, 1, pp, m, sched, bnd), timeline=True)
+        pf = [2 + act[bnd[s + 1] - 1] // 5 for s in range(pp - 1)] + [0]
+        pb = [0] + [2 + act[bnd[s] - 1] // 5 for s in range(1, pp)]
+        F = [a + b for a, b in zip(_stage_sums(fc, bnd), pf)]
+        B = [a + b for a, b in zip(_stage_sums(bc, bnd), pb)]
+        start, end = longest_path(sched, pp, m, F, B, [0] * pp, [0] * pp)
+        for (k, s, j), v in start.items():
+            kd = 0 if k == "F" else 1
+            assert r["start"][kd, s, j] == v, (trial, k, s, j)
+            assert r["end"][kd, s, j] == end[(k, s, j)]
+        G = [100 * (bnd[s + 1] - bnd[s]) for s in range(pp)]
+        ar = [0 if dp == 1 else 2 + (2 * (dp - 1) * g) // (dp * 5) for g in G]
+        assert r["batch_ns"][0] == max(end[("B", s, m - 1)] + ar[s] for s in range(pp))
+        for s in range(pp):
+            assert r["comm_busy_ns"][s] == m * (pf[s] + pb[s]) + ar[s]
+    # against the latency reading: blocking can only delay
+    w = make_workload("gpt24")
+    from workloads import Workload
+    cl = dict(w.cluster); cl["p2p_blocking"] = 1
+    a = oracle_mod.simulate(w)
+    b = oracle_mod.simulate(Workload("x", w.costs, cl, w.cand))
+    assert np.all(b["batch_ns"] >= a["batch_ns"]) and np.any(b["batch_ns"] > a["batch_ns"])
+    assert np.array_equal(a["comm_busy_ns"], b["comm_busy_ns"])
+
+
 def test_exhaustive_partitions_small(oracle_mod):
     """Every partition of L = 5 layers, both schedules, m = 1..4, against the task graph."""
     L = 5
