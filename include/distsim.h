@@ -220,13 +220,33 @@ int distsim_search(distsim_ctx *ctx, const int64_t *batch_ns, const int64_t *wei
                    int objective, int64_t *best, void *scratch, void *hip_stream);
 
 /*
+ * Timeline dump for selected candidates: the per-device event lists that Algorithm 1 builds,
+ * reduced to their stage-tasks (Sec. 3.2: the timeline says when which device computes and
+ * communicates; Sec. 5.3 / 5.4 compare exactly these start and end timestamps).
+ *   sel[n]       device: candidate indices (status must be OK after distsim_simulate, or after
+ *                distsim_build_events with a stage table; other candidates get no task entries)
+ *   task_off[n]  device: first entry of the candidate's block in start_ns / end_ns; the block
+ *                holds 2*pp*m entries laid out [kind][stage][micro-batch], kind 0 = forward,
+ *                1 = backward.  With p2p_blocking the end includes the send.
+ *   ar_start_ns / ar_end_ns [n][DISTSIM_MAX_PP]: start of the first and end of the last gradient
+ *                all-reduce event on each stage's device, -1 where there is none.
+ * p2p events follow from the table: the one after task (kind, s, j) starts at that task's end
+ * (its compute end) and lasts stage_tab[PF or PB].  Errors: EINVAL, ERANGE, EHIP.
+ */
+int distsim_timeline(distsim_ctx *ctx, const distsim_cluster *cluster, const distsim_events *events,
+                     int64_t n, const int64_t *sel, const int64_t *task_off,
+                     int64_t *start_ns, int64_t *end_ns, int64_t *ar_start_ns, int64_t *ar_end_ns,
+                     void *hip_stream);
+
+/*
  * Optional kernel timing with HIP events recorded on the caller's stream around each kernel
  * launch.  distsim_timing_read blocks until the recorded launches have finished and returns
  * the accumulated time and launch count of one kernel, then clears that kernel's record.
  */
 enum {
     DISTSIM_K_LAYER_TABLES = 0, DISTSIM_K_DECODE, DISTSIM_K_BINS, DISTSIM_K_SCATTER,
-    DISTSIM_K_STAGE_EVENTS, DISTSIM_K_SIM_INIT, DISTSIM_K_SIMULATE, DISTSIM_K_SEARCH, DISTSIM_K_COUNT
+    DISTSIM_K_STAGE_EVENTS, DISTSIM_K_SIM_INIT, DISTSIM_K_SIMULATE, DISTSIM_K_SEARCH, DISTSIM_K_TIMELINE,
+    DISTSIM_K_COUNT
 };
 int distsim_timing_enable(distsim_ctx *ctx, int on);
 int distsim_timing_read(distsim_ctx *ctx, int kernel, double *total_ms, int64_t *launches);

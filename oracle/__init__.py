@@ -53,7 +53,8 @@ def simulate(w, nthreads: int = 1, timeline: bool = False) -> Dict[str, np.ndarr
     Returns status[C], batch_ns[C], num_events[C], stage_off[C+1] and the ragged
     per-stage arrays comp_busy_ns / comm_busy_ns / util (index stage_off[c] + s).
     ``timeline=True`` (single candidate only) adds start/end[2][pp][m] of every
-    forward (0) and backward (1) stage-task.
+    forward (0) and backward (1) stage-task and ar_window[2][pp]: start of the first and
+    end of the last gradient all-reduce event of every stage (-1 = none).
     """
     lib = _load()
     co, cl, ca = w.costs, w.cluster, w.cand
@@ -80,25 +81,26 @@ def simulate(w, nthreads: int = 1, timeline: bool = False) -> Dict[str, np.ndarr
     comp = np.zeros(max(S, 1), np.int64)
     comm = np.zeros(max(S, 1), np.int64)
     util = np.zeros(max(S, 1), np.float64)
-    tls = tle = None
+    tls = tle = tar = None
     if timeline:
         assert C == 1
         tls = np.full((2, int(pp[0]), int(m[0])), -1, np.int64)
         tle = np.full((2, int(pp[0]), int(m[0])), -1, np.int64)
+        tar = np.full((2, int(pp[0])), -1, np.int64)
     rc = lib.oracle_simulate(
         ctypes.c_int32(L), ctypes.c_int32(V), _p(vt), *[_p(a) for a in cols],
         ctypes.c_int32(int(cl["num_devices"])), ctypes.c_int32(int(cl["gpus_per_node"])),
         _p(alpha), _p(beta), ctypes.c_int64(int(cl["dp_bucket_bytes"])), ctypes.c_int32(int(cl.get("p2p_blocking", 0))),
         ctypes.c_int64(C), _p(dp), _p(tp), _p(pp), _p(m), _p(sched), _p(poff), _p(pool),
         _p(status), _p(batch), _p(nev), _p(soff), _p(comp), _p(comm), _p(util),
-        _p(tls), _p(tle), ctypes.c_int32(int(nthreads)))
+        _p(tls), _p(tle), _p(tar), ctypes.c_int32(int(nthreads)))
     if rc != 0:
         raise ValueError(f"oracle_simulate rejected its arguments (rc={rc})")
     n = int(soff[C])
     out = {"status": status, "batch_ns": batch, "num_events": nev, "stage_off": soff,
            "comp_busy_ns": comp[:n], "comm_busy_ns": comm[:n], "util": util[:n]}
     if timeline:
-        out["start"], out["end"] = tls, tle
+        out["start"], out["end"], out["ar_window"] = tls, tle, tar
     return out
 
 

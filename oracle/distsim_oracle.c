@@ -188,7 +188,8 @@ static void simulate_one(const costs_t *co, const cluster_t *cl,
                          const uint8_t *bnd_in /* NULL = uniform */,
                          scratch_t *sc, result_t *res,
                          int64_t *comp_busy, int64_t *comm_busy, double *util, /* [pp] or NULL */
-                         int64_t *tl_start, int64_t *tl_end /* [2][pp][m] or NULL */) {
+                         int64_t *tl_start, int64_t *tl_end /* [2][pp][m] or NULL */,
+                         int64_t *tl_ar /* [2][pp]: start of the first, end of the last all-reduce; or NULL */) {
     const int L = co->L;
     res->status = ST_INVALID;
     res->batch_ns = INT64_MAX;
@@ -266,6 +267,7 @@ static void simulate_one(const costs_t *co, const cluster_t *cl,
     int64_t comm_free[256], acc[256];   /* DP communication stream, open bucket bytes */
     for (int s = 0; s < pp; s++) { next[s] = 0; busy[s] = 0; cb[s] = 0; mb_[s] = 0; comm_free[s] = 0; acc[s] = 0; }
     int64_t nev = 0, now = 0;
+    if (tl_ar) for (int s = 0; s < 2 * pp; s++) tl_ar[s] = -1;
     const int64_t cap = cl->bucket;
 
 /* start the next task of stage s if the device is idle and the input is there */
@@ -335,6 +337,7 @@ static void simulate_one(const costs_t *co, const cluster_t *cl,
                     int64_t d = allreduce_ns(cl, dp, G);
                     heap_push(h, now + d, EV_AR_DONE, s, 0, 0);
                     mb_[s] += d;
+                    if (tl_ar) { tl_ar[s] = now; tl_ar[pp + s] = now + d; }
                 }
             }
             TRY_START(s);
@@ -356,6 +359,7 @@ static void simulate_one(const costs_t *co, const cluster_t *cl,
                 comm_free[s] = st + d;
                 heap_push(h, comm_free[s], EV_AR_DONE, s, 0, 0);
                 mb_[s] += d;
+                if (tl_ar) { if (tl_ar[s] < 0) tl_ar[s] = st; tl_ar[pp + s] = comm_free[s]; }
                 acc[s] -= cap;
             }
             if (e.layer == bnd[s] && acc[s] > 0) {   /* the stage's first layer finishes last */
@@ -364,6 +368,7 @@ static void simulate_one(const costs_t *co, const cluster_t *cl,
                 comm_free[s] = st + d;
                 heap_push(h, comm_free[s], EV_AR_DONE, s, 0, 0);
                 mb_[s] += d;
+                if (tl_ar) { if (tl_ar[s] < 0) tl_ar[s] = st; tl_ar[pp + s] = comm_free[s]; }
                 acc[s] = 0;
             }
             break;
@@ -398,7 +403,7 @@ int oracle_simulate(int32_t L, int32_t V, const int32_t *variant_tp,
                     const uint8_t *schedule, const int64_t *part_off, const uint8_t *part_pool,
                     int32_t *status, int64_t *batch_ns, int64_t *num_events, int64_t *stage_off,
                     int64_t *comp_busy, int64_t *comm_busy, double *util,
-                    int64_t *tl_start, int64_t *tl_end, int32_t nthreads) {
+                    int64_t *tl_start, int64_t *tl_end, int64_t *tl_ar, int32_t nthreads) {
     if (L < 1 || V < 1 || C < 0 || beta2[0] < 1 || beta2[1] < 1 || gpus_per_node < 1) return -1;
     costs_t co = { L, V, variant_tp, fc, bc, fa, ba, act, grad, a2a };
     cluster_t cl = { num_devices, gpus_per_node, { alpha2[0], alpha2[1] }, { beta2[0], beta2[1] }, bucket, p2p_blocking };
@@ -421,7 +426,7 @@ int oracle_simulate(int32_t L, int32_t V, const int32_t *variant_tp,
             const uint8_t *b = part_off[c] >= 0 ? part_pool + part_off[c] : NULL;
             simulate_one(&co, &cl, dp[c], tp[c], p, m[c], schedule[c], b, &sc, &r,
                          buf, buf ? buf + p : NULL, buf ? (double *)(buf + 2 * p) : NULL,
-                         C == 1 ? tl_start : NULL, C == 1 ? tl_end : NULL);
+                         C == 1 ? tl_start : NULL, C == 1 ? tl_end : NULL, C == 1 ? tl_ar : NULL);
             status[c] = r.status;
             batch_ns[c] = r.batch_ns;
             num_events[c] = r.num_events;

@@ -6,6 +6,6 @@ PyTorch device tensors into those calls.
 """
 from .binding import (  # noqa: F401
     Context, DeviceWorkload, DistSimError, Events, SimOutputs, EXPORTS, KERNELS, COL, LIB_PATH,
-    alloc_events, alloc_outputs, alloc_search, distsim_build_events, distsim_search, distsim_simulate,
+    alloc_events, alloc_outputs, alloc_search, distsim_build_events, distsim_search, distsim_simulate, distsim_timeline,
     load_library, stage_entries, stage_rows, upload,
 )

@@ -19,13 +19,13 @@ LIB_PATH = os.path.join(_HERE, "libdistsim_hip.so")
 EXPORTS = (
     "distsim_create", "distsim_destroy", "distsim_last_error", "distsim_workspace_bytes", "distsim_stage_entries",
     "distsim_build_events", "distsim_simulate", "distsim_search_scratch_bytes", "distsim_search",
-    "distsim_timing_enable", "distsim_timing_read", "distsim_kernel_name",
+    "distsim_timeline", "distsim_timing_enable", "distsim_timing_read", "distsim_kernel_name",
 )
 
 NCOLS = 8
 COL = {"FC": 0, "FA": 1, "BC": 2, "BA": 3, "PF": 4, "PB": 5, "G": 6, "AR": 7}
 KERNELS = ("k_layer_tables", "k_decode", "k_bins", "k_scatter", "k_stage_events",
-           "k_sim_init", "k_simulate", "k_search")
+           "k_sim_init", "k_simulate", "k_search", "k_timeline")
 INT64_MAX = (1 << 63) - 1
 
 
@@ -88,6 +88,8 @@ def load_library():
     lib.distsim_search.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int, C.c_void_p,
                                    C.c_void_p, C.c_void_p]
     lib.distsim_search.restype = C.c_int
+    lib.distsim_timeline.argtypes = [C.c_void_p, C.POINTER(_Cluster), C.POINTER(_Events), C.c_int64] + [C.c_void_p] * 7
+    lib.distsim_timeline.restype = C.c_int
     lib.distsim_timing_enable.argtypes = [C.c_void_p, C.c_int]
     lib.distsim_timing_enable.restype = C.c_int
     lib.distsim_timing_read.argtypes = [C.c_void_p, C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
@@ -289,3 +291,11 @@ def distsim_search(ctx: Context, batch_ns: torch.Tensor, Cn: int, best: torch.Te
                    weight: Optional[torch.Tensor] = None, objective: int = 0) -> None:
     ctx.check(ctx.lib.distsim_search(ctx.h, _ptr(batch_ns), _ptr(weight), Cn, objective, _ptr(best), _ptr(scratch),
                                      _stream()))
+
+
+def distsim_timeline(ctx: Context, cluster, ev: Events, sel: torch.Tensor, task_off: torch.Tensor,
+                     start_ns: torch.Tensor, end_ns: torch.Tensor, ar_start_ns: torch.Tensor,
+                     ar_end_ns: torch.Tensor) -> None:
+    cl = cluster_struct(cluster)
+    ctx.check(ctx.lib.distsim_timeline(ctx.h, C.byref(cl), C.byref(ev.struct), sel.numel(), _ptr(sel), _ptr(task_off),
+                                       _ptr(start_ns), _ptr(end_ns), _ptr(ar_start_ns), _ptr(ar_end_ns), _stream()))

@@ -10,6 +10,7 @@
 #include "kernels_build.hpp"
 #include "kernels_search.hpp"
 #include "kernels_simulate.hpp"
+#include "kernels_timeline.hpp"
 
 using namespace distsim;
 
@@ -28,7 +29,7 @@ struct distsim_ctx {
 
 static const char* kKernelNames[DISTSIM_K_COUNT] = {
     "k_layer_tables", "k_decode", "k_bins", "k_scatter",
-    "k_stage_events", "k_sim_init", "k_simulate", "k_search",
+    "k_stage_events", "k_sim_init", "k_simulate", "k_search", "k_timeline",
 };
 
 static int fail(distsim_ctx* ctx, int code, const std::string& msg) {
@@ -65,6 +66,8 @@ struct Timer {
     }
 };
 
+ClusterDev to_dev(const distsim_cluster& c);
+ClusterDev cl_dev(const distsim_cluster& c) { return to_dev(c); }
 ClusterDev to_dev(const distsim_cluster& c) {
     ClusterDev d;
     d.num_devices = c.num_devices;
@@ -224,6 +227,40 @@ int distsim_simulate(distsim_ctx* ctx, const distsim_cluster* cluster, const dis
     {
         Timer t(ctx, st, DISTSIM_K_SIMULATE);
         hipLaunchKernelGGL(k_simulate, dim3(item_grid(ctx, C)), dim3(256), 0, st, co, cl, ca, ws, ev, out);
+    }
+    HIP_TRY(hipGetLastError());
+    return DISTSIM_OK;
+}
+
+int distsim_timeline(distsim_ctx* ctx, const distsim_cluster* cluster, const distsim_events* events, int64_t n,
+                     const int64_t* sel, const int64_t* task_off, int64_t* start_ns, int64_t* end_ns,
+                     int64_t* ar_start_ns, int64_t* ar_end_ns, void* hip_stream) {
+    if (!ctx) return DISTSIM_EINVAL;
+    if (!cluster || !events) return fail(ctx, DISTSIM_EINVAL, "null argument");
+    if (!cluster_ok(cluster)) return fail(ctx, DISTSIM_EINVAL, "cluster description out of range");
+    if (n < 0 || n > 0x7fffffff) return fail(ctx, DISTSIM_ERANGE, "selection size outside [0, 2^31)");
+    if (n == 0) return DISTSIM_OK;
+    if (!sel || !task_off || !start_ns || !end_ns || !ar_start_ns || !ar_end_ns || !events->status ||
+        !events->workspace)
+        return fail(ctx, DISTSIM_EINVAL, "null array");
+    const distsim_costs* cs = &events->costs;
+    const distsim_candidates* cd = &events->cand;
+    if (!cs->variant_tp || !cs->act_bytes || cs->L != events->L || cs->V != events->V || events->L < 1 ||
+        events->L > DISTSIM_MAX_L || events->V < 1 || events->V > DISTSIM_MAX_V)
+        return fail(ctx, DISTSIM_EINVAL, "events were not produced by distsim_build_events");
+    Workspace ws;
+    (void)carve(ws, events->workspace, events->L, events->V, 0);     // table addresses do not depend on C
+    HIP_TRY(hipSetDevice(ctx->device));
+    hipStream_t st = (hipStream_t)hip_stream;
+    CostsDev co{cs->L, cs->V, cs->variant_tp, cs->fwd_comp_ns, cs->bwd_comp_ns, cs->fwd_comm_ns, cs->bwd_comm_ns,
+                cs->act_bytes, cs->grad_bytes, cs->a2a_bytes};
+    CandDev ca{cd->dp, cd->tp, cd->pp, cd->m, cd->schedule, cd->part_off, cd->part_pool,
+               cd->part_pool ? cd->part_pool_len : 0};
+    TimelineOut out{sel, task_off, start_ns, end_ns, ar_start_ns, ar_end_ns};
+    {
+        Timer t(ctx, st, DISTSIM_K_TIMELINE);
+        hipLaunchKernelGGL(k_timeline, dim3((unsigned)n), dim3(kWave), 0, st, co, cl_dev(*cluster), ca, ws,
+                           events->status, n, out);
     }
     HIP_TRY(hipGetLastError());
     return DISTSIM_OK;

@@ -114,6 +114,58 @@ def test_blocking_p2p(H, oracle_mod):
     H.assert_same(H.run_hip(wb, table=False), oracle_mod.simulate(wb, nthreads=NT), what=wb.name)
 
 
+def _timeline_parity(H, oracle_mod, w, idx):
+    import torch
+    import paper_2306_08423_amd as ds
+    c = H.ctx()
+    dw = ds.upload(w, c.device)
+    ev = ds.alloc_events(c, dw.L, dw.V, dw.C, ds.stage_entries(w.cand["pp"]), table=False)
+    ds.distsim_build_events(c, dw, ev)
+    out = ds.alloc_outputs(c, ev)
+    ds.distsim_simulate(c, dw.cluster, ev, out)
+    idx = np.asarray(idx, np.int64)
+    sizes = 2 * w.cand["pp"][idx].astype(np.int64) * w.cand["m"][idx]
+    off = np.concatenate([[0], np.cumsum(sizes)])
+    dev = c.device
+    start = torch.full((int(off[-1]),), -7, dtype=torch.int64, device=dev)
+    end = torch.full((int(off[-1]),), -7, dtype=torch.int64, device=dev)
+    ar0 = torch.full((len(idx), 64), -7, dtype=torch.int64, device=dev)
+    ar1 = torch.full((len(idx), 64), -7, dtype=torch.int64, device=dev)
+    ds.distsim_timeline(c, dw.cluster, ev, torch.from_numpy(idx).to(dev), torch.from_numpy(off[:-1].copy()).to(dev),
+                        start, end, ar0, ar1)
+    torch.cuda.synchronize()
+    start, end, ar0, ar1 = (t.cpu().numpy() for t in (start, end, ar0, ar1))
+    batch = out.batch_ns.cpu().numpy()
+    for k, i in enumerate(idx):
+        r = oracle_mod.simulate(subset(w, [i]), timeline=True)
+        pp, m = int(w.cand["pp"][i]), int(w.cand["m"][i])
+        if r["status"][0] != 0:
+            assert (start[off[k]:off[k + 1]] == -7).all() and (ar0[k] == -1).all()
+            continue
+        assert np.array_equal(start[off[k]:off[k + 1]].reshape(2, pp, m), r["start"]), (i, "start")
+        assert np.array_equal(end[off[k]:off[k + 1]].reshape(2, pp, m), r["end"]), (i, "end")
+        assert np.array_equal(ar0[k, :pp], r["ar_window"][0]) and np.array_equal(ar1[k, :pp], r["ar_window"][1]), i
+        assert (ar0[k, pp:] == -1).all() and (ar1[k, pp:] == -1).all()
+        # the timeline ends where the simulation says the batch ends
+        assert max(int(end[off[k]:off[k + 1]].max()), int(ar1[k].max())) == batch[i] == r["batch_ns"][0]
+
+
+def test_timeline_dump(H, oracle_mod):
+    _say("[case] timeline")
+    w = make_workload("gpt24")
+    _timeline_parity(H, oracle_mod, w, np.arange(0, w.C, 3))
+    cl = dict(w.cluster); cl["p2p_blocking"] = 1
+    _timeline_parity(H, oracle_mod, Workload("gpt24+blocking", w.costs, cl, w.cand), np.arange(1, w.C, 7))
+    rng = np.random.default_rng(31)
+    w = make_workload("gpt96")                                  # bucketed all-reduce windows
+    _timeline_parity(H, oracle_mod, w, np.sort(rng.choice(w.C, 60, replace=False)))
+    w = make_workload("hetero64", C=20000)
+    _timeline_parity(H, oracle_mod, w, np.sort(rng.choice(w.C, 150, replace=False)))
+    costs = mk_costs([10] * 4, [20] * 4)
+    w = mk(costs, mk_cluster(2), [(1, 1, 2, 4, 1, None), (1, 1, 2, 4, 1, [0, 0, 4]), (2, 1, 2, 4, 1, None)])
+    _timeline_parity(H, oracle_mod, w, [0, 1, 2])
+
+
 def test_runs_are_deterministic(H):
     _say("[case] determinism")
     w = make_workload("gpt48")

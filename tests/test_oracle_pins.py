@@ -139,12 +139,13 @@ def test_golden_bucketed_allreduce(oracle_mod):
             line = line.strip()
             if not line or line.startswith("#"):
                 continue
-            name, dp, g0, g1, g2, batch, comm, nar = line.split()
+            name, dp, g0, g1, g2, batch, comm, nar, ar0, ar1 = line.split()
             dp = int(dp)
             costs = mk_costs([10, 10, 10], [50, 300, 500], grad=[int(g0), int(g1), int(g2)])
             cl = mk_cluster(dp, g=8, alpha=(100, 100), beta=(10, 10), bucket=1000)
-            r = one(oracle_mod, costs, cl, (dp, 1, 1, 1, 0, None))
+            r = one(oracle_mod, costs, cl, (dp, 1, 1, 1, 0, None), timeline=True)
             assert r["batch_ns"][0] == int(batch), name
+            assert list(r["ar_window"][:, 0]) == [int(ar0), int(ar1)], name
             assert r["comm_busy_ns"][0] == int(comm), name
             assert r["num_events"][0] == 2 + int(nar), name
             assert r["comp_busy_ns"][0] == 880
@@ -504,6 +505,10 @@ def test_dp_changes_only_the_tail(oracle_mod):
             cl = mk_cluster(dp * 4, g=1 << 20, alpha=(50, 50), beta=(200, 200))
             r = one(oracle_mod, costs, cl, (dp, 1, 4, 5, sched, None), timeline=True)
             ends[dp] = (r["end"].copy(), int(r["batch_ns"][0]), r["comm_busy_ns"].copy())
+            if dp > 1:      # the single trailing all-reduce starts when the device's last backward ends
+                assert np.array_equal(r["ar_window"][0], r["end"][1, :, 4])
+            else:
+                assert (r["ar_window"] == -1).all()
         assert np.array_equal(ends[1][0], ends[2][0]) and np.array_equal(ends[1][0], ends[8][0])
         G = [int(costs["grad_bytes"][0, 2 * s:2 * s + 2].sum()) for s in range(4)]
         for dp in (2, 8):
