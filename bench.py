@@ -59,6 +59,8 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--stage-table", dest="no_stage_table", action="store_false",
                     help="also write the optional per-stage event table during event generation")
+    ap.add_argument("--timeline", type=int, default=20000,
+                    help="also dump the stage-task timelines of this many seeded candidates (0 = skip)")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one 1 GiB device-to-device copy (known traffic, for scaling HBM counters)")
     args = ap.parse_args()
@@ -100,6 +102,34 @@ def main() -> int:
     dt = time.perf_counter() - t0
     kt = ctx.timing_read()
     ctx.timing_enable(False)
+
+    timeline = None
+    if args.timeline > 0:
+        nsel = min(args.timeline, dw.C)
+        sel = np.sort(np.random.default_rng(7).choice(dw.C, nsel, replace=False)).astype(np.int64)
+        sizes = 2 * w.cand["pp"][sel].astype(np.int64) * w.cand["m"][sel]
+        off = np.concatenate([[0], np.cumsum(sizes)])
+        d_sel = torch.from_numpy(sel).to(ctx.device)
+        d_off = torch.from_numpy(off[:-1].copy()).to(ctx.device)
+        t_start = torch.empty(int(off[-1]), dtype=torch.int64, device=ctx.device)
+        t_end = torch.empty_like(t_start)
+        ar0 = torch.empty((nsel, 64), dtype=torch.int64, device=ctx.device)
+        ar1 = torch.empty_like(ar0)
+        ds.distsim_timeline(ctx, dw.cluster, ev, d_sel, d_off, t_start, t_end, ar0, ar1)      # warm-up
+        torch.cuda.synchronize()
+        ctx.timing_enable(True)
+        for _ in range(5):
+            ds.distsim_timeline(ctx, dw.cluster, ev, d_sel, d_off, t_start, t_end, ar0, ar1)
+        torch.cuda.synchronize()
+        tl_ms, tl_n = ctx.timing_read()["k_timeline"]
+        ctx.timing_enable(False)
+        tl_s = tl_ms / max(tl_n, 1) / 1e3
+        tl_bytes = int(off[-1]) * 16 + nsel * 64 * 16
+        timeline = {"candidates": int(nsel), "stage_tasks": int(off[-1]), "ms": tl_s * 1e3,
+                    "stage_tasks_per_s": int(off[-1]) / tl_s, "bound": "hbm",
+                    "achieved": tl_bytes / tl_s / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                    "frac": tl_bytes / tl_s / 1e9 / HBM_PEAK_GBS}
+        del t_start, t_end, ar0, ar1
 
     if args.calib_copy:
         src = torch.empty(1 << 30, dtype=torch.uint8, device=ctx.device)
@@ -162,7 +192,7 @@ def main() -> int:
         "events_per_s": nev * args.steps / dt, "stage_tasks_per_s": tasks * args.steps / dt,
         "kernel_ms": {k: (v[0] / max(v[1], 1)) * (v[1] / args.steps) for k, v in kt.items()},
         "roofline": roofline, "roofline_hbm": roofline_hbm,
-        "cpu_baseline": cpu_baseline, "parity": parity,
+        "timeline": timeline, "cpu_baseline": cpu_baseline, "parity": parity,
     }
     print(json.dumps(line))
     return 0

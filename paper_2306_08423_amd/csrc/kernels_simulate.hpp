@@ -120,6 +120,11 @@ __global__ __launch_bounds__(256, 8) void k_simulate(CostsDev co, ClusterDev cl,
     if (W * kWave > ev.stage_cap) W = ev.stage_cap / kWave;
     const int L = co.L;
     const double ninf = -__builtin_huge_val();
+    // What only the epilogue needs is parked in LDS during the sweep (each lane its own slot),
+    // so that the sweep runs in few enough registers for eight wavefronts per SIMD.
+    __shared__ int64_t park_comp[256], park_comm[256], park_ar[256];
+    __shared__ int32_t park_cand[256], park_dp[256], park_misc[256];
+    const int slot = threadIdx.x;
 
     for (int64_t w = wave0; w < W; w += nwaves) {
         const Item it = decode_item(ws.hdr, w);
@@ -161,6 +166,9 @@ __global__ __launch_bounds__(256, 8) void k_simulate(CostsDev co, ClusterDev cl,
         }
         if (!(act && s > 0)) pfL = ninf;
         if (!(act && s + 1 < pp)) pbR = ninf;
+        park_comp[slot] = comp1; park_comm[slot] = comm1; park_ar[slot] = AR;
+        park_cand[slot] = (int32_t)c; park_dp[slot] = dp;
+        park_misc[slot] = lo | (hi << 8) | ((int)has_ar << 16) | (v << 17);
 
         // level windows of this lane, expressed on x = level - s:
         //   forward  x in [0, f1hi]  and  even x in [f2lo, f2hi]
@@ -262,8 +270,12 @@ __global__ __launch_bounds__(256, 8) void k_simulate(CostsDev co, ClusterDev cl,
 
         // data-parallel modelling: gradient all-reduce after (or overlapped with) the last backward
         const int64_t endB = (int64_t)own;
-        int64_t finish = endB + AR, ar_busy = AR, nar = has_ar ? 1 : 0;
-        if (has_ar && cl.bucket > 0) {
+        const int64_t AR_ = park_ar[slot];
+        const int misc = park_misc[slot];
+        const bool has_ar_ = (misc >> 16) & 1;
+        int64_t finish = endB + AR_, ar_busy = AR_, nar = has_ar_ ? 1 : 0;
+        if (has_ar_ && cl.bucket > 0) {
+            const int lo = misc & 0xff, hi = (misc >> 8) & 0xff, v = misc >> 17, dp = park_dp[slot];
             const size_t vr = (size_t)v * (L + 1), rr = (size_t)(v * kMaxPP + pp - 1) * (L + 1);
             const int64_t startB = endB - (int64_t)Bd;
             const int64_t tot_hi = ws.pbc[vr + hi] + ws.pba[rr + hi];
@@ -292,14 +304,15 @@ __global__ __launch_bounds__(256, 8) void k_simulate(CostsDev co, ClusterDev cl,
         nar = group_sum(nar, width);
         const int64_t batch = group_max(act ? finish : 0, width);
         // lanes outside a candidate have m = 0 and zero rows: they store zeros
-        const int64_t comp = (int64_t)m * comp1;
-        const int64_t comm = act ? (int64_t)m * comm1 + ar_busy : 0;
+        const int64_t comp = (int64_t)m * park_comp[slot];
+        const int64_t comm = act ? (int64_t)m * park_comm[slot] + ar_busy : 0;
         out.comp_busy[i] = comp;
         out.comm_busy[i] = comm;
         if (out.util) out.util[i] = batch > 0 ? (double)comp / (double)batch : 0.0;
         if (act && s == 0) {
-            out.batch_ns[c] = batch;
-            ev.num_events[c] = 2ll * m * pp + 2ll * m * (pp - 1) + nar;
+            const int64_t cc = park_cand[slot];
+            out.batch_ns[cc] = batch;
+            ev.num_events[cc] = 2ll * m * pp + 2ll * m * (pp - 1) + nar;
         }
     }
 }
