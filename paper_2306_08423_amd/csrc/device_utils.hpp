@@ -29,26 +29,70 @@ __device__ __forceinline__ double from_next_lane(double x) {
 
 __device__ __forceinline__ int lane_id() { return threadIdx.x & (kWave - 1); }
 
-// max / sum over aligned groups of `width` lanes (width a power of two <= 64); every lane of
-// the group gets the result.
-__device__ __forceinline__ int64_t group_max(int64_t v, int width) {
-    for (int d = 1; d < width; d <<= 1) {
-        int64_t o = __shfl_xor(v, d, kWave);
-        v = o > v ? o : v;
+// DPP controls that pair every lane with the lane holding the other half of a 2-, 4-, 8- and
+// 16-lane block: two quad permutations, then the mirrored half-row and the mirrored row.
+constexpr int kDppXor1 = 0xB1;          // quad_perm [1,0,3,2]
+constexpr int kDppXor2 = 0x4E;          // quad_perm [2,3,0,1]
+constexpr int kDppHalfMirror = 0x141;   // row_half_mirror
+constexpr int kDppMirror = 0x140;       // row_mirror
+
+template <int CTRL>
+__device__ __forceinline__ int dpp_i32(int v) { return __builtin_amdgcn_update_dpp(0, v, CTRL, 0xf, 0xf, true); }
+template <int CTRL>
+__device__ __forceinline__ int64_t dpp_i64(int64_t v) {
+    const int lo = dpp_i32<CTRL>((int)(uint32_t)v), hi = dpp_i32<CTRL>((int)(uint32_t)((uint64_t)v >> 32));
+    return (int64_t)(((uint64_t)(uint32_t)hi << 32) | (uint32_t)lo);
+}
+__device__ __forceinline__ int64_t readlane_i64(int64_t v, int l) {
+    const int lo = __builtin_amdgcn_readlane((int)(uint32_t)v, l);
+    const int hi = __builtin_amdgcn_readlane((int)(uint32_t)((uint64_t)v >> 32), l);
+    return (int64_t)(((uint64_t)(uint32_t)hi << 32) | (uint32_t)lo);
+}
+
+// Reduction over aligned groups of `width` lanes (a wave-uniform power of two <= 64); every lane
+// of the group gets the result.  DPP inside a row of 16 lanes, scalar row totals above.
+template <typename Op>
+__device__ __forceinline__ int64_t group_reduce(int64_t v, int width, Op op) {
+    if (width >= 2) v = op(v, dpp_i64<kDppXor1>(v));
+    if (width >= 4) v = op(v, dpp_i64<kDppXor2>(v));
+    if (width >= 8) v = op(v, dpp_i64<kDppHalfMirror>(v));
+    if (width >= 16) v = op(v, dpp_i64<kDppMirror>(v));
+    if (width >= 32) {
+        const int64_t a = op(readlane_i64(v, 0), readlane_i64(v, 16));
+        const int64_t b = op(readlane_i64(v, 32), readlane_i64(v, 48));
+        v = width == 64 ? op(a, b) : ((threadIdx.x & 32) ? b : a);
     }
     return v;
+}
+__device__ __forceinline__ int64_t group_max(int64_t v, int width) {
+    return group_reduce(v, width, [](int64_t x, int64_t y) { return x > y ? x : y; });
 }
 __device__ __forceinline__ int64_t group_sum(int64_t v, int width) {
-    for (int d = 1; d < width; d <<= 1)
-        v += __shfl_xor(v, d, kWave);
-    return v;
+    return group_reduce(v, width, [](int64_t x, int64_t y) { return x + y; });
 }
+// true in every lane of a group in which some lane has `b` set
+__device__ __forceinline__ bool group_any(bool b, int width) {
+    const uint64_t m = __builtin_amdgcn_ballot_w64(b);
+    if (width == 64) return m != 0;
+    const int base = (threadIdx.x & 63) & ~(width - 1);
+    return ((m >> base) & ((1ull << width) - 1)) != 0;
+}
+// number of lanes of the group that have `b` set
+__device__ __forceinline__ int group_count(bool b, int width) {
+    const uint64_t m = __builtin_amdgcn_ballot_w64(b);
+    if (width == 64) return __popcll(m);
+    const int base = (threadIdx.x & 63) & ~(width - 1);
+    return __popcll((m >> base) & ((1ull << width) - 1));
+}
+// max over the wavefront, wave-uniform
 __device__ __forceinline__ int wave_max_i32(int v) {
-    for (int d = 1; d < kWave; d <<= 1) {
-        int o = __shfl_xor(v, d, kWave);
-        v = o > v ? o : v;
-    }
-    return v;
+    auto mx = [](int x, int y) { return x > y ? x : y; };
+    v = mx(v, dpp_i32<kDppXor1>(v));
+    v = mx(v, dpp_i32<kDppXor2>(v));
+    v = mx(v, dpp_i32<kDppHalfMirror>(v));
+    v = mx(v, dpp_i32<kDppMirror>(v));
+    return mx(mx(__builtin_amdgcn_readlane(v, 0), __builtin_amdgcn_readlane(v, 16)),
+              mx(__builtin_amdgcn_readlane(v, 32), __builtin_amdgcn_readlane(v, 48)));
 }
 
 // Inclusive prefix sum over the 64 lanes of a wavefront.

@@ -261,15 +261,16 @@ __device__ __forceinline__ int stage_row(const ClusterDev& cl, const Workspace& 
     const bool act = s < pp;
     r = StageRow{0, 0, 0, 0, 0, 0, 0};
     int bad = 0;
-    int64_t node = 0;           // node of the stage's first rank (ranks ordered tp fastest, then dp, then pp)
+    int node = 0;               // node of the stage's first rank (ranks ordered tp fastest, then dp, then pp)
     if (act) {
         bad = (hi <= lo) || (hi > L) || (s == 0 && lo != 0) || (s == pp - 1 && hi != L);
         // a stage of at least a node's worth of ranks starts on a node of its own
         const int64_t tpdp = (int64_t)tp * dp;
-        node = tpdp >= cl.gpus_per_node ? s : (int64_t)udiv64((uint64_t)s * (uint64_t)tpdp, (uint64_t)cl.gpus_per_node);
+        node = tpdp >= cl.gpus_per_node ? s : (int)udiv64((uint64_t)s * (uint64_t)tpdp, (uint64_t)cl.gpus_per_node);
     }
-    bad = (int)group_sum(bad, width);
-    const int64_t node_next = __shfl_down(node, 1, kWave), node_prev = __shfl_up(node, 1, kWave);
+    bad = group_any(bad != 0, width) ? 1 : 0;
+    const int node_next = __builtin_amdgcn_update_dpp(0, node, kDppWaveShl1, 0xf, 0xf, true);
+    const int node_prev = __builtin_amdgcn_update_dpp(0, node, kDppWaveShr1, 0xf, 0xf, true);
     if (act && !bad) {
         const size_t vr = (size_t)v * (L + 1), rr = (size_t)(v * kMaxPP + pp - 1) * (L + 1);
         r.FC = ws.pfc[vr + hi] - ws.pfc[vr + lo];

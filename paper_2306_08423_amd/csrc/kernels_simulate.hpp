@@ -80,204 +80,261 @@ __device__ __forceinline__ double from_lanes(double x, int byte_addr) {
 // One level for the lanes whose pattern bit is set: own = max(own, nb + lat) + dur.
 // Requires EXEC == all ones on entry (wave-uniform control flow, full wavefronts) and leaves
 // it so.  The trailing s_nop keeps two wait states between the write of `own` and the DPP
-// read that follows.
-#define DISTSIM_STEP_ONE(bits, nb, lat, dur)                                   \
+// read that follows.  The *2 forms run the same level of two candidates' sweeps that share
+// one shape, hence one pattern and one EXEC mask.
+#define DISTSIM_STEP1(bits, o, t, lat, dur)                                    \
     asm volatile(                                                              \
         "v_add_co_u32_e64 %[p], %[k], %[p], %[p]\n\t"                        \
         "s_mov_b64 exec, %[k]\n\t"                                            \
-        "v_add_f64 %[t], %[t], %[c]\n\t"                                      \
-        "v_max_f64 %[t], %[t], %[o]\n\t"                                      \
-        "v_add_f64 %[o], %[t], %[d]\n\t"                                      \
+        "v_add_f64 %[t0], %[t0], %[c0]\n\t"                                   \
+        "v_max_f64 %[t0], %[t0], %[o0]\n\t"                                   \
+        "v_add_f64 %[o0], %[t0], %[d0]\n\t"                                   \
         "s_mov_b64 exec, -1\n\t"                                              \
         "s_nop 0"                                                              \
-        : [o] "+v"(own), [t] "+v"(nb), [p] "+v"(bits), [k] "=&s"(kmask)       \
-        : [c] "v"(lat), [d] "v"(dur))
+        : [o0] "+v"(o), [t0] "+v"(t), [p] "+v"(bits), [k] "=&s"(kmask)        \
+        : [c0] "v"(lat), [d0] "v"(dur))
 
-#define DISTSIM_STEP_BOTH()                                                    \
+#define DISTSIM_STEP2(bits, oa, ta, lata, dura, ob, tb, latb, durb)            \
     asm volatile(                                                              \
-        "v_add_co_u32_e64 %[pf], %[kf], %[pf], %[pf]\n\t"                    \
-        "v_add_co_u32_e64 %[pb], %[kb], %[pb], %[pb]\n\t"                    \
-        "s_mov_b64 exec, %[kf]\n\t"                                           \
-        "v_add_f64 %[tl], %[tl], %[cl]\n\t"                                   \
-        "v_max_f64 %[tl], %[tl], %[o]\n\t"                                    \
-        "v_add_f64 %[o], %[tl], %[df]\n\t"                                    \
-        "s_mov_b64 exec, %[kb]\n\t"                                           \
-        "v_add_f64 %[tr], %[tr], %[cr]\n\t"                                   \
-        "v_max_f64 %[tr], %[tr], %[o]\n\t"                                    \
-        "v_add_f64 %[o], %[tr], %[db]\n\t"                                    \
+        "v_add_co_u32_e64 %[p], %[k], %[p], %[p]\n\t"                        \
+        "s_mov_b64 exec, %[k]\n\t"                                            \
+        "v_add_f64 %[t0], %[t0], %[c0]\n\t"                                   \
+        "v_add_f64 %[t1], %[t1], %[c1]\n\t"                                   \
+        "v_max_f64 %[t0], %[t0], %[o0]\n\t"                                   \
+        "v_max_f64 %[t1], %[t1], %[o1]\n\t"                                   \
+        "v_add_f64 %[o0], %[t0], %[d0]\n\t"                                   \
+        "v_add_f64 %[o1], %[t1], %[d1]\n\t"                                   \
         "s_mov_b64 exec, -1\n\t"                                              \
         "s_nop 0"                                                              \
-        : [o] "+v"(own), [tl] "+v"(fromL), [tr] "+v"(fromR), [pf] "+v"(PFb), [pb] "+v"(PBb),  \
+        : [o0] "+v"(oa), [t0] "+v"(ta), [o1] "+v"(ob), [t1] "+v"(tb), [p] "+v"(bits), [k] "=&s"(kmask) \
+        : [c0] "v"(lata), [d0] "v"(dura), [c1] "v"(latb), [d1] "v"(durb))
+
+// A level with forward lanes (operand from the previous lane) and backward lanes (operand from
+// the next lane) in no particular arrangement: two masks, two task steps.
+#define DISTSIM_STEPFB1(pf, pb, o, tl, tr, cl_, cr_, df, db)                   \
+    asm volatile(                                                              \
+        "v_add_co_u32_e64 %[pf_], %[kf], %[pf_], %[pf_]\n\t"                 \
+        "v_add_co_u32_e64 %[pb_], %[kb], %[pb_], %[pb_]\n\t"                 \
+        "s_mov_b64 exec, %[kf]\n\t"                                           \
+        "v_add_f64 %[tl_], %[tl_], %[cl__]\n\t"                               \
+        "v_max_f64 %[tl_], %[tl_], %[o_]\n\t"                                 \
+        "v_add_f64 %[o_], %[tl_], %[df_]\n\t"                                 \
+        "s_mov_b64 exec, %[kb]\n\t"                                           \
+        "v_add_f64 %[tr_], %[tr_], %[cr__]\n\t"                               \
+        "v_max_f64 %[tr_], %[tr_], %[o_]\n\t"                                 \
+        "v_add_f64 %[o_], %[tr_], %[db_]\n\t"                                 \
+        "s_mov_b64 exec, -1\n\t"                                              \
+        "s_nop 0"                                                              \
+        : [o_] "+v"(o), [tl_] "+v"(tl), [tr_] "+v"(tr), [pf_] "+v"(pf), [pb_] "+v"(pb),   \
           [kf] "=&s"(kmask), [kb] "=&s"(kmask2)                               \
-        : [cl] "v"(pfL), [cr] "v"(pbR), [df] "v"(Fd), [db] "v"(Bd))
+        : [cl__] "v"(cl_), [cr__] "v"(cr_), [df_] "v"(df), [db_] "v"(db))
 
-__global__ __launch_bounds__(256, 8) void k_simulate(CostsDev co, ClusterDev cl, CandDev ca,
-                                                                    Workspace ws, EventsDev ev, SimOut out) {
-    const int lane = lane_id();
-    const int64_t wave0 = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / kWave;
-    const int64_t nwaves = ((int64_t)gridDim.x * blockDim.x) / kWave;
-    int64_t W = ws.hdr[H_NUM_ITEMS];
-    if (W * kWave > ev.stage_cap) W = ev.stage_cap / kWave;
-    const int L = co.L;
+// The same with masks that have already been taken from the patterns.
+#define DISTSIM_APPLYFB(o, tl, tr, cl_, cr_, df, db)                           \
+    asm volatile(                                                              \
+        "s_mov_b64 exec, %[kf]\n\t"                                           \
+        "v_add_f64 %[tl_], %[tl_], %[cl__]\n\t"                               \
+        "v_max_f64 %[tl_], %[tl_], %[o_]\n\t"                                 \
+        "v_add_f64 %[o_], %[tl_], %[df_]\n\t"                                 \
+        "s_mov_b64 exec, %[kb]\n\t"                                           \
+        "v_add_f64 %[tr_], %[tr_], %[cr__]\n\t"                               \
+        "v_max_f64 %[tr_], %[tr_], %[o_]\n\t"                                 \
+        "v_add_f64 %[o_], %[tr_], %[db_]\n\t"                                 \
+        "s_mov_b64 exec, -1\n\t"                                              \
+        "s_nop 0"                                                              \
+        : [o_] "+v"(o), [tl_] "+v"(tl), [tr_] "+v"(tr)                        \
+        : [kf] "s"(kmask), [kb] "s"(kmask2), [cl__] "v"(cl_), [cr__] "v"(cr_), [df_] "v"(df), [db_] "v"(db))
+
+// Per-lane state of one candidate's sweep.
+struct Sweep {
+    double own;            // end of the most recent task on this device
+    double pfL, pbR;       // p2p latency on the incoming forward / backward edge, -inf = no edge
+    double Fd, Bd;         // duration of a forward / backward stage-task
+};
+
+constexpr int kSimBlock = 256;
+
+// Simulates U wave-items at once.  For U = 2 the two items must have the same shape in every
+// lane (pp, m, schedule): then they share patterns, masks and control flow.
+template <int U>
+__device__ __forceinline__ void simulate_items(const ClusterDev& cl, const CandDev& ca, const Workspace& ws,
+                                               const EventsDev& ev, const SimOut& out, int L, int64_t w0,
+                                               int sh, const Desc (&d)[U], int lane,
+                                               int64_t (*park_comp)[kSimBlock], int64_t (*park_comm)[kSimBlock],
+                                               int64_t (*park_ar)[kSimBlock], int32_t (*park_cand)[kSimBlock],
+                                               int32_t (*park_dp)[kSimBlock], int32_t (*park_misc)[kSimBlock]) {
     const double ninf = -__builtin_huge_val();
-    // What only the epilogue needs is parked in LDS during the sweep (each lane its own slot),
-    // so that the sweep runs in few enough registers for eight wavefronts per SIMD.
-    __shared__ int64_t park_comp[256], park_comm[256], park_ar[256];
-    __shared__ int32_t park_cand[256], park_dp[256], park_misc[256];
     const int slot = threadIdx.x;
+    const int width = 1 << sh;
+    const int s = lane & (width - 1);
+    // shape (shared by the U items)
+    const int pp = d[0].meta & 0xff, sched = (d[0].meta >> 8) & 0xff;
+    const bool act = s < pp;
+    const int m = act ? d[0].m : 0;
 
-    for (int64_t w = wave0; w < W; w += nwaves) {
-        const Item it = decode_item(ws.hdr, w);
-        const int width = 1 << it.sh;
-        const int s = lane & (width - 1);
-        const int64_t pos = it.pos0 + (lane >> it.sh);
-        Desc d{};
-        if (pos < it.class_end) d = ws.desc[pos];
-        int pp = d.meta & 0xff;
-        const int sched = (d.meta >> 8) & 0xff, v = d.meta >> 16, dp = d.meta ? d.dp : 1;
-        const int64_t c = d.cand;
+    Sweep sw[U];
+#pragma unroll
+    for (int u = 0; u < U; u++) {
+        const int v = d[u].meta >> 16, dp = d[u].meta ? d[u].dp : 1;
+        const int64_t c = d[u].cand;
         // the stage's composed events, regenerated from the layer-event tables
         int lo = 0, hi = 0;
-        if (s < pp) {
-            if (d.poff >= 0) { lo = ca.part_pool[d.poff + s]; hi = ca.part_pool[d.poff + s + 1]; }
+        if (act) {
+            if (d[u].poff >= 0) { lo = ca.part_pool[d[u].poff + s]; hi = ca.part_pool[d[u].poff + s + 1]; }
             else { lo = (int)(((int64_t)s * L) / pp); hi = (int)(((int64_t)(s + 1) * L) / pp); }
         }
         StageRow r;
-        const int drop = stage_row(cl, ws, L, width, s, pp, v, d.m, dp, (int)d.spare, lo, hi, r);
-        if (drop) {
-            if (s == 0 && pp > 0) { ev.status[c] = drop; ev.num_events[c] = 0; out.batch_ns[c] = INT64_MAX; }
-            pp = 0;
-        }
-        const bool act = s < pp;
-        const int m = act ? d.m : 0;
-        const int64_t i = w * kWave + lane;
-        double Fd, Bd, pfL, pbR;
-        int64_t comp1, comm1, AR;            // per-micro-batch computation / communication, trailing all-reduce
-        bool has_ar;                         // the stage has gradient bytes to reduce over dp > 1 ranks
-        {
-            AR = cl.bucket > 0 ? 0 : allreduce_ns(cl, dp, r.G);
-            has_ar = act && dp > 1 && r.G > 0;
-            comp1 = r.FC + r.BC; comm1 = r.FA + r.BA + r.PF + r.PB;
-            // p2p on the incoming edges (the neighbours' outgoing events): latency of the edge, or,
-            // when the sender is occupied by it, part of the sender's task; -inf = no edge
-            const int64_t pf_task = cl.blocking ? r.PF : 0, pb_task = cl.blocking ? r.PB : 0;
-            Fd = (double)(r.FC + r.FA + pf_task); Bd = (double)(r.BC + r.BA + pb_task);
-            pfL = from_prev_lane((double)(r.PF - pf_task)); pbR = from_next_lane((double)(r.PB - pb_task));
-        }
-        if (!(act && s > 0)) pfL = ninf;
-        if (!(act && s + 1 < pp)) pbR = ninf;
-        park_comp[slot] = comp1; park_comm[slot] = comm1; park_ar[slot] = AR;
-        park_cand[slot] = (int32_t)c; park_dp[slot] = dp;
-        park_misc[slot] = lo | (hi << 8) | ((int)has_ar << 16) | (v << 17);
+        const int drop = stage_row(cl, ws, L, width, s, pp, v, d[u].m, dp, (int)d[u].spare, lo, hi, r);
+        if (drop && act && s == 0) { ev.status[c] = drop; ev.num_events[c] = 0; out.batch_ns[c] = INT64_MAX; }
+        const bool has_ar = act && dp > 1 && r.G > 0;       // gradient bytes to reduce over dp > 1 ranks
+        // p2p on the incoming edges (the neighbours' outgoing events): latency of the edge, or,
+        // when the sender is occupied by it, part of the sender's task; -inf = no edge
+        const int64_t pf_task = cl.blocking ? r.PF : 0, pb_task = cl.blocking ? r.PB : 0;
+        sw[u].own = 0.0;
+        sw[u].Fd = (double)(r.FC + r.FA + pf_task);
+        sw[u].Bd = (double)(r.BC + r.BA + pb_task);
+        sw[u].pfL = from_prev_lane((double)(r.PF - pf_task));
+        sw[u].pbR = from_next_lane((double)(r.PB - pb_task));
+        if (!(act && s > 0)) sw[u].pfL = ninf;
+        if (!(act && s + 1 < pp)) sw[u].pbR = ninf;
+        // what only the epilogue needs waits in LDS
+        park_comp[u][slot] = r.FC + r.BC;                                  // computation per micro-batch
+        park_comm[u][slot] = r.FA + r.BA + r.PF + r.PB;                    // communication per micro-batch
+        park_ar[u][slot] = cl.bucket > 0 ? 0 : allreduce_ns(cl, dp, r.G);  // single trailing all-reduce
+        park_cand[u][slot] = (int32_t)c;
+        park_dp[u][slot] = dp;
+        park_misc[u][slot] = lo | (hi << 8) | ((int)has_ar << 16) | ((drop ? 1 : 0) << 17) | (v << 18);
+    }
 
-        // level windows of this lane, expressed on x = level - s:
-        //   forward  x in [0, f1hi]  and  even x in [f2lo, f2hi]
-        //   backward x in [blo, bhi], every x (GPipe) or every second x (1F1B)
-        int f1hi, f2lo = 1, f2hi = 0, blo, bhi;
-        if (sched == 0) {
-            f1hi = m - 1;
-            blo = m + 2 * pp - 2 - 2 * s; bhi = blo + m - 1;
-        } else {
-            int wq = pp - 1 - s; if (wq > m) wq = m;
-            f1hi = wq < m - 1 ? wq : m - 1;
-            f2lo = 2 * wq + 2; f2hi = 2 * m - 2;
-            blo = 2 * pp - 1 - 2 * s; bhi = blo + 2 * m - 2;
-        }
-        const int nlev = __builtin_amdgcn_readfirstlane(wave_max_i32(act ? 2 * (m + pp - 1) : 0));
+    // level windows of this lane, expressed on x = level - s:
+    //   forward  x in [0, f1hi]  and  even x in [f2lo, f2hi]
+    //   backward x in [blo, bhi], every x (GPipe) or every second x (1F1B)
+    int f1hi, f2lo = 1, f2hi = 0, blo, bhi;
+    if (sched == 0) {
+        f1hi = m - 1;
+        blo = m + 2 * pp - 2 - 2 * s; bhi = blo + m - 1;
+    } else {
+        int wq = pp - 1 - s; if (wq > m) wq = m;
+        f1hi = wq < m - 1 ? wq : m - 1;
+        f2lo = 2 * wq + 2; f2hi = 2 * m - 2;
+        blo = 2 * pp - 1 - 2 * s; bhi = blo + 2 * m - 2;
+    }
+    const int nlev = wave_max_i32(act ? 2 * (m + pp - 1) : 0);
 
-        // 1F1B past its warm-up runs forwards on even x and backwards on odd x.  When every
-        // candidate of the wavefront is 1F1B with one pp, a level that has both kinds therefore
-        // splits the lanes by parity, and one merged operand (previous lane for the forward
-        // lanes, next lane for the backward lanes) feeds a single task step.
-        const int ppu = __builtin_amdgcn_readfirstlane(wave_max_i32(pp));
-        const bool par_ok = width >= 2 && __builtin_amdgcn_ballot_w64(act && (sched == 0 || pp != ppu)) == 0;
-        const bool even_s = (s & 1) == 0;
-        const double latE = even_s ? pfL : pbR, durE = even_s ? Fd : Bd;     // roles on even levels
-        const double latO = even_s ? pbR : pfL, durO = even_s ? Bd : Fd;     // roles on odd levels
-        const int adrE = (even_s ? lane - 1 : lane + 1) * 4;
+    // 1F1B past its warm-up runs forwards on even x and backwards on odd x.  When every
+    // candidate of the wavefront is 1F1B with one pp, a level that has both kinds therefore
+    // splits the lanes by parity, and one merged operand (previous lane for the forward
+    // lanes, next lane for the backward lanes) feeds a single task step.
+    const int ppu = wave_max_i32(pp);
+    const bool par_ok = width >= 2 && __builtin_amdgcn_ballot_w64(act && (sched == 0 || pp != ppu)) == 0;
+    const bool even_s = (s & 1) == 0;
+    const int adrE = (even_s ? lane - 1 : lane + 1) * 4;
 
-        double own = 0.0;
-        for (int l0 = 0; l0 < nlev; l0 += 32) {
-            const int x0 = l0 - s;
-            const uint32_t even_x = (x0 & 1) ? 0x55555555u : 0xaaaaaaaau;       // levels with even x
-            uint32_t PFb = level_bits(-x0, f1hi - x0) | (level_bits(f2lo - x0, f2hi - x0) & even_x);
-            uint32_t PBb = level_bits(blo - x0, bhi - x0);
-            if (sched != 0) PBb &= ((blo - x0) & 1) ? 0x55555555u : 0xaaaaaaaau;   // x - blo even
-            if (!act) { PFb = 0; PBb = 0; }
-            // chunk-relative level ranges in which any lane has a forward / a backward task
-            const uint32_t orF = wave_or_u32(PFb), orB = wave_or_u32(PBb);
-            if ((orF | orB) == 0) continue;
-            const int firstF = orF ? __builtin_clz(orF) : 64, lastF = orF ? 31 - __builtin_ctz(orF) : -1;
-            const int firstB = orB ? __builtin_clz(orB) : 64, lastB = orB ? 31 - __builtin_ctz(orB) : -1;
-            const int endk = (lastF > lastB ? lastF : lastB) + 1;
-            int k = firstF < firstB ? firstF : firstB;
-            PFb = shl32(PFb, k); PBb = shl32(PBb, k);            // skip the idle levels in front
-            uint64_t kmask, kmask2;
-            while (k < endk) {
-                const bool inF = k >= firstF && k <= lastF, inB = k >= firstB && k <= lastB;
-                int e = endk;                                     // next level at which the mix changes
-                if (firstF > k && firstF < e) e = firstF;
-                if (firstB > k && firstB < e) e = firstB;
-                if (lastF + 1 > k && lastF + 1 < e) e = lastF + 1;
-                if (lastB + 1 > k && lastB + 1 < e) e = lastB + 1;
-                const int len = e - k;
-                if (inF && inB) {
-                    if (par_ok) {
-                        uint32_t Pc = PFb | PBb;
-                        int j = 0;
-                        if (((l0 + k) & 1) && j < len) {
-                            double nb = from_pair_partner(own);
-                            DISTSIM_STEP_ONE(Pc, nb, latO, durO);
-                            j++;
-                        }
-                        for (; j + 1 < len; j += 2) {
-                            double nb = from_lanes(own, adrE);
-                            DISTSIM_STEP_ONE(Pc, nb, latE, durE);
-                            double nb2 = from_pair_partner(own);
-                            DISTSIM_STEP_ONE(Pc, nb2, latO, durO);
-                        }
-                        if (j < len) {
-                            double nb = from_lanes(own, adrE);
-                            DISTSIM_STEP_ONE(Pc, nb, latE, durE);
-                        }
-                        PFb = shl32(PFb, len); PBb = shl32(PBb, len);
-                    } else {
-                        for (int j = 0; j < len; j++) {
-                            double fromL = from_prev_lane(own);
-                            double fromR = from_next_lane(own);
-                            DISTSIM_STEP_BOTH();
-                        }
-                    }
-                } else if (inF) {
-                    for (int j = 0; j < len; j++) {
-                        double fromL = from_prev_lane(own);
-                        DISTSIM_STEP_ONE(PFb, fromL, pfL, Fd);
-                    }
-                    PBb = shl32(PBb, len);
-                } else if (inB) {
-                    for (int j = 0; j < len; j++) {
-                        double fromR = from_next_lane(own);
-                        DISTSIM_STEP_ONE(PBb, fromR, pbR, Bd);
-                    }
-                    PFb = shl32(PFb, len);
-                } else {
-                    PFb = shl32(PFb, len); PBb = shl32(PBb, len);
+    for (int l0 = 0; l0 < nlev; l0 += 32) {
+        const int x0 = l0 - s;
+        const uint32_t even_x = (x0 & 1) ? 0x55555555u : 0xaaaaaaaau;       // levels with even x
+        uint32_t PFb = level_bits(-x0, f1hi - x0) | (level_bits(f2lo - x0, f2hi - x0) & even_x);
+        uint32_t PBb = level_bits(blo - x0, bhi - x0);
+        if (sched != 0) PBb &= ((blo - x0) & 1) ? 0x55555555u : 0xaaaaaaaau;   // x - blo even
+        if (!act) { PFb = 0; PBb = 0; }
+        // chunk-relative level ranges in which any lane has a forward / a backward task
+        const uint32_t orF = wave_or_u32(PFb), orB = wave_or_u32(PBb);
+        if ((orF | orB) == 0) continue;
+        const int firstF = orF ? __builtin_clz(orF) : 64, lastF = orF ? 31 - __builtin_ctz(orF) : -1;
+        const int firstB = orB ? __builtin_clz(orB) : 64, lastB = orB ? 31 - __builtin_ctz(orB) : -1;
+        const int endk = (lastF > lastB ? lastF : lastB) + 1;
+        int k = firstF < firstB ? firstF : firstB;
+        PFb = shl32(PFb, k); PBb = shl32(PBb, k);            // skip the idle levels in front
+        uint64_t kmask, kmask2;
+        while (k < endk) {
+            const bool inF = k >= firstF && k <= lastF, inB = k >= firstB && k <= lastB;
+            int e = endk;                                     // next level at which the mix changes
+            if (firstF > k && firstF < e) e = firstF;
+            if (firstB > k && firstB < e) e = firstB;
+            if (lastF + 1 > k && lastF + 1 < e) e = lastF + 1;
+            if (lastB + 1 > k && lastB + 1 < e) e = lastB + 1;
+            const int len = e - k;
+            if (inF && inB && par_ok) {
+                // roles by parity: on even levels the even stages run forwards, on odd levels
+                // the odd stages do
+                double latE[U], durE[U], latO[U], durO[U];
+#pragma unroll
+                for (int u = 0; u < U; u++) {
+                    latE[u] = even_s ? sw[u].pfL : sw[u].pbR; durE[u] = even_s ? sw[u].Fd : sw[u].Bd;
+                    latO[u] = even_s ? sw[u].pbR : sw[u].pfL; durO[u] = even_s ? sw[u].Bd : sw[u].Fd;
                 }
-                k = e;
+                uint32_t Pc = PFb | PBb;
+                for (int j = 0; j < len; j++) {
+                    if ((l0 + k + j) & 1) {
+                        if constexpr (U == 1) {
+                            double nb = from_pair_partner(sw[0].own);
+                            DISTSIM_STEP1(Pc, sw[0].own, nb, latO[0], durO[0]);
+                        } else {
+                            double na = from_pair_partner(sw[0].own), nb = from_pair_partner(sw[U - 1].own);
+                            DISTSIM_STEP2(Pc, sw[0].own, na, latO[0], durO[0], sw[U - 1].own, nb, latO[U - 1], durO[U - 1]);
+                        }
+                    } else {
+                        if constexpr (U == 1) {
+                            double nb = from_lanes(sw[0].own, adrE);
+                            DISTSIM_STEP1(Pc, sw[0].own, nb, latE[0], durE[0]);
+                        } else {
+                            double na = from_lanes(sw[0].own, adrE), nb = from_lanes(sw[U - 1].own, adrE);
+                            DISTSIM_STEP2(Pc, sw[0].own, na, latE[0], durE[0], sw[U - 1].own, nb, latE[U - 1], durE[U - 1]);
+                        }
+                    }
+                }
+                PFb = shl32(PFb, len); PBb = shl32(PBb, len);
+            } else if (inF && inB) {
+                for (int j = 0; j < len; j++) {
+                    double fl = from_prev_lane(sw[0].own), fr = from_next_lane(sw[0].own);
+                    DISTSIM_STEPFB1(PFb, PBb, sw[0].own, fl, fr, sw[0].pfL, sw[0].pbR, sw[0].Fd, sw[0].Bd);
+                    if constexpr (U == 2) {
+                        double gl = from_prev_lane(sw[U - 1].own), gr = from_next_lane(sw[U - 1].own);
+                        DISTSIM_APPLYFB(sw[U - 1].own, gl, gr, sw[U - 1].pfL, sw[U - 1].pbR, sw[U - 1].Fd, sw[U - 1].Bd);
+                    }
+                }
+            } else if (inF) {
+                for (int j = 0; j < len; j++) {
+                    if constexpr (U == 1) {
+                        double fl = from_prev_lane(sw[0].own);
+                        DISTSIM_STEP1(PFb, sw[0].own, fl, sw[0].pfL, sw[0].Fd);
+                    } else {
+                        double fl = from_prev_lane(sw[0].own), gl = from_prev_lane(sw[U - 1].own);
+                        DISTSIM_STEP2(PFb, sw[0].own, fl, sw[0].pfL, sw[0].Fd, sw[U - 1].own, gl, sw[U - 1].pfL, sw[U - 1].Fd);
+                    }
+                }
+                PBb = shl32(PBb, len);
+            } else if (inB) {
+                for (int j = 0; j < len; j++) {
+                    if constexpr (U == 1) {
+                        double fr = from_next_lane(sw[0].own);
+                        DISTSIM_STEP1(PBb, sw[0].own, fr, sw[0].pbR, sw[0].Bd);
+                    } else {
+                        double fr = from_next_lane(sw[0].own), gr = from_next_lane(sw[U - 1].own);
+                        DISTSIM_STEP2(PBb, sw[0].own, fr, sw[0].pbR, sw[0].Bd, sw[U - 1].own, gr, sw[U - 1].pbR, sw[U - 1].Bd);
+                    }
+                }
+                PFb = shl32(PFb, len);
+            } else {
+                PFb = shl32(PFb, len); PBb = shl32(PBb, len);
             }
-            (void)kmask; (void)kmask2;
+            k = e;
         }
+        (void)kmask; (void)kmask2;
+    }
 
+#pragma unroll
+    for (int u = 0; u < U; u++) {
         // data-parallel modelling: gradient all-reduce after (or overlapped with) the last backward
-        const int64_t endB = (int64_t)own;
-        const int64_t AR_ = park_ar[slot];
-        const int misc = park_misc[slot];
-        const bool has_ar_ = (misc >> 16) & 1;
-        int64_t finish = endB + AR_, ar_busy = AR_, nar = has_ar_ ? 1 : 0;
-        if (has_ar_ && cl.bucket > 0) {
-            const int lo = misc & 0xff, hi = (misc >> 8) & 0xff, v = misc >> 17, dp = park_dp[slot];
+        const int64_t endB = (int64_t)sw[u].own;
+        const int64_t AR = park_ar[u][slot];
+        const int misc = park_misc[u][slot];
+        const bool has_ar = (misc >> 16) & 1, dropped = (misc >> 17) & 1;
+        int64_t finish = endB + AR, ar_busy = AR, nar = has_ar ? 1 : 0;
+        if (has_ar && cl.bucket > 0) {
+            const int lo = misc & 0xff, hi = (misc >> 8) & 0xff, v = misc >> 18, dp = park_dp[u][slot];
             const size_t vr = (size_t)v * (L + 1), rr = (size_t)(v * kMaxPP + pp - 1) * (L + 1);
-            const int64_t startB = endB - (int64_t)Bd;
+            const int64_t startB = endB - (int64_t)sw[u].Bd;
             const int64_t tot_hi = ws.pbc[vr + hi] + ws.pba[rr + hi];
             const int64_t ar_cap = allreduce_ns(cl, dp, cl.bucket);
             int64_t acc = 0, t = 0;
@@ -285,12 +342,12 @@ __global__ __launch_bounds__(256, 8) void k_simulate(CostsDev co, ClusterDev cl,
             for (int l = hi - 1; l >= lo; l--) {
                 const int64_t ready = startB + (tot_hi - (ws.pbc[vr + l] + ws.pba[rr + l]));
                 acc += ws.pg[vr + l + 1] - ws.pg[vr + l];
-                const int64_t k = (int64_t)udiv64((uint64_t)acc, (uint64_t)cl.bucket);
-                if (k > 0) {
-                    t = (t > ready ? t : ready) + k * ar_cap;
-                    ar_busy += k * ar_cap;
-                    nar += k;
-                    acc -= k * cl.bucket;
+                const int64_t kk = (int64_t)udiv64((uint64_t)acc, (uint64_t)cl.bucket);
+                if (kk > 0) {
+                    t = (t > ready ? t : ready) + kk * ar_cap;
+                    ar_busy += kk * ar_cap;
+                    nar += kk;
+                    acc -= kk * cl.bucket;
                 }
                 if (l == lo && acc > 0) {
                     const int64_t dlast = allreduce_ns(cl, dp, acc);
@@ -301,18 +358,61 @@ __global__ __launch_bounds__(256, 8) void k_simulate(CostsDev co, ClusterDev cl,
             }
             finish = t > endB ? t : endB;
         }
-        nar = group_sum(nar, width);
-        const int64_t batch = group_max(act ? finish : 0, width);
-        // lanes outside a candidate have m = 0 and zero rows: they store zeros
-        const int64_t comp = (int64_t)m * park_comp[slot];
-        const int64_t comm = act ? (int64_t)m * park_comm[slot] + ar_busy : 0;
+        // one event per stage that has one, or the stages' bucket counts
+        nar = cl.bucket > 0 ? group_sum(nar, width) : group_count(has_ar, width);
+        const int64_t batch = group_max(act && !dropped ? finish : 0, width);
+        // lanes outside a candidate and dropped candidates have zero rows: they store zeros
+        const bool live = act && !dropped;
+        const int64_t comp = live ? (int64_t)m * park_comp[u][slot] : 0;
+        const int64_t comm = live ? (int64_t)m * park_comm[u][slot] + ar_busy : 0;
+        const int64_t i = (w0 + u) * kWave + lane;
         out.comp_busy[i] = comp;
         out.comm_busy[i] = comm;
         if (out.util) out.util[i] = batch > 0 ? (double)comp / (double)batch : 0.0;
-        if (act && s == 0) {
-            const int64_t cc = park_cand[slot];
+        if (live && s == 0) {
+            const int64_t cc = park_cand[u][slot];
             out.batch_ns[cc] = batch;
             ev.num_events[cc] = 2ll * m * pp + 2ll * m * (pp - 1) + nar;
+        }
+    }
+}
+
+__global__ __launch_bounds__(kSimBlock, 8) void k_simulate(CostsDev co, ClusterDev cl, CandDev ca, Workspace ws,
+                                                           EventsDev ev, SimOut out) {
+    const int lane = lane_id();
+    const int64_t wave0 = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / kWave;
+    const int64_t nwaves = ((int64_t)gridDim.x * blockDim.x) / kWave;
+    int64_t W = ws.hdr[H_NUM_ITEMS];
+    if (W * kWave > ev.stage_cap) W = ev.stage_cap / kWave;
+    const int L = co.L;
+    // What only the epilogue needs is parked in LDS during the sweep (each lane its own slot),
+    // so that the sweep runs in few enough registers for eight wavefronts per SIMD.
+    __shared__ int64_t park_comp[2][kSimBlock], park_comm[2][kSimBlock], park_ar[2][kSimBlock];
+    __shared__ int32_t park_cand[2][kSimBlock], park_dp[2][kSimBlock], park_misc[2][kSimBlock];
+
+    // A wavefront takes two neighbouring items per turn; they are simulated together when every
+    // lane sees the same shape (pp, m, schedule) in both, which neighbours in visiting order
+    // mostly do, else one after the other.
+    for (int64_t w = 2 * wave0; w < W; w += 2 * nwaves) {
+        const bool pair = w + 1 < W;
+        const Item ia = decode_item(ws.hdr, w);
+        const Item ib = decode_item(ws.hdr, pair ? w + 1 : w);
+        const int64_t posa = ia.pos0 + (lane >> ia.sh), posb = ib.pos0 + (lane >> ib.sh);
+        Desc da{}, db{};
+        if (posa < ia.class_end) da = ws.desc[posa];
+        if (pair && posb < ib.class_end) db = ws.desc[posb];
+        const bool same = pair && ia.sh == ib.sh &&
+                          __builtin_amdgcn_ballot_w64(((da.meta ^ db.meta) & 0xffff) != 0 || da.m != db.m) == 0;
+        if (same) {
+            const Desc two[2] = {da, db};
+            simulate_items<2>(cl, ca, ws, ev, out, L, w, ia.sh, two, lane, park_comp, park_comm, park_ar,
+                              park_cand, park_dp, park_misc);
+        } else {
+            for (int q = 0; q < (pair ? 2 : 1); q++) {
+                const Desc one[1] = {q ? db : da};
+                simulate_items<1>(cl, ca, ws, ev, out, L, w + q, q ? ib.sh : ia.sh, one, lane, park_comp, park_comm,
+                                  park_ar, park_cand, park_dp, park_misc);
+            }
         }
     }
 }
