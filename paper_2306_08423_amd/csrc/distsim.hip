@@ -85,6 +85,14 @@ bool cluster_ok(const distsim_cluster* c) {
 }
 
 // Waves that sweep the wave-items: enough to fill every SIMD, never more than one per candidate.
+// Grid of k_simulate: a wavefront takes two items per turn and items differ a lot in length, so
+// the grid is many times what is resident at once and the dispatcher evens the load out.
+int simulate_grid(const distsim_ctx* ctx, int64_t C) {
+    const int64_t want = (int64_t)ctx->num_cus * 128;
+    const int64_t need = (C + 7) / 8;                         // blocks of 4 waves, 2 items per wave
+    return (int)(need < want ? (need < 1 ? 1 : need) : want);
+}
+
 int item_grid(const distsim_ctx* ctx, int64_t C) {
     const int64_t want = (int64_t)ctx->num_cus * 8;           // blocks of 4 waves: 8 waves per SIMD
     const int64_t need = (C + 3) / 4;
@@ -226,7 +234,7 @@ int distsim_simulate(distsim_ctx* ctx, const distsim_cluster* cluster, const dis
     }
     {
         Timer t(ctx, st, DISTSIM_K_SIMULATE);
-        hipLaunchKernelGGL(k_simulate, dim3(item_grid(ctx, C)), dim3(256), 0, st, co, cl, ca, ws, ev, out);
+        hipLaunchKernelGGL(k_simulate, dim3(simulate_grid(ctx, C)), dim3(256), 0, st, co, cl, ca, ws, ev, out);
     }
     HIP_TRY(hipGetLastError());
     return DISTSIM_OK;

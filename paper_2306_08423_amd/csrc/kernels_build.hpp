@@ -70,10 +70,12 @@ __global__ __launch_bounds__(64) void k_layer_tables(CostsDev co, ClusterDev cl,
     int64_t* pfc = ws.pfc + (size_t)v * (L + 1);
     int64_t* pbc = ws.pbc + (size_t)v * (L + 1);
     int64_t* pg = ws.pg + (size_t)v * (L + 1);
+    int64_t* comb = ws.comb + (size_t)row * (L + 1) * kCombWords;
     int64_t c_fa = 0, c_ba = 0, c_fc = 0, c_bc = 0, c_g = 0;
     if (lane == 0) {
         pfa[0] = 0; pba[0] = 0;
         if (base) { pfc[0] = 0; pbc[0] = 0; pg[0] = 0; }
+        for (int k = 0; k < kCombWords; k++) comb[k] = 0;
     }
     for (int l0 = 0; l0 < L; l0 += kWave) {
         const int l = l0 + lane;
@@ -85,22 +87,25 @@ __global__ __launch_bounds__(64) void k_layer_tables(CostsDev co, ClusterDev cl,
         int64_t b = in ? x + (tp > 1 ? co.ba[i] : 0) : 0;
         f = wave_inclusive_sum(f) + c_fa;
         b = wave_inclusive_sum(b) + c_ba;
-        if (in) { pfa[l + 1] = f; pba[l + 1] = b; }
+        const int64_t a = wave_inclusive_sum(in ? co.fc[i] : 0) + c_fc;
+        const int64_t bb = wave_inclusive_sum(in ? co.bc[i] : 0) + c_bc;
+        const int64_t g = wave_inclusive_sum(in ? co.grad[i] : 0) + c_g;
+        if (in) {
+            const int64_t p_intra = p2p_ns(cl, co.act[i], 0), p_inter = p2p_ns(cl, co.act[i], 1);
+            pfa[l + 1] = f; pba[l + 1] = b;
+            int64_t* e = comb + (size_t)(l + 1) * kCombWords;
+            e[0] = a + f; e[1] = bb + b; e[2] = a + bb; e[3] = g; e[4] = p_intra; e[5] = p_inter;
+            if (base) {
+                pfc[l + 1] = a; pbc[l + 1] = bb; pg[l + 1] = g;
+                ws.p2p[i * 2 + 0] = p_intra;
+                ws.p2p[i * 2 + 1] = p_inter;
+            }
+        }
         c_fa = __shfl(f, kWave - 1, kWave);
         c_ba = __shfl(b, kWave - 1, kWave);
-        if (base) {
-            int64_t a = wave_inclusive_sum(in ? co.fc[i] : 0) + c_fc;
-            int64_t bb = wave_inclusive_sum(in ? co.bc[i] : 0) + c_bc;
-            int64_t g = wave_inclusive_sum(in ? co.grad[i] : 0) + c_g;
-            if (in) {
-                pfc[l + 1] = a; pbc[l + 1] = bb; pg[l + 1] = g;
-                ws.p2p[i * 2 + 0] = p2p_ns(cl, co.act[i], 0);
-                ws.p2p[i * 2 + 1] = p2p_ns(cl, co.act[i], 1);
-            }
-            c_fc = __shfl(a, kWave - 1, kWave);
-            c_bc = __shfl(bb, kWave - 1, kWave);
-            c_g = __shfl(g, kWave - 1, kWave);
-        }
+        c_fc = __shfl(a, kWave - 1, kWave);
+        c_bc = __shfl(bb, kWave - 1, kWave);
+        c_g = __shfl(g, kWave - 1, kWave);
     }
 }
 
@@ -256,36 +261,80 @@ struct StageRow {
 // applies the 2^53 guard (both are reductions over the candidate's lanes).  Every lane of the
 // wavefront must call it.  Returns 0, or the status of a candidate that must be dropped
 // (1 = not a partition, 2 = range); rows of dropped candidates and of idle lanes are zero.
-__device__ __forceinline__ int stage_row(const ClusterDev& cl, const Workspace& ws, int L, int width, int s,
-                                         int pp, int v, int m, int dp, int tp, int lo, int hi, StageRow& r) {
-    const bool act = s < pp;
-    r = StageRow{0, 0, 0, 0, 0, 0, 0};
+// Partition check and link classes of one stage: returns nonzero when the candidate's layer
+// bounds are not a partition of [0, L) (a reduction over the candidate's lanes); inter_next /
+// inter_prev say whether the p2p to the next / previous stage crosses nodes.
+__device__ __forceinline__ int stage_check(const ClusterDev& cl, int L, int width, int s, int pp, int dp, int tp,
+                                           int lo, int hi, int& inter_next, int& inter_prev) {
     int bad = 0;
     int node = 0;               // node of the stage's first rank (ranks ordered tp fastest, then dp, then pp)
-    if (act) {
+    if (s < pp) {
         bad = (hi <= lo) || (hi > L) || (s == 0 && lo != 0) || (s == pp - 1 && hi != L);
         // a stage of at least a node's worth of ranks starts on a node of its own
         const int64_t tpdp = (int64_t)tp * dp;
         node = tpdp >= cl.gpus_per_node ? s : (int)udiv64((uint64_t)s * (uint64_t)tpdp, (uint64_t)cl.gpus_per_node);
     }
-    bad = group_any(bad != 0, width) ? 1 : 0;
-    const int node_next = __builtin_amdgcn_update_dpp(0, node, kDppWaveShl1, 0xf, 0xf, true);
-    const int node_prev = __builtin_amdgcn_update_dpp(0, node, kDppWaveShr1, 0xf, 0xf, true);
-    if (act && !bad) {
+    inter_next = node != __builtin_amdgcn_update_dpp(0, node, kDppWaveShl1, 0xf, 0xf, true);
+    inter_prev = node != __builtin_amdgcn_update_dpp(0, node, kDppWaveShr1, 0xf, 0xf, true);
+    return group_any(bad != 0, width) ? 1 : 0;
+}
+
+// The 2^53 guard: every timestamp of the pipeline phase is bounded by m * (all task and p2p
+// durations of the candidate); per_stage is this lane's share of that sum.
+__device__ __forceinline__ bool stage_out_of_range(int64_t per_stage, int m, int width) {
+    const uint64_t t1 = (uint64_t)group_sum(per_stage, width);
+    return __umul64hi(t1, (uint64_t)m) != 0 || t1 * (uint64_t)m >= (1ull << 53);
+}
+
+__device__ __forceinline__ int stage_row(const ClusterDev& cl, const Workspace& ws, int L, int width, int s,
+                                         int pp, int v, int m, int dp, int tp, int lo, int hi, StageRow& r) {
+    r = StageRow{0, 0, 0, 0, 0, 0, 0};
+    int inter_next, inter_prev;
+    const int bad = stage_check(cl, L, width, s, pp, dp, tp, lo, hi, inter_next, inter_prev);
+    if (s < pp && !bad) {
         const size_t vr = (size_t)v * (L + 1), rr = (size_t)(v * kMaxPP + pp - 1) * (L + 1);
         r.FC = ws.pfc[vr + hi] - ws.pfc[vr + lo];
         r.BC = ws.pbc[vr + hi] - ws.pbc[vr + lo];
         r.FA = ws.pfa[rr + hi] - ws.pfa[rr + lo];
         r.BA = ws.pba[rr + hi] - ws.pba[rr + lo];
         r.G = ws.pg[vr + hi] - ws.pg[vr + lo];
-        if (s + 1 < pp) r.PF = ws.p2p[((size_t)v * L + hi - 1) * 2 + (node != node_next ? 1 : 0)];
-        if (s > 0) r.PB = ws.p2p[((size_t)v * L + lo - 1) * 2 + (node != node_prev ? 1 : 0)];
+        if (s + 1 < pp) r.PF = ws.p2p[((size_t)v * L + hi - 1) * 2 + inter_next];
+        if (s > 0) r.PB = ws.p2p[((size_t)v * L + lo - 1) * 2 + inter_prev];
     }
-    // every timestamp of the pipeline phase is bounded by m * (all task and p2p durations)
-    const uint64_t t1 = (uint64_t)group_sum(r.FC + r.FA + r.BC + r.BA + r.PF + r.PB, width);
-    const bool range = __umul64hi(t1, (uint64_t)m) != 0 || t1 * (uint64_t)m >= (1ull << 53);
+    const bool range = stage_out_of_range(r.FC + r.FA + r.BC + r.BA + r.PF + r.PB, m, width);
     const int drop = bad ? 1 : (range ? 2 : 0);
     if (drop) r = StageRow{0, 0, 0, 0, 0, 0, 0};
+    return drop;
+}
+
+// What simulate needs of a stage's composed events: duration of the forward and of the backward
+// stage-task without p2p (computation + in-stage communication), the computation of both, the
+// gradient bytes and the two outgoing p2p events.  Same contract as stage_row, fed from
+// Workspace::comb.
+struct StageSums {
+    int64_t FT, BT, CP, G, PF, PB;
+};
+
+__device__ __forceinline__ int stage_sums(const ClusterDev& cl, const Workspace& ws, int L, int width, int s,
+                                          int pp, int v, int m, int dp, int tp, int lo, int hi, StageSums& r) {
+    r = StageSums{0, 0, 0, 0, 0, 0};
+    int inter_next, inter_prev;
+    const int bad = stage_check(cl, L, width, s, pp, dp, tp, lo, hi, inter_next, inter_prev);
+    if (s < pp && !bad) {
+        const int64_t* row = ws.comb + (size_t)((v * kMaxPP + pp - 1) * (L + 1)) * kCombWords;
+        const longlong2* e_hi = (const longlong2*)(row + hi * kCombWords);
+        const longlong2* e_lo = (const longlong2*)(row + lo * kCombWords);
+        const longlong2 h0 = e_hi[0], h1 = e_hi[1], l0 = e_lo[0], l1 = e_lo[1];
+        r.FT = h0.x - l0.x;
+        r.BT = h0.y - l0.y;
+        r.CP = h1.x - l1.x;
+        r.G = h1.y - l1.y;
+        if (s + 1 < pp) r.PF = row[hi * kCombWords + 4 + inter_next];
+        if (s > 0) r.PB = row[lo * kCombWords + 4 + inter_prev];
+    }
+    const bool range = stage_out_of_range(r.FT + r.BT + r.PF + r.PB, m, width);
+    const int drop = bad ? 1 : (range ? 2 : 0);
+    if (drop) r = StageSums{0, 0, 0, 0, 0, 0};
     return drop;
 }
 

@@ -183,23 +183,23 @@ __device__ __forceinline__ void simulate_items(const ClusterDev& cl, const CandD
             if (d[u].poff >= 0) { lo = ca.part_pool[d[u].poff + s]; hi = ca.part_pool[d[u].poff + s + 1]; }
             else { lo = (int)(((int64_t)s * L) / pp); hi = (int)(((int64_t)(s + 1) * L) / pp); }
         }
-        StageRow r;
-        const int drop = stage_row(cl, ws, L, width, s, pp, v, d[u].m, dp, (int)d[u].spare, lo, hi, r);
+        StageSums r;
+        const int drop = stage_sums(cl, ws, L, width, s, pp, v, d[u].m, dp, (int)d[u].spare, lo, hi, r);
         if (drop && act && s == 0) { ev.status[c] = drop; ev.num_events[c] = 0; out.batch_ns[c] = INT64_MAX; }
         const bool has_ar = act && dp > 1 && r.G > 0;       // gradient bytes to reduce over dp > 1 ranks
         // p2p on the incoming edges (the neighbours' outgoing events): latency of the edge, or,
         // when the sender is occupied by it, part of the sender's task; -inf = no edge
         const int64_t pf_task = cl.blocking ? r.PF : 0, pb_task = cl.blocking ? r.PB : 0;
         sw[u].own = 0.0;
-        sw[u].Fd = (double)(r.FC + r.FA + pf_task);
-        sw[u].Bd = (double)(r.BC + r.BA + pb_task);
+        sw[u].Fd = (double)(r.FT + pf_task);
+        sw[u].Bd = (double)(r.BT + pb_task);
         sw[u].pfL = from_prev_lane((double)(r.PF - pf_task));
         sw[u].pbR = from_next_lane((double)(r.PB - pb_task));
         if (!(act && s > 0)) sw[u].pfL = ninf;
         if (!(act && s + 1 < pp)) sw[u].pbR = ninf;
         // what only the epilogue needs waits in LDS
-        park_comp[u][slot] = r.FC + r.BC;                                  // computation per micro-batch
-        park_comm[u][slot] = r.FA + r.BA + r.PF + r.PB;                    // communication per micro-batch
+        park_comp[u][slot] = r.CP;                                         // computation per micro-batch
+        park_comm[u][slot] = r.FT + r.BT - r.CP + r.PF + r.PB;             // communication per micro-batch
         park_ar[u][slot] = cl.bucket > 0 ? 0 : allreduce_ns(cl, dp, r.G);  // single trailing all-reduce
         park_cand[u][slot] = (int32_t)c;
         park_dp[u][slot] = dp;
@@ -333,15 +333,16 @@ __device__ __forceinline__ void simulate_items(const ClusterDev& cl, const CandD
         int64_t finish = endB + AR, ar_busy = AR, nar = has_ar ? 1 : 0;
         if (has_ar && cl.bucket > 0) {
             const int lo = misc & 0xff, hi = (misc >> 8) & 0xff, v = misc >> 18, dp = park_dp[u][slot];
-            const size_t vr = (size_t)v * (L + 1), rr = (size_t)(v * kMaxPP + pp - 1) * (L + 1);
+            // per layer: backward time up to the layer (word 1) and gradient bytes (word 3)
+            const int64_t* row = ws.comb + (size_t)((v * kMaxPP + pp - 1) * (L + 1)) * kCombWords;
             const int64_t startB = endB - (int64_t)sw[u].Bd;
-            const int64_t tot_hi = ws.pbc[vr + hi] + ws.pba[rr + hi];
+            const int64_t tot_hi = row[hi * kCombWords + 1];
             const int64_t ar_cap = allreduce_ns(cl, dp, cl.bucket);
             int64_t acc = 0, t = 0;
             ar_busy = 0; nar = 0;
             for (int l = hi - 1; l >= lo; l--) {
-                const int64_t ready = startB + (tot_hi - (ws.pbc[vr + l] + ws.pba[rr + l]));
-                acc += ws.pg[vr + l + 1] - ws.pg[vr + l];
+                const int64_t ready = startB + (tot_hi - row[l * kCombWords + 1]);
+                acc += row[(l + 1) * kCombWords + 3] - row[l * kCombWords + 3];
                 const int64_t kk = (int64_t)udiv64((uint64_t)acc, (uint64_t)cl.bucket);
                 if (kk > 0) {
                     t = (t > ready ? t : ready) + kk * ar_cap;
@@ -377,7 +378,7 @@ __device__ __forceinline__ void simulate_items(const ClusterDev& cl, const CandD
     }
 }
 
-__global__ __launch_bounds__(kSimBlock, 8) void k_simulate(CostsDev co, ClusterDev cl, CandDev ca, Workspace ws,
+__global__ __launch_bounds__(kSimBlock, 6) void k_simulate(CostsDev co, ClusterDev cl, CandDev ca, Workspace ws,
                                                            EventsDev ev, SimOut out) {
     const int lane = lane_id();
     const int64_t wave0 = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / kWave;
@@ -386,7 +387,7 @@ __global__ __launch_bounds__(kSimBlock, 8) void k_simulate(CostsDev co, ClusterD
     if (W * kWave > ev.stage_cap) W = ev.stage_cap / kWave;
     const int L = co.L;
     // What only the epilogue needs is parked in LDS during the sweep (each lane its own slot),
-    // so that the sweep runs in few enough registers for eight wavefronts per SIMD.
+    // so that the sweep runs in few enough registers for six wavefronts per SIMD.
     __shared__ int64_t park_comp[2][kSimBlock], park_comm[2][kSimBlock], park_ar[2][kSimBlock];
     __shared__ int32_t park_cand[2][kSimBlock], park_dp[2][kSimBlock], park_misc[2][kSimBlock];
 

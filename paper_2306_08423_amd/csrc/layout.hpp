@@ -11,6 +11,7 @@ constexpr int kClasses = 7;                 // lanes per candidate: 64, 32, 16, 
 constexpr int kMBins = 1024;                // micro-batch count is clamped to this for ordering only
 constexpr int kBinsPerClass = 2 * kMBins;   // schedule x m
 constexpr int kBins = kClasses * kBinsPerClass;
+constexpr int kCombWords = 6;               // int64 words per entry of Workspace::comb
 
 // Header words kept in device memory (int64 each).
 enum {
@@ -34,6 +35,11 @@ struct Workspace {
     int64_t *pfc, *pbc, *pg;       // row = variant
     int64_t *pfa, *pba;            // row = variant*kMaxPP + (pp-1): in-stage communication incl. all-to-all
     int64_t *p2p;                  // [(variant*L + l)*2 + link class]: p2p event of the activation after layer l
+    // The same sums arranged for simulate, row = variant*kMaxPP + (pp-1), six words per entry l:
+    //   pfc+pfa, pbc+pba | pfc+pbc, pg | p2p event (intra-, inter-node) of the activation that
+    //   enters layer l (zero at l = 0)
+    // so that a stage's composed events come from two neighbouring-in-memory places.
+    int64_t *comb;
     int32_t *key;                  // [C] ordering bin | variant << 24, -1 = not simulated
     int32_t *bin_count;            // [kBins]
     int32_t *bin_start;            // [kBins+1]
@@ -57,6 +63,7 @@ inline size_t carve(Workspace& w, void* base, int32_t L, int32_t V, int64_t C) {
     w.pfa = (int64_t*)take(row * V * kMaxPP);
     w.pba = (int64_t*)take(row * V * kMaxPP);
     w.p2p = (int64_t*)take((size_t)V * L * 2 * sizeof(int64_t));
+    w.comb = (int64_t*)take(row * V * kMaxPP * kCombWords);
     w.key = (int32_t*)take(Cc * 4);
     w.bin_count = (int32_t*)take((size_t)kBins * 4);
     w.bin_start = (int32_t*)take((size_t)(kBins + 1) * 4);
