@@ -219,7 +219,13 @@ __device__ __forceinline__ void simulate_items(const ClusterDev& cl, const CandD
         f2lo = 2 * wq + 2; f2hi = 2 * m - 2;
         blo = 2 * pp - 1 - 2 * s; bhi = blo + 2 * m - 2;
     }
-    const int nlev = wave_max_i32(act ? 2 * (m + pp - 1) : 0);
+    // Levels at which some lane of the wavefront has a forward / a backward task: forwards from
+    // level 0 to gLastF, backwards from gFirstB to gLastB (the last level of the sweep).
+    const int lastFx = (f2lo <= f2hi && f2hi > f1hi) ? f2hi : f1hi;
+    const int gLastF = wave_max_i32(act ? s + lastFx : -1);
+    const int gFirstB = -wave_max_i32(act ? -(s + blo) : -(1 << 30));
+    const int gLastB = wave_max_i32(act ? s + bhi : -1);
+    const int nlev = gLastB + 1;
 
     // 1F1B past its warm-up runs forwards on even x and backwards on odd x.  When every
     // candidate of the wavefront is 1F1B with one pp, a level that has both kinds therefore
@@ -237,11 +243,11 @@ __device__ __forceinline__ void simulate_items(const ClusterDev& cl, const CandD
         uint32_t PBb = level_bits(blo - x0, bhi - x0);
         if (sched != 0) PBb &= ((blo - x0) & 1) ? 0x55555555u : 0xaaaaaaaau;   // x - blo even
         if (!act) { PFb = 0; PBb = 0; }
-        // chunk-relative level ranges in which any lane has a forward / a backward task
-        const uint32_t orF = wave_or_u32(PFb), orB = wave_or_u32(PBb);
-        if ((orF | orB) == 0) continue;
-        const int firstF = orF ? __builtin_clz(orF) : 64, lastF = orF ? 31 - __builtin_ctz(orF) : -1;
-        const int firstB = orB ? __builtin_clz(orB) : 64, lastB = orB ? 31 - __builtin_ctz(orB) : -1;
+        // chunk-relative level ranges in which a lane may have a forward / a backward task
+        const bool anyF = gLastF >= l0, anyB = gFirstB < l0 + 32;
+        const int firstF = anyF ? 0 : 64, lastF = anyF ? (gLastF - l0 < 31 ? gLastF - l0 : 31) : -1;
+        const int firstB = anyB ? (gFirstB > l0 ? gFirstB - l0 : 0) : 64;
+        const int lastB = anyB ? (gLastB - l0 < 31 ? gLastB - l0 : 31) : -1;
         const int endk = (lastF > lastB ? lastF : lastB) + 1;
         int k = firstF < firstB ? firstF : firstB;
         PFb = shl32(PFb, k); PBb = shl32(PBb, k);            // skip the idle levels in front
