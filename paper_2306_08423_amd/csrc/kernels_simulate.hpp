@@ -154,15 +154,24 @@ struct Sweep {
 
 constexpr int kSimBlock = 256;
 
+// What only the epilogue of an item needs waits here during the sweep, one slot per lane of the
+// workgroup and per item of a lockstep pair (one block, so that one address register serves).
+struct Park {
+    int64_t comp[2][kSimBlock];        // computation per micro-batch
+    int64_t comm[2][kSimBlock];        // communication per micro-batch
+    int64_t ar[2][kSimBlock];          // single trailing all-reduce
+    int32_t cand[2][kSimBlock];
+    int32_t dp[2][kSimBlock];
+    int32_t misc[2][kSimBlock];        // layer bounds, flags, variant
+};
+
 // Simulates U wave-items at once.  For U = 2 the two items must have the same shape in every
 // lane (pp, m, schedule): then they share patterns, masks and control flow.
 template <int U>
 __device__ __forceinline__ void simulate_items(const ClusterDev& cl, const CandDev& ca, const Workspace& ws,
                                                const EventsDev& ev, const SimOut& out, int L, int64_t w0,
                                                int sh, const Desc (&d)[U], int lane,
-                                               int64_t (*park_comp)[kSimBlock], int64_t (*park_comm)[kSimBlock],
-                                               int64_t (*park_ar)[kSimBlock], int32_t (*park_cand)[kSimBlock],
-                                               int32_t (*park_dp)[kSimBlock], int32_t (*park_misc)[kSimBlock]) {
+                                               Park& park) {
     const double ninf = -__builtin_huge_val();
     const int slot = threadIdx.x;
     const int width = 1 << sh;
@@ -198,12 +207,12 @@ __device__ __forceinline__ void simulate_items(const ClusterDev& cl, const CandD
         if (!(act && s > 0)) sw[u].pfL = ninf;
         if (!(act && s + 1 < pp)) sw[u].pbR = ninf;
         // what only the epilogue needs waits in LDS
-        park_comp[u][slot] = r.CP;                                         // computation per micro-batch
-        park_comm[u][slot] = r.FT + r.BT - r.CP + r.PF + r.PB;             // communication per micro-batch
-        park_ar[u][slot] = cl.bucket > 0 ? 0 : allreduce_ns(cl, dp, r.G);  // single trailing all-reduce
-        park_cand[u][slot] = (int32_t)c;
-        park_dp[u][slot] = dp;
-        park_misc[u][slot] = lo | (hi << 8) | ((int)has_ar << 16) | ((drop ? 1 : 0) << 17) | (v << 18);
+        park.comp[u][slot] = r.CP;                                         // computation per micro-batch
+        park.comm[u][slot] = r.FT + r.BT - r.CP + r.PF + r.PB;             // communication per micro-batch
+        park.ar[u][slot] = cl.bucket > 0 ? 0 : allreduce_ns(cl, dp, r.G);  // single trailing all-reduce
+        park.cand[u][slot] = (int32_t)c;
+        park.dp[u][slot] = dp;
+        park.misc[u][slot] = lo | (hi << 8) | ((int)has_ar << 16) | ((drop ? 1 : 0) << 17) | (v << 18);
     }
 
     // level windows of this lane, expressed on x = level - s:
@@ -333,12 +342,12 @@ __device__ __forceinline__ void simulate_items(const ClusterDev& cl, const CandD
     for (int u = 0; u < U; u++) {
         // data-parallel modelling: gradient all-reduce after (or overlapped with) the last backward
         const int64_t endB = (int64_t)sw[u].own;
-        const int64_t AR = park_ar[u][slot];
-        const int misc = park_misc[u][slot];
+        const int64_t AR = park.ar[u][slot];
+        const int misc = park.misc[u][slot];
         const bool has_ar = (misc >> 16) & 1, dropped = (misc >> 17) & 1;
         int64_t finish = endB + AR, ar_busy = AR, nar = has_ar ? 1 : 0;
         if (has_ar && cl.bucket > 0) {
-            const int lo = misc & 0xff, hi = (misc >> 8) & 0xff, v = misc >> 18, dp = park_dp[u][slot];
+            const int lo = misc & 0xff, hi = (misc >> 8) & 0xff, v = misc >> 18, dp = park.dp[u][slot];
             // per layer: backward time up to the layer (word 1) and gradient bytes (word 3)
             const int64_t* row = ws.comb + (size_t)((v * kMaxPP + pp - 1) * (L + 1)) * kCombWords;
             const int64_t startB = endB - (int64_t)sw[u].Bd;
@@ -370,14 +379,14 @@ __device__ __forceinline__ void simulate_items(const ClusterDev& cl, const CandD
         const int64_t batch = group_max(act && !dropped ? finish : 0, width);
         // lanes outside a candidate and dropped candidates have zero rows: they store zeros
         const bool live = act && !dropped;
-        const int64_t comp = live ? (int64_t)m * park_comp[u][slot] : 0;
-        const int64_t comm = live ? (int64_t)m * park_comm[u][slot] + ar_busy : 0;
+        const int64_t comp = live ? (int64_t)m * park.comp[u][slot] : 0;
+        const int64_t comm = live ? (int64_t)m * park.comm[u][slot] + ar_busy : 0;
         const int64_t i = (w0 + u) * kWave + lane;
         out.comp_busy[i] = comp;
         out.comm_busy[i] = comm;
         if (out.util) out.util[i] = batch > 0 ? (double)comp / (double)batch : 0.0;
         if (live && s == 0) {
-            const int64_t cc = park_cand[u][slot];
+            const int64_t cc = park.cand[u][slot];
             out.batch_ns[cc] = batch;
             ev.num_events[cc] = 2ll * m * pp + 2ll * m * (pp - 1) + nar;
         }
@@ -394,8 +403,7 @@ __global__ __launch_bounds__(kSimBlock, 6) void k_simulate(CostsDev co, ClusterD
     const int L = co.L;
     // What only the epilogue needs is parked in LDS during the sweep (each lane its own slot),
     // so that the sweep runs in few enough registers for six wavefronts per SIMD.
-    __shared__ int64_t park_comp[2][kSimBlock], park_comm[2][kSimBlock], park_ar[2][kSimBlock];
-    __shared__ int32_t park_cand[2][kSimBlock], park_dp[2][kSimBlock], park_misc[2][kSimBlock];
+    __shared__ Park park;
 
     // A wavefront takes two neighbouring items per turn; they are simulated together when every
     // lane sees the same shape (pp, m, schedule) in both, which neighbours in visiting order
@@ -412,13 +420,11 @@ __global__ __launch_bounds__(kSimBlock, 6) void k_simulate(CostsDev co, ClusterD
                           __builtin_amdgcn_ballot_w64(((da.meta ^ db.meta) & 0xffff) != 0 || da.m != db.m) == 0;
         if (same) {
             const Desc two[2] = {da, db};
-            simulate_items<2>(cl, ca, ws, ev, out, L, w, ia.sh, two, lane, park_comp, park_comm, park_ar,
-                              park_cand, park_dp, park_misc);
+            simulate_items<2>(cl, ca, ws, ev, out, L, w, ia.sh, two, lane, park);
         } else {
             for (int q = 0; q < (pair ? 2 : 1); q++) {
                 const Desc one[1] = {q ? db : da};
-                simulate_items<1>(cl, ca, ws, ev, out, L, w + q, q ? ib.sh : ia.sh, one, lane, park_comp, park_comm,
-                                  park_ar, park_cand, park_dp, park_misc);
+                simulate_items<1>(cl, ca, ws, ev, out, L, w + q, q ? ib.sh : ia.sh, one, lane, park);
             }
         }
     }
