@@ -34,13 +34,12 @@ __global__ __launch_bounds__(256) void k_sim_init(const int32_t* __restrict__ st
 // shifts it by one level and drops the current level's bit into the carry mask, which becomes
 // the EXEC mask of the three fp64 instructions of the task: no per-level compares or selects.
 
-// bits of the chunk-relative levels a..b (inclusive), bit 31 = level 0
+// bits of the chunk-relative levels a..b (inclusive), bit 31 = level 0; empty when a > b or the
+// range misses the chunk (64-bit shifts, so that shifting by 32 clears the word)
 __device__ __forceinline__ uint32_t level_bits(int a, int b) {
-    const bool any = a <= b && a <= 31 && b >= 0;
-    const int lo = a < 0 ? 0 : (a > 31 ? 31 : a);
-    const int hi = b > 31 ? 31 : (b < 0 ? 0 : b);
-    const uint32_t r = (0xffffffffu >> lo) & (0xffffffffu << (31 - hi));
-    return any ? r : 0u;
+    const int lo = a < 0 ? 0 : (a > 32 ? 32 : a);
+    const int hi = b > 31 ? 31 : (b < -1 ? -1 : b);
+    return (uint32_t)(0xffffffffull >> lo) & (uint32_t)(0xffffffffull << (31 - hi));
 }
 
 __device__ __forceinline__ uint32_t shl32(uint32_t x, int n) { return n >= 32 ? 0u : x << n; }
