@@ -61,6 +61,9 @@ def main() -> int:
                     help="also write the optional per-stage event table during event generation")
     ap.add_argument("--timeline", type=int, default=20000,
                     help="also dump the stage-task timelines of this many seeded candidates (0 = skip)")
+    ap.add_argument("--ingest", type=int, default=4_000_000,
+                    help="also time the steps in front of event generation (operator dedup, communication "
+                         "event times) on this many seeded records (0 = skip)")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one 1 GiB device-to-device copy (known traffic, for scaling HBM counters)")
     args = ap.parse_args()
@@ -131,6 +134,39 @@ def main() -> int:
                     "frac": tl_bytes / tl_s / 1e9 / HBM_PEAK_GBS}
         del t_start, t_end, ar0, ar1
 
+    ingest = None
+    if args.ingest > 0:
+        from workloads import make_comm_profiles, make_operator_records
+        n_rec = args.ingest
+        rec = make_operator_records(n_rec, 50_000)
+        d_rec = torch.from_numpy(rec).to(ctx.device)
+        eid, rep, num, wsp = ds.alloc_dedup(ctx, n_rec, ctx.device)
+        prof = [torch.from_numpy(x).to(ctx.device) for x in make_comm_profiles(n_rec)]
+        elapsed = torch.empty(n_rec, dtype=torch.int64, device=ctx.device)
+        ds.distsim_dedup_events(ctx, d_rec, eid, rep, num, wsp)                               # warm-up
+        ds.distsim_comm_event_times(ctx, prof[0], prof[1], prof[2], prof[3], elapsed)
+        torch.cuda.synchronize()
+        ctx.timing_enable(True)
+        for _ in range(5):
+            ds.distsim_dedup_events(ctx, d_rec, eid, rep, num, wsp)
+            ds.distsim_comm_event_times(ctx, prof[0], prof[1], prof[2], prof[3], elapsed)
+        torch.cuda.synchronize()
+        kt2 = ctx.timing_read()
+        ctx.timing_enable(False)
+        dd_s = kt2["k_dedup"][0] / max(kt2["k_dedup"][1], 1) / 1e3
+        ct_s = kt2["k_comm_event_times"][0] / max(kt2["k_comm_event_times"][1], 1) / 1e3
+        n_ev = int(num.item())
+        dd_bytes = n_rec * (rec.shape[1] * 8 + 4) + n_ev * 4         # records in, event ids and representatives out
+        ct_bytes = n_rec * (4 + 4 + 8 + 8 + 8)
+        ingest = {"records": n_rec, "words": int(rec.shape[1]), "events": n_ev,
+                  "dedup": {"ms": dd_s * 1e3, "records_per_s": n_rec / dd_s, "bound": "hbm",
+                            "achieved": dd_bytes / dd_s / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                            "frac": dd_bytes / dd_s / 1e9 / HBM_PEAK_GBS},
+                  "comm_event_times": {"ms": ct_s * 1e3, "records_per_s": n_rec / ct_s, "bound": "hbm",
+                                       "achieved": ct_bytes / ct_s / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                                       "frac": ct_bytes / ct_s / 1e9 / HBM_PEAK_GBS}}
+        del d_rec, eid, rep, wsp, prof, elapsed
+
     if args.calib_copy:
         src = torch.empty(1 << 30, dtype=torch.uint8, device=ctx.device)
         dst = torch.empty_like(src)
@@ -192,7 +228,7 @@ def main() -> int:
         "events_per_s": nev * args.steps / dt, "stage_tasks_per_s": tasks * args.steps / dt,
         "kernel_ms": {k: (v[0] / max(v[1], 1)) * (v[1] / args.steps) for k, v in kt.items()},
         "roofline": roofline, "roofline_hbm": roofline_hbm,
-        "timeline": timeline, "cpu_baseline": cpu_baseline, "parity": parity,
+        "timeline": timeline, "ingest": ingest, "cpu_baseline": cpu_baseline, "parity": parity,
     }
     print(json.dumps(line))
     return 0

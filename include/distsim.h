@@ -239,6 +239,38 @@ int distsim_timeline(distsim_ctx *ctx, const distsim_cluster *cluster, const dis
                      void *hip_stream);
 
 /*
+ * Event generator (Sec. 4.1): operators that agree in name, parameters and input shape (and,
+ * for communication, in the intra-/inter-node attribute) are one event and are profiled once.
+ *   records[n][K]  device: one operator per row, K int64 words that identify it (how names and
+ *                  shapes are encoded in words is the caller's business); 1 <= K <= 16
+ *   event_id[n]    device out: the operator's event; events are numbered 0, 1, ... in the order
+ *                  of their first operator
+ *   rep[n]         device out: rep[e] = index of the first operator of event e, for
+ *                  e < *num_events (the rest is left untouched)
+ *   num_events     device out, one int64
+ *   workspace      device memory of distsim_dedup_workspace_bytes(n) bytes
+ * n <= 2^28.  Errors: EINVAL, ERANGE, EHIP.
+ */
+size_t distsim_dedup_workspace_bytes(int64_t n);
+int distsim_dedup_events(distsim_ctx *ctx, const int64_t *records, int64_t n, int32_t K,
+                         int32_t *event_id, int32_t *rep, int64_t *num_events,
+                         void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Elapsed time of communication events from their profiles (Sec. 4.2), all arrays device, [n]:
+ *   kind 0  point-to-point: elapsed = min(t_a, t_b), the profiled durations of the SEND and of
+ *           the RECV call (the transmission starts when the second of them is called)
+ *   kind 1  all-reduce over ranks[i] devices: t_a is the profile on min(ranks, 8) devices;
+ *           elapsed = t_a for up to 8 devices, else floor(t_a * 8 (N-1) / (7 N)), the ratio of
+ *           the ring volumes 2(N-1)P/N at N and at 8 devices; t_b is ignored
+ * A record of another kind, with ranks < 1 or with a negative time gets elapsed = -1.
+ * Times below 2^62.  Errors: EINVAL, EHIP.
+ */
+int distsim_comm_event_times(distsim_ctx *ctx, int64_t n, const int32_t *kind, const int32_t *ranks,
+                             const int64_t *t_a, const int64_t *t_b, int64_t *elapsed_ns,
+                             void *hip_stream);
+
+/*
  * Optional kernel timing with HIP events recorded on the caller's stream around each kernel
  * launch.  distsim_timing_read blocks until the recorded launches have finished and returns
  * the accumulated time and launch count of one kernel, then clears that kernel's record.
@@ -246,6 +278,7 @@ int distsim_timeline(distsim_ctx *ctx, const distsim_cluster *cluster, const dis
 enum {
     DISTSIM_K_LAYER_TABLES = 0, DISTSIM_K_DECODE, DISTSIM_K_BINS, DISTSIM_K_SCATTER,
     DISTSIM_K_STAGE_EVENTS, DISTSIM_K_SIM_INIT, DISTSIM_K_SIMULATE, DISTSIM_K_SEARCH, DISTSIM_K_TIMELINE,
+    DISTSIM_K_DEDUP, DISTSIM_K_COMM_TIMES,
     DISTSIM_K_COUNT
 };
 int distsim_timing_enable(distsim_ctx *ctx, int on);

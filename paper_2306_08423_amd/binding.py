@@ -9,7 +9,7 @@ from __future__ import annotations
 import ctypes as C
 import os
 from dataclasses import dataclass
-from typing import Dict, Optional
+from typing import Dict, Optional, Tuple
 
 import torch
 
@@ -19,13 +19,14 @@ LIB_PATH = os.path.join(_HERE, "libdistsim_hip.so")
 EXPORTS = (
     "distsim_create", "distsim_destroy", "distsim_last_error", "distsim_workspace_bytes", "distsim_stage_entries",
     "distsim_build_events", "distsim_simulate", "distsim_search_scratch_bytes", "distsim_search",
-    "distsim_timeline", "distsim_timing_enable", "distsim_timing_read", "distsim_kernel_name",
+    "distsim_timeline", "distsim_dedup_workspace_bytes", "distsim_dedup_events", "distsim_comm_event_times",
+    "distsim_timing_enable", "distsim_timing_read", "distsim_kernel_name",
 )
 
 NCOLS = 8
 COL = {"FC": 0, "FA": 1, "BC": 2, "BA": 3, "PF": 4, "PB": 5, "G": 6, "AR": 7}
 KERNELS = ("k_layer_tables", "k_decode", "k_bins", "k_scatter", "k_stage_events",
-           "k_sim_init", "k_simulate", "k_search", "k_timeline")
+           "k_sim_init", "k_simulate", "k_search", "k_timeline", "k_dedup", "k_comm_event_times")
 INT64_MAX = (1 << 63) - 1
 
 
@@ -90,6 +91,13 @@ def load_library():
     lib.distsim_search.restype = C.c_int
     lib.distsim_timeline.argtypes = [C.c_void_p, C.POINTER(_Cluster), C.POINTER(_Events), C.c_int64] + [C.c_void_p] * 7
     lib.distsim_timeline.restype = C.c_int
+    lib.distsim_dedup_workspace_bytes.argtypes = [C.c_int64]
+    lib.distsim_dedup_workspace_bytes.restype = C.c_size_t
+    lib.distsim_dedup_events.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int32, C.c_void_p, C.c_void_p,
+                                         C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+    lib.distsim_dedup_events.restype = C.c_int
+    lib.distsim_comm_event_times.argtypes = [C.c_void_p, C.c_int64] + [C.c_void_p] * 6
+    lib.distsim_comm_event_times.restype = C.c_int
     lib.distsim_timing_enable.argtypes = [C.c_void_p, C.c_int]
     lib.distsim_timing_enable.restype = C.c_int
     lib.distsim_timing_read.argtypes = [C.c_void_p, C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
@@ -299,3 +307,26 @@ def distsim_timeline(ctx: Context, cluster, ev: Events, sel: torch.Tensor, task_
     cl = cluster_struct(cluster)
     ctx.check(ctx.lib.distsim_timeline(ctx.h, C.byref(cl), C.byref(ev.struct), sel.numel(), _ptr(sel), _ptr(task_off),
                                        _ptr(start_ns), _ptr(end_ns), _ptr(ar_start_ns), _ptr(ar_end_ns), _stream()))
+
+
+def distsim_dedup_events(ctx: Context, records: torch.Tensor, event_id: torch.Tensor, rep: torch.Tensor,
+                         num_events: torch.Tensor, workspace: torch.Tensor) -> None:
+    """records [n][K] int64; event_id, rep [n] int32; num_events [1] int64; workspace uint8."""
+    n, K = (int(records.shape[0]), int(records.shape[1])) if records.dim() == 2 else (0, 1)
+    ctx.check(ctx.lib.distsim_dedup_events(ctx.h, _ptr(records), n, K, _ptr(event_id), _ptr(rep), _ptr(num_events),
+                                           _ptr(workspace), workspace.numel(), _stream()))
+
+
+def distsim_comm_event_times(ctx: Context, kind: torch.Tensor, ranks: torch.Tensor, t_a: torch.Tensor,
+                             t_b: torch.Tensor, elapsed_ns: torch.Tensor) -> None:
+    ctx.check(ctx.lib.distsim_comm_event_times(ctx.h, kind.numel(), _ptr(kind), _ptr(ranks), _ptr(t_a), _ptr(t_b),
+                                               _ptr(elapsed_ns), _stream()))
+
+
+def alloc_dedup(ctx: Context, n: int, device) -> Tuple[torch.Tensor, torch.Tensor, torch.Tensor, torch.Tensor]:
+    """event_id, rep, num_events and the workspace for distsim_dedup_events on n records."""
+    nbytes = int(ctx.lib.distsim_dedup_workspace_bytes(n))
+    return (torch.empty(max(n, 1), dtype=torch.int32, device=device),
+            torch.full((max(n, 1),), -1, dtype=torch.int32, device=device),
+            torch.zeros(1, dtype=torch.int64, device=device),
+            torch.empty(max(nbytes, 1), dtype=torch.uint8, device=device))

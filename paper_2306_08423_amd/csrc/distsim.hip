@@ -8,6 +8,7 @@
 
 #include "distsim.h"
 #include "kernels_build.hpp"
+#include "kernels_ingest.hpp"
 #include "kernels_search.hpp"
 #include "kernels_simulate.hpp"
 #include "kernels_timeline.hpp"
@@ -30,6 +31,7 @@ struct distsim_ctx {
 static const char* kKernelNames[DISTSIM_K_COUNT] = {
     "k_layer_tables", "k_decode", "k_bins", "k_scatter",
     "k_stage_events", "k_sim_init", "k_simulate", "k_search", "k_timeline",
+    "k_dedup", "k_comm_event_times",
 };
 
 static int fail(distsim_ctx* ctx, int code, const std::string& msg) {
@@ -300,6 +302,83 @@ int distsim_search(distsim_ctx* ctx, const int64_t* batch_ns, const int64_t* wei
         hipLaunchKernelGGL(k_search_partial<1>, dim3((int)nb), dim3(kSearchBlock), 0, st, batch_ns, weight, C, partial);
         hipLaunchKernelGGL(k_search_final<1>, dim3(1), dim3(kSearchBlock), 0, st, partial, (int)nb, best);
     }
+    HIP_TRY(hipGetLastError());
+    return DISTSIM_OK;
+}
+
+namespace {
+
+struct DedupSpace {
+    int64_t table_size;          // power of two >= 2n
+    int32_t *table, *slot_of, *excl, *block_tot;
+};
+
+size_t carve_dedup(DedupSpace& d, void* base, int64_t n) {
+    size_t off = 0;
+    char* b = (char*)base;
+    auto take = [&](size_t bytes) { void* p = b ? (void*)(b + off) : nullptr; off += align256(bytes); return p; };
+    const int64_t nn = n > 0 ? n : 1;
+    int64_t size = 64;
+    while (size < 2 * nn) size <<= 1;
+    d.table_size = size;
+    d.table = (int32_t*)take((size_t)size * 4);
+    d.slot_of = (int32_t*)take((size_t)nn * 4);
+    d.excl = (int32_t*)take((size_t)nn * 4);
+    d.block_tot = (int32_t*)take((size_t)((nn + kScanBlock - 1) / kScanBlock) * 4);
+    return off;
+}
+
+constexpr int64_t kMaxDedupRecords = 1ll << 28;
+
+}  // namespace
+
+size_t distsim_dedup_workspace_bytes(int64_t n) {
+    if (n < 0 || n > kMaxDedupRecords) return 0;
+    DedupSpace d;
+    return carve_dedup(d, nullptr, n);
+}
+
+int distsim_dedup_events(distsim_ctx* ctx, const int64_t* records, int64_t n, int32_t K, int32_t* event_id,
+                         int32_t* rep, int64_t* num_events, void* workspace, size_t workspace_bytes,
+                         void* hip_stream) {
+    if (!ctx) return DISTSIM_EINVAL;
+    if (n < 0 || K < 1 || !num_events) return fail(ctx, DISTSIM_EINVAL, "bad size or null num_events");
+    if (K > kMaxRecordWords || n > kMaxDedupRecords) return fail(ctx, DISTSIM_ERANGE, "K above 16 or n above 2^28");
+    if (n > 0 && (!records || !event_id || !rep || !workspace)) return fail(ctx, DISTSIM_EINVAL, "null argument");
+    DedupSpace d;
+    if (workspace_bytes < carve_dedup(d, workspace, n) && n > 0) return fail(ctx, DISTSIM_EINVAL, "workspace too small");
+    HIP_TRY(hipSetDevice(ctx->device));
+    hipStream_t st = (hipStream_t)hip_stream;
+    Timer t(ctx, st, DISTSIM_K_DEDUP);
+    const int64_t nb = (n + kScanBlock - 1) / kScanBlock;
+    if (n > 0) {
+        hipLaunchKernelGGL(k_dedup_clear, dim3((unsigned)((d.table_size + 255) / 256)), dim3(256), 0, st, d.table,
+                           d.table_size);
+        hipLaunchKernelGGL(k_dedup_insert, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, records, n, (int)K,
+                           d.table, d.table_size, d.slot_of);
+        hipLaunchKernelGGL(k_dedup_scan_blocks, dim3((unsigned)nb), dim3(kScanBlock), 0, st, d.table, d.slot_of, n,
+                           d.excl, d.block_tot);
+    }
+    hipLaunchKernelGGL(k_dedup_scan_totals, dim3(1), dim3(kScanBlock), 0, st, n > 0 ? d.block_tot : nullptr, nb,
+                       num_events);
+    if (n > 0)
+        hipLaunchKernelGGL(k_dedup_assign, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, d.table, d.slot_of,
+                           d.excl, d.block_tot, n, event_id, rep);
+    HIP_TRY(hipGetLastError());
+    return DISTSIM_OK;
+}
+
+int distsim_comm_event_times(distsim_ctx* ctx, int64_t n, const int32_t* kind, const int32_t* ranks,
+                             const int64_t* t_a, const int64_t* t_b, int64_t* elapsed_ns, void* hip_stream) {
+    if (!ctx) return DISTSIM_EINVAL;
+    if (n < 0) return fail(ctx, DISTSIM_EINVAL, "negative size");
+    if (n == 0) return DISTSIM_OK;
+    if (!kind || !ranks || !t_a || !t_b || !elapsed_ns) return fail(ctx, DISTSIM_EINVAL, "null argument");
+    HIP_TRY(hipSetDevice(ctx->device));
+    hipStream_t st = (hipStream_t)hip_stream;
+    Timer t(ctx, st, DISTSIM_K_COMM_TIMES);
+    hipLaunchKernelGGL(k_comm_event_times, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, n, kind, ranks, t_a,
+                       t_b, elapsed_ns);
     HIP_TRY(hipGetLastError());
     return DISTSIM_OK;
 }

@@ -1,0 +1,109 @@
+"""Pins of the oracle for the steps in front of event-flow generation (Sec. 4.1 event generator,
+Sec. 4.2 profiling events).  CPU only."""
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+from oracle.ingest import comm_event_times, dedup_events
+from workloads import make_comm_profiles, make_operator_records
+
+
+def _i32(x): return np.asarray(x, dtype=np.int32)
+def _i64(x): return np.asarray(x, dtype=np.int64)
+
+
+# ---- Sec. 4.2 --------------------------------------------------------------------------
+
+def test_p2p_is_min_of_send_and_recv():
+    e = comm_event_times(_i32([0, 0, 0]), _i32([2, 2, 2]), _i64([700, 300, 5]), _i64([300, 700, 5]))
+    assert e.tolist() == [300, 300, 5]
+
+
+def test_allreduce_up_to_8_devices_is_the_profile_itself():
+    for n in range(1, 9):
+        assert comm_event_times(_i32([1]), _i32([n]), _i64([123456]), _i64([0])).tolist() == [123456]
+
+
+def test_allreduce_rescale_is_the_ratio_of_ring_volumes():
+    # Sec. 4.2: per-device volume 2(N-1)P/N; the 8-device profile is scaled by volume(N)/volume(8)
+    P = 7 * 3 * 5 * 11 * 13 * 64            # divisible by many N, so that the volumes are integers
+    for n in (9, 12, 16, 24, 64, 1024, 1536):
+        vol_n, vol_8 = Fraction(2 * (n - 1) * P, n), Fraction(2 * 7 * P, 8)
+        t8 = 10 ** 9
+        want = int(Fraction(t8) * vol_n / vol_8)        # truncation
+        assert comm_event_times(_i32([1]), _i32([n]), _i64([t8]), _i64([0])).tolist() == [want]
+    # a bandwidth-only link (time = volume / beta): the rescaled 8-device time is the N-device time
+    beta = 1
+    for n in (16, 48, 112):
+        t8 = 2 * 7 * P // 8 // beta
+        tn = 2 * (n - 1) * P // n // beta
+        assert 2 * (n - 1) * P % n == 0
+        assert comm_event_times(_i32([1]), _i32([n]), _i64([t8]), _i64([0])).tolist() == [tn]
+
+
+def test_allreduce_rescale_limit_and_monotonicity():
+    t8 = 7 * 10 ** 12
+    vals = comm_event_times(_i32([1] * 6), _i32([9, 10, 100, 10 ** 4, 10 ** 6, 2 ** 31 - 1]), _i64([t8] * 6), _i64([0] * 6))
+    assert all(a <= b for a, b in zip(vals[:-1], vals[1:]))
+    assert vals[0] == t8 * 8 * 8 // (7 * 9)
+    assert vals[-1] <= t8 * 8 // 7 and t8 * 8 // 7 - vals[-1] <= t8 * 8 // 7 // 10 ** 9 + 1     # tends to 8/7 t8
+
+
+def test_large_times_do_not_wrap():
+    t8 = (1 << 61) + 12345
+    n = 1000
+    assert comm_event_times(_i32([1]), _i32([n]), _i64([t8]), _i64([0])).tolist() == [t8 * 8 * 999 // 7000]
+
+
+def test_invalid_profile_records():
+    e = comm_event_times(_i32([2, 1, 1, 0, 0, -1]), _i32([4, 0, 4, 2, 2, 2]), _i64([5, 5, -1, -1, 5, 5]), _i64([5, 5, 5, 5, -2, 5]))
+    assert e.tolist() == [-1, -1, -1, -1, -1, -1]
+
+
+# ---- Sec. 4.1 --------------------------------------------------------------------------
+
+def _brute_partition(records):
+    n = len(records)
+    return {(i, j) for i in range(n) for j in range(n) if (records[i] == records[j]).all()}
+
+
+def test_dedup_small_against_all_pairs():
+    rng = np.random.default_rng(5)
+    rec = rng.integers(0, 3, size=(60, 3)).astype(np.int64)
+    eid, rep = dedup_events(rec)
+    assert {(i, j) for i in range(60) for j in range(60) if eid[i] == eid[j]} == _brute_partition(rec)
+    # numbered by first occurrence; rep is that occurrence
+    firsts = [int(np.nonzero(eid == e)[0][0]) for e in range(len(rep))]
+    assert firsts == sorted(firsts) and firsts == rep.tolist()
+    assert eid.max() + 1 == len(rep) == len(np.unique(rec, axis=0))
+
+
+def test_dedup_agrees_with_row_unique_on_a_large_draw():
+    rec = make_operator_records(200_000, 3000)
+    eid, rep = dedup_events(rec)
+    uniq, first, inv = np.unique(rec, axis=0, return_index=True, return_inverse=True)
+    order = np.argsort(first)                       # unique rows by first occurrence
+    rank = np.empty_like(order); rank[order] = np.arange(len(order))
+    assert (eid == rank[inv.reshape(-1)]).all()
+    assert (rep == first[order]).all()
+
+
+def test_dedup_special_cases():
+    eid, rep = dedup_events(np.zeros((0, 4), dtype=np.int64))
+    assert len(eid) == 0 and len(rep) == 0
+    eid, rep = dedup_events(np.full((17, 2), 9, dtype=np.int64))
+    assert eid.tolist() == [0] * 17 and rep.tolist() == [0]
+    rec = np.arange(10, dtype=np.int64).reshape(10, 1)
+    eid, rep = dedup_events(rec)
+    assert eid.tolist() == list(range(10)) and rep.tolist() == list(range(10))
+    # records that differ only in the last word (the intra-/inter-node attribute) are two events
+    eid, _ = dedup_events(_i64([[1, 2, 0], [1, 2, 1], [1, 2, 0]]))
+    assert eid.tolist() == [0, 1, 0]
+
+
+def test_profiled_once_per_event():
+    # "identical operators ... profiled only once": the number of profiling jobs is the number of events
+    rec = make_operator_records(50_000, 400)
+    eid, rep = dedup_events(rec)
+    assert len(rep) <= 400 and (rec[rep[eid]] == rec).all()

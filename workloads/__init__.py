@@ -13,4 +13,6 @@ from .configs import (  # noqa: F401
     subset,
     total_stages,
     CONFIG_NAMES,
+    make_operator_records,
+    make_comm_profiles,
 )

@@ -296,3 +296,40 @@ def subset(w: Workload, idx) -> Workload:
 
 def total_stages(w: Workload) -> int:
     return int(w.cand["pp"].astype(np.int64).sum())
+
+
+# ---------------------------------------------------------------------------------------
+# Inputs of the steps in front of event-flow generation (Sec. 4.1, Sec. 4.2).  No arithmetic of
+# the method here: only the seeded draw of operator records and of profile records.
+
+def make_operator_records(n: int, n_distinct: int, K: int = 6, seed: int = 2306084230 + 11) -> np.ndarray:
+    """n operator records of K int64 words drawn from n_distinct distinct operators with a skewed
+    (Zipf-like) popularity, the way the per-rank sub-models of one training job repeat the same
+    few layer operators: word 0 an operator-name id, words 1..K-2 parameters / shape, word K-1 the
+    intra-/inter-node attribute."""
+    rng = np.random.Generator(np.random.Philox(seed))
+    proto = rng.integers(0, 1 << 40, size=(n_distinct, K), dtype=np.int64)
+    proto[:, 0] = rng.integers(0, 64, size=n_distinct)
+    proto[:, K - 1] = rng.integers(0, 2, size=n_distinct)
+    proto = np.unique(proto, axis=0)
+    rng.shuffle(proto, axis=0)
+    w = 1.0 / np.arange(1, proto.shape[0] + 1)
+    pick = rng.choice(proto.shape[0], size=n, p=w / w.sum())
+    return np.ascontiguousarray(proto[pick])
+
+
+def make_comm_profiles(n: int, seed: int = 2306084230 + 12):
+    """n communication-event profile records: kind (0 p2p, 1 all-reduce, a few invalid), ranks,
+    t_a, t_b in ns."""
+    rng = np.random.Generator(np.random.Philox(seed))
+    kind = rng.choice(np.array([0, 1, 2], dtype=np.int32), size=n, p=[0.45, 0.54, 0.01]).astype(np.int32)
+    ranks = (1 << rng.integers(0, 11, size=n)).astype(np.int32)
+    odd = rng.random(n) < 0.2
+    ranks[odd] = rng.integers(1, 3000, size=int(odd.sum()), dtype=np.int32)
+    ranks[rng.random(n) < 0.005] = 0
+    t_a = rng.integers(0, 1 << 36, size=n, dtype=np.int64)
+    t_b = rng.integers(0, 1 << 36, size=n, dtype=np.int64)
+    big = rng.random(n) < 0.01
+    t_a[big] = rng.integers(1 << 58, 1 << 61, size=int(big.sum()), dtype=np.int64)
+    t_a[rng.random(n) < 0.003] = -5
+    return kind, ranks, t_a, t_b
