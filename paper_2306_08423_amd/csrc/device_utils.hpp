@@ -105,6 +105,13 @@ __device__ __forceinline__ int64_t wave_inclusive_sum(int64_t v) {
     return v;
 }
 
+// Exact conversion of a double that holds an integer of [0, 2^53) (five instructions).
+__device__ __forceinline__ int64_t double_to_i64(double d) {
+    const uint32_t hi = (uint32_t)(d * (1.0 / 4294967296.0));              // truncates
+    const uint32_t lo = (uint32_t)__fma_rn(-(double)hi, 4294967296.0, d);
+    return (int64_t)(((uint64_t)hi << 32) | lo);
+}
+
 // Truncating unsigned division.  Operands below 2^53 (the usual case) go through one
 // correctly rounded fp64 division and an exact integer fix-up of the quotient; anything
 // larger takes the generic 64-bit path.

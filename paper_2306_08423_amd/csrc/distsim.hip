@@ -269,8 +269,8 @@ int distsim_timeline(distsim_ctx* ctx, const distsim_cluster* cluster, const dis
     TimelineOut out{sel, task_off, start_ns, end_ns, ar_start_ns, ar_end_ns};
     {
         Timer t(ctx, st, DISTSIM_K_TIMELINE);
-        hipLaunchKernelGGL(k_timeline, dim3((unsigned)n), dim3(kWave), 0, st, co, cl_dev(*cluster), ca, ws,
-                           events->status, n, out);
+        hipLaunchKernelGGL(k_timeline, dim3((unsigned)((n + kTlChunk - 1) / kTlChunk)), dim3(kTlWaves * kWave), 0, st,
+                           co, cl_dev(*cluster), ca, ws, events->status, n, out);
     }
     HIP_TRY(hipGetLastError());
     return DISTSIM_OK;

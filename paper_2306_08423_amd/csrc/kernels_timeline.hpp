@@ -3,7 +3,7 @@
 // all-reduce events of every stage (Sec. 3.2: "when and which device will compute and
 // communicate").
 #pragma once
-#include "kernels_build.hpp"
+#include "kernels_simulate.hpp"
 
 namespace distsim {
 
@@ -16,139 +16,242 @@ struct TimelineOut {
     int64_t* ar_end;            // [n][kMaxPP] end of its last one
 };
 
-// Levels between two flushes of the staging ring = entries a stage can add to one row meanwhile.
-#ifndef DISTSIM_TL_RING
-#define DISTSIM_TL_RING 8
+// A row of the staging ring takes the entries of kTlFlush levels plus what the last flush left
+// behind because it did not fill an aligned group of kTlFlush entries (32 bytes).
+#ifndef DISTSIM_TL_FLUSH
+#define DISTSIM_TL_FLUSH 4
 #endif
-constexpr int kTlRing = DISTSIM_TL_RING;
+constexpr int kTlFlush = DISTSIM_TL_FLUSH;   // levels between two flushes = entries per aligned write
+constexpr int kTlRing = 2 * kTlFlush;    // ring capacity per row
 constexpr int kTlRow = kTlRing + 1;      // padded: consecutive stages start in different LDS banks
+#ifndef DISTSIM_TL_CHUNK
+#define DISTSIM_TL_CHUNK 16
+#endif
+#ifndef DISTSIM_TL_WAVES
+#define DISTSIM_TL_WAVES 4
+#endif
+constexpr int kTlChunk = DISTSIM_TL_CHUNK;   // selected candidates per workgroup (at most 64)
+constexpr int kTlWaves = DISTSIM_TL_WAVES;
 
-// One wavefront per selected candidate, lane = stage.  The sweep is written with explicit
-// per-level predicates on x = level - s (see the level functions in kernels_simulate.hpp).
-// A stage's tasks of one kind come in micro-batch order, so the entries it produces between two
-// flushes are one run of consecutive micro-batches of its row [kind][stage][.].  Start times are
-// staged in an LDS ring per row; every kTlRing levels the wavefront writes the new runs out,
-// kTlRing lanes per row and several rows per store, so that a store instruction touches a few cache lines
-// instead of one per lane.  The end time is the start plus the row's task duration.
-__global__ __launch_bounds__(64) void k_timeline(CostsDev co, ClusterDev cl, CandDev ca, Workspace ws,
-                                                 const int32_t* __restrict__ status, int64_t n, TimelineOut out) {
-    __shared__ int64_t ring[2][kMaxPP][kTlRow];
-    __shared__ int64_t dur[2][kMaxPP];
-    __shared__ int32_t done[2][kMaxPP], flushed[2][kMaxPP];
-    const int64_t q = blockIdx.x;
-    if (q >= n) return;
-    const int s = threadIdx.x;
-    const int64_t c = out.sel[q];
-    out.ar_start[q * kMaxPP + s] = -1;
-    out.ar_end[q * kMaxPP + s] = -1;
-    if (status[c] != 0) return;                      // uniform: the whole wavefront leaves
+// Per-wavefront staging area.
+struct TlRowMeta { int64_t base, dur; };     // index of the row's entry 0 in start / end; task duration
+struct TlStage {
+    double ring[2][kWave][kTlRow];           // start times of the newest tasks, [kind][lane][micro-batch mod kTlRing]
+    TlRowMeta meta[2][kWave];
+    int2 span[2][kWave];                     // entries [x, y) of the row that the running flush writes
+};
+
+// A workgroup takes kTlChunk consecutive entries of the selection, sorts them by the number of
+// lanes they need (64, 32, ... 1) and packs them into wave-items like simulate does, so that
+// candidates with few stages share a wavefront; its four wavefronts take the items in turn.
+// The sweep is the level sweep of kernels_simulate.hpp (same level functions, bit patterns and
+// task step) with one addition: after each step the lanes that ran a task put its start time
+// into an LDS ring, one row per (kind, lane).  A stage's tasks of one kind come in micro-batch
+// order, so what a row gains between two flushes is one run of consecutive micro-batches; every
+// kTlFlush levels the wavefront writes out, per row, the entries up to the last 32-byte boundary
+// of the output arrays (the rest waits for the next flush; the last flush writes everything),
+// kTlFlush lanes per row and 64 / kTlFlush rows per store: whole aligned sectors instead of one
+// partial cache line per lane.  The end time is the start plus the row's task duration.  The staging area belongs to one
+// wavefront, whose LDS instructions execute in order: between its writes and the reads by other
+// lanes only the compiler has to be kept from reordering (wavefront-scope fences).
+__global__ __launch_bounds__(kTlWaves * kWave) void k_timeline(CostsDev co, ClusterDev cl, CandDev ca, Workspace ws,
+                                                               const int32_t* __restrict__ status, int64_t n,
+                                                               TimelineOut out) {
+    __shared__ TlStage stage_mem[kTlWaves];
+    __shared__ int32_t order[kTlChunk];
+    __shared__ int32_t cls_start[kClasses + 1], cls_count[kClasses], item_start[kClasses + 1];
+    const int lane = lane_id(), wave = threadIdx.x / kWave;
+    const int64_t q0 = (int64_t)blockIdx.x * kTlChunk;
     const int L = co.L;
-    const int pp = ca.pp[c], m = ca.m[c], dp = ca.dp[c], tp = ca.tp[c], sched = ca.schedule[c];
-    const int64_t poff = ca.part_off[c];
-    int v = 0;
-    for (int i = co.V - 1; i >= 0; i--) if (co.variant_tp[i] == tp) v = i;
-    const bool act = s < pp;
-    int lo = 0, hi = 0;
-    if (act) {
-        if (poff >= 0) { lo = ca.part_pool[poff + s]; hi = ca.part_pool[poff + s + 1]; }
-        else { lo = (int)(((int64_t)s * L) / pp); hi = (int)(((int64_t)(s + 1) * L) / pp); }
-    }
-    StageRow r;
-    if (stage_row(cl, ws, L, kWave, s, pp, v, m, dp, tp, lo, hi, r) != 0) return;
-    const int64_t pf_task = cl.blocking ? r.PF : 0, pb_task = cl.blocking ? r.PB : 0;
-    const int64_t Fd = r.FC + r.FA + pf_task, Bd = r.BC + r.BA + pb_task;
-    const int64_t latF = dpp_i64<kDppWaveShr1>(r.PF - pf_task), latB = dpp_i64<kDppWaveShl1>(r.PB - pb_task);
-    const bool hasL = act && s > 0, hasR = act && s + 1 < pp;
-    dur[0][s] = Fd; dur[1][s] = Bd;
-    flushed[0][s] = 0; flushed[1][s] = 0;
 
-    int wq = pp - 1 - s; if (wq > m) wq = m;                 // 1F1B warm-up forwards
-    const int offB = sched == 0 ? m + 2 * pp - 2 - 2 * s : 2 * pp - 1 - 2 * s;
-    const int nlev = 2 * (m + pp - 1);
-    int64_t* st = out.start + out.task_off[q];
-    int64_t* en = out.end + out.task_off[q];
-    const int sub = s / kTlRing, e = s & (kTlRing - 1);           // flush role: row within a group of 4, entry
-    int64_t own = 0;
-    int nF = 0, nB = 0;                                      // tasks of each kind done so far
-    for (int lvl = 0; lvl < nlev; lvl++) {
-        const int64_t fromL = dpp_i64<kDppWaveShr1>(own), fromR = dpp_i64<kDppWaveShl1>(own);
-        const int x = lvl - s, y = x - offB;
-        int jF = -1, jB = -1;
-        if (act && x >= 0) {
-            if (sched == 0) { if (x < m) jF = x; }
-            else if (x <= wq) { if (x < m) jF = x; }
-            else if ((x & 1) == 0 && x > 2 * wq && x < 2 * m) jF = x >> 1;
+    // all-reduce windows default to "none"
+    for (int i = threadIdx.x; i < kTlChunk * kMaxPP; i += blockDim.x) {
+        const int64_t q = q0 + i / kMaxPP;
+        if (q < n) { out.ar_start[q * kMaxPP + i % kMaxPP] = -1; out.ar_end[q * kMaxPP + i % kMaxPP] = -1; }
+    }
+    // counting sort of the chunk by width class (first wavefront)
+    if (wave == 0) {
+        const int64_t q = q0 + lane;
+        int k = -1;
+        if (lane < kTlChunk && q < n) {
+            const int64_t c = out.sel[q];
+            if (status[c] == 0) {
+                const int pp = ca.pp[c];
+                int sh = 0;
+                while ((1 << sh) < pp) sh++;
+                k = 6 - sh;
+            }
         }
-        if (act && y >= 0) {
-            if (sched == 0) { if (y < m) jB = y; }
-            else if ((y & 1) == 0 && y < 2 * m) jB = y >> 1;
+        int at = 0, items = 0;
+        for (int kk = 0; kk < kClasses; kk++) {
+            const uint64_t b = __builtin_amdgcn_ballot_w64(k == kk);
+            const int cnt = __popcll(b);
+            if (k == kk) order[at + __popcll(b & ((1ull << lane) - 1))] = lane;
+            if (lane == 0) { cls_start[kk] = at; cls_count[kk] = cnt; item_start[kk] = items; }
+            at += cnt;
+            items += (cnt + (1 << kk) - 1) >> kk;
         }
-        if (jF >= 0) {
-            int64_t t0 = own;
-            if (hasL && fromL + latF > t0) t0 = fromL + latF;
-            own = t0 + Fd;
-            ring[0][s][jF & (kTlRing - 1)] = t0;
-            nF = jF + 1;
-        } else if (jB >= 0) {
-            int64_t t0 = own;
-            if (hasR && fromR + latB > t0) t0 = fromR + latB;
-            own = t0 + Bd;
-            ring[1][s][jB & (kTlRing - 1)] = t0;
-            nB = jB + 1;
+        if (lane == 0) { cls_start[kClasses] = at; item_start[kClasses] = items; }
+    }
+    __syncthreads();
+
+    TlStage& sm = stage_mem[wave];
+    const double ninf = -__builtin_huge_val();
+    const int total_items = item_start[kClasses];
+    for (int w = wave; w < total_items; w += kTlWaves) {
+        int k = 0;
+        while (w >= item_start[k + 1]) k++;
+        const int sh = 6 - k, width = 1 << sh;
+        const int g = lane >> sh, s = lane & (width - 1);
+        const int slot = ((w - item_start[k]) << k) + g;          // position inside the class
+        const bool have = slot < cls_count[k];
+        const int64_t q = q0 + (have ? order[cls_start[k] + slot] : 0);
+        const int64_t c = have ? out.sel[q] : 0;
+        int pp = 0, m = 0, dp = 1, tp = 1, sched = 0;
+        int64_t poff = -1;
+        if (have) { pp = ca.pp[c]; m = ca.m[c]; dp = ca.dp[c]; tp = ca.tp[c]; sched = ca.schedule[c]; poff = ca.part_off[c]; }
+        int v = 0;
+        for (int i = co.V - 1; i >= 0; i--) if (co.variant_tp[i] == tp) v = i;
+        bool act = s < pp;
+        int lo = 0, hi = 0;
+        if (act) {
+            if (poff >= 0) { lo = ca.part_pool[poff + s]; hi = ca.part_pool[poff + s + 1]; }
+            else { lo = (int)(((int64_t)s * L) / pp); hi = (int)(((int64_t)(s + 1) * L) / pp); }
         }
-        if ((lvl & (kTlRing - 1)) != kTlRing - 1 && lvl != nlev - 1) continue;
-        // flush: rows [kind][stage], the run [flushed, done) of each
-        done[0][s] = nF; done[1][s] = nB;
-        __syncthreads();
-        for (int kind = 0; kind < 2; kind++) {
-            if (__builtin_amdgcn_ballot_w64(done[kind][s] > flushed[kind][s]) == 0) continue;
-            for (int r0 = 0; r0 < pp; r0 += kWave / kTlRing) {
-                const int row = r0 + sub;
-                if (row < pp) {
-                    const int j = flushed[kind][row] + e;
-                    if (j < done[kind][row]) {
-                        const int64_t t0 = ring[kind][row][j & (kTlRing - 1)];
-                        const int64_t i = ((int64_t)kind * pp + row) * m + j;
-                        st[i] = t0;
-                        en[i] = t0 + dur[kind][row];
+        StageRow r;
+        // a candidate whose partition or range check fails gets no entries
+        if (stage_row(cl, ws, L, width, s, pp, v, m, dp, tp, lo, hi, r) != 0) act = false;
+        if (!act) { pp = 0; m = 0; }
+        const int64_t pf_task = cl.blocking ? r.PF : 0, pb_task = cl.blocking ? r.PB : 0;
+        const int64_t Fd_i = r.FC + r.FA + pf_task, Bd_i = r.BC + r.BA + pb_task;
+        const double Fd = (double)Fd_i, Bd = (double)Bd_i;
+        double pfL = from_prev_lane((double)(r.PF - pf_task)), pbR = from_next_lane((double)(r.PB - pb_task));
+        if (!(act && s > 0)) pfL = ninf;
+        if (!(act && s + 1 < pp)) pbR = ninf;
+        const int64_t off = act ? out.task_off[q] : 0;
+        const int64_t baseF = off + (int64_t)s * m, baseB = off + ((int64_t)pp + s) * m;   // rows [kind][stage][0]
+        sm.meta[0][lane] = TlRowMeta{baseF, Fd_i};
+        sm.meta[1][lane] = TlRowMeta{baseB, Bd_i};
+
+        // level windows of this lane on x = level - s (see kernels_simulate.hpp)
+        int f1hi, f2lo = 1, f2hi = 0, blo, bhi;
+        if (sched == 0) {
+            f1hi = m - 1;
+            blo = m + 2 * pp - 2 - 2 * s; bhi = blo + m - 1;
+        } else {
+            int wq = pp - 1 - s; if (wq > m) wq = m;
+            f1hi = wq < m - 1 ? wq : m - 1;
+            f2lo = 2 * wq + 2; f2hi = 2 * m - 2;
+            blo = 2 * pp - 1 - 2 * s; bhi = blo + 2 * m - 2;
+        }
+        const int nlev = wave_max_i32(act ? 2 * (m + pp - 1) : 0);
+        double own = 0.0;
+        int nF = 0, nB = 0, fF = 0, fB = 0;                   // tasks run / written out, per kind
+        uint64_t kmask = 0, kmask2 = 0;
+        for (int l0 = 0; l0 < nlev; l0 += 32) {
+            const int x0 = l0 - s;
+            const uint32_t even_x = (x0 & 1) ? 0x55555555u : 0xaaaaaaaau;
+            uint32_t PFb = level_bits(-x0, f1hi - x0) | (level_bits(f2lo - x0, f2hi - x0) & even_x);
+            uint32_t PBb = level_bits(blo - x0, bhi - x0);
+            if (sched != 0) PBb &= ((blo - x0) & 1) ? 0x55555555u : 0xaaaaaaaau;
+            if (!act) { PFb = 0; PBb = 0; }
+            const bool anyF = wave_or_u32(PFb) != 0, anyB = wave_or_u32(PBb) != 0;
+            const int kend = nlev - l0 < 32 ? nlev - l0 : 32;
+            for (int kk = 0; kk < kend; kk++) {
+                if (anyF && anyB) {
+                    double tl = from_prev_lane(own), tr = from_next_lane(own);
+                    DISTSIM_STEPFB1(PFb, PBb, own, tl, tr, pfL, pbR, Fd, Bd);
+                    if ((kmask >> lane) & 1) { sm.ring[0][lane][nF & (kTlRing - 1)] = tl; nF++; }
+                    if ((kmask2 >> lane) & 1) { sm.ring[1][lane][nB & (kTlRing - 1)] = tr; nB++; }
+                } else if (anyF) {
+                    double tl = from_prev_lane(own);
+                    DISTSIM_STEP1(PFb, own, tl, pfL, Fd);
+                    if ((kmask >> lane) & 1) { sm.ring[0][lane][nF & (kTlRing - 1)] = tl; nF++; }
+                } else if (anyB) {
+                    double tr = from_next_lane(own);
+                    DISTSIM_STEP1(PBb, own, tr, pbR, Bd);
+                    if ((kmask >> lane) & 1) { sm.ring[1][lane][nB & (kTlRing - 1)] = tr; nB++; }
+                }
+                const bool last = l0 + kk == nlev - 1;
+                if ((kk & (kTlFlush - 1)) != kTlFlush - 1 && !last) continue;
+                // flush: per row the entries [flushed, upto), upto = done rounded down to a sector
+                // boundary of the output (done itself in the last flush, which may take two rounds)
+                constexpr int kGroups = kTlFlush, kRowsPer = kWave / kTlFlush;   // stores per kind, rows per store
+                for (int round = 0; round < (last ? 2 : 1); round++) {
+                    int upF = last ? nF : nF - (int)((baseF + nF) & (kTlFlush - 1));
+                    int upB = last ? nB : nB - (int)((baseB + nB) & (kTlFlush - 1));
+                    if (upF > fF + kTlFlush) upF = fF + kTlFlush;
+                    if (upB > fB + kTlFlush) upB = fB + kTlFlush;
+                    sm.span[0][lane] = make_int2(fF, upF);
+                    sm.span[1][lane] = make_int2(fB, upB);
+                    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+                    const int rsub = lane / kTlFlush, e = lane & (kTlFlush - 1);
+                    for (int kind = 0; kind < 2; kind++) {
+                        if (__builtin_amdgcn_ballot_w64(kind ? upB > fB : upF > fF) == 0) continue;
+                        // all LDS reads of the kGroups stores first, then the stores
+                        int2 sp[kGroups];
+                        TlRowMeta mt[kGroups];
+                        double val[kGroups];
+#pragma unroll
+                        for (int gi = 0; gi < kGroups; gi++) {
+                            sp[gi] = sm.span[kind][gi * kRowsPer + rsub];
+                            mt[gi] = sm.meta[kind][gi * kRowsPer + rsub];
+                        }
+#pragma unroll
+                        for (int gi = 0; gi < kGroups; gi++)
+                            val[gi] = sm.ring[kind][gi * kRowsPer + rsub][(sp[gi].x + e) & (kTlRing - 1)];
+#pragma unroll
+                        for (int gi = 0; gi < kGroups; gi++) {
+                            const int j = sp[gi].x + e;
+                            if (j < sp[gi].y) {
+                                const int64_t t0 = double_to_i64(val[gi]);
+                                out.start[mt[gi].base + j] = t0;
+                                out.end[mt[gi].base + j] = t0 + mt[gi].dur;
+                            }
+                        }
                     }
+                    if (upF > fF) fF = upF;
+                    if (upB > fB) fB = upB;
+                    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
                 }
             }
         }
-        __syncthreads();
-        flushed[0][s] = nF; flushed[1][s] = nB;
-    }
-    // data-parallel modelling: window of the gradient all-reduce events on this device
-    if (!(act && dp > 1 && r.G > 0)) return;
-    const int64_t endB = own;
-    if (cl.bucket <= 0) {
-        out.ar_start[q * kMaxPP + s] = endB;
-        out.ar_end[q * kMaxPP + s] = endB + allreduce_ns(cl, dp, r.G);
-        return;
-    }
-    const size_t vr = (size_t)v * (L + 1), rr = (size_t)(v * kMaxPP + pp - 1) * (L + 1);
-    const int64_t startB = endB - Bd;
-    const int64_t tot_hi = ws.pbc[vr + hi] + ws.pba[rr + hi];
-    const int64_t ar_cap = allreduce_ns(cl, dp, cl.bucket);
-    int64_t acc = 0, t = 0, first = -1;
-    for (int l = hi - 1; l >= lo; l--) {
-        const int64_t ready = startB + (tot_hi - (ws.pbc[vr + l] + ws.pba[rr + l]));
-        acc += ws.pg[vr + l + 1] - ws.pg[vr + l];
-        const int64_t k = (int64_t)udiv64((uint64_t)acc, (uint64_t)cl.bucket);
-        if (k > 0) {
-            const int64_t b0 = t > ready ? t : ready;
-            if (first < 0) first = b0;
-            t = b0 + k * ar_cap;
-            acc -= k * cl.bucket;
+        (void)kmask; (void)kmask2;
+
+        // data-parallel modelling: window of the gradient all-reduce events on this device
+        if (act && dp > 1 && r.G > 0) {
+            const int64_t endB = double_to_i64(own);
+            if (cl.bucket <= 0) {
+                out.ar_start[q * kMaxPP + s] = endB;
+                out.ar_end[q * kMaxPP + s] = endB + allreduce_ns(cl, dp, r.G);
+            } else {
+                const size_t vr = (size_t)v * (L + 1), rr = (size_t)(v * kMaxPP + pp - 1) * (L + 1);
+                const int64_t startB = endB - Bd_i;
+                const int64_t tot_hi = ws.pbc[vr + hi] + ws.pba[rr + hi];
+                const int64_t ar_cap = allreduce_ns(cl, dp, cl.bucket);
+                int64_t acc = 0, t = 0, first = -1;
+                for (int l = hi - 1; l >= lo; l--) {
+                    const int64_t ready = startB + (tot_hi - (ws.pbc[vr + l] + ws.pba[rr + l]));
+                    acc += ws.pg[vr + l + 1] - ws.pg[vr + l];
+                    const int64_t kb = (int64_t)udiv64((uint64_t)acc, (uint64_t)cl.bucket);
+                    if (kb > 0) {
+                        const int64_t b0 = t > ready ? t : ready;
+                        if (first < 0) first = b0;
+                        t = b0 + kb * ar_cap;
+                        acc -= kb * cl.bucket;
+                    }
+                    if (l == lo && acc > 0) {
+                        const int64_t b0 = t > ready ? t : ready;
+                        if (first < 0) first = b0;
+                        t = b0 + allreduce_ns(cl, dp, acc);
+                    }
+                }
+                out.ar_start[q * kMaxPP + s] = first;
+                out.ar_end[q * kMaxPP + s] = t;
+            }
         }
-        if (l == lo && acc > 0) {
-            const int64_t b0 = t > ready ? t : ready;
-            if (first < 0) first = b0;
-            t = b0 + allreduce_ns(cl, dp, acc);
-        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");   // the staging area is reused by the next item
     }
-    out.ar_start[q * kMaxPP + s] = first;
-    out.ar_end[q * kMaxPP + s] = t;
 }
 
 }  // namespace distsim
