@@ -45,6 +45,9 @@ extern "C" {
 
 #define DISTSIM_GPIPE    0     /* all forwards, then all backwards (Sec. 2.1.3)              */
 #define DISTSIM_1F1B     1     /* Dapple early backward: at most pp - s micro-batches alive  */
+#define DISTSIM_1F1B_ASYNC 2   /* asynchronous pipeline (Sec. 7, discussion of new algorithms):
+                                  the Dapple order without the global synchronisation event, i.e.
+                                  no gradient all-reduce event is appended to the device lists   */
 
 /* per-candidate status written by distsim_build_events */
 #define DISTSIM_ST_OK       0
@@ -113,7 +116,7 @@ typedef struct {
  * Struct of arrays, device pointers, C entries each. */
 typedef struct {
     const int32_t *dp, *tp, *pp, *m;
-    const uint8_t *schedule;         /* DISTSIM_GPIPE / DISTSIM_1F1B                              */
+    const uint8_t *schedule;         /* DISTSIM_GPIPE / DISTSIM_1F1B / DISTSIM_1F1B_ASYNC          */
     const int64_t *part_off;         /* -1: uniform split, stage s owns layers [s L / pp, (s+1) L / pp);
                                         else offset into part_pool of b0..bpp                    */
     const uint8_t *part_pool;        /* concatenated boundaries; may be NULL if never referenced  */

@@ -28,6 +28,9 @@
  *      bucket size the gradient all-reduce is split into buckets that start as
  *      soon as the last micro-batch's backward has produced their bytes
  *      (extension; bucket = 0 gives the paper's single trailing event).
+ *      Schedule 2 is the asynchronous pipeline of the paper's discussion of new
+ *      algorithms (Sec. 7): the Dapple order "only without a global synchronize
+ *      event", i.e. no gradient all-reduce event is appended.
  *   4. analysis -- batch (iteration) time = time of the last event; per-stage
  *      computation / communication busy time = sum of the durations of the
  *      events on that device's list; utilisation = busy / batch (Sec. 3.2,
@@ -196,7 +199,7 @@ static void simulate_one(const costs_t *co, const cluster_t *cl,
     res->num_events = 0;
 
     /* --- validation ("unreachable" configurations, Sec. 6) --- */
-    if (dp < 1 || tp < 1 || pp < 1 || m < 1 || m > MAX_M || (sched != 0 && sched != 1)) return;
+    if (dp < 1 || tp < 1 || pp < 1 || m < 1 || m > MAX_M || (sched != 0 && sched != 1 && sched != 2)) return;
     if ((int64_t)dp * tp * pp != cl->num_devices) return;
     if (pp > L || pp > MAX_PP) return;
     int v = -1;
@@ -257,6 +260,7 @@ static void simulate_one(const costs_t *co, const cluster_t *cl,
     memset(sc->arrF, 0, (size_t)narr);
     memset(sc->arrB, 0, (size_t)narr);
     build_schedule(pp, m, sched, sc->task_kind, sc->task_mb);
+    const int sync = sched != 2;        /* schedule 2: no global synchronisation (gradient all-reduce) event */
 
     heap_t *h = &sc->heap;
     h->n = 0; h->seq = 0;
@@ -296,7 +300,7 @@ static void simulate_one(const costs_t *co, const cluster_t *cl,
                         if (tp > 1) { t += ba[l]; mb_[s__] += ba[l]; }                  \
                         int64_t x = alltoall_ns(cl, dp, a2a[l]);                        \
                         t += x; mb_[s__] += x;                                          \
-                        if (last_bwd && cap > 0 && dp > 1)                              \
+                        if (last_bwd && cap > 0 && dp > 1 && sync)                      \
                             heap_push(h, t, EV_GRAD_READY, s__, j, l);                  \
                     }                                                                   \
                 }                                                                       \
@@ -330,7 +334,7 @@ static void simulate_one(const costs_t *co, const cluster_t *cl,
                 heap_push(h, now + (cl->p2p_blocking ? 0 : pb[s]), EV_ARRIVE_B, s - 1, j, 0);
                 mb_[s] += pb[s]; nev++;
             }
-            if (next[s] == 2 * m && dp > 1 && cap == 0) {   /* trailing gradient all-reduce */
+            if (next[s] == 2 * m && dp > 1 && cap == 0 && sync) {   /* trailing gradient all-reduce */
                 int64_t G = 0;
                 for (int l = bnd[s]; l < bnd[s + 1]; l++) G += grad[l];
                 if (G > 0) {

@@ -140,7 +140,7 @@ __global__ __launch_bounds__(kDecodeBlock) void k_decode(CostsDev co, ClusterDev
         const int32_t dp = ca.dp[c], tp = ca.tp[c], pp = ca.pp[c], m = ca.m[c];
         const int sched = ca.schedule[c];
         const int64_t poff = ca.part_off[c];
-        bool ok = dp >= 1 && tp >= 1 && pp >= 1 && m >= 1 && m <= kMaxM && sched <= 1 && pp <= co.L && pp <= kMaxPP;
+        bool ok = dp >= 1 && tp >= 1 && pp >= 1 && m >= 1 && m <= kMaxM && sched <= 2 && pp <= co.L && pp <= kMaxPP;
         ok = ok && (int64_t)dp * tp * pp == (int64_t)cl.num_devices;
         ok = ok && (poff == -1 || (poff >= 0 && ca.part_pool != nullptr && poff + pp + 1 <= ca.part_pool_len));
         int v = -1;
@@ -152,7 +152,7 @@ __global__ __launch_bounds__(kDecodeBlock) void k_decode(CostsDev co, ClusterDev
             int k = 0;                               // class 0 = 64 lanes ... class 6 = 1 lane
             while (k < 6 && (32 >> k) >= pp) k++;
             const int mb = (m < kMBins ? m : kMBins) - 1;
-            const int bin = k * kBinsPerClass + sched * kMBins + (kMBins - 1 - mb);
+            const int bin = k * kBinsPerClass + (sched != 0 ? kMBins : 0) + (kMBins - 1 - mb);   // ordered by sweep shape
             rank[j] = atomicAdd(&hist[bin], 1);
             key[j] = bin | (v << 24);
         } else {
@@ -409,8 +409,9 @@ __global__ __launch_bounds__(256) void k_stage_events(CostsDev co, ClusterDev cl
         const bool act = s < pp;
         StageRow r;
         const int drop = stage_row(cl, ws, L, width, s, pp, v, m, dp, (int)d.spare, cur.lo, cur.hi, r);
-        const int64_t AR = allreduce_ns(cl, dp, r.G);
-        int64_t nar = (act && !drop) ? count_allreduce_events(cl, ws, L, v, dp, cur.lo, cur.hi, r.G) : 0;
+        const bool sync = ((d.meta >> 8) & 0xff) != 2;      // the asynchronous schedule has no gradient all-reduce
+        const int64_t AR = sync ? allreduce_ns(cl, dp, r.G) : 0;
+        int64_t nar = (act && !drop && sync) ? count_allreduce_events(cl, ws, L, v, dp, cur.lo, cur.hi, r.G) : 0;
         if (more) stage_fetch_bounds(ca, L, nx);
         nar = group_sum(nar, width);
         const int lo_w = drop ? 0 : cur.lo, hi_w = drop ? 0 : cur.hi;

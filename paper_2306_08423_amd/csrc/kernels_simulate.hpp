@@ -194,7 +194,8 @@ __device__ __forceinline__ void simulate_items(const ClusterDev& cl, const CandD
         StageSums r;
         const int drop = stage_sums(cl, ws, L, width, s, pp, v, d[u].m, dp, (int)d[u].spare, lo, hi, r);
         if (drop && act && s == 0) { ev.status[c] = drop; ev.num_events[c] = 0; out.batch_ns[c] = INT64_MAX; }
-        const bool has_ar = act && dp > 1 && r.G > 0;       // gradient bytes to reduce over dp > 1 ranks
+        // gradient bytes to reduce over dp > 1 ranks; the asynchronous schedule has no such event
+        const bool has_ar = act && dp > 1 && r.G > 0 && sched != 2;
         // p2p on the incoming edges (the neighbours' outgoing events): latency of the edge, or,
         // when the sender is occupied by it, part of the sender's task; -inf = no edge
         const int64_t pf_task = cl.blocking ? r.PF : 0, pb_task = cl.blocking ? r.PB : 0;
@@ -208,7 +209,7 @@ __device__ __forceinline__ void simulate_items(const ClusterDev& cl, const CandD
         // what only the epilogue needs waits in LDS
         park.comp[u][slot] = r.CP;                                         // computation per micro-batch
         park.comm[u][slot] = r.FT + r.BT - r.CP + r.PF + r.PB;             // communication per micro-batch
-        park.ar[u][slot] = cl.bucket > 0 ? 0 : allreduce_ns(cl, dp, r.G);  // single trailing all-reduce
+        park.ar[u][slot] = (cl.bucket > 0 || !has_ar) ? 0 : allreduce_ns(cl, dp, r.G);  // single trailing all-reduce
         park.cand[u][slot] = (int32_t)c;
         park.dp[u][slot] = dp;
         park.misc[u][slot] = lo | (hi << 8) | ((int)has_ar << 16) | ((drop ? 1 : 0) << 17) | (v << 18);

@@ -219,7 +219,7 @@ __global__ __launch_bounds__(kTlWaves * kWave) void k_timeline(CostsDev co, Clus
         (void)kmask; (void)kmask2;
 
         // data-parallel modelling: window of the gradient all-reduce events on this device
-        if (act && dp > 1 && r.G > 0) {
+        if (act && dp > 1 && r.G > 0 && sched != 2) {
             const int64_t endB = double_to_i64(own);
             if (cl.bucket <= 0) {
                 out.ar_start[q * kMaxPP + s] = endB;

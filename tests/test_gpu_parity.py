@@ -166,6 +166,31 @@ def test_timeline_dump(H, oracle_mod):
     _timeline_parity(H, oracle_mod, w, [0, 1, 2])
 
 
+def test_async_schedule(H, oracle_mod):
+    """Schedule 2 (Dapple order without the gradient all-reduce event) next to the other two, with and
+    without buckets and the stage table, and in the timeline dump."""
+    _say("[case] async schedule")
+    w0 = make_workload("gpt48")
+    rng = np.random.default_rng(12)
+    cand = {k: v.copy() for k, v in w0.cand.items()}
+    cand["schedule"] = rng.integers(0, 3, len(cand["schedule"])).astype(np.uint8)
+    for bucket in (0, 25 << 20):
+        cl = dict(w0.cluster); cl["dp_bucket_bytes"] = bucket
+        w = Workload(f"gpt48+async bucket={bucket}", w0.costs, cl, cand)
+        ora = oracle_mod.simulate(w, nthreads=NT)
+        assert ((ora["status"] == 0) & (cand["schedule"] == 2)).sum() > 1000
+        H.assert_same(H.run_hip(w), ora, what=w.name)
+        H.assert_same(H.run_hip(w, table=False), ora, what=w.name + " no table")
+    sel = np.nonzero(cand["schedule"] == 2)[0][::40]
+    _timeline_parity(H, oracle_mod, w, sel)
+    # an unknown schedule is an invalid candidate
+    cand["schedule"][:5] = 3
+    w = Workload("gpt48+bad schedule", w0.costs, w0.cluster, cand)
+    hip = H.run_hip(w)
+    assert (hip["status"][:5] == 1).all()
+    H.assert_same(hip, oracle_mod.simulate(w, nthreads=NT), what=w.name)
+
+
 def test_runs_are_deterministic(H):
     _say("[case] determinism")
     w = make_workload("gpt48")
@@ -227,7 +252,7 @@ def test_invalid_range_and_capacity_status(H, oracle_mod):
     costs = mk_costs([10] * 4, [20] * 4, tps=(1,))
     rows = [
         (1, 1, 2, 4, 1, None), (2, 1, 2, 4, 1, None), (1, 2, 1, 4, 1, None), (1, 1, 2, 0, 1, None),
-        (1, 1, 2, 4, 1, [0, 0, 4]), (1, 1, 2, 4, 1, [0, 2, 3]), (1, 1, 2, 4, 2, None), (1, 1, 2, 4, 0, [0, 1, 4]),
+        (1, 1, 2, 4, 1, [0, 0, 4]), (1, 1, 2, 4, 1, [0, 2, 3]), (1, 1, 2, 4, 3, None), (1, 1, 2, 4, 0, [0, 1, 4]),
         (1, 1, 2, (1 << 16) + 1, 0, None), (-1, -1, 2, 4, 0, None), (1, 1, 0, 4, 0, None),
     ]
     w = mk(costs, mk_cluster(2), rows)

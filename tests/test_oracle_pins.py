@@ -518,6 +518,37 @@ def test_dp_changes_only_the_tail(oracle_mod):
             assert list(ends[dp][2] - ends[1][2]) == ar
 
 
+def test_async_schedule_is_dapple_without_the_global_sync(oracle_mod):
+    """Sec. 7 (new algorithms): an asynchronous pipeline keeps the schedule "only without a global
+    synchronize event (usually an all-reduce event)"."""
+    L = 8
+    rng = np.random.default_rng(4)
+    costs = mk_costs(rng.integers(1, 999, L).tolist(), rng.integers(1, 999, L).tolist(),
+                     act=[400] * L, grad=rng.integers(1, 10**6, L).tolist())
+    for bucket in (0, 3000):
+        cl = mk_cluster(16, g=1 << 20, alpha=(50, 50), beta=(200, 200), bucket=bucket)
+        sync = one(oracle_mod, costs, cl, (4, 1, 4, 6, 1, None), timeline=True)
+        asyn = one(oracle_mod, costs, cl, (4, 1, 4, 6, 2, None), timeline=True)
+        assert int(asyn["status"][0]) == 0
+        # same device lists up to the all-reduce events
+        assert np.array_equal(sync["start"], asyn["start"]) and np.array_equal(sync["end"], asyn["end"])
+        assert (asyn["ar_window"] == -1).all() and (sync["ar_window"] >= 0).all()
+        # the iteration ends with the last backward, and no all-reduce is accounted
+        assert int(asyn["batch_ns"][0]) == int(asyn["end"].max()) < int(sync["batch_ns"][0])
+        assert np.array_equal(asyn["comp_busy_ns"], sync["comp_busy_ns"])
+        assert (asyn["comm_busy_ns"] < sync["comm_busy_ns"]).all()
+        n_task, n_p2p = 2 * 6 * 4, 2 * 6 * 3
+        assert int(asyn["num_events"][0]) == n_task + n_p2p
+    # with one replica (no gradient exchange) the two schedules are the same thing
+    cl = mk_cluster(4, g=1 << 20, alpha=(50, 50), beta=(200, 200))
+    a = one(oracle_mod, costs, cl, (1, 1, 4, 6, 1, None))
+    b = one(oracle_mod, costs, cl, (1, 1, 4, 6, 2, None))
+    for k in ("batch_ns", "num_events", "comp_busy_ns", "comm_busy_ns"):
+        assert np.array_equal(a[k], b[k])
+    # unknown schedules stay invalid
+    assert int(one(oracle_mod, costs, cl, (1, 1, 4, 6, 3, None))["status"][0]) == 1
+
+
 # ----------------------------------------------------------------------------- paper facts
 
 def test_paper_grid_has_15_settings():
@@ -557,7 +588,7 @@ def test_invalid_and_range_status(oracle_mod):
         (1, 1, 2, 0, 1, None),          # m < 1
         (1, 1, 2, 4, 1, [0, 0, 4]),     # empty stage
         (1, 1, 2, 4, 1, [0, 2, 3]),     # does not end at L
-        (1, 1, 2, 4, 2, None),          # unknown schedule
+        (1, 1, 2, 4, 3, None),          # unknown schedule
         (1, 1, 2, 4, 0, [0, 1, 4]),     # ok
     ]
     r = oracle_mod.simulate(mk(costs, mk_cluster(2), rows))
