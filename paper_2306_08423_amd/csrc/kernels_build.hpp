@@ -122,7 +122,10 @@ __global__ void k_clear_bins(Workspace ws) {
 // only the non-empty bins go to the global counters (one atomic each), which hands the
 // workgroup its base rank in every bin.  rank[c] is the candidate's position inside its bin.
 constexpr int kDecodeBlock = 1024;
-constexpr int kDecodePer = 16;
+#ifndef DISTSIM_DECODE_PER
+#define DISTSIM_DECODE_PER 4
+#endif
+constexpr int kDecodePer = DISTSIM_DECODE_PER;
 constexpr int kDecodeChunk = kDecodeBlock * kDecodePer;
 
 __global__ __launch_bounds__(kDecodeBlock) void k_decode(CostsDev co, ClusterDev cl, CandDev ca, int64_t C,
