@@ -64,6 +64,7 @@ def main() -> int:
     ap.add_argument("--ingest", type=int, default=4_000_000,
                     help="also time the steps in front of event generation (operator dedup, communication "
                          "event times) on this many seeded records (0 = skip)")
+    ap.add_argument("--no-graph", action="store_true", help="skip the HIP-graph replay of the step")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one 1 GiB device-to-device copy (known traffic, for scaling HBM counters)")
     args = ap.parse_args()
@@ -105,6 +106,29 @@ def main() -> int:
     dt = time.perf_counter() - t0
     kt = ctx.timing_read()
     ctx.timing_enable(False)
+
+    # the same step recorded once into a HIP graph and replayed (the calls allocate nothing and never
+    # synchronise): what a caller in a tight loop pays when launch overhead matters
+    graph = None
+    if not args.no_graph:
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            step()
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=side):
+            step()
+        g.replay()
+        torch.cuda.synchronize()
+        t0g = time.perf_counter()
+        for _ in range(args.steps):
+            g.replay()
+        torch.cuda.synchronize()
+        dtg = time.perf_counter() - t0g
+        graph = {"ms_per_step": dtg / args.steps * 1e3, "value": dw.C * args.steps / dtg, "unit": "strategies/s"}
+        del g
 
     timeline = None
     if args.timeline > 0:
@@ -228,7 +252,7 @@ def main() -> int:
         "events_per_s": nev * args.steps / dt, "stage_tasks_per_s": tasks * args.steps / dt,
         "kernel_ms": {k: (v[0] / max(v[1], 1)) * (v[1] / args.steps) for k, v in kt.items()},
         "roofline": roofline, "roofline_hbm": roofline_hbm,
-        "timeline": timeline, "ingest": ingest, "cpu_baseline": cpu_baseline, "parity": parity,
+        "graph_replay": graph, "timeline": timeline, "ingest": ingest, "cpu_baseline": cpu_baseline, "parity": parity,
     }
     print(json.dumps(line))
     return 0

@@ -191,6 +191,51 @@ def test_async_schedule(H, oracle_mod):
     H.assert_same(hip, oracle_mod.simulate(w, nthreads=NT), what=w.name)
 
 
+def test_graph_capture_and_replay(H, oracle_mod):
+    """The three calls allocate nothing and never synchronise, so a caller can record them into a
+    HIP graph; every replay (with eager work and synchronisation in between) must give the eager result."""
+    import torch
+    import paper_2306_08423_amd as ds
+    _say("[case] graph capture")
+    w = make_workload("gpt48")
+    c = H.ctx()
+    dw = ds.upload(w, c.device)
+    ev = ds.alloc_events(c, dw.L, dw.V, dw.C, ds.stage_entries(w.cand["pp"]), table=False)
+    out = ds.alloc_outputs(c, ev, util=True)
+    best, scratch = ds.alloc_search(c, dw.C)
+
+    def step():
+        ds.distsim_build_events(c, dw, ev)
+        ds.distsim_simulate(c, dw.cluster, ev, out)
+        ds.distsim_search(c, out.batch_ns, dw.C, best, scratch)
+
+    step()
+    torch.cuda.synchronize()
+    want = (out.batch_ns.clone(), out.comp_busy_ns.clone(), out.comm_busy_ns.clone(), best.clone())
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()                                             # warm-up on the capture stream
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=side):
+        step()
+    for rep in range(3):
+        out.batch_ns.fill_(-3); out.comp_busy_ns.fill_(-3); out.comm_busy_ns.fill_(-3); best.fill_(-3)
+        ev.status.fill_(-3)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        got = (out.batch_ns, out.comp_busy_ns, out.comm_busy_ns, best)
+        for a, b in zip(got, want):
+            assert torch.equal(a, b), rep
+        step()                                             # eager work between replays
+        torch.cuda.synchronize()
+    ora = oracle_mod.simulate(w, nthreads=NT)
+    assert np.array_equal(out.batch_ns.cpu().numpy()[:dw.C], ora["batch_ns"])
+
+
 def test_runs_are_deterministic(H):
     _say("[case] determinism")
     w = make_workload("gpt48")
