@@ -78,6 +78,17 @@ def test_sampled_parity_full_size_launch(H, oracle_mod, name, nsample):
     assert np.all(hip["num_events"] >= 2 * m * pp + 2 * m * (pp - 1))
 
 
+@pytest.mark.parametrize("name", ["gpt96", "hetero64"])
+def test_full_parity_largest_configs(H, oracle_mod, name):
+    """Every candidate of the two largest configurations, in the launch shape the benchmark times
+    (no stage table), against the oracle on all host threads."""
+    _say(f"[case] full parity {name}")
+    w = make_workload(name)
+    hip = H.run_hip(w, table=False)
+    ora = oracle_mod.simulate(w, nthreads=NT)
+    H.assert_same(hip, ora, what=name + " (all candidates)")
+
+
 def test_without_stage_table(H, oracle_mod):
     """stage_tab == NULL: nothing per-stage is written by event generation and simulate composes
     the stage events itself; results, statuses and event counts must be the same."""
