@@ -169,6 +169,8 @@ typedef struct {
                                 + 2 m (pp-1) p2p + gradient all-reduce events; 0 if not OK       */
     void    *workspace;      /* distsim_workspace_bytes() bytes, 256-byte aligned; opaque         */
     size_t   workspace_bytes;
+    int64_t  num_candidates; /* C of the call that produced the events; filled in by
+                                distsim_build_events, checked by distsim_simulate / _timeline     */
     distsim_costs      costs;   /* copies of the inputs' pointers, filled in by distsim_build_events: */
     distsim_candidates cand;    /* the arrays they point to must stay alive until distsim_simulate    */
 } distsim_events;
@@ -227,7 +229,8 @@ int distsim_search(distsim_ctx *ctx, const int64_t *batch_ns, const int64_t *wei
  * reduced to their stage-tasks (Sec. 3.2: the timeline says when which device computes and
  * communicates; Sec. 5.3 / 5.4 compare exactly these start and end timestamps).
  *   sel[n]       device: candidate indices (status must be OK after distsim_simulate, or after
- *                distsim_build_events with a stage table; other candidates get no task entries)
+ *                distsim_build_events with a stage table; other candidates, and indices outside
+ *                [0, C), get no task entries and no all-reduce windows)
  *   task_off[n]  device: first entry of the candidate's block in start_ns / end_ns; the block
  *                holds 2*pp*m entries laid out [kind][stage][micro-batch], kind 0 = forward,
  *                1 = backward.  With p2p_blocking the end includes the send.

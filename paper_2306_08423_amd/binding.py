@@ -53,7 +53,7 @@ class _Events(C.Structure):
     _fields_ = [("stage_cap", C.c_int64), ("L", C.c_int32), ("V", C.c_int32),
                 ("status", C.c_void_p), ("stage_pos", C.c_void_p), ("stage_tab", C.c_void_p),
                 ("stage_layers", C.c_void_p), ("num_events", C.c_void_p),
-                ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t),
+                ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t), ("num_candidates", C.c_int64),
                 ("costs", _Costs), ("cand", _Cand)]
 
 
@@ -256,7 +256,7 @@ def alloc_events(ctx: Context, L: int, V: int, Cn: int, stage_cap: Optional[int]
     # torch's caching allocator hands out 512-byte aligned blocks
     workspace = torch.empty(nbytes, dtype=torch.uint8, device=dev)
     st = _Events(cap, 0, 0, _ptr(status), _ptr(stage_pos), _ptr(stage_tab), _ptr(stage_layers), _ptr(num_events),
-                 _ptr(workspace), nbytes, _Costs(), _Cand())
+                 _ptr(workspace), nbytes, 0, _Costs(), _Cand())
     return Events(Cn, cap, status, stage_pos, stage_tab, stage_layers, num_events, workspace, st)
 
 

@@ -168,6 +168,7 @@ int distsim_build_events(distsim_ctx* ctx, const distsim_costs* costs, const dis
     EventsDev ev{out->stage_cap, out->status, out->stage_pos, out->stage_tab, out->stage_layers, out->num_events};
     out->L = costs->L;
     out->V = costs->V;
+    out->num_candidates = C;
     out->costs = *costs;
     out->cand = *cand;
 
@@ -207,6 +208,7 @@ int distsim_simulate(distsim_ctx* ctx, const distsim_cluster* cluster, const dis
     if (!cluster || !events) return fail(ctx, DISTSIM_EINVAL, "null argument");
     if (!cluster_ok(cluster)) return fail(ctx, DISTSIM_EINVAL, "cluster description out of range");
     if (C < 0 || C > 0x7fffffff) return fail(ctx, DISTSIM_ERANGE, "candidate count outside [0, 2^31)");
+    if (C != events->num_candidates) return fail(ctx, DISTSIM_EINVAL, "C differs from the distsim_build_events call");
     if (C == 0) return DISTSIM_OK;
     if (!batch_ns || !events->status || !events->num_events || !events->workspace ||
         (events->stage_cap > 0 && (!comp_busy_ns || !comm_busy_ns)))
@@ -270,7 +272,7 @@ int distsim_timeline(distsim_ctx* ctx, const distsim_cluster* cluster, const dis
     {
         Timer t(ctx, st, DISTSIM_K_TIMELINE);
         hipLaunchKernelGGL(k_timeline, dim3((unsigned)((n + kTlChunk - 1) / kTlChunk)), dim3(kTlWaves * kWave), 0, st,
-                           co, cl_dev(*cluster), ca, ws, events->status, n, out);
+                           co, cl_dev(*cluster), ca, ws, events->status, events->num_candidates, n, out);
     }
     HIP_TRY(hipGetLastError());
     return DISTSIM_OK;

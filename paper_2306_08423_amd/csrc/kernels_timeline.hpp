@@ -55,8 +55,8 @@ struct TlStage {
 // wavefront, whose LDS instructions execute in order: between its writes and the reads by other
 // lanes only the compiler has to be kept from reordering (wavefront-scope fences).
 __global__ __launch_bounds__(kTlWaves * kWave) void k_timeline(CostsDev co, ClusterDev cl, CandDev ca, Workspace ws,
-                                                               const int32_t* __restrict__ status, int64_t n,
-                                                               TimelineOut out) {
+                                                               const int32_t* __restrict__ status, int64_t C,
+                                                               int64_t n, TimelineOut out) {
     __shared__ TlStage stage_mem[kTlWaves];
     __shared__ int32_t order[kTlChunk];
     __shared__ int32_t cls_start[kClasses + 1], cls_count[kClasses], item_start[kClasses + 1];
@@ -75,7 +75,7 @@ __global__ __launch_bounds__(kTlWaves * kWave) void k_timeline(CostsDev co, Clus
         int k = -1;
         if (lane < kTlChunk && q < n) {
             const int64_t c = out.sel[q];
-            if (status[c] == 0) {
+            if (c >= 0 && c < C && status[c] == 0) {
                 const int pp = ca.pp[c];
                 int sh = 0;
                 while ((1 << sh) < pp) sh++;

@@ -175,6 +175,26 @@ def test_timeline_dump(H, oracle_mod):
     costs = mk_costs([10] * 4, [20] * 4)
     w = mk(costs, mk_cluster(2), [(1, 1, 2, 4, 1, None), (1, 1, 2, 4, 1, [0, 0, 4]), (2, 1, 2, 4, 1, None)])
     _timeline_parity(H, oracle_mod, w, [0, 1, 2])
+    # indices outside the candidate list select nothing
+    import torch
+    import paper_2306_08423_amd as ds
+    c = H.ctx()
+    dw = ds.upload(w, c.device)
+    ev = ds.alloc_events(c, dw.L, dw.V, dw.C, ds.stage_entries(w.cand["pp"]), table=False)
+    ds.distsim_build_events(c, dw, ev)
+    out = ds.alloc_outputs(c, ev)
+    ds.distsim_simulate(c, dw.cluster, ev, out)
+    sel = torch.tensor([-1, 0, 3, 1 << 40], dtype=torch.int64, device=c.device)
+    off = torch.tensor([0, 16, 32, 48], dtype=torch.int64, device=c.device)
+    start = torch.full((64,), -7, dtype=torch.int64, device=c.device)
+    end = torch.full((64,), -7, dtype=torch.int64, device=c.device)
+    ar0 = torch.full((4, 64), -7, dtype=torch.int64, device=c.device)
+    ar1 = torch.full((4, 64), -7, dtype=torch.int64, device=c.device)
+    ds.distsim_timeline(c, dw.cluster, ev, sel, off, start, end, ar0, ar1)
+    torch.cuda.synchronize()
+    start = start.cpu().numpy()
+    assert (start[:16] == -7).all() and (start[32:] == -7).all() and (start[16:32] >= 0).all()
+    assert (ar0.cpu().numpy() == -1).all() and (ar1.cpu().numpy() == -1).all()
 
 
 def test_async_schedule(H, oracle_mod):
@@ -379,6 +399,19 @@ def test_search_parity(H, oracle_mod):
     best, scratch = ds.alloc_search(c, 100)
     ds.distsim_search(c, torch.from_numpy(b).to(c.device), 100, best, scratch)
     assert tuple(int(x) for x in best.cpu().numpy()) == (-1, INT64_MAX)
+
+
+def test_simulate_rejects_other_candidate_count(H):
+    import paper_2306_08423_amd as ds
+    w = make_workload("gpt24")
+    c = H.ctx()
+    dw = ds.upload(w, c.device)
+    ev = ds.alloc_events(c, dw.L, dw.V, dw.C, ds.stage_entries(w.cand["pp"]), table=False)
+    ds.distsim_build_events(c, dw, ev)
+    out = ds.alloc_outputs(c, ev)
+    ev.C = dw.C - 1
+    with pytest.raises(ds.DistSimError):
+        ds.distsim_simulate(c, dw.cluster, ev, out)
 
 
 def test_api_errors(H):
