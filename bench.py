@@ -235,9 +235,14 @@ def main() -> int:
         t1 = time.perf_counter()
         ora = oracle.simulate(ws, nthreads=ncores)
         t_or = time.perf_counter() - t1
+        n1 = min(ns, 10_000)                                            # and the rate of one thread
+        t2 = time.perf_counter()
+        oracle.simulate(subset(w, idx[:n1]), nthreads=1)
+        t_1 = time.perf_counter() - t2
         cpu_baseline = {"value": ns / t_or, "unit": "strategies/s", "cores": ncores, "kind": "oracle",
                         "sample": f"{ns} seeded candidates of {args.workload}, {t_or:.2f} s wall",
-                        "events_per_s": int(ora["num_events"].sum()) / t_or}
+                        "events_per_s": int(ora["num_events"].sum()) / t_or,
+                        "one_thread": {"value": n1 / t_1, "sample": f"first {n1} of the same sample, {t_1:.2f} s"}}
         got = out.batch_ns[:C].cpu().numpy()[idx]
         parity = {"sampled": int(ns), "batch_ns_equal": bool(np.array_equal(got, ora["batch_ns"]))}
 
