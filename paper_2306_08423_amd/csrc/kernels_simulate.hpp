@@ -279,25 +279,30 @@ __device__ __forceinline__ void simulate_items(const ClusterDev& cl, const CandD
                     latO[u] = even_s ? sw[u].pbR : sw[u].pfL; durO[u] = even_s ? sw[u].Bd : sw[u].Fd;
                 }
                 uint32_t Pc = PFb | PBb;
-                for (int j = 0; j < len; j++) {
-                    if ((l0 + k + j) & 1) {
-                        if constexpr (U == 1) {
-                            double nb = from_pair_partner(sw[0].own);
-                            DISTSIM_STEP1(Pc, sw[0].own, nb, latO[0], durO[0]);
-                        } else {
-                            double na = from_pair_partner(sw[0].own), nb = from_pair_partner(sw[U - 1].own);
-                            DISTSIM_STEP2(Pc, sw[0].own, na, latO[0], durO[0], sw[U - 1].own, nb, latO[U - 1], durO[U - 1]);
-                        }
+                // straight-line (odd level, even level) pairs, so that both kinds of level keep
+                // their state in the same registers; a leading even and a trailing odd level apart
+                auto odd_level = [&]() {
+                    if constexpr (U == 1) {
+                        double nb = from_pair_partner(sw[0].own);
+                        DISTSIM_STEP1(Pc, sw[0].own, nb, latO[0], durO[0]);
                     } else {
-                        if constexpr (U == 1) {
-                            double nb = from_lanes(sw[0].own, adrE);
-                            DISTSIM_STEP1(Pc, sw[0].own, nb, latE[0], durE[0]);
-                        } else {
-                            double na = from_lanes(sw[0].own, adrE), nb = from_lanes(sw[U - 1].own, adrE);
-                            DISTSIM_STEP2(Pc, sw[0].own, na, latE[0], durE[0], sw[U - 1].own, nb, latE[U - 1], durE[U - 1]);
-                        }
+                        double na = from_pair_partner(sw[0].own), nb = from_pair_partner(sw[U - 1].own);
+                        DISTSIM_STEP2(Pc, sw[0].own, na, latO[0], durO[0], sw[U - 1].own, nb, latO[U - 1], durO[U - 1]);
                     }
-                }
+                };
+                auto even_level = [&]() {
+                    if constexpr (U == 1) {
+                        double nb = from_lanes(sw[0].own, adrE);
+                        DISTSIM_STEP1(Pc, sw[0].own, nb, latE[0], durE[0]);
+                    } else {
+                        double na = from_lanes(sw[0].own, adrE), nb = from_lanes(sw[U - 1].own, adrE);
+                        DISTSIM_STEP2(Pc, sw[0].own, na, latE[0], durE[0], sw[U - 1].own, nb, latE[U - 1], durE[U - 1]);
+                    }
+                };
+                int j = 0;
+                if (((l0 + k) & 1) == 0) { even_level(); j = 1; }
+                for (; j + 1 < len; j += 2) { odd_level(); even_level(); }
+                if (j < len) odd_level();
                 PFb = shl32(PFb, len); PBb = shl32(PBb, len);
             } else if (inF && inB) {
                 for (int j = 0; j < len; j++) {
