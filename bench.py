@@ -148,7 +148,13 @@ def main() -> int:
         for _ in range(5):
             ds.distsim_timeline(ctx, dw.cluster, ev, d_sel, d_off, t_start, t_end, ar0, ar1)
         torch.cuda.synchronize()
-        tl_ms, tl_n = ctx.timing_read()["k_timeline"]
+        t_idle = torch.empty_like(t_start)
+        for _ in range(5):
+            ds.distsim_bubbles(ctx, ev, d_sel, d_off, t_start, t_end, t_idle)
+        torch.cuda.synchronize()
+        kt3 = ctx.timing_read()
+        tl_ms, tl_n = kt3["k_timeline"]
+        bb_ms, bb_n = kt3["k_bubbles"]
         ctx.timing_enable(False)
         tl_s = tl_ms / max(tl_n, 1) / 1e3
         tl_bytes = int(off[-1]) * 16 + nsel * 64 * 16
@@ -156,7 +162,11 @@ def main() -> int:
                     "stage_tasks_per_s": int(off[-1]) / tl_s, "bound": "hbm",
                     "achieved": tl_bytes / tl_s / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                     "frac": tl_bytes / tl_s / 1e9 / HBM_PEAK_GBS}
-        del t_start, t_end, ar0, ar1
+        bb_s = bb_ms / max(bb_n, 1) / 1e3
+        bb_bytes = int(off[-1]) * 24                       # start and predecessor's end in, idle time out
+        timeline["bubbles"] = {"ms": bb_s * 1e3, "bound": "hbm", "achieved": bb_bytes / bb_s / 1e9,
+                               "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": bb_bytes / bb_s / 1e9 / HBM_PEAK_GBS}
+        del t_start, t_end, t_idle, ar0, ar1
 
     ingest = None
     if args.ingest > 0:

@@ -245,6 +245,19 @@ int distsim_timeline(distsim_ctx *ctx, const distsim_cluster *cluster, const dis
                      void *hip_stream);
 
 /*
+ * Bubble analysis of a timeline dumped by distsim_timeline (Sec. 3.2 names pipeline bubble
+ * analysis as a use of the timeline; Sec. 5: the per-stage, per-micro-batch timestamps locate the
+ * bubbles).  For the same sel / task_off and the start_ns / end_ns that distsim_timeline wrote,
+ * idle_before_ns gets, in the same [kind][stage][micro-batch] layout, the time the stage's device
+ * was idle in front of each stage-task: its start minus the end of the task the device ran before
+ * it in the schedule's order (minus 0 for the device's first task).  Candidates that got no
+ * timeline get nothing.  Errors: EINVAL, ERANGE, EHIP.
+ */
+int distsim_bubbles(distsim_ctx *ctx, const distsim_events *events, int64_t n, const int64_t *sel,
+                    const int64_t *task_off, const int64_t *start_ns, const int64_t *end_ns,
+                    int64_t *idle_before_ns, void *hip_stream);
+
+/*
  * Event generator (Sec. 4.1): operators that agree in name, parameters and input shape (and,
  * for communication, in the intra-/inter-node attribute) are one event and are profiled once.
  *   records[n][K]  device: one operator per row, K int64 words that identify it (how names and
@@ -284,7 +297,7 @@ int distsim_comm_event_times(distsim_ctx *ctx, int64_t n, const int32_t *kind, c
 enum {
     DISTSIM_K_LAYER_TABLES = 0, DISTSIM_K_DECODE, DISTSIM_K_BINS, DISTSIM_K_SCATTER,
     DISTSIM_K_STAGE_EVENTS, DISTSIM_K_SIM_INIT, DISTSIM_K_SIMULATE, DISTSIM_K_SEARCH, DISTSIM_K_TIMELINE,
-    DISTSIM_K_DEDUP, DISTSIM_K_COMM_TIMES,
+    DISTSIM_K_DEDUP, DISTSIM_K_COMM_TIMES, DISTSIM_K_BUBBLES,
     DISTSIM_K_COUNT
 };
 int distsim_timing_enable(distsim_ctx *ctx, int on);

@@ -19,14 +19,14 @@ LIB_PATH = os.path.join(_HERE, "libdistsim_hip.so")
 EXPORTS = (
     "distsim_create", "distsim_destroy", "distsim_last_error", "distsim_workspace_bytes", "distsim_stage_entries",
     "distsim_build_events", "distsim_simulate", "distsim_search_scratch_bytes", "distsim_search",
-    "distsim_timeline", "distsim_dedup_workspace_bytes", "distsim_dedup_events", "distsim_comm_event_times",
+    "distsim_timeline", "distsim_bubbles", "distsim_dedup_workspace_bytes", "distsim_dedup_events", "distsim_comm_event_times",
     "distsim_timing_enable", "distsim_timing_read", "distsim_kernel_name",
 )
 
 NCOLS = 8
 COL = {"FC": 0, "FA": 1, "BC": 2, "BA": 3, "PF": 4, "PB": 5, "G": 6, "AR": 7}
 KERNELS = ("k_layer_tables", "k_decode", "k_bins", "k_scatter", "k_stage_events",
-           "k_sim_init", "k_simulate", "k_search", "k_timeline", "k_dedup", "k_comm_event_times")
+           "k_sim_init", "k_simulate", "k_search", "k_timeline", "k_dedup", "k_comm_event_times", "k_bubbles")
 INT64_MAX = (1 << 63) - 1
 
 
@@ -91,6 +91,8 @@ def load_library():
     lib.distsim_search.restype = C.c_int
     lib.distsim_timeline.argtypes = [C.c_void_p, C.POINTER(_Cluster), C.POINTER(_Events), C.c_int64] + [C.c_void_p] * 7
     lib.distsim_timeline.restype = C.c_int
+    lib.distsim_bubbles.argtypes = [C.c_void_p, C.POINTER(_Events), C.c_int64] + [C.c_void_p] * 6
+    lib.distsim_bubbles.restype = C.c_int
     lib.distsim_dedup_workspace_bytes.argtypes = [C.c_int64]
     lib.distsim_dedup_workspace_bytes.restype = C.c_size_t
     lib.distsim_dedup_events.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int32, C.c_void_p, C.c_void_p,
@@ -307,6 +309,12 @@ def distsim_timeline(ctx: Context, cluster, ev: Events, sel: torch.Tensor, task_
     cl = cluster_struct(cluster)
     ctx.check(ctx.lib.distsim_timeline(ctx.h, C.byref(cl), C.byref(ev.struct), sel.numel(), _ptr(sel), _ptr(task_off),
                                        _ptr(start_ns), _ptr(end_ns), _ptr(ar_start_ns), _ptr(ar_end_ns), _stream()))
+
+
+def distsim_bubbles(ctx: Context, ev: Events, sel: torch.Tensor, task_off: torch.Tensor, start_ns: torch.Tensor,
+                    end_ns: torch.Tensor, idle_before_ns: torch.Tensor) -> None:
+    ctx.check(ctx.lib.distsim_bubbles(ctx.h, C.byref(ev.struct), sel.numel(), _ptr(sel), _ptr(task_off),
+                                      _ptr(start_ns), _ptr(end_ns), _ptr(idle_before_ns), _stream()))
 
 
 def distsim_dedup_events(ctx: Context, records: torch.Tensor, event_id: torch.Tensor, rep: torch.Tensor,

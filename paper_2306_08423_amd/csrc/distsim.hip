@@ -31,7 +31,7 @@ struct distsim_ctx {
 static const char* kKernelNames[DISTSIM_K_COUNT] = {
     "k_layer_tables", "k_decode", "k_bins", "k_scatter",
     "k_stage_events", "k_sim_init", "k_simulate", "k_search", "k_timeline",
-    "k_dedup", "k_comm_event_times",
+    "k_dedup", "k_comm_event_times", "k_bubbles",
 };
 
 static int fail(distsim_ctx* ctx, int code, const std::string& msg) {
@@ -303,6 +303,30 @@ int distsim_search(distsim_ctx* ctx, const int64_t* batch_ns, const int64_t* wei
     } else {
         hipLaunchKernelGGL(k_search_partial<1>, dim3((int)nb), dim3(kSearchBlock), 0, st, batch_ns, weight, C, partial);
         hipLaunchKernelGGL(k_search_final<1>, dim3(1), dim3(kSearchBlock), 0, st, partial, (int)nb, best);
+    }
+    HIP_TRY(hipGetLastError());
+    return DISTSIM_OK;
+}
+
+int distsim_bubbles(distsim_ctx* ctx, const distsim_events* events, int64_t n, const int64_t* sel,
+                    const int64_t* task_off, const int64_t* start_ns, const int64_t* end_ns, int64_t* idle_before_ns,
+                    void* hip_stream) {
+    if (!ctx) return DISTSIM_EINVAL;
+    if (!events) return fail(ctx, DISTSIM_EINVAL, "null argument");
+    if (n < 0 || n > 0x7fffffff) return fail(ctx, DISTSIM_ERANGE, "selection size outside [0, 2^31)");
+    if (n == 0) return DISTSIM_OK;
+    const distsim_candidates* cd = &events->cand;
+    if (!sel || !task_off || !start_ns || !end_ns || !idle_before_ns || !events->status || !cd->pp || !cd->m ||
+        !cd->schedule)
+        return fail(ctx, DISTSIM_EINVAL, "null array");
+    HIP_TRY(hipSetDevice(ctx->device));
+    hipStream_t st = (hipStream_t)hip_stream;
+    CandDev ca{cd->dp, cd->tp, cd->pp, cd->m, cd->schedule, cd->part_off, cd->part_pool,
+               cd->part_pool ? cd->part_pool_len : 0};
+    {
+        Timer t(ctx, st, DISTSIM_K_BUBBLES);
+        hipLaunchKernelGGL(k_bubbles, dim3((unsigned)n), dim3(256), 0, st, ca, events->status, events->num_candidates,
+                           n, sel, task_off, start_ns, end_ns, idle_before_ns);
     }
     HIP_TRY(hipGetLastError());
     return DISTSIM_OK;

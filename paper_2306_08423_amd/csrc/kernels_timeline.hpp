@@ -254,4 +254,49 @@ __global__ __launch_bounds__(kTlWaves * kWave) void k_timeline(CostsDev co, Clus
     }
 }
 
+// Bubble analysis of a dumped timeline (Sec. 3.2: the timeline serves "pipeline bubble analysis";
+// Sec. 5: per-stage, per-micro-batch timestamps let a user locate the bubbles): the idle time of
+// the device in front of every stage-task = start of the task - end of the task the device ran
+// before it (0, the start of the iteration, for its first task).  The predecessor in device order
+// follows from the schedule:
+//   GPipe   F(s,j) after F(s,j-1);  B(s,0) after F(s,m-1);  B(s,j) after B(s,j-1)
+//   Dapple  with w = min(pp-1-s, m) warm-up forwards:
+//           F(s,j) after F(s,j-1) for j <= w, after B(s,j-w-1) for j > w;
+//           B(s,j) after F(s,w+j) for j < m-w, else after B(s,j-1) (after F(s,m-1) if j = 0)
+// One workgroup per selected candidate; entries in the layout of the dump, [kind][stage][micro-batch].
+__global__ __launch_bounds__(256) void k_bubbles(CandDev ca, const int32_t* __restrict__ status, int64_t C, int64_t n,
+                                                 const int64_t* __restrict__ sel, const int64_t* __restrict__ task_off,
+                                                 const int64_t* __restrict__ start, const int64_t* __restrict__ end,
+                                                 int64_t* __restrict__ idle) {
+    const int64_t q = blockIdx.x;
+    if (q >= n) return;
+    const int64_t c = sel[q];
+    if (c < 0 || c >= C || status[c] != 0) return;
+    const int pp = ca.pp[c], m = ca.m[c], sched = ca.schedule[c];
+    const int64_t off = task_off[q];
+    const int per_kind = pp * m;                          // <= 64 * 65536
+    for (int t = threadIdx.x; t < 2 * per_kind; t += blockDim.x) {
+        const int kind = t >= per_kind ? 1 : 0;
+        const int r = t - kind * per_kind;
+        const int s = r / m, j = r - s * m;
+        int pk = -1, pj = 0;                              // predecessor (kind, micro-batch); pk < 0: none
+        if (sched == 0) {
+            if (j > 0) { pk = kind; pj = j - 1; }
+            else if (kind == 1) { pk = 0; pj = m - 1; }
+        } else {
+            int w = pp - 1 - s; if (w > m) w = m;
+            if (kind == 0) {
+                if (j > w) { pk = 1; pj = j - w - 1; }
+                else if (j > 0) { pk = 0; pj = j - 1; }
+            } else {
+                if (j < m - w) { pk = 0; pj = w + j; }
+                else if (j > 0) { pk = 1; pj = j - 1; }
+                else { pk = 0; pj = m - 1; }
+            }
+        }
+        const int64_t before = pk < 0 ? 0 : end[off + ((int64_t)pk * pp + s) * m + pj];
+        idle[off + t] = start[off + t] - before;
+    }
+}
+
 }  // namespace distsim

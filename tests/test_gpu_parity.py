@@ -144,15 +144,21 @@ def _timeline_parity(H, oracle_mod, w, idx):
     ar1 = torch.full((len(idx), 64), -7, dtype=torch.int64, device=dev)
     ds.distsim_timeline(c, dw.cluster, ev, torch.from_numpy(idx).to(dev), torch.from_numpy(off[:-1].copy()).to(dev),
                         start, end, ar0, ar1)
+    idle = torch.full((int(off[-1]),), -7, dtype=torch.int64, device=dev)
+    ds.distsim_bubbles(c, ev, torch.from_numpy(idx).to(dev), torch.from_numpy(off[:-1].copy()).to(dev), start, end, idle)
     torch.cuda.synchronize()
-    start, end, ar0, ar1 = (t.cpu().numpy() for t in (start, end, ar0, ar1))
+    start, end, ar0, ar1, idle = (t.cpu().numpy() for t in (start, end, ar0, ar1, idle))
     batch = out.batch_ns.cpu().numpy()
+    from oracle.bubbles import idle_before
     for k, i in enumerate(idx):
         r = oracle_mod.simulate(subset(w, [i]), timeline=True)
         pp, m = int(w.cand["pp"][i]), int(w.cand["m"][i])
         if r["status"][0] != 0:
             assert (start[off[k]:off[k + 1]] == -7).all() and (ar0[k] == -1).all()
+            assert (idle[off[k]:off[k + 1]] == -7).all()
             continue
+        want_idle = idle_before(r["start"], r["end"], int(w.cand["schedule"][i]))
+        assert np.array_equal(idle[off[k]:off[k + 1]].reshape(2, pp, m), want_idle), (i, "idle")
         assert np.array_equal(start[off[k]:off[k + 1]].reshape(2, pp, m), r["start"]), (i, "start")
         assert np.array_equal(end[off[k]:off[k + 1]].reshape(2, pp, m), r["end"]), (i, "end")
         assert np.array_equal(ar0[k, :pp], r["ar_window"][0]) and np.array_equal(ar1[k, :pp], r["ar_window"][1]), i

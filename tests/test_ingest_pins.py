@@ -107,3 +107,52 @@ def test_profiled_once_per_event():
     rec = make_operator_records(50_000, 400)
     eid, rep = dedup_events(rec)
     assert len(rep) <= 400 and (rec[rep[eid]] == rec).all()
+
+
+# ---- bubble analysis of a timeline (Sec. 3.2, Sec. 5) ------------------------------------------
+
+def _timeline_of(oracle_mod, costs, cluster, row):
+    from helpers import mk
+    return oracle_mod.simulate(mk(costs, cluster, [row]), timeline=True)
+
+
+@pytest.mark.parametrize("sched", [0, 1, 2])
+def test_bubbles_account_for_all_idle_time(oracle_mod, sched):
+    from helpers import mk_cluster, mk_costs
+    from oracle.bubbles import device_order, idle_before
+    rng = np.random.default_rng(8 + sched)
+    L = 12
+    for pp, m in [(1, 1), (1, 5), (2, 4), (3, 7), (4, 2), (6, 6), (12, 3)]:
+        costs = mk_costs(rng.integers(1, 900, L).tolist(), rng.integers(1, 900, L).tolist(), act=[3000] * L)
+        r = _timeline_of(oracle_mod, costs, mk_cluster(pp, alpha=(40, 40), beta=(10, 10)), (1, 1, pp, m, sched, None))
+        st, en = r["start"], r["end"]
+        idle = idle_before(st, en, sched)
+        assert (idle >= 0).all()
+        for s in range(pp):
+            order = device_order(pp, m, sched, s)
+            assert sorted(order) == sorted([(k, j) for k in (0, 1) for j in range(m)])       # every task once
+            # idle + busy = the time at which the device finishes its last task
+            busy = int((en[:, s, :] - st[:, s, :]).sum())
+            assert int(idle[:, s, :].sum()) + busy == int(en[:, s, :].max())
+            # without zero-length tasks the device order is the order of the start times
+            by_time = sorted([(int(st[k, s, j]), k, j) for k in (0, 1) for j in range(m)])
+            assert [(k, j) for _, k, j in by_time] == order
+        # the first stage never waits for its first forward; the last stage's first backward follows
+        # its own forward of the same micro-batch under Dapple
+        assert idle[0, 0, 0] == 0
+
+
+def test_bubbles_of_the_hand_unrolled_pipeline(oracle_mod):
+    """pp = 2, m = 4, Dapple, uniform stages F = 10, B = 20, p2p c = 3 (the timeline of
+    tests/golden/pipeline_pp2_m4.txt with numbers put in): stage 1 idles F + c before its first
+    forward; stage 0 idles c + B + c between its second forward and its first backward."""
+    from helpers import mk_cluster, mk_costs
+    from oracle.bubbles import idle_before
+    costs = mk_costs([10, 10], [20, 20], act=[30, 30])
+    r = _timeline_of(oracle_mod, costs, mk_cluster(2, alpha=(0, 0), beta=(10, 10)), (1, 1, 2, 4, 1, [0, 1, 2]))
+    idle = idle_before(r["start"], r["end"], 1)
+    F, B, c = 10, 20, 3
+    assert idle[0, 1, 0] == F + c                       # stage 1 waits for the first activation
+    assert idle[0, 0, 0] == 0 and idle[0, 0, 1] == 0    # stage 0: warm-up forward, then F1 back to back
+    assert idle[1, 0, 0] == (F + c + F + B + c) - 2 * F  # B0 on stage 0 arrives after stage 1's F0, B0 and two sends
+    assert int(idle.sum()) > 0
