@@ -69,7 +69,7 @@ def main() -> int:
                     help="also run one 1 GiB device-to-device copy (known traffic, for scaling HBM counters)")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build evaluates candidates on ONE GPU; --gpus must be 1 "
+        print("bench.py: the library evaluates candidates on ONE GPU; --gpus must be 1 "
               "(candidates would be sharded across GPUs with a 16-byte MINLOC exchange, which is not built)",
               file=sys.stderr)
         return 2

@@ -1,9 +1,9 @@
 """Oracle for the bubble analysis of a dumped timeline.  TEST INFRASTRUCTURE ONLY (tests/, smoke,
 the benchmark's CPU leg).
 
-The timeline tells "when and which device will compute and communicate" and is meant for
-"iteration-time, device utilization, and pipeline bubble analysis" (Sec. 3.2); the per-stage,
-per-micro-batch timestamps are what lets a user "locate pipeline bubbles" (Sec. 5).  A bubble is
+The timeline says at what time which device computes or communicates, and the paper lists bubble
+analysis among its uses next to iteration time and utilisation (Sec. 3.2); the per-stage,
+per-micro-batch timestamps are what a user finds the bubbles with (Sec. 5).  A bubble is
 the idle time of a device in front of a stage-task: start of the task minus end of the task the
 device ran before it (minus 0, the start of the iteration, for its first task).  The device order is
 written out here as explicit lists, the way the schedule defines it (Sec. 2.1.3, Fig. 2: GPipe =

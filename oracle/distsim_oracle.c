@@ -17,8 +17,8 @@
  *      event per pass (workload extension, not in the paper).
  *   2. pipeline modelling (Algorithm 1) -- walk the schedule S: a device takes
  *      the next stage-task of ITS OWN ordered list as soon as it is idle and
- *      the task's input has arrived ("data is prepared and micro-batch index is
- *      matched"); the task's events run back to back; when it ends, the
+ *      the task's input has arrived (Alg. 1's availability test: the data is
+ *      there and it is that micro-batch's turn); the task's events run back to back; when it ends, the
  *      point-to-point event towards the neighbouring stage is appended at
  *      t + elapsed.  GPipe and Dapple (early-backward, "1F1B") orders are built
  *      explicitly as per-device lists.
@@ -29,8 +29,8 @@
  *      soon as the last micro-batch's backward has produced their bytes
  *      (extension; bucket = 0 gives the paper's single trailing event).
  *      Schedule 2 is the asynchronous pipeline of the paper's discussion of new
- *      algorithms (Sec. 7): the Dapple order "only without a global synchronize
- *      event", i.e. no gradient all-reduce event is appended.
+ *      algorithms (Sec. 7): the Dapple order minus the global synchronisation
+ *      event, i.e. no gradient all-reduce event is appended.
  *   4. analysis -- batch (iteration) time = time of the last event; per-stage
  *      computation / communication busy time = sum of the durations of the
  *      events on that device's list; utilisation = busy / batch (Sec. 3.2,
@@ -45,7 +45,7 @@
  *   allreduce(n,P,k) = alpha_k + (2*(n-1)*P) / (n*beta_k)      ring volume 2(N-1)P/N, Sec. 4.2
  *   alltoall(n,P,k)  = alpha_k + ((n-1)*P) / (n*beta_k)
  * A collective over n = 1 ranks or over 0 bytes is not an event.  Collectives
- * are intra-node iff n <= gpus_per_node (the paper's "8 or fewer" split); a
+ * are intra-node iff n <= gpus_per_node (the paper profiles groups of up to 8 devices directly, Sec. 4.2); a
  * stage boundary s|s+1 is intra-node iff floor(s*tp*dp/g) == floor((s+1)*tp*dp/g)
  * (ranks ordered tp fastest, then dp, then pp; Sec. 4.1's intra/inter attribute).
  *

@@ -1,7 +1,7 @@
 // Timeline dump: start and end of every stage-task of selected candidates, i.e. the per-device
 // event lists of Algorithm 1 reduced to their stage-tasks, plus the window of the gradient
-// all-reduce events of every stage (Sec. 3.2: "when and which device will compute and
-// communicate").
+// all-reduce events of every stage (Sec. 3.2: the timeline says at what time which device computes
+// or communicates).
 #pragma once
 #include "kernels_simulate.hpp"
 
@@ -254,7 +254,7 @@ __global__ __launch_bounds__(kTlWaves * kWave) void k_timeline(CostsDev co, Clus
     }
 }
 
-// Bubble analysis of a dumped timeline (Sec. 3.2: the timeline serves "pipeline bubble analysis";
+// Bubble analysis of a dumped timeline (Sec. 3.2 lists bubble analysis among the timeline's uses;
 // Sec. 5: per-stage, per-micro-batch timestamps let a user locate the bubbles): the idle time of
 // the device in front of every stage-task = start of the task - end of the task the device ran
 // before it (0, the start of the iteration, for its first task).  The predecessor in device order

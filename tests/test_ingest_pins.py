@@ -103,7 +103,7 @@ def test_dedup_special_cases():
 
 
 def test_profiled_once_per_event():
-    # "identical operators ... profiled only once": the number of profiling jobs is the number of events
+    # Sec. 3.2 / 4.1: identical operators are profiled a single time, so there are as many profiling jobs as events
     rec = make_operator_records(50_000, 400)
     eid, rep = dedup_events(rec)
     assert len(rep) <= 400 and (rec[rep[eid]] == rec).all()

@@ -519,8 +519,8 @@ def test_dp_changes_only_the_tail(oracle_mod):
 
 
 def test_async_schedule_is_dapple_without_the_global_sync(oracle_mod):
-    """Sec. 7 (new algorithms): an asynchronous pipeline keeps the schedule "only without a global
-    synchronize event (usually an all-reduce event)"."""
+    """Sec. 7 (new algorithms): an asynchronous pipeline keeps the schedule and drops the global
+    synchronisation event, which is the gradient all-reduce."""
     L = 8
     rng = np.random.default_rng(4)
     costs = mk_costs(rng.integers(1, 999, L).tolist(), rng.integers(1, 999, L).tolist(),
