@@ -109,7 +109,12 @@ typedef struct {
                                         stage, the sender goes on with its next task (default);
                                         1: the sender's device is occupied for the p2p event, which
                                         then counts as the tail of the stage-task, and the
-                                        neighbour may start when it ends                         */
+                                        neighbour may start when it ends;
+                                        2: the sender goes on, but sends queue on their link: each
+                                        boundary carries one transfer per direction at a time, a
+                                        send starts when its task has ended and the previous send
+                                        over that link has arrived (slower kernel; an extension,
+                                        the paper models no contention)                          */
 } distsim_cluster;
 
 /* Candidate strategies "xM xP xD" (Sec. 5.1) x micro-batches x schedule x partition.

@@ -124,7 +124,8 @@ typedef struct {
     int32_t num_devices, gpus_per_node;
     int64_t alpha[2], beta[2];
     int64_t bucket;
-    int32_t p2p_blocking;   /* the p2p event occupies the sender: it is the tail of the stage-task */
+    int32_t p2p_blocking;   /* 1: the p2p event occupies the sender (it is the tail of the stage-task);
+                               2: sends queue on their link (one transfer at a time per direction and boundary) */
 } cluster_t;
 
 static int64_t p2p_ns(const cluster_t *cl, int64_t bytes, int k) {
@@ -269,7 +270,8 @@ static void simulate_one(const costs_t *co, const cluster_t *cl,
     uint8_t busy[256];
     int64_t cb[256], mb_[256];          /* computation / communication busy */
     int64_t comm_free[256], acc[256];   /* DP communication stream, open bucket bytes */
-    for (int s = 0; s < pp; s++) { next[s] = 0; busy[s] = 0; cb[s] = 0; mb_[s] = 0; comm_free[s] = 0; acc[s] = 0; }
+    int64_t link_f[256], link_b[256];   /* time at which the outgoing forward / backward link is free again */
+    for (int s = 0; s < pp; s++) { next[s] = 0; busy[s] = 0; cb[s] = 0; mb_[s] = 0; comm_free[s] = 0; acc[s] = 0; link_f[s] = 0; link_b[s] = 0; }
     int64_t nev = 0, now = 0;
     if (tl_ar) for (int s = 0; s < 2 * pp; s++) tl_ar[s] = -1;
     const int64_t cap = cl->bucket;
@@ -304,7 +306,7 @@ static void simulate_one(const costs_t *co, const cluster_t *cl,
                             heap_push(h, t, EV_GRAD_READY, s__, j, l);                  \
                     }                                                                   \
                 }                                                                       \
-                if (cl->p2p_blocking) {           /* the send runs on the device */     \
+                if (cl->p2p_blocking == 1) {      /* the send runs on the device */     \
                     if (kd == 0 && s__ + 1 < pp) t += pf[s__];                          \
                     if (kd == 1 && s__ > 0) t += pb[s__];                               \
                 }                                                                       \
@@ -327,11 +329,25 @@ static void simulate_one(const costs_t *co, const cluster_t *cl,
             busy[s] = 0;
             next[s]++;
             if (kd == 0 && s + 1 < pp) {            /* (e_comm, t + e.elapsed, m) of Algorithm 1 */
-                heap_push(h, now + (cl->p2p_blocking ? 0 : pf[s]), EV_ARRIVE_F, s + 1, j, 0);
+                int64_t arrive = now + pf[s];
+                if (cl->p2p_blocking == 1) arrive = now;
+                if (cl->p2p_blocking == 2) {         /* the link carries one activation at a time */
+                    int64_t depart = now > link_f[s] ? now : link_f[s];
+                    arrive = depart + pf[s];
+                    link_f[s] = arrive;
+                }
+                heap_push(h, arrive, EV_ARRIVE_F, s + 1, j, 0);
                 mb_[s] += pf[s]; nev++;
             }
             if (kd == 1 && s > 0) {
-                heap_push(h, now + (cl->p2p_blocking ? 0 : pb[s]), EV_ARRIVE_B, s - 1, j, 0);
+                int64_t arrive = now + pb[s];
+                if (cl->p2p_blocking == 1) arrive = now;
+                if (cl->p2p_blocking == 2) {
+                    int64_t depart = now > link_b[s] ? now : link_b[s];
+                    arrive = depart + pb[s];
+                    link_b[s] = arrive;
+                }
+                heap_push(h, arrive, EV_ARRIVE_B, s - 1, j, 0);
                 mb_[s] += pb[s]; nev++;
             }
             if (next[s] == 2 * m && dp > 1 && cap == 0 && sync) {   /* trailing gradient all-reduce */

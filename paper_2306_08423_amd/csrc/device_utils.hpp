@@ -132,7 +132,7 @@ struct ClusterDev {
     int32_t num_devices, gpus_per_node;
     int64_t alpha[2], beta[2];
     int64_t bucket;
-    int32_t blocking;          // p2p events occupy the sender
+    int32_t blocking;          // 1: p2p events occupy the sender; 2: sends queue on their link
 };
 
 __device__ __forceinline__ int64_t p2p_ns(const ClusterDev& cl, int64_t bytes, int k) {

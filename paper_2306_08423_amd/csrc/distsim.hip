@@ -77,13 +77,14 @@ ClusterDev to_dev(const distsim_cluster& c) {
     d.alpha[0] = c.alpha_ns[0]; d.alpha[1] = c.alpha_ns[1];
     d.beta[0] = c.beta_bytes_per_ns[0]; d.beta[1] = c.beta_bytes_per_ns[1];
     d.bucket = c.dp_bucket_bytes;
-    d.blocking = c.p2p_blocking != 0;
+    d.blocking = c.p2p_blocking;
     return d;
 }
 
 bool cluster_ok(const distsim_cluster* c) {
     return c && c->num_devices >= 1 && c->gpus_per_node >= 1 && c->alpha_ns[0] >= 0 && c->alpha_ns[1] >= 0 &&
-           c->beta_bytes_per_ns[0] >= 1 && c->beta_bytes_per_ns[1] >= 1 && c->dp_bucket_bytes >= 0;
+           c->beta_bytes_per_ns[0] >= 1 && c->beta_bytes_per_ns[1] >= 1 && c->dp_bucket_bytes >= 0 &&
+           c->p2p_blocking >= 0 && c->p2p_blocking <= 2;
 }
 
 // Waves that sweep the wave-items: enough to fill every SIMD, never more than one per candidate.
@@ -238,7 +239,10 @@ int distsim_simulate(distsim_ctx* ctx, const distsim_cluster* cluster, const dis
     }
     {
         Timer t(ctx, st, DISTSIM_K_SIMULATE);
-        hipLaunchKernelGGL(k_simulate, dim3(simulate_grid(ctx, C)), dim3(256), 0, st, co, cl, ca, ws, ev, out);
+        if (cl.blocking == 2)
+            hipLaunchKernelGGL(k_simulate_links, dim3(simulate_grid(ctx, C)), dim3(256), 0, st, co, cl, ca, ws, ev, out);
+        else
+            hipLaunchKernelGGL(k_simulate, dim3(simulate_grid(ctx, C)), dim3(256), 0, st, co, cl, ca, ws, ev, out);
     }
     HIP_TRY(hipGetLastError());
     return DISTSIM_OK;

@@ -166,7 +166,7 @@ struct Park {
 
 // Simulates U wave-items at once.  For U = 2 the two items must have the same shape in every
 // lane (pp, m, schedule): then they share patterns, masks and control flow.
-template <int U>
+template <int U, bool LINKS = false>
 __device__ __forceinline__ void simulate_items(const ClusterDev& cl, const CandDev& ca, const Workspace& ws,
                                                const EventsDev& ev, const SimOut& out, int L, int64_t w0,
                                                int sh, const Desc (&d)[U], int lane,
@@ -181,6 +181,7 @@ __device__ __forceinline__ void simulate_items(const ClusterDev& cl, const CandD
     const int m = act ? d[0].m : 0;
 
     Sweep sw[U];
+    double sendF[U], sendB[U];      // LINKS: duration of this stage's outgoing forward / backward send
 #pragma unroll
     for (int u = 0; u < U; u++) {
         const int v = d[u].meta >> 16, dp = d[u].meta ? d[u].dp : 1;
@@ -198,12 +199,13 @@ __device__ __forceinline__ void simulate_items(const ClusterDev& cl, const CandD
         const bool has_ar = act && dp > 1 && r.G > 0 && sched != 2;
         // p2p on the incoming edges (the neighbours' outgoing events): latency of the edge, or,
         // when the sender is occupied by it, part of the sender's task; -inf = no edge
-        const int64_t pf_task = cl.blocking ? r.PF : 0, pb_task = cl.blocking ? r.PB : 0;
+        const int64_t pf_task = cl.blocking == 1 ? r.PF : 0, pb_task = cl.blocking == 1 ? r.PB : 0;
         sw[u].own = 0.0;
         sw[u].Fd = (double)(r.FT + pf_task);
         sw[u].Bd = (double)(r.BT + pb_task);
         sw[u].pfL = from_prev_lane((double)(r.PF - pf_task));
         sw[u].pbR = from_next_lane((double)(r.PB - pb_task));
+        sendF[u] = (double)r.PF; sendB[u] = (double)r.PB;
         if (!(act && s > 0)) sw[u].pfL = ninf;
         if (!(act && s + 1 < pp)) sw[u].pbR = ninf;
         // what only the epilogue needs waits in LDS
@@ -228,119 +230,153 @@ __device__ __forceinline__ void simulate_items(const ClusterDev& cl, const CandD
         f2lo = 2 * wq + 2; f2hi = 2 * m - 2;
         blo = 2 * pp - 1 - 2 * s; bhi = blo + 2 * m - 2;
     }
-    // Levels at which some lane of the wavefront has a forward / a backward task: forwards from
-    // level 0 to gLastF, backwards from gFirstB to gLastB (the last level of the sweep).
-    const int lastFx = (f2lo <= f2hi && f2hi > f1hi) ? f2hi : f1hi;
-    const int gLastF = wave_max_i32(act ? s + lastFx : -1);
-    const int gFirstB = -wave_max_i32(act ? -(s + blo) : -(1 << 30));
-    const int gLastB = wave_max_i32(act ? s + bhi : -1);
-    const int nlev = gLastB + 1;
-
-    // 1F1B past its warm-up runs forwards on even x and backwards on odd x.  When every
-    // candidate of the wavefront is 1F1B with one pp, a level that has both kinds therefore
-    // splits the lanes by parity, and one merged operand (previous lane for the forward
-    // lanes, next lane for the backward lanes) feeds a single task step.
-    const int ppu = wave_max_i32(pp);
-    const bool par_ok = width >= 2 && __builtin_amdgcn_ballot_w64(act && (sched == 0 || pp != ppu)) == 0;
-    const bool even_s = (s & 1) == 0;
-    const int adrE = (even_s ? lane - 1 : lane + 1) * 4;
-
-    for (int l0 = 0; l0 < nlev; l0 += 32) {
-        const int x0 = l0 - s;
-        const uint32_t even_x = (x0 & 1) ? 0x55555555u : 0xaaaaaaaau;       // levels with even x
-        uint32_t PFb = level_bits(-x0, f1hi - x0) | (level_bits(f2lo - x0, f2hi - x0) & even_x);
-        uint32_t PBb = level_bits(blo - x0, bhi - x0);
-        if (sched != 0) PBb &= ((blo - x0) & 1) ? 0x55555555u : 0xaaaaaaaau;   // x - blo even
-        if (!act) { PFb = 0; PBb = 0; }
-        // chunk-relative level ranges in which a lane may have a forward / a backward task
-        const bool anyF = gLastF >= l0, anyB = gFirstB < l0 + 32;
-        const int firstF = anyF ? 0 : 64, lastF = anyF ? (gLastF - l0 < 31 ? gLastF - l0 : 31) : -1;
-        const int firstB = anyB ? (gFirstB > l0 ? gFirstB - l0 : 0) : 64;
-        const int lastB = anyB ? (gLastB - l0 < 31 ? gLastB - l0 : 31) : -1;
-        const int endk = (lastF > lastB ? lastF : lastB) + 1;
-        int k = firstF < firstB ? firstF : firstB;
-        PFb = shl32(PFb, k); PBb = shl32(PBb, k);            // skip the idle levels in front
-        uint64_t kmask, kmask2;
-        while (k < endk) {
-            const bool inF = k >= firstF && k <= lastF, inB = k >= firstB && k <= lastB;
-            int e = endk;                                     // next level at which the mix changes
-            if (firstF > k && firstF < e) e = firstF;
-            if (firstB > k && firstB < e) e = firstB;
-            if (lastF + 1 > k && lastF + 1 < e) e = lastF + 1;
-            if (lastB + 1 > k && lastB + 1 < e) e = lastB + 1;
-            const int len = e - k;
-            if (inF && inB && par_ok) {
-                // roles by parity: on even levels the even stages run forwards, on odd levels
-                // the odd stages do
-                double latE[U], durE[U], latO[U], durO[U];
-#pragma unroll
-                for (int u = 0; u < U; u++) {
-                    latE[u] = even_s ? sw[u].pfL : sw[u].pbR; durE[u] = even_s ? sw[u].Fd : sw[u].Bd;
-                    latO[u] = even_s ? sw[u].pbR : sw[u].pfL; durO[u] = even_s ? sw[u].Bd : sw[u].Fd;
+    if constexpr (LINKS) {
+        // Sends queue on their link (p2p_blocking = 2): every lane keeps the arrival time of its
+        // latest forward send and of its latest backward send; a send starts when its task has
+        // ended and the link is free, and the neighbour reads the arrival time instead of the end
+        // of the task.  Plain per-level form of the sweep, one item at a time.
+        static_assert(U == 1, "the serialised sweep takes one item at a time");
+        const int nlev = wave_max_i32(act ? 2 * (m + pp - 1) : 0);
+        const bool hasL = act && s > 0, hasR = act && s + 1 < pp;
+        double own = 0.0, linkF = 0.0, linkB = 0.0;
+        for (int l0 = 0; l0 < nlev; l0 += 32) {
+            const int x0 = l0 - s;
+            const uint32_t even_x = (x0 & 1) ? 0x55555555u : 0xaaaaaaaau;
+            uint32_t PFb = level_bits(-x0, f1hi - x0) | (level_bits(f2lo - x0, f2hi - x0) & even_x);
+            uint32_t PBb = level_bits(blo - x0, bhi - x0);
+            if (sched != 0) PBb &= ((blo - x0) & 1) ? 0x55555555u : 0xaaaaaaaau;
+            if (!act) { PFb = 0; PBb = 0; }
+            const int kend = nlev - l0 < 32 ? nlev - l0 : 32;
+            for (int k = 0; k < kend; k++) {
+                const double arrL = from_prev_lane(linkF), arrR = from_next_lane(linkB);
+                if (PFb >> 31) {
+                    const double t0 = hasL && arrL > own ? arrL : own;
+                    own = t0 + sw[0].Fd;
+                    if (hasR) linkF = (own > linkF ? own : linkF) + sendF[0];
+                } else if (PBb >> 31) {
+                    const double t0 = hasR && arrR > own ? arrR : own;
+                    own = t0 + sw[0].Bd;
+                    if (hasL) linkB = (own > linkB ? own : linkB) + sendB[0];
                 }
-                uint32_t Pc = PFb | PBb;
-                // straight-line (odd level, even level) pairs, so that both kinds of level keep
-                // their state in the same registers; a leading even and a trailing odd level apart
-                auto odd_level = [&]() {
-                    if constexpr (U == 1) {
-                        double nb = from_pair_partner(sw[0].own);
-                        DISTSIM_STEP1(Pc, sw[0].own, nb, latO[0], durO[0]);
-                    } else {
-                        double na = from_pair_partner(sw[0].own), nb = from_pair_partner(sw[U - 1].own);
-                        DISTSIM_STEP2(Pc, sw[0].own, na, latO[0], durO[0], sw[U - 1].own, nb, latO[U - 1], durO[U - 1]);
-                    }
-                };
-                auto even_level = [&]() {
-                    if constexpr (U == 1) {
-                        double nb = from_lanes(sw[0].own, adrE);
-                        DISTSIM_STEP1(Pc, sw[0].own, nb, latE[0], durE[0]);
-                    } else {
-                        double na = from_lanes(sw[0].own, adrE), nb = from_lanes(sw[U - 1].own, adrE);
-                        DISTSIM_STEP2(Pc, sw[0].own, na, latE[0], durE[0], sw[U - 1].own, nb, latE[U - 1], durE[U - 1]);
-                    }
-                };
-                int j = 0;
-                if (((l0 + k) & 1) == 0) { even_level(); j = 1; }
-                for (; j + 1 < len; j += 2) { odd_level(); even_level(); }
-                if (j < len) odd_level();
-                PFb = shl32(PFb, len); PBb = shl32(PBb, len);
-            } else if (inF && inB) {
-                for (int j = 0; j < len; j++) {
-                    double fl = from_prev_lane(sw[0].own), fr = from_next_lane(sw[0].own);
-                    DISTSIM_STEPFB1(PFb, PBb, sw[0].own, fl, fr, sw[0].pfL, sw[0].pbR, sw[0].Fd, sw[0].Bd);
-                    if constexpr (U == 2) {
-                        double gl = from_prev_lane(sw[U - 1].own), gr = from_next_lane(sw[U - 1].own);
-                        DISTSIM_APPLYFB(sw[U - 1].own, gl, gr, sw[U - 1].pfL, sw[U - 1].pbR, sw[U - 1].Fd, sw[U - 1].Bd);
-                    }
-                }
-            } else if (inF) {
-                for (int j = 0; j < len; j++) {
-                    if constexpr (U == 1) {
-                        double fl = from_prev_lane(sw[0].own);
-                        DISTSIM_STEP1(PFb, sw[0].own, fl, sw[0].pfL, sw[0].Fd);
-                    } else {
-                        double fl = from_prev_lane(sw[0].own), gl = from_prev_lane(sw[U - 1].own);
-                        DISTSIM_STEP2(PFb, sw[0].own, fl, sw[0].pfL, sw[0].Fd, sw[U - 1].own, gl, sw[U - 1].pfL, sw[U - 1].Fd);
-                    }
-                }
-                PBb = shl32(PBb, len);
-            } else if (inB) {
-                for (int j = 0; j < len; j++) {
-                    if constexpr (U == 1) {
-                        double fr = from_next_lane(sw[0].own);
-                        DISTSIM_STEP1(PBb, sw[0].own, fr, sw[0].pbR, sw[0].Bd);
-                    } else {
-                        double fr = from_next_lane(sw[0].own), gr = from_next_lane(sw[U - 1].own);
-                        DISTSIM_STEP2(PBb, sw[0].own, fr, sw[0].pbR, sw[0].Bd, sw[U - 1].own, gr, sw[U - 1].pbR, sw[U - 1].Bd);
-                    }
-                }
-                PFb = shl32(PFb, len);
-            } else {
-                PFb = shl32(PFb, len); PBb = shl32(PBb, len);
+                PFb <<= 1; PBb <<= 1;
             }
-            k = e;
         }
-        (void)kmask; (void)kmask2;
+        sw[0].own = own;
+    } else {
+        // Levels at which some lane of the wavefront has a forward / a backward task: forwards from
+        // level 0 to gLastF, backwards from gFirstB to gLastB (the last level of the sweep).
+        const int lastFx = (f2lo <= f2hi && f2hi > f1hi) ? f2hi : f1hi;
+        const int gLastF = wave_max_i32(act ? s + lastFx : -1);
+        const int gFirstB = -wave_max_i32(act ? -(s + blo) : -(1 << 30));
+        const int gLastB = wave_max_i32(act ? s + bhi : -1);
+        const int nlev = gLastB + 1;
+
+        // 1F1B past its warm-up runs forwards on even x and backwards on odd x.  When every
+        // candidate of the wavefront is 1F1B with one pp, a level that has both kinds therefore
+        // splits the lanes by parity, and one merged operand (previous lane for the forward
+        // lanes, next lane for the backward lanes) feeds a single task step.
+        const int ppu = wave_max_i32(pp);
+        const bool par_ok = width >= 2 && __builtin_amdgcn_ballot_w64(act && (sched == 0 || pp != ppu)) == 0;
+        const bool even_s = (s & 1) == 0;
+        const int adrE = (even_s ? lane - 1 : lane + 1) * 4;
+
+        for (int l0 = 0; l0 < nlev; l0 += 32) {
+            const int x0 = l0 - s;
+            const uint32_t even_x = (x0 & 1) ? 0x55555555u : 0xaaaaaaaau;       // levels with even x
+            uint32_t PFb = level_bits(-x0, f1hi - x0) | (level_bits(f2lo - x0, f2hi - x0) & even_x);
+            uint32_t PBb = level_bits(blo - x0, bhi - x0);
+            if (sched != 0) PBb &= ((blo - x0) & 1) ? 0x55555555u : 0xaaaaaaaau;   // x - blo even
+            if (!act) { PFb = 0; PBb = 0; }
+            // chunk-relative level ranges in which a lane may have a forward / a backward task
+            const bool anyF = gLastF >= l0, anyB = gFirstB < l0 + 32;
+            const int firstF = anyF ? 0 : 64, lastF = anyF ? (gLastF - l0 < 31 ? gLastF - l0 : 31) : -1;
+            const int firstB = anyB ? (gFirstB > l0 ? gFirstB - l0 : 0) : 64;
+            const int lastB = anyB ? (gLastB - l0 < 31 ? gLastB - l0 : 31) : -1;
+            const int endk = (lastF > lastB ? lastF : lastB) + 1;
+            int k = firstF < firstB ? firstF : firstB;
+            PFb = shl32(PFb, k); PBb = shl32(PBb, k);            // skip the idle levels in front
+            uint64_t kmask, kmask2;
+            while (k < endk) {
+                const bool inF = k >= firstF && k <= lastF, inB = k >= firstB && k <= lastB;
+                int e = endk;                                     // next level at which the mix changes
+                if (firstF > k && firstF < e) e = firstF;
+                if (firstB > k && firstB < e) e = firstB;
+                if (lastF + 1 > k && lastF + 1 < e) e = lastF + 1;
+                if (lastB + 1 > k && lastB + 1 < e) e = lastB + 1;
+                const int len = e - k;
+                if (inF && inB && par_ok) {
+                    // roles by parity: on even levels the even stages run forwards, on odd levels
+                    // the odd stages do
+                    double latE[U], durE[U], latO[U], durO[U];
+    #pragma unroll
+                    for (int u = 0; u < U; u++) {
+                        latE[u] = even_s ? sw[u].pfL : sw[u].pbR; durE[u] = even_s ? sw[u].Fd : sw[u].Bd;
+                        latO[u] = even_s ? sw[u].pbR : sw[u].pfL; durO[u] = even_s ? sw[u].Bd : sw[u].Fd;
+                    }
+                    uint32_t Pc = PFb | PBb;
+                    // straight-line (odd level, even level) pairs, so that both kinds of level keep
+                    // their state in the same registers; a leading even and a trailing odd level apart
+                    auto odd_level = [&]() {
+                        if constexpr (U == 1) {
+                            double nb = from_pair_partner(sw[0].own);
+                            DISTSIM_STEP1(Pc, sw[0].own, nb, latO[0], durO[0]);
+                        } else {
+                            double na = from_pair_partner(sw[0].own), nb = from_pair_partner(sw[U - 1].own);
+                            DISTSIM_STEP2(Pc, sw[0].own, na, latO[0], durO[0], sw[U - 1].own, nb, latO[U - 1], durO[U - 1]);
+                        }
+                    };
+                    auto even_level = [&]() {
+                        if constexpr (U == 1) {
+                            double nb = from_lanes(sw[0].own, adrE);
+                            DISTSIM_STEP1(Pc, sw[0].own, nb, latE[0], durE[0]);
+                        } else {
+                            double na = from_lanes(sw[0].own, adrE), nb = from_lanes(sw[U - 1].own, adrE);
+                            DISTSIM_STEP2(Pc, sw[0].own, na, latE[0], durE[0], sw[U - 1].own, nb, latE[U - 1], durE[U - 1]);
+                        }
+                    };
+                    int j = 0;
+                    if (((l0 + k) & 1) == 0) { even_level(); j = 1; }
+                    for (; j + 1 < len; j += 2) { odd_level(); even_level(); }
+                    if (j < len) odd_level();
+                    PFb = shl32(PFb, len); PBb = shl32(PBb, len);
+                } else if (inF && inB) {
+                    for (int j = 0; j < len; j++) {
+                        double fl = from_prev_lane(sw[0].own), fr = from_next_lane(sw[0].own);
+                        DISTSIM_STEPFB1(PFb, PBb, sw[0].own, fl, fr, sw[0].pfL, sw[0].pbR, sw[0].Fd, sw[0].Bd);
+                        if constexpr (U == 2) {
+                            double gl = from_prev_lane(sw[U - 1].own), gr = from_next_lane(sw[U - 1].own);
+                            DISTSIM_APPLYFB(sw[U - 1].own, gl, gr, sw[U - 1].pfL, sw[U - 1].pbR, sw[U - 1].Fd, sw[U - 1].Bd);
+                        }
+                    }
+                } else if (inF) {
+                    for (int j = 0; j < len; j++) {
+                        if constexpr (U == 1) {
+                            double fl = from_prev_lane(sw[0].own);
+                            DISTSIM_STEP1(PFb, sw[0].own, fl, sw[0].pfL, sw[0].Fd);
+                        } else {
+                            double fl = from_prev_lane(sw[0].own), gl = from_prev_lane(sw[U - 1].own);
+                            DISTSIM_STEP2(PFb, sw[0].own, fl, sw[0].pfL, sw[0].Fd, sw[U - 1].own, gl, sw[U - 1].pfL, sw[U - 1].Fd);
+                        }
+                    }
+                    PBb = shl32(PBb, len);
+                } else if (inB) {
+                    for (int j = 0; j < len; j++) {
+                        if constexpr (U == 1) {
+                            double fr = from_next_lane(sw[0].own);
+                            DISTSIM_STEP1(PBb, sw[0].own, fr, sw[0].pbR, sw[0].Bd);
+                        } else {
+                            double fr = from_next_lane(sw[0].own), gr = from_next_lane(sw[U - 1].own);
+                            DISTSIM_STEP2(PBb, sw[0].own, fr, sw[0].pbR, sw[0].Bd, sw[U - 1].own, gr, sw[U - 1].pbR, sw[U - 1].Bd);
+                        }
+                    }
+                    PFb = shl32(PFb, len);
+                } else {
+                    PFb = shl32(PFb, len); PBb = shl32(PBb, len);
+                }
+                k = e;
+            }
+            (void)kmask; (void)kmask2;
+        }
     }
 
 #pragma unroll
@@ -432,6 +468,26 @@ __global__ __launch_bounds__(kSimBlock, 6) void k_simulate(CostsDev co, ClusterD
                 simulate_items<1>(cl, ca, ws, ev, out, L, w + q, q ? ib.sh : ia.sh, one, lane, park);
             }
         }
+    }
+}
+
+// Same contract as k_simulate for p2p_blocking = 2 (sends queue on their link): one item per
+// wavefront turn, plain sweep.
+__global__ __launch_bounds__(kSimBlock) void k_simulate_links(CostsDev co, ClusterDev cl, CandDev ca, Workspace ws,
+                                                              EventsDev ev, SimOut out) {
+    const int lane = lane_id();
+    const int64_t wave0 = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / kWave;
+    const int64_t nwaves = ((int64_t)gridDim.x * blockDim.x) / kWave;
+    int64_t W = ws.hdr[H_NUM_ITEMS];
+    if (W * kWave > ev.stage_cap) W = ev.stage_cap / kWave;
+    __shared__ Park park;
+    for (int64_t w = wave0; w < W; w += nwaves) {
+        const Item it = decode_item(ws.hdr, w);
+        const int64_t pos = it.pos0 + (lane >> it.sh);
+        Desc d{};
+        if (pos < it.class_end) d = ws.desc[pos];
+        const Desc one[1] = {d};
+        simulate_items<1, true>(cl, ca, ws, ev, out, co.L, w, it.sh, one, lane, park);
     }
 }
 

@@ -122,7 +122,7 @@ __global__ __launch_bounds__(kTlWaves * kWave) void k_timeline(CostsDev co, Clus
         // a candidate whose partition or range check fails gets no entries
         if (stage_row(cl, ws, L, width, s, pp, v, m, dp, tp, lo, hi, r) != 0) act = false;
         if (!act) { pp = 0; m = 0; }
-        const int64_t pf_task = cl.blocking ? r.PF : 0, pb_task = cl.blocking ? r.PB : 0;
+        const int64_t pf_task = cl.blocking == 1 ? r.PF : 0, pb_task = cl.blocking == 1 ? r.PB : 0;
         const int64_t Fd_i = r.FC + r.FA + pf_task, Bd_i = r.BC + r.BA + pb_task;
         const double Fd = (double)Fd_i, Bd = (double)Bd_i;
         double pfL = from_prev_lane((double)(r.PF - pf_task)), pbR = from_next_lane((double)(r.PB - pb_task));
@@ -146,6 +146,9 @@ __global__ __launch_bounds__(kTlWaves * kWave) void k_timeline(CostsDev co, Clus
         }
         const int nlev = wave_max_i32(act ? 2 * (m + pp - 1) : 0);
         double own = 0.0;
+        double linkF = 0.0, linkB = 0.0;                      // p2p_blocking = 2: arrival of the lane's latest sends
+        const double sendF = (double)r.PF, sendB = (double)r.PB;
+        const bool hasL = act && s > 0, hasR = act && s + 1 < pp;
         int nF = 0, nB = 0, fF = 0, fB = 0;                   // tasks run / written out, per kind
         uint64_t kmask = 0, kmask2 = 0;
         for (int l0 = 0; l0 < nlev; l0 += 32) {
@@ -158,20 +161,39 @@ __global__ __launch_bounds__(kTlWaves * kWave) void k_timeline(CostsDev co, Clus
             const bool anyF = wave_or_u32(PFb) != 0, anyB = wave_or_u32(PBb) != 0;
             const int kend = nlev - l0 < 32 ? nlev - l0 : 32;
             for (int kk = 0; kk < kend; kk++) {
-                if (anyF && anyB) {
+                bool ranF = false, ranB = false;                 // this lane ran a forward / backward task
+                double tF = 0.0, tB = 0.0;                       // and it started at
+                if (cl.blocking == 2) {
+                    // sends queue on their link: the neighbour reads the arrival time of the send
+                    const double arrL = from_prev_lane(linkF), arrR = from_next_lane(linkB);
+                    if (PFb >> 31) {
+                        tF = hasL && arrL > own ? arrL : own;
+                        own = tF + Fd;
+                        if (hasR) linkF = (own > linkF ? own : linkF) + sendF;
+                        ranF = true;
+                    } else if (PBb >> 31) {
+                        tB = hasR && arrR > own ? arrR : own;
+                        own = tB + Bd;
+                        if (hasL) linkB = (own > linkB ? own : linkB) + sendB;
+                        ranB = true;
+                    }
+                    PFb <<= 1; PBb <<= 1;
+                } else if (anyF && anyB) {
                     double tl = from_prev_lane(own), tr = from_next_lane(own);
                     DISTSIM_STEPFB1(PFb, PBb, own, tl, tr, pfL, pbR, Fd, Bd);
-                    if ((kmask >> lane) & 1) { sm.ring[0][lane][nF & (kTlRing - 1)] = tl; nF++; }
-                    if ((kmask2 >> lane) & 1) { sm.ring[1][lane][nB & (kTlRing - 1)] = tr; nB++; }
+                    ranF = (kmask >> lane) & 1; tF = tl;
+                    ranB = (kmask2 >> lane) & 1; tB = tr;
                 } else if (anyF) {
                     double tl = from_prev_lane(own);
                     DISTSIM_STEP1(PFb, own, tl, pfL, Fd);
-                    if ((kmask >> lane) & 1) { sm.ring[0][lane][nF & (kTlRing - 1)] = tl; nF++; }
+                    ranF = (kmask >> lane) & 1; tF = tl;
                 } else if (anyB) {
                     double tr = from_next_lane(own);
                     DISTSIM_STEP1(PBb, own, tr, pbR, Bd);
-                    if ((kmask >> lane) & 1) { sm.ring[1][lane][nB & (kTlRing - 1)] = tr; nB++; }
+                    ranB = (kmask >> lane) & 1; tB = tr;
                 }
+                if (ranF) { sm.ring[0][lane][nF & (kTlRing - 1)] = tF; nF++; }
+                if (ranB) { sm.ring[1][lane][nB & (kTlRing - 1)] = tB; nB++; }
                 const bool last = l0 + kk == nlev - 1;
                 if ((kk & (kTlFlush - 1)) != kTlFlush - 1 && !last) continue;
                 // flush: per row the entries [flushed, upto), upto = done rounded down to a sector

@@ -125,6 +125,34 @@ def test_blocking_p2p(H, oracle_mod):
     H.assert_same(H.run_hip(wb, table=False), oracle_mod.simulate(wb, nthreads=NT), what=wb.name)
 
 
+def test_serialised_links(H, oracle_mod):
+    """p2p_blocking = 2: sends queue on their link.  Activations made large enough that the queueing
+    changes batch times; all three schedules; the ragged hetero64 shapes; the timeline dump."""
+    _say("[case] serialised links")
+    for name in ("gpt24", "gpt48"):
+        w = make_workload(name)
+        costs = dict(w.costs); costs["act_bytes"] = w.costs["act_bytes"] * 40
+        cand = {k: v.copy() for k, v in w.cand.items()}
+        cand["schedule"] = (np.arange(len(cand["schedule"])) % 3).astype(np.uint8)
+        free = Workload(name + "+big act", costs, w.cluster, cand)
+        cl = dict(w.cluster); cl["p2p_blocking"] = 2
+        ws = Workload(name + "+links", costs, cl, cand)
+        ora = oracle_mod.simulate(ws, nthreads=NT)
+        base = oracle_mod.simulate(free, nthreads=NT)
+        ok = ora["status"] == 0
+        assert np.all(ora["batch_ns"][ok] >= base["batch_ns"][ok]) and (ora["batch_ns"][ok] > base["batch_ns"][ok]).sum() > 50
+        H.assert_same(H.run_hip(ws), ora, what=ws.name)
+        H.assert_same(H.run_hip(ws, table=False), ora, what=ws.name + " no table")
+    _timeline_parity(H, oracle_mod, ws, np.arange(2, ws.C, 11))
+    w = make_workload("hetero64", C=30000)
+    cl = dict(w.cluster); cl["p2p_blocking"] = 2
+    costs = dict(w.costs); costs["act_bytes"] = w.costs["act_bytes"] * 25
+    ws = Workload("hetero64+links", costs, cl, w.cand)
+    H.assert_same(H.run_hip(ws, table=False), oracle_mod.simulate(ws, nthreads=NT), what=ws.name)
+    rng = np.random.default_rng(9)
+    _timeline_parity(H, oracle_mod, ws, np.sort(rng.choice(ws.C, 60, replace=False)))
+
+
 def _timeline_parity(H, oracle_mod, w, idx):
     import torch
     import paper_2306_08423_amd as ds

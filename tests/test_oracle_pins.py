@@ -321,6 +321,88 @@ def test_blocking_p2p_against_task_graph(oracle_mod):
     assert np.array_equal(a["comm_busy_ns"], b["comm_busy_ns"])
 
 
+def test_serialised_links_against_graph_with_send_nodes(oracle_mod):
+    """p2p_blocking = 2: sends do not occupy the device but queue on their link.  Graph: every task
+    and every send is a node; a send starts after its task has ended and after the previous send on
+    the same link has arrived; the consumer starts after the send has arrived.  Solved by relaxation."""
+    rng = np.random.default_rng(33)
+    L = 6
+    slower = 0
+    for trial in range(300):
+        pp = int(rng.integers(1, 5))
+        m = int(rng.integers(1, 7))
+        sched = int(rng.integers(0, 3))
+        cuts = sorted(rng.choice(np.arange(1, L), size=pp - 1, replace=False).tolist())
+        bnd = [0] + cuts + [L]
+        fc = rng.integers(0, 30, L).tolist()
+        bc = rng.integers(0, 30, L).tolist()
+        act = (rng.integers(0, 40, L) * 5).tolist()          # sends often longer than the tasks
+        costs = mk_costs(fc, bc, act=act)
+        cl = mk_cluster(pp, g=1 << 20, alpha=(2, 0), beta=(5, 1), blocking=2)
+        r = one(oracle_mod, costs, cl, (1, 1, pp, m, sched, bnd), timeline=True)
+        pf = [2 + act[bnd[s + 1] - 1] // 5 for s in range(pp - 1)] + [0]
+        pb = [0] + [2 + act[bnd[s] - 1] // 5 for s in range(1, pp)]
+        F, B = _stage_sums(fc, bnd), _stage_sums(bc, bnd)
+        dur = lambda k, s: F[s] if k == "F" else B[s]
+        # nodes ("T", k, s, j) and ("S", k, s, j); preds as (node, weight added to the node's START)
+        preds = {}
+        for s in range(pp):
+            order = device_order(1 if sched else 0, pp, m, s)
+            for i, (k, j) in enumerate(order):
+                p = []
+                if i > 0:
+                    pk, pj = order[i - 1]
+                    p.append((("T", pk, s, pj), dur(pk, s)))
+                if k == "F" and s > 0:
+                    p.append((("S", "F", s - 1, j), pf[s - 1]))
+                if k == "B" and s < pp - 1:
+                    p.append((("S", "B", s + 1, j), pb[s + 1]))
+                if k == "B" and s == pp - 1:
+                    p.append((("T", "F", s, j), F[s]))
+                preds[("T", k, s, j)] = p
+            for j in range(m):
+                if s < pp - 1:
+                    p = [(("T", "F", s, j), F[s])]
+                    if j > 0:
+                        p.append((("S", "F", s, j - 1), pf[s]))
+                    preds[("S", "F", s, j)] = p
+                if s > 0:
+                    p = [(("T", "B", s, j), B[s])]
+                    if j > 0:
+                        p.append((("S", "B", s, j - 1), pb[s]))
+                    preds[("S", "B", s, j)] = p
+        start = {n: 0 for n in preds}
+        changed, rounds = True, 0
+        while changed:
+            changed = False
+            rounds += 1
+            assert rounds < 10 * len(preds) + 10
+            for n, ps in preds.items():
+                v = max([start[q] + wgt for q, wgt in ps], default=0)
+                if v != start[n]:
+                    start[n] = v
+                    changed = True
+        for n, v in start.items():
+            if n[0] != "T":
+                continue
+            kd = 0 if n[1] == "F" else 1
+            assert r["start"][kd, n[2], n[3]] == v, (trial, n)
+            assert r["end"][kd, n[2], n[3]] == v + dur(n[1], n[2])
+        assert r["batch_ns"][0] == max(start[("T", "B", s, m - 1)] + B[s] for s in range(pp))
+        for s in range(pp):
+            assert r["comm_busy_ns"][s] == m * (pf[s] + pb[s])
+        free = one(oracle_mod, costs, mk_cluster(pp, g=1 << 20, alpha=(2, 0), beta=(5, 1)), (1, 1, pp, m, sched, bnd))
+        assert r["batch_ns"][0] >= free["batch_ns"][0]
+        slower += int(r["batch_ns"][0] > free["batch_ns"][0])
+    assert slower > 10            # the queueing really bites in a good number of the cases
+    # sends shorter than every task never queue: same result as the latency reading
+    costs = mk_costs([50] * 6, [70] * 6, act=[5] * 6)
+    for sched in (0, 1):
+        a = one(oracle_mod, costs, mk_cluster(3, g=1 << 20, alpha=(2, 0), beta=(5, 1)), (1, 1, 3, 5, sched, None))
+        b = one(oracle_mod, costs, mk_cluster(3, g=1 << 20, alpha=(2, 0), beta=(5, 1), blocking=2), (1, 1, 3, 5, sched, None))
+        assert a["batch_ns"][0] == b["batch_ns"][0]
+
+
 def test_exhaustive_partitions_small(oracle_mod):
     """Every partition of L = 5 layers, both schedules, m = 1..4, against the task graph."""
     L = 5
