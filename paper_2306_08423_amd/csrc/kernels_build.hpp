@@ -285,7 +285,12 @@ __device__ __forceinline__ int stage_check(const ClusterDev& cl, int L, int widt
 // The 2^53 guard: every timestamp of the pipeline phase is bounded by m * (all task and p2p
 // durations of the candidate); per_stage is this lane's share of that sum.
 __device__ __forceinline__ bool stage_out_of_range(int64_t per_stage, int m, int width) {
-    const uint64_t t1 = (uint64_t)group_sum(per_stage, width);
+    // a cheap sufficient test first: if width * m * (a lane's share) stays below 2^53 in every
+    // lane, so does m * (sum of the shares); only otherwise the sum itself is formed
+    const uint64_t v = (uint64_t)per_stage;
+    const bool small = (v >> 32) == 0 && (uint64_t)(uint32_t)v * (uint32_t)(m * width) < (1ull << 53);
+    uint64_t t1 = 0;
+    if (__builtin_amdgcn_ballot_w64(!small) != 0) t1 = (uint64_t)group_sum(per_stage, width);
     return __umul64hi(t1, (uint64_t)m) != 0 || t1 * (uint64_t)m >= (1ull << 53);
 }
 
