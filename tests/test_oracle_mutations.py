@@ -1,0 +1,99 @@
+"""Are the pins sharp?  Each case plants one plausible mistake in a COPY of the oracle's source (on
+the CPU, in a temporary directory), builds it, points the oracle's front end at the mutant and runs
+the pins: at least one of them has to fail.  The real oracle is restored afterwards."""
+import ctypes
+import os
+import subprocess
+
+import pytest
+
+import oracle
+import test_oracle_pins as pins
+
+SRC = os.path.join(os.path.dirname(os.path.abspath(oracle.__file__)), "distsim_oracle.c")
+
+MUTANTS = [
+    ("warm-up one deeper", "int w = pp - 1 - s;", "int w = pp - s;"),
+    ("warm-up one shallower", "int w = pp - 1 - s;", "int w = pp - 2 - s; if (w < 0) w = 0;"),
+    ("p2p bytes of the wrong layer", "int64_t bytes = act[bnd[s + 1] - 1];", "int64_t bytes = act[bnd[s + 1] < L ? bnd[s + 1] : L - 1];"),
+    ("forward p2p latency dropped", "int64_t arrive = now + pf[s];", "int64_t arrive = now;"),
+    ("backward p2p latency dropped", "int64_t arrive = now + pb[s];", "int64_t arrive = now;"),
+    ("ring volume without the factor 2", "(2ull * (uint64_t)(n - 1) * (uint64_t)bytes)", "((uint64_t)(n - 1) * (uint64_t)bytes)"),
+    ("ring volume with N instead of N-1", "(2ull * (uint64_t)(n - 1) * (uint64_t)bytes)", "(2ull * (uint64_t)n * (uint64_t)bytes)"),
+    ("collective link class off by one", "int k = n <= cl->gpus_per_node ? 0 : 1;\n    return cl->alpha[k] + (int64_t)((2ull",
+     "int k = n < cl->gpus_per_node ? 0 : 1;\n    return cl->alpha[k] + (int64_t)((2ull"),
+    ("p2p link class ignores dp", "int64_t na = ((int64_t)s * tp * dp) / g, nb = ((int64_t)(s + 1) * tp * dp) / g;",
+     "int64_t na = ((int64_t)s * tp) / g, nb = ((int64_t)(s + 1) * tp) / g;"),
+    ("tp all-reduce also for tp = 1", "if (tp > 1) { t += fa[l]; mb_[s__] += fa[l]; }", "{ t += fa[l]; mb_[s__] += fa[l]; }"),
+    ("backward all-reduce forgotten", "if (tp > 1) { t += ba[l]; mb_[s__] += ba[l]; }", "if (tp > 1) { mb_[s__] += ba[l]; }"),
+    ("p2p not counted as communication", "mb_[s] += pf[s]; nev++;", "nev++;"),
+    ("all-reduce starts at time zero", "heap_push(h, now + d, EV_AR_DONE, s, 0, 0);", "heap_push(h, d, EV_AR_DONE, s, 0, 0);"),
+    ("last bucket dropped", "if (e.layer == bnd[s] && acc[s] > 0) {", "if (0 && e.layer == bnd[s] && acc[s] > 0) {"),
+    ("buckets do not queue", "int64_t st = comm_free[s] > now ? comm_free[s] : now;\n                comm_free[s] = st + d;\n                heap_push(h, comm_free[s], EV_AR_DONE, s, 0, 0);\n                mb_[s] += d;\n                if (tl_ar) { if (tl_ar[s] < 0) tl_ar[s] = st; tl_ar[pp + s] = comm_free[s]; }\n                acc[s] -= cap;",
+     "int64_t st = now;\n                comm_free[s] = st + d;\n                heap_push(h, comm_free[s], EV_AR_DONE, s, 0, 0);\n                mb_[s] += d;\n                if (tl_ar) { if (tl_ar[s] < 0) tl_ar[s] = st; tl_ar[pp + s] = comm_free[s]; }\n                acc[s] -= cap;"),
+    ("gradients of every micro-batch", "int last_bwd = (kd == 1 && next[s__] == 2 * m - 1);", "int last_bwd = (kd == 1);"),
+    ("async schedule keeps the all-reduce", "const int sync = sched != 2;", "const int sync = 1;"),
+    ("blocking send not on the device", "if (cl->p2p_blocking == 1) {      /* the send runs on the device */", "if (0) {"),
+    ("links do not serialise", "int64_t depart = now > link_f[s] ? now : link_f[s];", "int64_t depart = now;"),
+    ("all-to-all volume without (n-1)/n", "(((uint64_t)(n - 1) * (uint64_t)bytes) / ((uint64_t)n * (uint64_t)cl->beta[k]))", "((uint64_t)bytes / (uint64_t)cl->beta[k])"),
+    ("GPipe backward before the last forward", "for (int i = 0; i < m; i++) { k[n] = 0; j[n++] = i; }\n            for (int i = 0; i < m; i++) { k[n] = 1; j[n++] = i; }",
+     "for (int i = 0; i < m - 1; i++) { k[n] = 0; j[n++] = i; }\n            k[n] = 1; j[n++] = 0; k[n] = 0; j[n++] = m - 1;\n            for (int i = 1; i < m; i++) { k[n] = 1; j[n++] = i; }"),
+    ("utilisation from communication", "util[s] = now > 0 ? (double)cb[s] / (double)now : 0.0;", "util[s] = now > 0 ? (double)mb_[s] / (double)now : 0.0;"),
+]
+
+# pins that take only the oracle module (parametrised ones are called with one or two settings)
+PINS = [
+    lambda o: pins.test_golden_pp2_m4_timeline(o, 1_000_000, 2_025_000, 5000, 4 << 20),
+    lambda o: pins.test_golden_pp2_m4_timeline(o, 5, 11, 1, 200 * 13),
+    pins.test_golden_tiny_numbers,
+    pins.test_golden_bucketed_allreduce,
+    lambda o: pins.test_uniform_pipeline_closed_form(o, 0),
+    lambda o: pins.test_uniform_pipeline_closed_form(o, 1),
+    pins.test_gpipe_flow_shop_closed_form,
+    pins.test_brute_force_longest_path_all_timestamps,
+    pins.test_blocking_p2p_against_task_graph,
+    pins.test_serialised_links_against_graph_with_send_nodes,
+    lambda o: pins.test_inflight_bound_of_early_backward(o, 4, 8),
+    pins.test_ring_allreduce_volume,
+    pins.test_p2p_link_class_and_alltoall,
+    pins.test_model_parallel_mapping,
+    pins.test_metamorphic,
+    pins.test_dp_changes_only_the_tail,
+    pins.test_async_schedule_is_dapple_without_the_global_sync,
+    lambda o: pins.test_invariants_on_workloads(o, "gpt24"),
+]
+
+
+def _caught(mod) -> bool:
+    for pin in PINS:
+        try:
+            pin(mod)
+        except AssertionError:
+            return True
+        except Exception:          # a mutant may also crash a pin's bookkeeping (index, key): caught as well
+            return True
+    return False
+
+
+def test_every_pin_passes_on_the_real_oracle(oracle_mod):
+    assert not _caught(oracle_mod)
+
+
+@pytest.mark.parametrize("name,old,new", MUTANTS, ids=[m[0] for m in MUTANTS])
+def test_planted_mistake_is_caught(oracle_mod, tmp_path, name, old, new):
+    text = open(SRC).read()
+    assert text.count(old) >= 1, f"mutation site not found: {name}"
+    mutated = text.replace(old, new, 1)
+    c = tmp_path / "mutant.c"
+    so = tmp_path / "libmutant.so"
+    c.write_text(mutated)
+    subprocess.check_call(["gcc", "-O1", "-fopenmp", "-shared", "-fPIC", "-w", "-o", str(so), str(c)])
+    real = oracle._load()
+    mutant = ctypes.CDLL(str(so))
+    mutant.oracle_simulate.restype = ctypes.c_int
+    mutant.oracle_search.restype = ctypes.c_int
+    oracle._lib = mutant
+    try:
+        assert _caught(oracle_mod), f"no pin notices: {name}"
+    finally:
+        oracle._lib = real

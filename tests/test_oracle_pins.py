@@ -492,6 +492,14 @@ def test_p2p_link_class_and_alltoall(oracle_mod):
     want = 2 * ((5000 + 1) + (10_000 + 400 // 25) + (5000 + 4))
     assert r["batch_ns"][0] == want
     assert list(r["comm_busy_ns"]) == [5001, 5001 + 10016, 10016 + 5004, 5004]
+    # the data-parallel replicas sit between the stages in rank order (tp fastest, then dp, then pp):
+    # tp = 2, dp = 2 puts 4 ranks on a stage, so again stages 0,1 | 2,3 and one inter-node boundary;
+    # with dp = 1 (2 ranks per stage) all four stages share a node
+    costs = mk_costs([0] * 4, [0] * 4, act=[200, 400, 800, 0], tps=(2,), grad=[0] * 4)
+    r = one(oracle_mod, costs, mk_cluster(16), (2, 2, 4, 1, 0, None))
+    assert r["batch_ns"][0] == 2 * ((5000 + 1) + (10_000 + 400 // 25) + (5000 + 4))
+    r = one(oracle_mod, costs, mk_cluster(8), (1, 2, 4, 1, 0, None))
+    assert r["batch_ns"][0] == 2 * ((5000 + 1) + (5000 + 2) + (5000 + 4))
     # all-to-all: (n-1)/n of the bytes leave each rank
     costs = mk_costs([7], [9], a2a=[8000], grad=[0])
     for n, want in ((1, 0), (2, 5000 + 4000 // 200), (8, 5000 + (7 * 8000) // (8 * 200)), (16, 10_000 + (15 * 8000) // (16 * 25))):
