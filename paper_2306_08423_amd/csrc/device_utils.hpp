@@ -126,6 +126,20 @@ __device__ __forceinline__ uint64_t udiv64(uint64_t num, uint64_t den) {
     return num / den;
 }
 
+// The same with the reciprocal of the divisor at hand (a divisor used many times): one
+// multiplication instead of the division; the fix-up makes the quotient exact whatever the
+// rounding of the product (its error is a few units for quotients below 2^53).
+__device__ __forceinline__ uint64_t udiv64_by(uint64_t num, uint64_t den, double inv_den) {
+    if (((num | den) >> 53) == 0) {
+        uint64_t q = (uint64_t)((double)num * inv_den);
+        int64_t r = (int64_t)(num - q * den);
+        while (r < 0) { q--; r += (int64_t)den; }
+        while (r >= (int64_t)den) { q++; r -= (int64_t)den; }
+        return q;
+    }
+    return num / den;
+}
+
 // ---- collective cost events (Sec. 4.2 ring volume; integer, truncating) ---------------
 
 struct ClusterDev {
