@@ -68,6 +68,7 @@ def simulate(w, nthreads: int = 1, timeline: bool = False) -> Dict[str, np.ndarr
     beta = _c(cl["beta_bytes_per_ns"], np.int64)
     dp, tp, pp, m = (_c(ca[k], np.int32) for k in ("dp", "tp", "pp", "m"))
     sched = _c(ca["schedule"], np.uint8)
+    chunks = _c(ca["chunks"], np.int32) if ca.get("chunks") is not None else None
     poff = _c(ca["part_off"], np.int64)
     pool = _c(ca["part_pool"], np.uint8)
     if pool.size == 0:
@@ -84,14 +85,15 @@ def simulate(w, nthreads: int = 1, timeline: bool = False) -> Dict[str, np.ndarr
     tls = tle = tar = None
     if timeline:
         assert C == 1
-        tls = np.full((2, int(pp[0]), int(m[0])), -1, np.int64)
-        tle = np.full((2, int(pp[0]), int(m[0])), -1, np.int64)
+        rows = int(pp[0]) * (int(chunks[0]) if chunks is not None and sched[0] == 3 else 1)   # virtual stages
+        tls = np.full((2, rows, int(m[0])), -1, np.int64)
+        tle = np.full((2, rows, int(m[0])), -1, np.int64)
         tar = np.full((2, int(pp[0])), -1, np.int64)
     rc = lib.oracle_simulate(
         ctypes.c_int32(L), ctypes.c_int32(V), _p(vt), *[_p(a) for a in cols],
         ctypes.c_int32(int(cl["num_devices"])), ctypes.c_int32(int(cl["gpus_per_node"])),
         _p(alpha), _p(beta), ctypes.c_int64(int(cl["dp_bucket_bytes"])), ctypes.c_int32(int(cl.get("p2p_blocking", 0))),
-        ctypes.c_int64(C), _p(dp), _p(tp), _p(pp), _p(m), _p(sched), _p(poff), _p(pool),
+        ctypes.c_int64(C), _p(dp), _p(tp), _p(pp), _p(m), _p(sched), _p(chunks), _p(poff), _p(pool),
         _p(status), _p(batch), _p(nev), _p(soff), _p(comp), _p(comm), _p(util),
         _p(tls), _p(tle), _p(tar), ctypes.c_int32(int(nthreads)))
     if rc != 0:

@@ -411,6 +411,216 @@ static void simulate_one(const costs_t *co, const cluster_t *cl,
 
 /* ---- entry points (plain C ABI for ctypes; all pointers are host memory) ---------- */
 
+/* ---- schedule 3: interleaved one-forward-one-backward (extension; the paper's discussion of
+ * new algorithms, Sec. 7, says a new pipeline algorithm enters through its schedule) ----------
+ *
+ * Every device holds `vch` model chunks: virtual stage k = c * pp + d is chunk c of device d and
+ * owns the layers [bnd[k], bnd[k+1]) of a partition into S = pp * vch parts.  Micro-batches come
+ * in groups of pp (m must be a multiple of pp).  The i-th forward of a device works on chunk
+ * (i mod (pp vch)) / pp and micro-batch (i / (pp vch)) pp + i mod pp; the i-th backward on chunk
+ * vch - 1 - (i mod (pp vch)) / pp and the same micro-batch.  Device d runs
+ * W = min(2 (pp - d - 1) + (vch - 1) pp, m vch) forwards first, then alternates forward and
+ * backward, then runs the backwards that are left (Narayanan et al., SC 2021, Sec. 2.2.2).
+ * A forward of virtual stage k needs the forward of k - 1 for that micro-batch (the edge from
+ * the last device back to the first included), a backward the backward of k + 1; the last
+ * virtual stage turns a micro-batch around on its own device.  One gradient all-reduce per device
+ * over the bytes of all its chunks follows its last backward (buckets are not modelled for this
+ * schedule; link serialisation is not either: such a candidate is invalid).
+ * Timeline arrays, if given, are [2][S][m] (virtual stage, not device).
+ */
+static void simulate_interleaved(const costs_t *co, const cluster_t *cl,
+                                 int32_t dp, int32_t tp, int32_t pp, int32_t m, int32_t vch,
+                                 const uint8_t *bnd_in, scratch_t *sc, result_t *res,
+                                 int64_t *comp_busy, int64_t *comm_busy, double *util,
+                                 int64_t *tl_start, int64_t *tl_end, int64_t *tl_ar) {
+    const int L = co->L;
+    res->status = ST_INVALID;
+    res->batch_ns = INT64_MAX;
+    res->num_events = 0;
+    if (dp < 1 || tp < 1 || pp < 1 || m < 1 || m > MAX_M || vch < 1) return;
+    if ((int64_t)dp * tp * pp != cl->num_devices) return;
+    if ((int64_t)pp * vch > MAX_PP || (int64_t)pp * vch > L || m % pp != 0 || cl->p2p_blocking == 2) return;
+    const int S = pp * vch;
+    int v = -1;
+    for (int i = 0; i < co->V; i++) if (co->variant_tp[i] == tp) { v = i; break; }
+    if (v < 0) return;
+    int bnd[257];
+    if (bnd_in) {
+        for (int k = 0; k <= S; k++) bnd[k] = bnd_in[k];
+        if (bnd[0] != 0 || bnd[S] != L) return;
+        for (int k = 0; k < S; k++) if (bnd[k + 1] <= bnd[k]) return;
+    } else {
+        for (int k = 0; k <= S; k++) bnd[k] = (int)(((int64_t)k * L) / S);
+    }
+    const int64_t *fc = co->fc + (int64_t)v * L, *bc = co->bc + (int64_t)v * L;
+    const int64_t *fa = co->fa + (int64_t)v * L, *ba = co->ba + (int64_t)v * L;
+    const int64_t *act = co->act + (int64_t)v * L, *grad = co->grad + (int64_t)v * L;
+    const int64_t *a2a = co->a2a + (int64_t)v * L;
+
+    /* p2p events of every boundary between virtual stages, by the nodes of the two devices */
+    int64_t pf[256], pb[256];
+    const int64_t g = cl->gpus_per_node;
+    for (int k = 0; k < S; k++) { pf[k] = 0; pb[k] = 0; }
+    for (int k = 0; k + 1 < S; k++) {
+        int64_t na = ((int64_t)(k % pp) * tp * dp) / g, nb = ((int64_t)((k + 1) % pp) * tp * dp) / g;
+        int cls = na == nb ? 0 : 1;
+        int64_t bytes = act[bnd[k + 1] - 1];
+        pf[k] = p2p_ns(cl, bytes, cls);
+        pb[k + 1] = p2p_ns(cl, bytes, cls);
+    }
+    {
+        unsigned __int128 t1 = 0;
+        for (int k = 0; k < S; k++) {
+            for (int l = bnd[k]; l < bnd[k + 1]; l++) {
+                t1 += (unsigned __int128)(fc[l] + bc[l]);
+                if (tp > 1) t1 += (unsigned __int128)(fa[l] + ba[l]);
+                t1 += 2 * (unsigned __int128)alltoall_ns(cl, dp, a2a[l]);
+            }
+            t1 += (unsigned __int128)(pf[k] + pb[k]);
+        }
+        if (t1 * (unsigned __int128)m >= ((unsigned __int128)1 << 53)) { res->status = ST_RANGE; return; }
+    }
+    res->status = ST_OK;
+
+    /* per-device ordered task lists: kind, micro-batch; the virtual stage goes to a third array */
+    const int64_t per_dev = 2ll * m * vch;
+    int64_t ntask = (int64_t)pp * per_dev, narr = (int64_t)S * m;
+    if (ntask > sc->cap_tasks) {
+        sc->cap_tasks = ntask;
+        sc->task_kind = (uint8_t *)realloc(sc->task_kind, (size_t)ntask);
+        sc->task_mb = (int32_t *)realloc(sc->task_mb, (size_t)ntask * sizeof(int32_t));
+    }
+    if (narr > sc->cap_arr) {
+        sc->cap_arr = narr;
+        sc->arrF = (uint8_t *)realloc(sc->arrF, (size_t)narr);
+        sc->arrB = (uint8_t *)realloc(sc->arrB, (size_t)narr);
+    }
+    memset(sc->arrF, 0, (size_t)narr);
+    memset(sc->arrB, 0, (size_t)narr);
+    uint8_t *task_vs = (uint8_t *)malloc((size_t)ntask);
+    const int64_t nslot = (int64_t)m * vch;
+    for (int d = 0; d < pp; d++) {
+        uint8_t *kk = sc->task_kind + d * per_dev, *vs = task_vs + d * per_dev;
+        int32_t *jj = sc->task_mb + d * per_dev;
+        int64_t W = 2ll * (pp - d - 1) + (int64_t)(vch - 1) * pp;
+        if (W > nslot) W = nslot;
+        int64_t n = 0, f = 0, b = 0;
+#define PUT_F(i_) do { int64_t i__ = (i_), w__ = i__ % ((int64_t)pp * vch);                              \
+            kk[n] = 0; vs[n] = (uint8_t)((w__ / pp) * pp + d);                                            \
+            jj[n] = (int32_t)((i__ / ((int64_t)pp * vch)) * pp + w__ % pp); n++; } while (0)
+#define PUT_B(i_) do { int64_t i__ = (i_), w__ = i__ % ((int64_t)pp * vch);                              \
+            kk[n] = 1; vs[n] = (uint8_t)((vch - 1 - w__ / pp) * pp + d);                                  \
+            jj[n] = (int32_t)((i__ / ((int64_t)pp * vch)) * pp + w__ % pp); n++; } while (0)
+        for (; f < W; f++) PUT_F(f);
+        while (f < nslot) { PUT_F(f); f++; PUT_B(b); b++; }
+        while (b < nslot) { PUT_B(b); b++; }
+#undef PUT_F
+#undef PUT_B
+    }
+
+    heap_t *h = &sc->heap;
+    h->n = 0; h->seq = 0;
+    int64_t next[64];
+    uint8_t busy[64];
+    int64_t cb[64], mb_[64];
+    for (int d = 0; d < pp; d++) { next[d] = 0; busy[d] = 0; cb[d] = 0; mb_[d] = 0; }
+    int64_t nev = 0, now = 0;
+    if (tl_ar) for (int d = 0; d < 2 * pp; d++) tl_ar[d] = -1;
+
+#define TRY_START_I(d_) do {                                                            \
+        int d__ = (d_);                                                                 \
+        if (!busy[d__] && next[d__] < per_dev) {                                        \
+            int64_t ti = d__ * per_dev + next[d__];                                     \
+            int kd = sc->task_kind[ti], j = sc->task_mb[ti], k = task_vs[ti];           \
+            int ready = kd == 0 ? (k == 0 || sc->arrF[(int64_t)k * m + j])              \
+                                : sc->arrB[(int64_t)k * m + j];                         \
+            if (ready) {                                                                \
+                busy[d__] = 1;                                                          \
+                int64_t t = now;                                                        \
+                if (tl_start) tl_start[((int64_t)kd * S + k) * m + j] = t;              \
+                if (kd == 0) {                                                          \
+                    for (int l = bnd[k]; l < bnd[k + 1]; l++) {                         \
+                        t += fc[l]; cb[d__] += fc[l];                                   \
+                        if (tp > 1) { t += fa[l]; mb_[d__] += fa[l]; }                  \
+                        int64_t x = alltoall_ns(cl, dp, a2a[l]);                        \
+                        t += x; mb_[d__] += x;                                          \
+                    }                                                                   \
+                } else {                                                                \
+                    for (int l = bnd[k + 1] - 1; l >= bnd[k]; l--) {                    \
+                        t += bc[l]; cb[d__] += bc[l];                                   \
+                        if (tp > 1) { t += ba[l]; mb_[d__] += ba[l]; }                  \
+                        int64_t x = alltoall_ns(cl, dp, a2a[l]);                        \
+                        t += x; mb_[d__] += x;                                          \
+                    }                                                                   \
+                }                                                                       \
+                if (cl->p2p_blocking == 1) {                                            \
+                    if (kd == 0 && k + 1 < S) t += pf[k];                               \
+                    if (kd == 1 && k > 0) t += pb[k];                                   \
+                }                                                                       \
+                heap_push(h, t, EV_TASK_DONE, k, j, kd);                                \
+            }                                                                           \
+        }                                                                               \
+    } while (0)
+
+    for (int d = 0; d < pp; d++) TRY_START_I(d);
+    while (h->n > 0) {
+        event_t e = heap_pop(h);
+        now = e.t;
+        int k = e.stage, d = k % pp;
+        switch (e.kind) {
+        case EV_TASK_DONE: {
+            int kd = e.layer, j = e.mb;
+            nev++;
+            if (tl_end) tl_end[((int64_t)kd * S + k) * m + j] = now;
+            busy[d] = 0;
+            next[d]++;
+            if (kd == 0 && k + 1 < S) {
+                heap_push(h, now + (cl->p2p_blocking == 1 ? 0 : pf[k]), EV_ARRIVE_F, k + 1, j, 0);
+                mb_[d] += pf[k]; nev++;
+            }
+            if (kd == 0 && k + 1 == S) sc->arrB[(int64_t)k * m + j] = 1;     /* turn-around on the last virtual stage */
+            if (kd == 1 && k > 0) {
+                heap_push(h, now + (cl->p2p_blocking == 1 ? 0 : pb[k]), EV_ARRIVE_B, k - 1, j, 0);
+                mb_[d] += pb[k]; nev++;
+            }
+            if (next[d] == per_dev && dp > 1) {       /* trailing gradient all-reduce of the device */
+                int64_t G = 0;
+                for (int c = 0; c < vch; c++)
+                    for (int l = bnd[c * pp + d]; l < bnd[c * pp + d + 1]; l++) G += grad[l];
+                if (G > 0) {
+                    int64_t dd = allreduce_ns(cl, dp, G);
+                    heap_push(h, now + dd, EV_AR_DONE, k, 0, 0);
+                    mb_[d] += dd;
+                    if (tl_ar) { tl_ar[d] = now; tl_ar[pp + d] = now + dd; }
+                }
+            }
+            TRY_START_I(d);
+            break;
+        }
+        case EV_ARRIVE_F:
+            sc->arrF[(int64_t)k * m + e.mb] = 1;
+            TRY_START_I(d);
+            break;
+        case EV_ARRIVE_B:
+            sc->arrB[(int64_t)k * m + e.mb] = 1;
+            TRY_START_I(d);
+            break;
+        case EV_AR_DONE:
+            nev++;
+            break;
+        }
+    }
+#undef TRY_START_I
+    free(task_vs);
+    res->batch_ns = now;
+    res->num_events = nev;
+    for (int d = 0; d < pp; d++) {
+        if (comp_busy) comp_busy[d] = cb[d];
+        if (comm_busy) comm_busy[d] = mb_[d];
+        if (util) util[d] = now > 0 ? (double)cb[d] / (double)now : 0.0;
+    }
+}
+
 /* Per-candidate outputs: status, batch_ns, num_events [C]; stage_off [C+1] is written here
  * (exclusive prefix of pp over candidates with status 0); comp/comm/util are ragged
  * arrays indexed stage_off[c] + s and must hold sum(pp) entries. */
@@ -420,7 +630,8 @@ int oracle_simulate(int32_t L, int32_t V, const int32_t *variant_tp,
                     int32_t num_devices, int32_t gpus_per_node,
                     const int64_t *alpha2, const int64_t *beta2, int64_t bucket, int32_t p2p_blocking,
                     int64_t C, const int32_t *dp, const int32_t *tp, const int32_t *pp, const int32_t *m,
-                    const uint8_t *schedule, const int64_t *part_off, const uint8_t *part_pool,
+                    const uint8_t *schedule, const int32_t *chunks /* or NULL */, const int64_t *part_off,
+                    const uint8_t *part_pool,
                     int32_t *status, int64_t *batch_ns, int64_t *num_events, int64_t *stage_off,
                     int64_t *comp_busy, int64_t *comm_busy, double *util,
                     int64_t *tl_start, int64_t *tl_end, int64_t *tl_ar, int32_t nthreads) {
@@ -444,9 +655,14 @@ int oracle_simulate(int32_t L, int32_t V, const int32_t *variant_tp,
             if (p >= 1 && p <= MAX_PP) buf = (int64_t *)malloc((size_t)p * 3 * sizeof(int64_t));
             result_t r;
             const uint8_t *b = part_off[c] >= 0 ? part_pool + part_off[c] : NULL;
-            simulate_one(&co, &cl, dp[c], tp[c], p, m[c], schedule[c], b, &sc, &r,
-                         buf, buf ? buf + p : NULL, buf ? (double *)(buf + 2 * p) : NULL,
-                         C == 1 ? tl_start : NULL, C == 1 ? tl_end : NULL, C == 1 ? tl_ar : NULL);
+            if (schedule[c] == 3)
+                simulate_interleaved(&co, &cl, dp[c], tp[c], p, m[c], chunks ? chunks[c] : 1, b, &sc, &r,
+                                     buf, buf ? buf + p : NULL, buf ? (double *)(buf + 2 * p) : NULL,
+                                     C == 1 ? tl_start : NULL, C == 1 ? tl_end : NULL, C == 1 ? tl_ar : NULL);
+            else
+                simulate_one(&co, &cl, dp[c], tp[c], p, m[c], schedule[c], b, &sc, &r,
+                             buf, buf ? buf + p : NULL, buf ? (double *)(buf + 2 * p) : NULL,
+                             C == 1 ? tl_start : NULL, C == 1 ? tl_end : NULL, C == 1 ? tl_ar : NULL);
             status[c] = r.status;
             batch_ns[c] = r.batch_ns;
             num_events[c] = r.num_events;

@@ -41,9 +41,11 @@ def mk_cluster(n, g=8, alpha=(5000, 10000), beta=(200, 25), bucket=0, blocking=0
 
 
 def mk_cands(rows):
-    """rows: list of (dp, tp, pp, m, schedule, bnd-or-None)."""
-    dp, tp, pp, m, sc, off, pool = [], [], [], [], [], [], []
-    for (d, t, p, mm, s, bnd) in rows:
+    """rows: list of (dp, tp, pp, m, schedule, bnd-or-None[, chunks])."""
+    dp, tp, pp, m, sc, off, pool, ch = [], [], [], [], [], [], [], []
+    for row in rows:
+        (d, t, p, mm, s, bnd) = row[:6]
+        ch.append(row[6] if len(row) > 6 else 1)
         dp.append(d); tp.append(t); pp.append(p); m.append(mm); sc.append(s)
         if bnd is None:
             off.append(-1)
@@ -55,6 +57,7 @@ def mk_cands(rows):
         "pp": np.asarray(pp, np.int32), "m": np.asarray(m, np.int32),
         "schedule": np.asarray(sc, np.uint8), "part_off": np.asarray(off, np.int64),
         "part_pool": np.asarray(pool, np.uint8),
+        **({"chunks": np.asarray(ch, np.int32)} if any(len(r) > 6 for r in rows) else {}),
     }
 
 

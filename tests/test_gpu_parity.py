@@ -249,7 +249,7 @@ def test_async_schedule(H, oracle_mod):
     sel = np.nonzero(cand["schedule"] == 2)[0][::40]
     _timeline_parity(H, oracle_mod, w, sel)
     # an unknown schedule is an invalid candidate
-    cand["schedule"][:5] = 3
+    cand["schedule"][:5] = 4
     w = Workload("gpt48+bad schedule", w0.costs, w0.cluster, cand)
     hip = H.run_hip(w)
     assert (hip["status"][:5] == 1).all()
@@ -362,7 +362,7 @@ def test_invalid_range_and_capacity_status(H, oracle_mod):
     costs = mk_costs([10] * 4, [20] * 4, tps=(1,))
     rows = [
         (1, 1, 2, 4, 1, None), (2, 1, 2, 4, 1, None), (1, 2, 1, 4, 1, None), (1, 1, 2, 0, 1, None),
-        (1, 1, 2, 4, 1, [0, 0, 4]), (1, 1, 2, 4, 1, [0, 2, 3]), (1, 1, 2, 4, 3, None), (1, 1, 2, 4, 0, [0, 1, 4]),
+        (1, 1, 2, 4, 1, [0, 0, 4]), (1, 1, 2, 4, 1, [0, 2, 3]), (1, 1, 2, 4, 4, None), (1, 1, 2, 4, 0, [0, 1, 4]),
         (1, 1, 2, (1 << 16) + 1, 0, None), (-1, -1, 2, 4, 0, None), (1, 1, 0, 4, 0, None),
     ]
     w = mk(costs, mk_cluster(2), rows)

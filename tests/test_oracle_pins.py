@@ -636,7 +636,146 @@ def test_async_schedule_is_dapple_without_the_global_sync(oracle_mod):
     for k in ("batch_ns", "num_events", "comp_busy_ns", "comm_busy_ns"):
         assert np.array_equal(a[k], b[k])
     # unknown schedules stay invalid
-    assert int(one(oracle_mod, costs, cl, (1, 1, 4, 6, 3, None))["status"][0]) == 1
+    assert int(one(oracle_mod, costs, cl, (1, 1, 4, 6, 4, None))["status"][0]) == 1
+
+
+# ----------------------------------------------------------------------------- interleaved schedule
+
+def interleaved_order(pp, v, m, d):
+    """Device d's task order under the interleaved schedule, from its definition: forward slot i is
+    chunk (i mod pp v) / pp, micro-batch (i / (pp v)) pp + i mod pp; backward slot i the mirrored
+    chunk; 2 (pp - d - 1) + (v - 1) pp warm-up forwards, then forward / backward in turn."""
+    n = m * v
+
+    def fwd(i):
+        g, w = divmod(i, pp * v)
+        return (w // pp, g * pp + w % pp)
+
+    def bwd(i):
+        g, w = divmod(i, pp * v)
+        return (v - 1 - w // pp, g * pp + w % pp)
+    W = min((pp - d - 1) * 2 + (v - 1) * pp, n)
+    order = [("F",) + fwd(i) for i in range(W)]
+    for i in range(n - W):
+        order.append(("F",) + fwd(W + i))
+        order.append(("B",) + bwd(i))
+    order += [("B",) + bwd(i) for i in range(n - W, n)]
+    return order
+
+
+def interleaved_longest_path(pp, v, m, Fd, Bd, pf, pb):
+    """End of every task (kind, virtual stage, micro-batch) by relaxation over the explicit graph."""
+    S = pp * v
+    preds = {}
+    for d in range(pp):
+        order = interleaved_order(pp, v, m, d)
+        assert len(set(order)) == 2 * m * v == len(order)
+        for i, (kd, c, j) in enumerate(order):
+            k = c * pp + d
+            p = []
+            if i > 0:
+                pk, pc, pj = order[i - 1]
+                p.append(((pk, pc * pp + d, pj), 0))
+            if kd == "F" and k > 0:
+                p.append((("F", k - 1, j), pf[k - 1]))
+            if kd == "B" and k < S - 1:
+                p.append((("B", k + 1, j), pb[k + 1]))
+            if kd == "B" and k == S - 1:
+                p.append((("F", k, j), 0))
+            preds[(kd, k, j)] = p
+    dur = lambda n: Fd[n[1]] if n[0] == "F" else Bd[n[1]]
+    start = {n: 0 for n in preds}
+    changed, rounds = True, 0
+    while changed:
+        changed = False
+        rounds += 1
+        assert rounds < 20 * len(preds) + 10, "cycle in the task graph"
+        for n, ps in preds.items():
+            val = max([start[q] + dur(q) + lat for q, lat in ps], default=0)
+            if val != start[n]:
+                start[n] = val
+                changed = True
+    return start, {n: start[n] + dur(n) for n in preds}
+
+
+def test_interleaved_uniform_closed_form(oracle_mod):
+    """Equal chunks, no p2p: the bubble of the interleaved schedule is (pp - 1)(tF + tB) / v for
+    per-device times tF, tB (Narayanan et al., SC 2021), so batch = m (tF + tB) + (pp - 1)(tF + tB) / v."""
+    for pp, v, groups in [(2, 2, 1), (4, 2, 2), (4, 4, 3), (8, 2, 1), (2, 3, 4), (3, 5, 2)]:
+        m, S = pp * groups, pp * v
+        f, b = 6, 10                                     # per chunk
+        costs = mk_costs([f] * S, [b] * S, act=[0] * S)
+        cl = mk_cluster(pp, g=1 << 20, alpha=(0, 0), beta=(1, 1))
+        r = one(oracle_mod, costs, cl, (1, 1, pp, m, 3, None, v))
+        assert int(r["status"][0]) == 0
+        assert int(r["batch_ns"][0]) == m * v * (f + b) + (pp - 1) * (f + b)
+        assert list(r["comp_busy_ns"]) == [m * v * (f + b)] * pp
+        assert int(r["num_events"][0]) == 2 * m * S + 2 * m * (S - 1)
+        # fewer bubbles than Dapple with the same devices and layers (v times thicker stages)
+        costs1 = mk_costs([f * v] * pp, [b * v] * pp, act=[0] * pp)
+        r1 = one(oracle_mod, costs1, cl, (1, 1, pp, m, 1, None))
+        assert int(r1["batch_ns"][0]) == (m + pp - 1) * v * (f + b) >= int(r["batch_ns"][0])
+
+
+def test_interleaved_against_task_graph(oracle_mod):
+    rng = np.random.default_rng(41)
+    for trial in range(250):
+        pp = int(rng.integers(1, 6))
+        v = int(rng.integers(1, 5))
+        m = pp * int(rng.integers(1, 4))
+        S = pp * v
+        L = S + int(rng.integers(0, 4))
+        cuts = sorted(rng.choice(np.arange(1, L), size=S - 1, replace=False).tolist())
+        bnd = [0] + cuts + [L]
+        fc = rng.integers(0, 40, L).tolist()
+        bc = rng.integers(0, 60, L).tolist()
+        act = (rng.integers(0, 9, L) * 5).tolist()
+        dp = int(rng.choice([1, 2]))
+        blocking = int(rng.integers(0, 2))
+        costs = mk_costs(fc, bc, act=act, grad=[100] * L)
+        cl = mk_cluster(dp * pp, g=1 << 20, alpha=(2, 0), beta=(5, 1), blocking=blocking)
+        r = one(oracle_mod, costs, cl, (dp, 1, pp, m, 3, bnd, v), timeline=True)
+        assert int(r["status"][0]) == 0
+        pf = [2 + act[bnd[k + 1] - 1] // 5 for k in range(S - 1)] + [0]
+        pb = [0] + [2 + act[bnd[k] - 1] // 5 for k in range(1, S)]
+        F, B = _stage_sums(fc, bnd), _stage_sums(bc, bnd)
+        if blocking:
+            start, end = interleaved_longest_path(pp, v, m, [a + b for a, b in zip(F, pf)],
+                                                  [a + b for a, b in zip(B, pb)], [0] * S, [0] * S)
+        else:
+            start, end = interleaved_longest_path(pp, v, m, F, B, pf, pb)
+        for (k_, vs, j), val in end.items():
+            kd = 0 if k_ == "F" else 1
+            assert r["end"][kd, vs, j] == val, (trial, k_, vs, j)
+            assert r["start"][kd, vs, j] == start[(k_, vs, j)]
+        G = [100 * sum(bnd[c * pp + d + 1] - bnd[c * pp + d] for c in range(v)) for d in range(pp)]
+        ar = [0 if dp == 1 else 2 + (2 * (dp - 1) * g) // (dp * 5) for g in G]
+        dev_end = [max(val for (k_, vs, j), val in end.items() if vs % pp == d) for d in range(pp)]
+        assert r["batch_ns"][0] == max(dev_end[d] + ar[d] for d in range(pp))
+        for d in range(pp):
+            comm = m * sum(pf[c * pp + d] + pb[c * pp + d] for c in range(v)) + ar[d]
+            assert r["comm_busy_ns"][d] == comm
+            assert r["comp_busy_ns"][d] == m * sum(F[c * pp + d] + B[c * pp + d] for c in range(v))
+
+
+def test_interleaved_validity_rules(oracle_mod):
+    costs = mk_costs([5] * 12, [7] * 12)
+    cl = mk_cluster(4, g=1 << 20)
+    ok = lambda row: int(one(oracle_mod, costs, cl, row)["status"][0])
+    assert ok((1, 1, 4, 8, 3, None, 3)) == 0
+    assert ok((1, 1, 4, 6, 3, None, 3)) == 1           # m is not a multiple of pp
+    assert ok((1, 1, 4, 8, 3, None, 4)) == 1           # 16 virtual stages, 12 layers
+    assert ok((1, 1, 4, 8, 3, None, 0)) == 1
+    assert ok((1, 1, 4, 8, 3, list(range(13)), 3)) == 0
+    assert ok((1, 1, 4, 8, 3, [0, 3, 6, 9, 12], 3)) == 1     # boundaries of 4 parts where 12 are needed
+    cl2 = mk_cluster(4, g=1 << 20, blocking=2)
+    assert int(one(oracle_mod, costs, cl2, (1, 1, 4, 8, 3, None, 3))["status"][0]) == 1
+    # one chunk per device is a valid degenerate case: Dapple's order with a warm-up twice as deep,
+    # which hides the p2p latencies that Dapple's steady state leaves exposed
+    a = one(oracle_mod, costs, cl, (1, 1, 4, 8, 3, None, 1))
+    b = one(oracle_mod, costs, cl, (1, 1, 4, 8, 1, None))
+    assert int(a["status"][0]) == 0 and int(a["batch_ns"][0]) <= int(b["batch_ns"][0])
+    assert np.array_equal(a["comp_busy_ns"], b["comp_busy_ns"]) and np.array_equal(a["comm_busy_ns"], b["comm_busy_ns"])
 
 
 # ----------------------------------------------------------------------------- paper facts
@@ -678,7 +817,7 @@ def test_invalid_and_range_status(oracle_mod):
         (1, 1, 2, 0, 1, None),          # m < 1
         (1, 1, 2, 4, 1, [0, 0, 4]),     # empty stage
         (1, 1, 2, 4, 1, [0, 2, 3]),     # does not end at L
-        (1, 1, 2, 4, 3, None),          # unknown schedule
+        (1, 1, 2, 4, 4, None),          # unknown schedule
         (1, 1, 2, 4, 0, [0, 1, 4]),     # ok
     ]
     r = oracle_mod.simulate(mk(costs, mk_cluster(2), rows))
