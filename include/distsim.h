@@ -45,6 +45,19 @@ extern "C" {
 
 #define DISTSIM_GPIPE    0     /* all forwards, then all backwards (Sec. 2.1.3)              */
 #define DISTSIM_1F1B     1     /* Dapple early backward: at most pp - s micro-batches alive  */
+#define DISTSIM_INTERLEAVED 3  /* interleaved one-forward-one-backward (Narayanan et al., SC 2021;
+                                  an extension in the sense of the paper's Sec. 7: a new pipeline
+                                  algorithm enters through its schedule).  Every device holds
+                                  chunks[c] model chunks; virtual stage k = chunk * pp + device
+                                  owns the k-th of pp * chunks parts of the layers (part_pool
+                                  then holds pp * chunks + 1 boundaries).  Needs m % pp == 0,
+                                  pp * chunks <= min(64, L), p2p_blocking != 2.  Forward slot i
+                                  of a device: chunk (i mod (pp chunks)) / pp, micro-batch
+                                  (i / (pp chunks)) pp + i mod pp; backward slot i: the mirrored
+                                  chunk.  Device d runs 2 (pp-d-1) + (chunks-1) pp forwards,
+                                  then forward / backward in turn, then the backwards left.
+                                  One trailing gradient all-reduce per device (no buckets).
+                                  Per-stage outputs are per device; no timeline / stage table. */
 #define DISTSIM_1F1B_ASYNC 2   /* asynchronous pipeline (Sec. 7, discussion of new algorithms):
                                   the Dapple order without the global synchronisation event, i.e.
                                   no gradient all-reduce event is appended to the device lists   */
@@ -121,11 +134,13 @@ typedef struct {
  * Struct of arrays, device pointers, C entries each. */
 typedef struct {
     const int32_t *dp, *tp, *pp, *m;
-    const uint8_t *schedule;         /* DISTSIM_GPIPE / DISTSIM_1F1B / DISTSIM_1F1B_ASYNC          */
+    const uint8_t *schedule;         /* DISTSIM_GPIPE / _1F1B / _1F1B_ASYNC / _INTERLEAVED        */
     const int64_t *part_off;         /* -1: uniform split, stage s owns layers [s L / pp, (s+1) L / pp);
                                         else offset into part_pool of b0..bpp                    */
     const uint8_t *part_pool;        /* concatenated boundaries; may be NULL if never referenced  */
     int64_t part_pool_len;           /* entries in part_pool (offsets beyond it => invalid)       */
+    const int32_t *chunks;           /* model chunks per device of DISTSIM_INTERLEAVED candidates
+                                        (ignored for the other schedules); NULL = 1 everywhere     */
 } distsim_candidates;
 
 /* Columns of distsim_events.stage_tab: per pipeline stage of a candidate */
@@ -302,7 +317,7 @@ int distsim_comm_event_times(distsim_ctx *ctx, int64_t n, const int32_t *kind, c
 enum {
     DISTSIM_K_LAYER_TABLES = 0, DISTSIM_K_DECODE, DISTSIM_K_BINS, DISTSIM_K_SCATTER,
     DISTSIM_K_STAGE_EVENTS, DISTSIM_K_SIM_INIT, DISTSIM_K_SIMULATE, DISTSIM_K_SEARCH, DISTSIM_K_TIMELINE,
-    DISTSIM_K_DEDUP, DISTSIM_K_COMM_TIMES, DISTSIM_K_BUBBLES,
+    DISTSIM_K_DEDUP, DISTSIM_K_COMM_TIMES, DISTSIM_K_BUBBLES, DISTSIM_K_SIMULATE_VIRTUAL,
     DISTSIM_K_COUNT
 };
 int distsim_timing_enable(distsim_ctx *ctx, int on);

@@ -26,7 +26,7 @@ EXPORTS = (
 NCOLS = 8
 COL = {"FC": 0, "FA": 1, "BC": 2, "BA": 3, "PF": 4, "PB": 5, "G": 6, "AR": 7}
 KERNELS = ("k_layer_tables", "k_decode", "k_bins", "k_scatter", "k_stage_events",
-           "k_sim_init", "k_simulate", "k_search", "k_timeline", "k_dedup", "k_comm_event_times", "k_bubbles")
+           "k_sim_init", "k_simulate", "k_search", "k_timeline", "k_dedup", "k_comm_event_times", "k_bubbles", "k_simulate_virtual")
 INT64_MAX = (1 << 63) - 1
 
 
@@ -46,7 +46,7 @@ class _Cluster(C.Structure):
 class _Cand(C.Structure):
     _fields_ = [("dp", C.c_void_p), ("tp", C.c_void_p), ("pp", C.c_void_p), ("m", C.c_void_p),
                 ("schedule", C.c_void_p), ("part_off", C.c_void_p), ("part_pool", C.c_void_p),
-                ("part_pool_len", C.c_int64)]
+                ("part_pool_len", C.c_int64), ("chunks", C.c_void_p)]
 
 
 class _Events(C.Structure):
@@ -184,7 +184,7 @@ class DeviceWorkload:
         k = self.cand
         pool = k["part_pool"]
         return _Cand(_ptr(k["dp"]), _ptr(k["tp"]), _ptr(k["pp"]), _ptr(k["m"]), _ptr(k["schedule"]),
-                     _ptr(k["part_off"]), _ptr(pool) if pool.numel() else None, pool.numel())
+                     _ptr(k["part_off"]), _ptr(pool) if pool.numel() else None, pool.numel(), _ptr(k.get("chunks")))
 
 
 def cluster_struct(cl) -> _Cluster:

@@ -12,6 +12,7 @@
 #include "kernels_search.hpp"
 #include "kernels_simulate.hpp"
 #include "kernels_timeline.hpp"
+#include "kernels_virtual.hpp"
 
 using namespace distsim;
 
@@ -31,7 +32,7 @@ struct distsim_ctx {
 static const char* kKernelNames[DISTSIM_K_COUNT] = {
     "k_layer_tables", "k_decode", "k_bins", "k_scatter",
     "k_stage_events", "k_sim_init", "k_simulate", "k_search", "k_timeline",
-    "k_dedup", "k_comm_event_times", "k_bubbles",
+    "k_dedup", "k_comm_event_times", "k_bubbles", "k_simulate_virtual",
 };
 
 static int fail(distsim_ctx* ctx, int code, const std::string& msg) {
@@ -165,7 +166,7 @@ int distsim_build_events(distsim_ctx* ctx, const distsim_costs* costs, const dis
                 costs->bwd_comm_ns, costs->act_bytes, costs->grad_bytes, costs->a2a_bytes};
     const ClusterDev cl = to_dev(*cluster);
     CandDev ca{cand->dp, cand->tp, cand->pp, cand->m, cand->schedule, cand->part_off, cand->part_pool,
-               cand->part_pool ? cand->part_pool_len : 0};
+               cand->part_pool ? cand->part_pool_len : 0, cand->chunks};
     EventsDev ev{out->stage_cap, out->status, out->stage_pos, out->stage_tab, out->stage_layers, out->num_events};
     out->L = costs->L;
     out->V = costs->V;
@@ -228,7 +229,7 @@ int distsim_simulate(distsim_ctx* ctx, const distsim_cluster* cluster, const dis
     CostsDev co{cs->L, cs->V, cs->variant_tp, cs->fwd_comp_ns, cs->bwd_comp_ns, cs->fwd_comm_ns, cs->bwd_comm_ns,
                 cs->act_bytes, cs->grad_bytes, cs->a2a_bytes};
     CandDev ca{cd->dp, cd->tp, cd->pp, cd->m, cd->schedule, cd->part_off, cd->part_pool,
-               cd->part_pool ? cd->part_pool_len : 0};
+               cd->part_pool ? cd->part_pool_len : 0, cd->chunks};
     const ClusterDev cl = to_dev(*cluster);
     EventsDev ev{events->stage_cap, events->status, events->stage_pos, events->stage_tab, events->stage_layers,
                  events->num_events};
@@ -243,6 +244,11 @@ int distsim_simulate(distsim_ctx* ctx, const distsim_cluster* cluster, const dis
             hipLaunchKernelGGL(k_simulate_links, dim3(simulate_grid(ctx, C)), dim3(256), 0, st, co, cl, ca, ws, ev, out);
         else
             hipLaunchKernelGGL(k_simulate, dim3(simulate_grid(ctx, C)), dim3(256), 0, st, co, cl, ca, ws, ev, out);
+    }
+    if (cd->chunks) {       // candidates of the interleaved schedule, if the caller has any
+        Timer t(ctx, st, DISTSIM_K_SIMULATE_VIRTUAL);
+        const int64_t blocks = C < (int64_t)ctx->num_cus * 16 ? C : (int64_t)ctx->num_cus * 16;
+        hipLaunchKernelGGL(k_simulate_virtual, dim3((unsigned)blocks), dim3(kWave), 0, st, co, cl, ca, ws, ev, out, C);
     }
     HIP_TRY(hipGetLastError());
     return DISTSIM_OK;
@@ -271,7 +277,7 @@ int distsim_timeline(distsim_ctx* ctx, const distsim_cluster* cluster, const dis
     CostsDev co{cs->L, cs->V, cs->variant_tp, cs->fwd_comp_ns, cs->bwd_comp_ns, cs->fwd_comm_ns, cs->bwd_comm_ns,
                 cs->act_bytes, cs->grad_bytes, cs->a2a_bytes};
     CandDev ca{cd->dp, cd->tp, cd->pp, cd->m, cd->schedule, cd->part_off, cd->part_pool,
-               cd->part_pool ? cd->part_pool_len : 0};
+               cd->part_pool ? cd->part_pool_len : 0, cd->chunks};
     TimelineOut out{sel, task_off, start_ns, end_ns, ar_start_ns, ar_end_ns};
     {
         Timer t(ctx, st, DISTSIM_K_TIMELINE);
@@ -326,7 +332,7 @@ int distsim_bubbles(distsim_ctx* ctx, const distsim_events* events, int64_t n, c
     HIP_TRY(hipSetDevice(ctx->device));
     hipStream_t st = (hipStream_t)hip_stream;
     CandDev ca{cd->dp, cd->tp, cd->pp, cd->m, cd->schedule, cd->part_off, cd->part_pool,
-               cd->part_pool ? cd->part_pool_len : 0};
+               cd->part_pool ? cd->part_pool_len : 0, cd->chunks};
     {
         Timer t(ctx, st, DISTSIM_K_BUBBLES);
         hipLaunchKernelGGL(k_bubbles, dim3((unsigned)n), dim3(256), 0, st, ca, events->status, events->num_candidates,

@@ -18,6 +18,7 @@ struct CandDev {
     const int64_t* part_off;
     const uint8_t* part_pool;
     int64_t part_pool_len;
+    const int32_t* chunks;         // model chunks per device (interleaved schedule), may be null
 };
 
 struct EventsDev {
@@ -35,6 +36,10 @@ struct Item {
     int sh;
     int64_t pos0, class_end;
 };
+
+// Candidates of the interleaved schedule keep their place in the visiting order (their per-stage
+// rows are per device) but are simulated by k_simulate_virtual; the other sweeps see them as empty.
+__device__ __forceinline__ bool is_interleaved(const Desc& d) { return ((d.meta >> 8) & 0xff) == 3; }
 
 __device__ __forceinline__ Item decode_item(const int64_t* __restrict__ hdr, int64_t w) {
     int k = 0;
@@ -143,9 +148,15 @@ __global__ __launch_bounds__(kDecodeBlock) void k_decode(CostsDev co, ClusterDev
         const int32_t dp = ca.dp[c], tp = ca.tp[c], pp = ca.pp[c], m = ca.m[c];
         const int sched = ca.schedule[c];
         const int64_t poff = ca.part_off[c];
-        bool ok = dp >= 1 && tp >= 1 && pp >= 1 && m >= 1 && m <= kMaxM && sched <= 2 && pp <= co.L && pp <= kMaxPP;
+        bool ok = dp >= 1 && tp >= 1 && pp >= 1 && m >= 1 && m <= kMaxM && sched <= 3 && pp <= co.L && pp <= kMaxPP;
         ok = ok && (int64_t)dp * tp * pp == (int64_t)cl.num_devices;
-        ok = ok && (poff == -1 || (poff >= 0 && ca.part_pool != nullptr && poff + pp + 1 <= ca.part_pool_len));
+        int64_t parts = pp;                      // parts of the layer partition
+        if (ok && sched == 3) {                  // interleaved: pp * chunks virtual stages
+            const int64_t vch = ca.chunks ? ca.chunks[c] : 1;
+            parts = (int64_t)pp * vch;
+            ok = vch >= 1 && parts <= kMaxPP && parts <= co.L && m % pp == 0 && cl.blocking != 2;
+        }
+        ok = ok && (poff == -1 || (poff >= 0 && ca.part_pool != nullptr && poff + parts + 1 <= ca.part_pool_len));
         int v = -1;
         if (ok) {
             for (int i = co.V - 1; i >= 0; i--) if (co.variant_tp[i] == tp) v = i;
@@ -240,7 +251,7 @@ __global__ __launch_bounds__(256) void k_scatter(CandDev ca, int64_t C, Workspac
     d.m = ca.m[c];
     d.dp = ca.dp[c];
     d.poff = ca.part_off[c];
-    d.spare = ca.tp[c];
+    d.spare = (int64_t)ca.tp[c] | ((int64_t)(ca.chunks ? ca.chunks[c] : 1) << 32);   // tp | chunks << 32
     ws.desc[pos] = d;
     ev.stage_pos[c] = room ? slot : -1;
     if (!room) { ev.status[c] = 3; ev.num_events[c] = 0; }
@@ -379,6 +390,7 @@ __device__ __forceinline__ void stage_fetch_desc(const Workspace& ws, const int6
     x.pos = it.pos0 + (lane >> it.sh);
     x.d = Desc{};
     if (x.pos < it.class_end) x.d = ws.desc[x.pos];
+    if (is_interleaved(x.d)) x.d = Desc{};
 }
 
 __device__ __forceinline__ void stage_fetch_bounds(const CandDev& ca, int L, StageWork& x) {

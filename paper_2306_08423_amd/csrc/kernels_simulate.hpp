@@ -458,6 +458,8 @@ __global__ __launch_bounds__(kSimBlock, 6) void k_simulate(CostsDev co, ClusterD
         Desc da{}, db{};
         if (posa < ia.class_end) da = ws.desc[posa];
         if (pair && posb < ib.class_end) db = ws.desc[posb];
+        if (is_interleaved(da)) da = Desc{};          // those candidates have a kernel of their own
+        if (is_interleaved(db)) db = Desc{};
         const bool same = pair && ia.sh == ib.sh &&
                           __builtin_amdgcn_ballot_w64(((da.meta ^ db.meta) & 0xffff) != 0 || da.m != db.m) == 0;
         if (same) {
@@ -487,6 +489,7 @@ __global__ __launch_bounds__(kSimBlock) void k_simulate_links(CostsDev co, Clust
         const int64_t pos = it.pos0 + (lane >> it.sh);
         Desc d{};
         if (pos < it.class_end) d = ws.desc[pos];
+        if (is_interleaved(d)) d = Desc{};
         const Desc one[1] = {d};
         simulate_items<1, true>(cl, ca, ws, ev, out, co.L, w, it.sh, one, lane, park);
     }

@@ -75,7 +75,7 @@ __global__ __launch_bounds__(kTlWaves * kWave) void k_timeline(CostsDev co, Clus
         int k = -1;
         if (lane < kTlChunk && q < n) {
             const int64_t c = out.sel[q];
-            if (c >= 0 && c < C && status[c] == 0) {
+            if (c >= 0 && c < C && status[c] == 0 && ca.schedule[c] != 3) {      // no dump for the interleaved schedule
                 const int pp = ca.pp[c];
                 int sh = 0;
                 while ((1 << sh) < pp) sh++;
@@ -295,6 +295,7 @@ __global__ __launch_bounds__(256) void k_bubbles(CandDev ca, const int32_t* __re
     const int64_t c = sel[q];
     if (c < 0 || c >= C || status[c] != 0) return;
     const int pp = ca.pp[c], m = ca.m[c], sched = ca.schedule[c];
+    if (sched == 3) return;
     const int64_t off = task_off[q];
     const int per_kind = pp * m;                          // <= 64 * 65536
     for (int t = threadIdx.x; t < 2 * per_kind; t += blockDim.x) {

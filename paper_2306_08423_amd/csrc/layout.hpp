@@ -27,7 +27,7 @@ struct alignas(16) Desc {
     int32_t meta;                  // pp | schedule << 8 | variant << 16 ; pp == 0: skip
     int32_t m, dp;
     int64_t poff;                  // offset of the partition in part_pool, -1 = uniform
-    int64_t spare;                 // tensor-parallel size
+    int64_t spare;                 // tensor-parallel size | chunks per device << 32
 };
 
 struct Workspace {

@@ -301,6 +301,59 @@ def test_graph_capture_and_replay(H, oracle_mod):
     assert np.array_equal(out.batch_ns.cpu().numpy()[:dw.C], ora["batch_ns"])
 
 
+def test_interleaved_schedule(H, oracle_mod):
+    """Schedule 3 (several model chunks per device) next to the other schedules: uniform and explicit
+    partitions, blocking and latency p2p, invalid combinations, large pipelines."""
+    _say("[case] interleaved schedule")
+    w0 = make_workload("gpt48")                       # L = 48, 128 devices
+    rng = np.random.default_rng(17)
+    cand = {k: v.copy() for k, v in w0.cand.items()}
+    C = len(cand["pp"])
+    chunks = np.ones(C, np.int32)
+    pick = rng.random(C) < 0.5
+    cand["schedule"][pick] = 3
+    chunks[pick] = rng.integers(1, 7, int(pick.sum()))
+    cand["chunks"] = chunks
+    for blocking in (0, 1, 2):
+        cl = dict(w0.cluster); cl["p2p_blocking"] = blocking
+        w = Workload(f"gpt48+interleaved blocking={blocking}", w0.costs, cl, cand)
+        ora = oracle_mod.simulate(w, nthreads=NT)
+        n_ok = int(((ora["status"] == 0) & (cand["schedule"] == 3)).sum())
+        assert (n_ok > 300) if blocking < 2 else (n_ok == 0)
+        H.assert_same(H.run_hip(w, table=False), ora, what=w.name)
+        H.assert_same(H.run_hip(w), ora, what=w.name + " with table")
+    # explicit partitions into pp * chunks parts, ragged sizes, many micro-batches, 64 virtual stages
+    L = 96
+    costs = mk_costs(rng.integers(0, 5000, (2, L)).tolist(), rng.integers(0, 9000, (2, L)).tolist(),
+                     fa=rng.integers(0, 300, (2, L)).tolist(), ba=rng.integers(0, 300, (2, L)).tolist(),
+                     act=(rng.integers(0, 100, (2, L)) * 64).tolist(), grad=rng.integers(0, 1 << 20, (2, L)).tolist(),
+                     a2a=(rng.integers(0, 3, (2, L)) * 4096).tolist(), tps=(1, 2))
+    N = 64 * 9 * 5 * 7
+    rows = []
+    for pp, v in [(1, 1), (1, 5), (2, 2), (2, 32), (3, 4), (4, 16), (5, 3), (7, 9), (8, 8), (16, 4), (21, 3), (32, 2), (64, 1),
+                  (9, 7), (12, 5), (6, 11)]:
+        for tp in (1, 2):
+            if N % (pp * tp):
+                continue
+            dp = N // (pp * tp)
+            for groups in (1, 2, 5):
+                S = pp * v
+                bnd = None
+                if S <= L and (pp + v + groups) % 2 == 0:
+                    cuts = np.sort(rng.choice(np.arange(1, L), S - 1, replace=False))
+                    bnd = [0] + cuts.tolist() + [L]
+                rows.append((dp, tp, pp, pp * groups, 3, bnd, v))
+    rows.append((N // 8, 1, 8, 8 * 40, 3, None, 8))                   # more slots than the ring holds
+    rows.append((N // 2, 1, 2, 2 * 200, 3, None, 3))
+    rows.append((N // 4, 1, 4, 6, 3, None, 2))                        # m not a multiple of pp
+    rows.append((N // 4, 1, 4, 8, 3, [0, 10, 20, 30, 96], 2))         # too few boundaries in the pool (runs off its end)
+    rows.append((N // 4, 1, 4, 8, 1, None))                           # a Dapple candidate among them
+    w = mk(costs, mk_cluster(N), rows)
+    ora = oracle_mod.simulate(w, nthreads=NT)
+    assert (ora["status"] == 0).sum() > 40
+    H.assert_same(H.run_hip(w, table=False), ora, what="interleaved ragged")
+
+
 def test_runs_are_deterministic(H):
     _say("[case] determinism")
     w = make_workload("gpt48")

@@ -38,6 +38,11 @@ MUTANTS = [
     ("all-to-all volume without (n-1)/n", "(((uint64_t)(n - 1) * (uint64_t)bytes) / ((uint64_t)n * (uint64_t)cl->beta[k]))", "((uint64_t)bytes / (uint64_t)cl->beta[k])"),
     ("GPipe backward before the last forward", "for (int i = 0; i < m; i++) { k[n] = 0; j[n++] = i; }\n            for (int i = 0; i < m; i++) { k[n] = 1; j[n++] = i; }",
      "for (int i = 0; i < m - 1; i++) { k[n] = 0; j[n++] = i; }\n            k[n] = 1; j[n++] = 0; k[n] = 0; j[n++] = m - 1;\n            for (int i = 1; i < m; i++) { k[n] = 1; j[n++] = i; }"),
+    ("interleaved: warm-up of the plain schedule", "int64_t W = 2ll * (pp - d - 1) + (int64_t)(vch - 1) * pp;", "int64_t W = (pp - d - 1) + (int64_t)(vch - 1) * pp;"),
+    ("interleaved: backward chunks not mirrored", "kk[n] = 1; vs[n] = (uint8_t)((vch - 1 - w__ / pp) * pp + d);", "kk[n] = 1; vs[n] = (uint8_t)((w__ / pp) * pp + d);"),
+    ("interleaved: micro-batch groups ignored", "jj[n] = (int32_t)((i__ / ((int64_t)pp * vch)) * pp + w__ % pp); n++; } while (0)\n#define PUT_B", "jj[n] = (int32_t)(w__ % pp); n++; } while (0)\n#define PUT_B"),
+    ("interleaved: link class by virtual stage", "int64_t na = ((int64_t)(k % pp) * tp * dp) / g, nb = ((int64_t)((k + 1) % pp) * tp * dp) / g;", "int64_t na = ((int64_t)k * tp * dp) / g, nb = ((int64_t)(k + 1) * tp * dp) / g;"),
+    ("interleaved: all-reduce of one chunk only", "for (int c = 0; c < vch; c++)\n                    for (int l = bnd[c * pp + d]; l < bnd[c * pp + d + 1]; l++) G += grad[l];", "for (int c = 0; c < 1; c++)\n                    for (int l = bnd[c * pp + d]; l < bnd[c * pp + d + 1]; l++) G += grad[l];"),
     ("utilisation from communication", "util[s] = now > 0 ? (double)cb[s] / (double)now : 0.0;", "util[s] = now > 0 ? (double)mb_[s] / (double)now : 0.0;"),
 ]
 
@@ -61,6 +66,10 @@ PINS = [
     pins.test_dp_changes_only_the_tail,
     pins.test_async_schedule_is_dapple_without_the_global_sync,
     lambda o: pins.test_invariants_on_workloads(o, "gpt24"),
+    pins.test_interleaved_uniform_closed_form,
+    pins.test_interleaved_against_task_graph,
+    pins.test_interleaved_validity_rules,
+    pins.test_interleaved_link_classes_follow_the_devices,
 ]
 
 

@@ -758,6 +758,28 @@ def test_interleaved_against_task_graph(oracle_mod):
             assert r["comp_busy_ns"][d] == m * sum(F[c * pp + d] + B[c * pp + d] for c in range(v))
 
 
+def test_interleaved_link_classes_follow_the_devices(oracle_mod):
+    """Boundaries between virtual stages connect devices: with 2 ranks per device and 4 ranks per node,
+    devices 0,1 | 2,3 sit on two nodes; 0->1 and 2->3 are intra-node, 1->2 and the edge from the last
+    device back to the first (chunk c to chunk c + 1) are inter-node."""
+    pp, v, m, S = 4, 2, 4, 8
+    costs = mk_costs([0] * S, [0] * S, act=[200] * S, tps=(2,), grad=[0] * S)
+    cl = mk_cluster(8, g=4)                            # alpha 5000 / 10000 ns, beta 200 / 25 B per ns
+    r = one(oracle_mod, costs, cl, (1, 2, pp, m, 3, None, v))
+    assert int(r["status"][0]) == 0
+    intra, inter = 5000 + 200 // 200, 10_000 + 200 // 25
+    edge = [intra, inter, intra, inter, intra, inter, intra]          # boundaries k | k+1 for k = 0..6
+    pf = edge + [0]
+    pb = [0] + edge
+    want = [m * sum(pf[c * pp + d] + pb[c * pp + d] for c in range(v)) for d in range(pp)]
+    assert list(r["comm_busy_ns"]) == want
+    # four devices on one node hold 16 virtual stages: every boundary stays inside the node
+    costs = mk_costs([0] * 16, [0] * 16, act=[200] * 16, grad=[0] * 16)
+    r = one(oracle_mod, costs, mk_cluster(4, g=8), (1, 1, 4, 4, 3, None, 4))
+    per_dev = [4 * (2 * 4 - (1 if d == 3 else 0) - (1 if d == 0 else 0)) * intra for d in range(4)]
+    assert list(r["comm_busy_ns"]) == per_dev
+
+
 def test_interleaved_validity_rules(oracle_mod):
     costs = mk_costs([5] * 12, [7] * 12)
     cl = mk_cluster(4, g=1 << 20)
