@@ -57,7 +57,7 @@ extern "C" {
                                   chunk.  Device d runs 2 (pp-d-1) + (chunks-1) pp forwards,
                                   then forward / backward in turn, then the backwards left.
                                   One trailing gradient all-reduce per device (no buckets).
-                                  Per-stage outputs are per device; no timeline / stage table. */
+                                  Per-stage outputs are per device; no stage table.            */
 #define DISTSIM_1F1B_ASYNC 2   /* asynchronous pipeline (Sec. 7, discussion of new algorithms):
                                   the Dapple order without the global synchronisation event, i.e.
                                   no gradient all-reduce event is appended to the device lists   */
@@ -140,7 +140,8 @@ typedef struct {
     const uint8_t *part_pool;        /* concatenated boundaries; may be NULL if never referenced  */
     int64_t part_pool_len;           /* entries in part_pool (offsets beyond it => invalid)       */
     const int32_t *chunks;           /* model chunks per device of DISTSIM_INTERLEAVED candidates
-                                        (ignored for the other schedules); NULL = 1 everywhere     */
+                                        (ignored for the other schedules); NULL = the list has no
+                                        such candidate (one that is there anyway is invalid)       */
 } distsim_candidates;
 
 /* Columns of distsim_events.stage_tab: per pipeline stage of a candidate */
@@ -253,9 +254,12 @@ int distsim_search(distsim_ctx *ctx, const int64_t *batch_ns, const int64_t *wei
  *                [0, C), get no task entries and no all-reduce windows)
  *   task_off[n]  device: first entry of the candidate's block in start_ns / end_ns; the block
  *                holds 2*pp*m entries laid out [kind][stage][micro-batch], kind 0 = forward,
- *                1 = backward.  With p2p_blocking the end includes the send.
+ *                1 = backward.  With p2p_blocking the end includes the send.  A candidate with
+ *                the interleaved schedule has 2*pp*chunks*m entries, [kind][virtual stage]
+ *                [micro-batch], virtual stage k on device k mod pp.
  *   ar_start_ns / ar_end_ns [n][DISTSIM_MAX_PP]: start of the first and end of the last gradient
- *                all-reduce event on each stage's device, -1 where there is none.
+ *                all-reduce event on each stage's device (interleaved: each device), -1 where
+ *                there is none.
  * p2p events follow from the table: the one after task (kind, s, j) starts at that task's end
  * (its compute end) and lasts stage_tab[PF or PB].  Errors: EINVAL, ERANGE, EHIP.
  */
@@ -318,7 +322,7 @@ enum {
     DISTSIM_K_LAYER_TABLES = 0, DISTSIM_K_DECODE, DISTSIM_K_BINS, DISTSIM_K_SCATTER,
     DISTSIM_K_STAGE_EVENTS, DISTSIM_K_SIM_INIT, DISTSIM_K_SIMULATE, DISTSIM_K_SEARCH, DISTSIM_K_TIMELINE,
     DISTSIM_K_DEDUP, DISTSIM_K_COMM_TIMES, DISTSIM_K_BUBBLES, DISTSIM_K_SIMULATE_VIRTUAL,
-    DISTSIM_K_COUNT
+    DISTSIM_K_TIMELINE_VIRTUAL, DISTSIM_K_COUNT
 };
 int distsim_timing_enable(distsim_ctx *ctx, int on);
 int distsim_timing_read(distsim_ctx *ctx, int kernel, double *total_ms, int64_t *launches);

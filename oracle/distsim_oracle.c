@@ -656,7 +656,7 @@ int oracle_simulate(int32_t L, int32_t V, const int32_t *variant_tp,
             result_t r;
             const uint8_t *b = part_off[c] >= 0 ? part_pool + part_off[c] : NULL;
             if (schedule[c] == 3)
-                simulate_interleaved(&co, &cl, dp[c], tp[c], p, m[c], chunks ? chunks[c] : 1, b, &sc, &r,
+                simulate_interleaved(&co, &cl, dp[c], tp[c], p, m[c], chunks ? chunks[c] : 0 /* no chunk counts: invalid */, b, &sc, &r,
                                      buf, buf ? buf + p : NULL, buf ? (double *)(buf + 2 * p) : NULL,
                                      C == 1 ? tl_start : NULL, C == 1 ? tl_end : NULL, C == 1 ? tl_ar : NULL);
             else

@@ -33,6 +33,7 @@ static const char* kKernelNames[DISTSIM_K_COUNT] = {
     "k_layer_tables", "k_decode", "k_bins", "k_scatter",
     "k_stage_events", "k_sim_init", "k_simulate", "k_search", "k_timeline",
     "k_dedup", "k_comm_event_times", "k_bubbles", "k_simulate_virtual",
+    "k_timeline_virtual",
 };
 
 static int fail(distsim_ctx* ctx, int code, const std::string& msg) {
@@ -283,6 +284,13 @@ int distsim_timeline(distsim_ctx* ctx, const distsim_cluster* cluster, const dis
         Timer t(ctx, st, DISTSIM_K_TIMELINE);
         hipLaunchKernelGGL(k_timeline, dim3((unsigned)((n + kTlChunk - 1) / kTlChunk)), dim3(kTlWaves * kWave), 0, st,
                            co, cl_dev(*cluster), ca, ws, events->status, events->num_candidates, n, out);
+    }
+    if (cd->chunks) {          // interleaved candidates among the selected ones: one wavefront each
+        Timer t(ctx, st, DISTSIM_K_TIMELINE_VIRTUAL);
+        const int64_t grid = n < 65536 ? n : 65536;
+        hipLaunchKernelGGL(k_timeline_virtual, dim3((unsigned)grid), dim3(kWave), 0, st, co, cl_dev(*cluster), ca, ws,
+                           events->status, events->num_candidates, n, sel, task_off, start_ns, end_ns, ar_start_ns,
+                           ar_end_ns);
     }
     HIP_TRY(hipGetLastError());
     return DISTSIM_OK;

@@ -152,7 +152,7 @@ __global__ __launch_bounds__(kDecodeBlock) void k_decode(CostsDev co, ClusterDev
         ok = ok && (int64_t)dp * tp * pp == (int64_t)cl.num_devices;
         int64_t parts = pp;                      // parts of the layer partition
         if (ok && sched == 3) {                  // interleaved: pp * chunks virtual stages
-            const int64_t vch = ca.chunks ? ca.chunks[c] : 1;
+            const int64_t vch = ca.chunks ? ca.chunks[c] : 0;      // no chunk counts: invalid
             parts = (int64_t)pp * vch;
             ok = vch >= 1 && parts <= kMaxPP && parts <= co.L && m % pp == 0 && cl.blocking != 2;
         }

@@ -285,6 +285,7 @@ __global__ __launch_bounds__(kTlWaves * kWave) void k_timeline(CostsDev co, Clus
 //   Dapple  with w = min(pp-1-s, m) warm-up forwards:
 //           F(s,j) after F(s,j-1) for j <= w, after B(s,j-w-1) for j > w;
 //           B(s,j) after F(s,w+j) for j < m-w, else after B(s,j-1) (after F(s,m-1) if j = 0)
+//   interleaved  the same order over slots; entries [kind][virtual stage][micro-batch]
 // One workgroup per selected candidate; entries in the layout of the dump, [kind][stage][micro-batch].
 __global__ __launch_bounds__(256) void k_bubbles(CandDev ca, const int32_t* __restrict__ status, int64_t C, int64_t n,
                                                  const int64_t* __restrict__ sel, const int64_t* __restrict__ task_off,
@@ -295,8 +296,41 @@ __global__ __launch_bounds__(256) void k_bubbles(CandDev ca, const int32_t* __re
     const int64_t c = sel[q];
     if (c < 0 || c >= C || status[c] != 0) return;
     const int pp = ca.pp[c], m = ca.m[c], sched = ca.schedule[c];
-    if (sched == 3) return;
     const int64_t off = task_off[q];
+    if (sched == 3) {
+        // Interleaved: device d = k mod pp runs slots, not micro-batches, in the Dapple order with
+        // W warm-up forwards.  Slot i of a direction <-> (chunk, micro-batch) and slot <-> position
+        // in the device's list are closed forms, so is the task one position earlier.
+        if (!ca.chunks) return;
+        const int vch = ca.chunks[c];
+        const int S = pp * vch, group = pp * vch;
+        const int64_t ns = (int64_t)m * vch, per = (int64_t)S * m;
+        for (int64_t t = threadIdx.x; t < 2 * per; t += blockDim.x) {
+            const int kind = t >= per ? 1 : 0;
+            const int64_t r = t - kind * per;
+            const int k = (int)(r / m), j = (int)(r - (int64_t)k * m);
+            const int d = k % pp, cch = k / pp;
+            int64_t W = 2ll * (pp - d - 1) + (int64_t)(vch - 1) * pp;
+            if (W > ns) W = ns;
+            const int64_t i = (int64_t)(j / pp) * group + (kind == 0 ? cch : vch - 1 - cch) * pp + j % pp;
+            const int64_t pos = kind == 0 ? (i < W ? i : W + 2 * (i - W)) : (i < ns - W ? W + 2 * i + 1 : ns + i);
+            int64_t before = 0;
+            if (pos > 0) {
+                const int64_t p = pos - 1;
+                int pk;
+                int64_t pi;
+                if (p < W) { pk = 0; pi = p; }
+                else if (p < W + 2 * (ns - W)) { const int64_t x = p - W; pk = (int)(x & 1); pi = pk ? x / 2 : W + x / 2; }
+                else { pk = 1; pi = p - ns; }
+                const int w = (int)(pi % group), cc = w / pp;
+                const int64_t pj = (pi / group) * pp + w % pp;
+                const int kk = (pk == 0 ? cc : vch - 1 - cc) * pp + d;
+                before = end[off + ((int64_t)pk * S + kk) * m + pj];
+            }
+            idle[off + t] = start[off + t] - before;
+        }
+        return;
+    }
     const int per_kind = pp * m;                          // <= 64 * 65536
     for (int t = threadIdx.x; t < 2 * per_kind; t += blockDim.x) {
         const int kind = t >= per_kind ? 1 : 0;

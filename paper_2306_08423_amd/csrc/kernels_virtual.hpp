@@ -23,152 +23,214 @@ struct VirtLds {
     int32_t doneF[kMaxPP], doneB[kMaxPP];       // by device: slots run, as of the previous round
 };
 
+// What one candidate needs from its descriptor (or, for the dump, from the candidate arrays).
+struct VirtCand {
+    int pp, v, m, dp, tp, vch;
+    int64_t poff, c;
+};
+
+// Where the dump of one candidate goes (the simulation proper passes none).
+struct VirtDump {
+    int64_t* start;      // [2][pp * vch][m]
+    int64_t* end;
+    int64_t* ar_start;   // [kMaxPP] by device
+    int64_t* ar_end;
+};
+
+// One candidate on one wavefront.  DUMP = false: writes status / batch time / busy sums.
+// DUMP = true: the candidate is known to be OK; writes every task's start and end and the
+// all-reduce windows, and none of the simulation's outputs.
+template <bool DUMP>
+__device__ __forceinline__ void virtual_candidate(const CostsDev& co, const ClusterDev& cl, const CandDev& ca,
+                                                  const Workspace& ws, const EventsDev& ev, const SimOut& out,
+                                                  const VirtCand& vc, const VirtDump& dump, VirtLds& sm) {
+    const int d = threadIdx.x;                                   // device
+    const int L = co.L;
+    const int pp = vc.pp, v = vc.v, m = vc.m, dp = vc.dp, tp = vc.tp, vch = vc.vch;
+    const int64_t c = vc.c;
+    const int S = pp * vch;
+    const bool act = d < pp;
+    const int64_t tpdp = (int64_t)tp * dp;
+    auto node_of = [&](int dev) -> int64_t {
+        return tpdp >= cl.gpus_per_node ? dev : (int64_t)udiv64((uint64_t)dev * (uint64_t)tpdp, (uint64_t)cl.gpus_per_node);
+    };
+    const int64_t* row = ws.comb + (size_t)((v * kMaxPP + pp - 1) * (L + 1)) * kCombWords;
+
+    // composed events of this device's chunks
+    int bad = 0;
+    int64_t comp = 0, comm = 0, G = 0, share = 0;
+    if (act) {
+        const int64_t my_node = node_of(d), next_node = node_of((d + 1) % pp), prev_node = node_of((d + pp - 1) % pp);
+        for (int cch = 0; cch < vch; cch++) {
+            const int k = cch * pp + d;
+            int lo, hi;
+            if (vc.poff >= 0) { lo = ca.part_pool[vc.poff + k]; hi = ca.part_pool[vc.poff + k + 1]; }
+            else { lo = (int)(((int64_t)k * L) / S); hi = (int)(((int64_t)(k + 1) * L) / S); }
+            if (hi <= lo || hi > L || (k == 0 && lo != 0) || (k == S - 1 && hi != L)) { bad = 1; break; }
+            const int64_t* eh = row + hi * kCombWords;
+            const int64_t* el = row + lo * kCombWords;
+            const int64_t FT = eh[0] - el[0], BT = eh[1] - el[1], CP = eh[2] - el[2];
+            const int64_t PF = k + 1 < S ? eh[4 + (my_node != next_node ? 1 : 0)] : 0;
+            const int64_t PB = k > 0 ? el[4 + (my_node != prev_node ? 1 : 0)] : 0;
+            G += eh[3] - el[3];
+            comp += CP;
+            comm += FT + BT - CP + PF + PB;
+            share += FT + BT + PF + PB;
+            const int64_t pf_task = cl.blocking == 1 ? PF : 0, pb_task = cl.blocking == 1 ? PB : 0;
+            sm.durF[k] = (double)(FT + pf_task);
+            sm.durB[k] = (double)(BT + pb_task);
+            sm.sendF[k] = PF - pf_task;
+            sm.sendB[k] = PB - pb_task;
+        }
+    }
+    bad = __builtin_amdgcn_ballot_w64(bad != 0) != 0;
+    const bool range = !bad && stage_out_of_range(act ? share : 0, m, kWave);
+    if (bad || range) {
+        if (!DUMP && d == 0) { ev.status[c] = bad ? 1 : 2; ev.num_events[c] = 0; out.batch_ns[c] = INT64_MAX; }
+        return;
+    }
+    __syncthreads();
+    // latency of the edge into virtual stage k: the send of k - 1 (forward), of k + 1 (backward)
+    if (act) {
+        for (int cch = 0; cch < vch; cch++) {
+            const int k = cch * pp + d;
+            sm.latF[k] = k > 0 ? (double)sm.sendF[k - 1] : 0.0;
+            sm.latB[k] = k + 1 < S ? (double)sm.sendB[k + 1] : 0.0;
+        }
+    }
+    __syncthreads();
+
+    // the rounds
+    const int64_t n = (int64_t)m * vch;                       // slots per direction
+    const int group = pp * vch;                               // slots per group of pp micro-batches
+    int64_t W = 2ll * (pp - d - 1) + (int64_t)(vch - 1) * pp; // warm-up forwards
+    if (W > n) W = n;
+    int64_t iF = 0, iB = 0;
+    double own = 0.0;
+    bool stuck = false;
+    const int64_t max_rounds = 4 * n + 8 * pp + 64;
+    for (int64_t round = 0; round < max_rounds; round++) {
+        if (act) { sm.doneF[d] = (int32_t)iF; sm.doneB[d] = (int32_t)iB; }
+        __syncthreads();
+        const bool todo = act && iB < n;
+        if (__builtin_amdgcn_ballot_w64(todo) == 0) break;
+        bool ran = false;
+        if (todo) {
+            const bool fwd = iF < W || (iF < n && iF - W == iB);
+            const int64_t i = fwd ? iF : iB;
+            const int w = (int)(i % group);
+            const int cch = fwd ? w / pp : vch - 1 - w / pp;
+            const int k = cch * pp + d;
+            bool ok = true;
+            double arrive = 0.0;
+            if (fwd) {
+                if (k > 0) {                                   // producer: the same slot on the device before,
+                    const int src = d > 0 ? d - 1 : pp - 1;    // or pp slots earlier on the last device
+                    const int64_t si = d > 0 ? i : i - pp;
+                    if (sm.doneF[src] > si) arrive = sm.ringF[src][si & (kVirtRing - 1)] + sm.latF[k];
+                    else ok = false;
+                }
+                // the slot this task overwrites in the ring must have been read by its consumers
+                if (ok && i >= kVirtRing) {
+                    if (d + 1 < pp && !(sm.doneF[d + 1] > i - kVirtRing)) ok = false;
+                    if (d == pp - 1 && vch > 1 && !(sm.doneF[0] > i - kVirtRing + pp)) ok = false;
+                }
+            } else {
+                if (k + 1 < S) {
+                    const int src = d + 1 < pp ? d + 1 : 0;
+                    const int64_t si = d + 1 < pp ? i : i - pp;
+                    if (sm.doneB[src] > si) arrive = sm.ringB[src][si & (kVirtRing - 1)] + sm.latB[k];
+                    else ok = false;
+                }
+                if (ok && i >= kVirtRing) {
+                    if (d > 0 && !(sm.doneB[d - 1] > i - kVirtRing)) ok = false;
+                    if (d == 0 && vch > 1 && !(sm.doneB[pp - 1] > i - kVirtRing + pp)) ok = false;
+                }
+            }
+            if (ok) {
+                const double t0 = arrive > own ? arrive : own;
+                own = t0 + (fwd ? sm.durF[k] : sm.durB[k]);
+                if (fwd) { sm.ringF[d][i & (kVirtRing - 1)] = own; iF++; }
+                else { sm.ringB[d][i & (kVirtRing - 1)] = own; iB++; }
+                if (DUMP) {
+                    const int64_t j = (i / group) * pp + w % pp;                 // micro-batch of the slot
+                    const int64_t e = ((int64_t)(fwd ? 0 : 1) * S + k) * m + j;
+                    dump.start[e] = double_to_i64(t0);
+                    dump.end[e] = double_to_i64(own);
+                }
+                ran = true;
+            }
+        }
+        if (__builtin_amdgcn_ballot_w64(ran) == 0) { stuck = true; break; }
+        __syncthreads();
+    }
+    __syncthreads();
+    if (stuck || __builtin_amdgcn_ballot_w64(act && iB < n) != 0) {
+        if (!DUMP && d == 0) { ev.status[c] = 1; ev.num_events[c] = 0; out.batch_ns[c] = INT64_MAX; }
+        return;
+    }
+
+    // data-parallel modelling per device: one trailing all-reduce over the bytes of all its chunks
+    const int64_t endB = double_to_i64(own);
+    const bool has_ar = act && dp > 1 && G > 0;
+    const int64_t AR = has_ar ? allreduce_ns(cl, dp, G) : 0;
+    if (DUMP) {
+        if (has_ar) { dump.ar_start[d] = endB; dump.ar_end[d] = endB + AR; }
+        return;
+    }
+    const int64_t batch = group_max(act ? endB + AR : 0, kWave);
+    const int64_t nar = group_count(has_ar, kWave);
+    const int64_t base = ev.stage_pos[c];
+    if (act && base >= 0) {
+        const int64_t cb = (int64_t)m * comp, mb = (int64_t)m * comm + AR;
+        out.comp_busy[base + d] = cb;
+        out.comm_busy[base + d] = mb;
+        if (out.util) out.util[base + d] = batch > 0 ? (double)cb / (double)batch : 0.0;
+    }
+    if (d == 0) {
+        out.batch_ns[c] = batch;
+        ev.num_events[c] = 2ll * m * S + 2ll * m * (S - 1) + nar;
+    }
+}
+
 __global__ __launch_bounds__(kWave) void k_simulate_virtual(CostsDev co, ClusterDev cl, CandDev ca, Workspace ws,
                                                             EventsDev ev, SimOut out, int64_t C) {
     __shared__ VirtLds sm;
-    const int d = threadIdx.x;                                   // device
-    const int L = co.L;
     for (int64_t pos = blockIdx.x; pos < C; pos += gridDim.x) {
         // descriptors beyond the valid candidates were never written: the class table bounds them
         if (pos >= ws.hdr[H_CLASS_START + kClasses]) break;
         const Desc ds = ws.desc[pos];
         if (!is_interleaved(ds) || (ds.meta & 0xff) == 0) continue;       // uniform: one descriptor per wavefront
-        const int pp = ds.meta & 0xff, v = ds.meta >> 16, m = ds.m, dp = ds.dp;
-        const int tp = (int)(uint32_t)ds.spare, vch = (int)(ds.spare >> 32);
-        const int64_t c = ds.cand;
-        const int S = pp * vch;
-        const bool act = d < pp;
-        const int64_t tpdp = (int64_t)tp * dp;
-        auto node_of = [&](int dev) -> int64_t {
-            return tpdp >= cl.gpus_per_node ? dev : (int64_t)udiv64((uint64_t)dev * (uint64_t)tpdp, (uint64_t)cl.gpus_per_node);
-        };
-        const int64_t* row = ws.comb + (size_t)((v * kMaxPP + pp - 1) * (L + 1)) * kCombWords;
-
-        // composed events of this device's chunks
-        int bad = 0;
-        int64_t comp = 0, comm = 0, G = 0, share = 0;
-        if (act) {
-            const int64_t my_node = node_of(d), next_node = node_of((d + 1) % pp), prev_node = node_of((d + pp - 1) % pp);
-            for (int cch = 0; cch < vch; cch++) {
-                const int k = cch * pp + d;
-                int lo, hi;
-                if (ds.poff >= 0) { lo = ca.part_pool[ds.poff + k]; hi = ca.part_pool[ds.poff + k + 1]; }
-                else { lo = (int)(((int64_t)k * L) / S); hi = (int)(((int64_t)(k + 1) * L) / S); }
-                if (hi <= lo || hi > L || (k == 0 && lo != 0) || (k == S - 1 && hi != L)) { bad = 1; break; }
-                const int64_t* eh = row + hi * kCombWords;
-                const int64_t* el = row + lo * kCombWords;
-                const int64_t FT = eh[0] - el[0], BT = eh[1] - el[1], CP = eh[2] - el[2];
-                const int64_t PF = k + 1 < S ? eh[4 + (my_node != next_node ? 1 : 0)] : 0;
-                const int64_t PB = k > 0 ? el[4 + (my_node != prev_node ? 1 : 0)] : 0;
-                G += eh[3] - el[3];
-                comp += CP;
-                comm += FT + BT - CP + PF + PB;
-                share += FT + BT + PF + PB;
-                const int64_t pf_task = cl.blocking == 1 ? PF : 0, pb_task = cl.blocking == 1 ? PB : 0;
-                sm.durF[k] = (double)(FT + pf_task);
-                sm.durB[k] = (double)(BT + pb_task);
-                sm.sendF[k] = PF - pf_task;
-                sm.sendB[k] = PB - pb_task;
-            }
-        }
-        bad = __builtin_amdgcn_ballot_w64(bad != 0) != 0;
-        const bool range = !bad && stage_out_of_range(act ? share : 0, m, kWave);
-        if (bad || range) {
-            if (d == 0) { ev.status[c] = bad ? 1 : 2; ev.num_events[c] = 0; out.batch_ns[c] = INT64_MAX; }
-            continue;
-        }
+        const VirtCand vc{ds.meta & 0xff, ds.meta >> 16, ds.m, ds.dp, (int)(uint32_t)ds.spare, (int)(ds.spare >> 32),
+                          ds.poff, ds.cand};
+        virtual_candidate<false>(co, cl, ca, ws, ev, out, vc, VirtDump{}, sm);
         __syncthreads();
-        // latency of the edge into virtual stage k: the send of k - 1 (forward), of k + 1 (backward)
-        if (act) {
-            for (int cch = 0; cch < vch; cch++) {
-                const int k = cch * pp + d;
-                sm.latF[k] = k > 0 ? (double)sm.sendF[k - 1] : 0.0;
-                sm.latB[k] = k + 1 < S ? (double)sm.sendB[k + 1] : 0.0;
-            }
-        }
-        __syncthreads();
+    }
+}
 
-        // the rounds
-        const int64_t n = (int64_t)m * vch;                       // slots per direction
-        const int group = pp * vch;                               // slots per group of pp micro-batches
-        int64_t W = 2ll * (pp - d - 1) + (int64_t)(vch - 1) * pp; // warm-up forwards
-        if (W > n) W = n;
-        int64_t iF = 0, iB = 0;
-        double own = 0.0;
-        bool stuck = false;
-        const int64_t max_rounds = 4 * n + 8 * pp + 64;
-        for (int64_t round = 0; round < max_rounds; round++) {
-            if (act) { sm.doneF[d] = (int32_t)iF; sm.doneB[d] = (int32_t)iB; }
-            __syncthreads();
-            const bool todo = act && iB < n;
-            if (__builtin_amdgcn_ballot_w64(todo) == 0) break;
-            bool ran = false;
-            if (todo) {
-                const bool fwd = iF < W || (iF < n && iF - W == iB);
-                const int64_t i = fwd ? iF : iB;
-                const int w = (int)(i % group);
-                const int cch = fwd ? w / pp : vch - 1 - w / pp;
-                const int k = cch * pp + d;
-                bool ok = true;
-                double arrive = 0.0;
-                if (fwd) {
-                    if (k > 0) {                                   // producer: the same slot on the device before,
-                        const int src = d > 0 ? d - 1 : pp - 1;    // or pp slots earlier on the last device
-                        const int64_t si = d > 0 ? i : i - pp;
-                        if (sm.doneF[src] > si) arrive = sm.ringF[src][si & (kVirtRing - 1)] + sm.latF[k];
-                        else ok = false;
-                    }
-                    // the slot this task overwrites in the ring must have been read by its consumers
-                    if (ok && i >= kVirtRing) {
-                        if (d + 1 < pp && !(sm.doneF[d + 1] > i - kVirtRing)) ok = false;
-                        if (d == pp - 1 && vch > 1 && !(sm.doneF[0] > i - kVirtRing + pp)) ok = false;
-                    }
-                } else {
-                    if (k + 1 < S) {
-                        const int src = d + 1 < pp ? d + 1 : 0;
-                        const int64_t si = d + 1 < pp ? i : i - pp;
-                        if (sm.doneB[src] > si) arrive = sm.ringB[src][si & (kVirtRing - 1)] + sm.latB[k];
-                        else ok = false;
-                    }
-                    if (ok && i >= kVirtRing) {
-                        if (d > 0 && !(sm.doneB[d - 1] > i - kVirtRing)) ok = false;
-                        if (d == 0 && vch > 1 && !(sm.doneB[pp - 1] > i - kVirtRing + pp)) ok = false;
-                    }
-                }
-                if (ok) {
-                    const double t0 = arrive > own ? arrive : own;
-                    own = t0 + (fwd ? sm.durF[k] : sm.durB[k]);
-                    if (fwd) { sm.ringF[d][i & (kVirtRing - 1)] = own; iF++; }
-                    else { sm.ringB[d][i & (kVirtRing - 1)] = own; iB++; }
-                    ran = true;
-                }
-            }
-            if (__builtin_amdgcn_ballot_w64(ran) == 0) { stuck = true; break; }
-            __syncthreads();
-        }
+// Timeline dump of the selected candidates that use the interleaved schedule; one wavefront per
+// selection.  The block of candidate sel[q] holds 2 * pp * chunks * m entries laid out
+// [kind][virtual stage][micro-batch]; the all-reduce windows are per device.  Runs after
+// k_timeline, which has set every all-reduce window to -1 and skipped these candidates.
+__global__ __launch_bounds__(kWave) void k_timeline_virtual(CostsDev co, ClusterDev cl, CandDev ca, Workspace ws,
+                                                            const int32_t* status, int64_t C, int64_t n,
+                                                            const int64_t* sel, const int64_t* task_off,
+                                                            int64_t* start_ns, int64_t* end_ns, int64_t* ar_start,
+                                                            int64_t* ar_end) {
+    __shared__ VirtLds sm;
+    for (int64_t q = blockIdx.x; q < n; q += gridDim.x) {
+        const int64_t c = sel[q];
+        if (c < 0 || c >= C || status[c] != 0 || ca.schedule[c] != 3 || !ca.chunks) continue;
+        const int tp = ca.tp[c];
+        int v = -1;
+        for (int i = 0; i < co.V; i++)
+            if (co.variant_tp[i] == tp) { v = i; break; }
+        if (v < 0) continue;                                              // cannot be: the status is OK
+        const VirtCand vc{ca.pp[c], v, ca.m[c], ca.dp[c], tp, ca.chunks[c], ca.part_off[c], c};
+        const int64_t off = task_off[q];
+        const VirtDump dump{start_ns + off, end_ns + off, ar_start + q * kMaxPP, ar_end + q * kMaxPP};
+        virtual_candidate<true>(co, cl, ca, ws, EventsDev{}, SimOut{}, vc, dump, sm);
         __syncthreads();
-        if (stuck || __builtin_amdgcn_ballot_w64(act && iB < n) != 0) {
-            if (d == 0) { ev.status[c] = 1; ev.num_events[c] = 0; out.batch_ns[c] = INT64_MAX; }
-            continue;
-        }
-
-        // data-parallel modelling per device: one trailing all-reduce over the bytes of all its chunks
-        const int64_t endB = double_to_i64(own);
-        const bool has_ar = act && dp > 1 && G > 0;
-        const int64_t AR = has_ar ? allreduce_ns(cl, dp, G) : 0;
-        const int64_t batch = group_max(act ? endB + AR : 0, kWave);
-        const int64_t nar = group_count(has_ar, kWave);
-        const int64_t base = ev.stage_pos[c];
-        if (act && base >= 0) {
-            const int64_t cb = (int64_t)m * comp, mb = (int64_t)m * comm + AR;
-            out.comp_busy[base + d] = cb;
-            out.comm_busy[base + d] = mb;
-            if (out.util) out.util[base + d] = batch > 0 ? (double)cb / (double)batch : 0.0;
-        }
-        if (d == 0) {
-            out.batch_ns[c] = batch;
-            ev.num_events[c] = 2ll * m * S + 2ll * m * (S - 1) + nar;
-        }
     }
 }
 

@@ -163,7 +163,10 @@ def _timeline_parity(H, oracle_mod, w, idx):
     out = ds.alloc_outputs(c, ev)
     ds.distsim_simulate(c, dw.cluster, ev, out)
     idx = np.asarray(idx, np.int64)
-    sizes = 2 * w.cand["pp"][idx].astype(np.int64) * w.cand["m"][idx]
+    vch = np.ones(w.C, np.int64)
+    if w.cand.get("chunks") is not None:
+        vch = np.where(w.cand["schedule"] == 3, w.cand["chunks"], 1).astype(np.int64)
+    sizes = 2 * w.cand["pp"][idx].astype(np.int64) * vch[idx] * w.cand["m"][idx]
     off = np.concatenate([[0], np.cumsum(sizes)])
     dev = c.device
     start = torch.full((int(off[-1]),), -7, dtype=torch.int64, device=dev)
@@ -185,10 +188,11 @@ def _timeline_parity(H, oracle_mod, w, idx):
             assert (start[off[k]:off[k + 1]] == -7).all() and (ar0[k] == -1).all()
             assert (idle[off[k]:off[k + 1]] == -7).all()
             continue
-        want_idle = idle_before(r["start"], r["end"], int(w.cand["schedule"][i]))
-        assert np.array_equal(idle[off[k]:off[k + 1]].reshape(2, pp, m), want_idle), (i, "idle")
-        assert np.array_equal(start[off[k]:off[k + 1]].reshape(2, pp, m), r["start"]), (i, "start")
-        assert np.array_equal(end[off[k]:off[k + 1]].reshape(2, pp, m), r["end"]), (i, "end")
+        S = pp * int(vch[i])                              # rows: stages, or virtual stages
+        want_idle = idle_before(r["start"], r["end"], int(w.cand["schedule"][i]), int(vch[i]))
+        assert np.array_equal(idle[off[k]:off[k + 1]].reshape(2, S, m), want_idle), (i, "idle")
+        assert np.array_equal(start[off[k]:off[k + 1]].reshape(2, S, m), r["start"]), (i, "start")
+        assert np.array_equal(end[off[k]:off[k + 1]].reshape(2, S, m), r["end"]), (i, "end")
         assert np.array_equal(ar0[k, :pp], r["ar_window"][0]) and np.array_equal(ar1[k, :pp], r["ar_window"][1]), i
         assert (ar0[k, pp:] == -1).all() and (ar1[k, pp:] == -1).all()
         # the timeline ends where the simulation says the batch ends
@@ -322,6 +326,16 @@ def test_interleaved_schedule(H, oracle_mod):
         assert (n_ok > 300) if blocking < 2 else (n_ok == 0)
         H.assert_same(H.run_hip(w, table=False), ora, what=w.name)
         H.assert_same(H.run_hip(w), ora, what=w.name + " with table")
+        if blocking < 2:                                  # dump and bubbles, both kinds of candidates
+            ok3 = np.nonzero((ora["status"] == 0) & (cand["schedule"] == 3))[0]
+            sel = np.sort(np.concatenate([ok3[::max(1, len(ok3) // 40)], np.arange(0, C, 97)]))
+            _timeline_parity(H, oracle_mod, w, np.unique(sel))
+    # without chunk counts an interleaved candidate is invalid
+    nc = {k: v for k, v in cand.items() if k != "chunks"}
+    w = Workload("gpt48+interleaved no chunks", w0.costs, w0.cluster, nc)
+    ora = oracle_mod.simulate(w, nthreads=NT)
+    assert (ora["status"][pick] == 1).all()
+    H.assert_same(H.run_hip(w, table=False), ora, what=w.name)
     # explicit partitions into pp * chunks parts, ragged sizes, many micro-batches, 64 virtual stages
     L = 96
     costs = mk_costs(rng.integers(0, 5000, (2, L)).tolist(), rng.integers(0, 9000, (2, L)).tolist(),
@@ -352,6 +366,7 @@ def test_interleaved_schedule(H, oracle_mod):
     ora = oracle_mod.simulate(w, nthreads=NT)
     assert (ora["status"] == 0).sum() > 40
     H.assert_same(H.run_hip(w, table=False), ora, what="interleaved ragged")
+    _timeline_parity(H, oracle_mod, w, np.arange(0, w.C, 3))
 
 
 def test_runs_are_deterministic(H):

@@ -142,6 +142,38 @@ def test_bubbles_account_for_all_idle_time(oracle_mod, sched):
         assert idle[0, 0, 0] == 0
 
 
+def test_bubbles_of_the_interleaved_schedule(oracle_mod):
+    """The same accounting over virtual stages: every task of a device once, no negative idle time,
+    idle + busy = end of the device's last task, and (positive durations) the list order is the
+    order of the start times.  With one chunk the list is the Dapple list with the longer warm-up."""
+    from helpers import mk_cluster, mk_costs
+    from oracle.bubbles import device_order_interleaved, idle_before
+    rng = np.random.default_rng(77)
+    L = 24
+    for pp, v, groups in [(1, 1, 3), (1, 4, 2), (2, 2, 1), (2, 3, 4), (3, 2, 2), (4, 3, 1), (4, 6, 3), (6, 4, 2), (8, 1, 2)]:
+        m = pp * groups
+        costs = mk_costs(rng.integers(1, 900, L).tolist(), rng.integers(1, 900, L).tolist(), act=[3000] * L)
+        r = _timeline_of(oracle_mod, costs, mk_cluster(pp, alpha=(40, 40), beta=(10, 10)), (1, 1, pp, m, 3, None, v))
+        assert r["status"][0] == 0
+        st, en = r["start"], r["end"]
+        assert st.shape == (2, pp * v, m)
+        idle = idle_before(st, en, 3, v)
+        assert (idle >= 0).all()
+        for d in range(pp):
+            order = device_order_interleaved(pp, m, v, d)
+            mine = [(k, c * pp + d, j) for k in (0, 1) for c in range(v) for j in range(m)]
+            assert sorted(order) == sorted(mine)
+            rows = [c * pp + d for c in range(v)]
+            busy = int((en[:, rows, :] - st[:, rows, :]).sum())
+            assert int(idle[:, rows, :].sum()) + busy == int(en[:, rows, :].max())
+            by_time = sorted([(int(st[k, vs, j]), k, vs, j) for k, vs, j in mine])
+            assert [(k, vs, j) for _, k, vs, j in by_time] == order
+            if v == 1:
+                w = min(2 * (pp - d - 1), m)
+                assert order[:w] == [(0, d, j) for j in range(w)] and (w == m or order[w + 1] == (1, d, 0))
+        assert idle[0, 0, 0] == 0
+
+
 def test_bubbles_of_the_hand_unrolled_pipeline(oracle_mod):
     """pp = 2, m = 4, Dapple, uniform stages F = 10, B = 20, p2p c = 3 (the timeline of
     tests/golden/pipeline_pp2_m4.txt with numbers put in): stage 1 idles F + c before its first

@@ -752,6 +752,9 @@ def test_interleaved_against_task_graph(oracle_mod):
         ar = [0 if dp == 1 else 2 + (2 * (dp - 1) * g) // (dp * 5) for g in G]
         dev_end = [max(val for (k_, vs, j), val in end.items() if vs % pp == d) for d in range(pp)]
         assert r["batch_ns"][0] == max(dev_end[d] + ar[d] for d in range(pp))
+        for d in range(pp):                       # all-reduce window of every device in the dump
+            assert r["ar_window"][0][d] == (dev_end[d] if dp > 1 else -1)
+            assert r["ar_window"][1][d] == (dev_end[d] + ar[d] if dp > 1 else -1)
         for d in range(pp):
             comm = m * sum(pf[c * pp + d] + pb[c * pp + d] for c in range(v)) + ar[d]
             assert r["comm_busy_ns"][d] == comm
