@@ -147,7 +147,20 @@ struct ClusterDev {
     int64_t alpha[2], beta[2];
     int64_t bucket;
     int32_t blocking;          // 1: p2p events occupy the sender; 2: sends queue on their link
+    double inv_gpus_per_node;  // 1 / gpus_per_node (set on the host)
 };
+
+// Node of the first rank of pipeline position s when a position spans tpdp < gpus_per_node
+// ranks: floor(s * tpdp / gpus_per_node) for s < 64.  The product is exact in fp64 and the
+// quotient is below 64, so one multiplication by the reciprocal and an exact remainder give it.
+__device__ __forceinline__ int node_of_position(const ClusterDev& cl, int s, int tpdp) {
+    const double x = (double)s * (double)tpdp, g = (double)cl.gpus_per_node;
+    int q = (int)(x * cl.inv_gpus_per_node);
+    const double r = __fma_rn(-(double)q, g, x);
+    if (r < 0.0) q--;
+    else if (r >= g) q++;
+    return q;
+}
 
 __device__ __forceinline__ int64_t p2p_ns(const ClusterDev& cl, int64_t bytes, int k) {
     return cl.alpha[k] + (int64_t)udiv64((uint64_t)bytes, (uint64_t)cl.beta[k]);

@@ -80,6 +80,7 @@ ClusterDev to_dev(const distsim_cluster& c) {
     d.beta[0] = c.beta_bytes_per_ns[0]; d.beta[1] = c.beta_bytes_per_ns[1];
     d.bucket = c.dp_bucket_bytes;
     d.blocking = c.p2p_blocking;
+    d.inv_gpus_per_node = 1.0 / (double)c.gpus_per_node;
     return d;
 }
 

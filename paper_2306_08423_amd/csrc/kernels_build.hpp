@@ -286,7 +286,7 @@ __device__ __forceinline__ int stage_check(const ClusterDev& cl, int L, int widt
         bad = (hi <= lo) || (hi > L) || (s == 0 && lo != 0) || (s == pp - 1 && hi != L);
         // a stage of at least a node's worth of ranks starts on a node of its own
         const int64_t tpdp = (int64_t)tp * dp;
-        node = tpdp >= cl.gpus_per_node ? s : (int)udiv64((uint64_t)s * (uint64_t)tpdp, (uint64_t)cl.gpus_per_node);
+        node = tpdp >= cl.gpus_per_node ? s : node_of_position(cl, s, (int)tpdp);
     }
     inter_next = node != __builtin_amdgcn_update_dpp(0, node, kDppWaveShl1, 0xf, 0xf, true);
     inter_prev = node != __builtin_amdgcn_update_dpp(0, node, kDppWaveShr1, 0xf, 0xf, true);

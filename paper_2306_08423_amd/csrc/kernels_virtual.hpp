@@ -52,7 +52,7 @@ __device__ __forceinline__ void virtual_candidate(const CostsDev& co, const Clus
     const bool act = d < pp;
     const int64_t tpdp = (int64_t)tp * dp;
     auto node_of = [&](int dev) -> int64_t {
-        return tpdp >= cl.gpus_per_node ? dev : (int64_t)udiv64((uint64_t)dev * (uint64_t)tpdp, (uint64_t)cl.gpus_per_node);
+        return tpdp >= cl.gpus_per_node ? dev : (int64_t)node_of_position(cl, dev, (int)tpdp);
     };
     const int64_t* row = ws.comb + (size_t)((v * kMaxPP + pp - 1) * (L + 1)) * kCombWords;
 
