@@ -33,7 +33,7 @@ static const char* kKernelNames[DISTSIM_K_COUNT] = {
     "k_layer_tables", "k_decode", "k_bins", "k_scatter",
     "k_stage_events", "k_sim_init", "k_simulate", "k_search", "k_timeline",
     "k_dedup", "k_comm_event_times", "k_bubbles", "k_simulate_virtual",
-    "k_timeline_virtual",
+    "k_timeline_virtual", "k_simulate_gpipe",
 };
 
 static int fail(distsim_ctx* ctx, int code, const std::string& msg) {
@@ -97,6 +97,13 @@ int simulate_grid(const distsim_ctx* ctx, int64_t C) {
     const int64_t want = (int64_t)ctx->num_cus * 128;
     const int64_t need = (C + 7) / 8;                         // blocks of 4 waves, 2 items per wave
     return (int)(need < want ? (need < 1 ? 1 : need) : want);
+}
+
+// k_simulate and k_simulate_gpipe share the items: half the grid each (a wavefront strides over
+// its kernel's pairs, so any split of the items is covered)
+int queue_grid(const distsim_ctx* ctx, int64_t C) {
+    const int g = simulate_grid(ctx, C) / 2;
+    return g < 1 ? 1 : g;
 }
 
 int item_grid(const distsim_ctx* ctx, int64_t C) {
@@ -189,7 +196,7 @@ int distsim_build_events(distsim_ctx* ctx, const distsim_costs* costs, const dis
     }
     {
         Timer t(ctx, st, DISTSIM_K_BINS);
-        hipLaunchKernelGGL(k_bins, dim3(1), dim3(kBinsBlock), 0, st, ws);
+        hipLaunchKernelGGL(k_bins, dim3(1), dim3(kBinsBlock), 0, st, ws, out->stage_cap);
     }
     if (C > 0) {
         {
@@ -245,7 +252,11 @@ int distsim_simulate(distsim_ctx* ctx, const distsim_cluster* cluster, const dis
         if (cl.blocking == 2)
             hipLaunchKernelGGL(k_simulate_links, dim3(simulate_grid(ctx, C)), dim3(256), 0, st, co, cl, ca, ws, ev, out);
         else
-            hipLaunchKernelGGL(k_simulate, dim3(simulate_grid(ctx, C)), dim3(256), 0, st, co, cl, ca, ws, ev, out);
+            hipLaunchKernelGGL(k_simulate, dim3(queue_grid(ctx, C)), dim3(256), 0, st, co, cl, ca, ws, ev, out);
+    }
+    if (cl.blocking != 2) {     // the pairs of GPipe items that k_simulate leaves out
+        Timer t(ctx, st, DISTSIM_K_SIMULATE_GPIPE);
+        hipLaunchKernelGGL(k_simulate_gpipe, dim3(queue_grid(ctx, C)), dim3(256), 0, st, co, cl, ca, ws, ev, out);
     }
     if (cd->chunks) {       // candidates of the interleaved schedule, if the caller has any
         Timer t(ctx, st, DISTSIM_K_SIMULATE_VIRTUAL);

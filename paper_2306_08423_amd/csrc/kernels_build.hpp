@@ -193,11 +193,12 @@ __global__ __launch_bounds__(kDecodeBlock) void k_decode(CostsDev co, ClusterDev
 // ---------------------------------------------------------------------------------------
 // Ordering bins -> first position of every bin, class ranges and wave-item ranges.
 constexpr int kBinsBlock = 1024;
-__global__ __launch_bounds__(kBinsBlock) void k_bins(Workspace ws) {
+__global__ __launch_bounds__(kBinsBlock) void k_bins(Workspace ws, int64_t stage_cap) {
     constexpr int per = kBins / kBinsBlock;
     static_assert(kBins % kBinsBlock == 0, "bins must split evenly");
     __shared__ int64_t wsum[kBinsBlock / kWave];
     __shared__ int32_t cls[kClasses + 1];
+    __shared__ int32_t mid[kClasses];        // first position of each class's second half of bins (schedule != GPipe)
     const int t = threadIdx.x;
     int loc[per];
     int64_t s = 0;
@@ -212,6 +213,7 @@ __global__ __launch_bounds__(kBinsBlock) void k_bins(Workspace ws) {
         const int b = t * per + i;
         ws.bin_start[b] = (int32_t)ex;
         if (b % kBinsPerClass == 0) cls[b / kBinsPerClass] = (int32_t)ex;
+        if (b % kBinsPerClass == kMBins) mid[b / kBinsPerClass] = (int32_t)ex;
         ex += loc[i];
     }
     if (t == kBinsBlock - 1) { ws.bin_start[kBins] = (int32_t)ex; cls[kClasses] = (int32_t)ex; }
@@ -223,6 +225,11 @@ __global__ __launch_bounds__(kBinsBlock) void k_bins(Workspace ws) {
             ws.hdr[H_CLASS_START + k] = a;
             ws.hdr[H_ITEM_START + k] = items;
             const int64_t per_item = 1 << k;       // candidates per wave-item in class k
+            // leading items of GPipe candidates only, as far as the per-stage arrays have room
+            int64_t g = k < kClasses - 1 ? (mid[k] - a) >> k : 0;
+            const int64_t room = stage_cap / kWave - items;
+            if (g > room) g = room < 0 ? 0 : room;
+            ws.hdr[H_GPIPE_ITEMS + k] = g & ~(int64_t)1;
             items += (b - a + per_item - 1) / per_item;
         }
         ws.hdr[H_CLASS_START + kClasses] = cls[kClasses];

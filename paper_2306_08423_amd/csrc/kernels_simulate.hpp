@@ -144,6 +144,42 @@ __device__ __forceinline__ double from_lanes(double x, int byte_addr) {
         : [o_] "+v"(o), [tl_] "+v"(tl), [tr_] "+v"(tr)                        \
         : [kf] "s"(kmask), [kb] "s"(kmask2), [cl__] "v"(cl_), [cr__] "v"(cr_), [df_] "v"(df), [db_] "v"(db))
 
+// Two chained tasks of one lane at one level: the first takes its operand from a neighbour lane
+// (t), the second from the first (two stages of one candidate held by one lane).  Both run under
+// the one mask taken from the pattern.
+#define DISTSIM_DSTEP(bits, o1st, o2nd, t, lat1st, dur1st, lat2nd, dur2nd)     \
+    asm volatile(                                                              \
+        "v_add_co_u32_e64 %[p], %[k], %[p], %[p]\n\t"                        \
+        "s_mov_b64 exec, %[k]\n\t"                                            \
+        "v_add_f64 %[t_], %[t_], %[ca]\n\t"                                   \
+        "v_max_f64 %[t_], %[t_], %[oa]\n\t"                                   \
+        "v_add_f64 %[oa], %[t_], %[da]\n\t"                                   \
+        "v_add_f64 %[t_], %[oa], %[cb]\n\t"                                   \
+        "v_max_f64 %[t_], %[t_], %[ob]\n\t"                                   \
+        "v_add_f64 %[ob], %[t_], %[db]\n\t"                                   \
+        "s_mov_b64 exec, -1\n\t"                                              \
+        "s_nop 0"                                                              \
+        : [oa] "+v"(o1st), [ob] "+v"(o2nd), [t_] "+v"(t), [p] "+v"(bits), [k] "=&s"(kmask) \
+        : [ca] "v"(lat1st), [da] "v"(dur1st), [cb] "v"(lat2nd), [db] "v"(dur2nd))
+
+// Level windows of a lane that holds stage s, expressed on x = level - s:
+//   forward  x in [0, f1hi]  and  even x in [f2lo, f2hi]
+//   backward x in [blo, bhi], every x (GPipe) or every second x (1F1B)
+struct LevelWindows {
+    int f1hi, f2lo = 1, f2hi = 0, blo, bhi;
+    __device__ __forceinline__ LevelWindows(int sched, int m, int pp, int s) {
+        if (sched == 0) {
+            f1hi = m - 1;
+            blo = m + 2 * pp - 2 - 2 * s; bhi = blo + m - 1;
+        } else {
+            int wq = pp - 1 - s; if (wq > m) wq = m;
+            f1hi = wq < m - 1 ? wq : m - 1;
+            f2lo = 2 * wq + 2; f2hi = 2 * m - 2;
+            blo = 2 * pp - 1 - 2 * s; bhi = blo + 2 * m - 2;
+        }
+    }
+};
+
 // Per-lane state of one candidate's sweep.
 struct Sweep {
     double own;            // end of the most recent task on this device
@@ -164,21 +200,113 @@ struct Park {
     int32_t misc[2][kSimBlock];        // layer bounds, flags, variant
 };
 
+// GPipe sweep of two items of one shape with the stages regrouped two to a lane.  In the usual
+// layout item u, lane l holds one stage and every level moves the neighbour's value across
+// lanes.  Here lane x holds the stages of the linear positions 2x and 2x + 1 (position = 64 u +
+// l), i.e. two neighbouring stages of one candidate (candidates take an even number of lanes:
+// sh >= 1), and a level runs both: forwards F(2i, j) then F(2i+1, j), whose operand is the
+// lane's own first result; backwards B(2i+1, j) then B(2i, j).  Levels, for pair i of a
+// candidate with I = ceil(pp / 2) pairs: forwards i + j, backwards (m + I - 1) + (I - 1 - i) + j.
+// One cross-lane move serves two stage-tasks and the ramps are half as long.  Edges that do not
+// exist carry -inf, stages that do not exist have zero durations, as in the usual layout.
+// The two items may differ in shape (pp, m of a lane's candidate); they share the lanes per
+// candidate.  xp: 128 doubles of LDS owned by this wavefront.
+__device__ __forceinline__ void sweep_gpipe_pair(Sweep (&sw)[2], int sh, int lane, const int (&pp)[2],
+                                                 const int (&m)[2], double* xp) {
+    auto regroup = [&](double a, double b, double& x0, double& x1) {
+        xp[lane] = a;
+        xp[kWave + lane] = b;
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        const double2 v = reinterpret_cast<const double2*>(xp)[lane];
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");       // read before the next overwrite
+        x0 = v.x; x1 = v.y;
+    };
+    double F0, F1, B0, B1, pl0, pl1, pr0, pr1;
+    regroup(sw[0].Fd, sw[1].Fd, F0, F1);
+    regroup(sw[0].Bd, sw[1].Bd, B0, B1);
+    regroup(sw[0].pfL, sw[1].pfL, pl0, pl1);
+    regroup(sw[0].pbR, sw[1].pbR, pr0, pr1);
+    // shape of the candidate whose stages this lane now holds
+    const int src = 2 * (lane & 31);
+    const int mp0 = __shfl(m[0] | (pp[0] << 24), src, kWave), mp1 = __shfl(m[1] | (pp[1] << 24), src, kWave);
+    const int mp = lane < 32 ? mp0 : mp1;
+    const int mm = mp & 0xffffff, I = ((mp >> 24) + 1) >> 1;       // mm = 0: no candidate here
+    const int i = (src & ((1 << sh) - 1)) >> 1;
+    const bool on = mm > 0;
+    const int blo = mm + 2 * I - 2 - 2 * i, bhi = blo + mm - 1;    // on x = level - i
+    const int gLastF = wave_max_i32(on ? i + mm - 1 : -1);
+    const int gFirstB = -wave_max_i32(on ? -(i + blo) : -(1 << 30));
+    const int gLastB = wave_max_i32(on ? i + bhi : -1);
+    const int nlev = gLastB + 1;
+    double own0 = 0.0, own1 = 0.0;
+    uint64_t kmask;
+    for (int l0 = 0; l0 < nlev; l0 += 32) {
+        const int x0 = l0 - i;
+        uint32_t PFb = on ? level_bits(-x0, mm - 1 - x0) : 0u;
+        uint32_t PBb = on ? level_bits(blo - x0, bhi - x0) : 0u;
+        // chunk-relative levels with forwards [0, lastF] and with backwards [firstB, lastB]
+        const bool anyF = gLastF >= l0, anyB = gFirstB < l0 + 32;
+        const int lastF = anyF ? (gLastF - l0 < 31 ? gLastF - l0 : 31) : -1;
+        const int firstB = anyB ? (gFirstB > l0 ? gFirstB - l0 : 0) : 64;
+        const int lastB = anyB ? (gLastB - l0 < 31 ? gLastB - l0 : 31) : -1;
+        // forwards only, then levels that have both kinds (candidates of different length in one
+        // wavefront), then backwards only; a pattern is shifted up to the level of its first use
+        const int onlyF = lastF + 1 < firstB ? lastF + 1 : firstB;
+        int k = 0;
+        for (; k < onlyF; k++) {
+            double t = from_prev_lane(own1);
+            DISTSIM_DSTEP(PFb, own0, own1, t, pl0, F0, pl1, F1);
+        }
+        if (k <= lastF) {
+            PBb = shl32(PBb, k);
+            for (; k <= lastF; k++) {
+                double t = from_prev_lane(own1), r = from_next_lane(own0);
+                DISTSIM_DSTEP(PFb, own0, own1, t, pl0, F0, pl1, F1);
+                DISTSIM_DSTEP(PBb, own1, own0, r, pr1, B1, pr0, B0);
+            }
+        } else {
+            k = firstB > k ? firstB : k;
+            PBb = shl32(PBb, k);
+        }
+        for (; k <= lastB; k++) {
+            double r = from_next_lane(own0);
+            DISTSIM_DSTEP(PBb, own1, own0, r, pr1, B1, pr0, B0);
+        }
+    }
+    (void)kmask;
+    // back to one stage per lane
+    reinterpret_cast<double2*>(xp)[lane] = double2{own0, own1};
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    sw[0].own = xp[lane];
+    sw[1].own = xp[kWave + lane];
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+}
+
 // Simulates U wave-items at once.  For U = 2 the two items must have the same shape in every
-// lane (pp, m, schedule): then they share patterns, masks and control flow.
-template <int U, bool LINKS = false>
+// lane (pp, m, schedule): then they share patterns, masks and control flow.  GPIPE_PAIR: the two
+// items hold GPipe candidates of at least two lanes each and are swept with the stages regrouped
+// two to a lane (sweep_gpipe_pair); the caller has checked that.
+template <int U, bool LINKS = false, bool GPIPE_PAIR = false>
 __device__ __forceinline__ void simulate_items(const ClusterDev& cl, const CandDev& ca, const Workspace& ws,
                                                const EventsDev& ev, const SimOut& out, int L, int64_t w0,
                                                int sh, const Desc (&d)[U], int lane,
-                                               Park& park) {
+                                               Park& park, double* xp = nullptr) {
     const double ninf = -__builtin_huge_val();
     const int slot = threadIdx.x;
     const int width = 1 << sh;
     const int s = lane & (width - 1);
-    // shape (shared by the U items)
-    const int pp = d[0].meta & 0xff, sched = (d[0].meta >> 8) & 0xff;
-    const bool act = s < pp;
-    const int m = act ? d[0].m : 0;
+    // shape: shared by the U items, except in a GPipe pair, where each item has its own
+    int ppv[U], mv[U];
+    bool actv[U];
+#pragma unroll
+    for (int u = 0; u < U; u++) {
+        const Desc& ds = d[GPIPE_PAIR ? u : 0];
+        ppv[u] = ds.meta & 0xff;
+        actv[u] = s < ppv[u];
+        mv[u] = actv[u] ? ds.m : 0;
+    }
+    const int pp = ppv[0], sched = (d[0].meta >> 8) & 0xff, m = mv[0];
+    const bool act = actv[0];
 
     Sweep sw[U];
     double sendF[U], sendB[U];      // LINKS: duration of this stage's outgoing forward / backward send
@@ -188,15 +316,15 @@ __device__ __forceinline__ void simulate_items(const ClusterDev& cl, const CandD
         const int64_t c = d[u].cand;
         // the stage's composed events, regenerated from the layer-event tables
         int lo = 0, hi = 0;
-        if (act) {
+        if (actv[u]) {
             if (d[u].poff >= 0) { lo = ca.part_pool[d[u].poff + s]; hi = ca.part_pool[d[u].poff + s + 1]; }
-            else { lo = (int)(((int64_t)s * L) / pp); hi = (int)(((int64_t)(s + 1) * L) / pp); }
+            else { lo = (int)(((int64_t)s * L) / ppv[u]); hi = (int)(((int64_t)(s + 1) * L) / ppv[u]); }
         }
         StageSums r;
-        const int drop = stage_sums(cl, ws, L, width, s, pp, v, d[u].m, dp, (int)d[u].spare, lo, hi, r);
-        if (drop && act && s == 0) { ev.status[c] = drop; ev.num_events[c] = 0; out.batch_ns[c] = INT64_MAX; }
+        const int drop = stage_sums(cl, ws, L, width, s, ppv[u], v, d[u].m, dp, (int)d[u].spare, lo, hi, r);
+        if (drop && actv[u] && s == 0) { ev.status[c] = drop; ev.num_events[c] = 0; out.batch_ns[c] = INT64_MAX; }
         // gradient bytes to reduce over dp > 1 ranks; the asynchronous schedule has no such event
-        const bool has_ar = act && dp > 1 && r.G > 0 && sched != 2;
+        const bool has_ar = actv[u] && dp > 1 && r.G > 0 && sched != 2;
         // p2p on the incoming edges (the neighbours' outgoing events): latency of the edge, or,
         // when the sender is occupied by it, part of the sender's task; -inf = no edge
         const int64_t pf_task = cl.blocking == 1 ? r.PF : 0, pb_task = cl.blocking == 1 ? r.PB : 0;
@@ -206,8 +334,8 @@ __device__ __forceinline__ void simulate_items(const ClusterDev& cl, const CandD
         sw[u].pfL = from_prev_lane((double)(r.PF - pf_task));
         sw[u].pbR = from_next_lane((double)(r.PB - pb_task));
         sendF[u] = (double)r.PF; sendB[u] = (double)r.PB;
-        if (!(act && s > 0)) sw[u].pfL = ninf;
-        if (!(act && s + 1 < pp)) sw[u].pbR = ninf;
+        if (!(actv[u] && s > 0)) sw[u].pfL = ninf;
+        if (!(actv[u] && s + 1 < ppv[u])) sw[u].pbR = ninf;
         // what only the epilogue needs waits in LDS
         park.comp[u][slot] = r.CP;                                         // computation per micro-batch
         park.comm[u][slot] = r.FT + r.BT - r.CP + r.PF + r.PB;             // communication per micro-batch
@@ -217,20 +345,9 @@ __device__ __forceinline__ void simulate_items(const ClusterDev& cl, const CandD
         park.misc[u][slot] = lo | (hi << 8) | ((int)has_ar << 16) | ((drop ? 1 : 0) << 17) | (v << 18);
     }
 
-    // level windows of this lane, expressed on x = level - s:
-    //   forward  x in [0, f1hi]  and  even x in [f2lo, f2hi]
-    //   backward x in [blo, bhi], every x (GPipe) or every second x (1F1B)
-    int f1hi, f2lo = 1, f2hi = 0, blo, bhi;
-    if (sched == 0) {
-        f1hi = m - 1;
-        blo = m + 2 * pp - 2 - 2 * s; bhi = blo + m - 1;
-    } else {
-        int wq = pp - 1 - s; if (wq > m) wq = m;
-        f1hi = wq < m - 1 ? wq : m - 1;
-        f2lo = 2 * wq + 2; f2hi = 2 * m - 2;
-        blo = 2 * pp - 1 - 2 * s; bhi = blo + 2 * m - 2;
-    }
     if constexpr (LINKS) {
+        const LevelWindows lw(sched, m, pp, s);
+        const int f1hi = lw.f1hi, f2lo = lw.f2lo, f2hi = lw.f2hi, blo = lw.blo, bhi = lw.bhi;
         // Sends queue on their link (p2p_blocking = 2): every lane keeps the arrival time of its
         // latest forward send and of its latest backward send; a send starts when its task has
         // ended and the link is free, and the neighbour reads the arrival time instead of the end
@@ -262,7 +379,12 @@ __device__ __forceinline__ void simulate_items(const ClusterDev& cl, const CandD
             }
         }
         sw[0].own = own;
+    } else if constexpr (GPIPE_PAIR) {
+        static_assert(U == 2, "the regrouped sweep takes two items");
+        sweep_gpipe_pair(sw, sh, lane, ppv, mv, xp);
     } else {
+        const LevelWindows lw(sched, m, pp, s);
+        const int f1hi = lw.f1hi, f2lo = lw.f2lo, f2hi = lw.f2hi, blo = lw.blo, bhi = lw.bhi;
         // Levels at which some lane of the wavefront has a forward / a backward task: forwards from
         // level 0 to gLastF, backwards from gFirstB to gLastB (the last level of the sweep).
         const int lastFx = (f2lo <= f2hi && f2hi > f1hi) ? f2hi : f1hi;
@@ -390,7 +512,7 @@ __device__ __forceinline__ void simulate_items(const ClusterDev& cl, const CandD
         if (has_ar && cl.bucket > 0) {
             const int lo = misc & 0xff, hi = (misc >> 8) & 0xff, v = misc >> 18, dp = park.dp[u][slot];
             // per layer: backward time up to the layer (word 1) and gradient bytes (word 3)
-            const int64_t* row = ws.comb + (size_t)((v * kMaxPP + pp - 1) * (L + 1)) * kCombWords;
+            const int64_t* row = ws.comb + (size_t)((v * kMaxPP + ppv[u] - 1) * (L + 1)) * kCombWords;
             const int64_t startB = endB - (int64_t)sw[u].Bd;
             const int64_t tot_hi = row[hi * kCombWords + 1];
             const int64_t ar_cap = allreduce_ns(cl, dp, cl.bucket);
@@ -418,11 +540,11 @@ __device__ __forceinline__ void simulate_items(const ClusterDev& cl, const CandD
         }
         // one event per stage that has one, or the stages' bucket counts
         nar = cl.bucket > 0 ? group_sum(nar, width) : group_count(has_ar, width);
-        const int64_t batch = group_max(act && !dropped ? finish : 0, width);
+        const int64_t batch = group_max(actv[u] && !dropped ? finish : 0, width);
         // lanes outside a candidate and dropped candidates have zero rows: they store zeros
-        const bool live = act && !dropped;
-        const int64_t comp = live ? (int64_t)m * park.comp[u][slot] : 0;
-        const int64_t comm = live ? (int64_t)m * park.comm[u][slot] + ar_busy : 0;
+        const bool live = actv[u] && !dropped;
+        const int64_t comp = live ? (int64_t)mv[u] * park.comp[u][slot] : 0;
+        const int64_t comm = live ? (int64_t)mv[u] * park.comm[u][slot] + ar_busy : 0;
         const int64_t i = (w0 + u) * kWave + lane;
         out.comp_busy[i] = comp;
         out.comm_busy[i] = comm;
@@ -430,48 +552,110 @@ __device__ __forceinline__ void simulate_items(const ClusterDev& cl, const CandD
         if (live && s == 0) {
             const int64_t cc = park.cand[u][slot];
             out.batch_ns[cc] = batch;
-            ev.num_events[cc] = 2ll * m * pp + 2ll * m * (pp - 1) + nar;
+            ev.num_events[cc] = 2ll * mv[u] * ppv[u] + 2ll * mv[u] * (ppv[u] - 1) + nar;
         }
     }
 }
 
-__global__ __launch_bounds__(kSimBlock, 6) void k_simulate(CostsDev co, ClusterDev cl, CandDev ca, Workspace ws,
-                                                           EventsDev ev, SimOut out) {
+// Two launches share the wave-items.  In every class the leading items that hold only GPipe
+// candidates (hdr[H_GPIPE_ITEMS + class], an even number) belong to k_simulate_gpipe, which
+// sweeps them two at a time with the stages regrouped two to a lane; all other items belong to
+// k_simulate.  Two kernels, so that each gets registers allotted for its own sweep.  Either
+// launch numbers its own items and a wavefront takes them two at a time, with the stride of
+// the grid (about one pair per wavefront for large lists: the hardware's dispatch order is the
+// load balancing, and the items of the widest class, the longest, go first).
+
+// Item number t of one launch's share -> its place in visiting order.
+struct OwnedItem {
+    Item it;
+    int64_t w;          // wave-item index (rows w * 64 .. of the per-stage arrays)
+};
+__device__ __forceinline__ OwnedItem owned_item(const int64_t* __restrict__ hdr, int64_t t, bool gpipe) {
+    int k = 0;
+    int64_t first = 0;                                  // first owned item of the class, relative to the class
+    for (; k < kClasses - 1; k++) {
+        const int64_t n = hdr[H_ITEM_START + k + 1] - hdr[H_ITEM_START + k], g = hdr[H_GPIPE_ITEMS + k];
+        const int64_t mine = gpipe ? g : n - g;
+        if (t < mine) break;
+        t -= mine;
+    }
+    first = gpipe ? 0 : hdr[H_GPIPE_ITEMS + k];
+    OwnedItem o;
+    o.w = hdr[H_ITEM_START + k] + first + t;
+    o.it.sh = 6 - k;
+    o.it.pos0 = hdr[H_CLASS_START + k] + ((first + t) << k);
+    o.it.class_end = hdr[H_CLASS_START + k + 1];
+    return o;
+}
+
+template <bool GPIPE_PAIRS>
+__device__ __forceinline__ void simulate_all(const CostsDev& co, const ClusterDev& cl, const CandDev& ca,
+                                             const Workspace& ws, const EventsDev& ev, const SimOut& out,
+                                             Park& park, double* xp) {
     const int lane = lane_id();
+    const int64_t* __restrict__ hdr = ws.hdr;
     const int64_t wave0 = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / kWave;
     const int64_t nwaves = ((int64_t)gridDim.x * blockDim.x) / kWave;
-    int64_t W = ws.hdr[H_NUM_ITEMS];
+    int64_t W = hdr[H_NUM_ITEMS];                       // items that have room in the per-stage arrays
     if (W * kWave > ev.stage_cap) W = ev.stage_cap / kWave;
+    int64_t gp_items = 0;
+    for (int k = 0; k < kClasses; k++) gp_items += hdr[H_GPIPE_ITEMS + k];
+    int64_t mine = GPIPE_PAIRS ? gp_items : hdr[H_NUM_ITEMS] - gp_items;
+    // items past the room in the per-stage arrays are skipped anyway
+    if (mine > ev.stage_cap + kClasses) mine = ev.stage_cap + kClasses;
+    const int64_t pairs = (mine + 1) / 2;
     const int L = co.L;
-    // What only the epilogue needs is parked in LDS during the sweep (each lane its own slot),
-    // so that the sweep runs in few enough registers for six wavefronts per SIMD.
-    __shared__ Park park;
-
-    // A wavefront takes two neighbouring items per turn; they are simulated together when every
-    // lane sees the same shape (pp, m, schedule) in both, which neighbours in visiting order
-    // mostly do, else one after the other.
-    for (int64_t w = 2 * wave0; w < W; w += 2 * nwaves) {
-        const bool pair = w + 1 < W;
-        const Item ia = decode_item(ws.hdr, w);
-        const Item ib = decode_item(ws.hdr, pair ? w + 1 : w);
+    for (int64_t q = wave0; q < pairs; q += nwaves) {
+        const bool pair = 2 * q + 1 < mine;
+        const OwnedItem oa = owned_item(hdr, 2 * q, GPIPE_PAIRS);
+        const OwnedItem ob = owned_item(hdr, pair ? 2 * q + 1 : 2 * q, GPIPE_PAIRS);
+        const Item ia = oa.it, ib = ob.it;
         const int64_t posa = ia.pos0 + (lane >> ia.sh), posb = ib.pos0 + (lane >> ib.sh);
         Desc da{}, db{};
         if (posa < ia.class_end) da = ws.desc[posa];
         if (pair && posb < ib.class_end) db = ws.desc[posb];
         if (is_interleaved(da)) da = Desc{};          // those candidates have a kernel of their own
         if (is_interleaved(db)) db = Desc{};
-        const bool same = pair && ia.sh == ib.sh &&
-                          __builtin_amdgcn_ballot_w64(((da.meta ^ db.meta) & 0xffff) != 0 || da.m != db.m) == 0;
-        if (same) {
+        if constexpr (GPIPE_PAIRS) {
+            // an even number of items per class and room for all of them: always two, side by side
             const Desc two[2] = {da, db};
-            simulate_items<2>(cl, ca, ws, ev, out, L, w, ia.sh, two, lane, park);
+            simulate_items<2, false, true>(cl, ca, ws, ev, out, L, oa.w, ia.sh, two, lane, park, xp);
         } else {
-            for (int q = 0; q < (pair ? 2 : 1); q++) {
-                const Desc one[1] = {q ? db : da};
-                simulate_items<1>(cl, ca, ws, ev, out, L, w + q, q ? ib.sh : ia.sh, one, lane, park);
+            const bool okA = oa.w < W, okB = pair && ob.w < W;
+            // simulated together when every lane sees the same shape (pp, m, schedule) in both,
+            // which neighbours in visiting order mostly do, else one after the other
+            const bool same = okA && okB && ob.w == oa.w + 1 && ia.sh == ib.sh &&
+                              __builtin_amdgcn_ballot_w64(((da.meta ^ db.meta) & 0xffff) != 0 || da.m != db.m) == 0;
+            if (same) {
+                const Desc two[2] = {da, db};
+                simulate_items<2>(cl, ca, ws, ev, out, L, oa.w, ia.sh, two, lane, park);
+            } else {
+                if (okA) {
+                    const Desc one[1] = {da};
+                    simulate_items<1>(cl, ca, ws, ev, out, L, oa.w, ia.sh, one, lane, park);
+                }
+                if (okB) {
+                    const Desc one[1] = {db};
+                    simulate_items<1>(cl, ca, ws, ev, out, L, ob.w, ib.sh, one, lane, park);
+                }
             }
         }
     }
+}
+
+__global__ __launch_bounds__(kSimBlock, 6) void k_simulate(CostsDev co, ClusterDev cl, CandDev ca, Workspace ws,
+                                                           EventsDev ev, SimOut out) {
+    // What only the epilogue needs is parked in LDS during the sweep (each lane its own slot),
+    // so that the sweep runs in few enough registers for six wavefronts per SIMD.
+    __shared__ Park park;
+    simulate_all<false>(co, cl, ca, ws, ev, out, park, nullptr);
+}
+
+__global__ __launch_bounds__(kSimBlock, 6) void k_simulate_gpipe(CostsDev co, ClusterDev cl, CandDev ca, Workspace ws,
+                                                                 EventsDev ev, SimOut out) {
+    __shared__ Park park;
+    __shared__ __align__(16) double regroup[kSimBlock / kWave][2 * kWave];     // 1 KB per wavefront
+    simulate_all<true>(co, cl, ca, ws, ev, out, park, regroup[threadIdx.x / kWave]);
 }
 
 // Same contract as k_simulate for p2p_blocking = 2 (sends queue on their link): one item per

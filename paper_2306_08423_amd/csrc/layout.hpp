@@ -18,6 +18,8 @@ enum {
     H_CLASS_START = 0,             // [kClasses+1] first sorted position of each class
     H_ITEM_START = 8,              // [kClasses+1] first wave-item of each class
     H_NUM_ITEMS = 16,              // total wave-items
+    H_GPIPE_ITEMS = 17,            // [kClasses] leading wave-items of each class that hold only GPipe candidates
+                                   //            (an even number; zero for the class of one lane per candidate)
     H_WORDS = 32
 };
 
