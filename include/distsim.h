@@ -74,7 +74,10 @@ extern "C" {
 
 typedef struct distsim_ctx distsim_ctx;   /* opaque; host-side state only (device id, error text, timers) */
 
-/* Create / destroy a context bound to HIP device `hip_device`.  Host memory only. */
+/* Create / destroy a context bound to HIP device `hip_device`.  Host memory only.
+ * One tuning knob is read from the environment here: DISTSIM_SPLIT_MIN_ITEMS, the number of
+ * 64-lane groups of stages from which distsim_simulate gives the GPipe candidates a launch of
+ * their own (default 98304; 0 = always).  Results do not depend on it. */
 int         distsim_create(distsim_ctx **out, int hip_device);
 void        distsim_destroy(distsim_ctx *ctx);
 /* Text of the last error on this context; valid until the next call on it. */

@@ -2,6 +2,7 @@
 #include <hip/hip_runtime.h>
 
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <string>
 #include <vector>
@@ -23,6 +24,7 @@ struct TimedLaunch {
 struct distsim_ctx {
     int device = 0;
     int num_cus = 256;
+    int64_t split_min_items = kSplitMinItems;   // lists of fewer wave-items go through k_simulate alone
     std::string err;
     bool timing = false;
     std::vector<TimedLaunch> rec[DISTSIM_K_COUNT];
@@ -99,9 +101,17 @@ int simulate_grid(const distsim_ctx* ctx, int64_t C) {
     return (int)(need < want ? (need < 1 ? 1 : need) : want);
 }
 
-// k_simulate and k_simulate_gpipe share the items: half the grid each (a wavefront strides over
-// its kernel's pairs, so any split of the items is covered)
-int queue_grid(const distsim_ctx* ctx, int64_t C) {
+// k_simulate: the whole grid for a list that it simulates alone, less for a list long enough to
+// be shared with k_simulate_gpipe (wavefronts stride over their kernel's pairs, so any split of
+// the items is covered by any grid)
+int general_grid(const distsim_ctx* ctx, int64_t C) {
+    const int g = simulate_grid(ctx, C);
+    return C >= ctx->split_min_items && g >= 2 ? g / 2 : g;
+}
+
+// k_simulate_gpipe takes at most the GPipe half of the items (a wavefront strides over its
+// kernel's pairs, so any split of the items is covered)
+int gpipe_grid(const distsim_ctx* ctx, int64_t C) {
     const int g = simulate_grid(ctx, C) / 2;
     return g < 1 ? 1 : g;
 }
@@ -126,6 +136,11 @@ int distsim_create(distsim_ctx** out, int hip_device) {
     hipDeviceProp_t prop;
     if (hipGetDeviceProperties(&prop, hip_device) == hipSuccess && prop.multiProcessorCount > 0)
         ctx->num_cus = prop.multiProcessorCount;
+    if (const char* e = getenv("DISTSIM_SPLIT_MIN_ITEMS")) {
+        char* end = nullptr;
+        const long long v = strtoll(e, &end, 10);
+        if (end != e && v >= 0) ctx->split_min_items = v;
+    }
     *out = ctx;
     return DISTSIM_OK;
 }
@@ -252,11 +267,14 @@ int distsim_simulate(distsim_ctx* ctx, const distsim_cluster* cluster, const dis
         if (cl.blocking == 2)
             hipLaunchKernelGGL(k_simulate_links, dim3(simulate_grid(ctx, C)), dim3(256), 0, st, co, cl, ca, ws, ev, out);
         else
-            hipLaunchKernelGGL(k_simulate, dim3(queue_grid(ctx, C)), dim3(256), 0, st, co, cl, ca, ws, ev, out);
+            hipLaunchKernelGGL(k_simulate, dim3(general_grid(ctx, C)), dim3(256), 0, st, co, cl, ca, ws, ev, out,
+                               ctx->split_min_items);
     }
-    if (cl.blocking != 2) {     // the pairs of GPipe items that k_simulate leaves out
+    if (cl.blocking != 2 && C >= ctx->split_min_items) {     // the pairs of GPipe items that k_simulate leaves out (none in a
+                                                       // list of fewer wave-items than that, and an item holds a candidate)
         Timer t(ctx, st, DISTSIM_K_SIMULATE_GPIPE);
-        hipLaunchKernelGGL(k_simulate_gpipe, dim3(queue_grid(ctx, C)), dim3(256), 0, st, co, cl, ca, ws, ev, out);
+        hipLaunchKernelGGL(k_simulate_gpipe, dim3(gpipe_grid(ctx, C)), dim3(256), 0, st, co, cl, ca, ws, ev, out,
+                           ctx->split_min_items);
     }
     if (cd->chunks) {       // candidates of the interleaved schedule, if the caller has any
         Timer t(ctx, st, DISTSIM_K_SIMULATE_VIRTUAL);

@@ -565,21 +565,23 @@ __device__ __forceinline__ void simulate_items(const ClusterDev& cl, const CandD
 // the grid (about one pair per wavefront for large lists: the hardware's dispatch order is the
 // load balancing, and the items of the widest class, the longest, go first).
 
+constexpr int64_t kSplitMinItems = 98304;      // default of the threshold below
+
 // Item number t of one launch's share -> its place in visiting order.
 struct OwnedItem {
     Item it;
     int64_t w;          // wave-item index (rows w * 64 .. of the per-stage arrays)
 };
-__device__ __forceinline__ OwnedItem owned_item(const int64_t* __restrict__ hdr, int64_t t, bool gpipe) {
+__device__ __forceinline__ OwnedItem owned_item(const int64_t* __restrict__ hdr, int64_t t, bool gpipe, bool split) {
     int k = 0;
     int64_t first = 0;                                  // first owned item of the class, relative to the class
     for (; k < kClasses - 1; k++) {
-        const int64_t n = hdr[H_ITEM_START + k + 1] - hdr[H_ITEM_START + k], g = hdr[H_GPIPE_ITEMS + k];
+        const int64_t n = hdr[H_ITEM_START + k + 1] - hdr[H_ITEM_START + k], g = split ? hdr[H_GPIPE_ITEMS + k] : 0;
         const int64_t mine = gpipe ? g : n - g;
         if (t < mine) break;
         t -= mine;
     }
-    first = gpipe ? 0 : hdr[H_GPIPE_ITEMS + k];
+    first = gpipe || !split ? 0 : hdr[H_GPIPE_ITEMS + k];
     OwnedItem o;
     o.w = hdr[H_ITEM_START + k] + first + t;
     o.it.sh = 6 - k;
@@ -591,15 +593,18 @@ __device__ __forceinline__ OwnedItem owned_item(const int64_t* __restrict__ hdr,
 template <bool GPIPE_PAIRS>
 __device__ __forceinline__ void simulate_all(const CostsDev& co, const ClusterDev& cl, const CandDev& ca,
                                              const Workspace& ws, const EventsDev& ev, const SimOut& out,
-                                             Park& park, double* xp) {
+                                             Park& park, double* xp, int64_t split_min_items) {
     const int lane = lane_id();
     const int64_t* __restrict__ hdr = ws.hdr;
     const int64_t wave0 = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / kWave;
     const int64_t nwaves = ((int64_t)gridDim.x * blockDim.x) / kWave;
     int64_t W = hdr[H_NUM_ITEMS];                       // items that have room in the per-stage arrays
     if (W * kWave > ev.stage_cap) W = ev.stage_cap / kWave;
+    // A short list is not worth two launches (two ramps and two tails on a machine that neither
+    // fills): below split_min_items wave-items k_simulate takes everything, GPipe pairs included.
+    const bool split = hdr[H_NUM_ITEMS] >= split_min_items;
     int64_t gp_items = 0;
-    for (int k = 0; k < kClasses; k++) gp_items += hdr[H_GPIPE_ITEMS + k];
+    for (int k = 0; k < kClasses; k++) gp_items += split ? hdr[H_GPIPE_ITEMS + k] : 0;
     int64_t mine = GPIPE_PAIRS ? gp_items : hdr[H_NUM_ITEMS] - gp_items;
     // items past the room in the per-stage arrays are skipped anyway
     if (mine > ev.stage_cap + kClasses) mine = ev.stage_cap + kClasses;
@@ -607,8 +612,8 @@ __device__ __forceinline__ void simulate_all(const CostsDev& co, const ClusterDe
     const int L = co.L;
     for (int64_t q = wave0; q < pairs; q += nwaves) {
         const bool pair = 2 * q + 1 < mine;
-        const OwnedItem oa = owned_item(hdr, 2 * q, GPIPE_PAIRS);
-        const OwnedItem ob = owned_item(hdr, pair ? 2 * q + 1 : 2 * q, GPIPE_PAIRS);
+        const OwnedItem oa = owned_item(hdr, 2 * q, GPIPE_PAIRS, split);
+        const OwnedItem ob = owned_item(hdr, pair ? 2 * q + 1 : 2 * q, GPIPE_PAIRS, split);
         const Item ia = oa.it, ib = ob.it;
         const int64_t posa = ia.pos0 + (lane >> ia.sh), posb = ib.pos0 + (lane >> ib.sh);
         Desc da{}, db{};
@@ -644,18 +649,18 @@ __device__ __forceinline__ void simulate_all(const CostsDev& co, const ClusterDe
 }
 
 __global__ __launch_bounds__(kSimBlock, 6) void k_simulate(CostsDev co, ClusterDev cl, CandDev ca, Workspace ws,
-                                                           EventsDev ev, SimOut out) {
+                                                           EventsDev ev, SimOut out, int64_t split_min_items) {
     // What only the epilogue needs is parked in LDS during the sweep (each lane its own slot),
     // so that the sweep runs in few enough registers for six wavefronts per SIMD.
     __shared__ Park park;
-    simulate_all<false>(co, cl, ca, ws, ev, out, park, nullptr);
+    simulate_all<false>(co, cl, ca, ws, ev, out, park, nullptr, split_min_items);
 }
 
 __global__ __launch_bounds__(kSimBlock, 6) void k_simulate_gpipe(CostsDev co, ClusterDev cl, CandDev ca, Workspace ws,
-                                                                 EventsDev ev, SimOut out) {
+                                                                 EventsDev ev, SimOut out, int64_t split_min_items) {
     __shared__ Park park;
     __shared__ __align__(16) double regroup[kSimBlock / kWave][2 * kWave];     // 1 KB per wavefront
-    simulate_all<true>(co, cl, ca, ws, ev, out, park, regroup[threadIdx.x / kWave]);
+    simulate_all<true>(co, cl, ca, ws, ev, out, park, regroup[threadIdx.x / kWave], split_min_items);
 }
 
 // Same contract as k_simulate for p2p_blocking = 2 (sends queue on their link): one item per

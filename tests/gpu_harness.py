@@ -17,9 +17,30 @@ def ctx():
     return _ctx
 
 
-def run_hip(w, stage_cap=None, util=True, search=None, table=True):
-    """search: None or (objective, weight ndarray or None)."""
-    c = ctx()
+_ctx_split = None
+
+
+def ctx_split():
+    """A context whose distsim_simulate gives GPipe candidates their own launch for any list length
+    (the default does so from about 10^5 wave-items on)."""
+    global _ctx_split
+    if _ctx_split is None:
+        import os
+        old = os.environ.get("DISTSIM_SPLIT_MIN_ITEMS")
+        os.environ["DISTSIM_SPLIT_MIN_ITEMS"] = "0"
+        try:
+            _ctx_split = ds.Context(0)
+        finally:
+            if old is None:
+                del os.environ["DISTSIM_SPLIT_MIN_ITEMS"]
+            else:
+                os.environ["DISTSIM_SPLIT_MIN_ITEMS"] = old
+    return _ctx_split
+
+
+def run_hip(w, stage_cap=None, util=True, search=None, table=True, split=False):
+    """search: None or (objective, weight ndarray or None).  split: through ctx_split()."""
+    c = ctx_split() if split else ctx()
     dw = ds.upload(w, c.device)
     cap = ds.stage_entries(w.cand["pp"]) if stage_cap is None else stage_cap
     ev = ds.alloc_events(c, dw.L, dw.V, dw.C, cap, table=table)

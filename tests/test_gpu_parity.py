@@ -31,6 +31,7 @@ def test_full_parity_small_configs(H, oracle_mod, name):
     ora = oracle_mod.simulate(w, nthreads=NT)
     H.assert_same(hip, ora, what=name)
     assert (hip["status"] == 0).all()
+    H.assert_same(H.run_hip(w, table=False, split=True), ora, what=name + ", GPipe launch")
 
 
 def test_tiny_golden_numbers(H):
@@ -418,11 +419,61 @@ def test_ragged_shapes_and_odd_stage_counts(H, oracle_mod):
         hip = H.run_hip(w)
         ora = oracle_mod.simulate(w, nthreads=NT)
         H.assert_same(hip, ora, what=f"ragged bucket={bucket}")
+        H.assert_same(H.run_hip(w, table=False, split=True), ora, what=f"ragged bucket={bucket}, GPipe launch")
         assert (ora["status"] == 0).sum() > 200
     # all-zero table
     z = mk_costs([0] * 8, [0] * 8)
     w = mk(z, mk_cluster(4), [(1, 1, 4, 3, 1, None), (2, 1, 2, 1, 0, None), (4, 1, 1, 9, 0, None)])
     H.assert_same(H.run_hip(w), oracle_mod.simulate(w), what="zeros")
+
+
+def test_gpipe_items_regrouped_two_stages_to_a_lane(H, oracle_mod):
+    """GPipe candidates are swept in pairs of wave-items with two stages to a lane (for long lists;
+    the harness's second context does so for any list).  Items of one
+    class that differ in pp and in m, odd numbers of GPipe items per class (the odd one goes the
+    usual way), odd pp (a lane with a single stage), m = 1, other schedules next to them, blocking
+    p2p, bucketed all-reduce, and per-stage arrays too small for all of them."""
+    _say("[case] GPipe pairs")
+    rng = np.random.default_rng(123)
+    L = 80
+    costs = mk_costs(rng.integers(0, 7000, (2, L)).tolist(), rng.integers(0, 9000, (2, L)).tolist(),
+                     fa=rng.integers(0, 400, (2, L)).tolist(), ba=rng.integers(0, 400, (2, L)).tolist(),
+                     act=(rng.integers(0, 200, (2, L)) * 128).tolist(), grad=rng.integers(0, 1 << 21, (2, L)).tolist(),
+                     tps=(1, 2))
+    N = 64 * 27 * 25 * 7 * 11
+    divs = [p for p in range(1, 65) if N % p == 0]
+    rows = []
+    for rep in range(1500):
+        pp = int(rng.choice(divs))
+        tp = int(rng.choice([1, 2])) if (N // pp) % 2 == 0 else 1
+        m = int(rng.choice([1, 2, 3, 5, 8, 13, 30, 31, 32, 33, 70]))
+        sc = int(rng.choice([0, 0, 0, 1, 2]))
+        bnd = None
+        if rng.random() < 0.5:
+            bnd = [0] + np.sort(rng.choice(np.arange(1, L), pp - 1, replace=False)).tolist() + [L]
+        rows.append((N // (pp * tp), tp, pp, m, sc, bnd))
+    for blocking, bucket in ((0, 0), (1, 0), (0, 1 << 19)):
+        w = mk(costs, mk_cluster(N, blocking=blocking, bucket=bucket), rows)
+        ora = oracle_mod.simulate(w, nthreads=NT)
+        assert ((ora["status"] == 0) & (w.cand["schedule"] == 0)).sum() > 700
+        H.assert_same(H.run_hip(w, table=False, split=True), ora, what=f"gpipe pairs blocking={blocking} bucket={bucket}")
+        H.assert_same(H.run_hip(w, table=False), ora, what=f"one launch blocking={blocking} bucket={bucket}")
+    H.assert_same(H.run_hip(w, split=True), ora, what="gpipe pairs with table")
+    _timeline_parity(H, oracle_mod, w, np.arange(0, w.C, 29))
+    # room for a part of the items only: the candidates that fit keep their results
+    full = H.run_hip(w, table=False, split=True)
+    need = int(full["stage_pos"].max()) + 64
+    for cap in (need // 2, need // 3 + 64, 640, 64):
+        part = H.run_hip(w, table=False, stage_cap=cap, split=True)
+        fit = part["status"] == 0
+        assert ((part["status"] == 3) | fit | (full["status"] != 0)).all() and fit.sum() > 0 and (part["status"] == 3).sum() > 0
+        assert np.array_equal(part["batch_ns"][fit], full["batch_ns"][fit])
+        assert np.array_equal(part["num_events"][fit], full["num_events"][fit])
+        rp, _ = H.rows_of(part, np.nonzero(fit)[0])
+        rf, _ = H.rows_of(full, np.nonzero(fit)[0])
+        assert np.array_equal(part["comp_busy_ns"][rp], full["comp_busy_ns"][rf])
+        assert np.array_equal(part["comm_busy_ns"][rp], full["comm_busy_ns"][rf])
+        assert (part["batch_ns"][part["status"] == 3] == INT64_MAX).all()
 
 
 def test_invalid_range_and_capacity_status(H, oracle_mod):
