@@ -476,6 +476,56 @@ def test_gpipe_items_regrouped_two_stages_to_a_lane(H, oracle_mod):
         assert (part["batch_ns"][part["status"] == 3] == INT64_MAX).all()
 
 
+def test_random_small_workloads(H, oracle_mod):
+    """Seeded random tables, clusters and candidate lists of every kind the interface takes (all four
+    schedules, the three p2p readings, buckets, several tensor-parallel variants, explicit and
+    uniform partitions, invalid candidates in between), through both ways of launching."""
+    _say("[case] random small workloads")
+    rng = np.random.default_rng(20230608)
+    for trial in range(24):
+        L = int(rng.integers(1, 130))
+        tps = [1] + sorted(rng.choice([2, 3, 4, 8], size=int(rng.integers(0, 3)), replace=False).tolist())
+        V = len(tps)
+        scale = int(rng.choice([1, 1000, 1 << 20, 1 << 34, 1 << 42]))
+        costs = mk_costs((rng.integers(0, 7, (V, L)) * scale).tolist(), (rng.integers(0, 9, (V, L)) * scale).tolist(),
+                         fa=(rng.integers(0, 3, (V, L)) * scale).tolist(), ba=(rng.integers(0, 3, (V, L)) * scale).tolist(),
+                         act=(rng.integers(0, 50, (V, L)) * int(rng.choice([1, 4096, 1 << 24]))).tolist(),
+                         grad=(rng.integers(0, 9, (V, L)) * int(rng.choice([1, 1 << 16, 1 << 26]))).tolist(),
+                         a2a=(rng.integers(0, 2, (V, L)) * 8192).tolist(), tps=tuple(tps))
+        N = int(rng.choice([1, 2, 6, 8, 24, 64, 360, 1024, 5040, 1 << 20]))
+        blocking = int(rng.integers(0, 3))
+        cl = mk_cluster(N, g=int(rng.choice([1, 2, 4, 8, 16])), alpha=(int(rng.integers(0, 9000)), int(rng.integers(0, 20000))),
+                        beta=(int(rng.integers(1, 400)), int(rng.integers(1, 60))),
+                        bucket=int(rng.choice([0, 0, 1 << 12, 1 << 22])), blocking=blocking)
+        rows = []
+        for _ in range(int(rng.integers(1, 260))):
+            if rng.random() < 0.85:                               # a factorisation of the cluster
+                pp = int(rng.choice([d for d in range(1, 65) if N % d == 0]))
+                tp = int(rng.choice([t for t in tps if (N // pp) % t == 0]))
+                dp = N // (pp * tp)
+            else:                                                 # anything: 5 is no variant, pp may exceed 64
+                tp, pp, dp = int(rng.choice(tps + [5])), int(rng.integers(1, 70)), int(rng.integers(1, 9))
+            m = int(rng.choice([1, 2, 3, 4, 7, 8, 16, 33, 100]))
+            sc = int(rng.choice([0, 0, 1, 1, 2, 3, 4]))
+            v = int(rng.integers(1, 4))
+            S = pp * v if sc == 3 else pp
+            bnd = None
+            if rng.random() < 0.5 and 1 <= S <= L:
+                bnd = [0] + np.sort(rng.choice(np.arange(1, L), S - 1, replace=False)).tolist() + [L]
+                if rng.random() < 0.05:
+                    bnd[int(rng.integers(0, len(bnd)))] = int(rng.integers(0, L + 1))      # most likely no partition any more
+            if sc == 3 and rng.random() < 0.7:
+                m = pp * int(rng.integers(1, 4))
+            rows.append((dp, tp, pp, m, sc, bnd, v))
+        w = mk(costs, cl, rows, name=f"random {trial}")
+        ora = oracle_mod.simulate(w, nthreads=NT)
+        H.assert_same(H.run_hip(w), ora, what=f"random {trial}")
+        H.assert_same(H.run_hip(w, table=False, split=True), ora, what=f"random {trial}, GPipe launch")
+        ok = np.nonzero(ora["status"] == 0)[0]
+        if len(ok):
+            _timeline_parity(H, oracle_mod, w, ok[:: max(1, len(ok) // 6)])
+
+
 def test_invalid_range_and_capacity_status(H, oracle_mod):
     _say("[case] status codes")
     costs = mk_costs([10] * 4, [20] * 4, tps=(1,))
