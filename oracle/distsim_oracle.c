@@ -621,6 +621,213 @@ static void simulate_interleaved(const costs_t *co, const cluster_t *cl,
     }
 }
 
+/* ---- explicit schedule (schedule 4) ------------------------------------------------------
+ * Algorithm 1 takes the pipeline schedule S as an input: which device runs which stage-task of
+ * which micro-batch, in which order (Sec. 4.3).  Here the caller supplies exactly that.  A
+ * schedule is a block of 32-bit words:
+ *   [0] pp devices  [1] S virtual stages  [2] m micro-batches  [3] nparts: parts of the layer
+ *   partition that the stages refer to  [4] replicas (the gradient all-reduce of a device spans
+ *   dp * replicas ranks)  [5 .. 5+pp] first task of every device's list and the task total
+ *   then S triples (device of the stage, its part, the stage before it in its pipeline or -1)
+ *   then the tasks, device after device: kind << 31 | stage << 16 | micro-batch.
+ * F(k, j) needs F(prev[k], j) and its p2p event; B(k, j) needs B(next[k], j) and its p2p event,
+ * or, on a stage without successor, its own F(k, j).  A device runs its list in order; a task
+ * starts when the device is free and its input has arrived.  One gradient all-reduce per device
+ * after its list, over the bytes of the parts of all stages it holds.  A schedule that cannot be
+ * run to its end (an input that never arrives) is invalid, as is any malformed block.
+ * Per-stage outputs are per device. */
+static void simulate_explicit(const costs_t *co, const cluster_t *cl,
+                              int32_t dp, int32_t tp, int32_t pp, int32_t m,
+                              const int32_t *w, int64_t nwords, const uint8_t *bnd_in,
+                              scratch_t *sc, result_t *res,
+                              int64_t *comp_busy, int64_t *comm_busy, double *util) {
+    const int L = co->L;
+    res->status = ST_INVALID;
+    res->batch_ns = INT64_MAX;
+    res->num_events = 0;
+    if (dp < 1 || tp < 1 || pp < 1 || pp > MAX_PP || m < 1 || m > MAX_M) return;
+    if ((int64_t)dp * tp * pp != cl->num_devices || cl->p2p_blocking == 2) return;
+    if (!w || nwords < 5 + pp + 1) return;
+    const int S = w[1], nparts = w[3], replicas = w[4];
+    if (w[0] != pp || w[2] != m || S < 1 || S > MAX_PP || nparts < 1 || nparts > MAX_PP || nparts > L || replicas < 1)
+        return;
+    const int32_t *dev_off = w + 5;
+    const int64_t ntask = dev_off[pp];
+    if (dev_off[0] != 0 || ntask < 0 || ntask > 2ll * S * m) return;
+    for (int d = 0; d < pp; d++) if (dev_off[d + 1] < dev_off[d]) return;
+    if (nwords != 5 + pp + 1 + 3ll * S + ntask) return;
+    const int32_t *st = dev_off + pp + 1, *tasks = st + 3 * S;
+    int place[64], part[64], prev[64], next[64];
+    for (int k = 0; k < S; k++) next[k] = -1;
+    for (int k = 0; k < S; k++) {
+        place[k] = st[3 * k]; part[k] = st[3 * k + 1]; prev[k] = st[3 * k + 2];
+        if (place[k] < 0 || place[k] >= pp || part[k] < 0 || part[k] >= nparts || prev[k] < -1 || prev[k] >= S || prev[k] == k)
+            return;
+    }
+    for (int k = 0; k < S; k++) if (prev[k] >= 0) { if (next[prev[k]] >= 0) return; next[prev[k]] = k; }
+    int v = -1;
+    for (int i = 0; i < co->V; i++) if (co->variant_tp[i] == tp) { v = i; break; }
+    if (v < 0) return;
+    int bnd[65];
+    if (bnd_in) {
+        for (int q = 0; q <= nparts; q++) bnd[q] = bnd_in[q];
+        if (bnd[0] != 0 || bnd[nparts] != L) return;
+        for (int q = 0; q < nparts; q++) if (bnd[q + 1] <= bnd[q]) return;
+    } else {
+        for (int q = 0; q <= nparts; q++) bnd[q] = (int)(((int64_t)q * L) / nparts);
+    }
+    /* every task once, on the device of its stage */
+    int64_t narr = (int64_t)S * m;
+    if (narr > sc->cap_arr) {
+        sc->cap_arr = narr;
+        sc->arrF = (uint8_t *)realloc(sc->arrF, (size_t)narr);
+        sc->arrB = (uint8_t *)realloc(sc->arrB, (size_t)narr);
+    }
+    uint8_t *seen = (uint8_t *)calloc((size_t)(2 * narr), 1);
+    int okl = 1;
+    for (int d = 0; d < pp && okl; d++)
+        for (int64_t i = dev_off[d]; i < dev_off[d + 1]; i++) {
+            uint32_t x = (uint32_t)tasks[i];
+            int kd = x >> 31, k = (x >> 16) & 0x7fff, j = x & 0xffff;
+            if (k >= S || j >= m || place[k] != d || seen[((int64_t)kd * S + k) * m + j]) { okl = 0; break; }
+            seen[((int64_t)kd * S + k) * m + j] = 1;
+        }
+    if (!okl) { free(seen); return; }
+
+    const int64_t *fc = co->fc + (int64_t)v * L, *bc = co->bc + (int64_t)v * L;
+    const int64_t *fa = co->fa + (int64_t)v * L, *ba = co->ba + (int64_t)v * L;
+    const int64_t *act = co->act + (int64_t)v * L, *grad = co->grad + (int64_t)v * L;
+    const int64_t *a2a = co->a2a + (int64_t)v * L;
+    /* p2p event on the edge prev[k] -> k, both directions: the activation that leaves prev[k] */
+    int64_t pf[64], pb[64];
+    const int64_t g = cl->gpus_per_node;
+    for (int k = 0; k < S; k++) { pf[k] = 0; pb[k] = 0; }
+    for (int k = 0; k < S; k++) if (prev[k] >= 0) {
+        int q = prev[k];
+        int64_t na = ((int64_t)place[q] * tp * dp) / g, nb = ((int64_t)place[k] * tp * dp) / g;
+        int64_t t = p2p_ns(cl, act[bnd[part[q] + 1] - 1], na == nb ? 0 : 1);
+        pf[q] = t;          /* sent by the forward task of prev[k] */
+        pb[k] = t;          /* sent by the backward task of k */
+    }
+    {
+        unsigned __int128 t1 = 0;
+        for (int k = 0; k < S; k++) {
+            for (int l = bnd[part[k]]; l < bnd[part[k] + 1]; l++) {
+                t1 += (unsigned __int128)(fc[l] + bc[l]);
+                if (tp > 1) t1 += (unsigned __int128)(fa[l] + ba[l]);
+                t1 += 2 * (unsigned __int128)alltoall_ns(cl, dp, a2a[l]);
+            }
+            t1 += (unsigned __int128)(pf[k] + pb[k]);
+        }
+        if (t1 * (unsigned __int128)m >= ((unsigned __int128)1 << 53)) { free(seen); res->status = ST_RANGE; return; }
+    }
+
+    memset(sc->arrF, 0, (size_t)narr);
+    memset(sc->arrB, 0, (size_t)narr);
+    uint8_t *doneF = seen;                 /* reused: forward task has ended */
+    memset(doneF, 0, (size_t)(2 * narr));
+    heap_t *h = &sc->heap;
+    h->n = 0; h->seq = 0;
+    int64_t nxt[64];
+    uint8_t busy[64];
+    int64_t cb[64], mb_[64];
+    for (int d = 0; d < pp; d++) { nxt[d] = dev_off[d]; busy[d] = 0; cb[d] = 0; mb_[d] = 0; }
+    int64_t nev = 0, now = 0, ran = 0;
+
+#define TRY_START_X(d_) do {                                                            \
+        int d__ = (d_);                                                                 \
+        if (!busy[d__] && nxt[d__] < dev_off[d__ + 1]) {                                \
+            uint32_t x = (uint32_t)tasks[nxt[d__]];                                     \
+            int kd = x >> 31, k = (x >> 16) & 0x7fff, j = x & 0xffff;                   \
+            int ready = kd == 0 ? (prev[k] < 0 || sc->arrF[(int64_t)k * m + j])         \
+                                : (next[k] < 0 ? doneF[(int64_t)k * m + j] : sc->arrB[(int64_t)k * m + j]); \
+            if (ready) {                                                                \
+                busy[d__] = 1;                                                          \
+                int64_t t = now;                                                        \
+                if (kd == 0) {                                                          \
+                    for (int l = bnd[part[k]]; l < bnd[part[k] + 1]; l++) {             \
+                        t += fc[l]; cb[d__] += fc[l];                                   \
+                        if (tp > 1) { t += fa[l]; mb_[d__] += fa[l]; }                  \
+                        int64_t y = alltoall_ns(cl, dp, a2a[l]);                        \
+                        t += y; mb_[d__] += y;                                          \
+                    }                                                                   \
+                } else {                                                                \
+                    for (int l = bnd[part[k] + 1] - 1; l >= bnd[part[k]]; l--) {        \
+                        t += bc[l]; cb[d__] += bc[l];                                   \
+                        if (tp > 1) { t += ba[l]; mb_[d__] += ba[l]; }                  \
+                        int64_t y = alltoall_ns(cl, dp, a2a[l]);                        \
+                        t += y; mb_[d__] += y;                                          \
+                    }                                                                   \
+                }                                                                       \
+                if (cl->p2p_blocking == 1) {                                            \
+                    if (kd == 0 && next[k] >= 0) t += pf[k];                            \
+                    if (kd == 1 && prev[k] >= 0) t += pb[k];                            \
+                }                                                                       \
+                heap_push(h, t, EV_TASK_DONE, k, j, kd);                                \
+            }                                                                           \
+        }                                                                               \
+    } while (0)
+
+    for (int d = 0; d < pp; d++) TRY_START_X(d);
+    while (h->n > 0) {
+        event_t e = heap_pop(h);
+        now = e.t;
+        int k = e.stage, d = place[k];
+        switch (e.kind) {
+        case EV_TASK_DONE: {
+            int kd = e.layer, j = e.mb;
+            nev++; ran++;
+            busy[d] = 0;
+            nxt[d]++;
+            if (kd == 0) {
+                doneF[(int64_t)k * m + j] = 1;
+                if (next[k] >= 0) {
+                    heap_push(h, now + (cl->p2p_blocking == 1 ? 0 : pf[k]), EV_ARRIVE_F, next[k], j, 0);
+                    mb_[d] += pf[k]; nev++;
+                }
+            } else if (prev[k] >= 0) {
+                heap_push(h, now + (cl->p2p_blocking == 1 ? 0 : pb[k]), EV_ARRIVE_B, prev[k], j, 0);
+                mb_[d] += pb[k]; nev++;
+            }
+            if (nxt[d] == dev_off[d + 1] && (int64_t)dp * replicas > 1) {      /* the device's gradient all-reduce */
+                int64_t G = 0;
+                for (int q = 0; q < S; q++) if (place[q] == d)
+                    for (int l = bnd[part[q]]; l < bnd[part[q] + 1]; l++) G += grad[l];
+                if (G > 0) {
+                    int64_t dd = allreduce_ns(cl, (int64_t)dp * replicas, G);
+                    heap_push(h, now + dd, EV_AR_DONE, k, 0, 0);
+                    mb_[d] += dd;
+                }
+            }
+            TRY_START_X(d);
+            break;
+        }
+        case EV_ARRIVE_F:
+            sc->arrF[(int64_t)k * m + e.mb] = 1;
+            TRY_START_X(d);
+            break;
+        case EV_ARRIVE_B:
+            sc->arrB[(int64_t)k * m + e.mb] = 1;
+            TRY_START_X(d);
+            break;
+        case EV_AR_DONE:
+            nev++;
+            break;
+        }
+    }
+#undef TRY_START_X
+    free(seen);
+    if (ran != ntask) return;                  /* some list could not be run to its end */
+    res->status = ST_OK;
+    res->batch_ns = now;
+    res->num_events = nev;
+    for (int d = 0; d < pp; d++) {
+        if (comp_busy) comp_busy[d] = cb[d];
+        if (comm_busy) comm_busy[d] = mb_[d];
+        if (util) util[d] = now > 0 ? (double)cb[d] / (double)now : 0.0;
+    }
+}
+
 /* Per-candidate outputs: status, batch_ns, num_events [C]; stage_off [C+1] is written here
  * (exclusive prefix of pp over candidates with status 0); comp/comm/util are ragged
  * arrays indexed stage_off[c] + s and must hold sum(pp) entries. */
@@ -632,6 +839,7 @@ int oracle_simulate(int32_t L, int32_t V, const int32_t *variant_tp,
                     int64_t C, const int32_t *dp, const int32_t *tp, const int32_t *pp, const int32_t *m,
                     const uint8_t *schedule, const int32_t *chunks /* or NULL */, const int64_t *part_off,
                     const uint8_t *part_pool,
+                    int64_t n_sched, const int64_t *sched_off /* [n_sched+1] or NULL */, const int32_t *sched_words,
                     int32_t *status, int64_t *batch_ns, int64_t *num_events, int64_t *stage_off,
                     int64_t *comp_busy, int64_t *comm_busy, double *util,
                     int64_t *tl_start, int64_t *tl_end, int64_t *tl_ar, int32_t nthreads) {
@@ -655,7 +863,17 @@ int oracle_simulate(int32_t L, int32_t V, const int32_t *variant_tp,
             if (p >= 1 && p <= MAX_PP) buf = (int64_t *)malloc((size_t)p * 3 * sizeof(int64_t));
             result_t r;
             const uint8_t *b = part_off[c] >= 0 ? part_pool + part_off[c] : NULL;
-            if (schedule[c] == 3)
+            if (schedule[c] == 4) {
+                const int32_t *blk = NULL;
+                int64_t nw = 0;
+                if (chunks && sched_off && sched_words && chunks[c] >= 0 && chunks[c] < n_sched &&
+                    sched_off[chunks[c] + 1] >= sched_off[chunks[c]]) {
+                    blk = sched_words + sched_off[chunks[c]];
+                    nw = sched_off[chunks[c] + 1] - sched_off[chunks[c]];
+                }
+                simulate_explicit(&co, &cl, dp[c], tp[c], p, m[c], blk, nw, b, &sc, &r,
+                                  buf, buf ? buf + p : NULL, buf ? (double *)(buf + 2 * p) : NULL);
+            } else if (schedule[c] == 3)
                 simulate_interleaved(&co, &cl, dp[c], tp[c], p, m[c], chunks ? chunks[c] : 0 /* no chunk counts: invalid */, b, &sc, &r,
                                      buf, buf ? buf + p : NULL, buf ? (double *)(buf + 2 * p) : NULL,
                                      C == 1 ? tl_start : NULL, C == 1 ? tl_end : NULL, C == 1 ? tl_ar : NULL);
