@@ -58,6 +58,31 @@ extern "C" {
                                   then forward / backward in turn, then the backwards left.
                                   One trailing gradient all-reduce per device (no buckets).
                                   Per-stage outputs are per device; no stage table.            */
+#define DISTSIM_EXPLICIT 4     /* the schedule S of Algorithm 1 given by the caller (Sec. 4.3: which device
+                                  runs which stage-task of which micro-batch, in which order; Sec. 7: a
+                                  new pipeline algorithm enters through its schedule).  chunks[c] names
+                                  one of the schedules in distsim_candidates.schedule_words, a block of
+                                  32-bit words:
+                                    [0] pp  [1] S virtual stages (<= 64)  [2] m  [3] nparts: parts of the
+                                    layer partition the stages refer to (<= min(64, L); part_pool then
+                                    holds nparts + 1 boundaries)  [4] replicas >= 1: a device's gradient
+                                    all-reduce spans dp * replicas ranks
+                                    [5 .. 5+pp] first task of each device's list, then the task total
+                                    S triples: device of the stage, its part, the stage before it in
+                                    its pipeline (-1: none; at most one stage after any stage)
+                                    the tasks, device after device: kind << 31 | stage << 16 |
+                                    micro-batch, kind 0 = forward; each at most once, on the device of
+                                    its stage.
+                                  F(k, j) needs F(prev k, j) and its p2p event (the activation leaving
+                                  prev k's part; link class by the nodes of the two devices); B(k, j)
+                                  needs B(next k, j) and its p2p event, or on a stage without successor
+                                  its own F(k, j).  A device runs its list in order.  One gradient
+                                  all-reduce per device after its list, over the bytes of the parts of
+                                  all its stages.  pp and m must equal the candidate's, S * m <=
+                                  DISTSIM_MAX_SLOTS, p2p_blocking != 2.  A schedule that cannot be run
+                                  to its end is invalid, as is a malformed block.  Per-stage outputs
+                                  are per device; no stage table, no timeline.                    */
+#define DISTSIM_MAX_SLOTS 2048 /* (virtual stage, micro-batch) pairs of an explicit schedule       */
 #define DISTSIM_1F1B_ASYNC 2   /* asynchronous pipeline (Sec. 7, discussion of new algorithms):
                                   the Dapple order without the global synchronisation event, i.e.
                                   no gradient all-reduce event is appended to the device lists   */
@@ -137,14 +162,19 @@ typedef struct {
  * Struct of arrays, device pointers, C entries each. */
 typedef struct {
     const int32_t *dp, *tp, *pp, *m;
-    const uint8_t *schedule;         /* DISTSIM_GPIPE / _1F1B / _1F1B_ASYNC / _INTERLEAVED        */
+    const uint8_t *schedule;         /* DISTSIM_GPIPE / _1F1B / _1F1B_ASYNC / _INTERLEAVED / _EXPLICIT */
     const int64_t *part_off;         /* -1: uniform split, stage s owns layers [s L / pp, (s+1) L / pp);
                                         else offset into part_pool of b0..bpp                    */
     const uint8_t *part_pool;        /* concatenated boundaries; may be NULL if never referenced  */
     int64_t part_pool_len;           /* entries in part_pool (offsets beyond it => invalid)       */
-    const int32_t *chunks;           /* model chunks per device of DISTSIM_INTERLEAVED candidates
-                                        (ignored for the other schedules); NULL = the list has no
-                                        such candidate (one that is there anyway is invalid)       */
+    const int32_t *chunks;           /* model chunks per device of DISTSIM_INTERLEAVED candidates,
+                                        index of its schedule for DISTSIM_EXPLICIT ones (ignored for
+                                        the other schedules); NULL = the list has no such
+                                        candidate (one that is there anyway is invalid)            */
+    int64_t n_schedules;             /* explicit schedules (see DISTSIM_EXPLICIT); 0 = none        */
+    const int64_t *schedule_off;     /* [n_schedules + 1] device: first word of each schedule      */
+    const int32_t *schedule_words;   /* device                                                     */
+    int64_t schedule_words_len;      /* words in schedule_words (a schedule beyond it => invalid)  */
 } distsim_candidates;
 
 /* Columns of distsim_events.stage_tab: per pipeline stage of a candidate */
@@ -325,7 +355,7 @@ enum {
     DISTSIM_K_LAYER_TABLES = 0, DISTSIM_K_DECODE, DISTSIM_K_BINS, DISTSIM_K_SCATTER,
     DISTSIM_K_STAGE_EVENTS, DISTSIM_K_SIM_INIT, DISTSIM_K_SIMULATE, DISTSIM_K_SEARCH, DISTSIM_K_TIMELINE,
     DISTSIM_K_DEDUP, DISTSIM_K_COMM_TIMES, DISTSIM_K_BUBBLES, DISTSIM_K_SIMULATE_VIRTUAL,
-    DISTSIM_K_TIMELINE_VIRTUAL, DISTSIM_K_SIMULATE_GPIPE, DISTSIM_K_COUNT
+    DISTSIM_K_TIMELINE_VIRTUAL, DISTSIM_K_SIMULATE_GPIPE, DISTSIM_K_SIMULATE_EXPLICIT, DISTSIM_K_COUNT
 };
 int distsim_timing_enable(distsim_ctx *ctx, int on);
 int distsim_timing_read(distsim_ctx *ctx, int kernel, double *total_ms, int64_t *launches);

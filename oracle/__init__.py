@@ -75,6 +75,7 @@ def simulate(w, nthreads: int = 1, timeline: bool = False) -> Dict[str, np.ndarr
     xoff = _c(ca["schedule_off"], np.int64) if ca.get("schedule_off") is not None else None
     xwords = _c(ca["schedule_words"], np.int32) if ca.get("schedule_words") is not None else None
     xn = (xoff.shape[0] - 1) if xoff is not None else 0
+    xlen = int(xwords.size) if xwords is not None else 0
     if xwords is not None and xwords.size == 0:
         xwords = np.zeros(1, np.int32)
     if pool.size == 0:
@@ -100,7 +101,7 @@ def simulate(w, nthreads: int = 1, timeline: bool = False) -> Dict[str, np.ndarr
         ctypes.c_int32(int(cl["num_devices"])), ctypes.c_int32(int(cl["gpus_per_node"])),
         _p(alpha), _p(beta), ctypes.c_int64(int(cl["dp_bucket_bytes"])), ctypes.c_int32(int(cl.get("p2p_blocking", 0))),
         ctypes.c_int64(C), _p(dp), _p(tp), _p(pp), _p(m), _p(sched), _p(chunks), _p(poff), _p(pool),
-        ctypes.c_int64(xn), _p(xoff), _p(xwords),
+        ctypes.c_int64(xn), _p(xoff), _p(xwords), ctypes.c_int64(xlen),
         _p(status), _p(batch), _p(nev), _p(soff), _p(comp), _p(comm), _p(util),
         _p(tls), _p(tle), _p(tar), ctypes.c_int32(int(nthreads)))
     if rc != 0:

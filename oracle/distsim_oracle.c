@@ -67,6 +67,7 @@
 #define ST_RANGE 2
 #define MAX_PP 64        /* interface limits of the evaluated library: a candidate beyond */
 #define MAX_M (1 << 16)  /* them is reported invalid                                      */
+#define MAX_SLOTS 2048   /* (virtual stage, micro-batch) pairs of an explicit schedule    */
 
 enum { EV_TASK_DONE = 0, EV_ARRIVE_F = 1, EV_ARRIVE_B = 2, EV_GRAD_READY = 3, EV_AR_DONE = 4 };
 
@@ -651,6 +652,7 @@ static void simulate_explicit(const costs_t *co, const cluster_t *cl,
     const int S = w[1], nparts = w[3], replicas = w[4];
     if (w[0] != pp || w[2] != m || S < 1 || S > MAX_PP || nparts < 1 || nparts > MAX_PP || nparts > L || replicas < 1)
         return;
+    if ((int64_t)S * m > MAX_SLOTS) return;
     const int32_t *dev_off = w + 5;
     const int64_t ntask = dev_off[pp];
     if (dev_off[0] != 0 || ntask < 0 || ntask > 2ll * S * m) return;
@@ -840,6 +842,7 @@ int oracle_simulate(int32_t L, int32_t V, const int32_t *variant_tp,
                     const uint8_t *schedule, const int32_t *chunks /* or NULL */, const int64_t *part_off,
                     const uint8_t *part_pool,
                     int64_t n_sched, const int64_t *sched_off /* [n_sched+1] or NULL */, const int32_t *sched_words,
+                    int64_t sched_words_len,
                     int32_t *status, int64_t *batch_ns, int64_t *num_events, int64_t *stage_off,
                     int64_t *comp_busy, int64_t *comm_busy, double *util,
                     int64_t *tl_start, int64_t *tl_end, int64_t *tl_ar, int32_t nthreads) {
@@ -867,7 +870,8 @@ int oracle_simulate(int32_t L, int32_t V, const int32_t *variant_tp,
                 const int32_t *blk = NULL;
                 int64_t nw = 0;
                 if (chunks && sched_off && sched_words && chunks[c] >= 0 && chunks[c] < n_sched &&
-                    sched_off[chunks[c] + 1] >= sched_off[chunks[c]]) {
+                    sched_off[chunks[c]] >= 0 && sched_off[chunks[c] + 1] >= sched_off[chunks[c]] &&
+                    sched_off[chunks[c] + 1] <= sched_words_len) {
                     blk = sched_words + sched_off[chunks[c]];
                     nw = sched_off[chunks[c] + 1] - sched_off[chunks[c]];
                 }

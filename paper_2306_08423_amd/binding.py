@@ -27,7 +27,7 @@ NCOLS = 8
 COL = {"FC": 0, "FA": 1, "BC": 2, "BA": 3, "PF": 4, "PB": 5, "G": 6, "AR": 7}
 KERNELS = ("k_layer_tables", "k_decode", "k_bins", "k_scatter", "k_stage_events",
            "k_sim_init", "k_simulate", "k_search", "k_timeline", "k_dedup", "k_comm_event_times", "k_bubbles", "k_simulate_virtual",
-           "k_timeline_virtual", "k_simulate_gpipe")
+           "k_timeline_virtual", "k_simulate_gpipe", "k_simulate_explicit")
 INT64_MAX = (1 << 63) - 1
 
 
@@ -47,7 +47,9 @@ class _Cluster(C.Structure):
 class _Cand(C.Structure):
     _fields_ = [("dp", C.c_void_p), ("tp", C.c_void_p), ("pp", C.c_void_p), ("m", C.c_void_p),
                 ("schedule", C.c_void_p), ("part_off", C.c_void_p), ("part_pool", C.c_void_p),
-                ("part_pool_len", C.c_int64), ("chunks", C.c_void_p)]
+                ("part_pool_len", C.c_int64), ("chunks", C.c_void_p),
+                ("n_schedules", C.c_int64), ("schedule_off", C.c_void_p), ("schedule_words", C.c_void_p),
+                ("schedule_words_len", C.c_int64)]
 
 
 class _Events(C.Structure):
@@ -184,8 +186,12 @@ class DeviceWorkload:
     def cand_struct(self) -> _Cand:
         k = self.cand
         pool = k["part_pool"]
+        soff, swords = k.get("schedule_off"), k.get("schedule_words")
+        nsched = int(soff.numel()) - 1 if soff is not None and swords is not None and swords.numel() else 0
         return _Cand(_ptr(k["dp"]), _ptr(k["tp"]), _ptr(k["pp"]), _ptr(k["m"]), _ptr(k["schedule"]),
-                     _ptr(k["part_off"]), _ptr(pool) if pool.numel() else None, pool.numel(), _ptr(k.get("chunks")))
+                     _ptr(k["part_off"]), _ptr(pool) if pool.numel() else None, pool.numel(), _ptr(k.get("chunks")),
+                     max(nsched, 0), _ptr(soff) if nsched > 0 else None, _ptr(swords) if nsched > 0 else None,
+                     int(swords.numel()) if nsched > 0 else 0)
 
 
 def cluster_struct(cl) -> _Cluster:

@@ -11,6 +11,7 @@
 #include "kernels_build.hpp"
 #include "kernels_ingest.hpp"
 #include "kernels_search.hpp"
+#include "kernels_explicit.hpp"
 #include "kernels_simulate.hpp"
 #include "kernels_timeline.hpp"
 #include "kernels_virtual.hpp"
@@ -35,7 +36,7 @@ static const char* kKernelNames[DISTSIM_K_COUNT] = {
     "k_layer_tables", "k_decode", "k_bins", "k_scatter",
     "k_stage_events", "k_sim_init", "k_simulate", "k_search", "k_timeline",
     "k_dedup", "k_comm_event_times", "k_bubbles", "k_simulate_virtual",
-    "k_timeline_virtual", "k_simulate_gpipe",
+    "k_timeline_virtual", "k_simulate_gpipe", "k_simulate_explicit",
 };
 
 static int fail(distsim_ctx* ctx, int code, const std::string& msg) {
@@ -190,7 +191,9 @@ int distsim_build_events(distsim_ctx* ctx, const distsim_costs* costs, const dis
                 costs->bwd_comm_ns, costs->act_bytes, costs->grad_bytes, costs->a2a_bytes};
     const ClusterDev cl = to_dev(*cluster);
     CandDev ca{cand->dp, cand->tp, cand->pp, cand->m, cand->schedule, cand->part_off, cand->part_pool,
-               cand->part_pool ? cand->part_pool_len : 0, cand->chunks};
+               cand->part_pool ? cand->part_pool_len : 0, cand->chunks,
+               cand->schedule_off && cand->schedule_words ? cand->n_schedules : 0, cand->schedule_off,
+               cand->schedule_words, cand->schedule_words_len};
     EventsDev ev{out->stage_cap, out->status, out->stage_pos, out->stage_tab, out->stage_layers, out->num_events};
     out->L = costs->L;
     out->V = costs->V;
@@ -253,7 +256,9 @@ int distsim_simulate(distsim_ctx* ctx, const distsim_cluster* cluster, const dis
     CostsDev co{cs->L, cs->V, cs->variant_tp, cs->fwd_comp_ns, cs->bwd_comp_ns, cs->fwd_comm_ns, cs->bwd_comm_ns,
                 cs->act_bytes, cs->grad_bytes, cs->a2a_bytes};
     CandDev ca{cd->dp, cd->tp, cd->pp, cd->m, cd->schedule, cd->part_off, cd->part_pool,
-               cd->part_pool ? cd->part_pool_len : 0, cd->chunks};
+               cd->part_pool ? cd->part_pool_len : 0, cd->chunks,
+               cd->schedule_off && cd->schedule_words ? cd->n_schedules : 0, cd->schedule_off, cd->schedule_words,
+               cd->schedule_words_len};
     const ClusterDev cl = to_dev(*cluster);
     EventsDev ev{events->stage_cap, events->status, events->stage_pos, events->stage_tab, events->stage_layers,
                  events->num_events};
@@ -280,6 +285,11 @@ int distsim_simulate(distsim_ctx* ctx, const distsim_cluster* cluster, const dis
         Timer t(ctx, st, DISTSIM_K_SIMULATE_VIRTUAL);
         const int64_t blocks = C < (int64_t)ctx->num_cus * 16 ? C : (int64_t)ctx->num_cus * 16;
         hipLaunchKernelGGL(k_simulate_virtual, dim3((unsigned)blocks), dim3(kWave), 0, st, co, cl, ca, ws, ev, out, C);
+    }
+    if (cd->chunks && ca.n_schedules > 0) {       // candidates with an explicit schedule, if the caller has any
+        Timer t(ctx, st, DISTSIM_K_SIMULATE_EXPLICIT);
+        const int64_t blocks = C < (int64_t)ctx->num_cus * 16 ? C : (int64_t)ctx->num_cus * 16;
+        hipLaunchKernelGGL(k_simulate_explicit, dim3((unsigned)blocks), dim3(kWave), 0, st, co, cl, ca, ws, ev, out, C);
     }
     HIP_TRY(hipGetLastError());
     return DISTSIM_OK;
@@ -308,7 +318,9 @@ int distsim_timeline(distsim_ctx* ctx, const distsim_cluster* cluster, const dis
     CostsDev co{cs->L, cs->V, cs->variant_tp, cs->fwd_comp_ns, cs->bwd_comp_ns, cs->fwd_comm_ns, cs->bwd_comm_ns,
                 cs->act_bytes, cs->grad_bytes, cs->a2a_bytes};
     CandDev ca{cd->dp, cd->tp, cd->pp, cd->m, cd->schedule, cd->part_off, cd->part_pool,
-               cd->part_pool ? cd->part_pool_len : 0, cd->chunks};
+               cd->part_pool ? cd->part_pool_len : 0, cd->chunks,
+               cd->schedule_off && cd->schedule_words ? cd->n_schedules : 0, cd->schedule_off, cd->schedule_words,
+               cd->schedule_words_len};
     TimelineOut out{sel, task_off, start_ns, end_ns, ar_start_ns, ar_end_ns};
     {
         Timer t(ctx, st, DISTSIM_K_TIMELINE);
@@ -370,7 +382,9 @@ int distsim_bubbles(distsim_ctx* ctx, const distsim_events* events, int64_t n, c
     HIP_TRY(hipSetDevice(ctx->device));
     hipStream_t st = (hipStream_t)hip_stream;
     CandDev ca{cd->dp, cd->tp, cd->pp, cd->m, cd->schedule, cd->part_off, cd->part_pool,
-               cd->part_pool ? cd->part_pool_len : 0, cd->chunks};
+               cd->part_pool ? cd->part_pool_len : 0, cd->chunks,
+               cd->schedule_off && cd->schedule_words ? cd->n_schedules : 0, cd->schedule_off, cd->schedule_words,
+               cd->schedule_words_len};
     {
         Timer t(ctx, st, DISTSIM_K_BUBBLES);
         hipLaunchKernelGGL(k_bubbles, dim3((unsigned)n), dim3(256), 0, st, ca, events->status, events->num_candidates,

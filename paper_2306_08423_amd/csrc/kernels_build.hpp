@@ -18,7 +18,11 @@ struct CandDev {
     const int64_t* part_off;
     const uint8_t* part_pool;
     int64_t part_pool_len;
-    const int32_t* chunks;         // model chunks per device (interleaved schedule), may be null
+    const int32_t* chunks;         // model chunks per device (interleaved schedule) / index of the explicit schedule; may be null
+    int64_t n_schedules;           // explicit schedules
+    const int64_t* schedule_off;   // [n_schedules + 1]
+    const int32_t* schedule_words;
+    int64_t schedule_words_len;
 };
 
 struct EventsDev {
@@ -40,6 +44,9 @@ struct Item {
 // Candidates of the interleaved schedule keep their place in the visiting order (their per-stage
 // rows are per device) but are simulated by k_simulate_virtual; the other sweeps see them as empty.
 __device__ __forceinline__ bool is_interleaved(const Desc& d) { return ((d.meta >> 8) & 0xff) == 3; }
+// ... and the explicit schedules (k_simulate_explicit); either kind is skipped by the level sweeps.
+__device__ __forceinline__ bool is_explicit(const Desc& d) { return ((d.meta >> 8) & 0xff) == 4; }
+__device__ __forceinline__ bool has_own_kernel(const Desc& d) { return ((d.meta >> 8) & 0xff) >= 3; }
 
 __device__ __forceinline__ Item decode_item(const int64_t* __restrict__ hdr, int64_t w) {
     int k = 0;
@@ -148,13 +155,27 @@ __global__ __launch_bounds__(kDecodeBlock) void k_decode(CostsDev co, ClusterDev
         const int32_t dp = ca.dp[c], tp = ca.tp[c], pp = ca.pp[c], m = ca.m[c];
         const int sched = ca.schedule[c];
         const int64_t poff = ca.part_off[c];
-        bool ok = dp >= 1 && tp >= 1 && pp >= 1 && m >= 1 && m <= kMaxM && sched <= 3 && pp <= co.L && pp <= kMaxPP;
+        bool ok = dp >= 1 && tp >= 1 && pp >= 1 && m >= 1 && m <= kMaxM && sched <= 4 && pp <= co.L && pp <= kMaxPP;
         ok = ok && (int64_t)dp * tp * pp == (int64_t)cl.num_devices;
         int64_t parts = pp;                      // parts of the layer partition
         if (ok && sched == 3) {                  // interleaved: pp * chunks virtual stages
             const int64_t vch = ca.chunks ? ca.chunks[c] : 0;      // no chunk counts: invalid
             parts = (int64_t)pp * vch;
             ok = vch >= 1 && parts <= kMaxPP && parts <= co.L && m % pp == 0 && cl.blocking != 2;
+        }
+        if (ok && sched == 4) {                  // explicit: the head of its schedule block; the kernel checks the rest
+            const int64_t id = ca.chunks ? ca.chunks[c] : -1;
+            ok = id >= 0 && id < ca.n_schedules && ca.schedule_off && ca.schedule_words && cl.blocking != 2;
+            if (ok) {
+                const int64_t o = ca.schedule_off[id], n = ca.schedule_off[id + 1] - o;
+                ok = o >= 0 && n >= 5 + pp + 1 && o + n <= ca.schedule_words_len;
+                if (ok) {
+                    const int32_t* w = ca.schedule_words + o;
+                    parts = w[3];
+                    ok = w[0] == pp && w[2] == m && w[1] >= 1 && w[1] <= kMaxPP && parts >= 1 && parts <= kMaxPP &&
+                         parts <= co.L && w[4] >= 1 && (int64_t)w[1] * m <= kMaxSlots;
+                }
+            }
         }
         ok = ok && (poff == -1 || (poff >= 0 && ca.part_pool != nullptr && poff + parts + 1 <= ca.part_pool_len));
         int v = -1;
@@ -397,7 +418,7 @@ __device__ __forceinline__ void stage_fetch_desc(const Workspace& ws, const int6
     x.pos = it.pos0 + (lane >> it.sh);
     x.d = Desc{};
     if (x.pos < it.class_end) x.d = ws.desc[x.pos];
-    if (is_interleaved(x.d)) x.d = Desc{};
+    if (has_own_kernel(x.d)) x.d = Desc{};
 }
 
 __device__ __forceinline__ void stage_fetch_bounds(const CandDev& ca, int L, StageWork& x) {

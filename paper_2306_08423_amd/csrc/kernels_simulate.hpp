@@ -619,8 +619,8 @@ __device__ __forceinline__ void simulate_all(const CostsDev& co, const ClusterDe
         Desc da{}, db{};
         if (posa < ia.class_end) da = ws.desc[posa];
         if (pair && posb < ib.class_end) db = ws.desc[posb];
-        if (is_interleaved(da)) da = Desc{};          // those candidates have a kernel of their own
-        if (is_interleaved(db)) db = Desc{};
+        if (has_own_kernel(da)) da = Desc{};          // those candidates have a kernel of their own
+        if (has_own_kernel(db)) db = Desc{};
         if constexpr (GPIPE_PAIRS) {
             // an even number of items per class and room for all of them: always two, side by side
             const Desc two[2] = {da, db};
@@ -678,7 +678,7 @@ __global__ __launch_bounds__(kSimBlock) void k_simulate_links(CostsDev co, Clust
         const int64_t pos = it.pos0 + (lane >> it.sh);
         Desc d{};
         if (pos < it.class_end) d = ws.desc[pos];
-        if (is_interleaved(d)) d = Desc{};
+        if (has_own_kernel(d)) d = Desc{};
         const Desc one[1] = {d};
         simulate_items<1, true>(cl, ca, ws, ev, out, co.L, w, it.sh, one, lane, park);
     }

@@ -75,7 +75,7 @@ __global__ __launch_bounds__(kTlWaves * kWave) void k_timeline(CostsDev co, Clus
         int k = -1;
         if (lane < kTlChunk && q < n) {
             const int64_t c = out.sel[q];
-            if (c >= 0 && c < C && status[c] == 0 && ca.schedule[c] != 3) {      // no dump for the interleaved schedule
+            if (c >= 0 && c < C && status[c] == 0 && ca.schedule[c] < 3) {       // the interleaved schedule has a dump of its own, explicit ones none
                 const int pp = ca.pp[c];
                 int sh = 0;
                 while ((1 << sh) < pp) sh++;
@@ -297,6 +297,7 @@ __global__ __launch_bounds__(256) void k_bubbles(CandDev ca, const int32_t* __re
     if (c < 0 || c >= C || status[c] != 0) return;
     const int pp = ca.pp[c], m = ca.m[c], sched = ca.schedule[c];
     const int64_t off = task_off[q];
+    if (sched > 3) return;
     if (sched == 3) {
         // Interleaved: device d = k mod pp runs slots, not micro-batches, in the Dapple order with
         // W warm-up forwards.  Slot i of a direction <-> (chunk, micro-batch) and slot <-> position

@@ -7,6 +7,7 @@ namespace distsim {
 
 constexpr int kMaxPP = 64;
 constexpr int kMaxM = 1 << 16;
+constexpr int kMaxSlots = 2048;             // (virtual stage, micro-batch) pairs of an explicit schedule
 constexpr int kClasses = 7;                 // lanes per candidate: 64, 32, 16, 8, 4, 2, 1
 constexpr int kMBins = 1024;                // micro-batch count is clamped to this for ordering only
 constexpr int kBinsPerClass = 2 * kMBins;   // schedule x m

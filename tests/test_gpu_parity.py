@@ -254,7 +254,7 @@ def test_async_schedule(H, oracle_mod):
     sel = np.nonzero(cand["schedule"] == 2)[0][::40]
     _timeline_parity(H, oracle_mod, w, sel)
     # an unknown schedule is an invalid candidate
-    cand["schedule"][:5] = 4
+    cand["schedule"][:5] = 5
     w = Workload("gpt48+bad schedule", w0.costs, w0.cluster, cand)
     hip = H.run_hip(w)
     assert (hip["status"][:5] == 1).all()
@@ -526,12 +526,97 @@ def test_random_small_workloads(H, oracle_mod):
             _timeline_parity(H, oracle_mod, w, ok[:: max(1, len(ok) // 6)])
 
 
+def test_explicit_schedules(H, oracle_mod):
+    """Schedule 4: device lists given by the caller.  The built-in schedules written out as lists,
+    bidirectional pipelines, random schedules over random placements, malformed and unrunnable
+    schedules, next to candidates of the other schedules; blocking and latency p2p."""
+    _say("[case] explicit schedules")
+    from test_explicit_schedule_pins import random_schedule
+    from workloads.schedules import (bidirectional_lists, bidirectional_stages, chain, dapple_lists, gpipe_lists,
+                                     interleaved_lists, interleaved_stages, pack_schedule, pack_schedules)
+    rng = np.random.default_rng(404)
+    L = 48
+    costs = mk_costs(rng.integers(0, 5000, (2, L)).tolist(), rng.integers(0, 9000, (2, L)).tolist(),
+                     fa=rng.integers(0, 300, (2, L)).tolist(), ba=rng.integers(0, 300, (2, L)).tolist(),
+                     act=(rng.integers(0, 100, (2, L)) * 64).tolist(), grad=rng.integers(0, 1 << 20, (2, L)).tolist(),
+                     a2a=(rng.integers(0, 3, (2, L)) * 4096).tolist(), tps=(1, 2))
+    N = 64 * 9 * 5 * 7
+    blocks, rows = [], []
+
+    def add(blk, pp, m, tp=1, bnd=None):
+        blocks.append(blk)
+        rows.append((N // (pp * tp), tp, pp, m, 4, bnd, len(blocks) - 1))
+    for pp in (1, 2, 3, 4, 6, 8, 12, 16, 32, 64):
+        for m in (1, 2, 5, 16, 32):
+            if pp * m > 2048 or N % pp:
+                continue
+            tp = 2 if (pp + m) % 3 == 0 else 1
+            bnd = None
+            if pp <= L and (pp + m) % 2 == 0:
+                bnd = [0] + np.sort(rng.choice(np.arange(1, L), pp - 1, replace=False)).tolist() + [L]
+            if pp > L:
+                continue
+            add(pack_schedule(pp, chain(pp), m, pp, 1, gpipe_lists(pp, m)), pp, m, tp, bnd)
+            add(pack_schedule(pp, chain(pp), m, pp, 1, dapple_lists(pp, m)), pp, m, tp, bnd)
+            rows.append((N // (pp * tp), tp, pp, m, 0, bnd, 0))            # the same two through the built-in schedules
+            rows.append((N // (pp * tp), tp, pp, m, 1, bnd, 0))
+            if pp >= 2 and pp % 2 == 0 and 2 * pp * m <= 2048:
+                add(pack_schedule(pp, bidirectional_stages(pp), m, pp, 2, bidirectional_lists(pp, m)), pp, m, tp, bnd)
+    for pp, v, g in [(2, 2, 1), (2, 8, 3), (4, 4, 2), (8, 2, 4), (3, 5, 2), (16, 3, 1)]:
+        m = pp * g
+        add(pack_schedule(pp, interleaved_stages(pp, v), m, pp * v, 1, interleaved_lists(pp, v, m)), pp, m)
+        rows.append((N // pp, 1, pp, m, 3, None, v))
+    for _ in range(60):                                                    # random placements and orders
+        pp = int(rng.choice([d for d in range(1, 13) if N % d == 0]))
+        S, m, nparts = int(rng.integers(1, 20)), int(rng.integers(1, 7)), int(rng.integers(1, 9))
+        place, prev, lists = random_schedule(rng, pp, S, m)
+        part = [int(rng.integers(0, nparts)) for _ in range(S)]
+        bnd = [0] + np.sort(rng.choice(np.arange(1, L), nparts - 1, replace=False)).tolist() + [L] if rng.random() < 0.6 else None
+        add(pack_schedule(pp, list(zip(place, part, prev)), m, nparts, int(rng.choice([1, 2, 3])), lists), pp, m, 1, bnd)
+        if rng.random() < 0.3 and len(lists[0]) >= 2:                      # the same with two tasks of device 0 swapped
+            sw = [list(x) for x in lists]
+            i = int(rng.integers(0, len(sw[0]) - 1))
+            sw[0][i], sw[0][i + 1] = sw[0][i + 1], sw[0][i]
+            add(pack_schedule(pp, list(zip(place, part, prev)), m, nparts, 1, sw), pp, m, 1, bnd)
+    # malformed blocks
+    good = pack_schedule(2, chain(2), 2, 2, 1, dapple_lists(2, 2))
+    lists = dapple_lists(2, 2)
+    add(good, 2, 2)
+    add(good, 2, 3)                                                        # m differs
+    add(good[:-1], 2, 2)                                                   # too short
+    add(pack_schedule(2, chain(2), 2, 2, 1, [lists[0] + [lists[0][0]], lists[1]]), 2, 2)          # a task twice
+    add(pack_schedule(2, chain(2), 2, 2, 1, [lists[1], lists[0]]), 2, 2)                          # wrong device
+    add(pack_schedule(2, [(0, 0, -1), (1, 1, 0), (1, 1, 0)], 2, 2, 1, lists), 2, 2)              # two stages after one
+    add(pack_schedule(2, [(0, 0, -1), (1, 5, 0)], 2, 2, 1, lists), 2, 2)                          # part out of range
+    add(pack_schedule(2, chain(2), 2, 2, 0, lists), 2, 2)                                         # replicas < 1
+    add(pack_schedule(64, chain(64), 33, 64, 1, [[] for _ in range(64)]), 64, 33)                 # 64 * 33 slots: too many
+    rows.append((N // 2, 1, 2, 2, 4, None, len(blocks) + 3))                                      # no such schedule
+    rows.append((N // 2, 1, 2, 2, 4, None, -1))
+    off, words = pack_schedules(blocks)
+    for blocking in (0, 1, 2):
+        w = mk(costs, mk_cluster(N, blocking=blocking), rows, name=f"explicit blocking={blocking}")
+        w.cand["schedule_off"], w.cand["schedule_words"] = off, words
+        ora = oracle_mod.simulate(w, nthreads=NT)
+        x = w.cand["schedule"] == 4
+        if blocking < 2:
+            assert (ora["status"][x] == 0).sum() > 150 and (ora["status"][x] == 1).sum() > 10
+        else:
+            assert (ora["status"][x] == 1).all()
+        H.assert_same(H.run_hip(w, table=False), ora, what=w.name)
+        H.assert_same(H.run_hip(w, split=True), ora, what=w.name + ", table, GPipe launch")
+    # without the tables an explicit candidate is invalid
+    w = mk(costs, mk_cluster(N), rows[:8])
+    ora = oracle_mod.simulate(w, nthreads=NT)
+    assert (ora["status"][w.cand["schedule"] == 4] == 1).all()
+    H.assert_same(H.run_hip(w, table=False), ora, what="explicit without tables")
+
+
 def test_invalid_range_and_capacity_status(H, oracle_mod):
     _say("[case] status codes")
     costs = mk_costs([10] * 4, [20] * 4, tps=(1,))
     rows = [
         (1, 1, 2, 4, 1, None), (2, 1, 2, 4, 1, None), (1, 2, 1, 4, 1, None), (1, 1, 2, 0, 1, None),
-        (1, 1, 2, 4, 1, [0, 0, 4]), (1, 1, 2, 4, 1, [0, 2, 3]), (1, 1, 2, 4, 4, None), (1, 1, 2, 4, 0, [0, 1, 4]),
+        (1, 1, 2, 4, 1, [0, 0, 4]), (1, 1, 2, 4, 1, [0, 2, 3]), (1, 1, 2, 4, 5, None), (1, 1, 2, 4, 0, [0, 1, 4]),
         (1, 1, 2, (1 << 16) + 1, 0, None), (-1, -1, 2, 4, 0, None), (1, 1, 0, 4, 0, None),
     ]
     w = mk(costs, mk_cluster(2), rows)

@@ -8,6 +8,7 @@ import subprocess
 import pytest
 
 import oracle
+import test_explicit_schedule_pins as xpins
 import test_oracle_pins as pins
 
 SRC = os.path.join(os.path.dirname(os.path.abspath(oracle.__file__)), "distsim_oracle.c")
@@ -43,6 +44,12 @@ MUTANTS = [
     ("interleaved: micro-batch groups ignored", "jj[n] = (int32_t)((i__ / ((int64_t)pp * vch)) * pp + w__ % pp); n++; } while (0)\n#define PUT_B", "jj[n] = (int32_t)(w__ % pp); n++; } while (0)\n#define PUT_B"),
     ("interleaved: link class by virtual stage", "int64_t na = ((int64_t)(k % pp) * tp * dp) / g, nb = ((int64_t)((k + 1) % pp) * tp * dp) / g;", "int64_t na = ((int64_t)k * tp * dp) / g, nb = ((int64_t)(k + 1) * tp * dp) / g;"),
     ("interleaved: all-reduce of one chunk only", "for (int c = 0; c < vch; c++)\n                    for (int l = bnd[c * pp + d]; l < bnd[c * pp + d + 1]; l++) G += grad[l];", "for (int c = 0; c < 1; c++)\n                    for (int l = bnd[c * pp + d]; l < bnd[c * pp + d + 1]; l++) G += grad[l];"),
+    ("explicit: backward of a last stage does not wait for its forward", "(next[k] < 0 ? doneF[(int64_t)k * m + j] : sc->arrB[(int64_t)k * m + j])", "(next[k] < 0 ? 1 : sc->arrB[(int64_t)k * m + j])"),
+    ("explicit: p2p of the receiving part", "int64_t t = p2p_ns(cl, act[bnd[part[q] + 1] - 1], na == nb ? 0 : 1);", "int64_t t = p2p_ns(cl, act[bnd[part[k] + 1] - 1], na == nb ? 0 : 1);"),
+    ("explicit: link class by stage number", "int64_t na = ((int64_t)place[q] * tp * dp) / g, nb = ((int64_t)place[k] * tp * dp) / g;", "int64_t na = ((int64_t)q * tp * dp) / g, nb = ((int64_t)k * tp * dp) / g;"),
+    ("explicit: all-reduce ignores the replicas", "int64_t dd = allreduce_ns(cl, (int64_t)dp * replicas, G);", "int64_t dd = allreduce_ns(cl, (int64_t)dp, G);"),
+    ("explicit: gradient bytes of every stage on every device", "for (int q = 0; q < S; q++) if (place[q] == d)\n                    for (int l = bnd[part[q]]", "for (int q = 0; q < S; q++)\n                    for (int l = bnd[part[q]]"),
+    ("explicit: backward gradient goes to the stage after", "heap_push(h, now + (cl->p2p_blocking == 1 ? 0 : pb[k]), EV_ARRIVE_B, prev[k], j, 0);\n                mb_[d] += pb[k]; nev++;\n            }\n            if (nxt[d] == dev_off[d + 1]", "heap_push(h, now, EV_ARRIVE_B, prev[k], j, 0);\n                mb_[d] += pb[k]; nev++;\n            }\n            if (nxt[d] == dev_off[d + 1]"),
     ("utilisation from communication", "util[s] = now > 0 ? (double)cb[s] / (double)now : 0.0;", "util[s] = now > 0 ? (double)mb_[s] / (double)now : 0.0;"),
 ]
 
@@ -70,6 +77,10 @@ PINS = [
     pins.test_interleaved_against_task_graph,
     pins.test_interleaved_validity_rules,
     pins.test_interleaved_link_classes_follow_the_devices,
+    xpins.test_builtin_schedules_written_out_as_lists,
+    xpins.test_random_schedules_against_the_task_graph,
+    xpins.test_bidirectional_lists_run_and_use_both_directions,
+    xpins.test_invalid_explicit_schedules,
 ]
 
 

@@ -636,7 +636,7 @@ def test_async_schedule_is_dapple_without_the_global_sync(oracle_mod):
     for k in ("batch_ns", "num_events", "comp_busy_ns", "comm_busy_ns"):
         assert np.array_equal(a[k], b[k])
     # unknown schedules stay invalid
-    assert int(one(oracle_mod, costs, cl, (1, 1, 4, 6, 4, None))["status"][0]) == 1
+    assert int(one(oracle_mod, costs, cl, (1, 1, 4, 6, 5, None))["status"][0]) == 1
 
 
 # ----------------------------------------------------------------------------- interleaved schedule
@@ -842,7 +842,7 @@ def test_invalid_and_range_status(oracle_mod):
         (1, 1, 2, 0, 1, None),          # m < 1
         (1, 1, 2, 4, 1, [0, 0, 4]),     # empty stage
         (1, 1, 2, 4, 1, [0, 2, 3]),     # does not end at L
-        (1, 1, 2, 4, 4, None),          # unknown schedule
+        (1, 1, 2, 4, 5, None),          # unknown schedule
         (1, 1, 2, 4, 0, [0, 1, 4]),     # ok
     ]
     r = oracle_mod.simulate(mk(costs, mk_cluster(2), rows))
