@@ -81,7 +81,7 @@ extern "C" {
                                   all its stages.  pp and m must equal the candidate's, S * m <=
                                   DISTSIM_MAX_SLOTS, p2p_blocking != 2.  A schedule that cannot be run
                                   to its end is invalid, as is a malformed block.  Per-stage outputs
-                                  are per device; no stage table, no timeline.                    */
+                                  are per device; no stage table.                                 */
 #define DISTSIM_MAX_SLOTS 2048 /* (virtual stage, micro-batch) pairs of an explicit schedule       */
 #define DISTSIM_1F1B_ASYNC 2   /* asynchronous pipeline (Sec. 7, discussion of new algorithms):
                                   the Dapple order without the global synchronisation event, i.e.
@@ -289,7 +289,8 @@ int distsim_search(distsim_ctx *ctx, const int64_t *batch_ns, const int64_t *wei
  *                holds 2*pp*m entries laid out [kind][stage][micro-batch], kind 0 = forward,
  *                1 = backward.  With p2p_blocking the end includes the send.  A candidate with
  *                the interleaved schedule has 2*pp*chunks*m entries, [kind][virtual stage]
- *                [micro-batch], virtual stage k on device k mod pp.
+ *                [micro-batch], virtual stage k on device k mod pp; one with an explicit schedule
+ *                2*S*m entries in the same layout, -1 for tasks that its lists do not hold.
  *   ar_start_ns / ar_end_ns [n][DISTSIM_MAX_PP]: start of the first and end of the last gradient
  *                all-reduce event on each stage's device (interleaved: each device), -1 where
  *                there is none.
@@ -308,7 +309,7 @@ int distsim_timeline(distsim_ctx *ctx, const distsim_cluster *cluster, const dis
  * idle_before_ns gets, in the same [kind][stage][micro-batch] layout, the time the stage's device
  * was idle in front of each stage-task: its start minus the end of the task the device ran before
  * it in the schedule's order (minus 0 for the device's first task).  Candidates that got no
- * timeline get nothing.  Errors: EINVAL, ERANGE, EHIP.
+ * timeline get nothing, nor do tasks that an explicit schedule does not list.  Errors: EINVAL, ERANGE, EHIP.
  */
 int distsim_bubbles(distsim_ctx *ctx, const distsim_events *events, int64_t n, const int64_t *sel,
                     const int64_t *task_off, const int64_t *start_ns, const int64_t *end_ns,
@@ -355,7 +356,8 @@ enum {
     DISTSIM_K_LAYER_TABLES = 0, DISTSIM_K_DECODE, DISTSIM_K_BINS, DISTSIM_K_SCATTER,
     DISTSIM_K_STAGE_EVENTS, DISTSIM_K_SIM_INIT, DISTSIM_K_SIMULATE, DISTSIM_K_SEARCH, DISTSIM_K_TIMELINE,
     DISTSIM_K_DEDUP, DISTSIM_K_COMM_TIMES, DISTSIM_K_BUBBLES, DISTSIM_K_SIMULATE_VIRTUAL,
-    DISTSIM_K_TIMELINE_VIRTUAL, DISTSIM_K_SIMULATE_GPIPE, DISTSIM_K_SIMULATE_EXPLICIT, DISTSIM_K_COUNT
+    DISTSIM_K_TIMELINE_VIRTUAL, DISTSIM_K_SIMULATE_GPIPE, DISTSIM_K_SIMULATE_EXPLICIT,
+    DISTSIM_K_TIMELINE_EXPLICIT, DISTSIM_K_COUNT
 };
 int distsim_timing_enable(distsim_ctx *ctx, int on);
 int distsim_timing_read(distsim_ctx *ctx, int kernel, double *total_ms, int64_t *launches);

@@ -93,6 +93,10 @@ def simulate(w, nthreads: int = 1, timeline: bool = False) -> Dict[str, np.ndarr
     if timeline:
         assert C == 1
         rows = int(pp[0]) * (int(chunks[0]) if chunks is not None and sched[0] == 3 else 1)   # virtual stages
+        if sched[0] == 4 and chunks is not None and xoff is not None and 0 <= int(chunks[0]) < xn:
+            o = int(xoff[int(chunks[0])])
+            if 0 <= o and o + 5 <= xlen:
+                rows = max(1, min(64, int(xwords[o + 1])))     # S of its schedule block
         tls = np.full((2, rows, int(m[0])), -1, np.int64)
         tle = np.full((2, rows, int(m[0])), -1, np.int64)
         tar = np.full((2, int(pp[0])), -1, np.int64)

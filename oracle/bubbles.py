@@ -53,6 +53,18 @@ def device_order_interleaved(pp: int, m: int, chunks: int, d: int):
     return order
 
 
+def idle_before_lists(start: np.ndarray, end: np.ndarray, lists) -> np.ndarray:
+    """The same for an explicit schedule: lists[d] = [(kind, virtual stage, micro-batch)] is the order
+    in which device d runs its tasks.  Entries of tasks that no list holds stay zero."""
+    out = np.zeros_like(start)
+    for lst in lists:
+        prev_end = 0
+        for kind, k, j in lst:
+            out[kind, k, j] = int(start[kind, k, j]) - prev_end
+            prev_end = int(end[kind, k, j])
+    return out
+
+
 def idle_before(start: np.ndarray, end: np.ndarray, schedule: int, chunks: int = 1) -> np.ndarray:
     """start, end [2][stages][m] of one candidate -> idle time in front of every stage-task, same
     shape; stages = pp, or pp * chunks virtual stages for the interleaved schedule (3)."""

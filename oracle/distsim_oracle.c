@@ -641,7 +641,9 @@ static void simulate_explicit(const costs_t *co, const cluster_t *cl,
                               int32_t dp, int32_t tp, int32_t pp, int32_t m,
                               const int32_t *w, int64_t nwords, const uint8_t *bnd_in,
                               scratch_t *sc, result_t *res,
-                              int64_t *comp_busy, int64_t *comm_busy, double *util) {
+                              int64_t *comp_busy, int64_t *comm_busy, double *util,
+                              int64_t *tl_start, int64_t *tl_end /* [2][S][m] or NULL; tasks not listed keep what is there */,
+                              int64_t *tl_ar /* [2][pp] or NULL */) {
     const int L = co->L;
     res->status = ST_INVALID;
     res->batch_ns = INT64_MAX;
@@ -735,6 +737,7 @@ static void simulate_explicit(const costs_t *co, const cluster_t *cl,
     int64_t cb[64], mb_[64];
     for (int d = 0; d < pp; d++) { nxt[d] = dev_off[d]; busy[d] = 0; cb[d] = 0; mb_[d] = 0; }
     int64_t nev = 0, now = 0, ran = 0;
+    if (tl_ar) for (int d = 0; d < 2 * pp; d++) tl_ar[d] = -1;
 
 #define TRY_START_X(d_) do {                                                            \
         int d__ = (d_);                                                                 \
@@ -746,6 +749,7 @@ static void simulate_explicit(const costs_t *co, const cluster_t *cl,
             if (ready) {                                                                \
                 busy[d__] = 1;                                                          \
                 int64_t t = now;                                                        \
+                if (tl_start) tl_start[((int64_t)kd * S + k) * m + j] = t;              \
                 if (kd == 0) {                                                          \
                     for (int l = bnd[part[k]]; l < bnd[part[k] + 1]; l++) {             \
                         t += fc[l]; cb[d__] += fc[l];                                   \
@@ -779,6 +783,7 @@ static void simulate_explicit(const costs_t *co, const cluster_t *cl,
         case EV_TASK_DONE: {
             int kd = e.layer, j = e.mb;
             nev++; ran++;
+            if (tl_end) tl_end[((int64_t)kd * S + k) * m + j] = now;
             busy[d] = 0;
             nxt[d]++;
             if (kd == 0) {
@@ -799,6 +804,7 @@ static void simulate_explicit(const costs_t *co, const cluster_t *cl,
                     int64_t dd = allreduce_ns(cl, (int64_t)dp * replicas, G);
                     heap_push(h, now + dd, EV_AR_DONE, k, 0, 0);
                     mb_[d] += dd;
+                    if (tl_ar) { tl_ar[d] = now; tl_ar[pp + d] = now + dd; }
                 }
             }
             TRY_START_X(d);
@@ -876,7 +882,8 @@ int oracle_simulate(int32_t L, int32_t V, const int32_t *variant_tp,
                     nw = sched_off[chunks[c] + 1] - sched_off[chunks[c]];
                 }
                 simulate_explicit(&co, &cl, dp[c], tp[c], p, m[c], blk, nw, b, &sc, &r,
-                                  buf, buf ? buf + p : NULL, buf ? (double *)(buf + 2 * p) : NULL);
+                                  buf, buf ? buf + p : NULL, buf ? (double *)(buf + 2 * p) : NULL,
+                                  C == 1 ? tl_start : NULL, C == 1 ? tl_end : NULL, C == 1 ? tl_ar : NULL);
             } else if (schedule[c] == 3)
                 simulate_interleaved(&co, &cl, dp[c], tp[c], p, m[c], chunks ? chunks[c] : 0 /* no chunk counts: invalid */, b, &sc, &r,
                                      buf, buf ? buf + p : NULL, buf ? (double *)(buf + 2 * p) : NULL,

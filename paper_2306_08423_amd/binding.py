@@ -27,7 +27,8 @@ NCOLS = 8
 COL = {"FC": 0, "FA": 1, "BC": 2, "BA": 3, "PF": 4, "PB": 5, "G": 6, "AR": 7}
 KERNELS = ("k_layer_tables", "k_decode", "k_bins", "k_scatter", "k_stage_events",
            "k_sim_init", "k_simulate", "k_search", "k_timeline", "k_dedup", "k_comm_event_times", "k_bubbles", "k_simulate_virtual",
-           "k_timeline_virtual", "k_simulate_gpipe", "k_simulate_explicit")
+           "k_timeline_virtual", "k_simulate_gpipe", "k_simulate_explicit",
+           "k_timeline_explicit")
 INT64_MAX = (1 << 63) - 1
 
 

@@ -36,7 +36,7 @@ static const char* kKernelNames[DISTSIM_K_COUNT] = {
     "k_layer_tables", "k_decode", "k_bins", "k_scatter",
     "k_stage_events", "k_sim_init", "k_simulate", "k_search", "k_timeline",
     "k_dedup", "k_comm_event_times", "k_bubbles", "k_simulate_virtual",
-    "k_timeline_virtual", "k_simulate_gpipe", "k_simulate_explicit",
+    "k_timeline_virtual", "k_simulate_gpipe", "k_simulate_explicit", "k_timeline_explicit",
 };
 
 static int fail(distsim_ctx* ctx, int code, const std::string& msg) {
@@ -331,6 +331,13 @@ int distsim_timeline(distsim_ctx* ctx, const distsim_cluster* cluster, const dis
         Timer t(ctx, st, DISTSIM_K_TIMELINE_VIRTUAL);
         const int64_t grid = n < 65536 ? n : 65536;
         hipLaunchKernelGGL(k_timeline_virtual, dim3((unsigned)grid), dim3(kWave), 0, st, co, cl_dev(*cluster), ca, ws,
+                           events->status, events->num_candidates, n, sel, task_off, start_ns, end_ns, ar_start_ns,
+                           ar_end_ns);
+    }
+    if (cd->chunks && ca.n_schedules > 0) {          // ... and those with an explicit schedule
+        Timer t(ctx, st, DISTSIM_K_TIMELINE_EXPLICIT);
+        const int64_t grid = n < 65536 ? n : 65536;
+        hipLaunchKernelGGL(k_timeline_explicit, dim3((unsigned)grid), dim3(kWave), 0, st, co, cl_dev(*cluster), ca, ws,
                            events->status, events->num_candidates, n, sel, task_off, start_ns, end_ns, ar_start_ns,
                            ar_end_ns);
     }

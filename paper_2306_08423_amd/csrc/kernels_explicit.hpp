@@ -7,7 +7,7 @@
 // the schedule cannot be run to its end and the candidate is invalid.  Same arithmetic as the
 // level sweeps: fp64 values that are integers below 2^53.  The slow path: generality, not speed.
 #pragma once
-#include "kernels_simulate.hpp"
+#include "kernels_virtual.hpp"
 
 namespace distsim {
 
@@ -23,190 +23,246 @@ struct ExplicitLds {
 };
 constexpr double kNotListed = -1.0, kListed = -2.0;
 
+// What one candidate needs from its descriptor (or, for the dump, from the candidate arrays).
+struct ExplicitCand {
+    int pp, v, m, dp, tp;
+    int64_t id, poff, c;
+};
+
+// One candidate on one wavefront.  DUMP = false: writes status / batch time / busy sums.
+// DUMP = true: the candidate is known to be OK; writes the start and end of every listed task
+// ([kind][virtual stage][micro-batch], -1 for tasks that are not listed) and the all-reduce
+// windows, and none of the simulation's outputs.
+template <bool DUMP>
+__device__ __forceinline__ void explicit_candidate(const CostsDev& co, const ClusterDev& cl, const CandDev& ca,
+                                                   const Workspace& ws, const EventsDev& ev, const SimOut& out,
+                                                   const ExplicitCand& xc, const VirtDump& dump, ExplicitLds& sm) {
+    const int lane = threadIdx.x;
+    const int L = co.L;
+    __syncthreads();                                                  // the previous candidate's LDS is free
+    const int pp = xc.pp, v = xc.v, m = xc.m, dp = xc.dp, tp = xc.tp;
+    const int64_t id = xc.id, c = xc.c;
+    auto invalid = [&]() {
+        if (!DUMP && lane == 0) { ev.status[c] = 1; ev.num_events[c] = 0; out.batch_ns[c] = INT64_MAX; }
+    };
+    // k_decode has checked the head of the block (pp, m, S, nparts, replicas, S * m)
+    const int64_t woff = ca.schedule_off[id], nwords = ca.schedule_off[id + 1] - woff;
+    const int32_t* w = ca.schedule_words + woff;
+    const int S = w[1], nparts = w[3], replicas = w[4];
+    const int32_t* dev_off = w + 5;
+    const int64_t ntask = dev_off[pp];
+    bool bad = dev_off[0] != 0 || ntask < 0 || ntask > 2ll * S * m || nwords != 5 + pp + 1 + 3ll * S + ntask;
+    const int t0 = lane < pp ? dev_off[lane] : 0, t1 = lane < pp ? dev_off[lane + 1] : 0;      // this device's list
+    bad = bad || __builtin_amdgcn_ballot_w64(t1 < t0) != 0;
+    if (bad) { invalid(); return; }
+    const int32_t* st = dev_off + pp + 1;
+    const int32_t* tasks = st + 3 * S;
+
+    // the stages (lane = virtual stage)
+    const bool isk = lane < S;
+    int place = 0, part = 0, prev = -1;
+    if (isk) { place = st[3 * lane]; part = st[3 * lane + 1]; prev = st[3 * lane + 2]; }
+    bool kbad = isk && (place < 0 || place >= pp || part < 0 || part >= nparts || prev < -1 || prev >= S || prev == lane);
+    sm.succ[lane] = 0;
+    sm.next[lane] = -1;
+    __syncthreads();
+    if (isk && !kbad && prev >= 0) atomicAdd(&sm.succ[prev], 1);
+    __syncthreads();
+    kbad = kbad || (isk && sm.succ[lane] > 1);                        // at most one stage after any stage
+    // the partition (lane = part): 0 = b0 < b1 < ... = L
+    int plo = 0, phi = 0;
+    if (lane < nparts) {
+        if (xc.poff >= 0) { plo = ca.part_pool[xc.poff + lane]; phi = ca.part_pool[xc.poff + lane + 1]; }
+        else { plo = (int)(((int64_t)lane * L) / nparts); phi = (int)(((int64_t)(lane + 1) * L) / nparts); }
+        if (phi <= plo || phi > L || (lane == 0 && plo != 0) || (lane == nparts - 1 && phi != L)) kbad = true;
+    }
+    if (__builtin_amdgcn_ballot_w64(kbad) != 0) { invalid(); return; }
+    if (isk && prev >= 0) sm.next[prev] = lane;
+    if (isk) { sm.place[lane] = place; sm.prev[lane] = prev; }
+    __syncthreads();
+
+    // every task at most once, on the device of its stage
+    const int slots = S * m;
+    for (int i = lane; i < slots; i += kWave) { sm.endF[i] = kNotListed; sm.endB[i] = kNotListed; }
+    __syncthreads();
+    bool lbad = false;
+    for (int i = t0; i < t1; i++) {
+        const uint32_t x = (uint32_t)tasks[i];
+        const int kd = x >> 31, k = (x >> 16) & 0x7fff, j = x & 0xffff;
+        if (k >= S || j >= m || sm.place[k] != lane) { lbad = true; break; }
+        double* e = (kd ? sm.endB : sm.endF) + k * m + j;               // only this lane holds stage k
+        if (*e != kNotListed) { lbad = true; break; }
+        *e = kListed;
+    }
+    if (__builtin_amdgcn_ballot_w64(lbad) != 0) { invalid(); return; }
+    __syncthreads();
+
+
+    // composed events of every stage's part, p2p events of the edges
+    const int64_t tpdp = (int64_t)tp * dp;
+    auto node_of = [&](int dev) -> int64_t {
+        return tpdp >= cl.gpus_per_node ? dev : (int64_t)node_of_position(cl, dev, (int)tpdp);
+    };
+    const int64_t* row = ws.comb + (size_t)((v * kMaxPP + pp - 1) * (L + 1)) * kCombWords;
+    const size_t vr = (size_t)v * (L + 1);
+    int64_t FT = 0, BT = 0, PB = 0, share = 0;
+    sm.sendF[lane] = 0;
+    __syncthreads();
+    if (isk) {
+        int lo, hi;
+        if (xc.poff >= 0) { lo = ca.part_pool[xc.poff + part]; hi = ca.part_pool[xc.poff + part + 1]; }
+        else { lo = (int)(((int64_t)part * L) / nparts); hi = (int)(((int64_t)(part + 1) * L) / nparts); }
+        const int64_t* eh = row + hi * kCombWords;
+        const int64_t* el = row + lo * kCombWords;
+        FT = eh[0] - el[0]; BT = eh[1] - el[1];
+        const int64_t fcp = ws.pfc[vr + hi] - ws.pfc[vr + lo], bcp = ws.pbc[vr + hi] - ws.pbc[vr + lo];
+        sm.compF[lane] = fcp; sm.compB[lane] = bcp;
+        sm.commF[lane] = FT - fcp; sm.commB[lane] = BT - bcp;
+        sm.grad[lane] = eh[3] - el[3];
+        if (prev >= 0) {
+            // the activation that leaves the part of the stage before: entry of the layer after it
+            const int pq = st[3 * prev + 1];
+            int qhi;
+            if (xc.poff >= 0) qhi = ca.part_pool[xc.poff + pq + 1];
+            else qhi = (int)(((int64_t)(pq + 1) * L) / nparts);
+            const int inter = node_of(sm.place[prev]) != node_of(place) ? 1 : 0;
+            PB = row[qhi * kCombWords + 4 + inter];
+            sm.sendF[prev] = PB;                                     // the same event, sent forwards by the stage before
+        }
+        sm.sendB[lane] = PB;
+    }
+    __syncthreads();
+    if (isk) share = FT + BT + sm.sendF[lane] + PB;
+    if (stage_out_of_range(isk ? share : 0, m, kWave)) {
+        if (!DUMP && lane == 0) { ev.status[c] = 2; ev.num_events[c] = 0; out.batch_ns[c] = INT64_MAX; }
+        return;
+    }
+    if (isk) {
+        const int64_t pf_task = cl.blocking == 1 ? sm.sendF[lane] : 0, pb_task = cl.blocking == 1 ? PB : 0;
+        sm.durF[lane] = (double)(FT + pf_task);
+        sm.durB[lane] = (double)(BT + pb_task);
+    }
+    __syncthreads();
+    if (isk) {
+        const int nx = sm.next[lane];
+        sm.latF[lane] = prev >= 0 && cl.blocking != 1 ? (double)sm.sendF[prev] : 0.0;
+        sm.latB[lane] = nx >= 0 && cl.blocking != 1 ? (double)sm.sendB[nx] : 0.0;
+    }
+    __syncthreads();
+    if (DUMP) {                                                      // tasks that are not listed read -1
+        for (int q = lane; q < 2 * slots; q += kWave) { dump.start[q] = -1; dump.end[q] = -1; }
+    }
+
+    // the rounds
+    int i = t0;
+    double own = 0.0;
+    int64_t comp = 0, comm = 0, nsend = 0;
+    bool stuck = false;
+    for (int64_t round = 0; round <= ntask; round++) {
+        const bool todo = i < t1;
+        if (__builtin_amdgcn_ballot_w64(todo) == 0) break;
+        bool ran = false;
+        int kd = 0, k = 0, j = 0;
+        double arrive = 0.0;
+        if (todo) {
+            const uint32_t x = (uint32_t)tasks[i];
+            kd = x >> 31; k = (x >> 16) & 0x7fff; j = x & 0xffff;
+            if (kd == 0) {
+                const int p = sm.prev[k];
+                if (p < 0) ran = true;
+                else { const double e = sm.endF[p * m + j]; ran = e >= 0.0; arrive = e + sm.latF[k]; }
+            } else {
+                const int nx = sm.next[k];
+                if (nx < 0) ran = sm.endF[k * m + j] >= 0.0;         // its own forward; this device ran it
+                else { const double e = sm.endB[nx * m + j]; ran = e >= 0.0; arrive = e + sm.latB[k]; }
+            }
+        }
+        __syncthreads();                                             // all reads of this round before its writes
+        if (ran) {
+            const double start = arrive > own ? arrive : own;
+            own = start + (kd ? sm.durB[k] : sm.durF[k]);
+            (kd ? sm.endB : sm.endF)[k * m + j] = own;
+            if (DUMP) {
+                const int64_t q = ((int64_t)kd * S + k) * m + j;
+                dump.start[q] = double_to_i64(start);
+                dump.end[q] = double_to_i64(own);
+            }
+            comp += kd ? sm.compB[k] : sm.compF[k];
+            const int64_t snd = kd ? sm.sendB[k] : sm.sendF[k];
+            comm += (kd ? sm.commB[k] : sm.commF[k]) + snd;
+            nsend += kd ? (sm.prev[k] >= 0 ? 1 : 0) : (sm.next[k] >= 0 ? 1 : 0);
+            i++;
+        }
+        if (__builtin_amdgcn_ballot_w64(ran) == 0) { stuck = true; break; }
+        __syncthreads();
+    }
+    if (stuck || __builtin_amdgcn_ballot_w64(i < t1) != 0) { invalid(); return; }
+
+    // data-parallel modelling per device: one all-reduce after its list, over the bytes of all its stages
+    const bool dev = lane < pp;
+    int64_t G = 0;
+    if (dev)
+        for (int k = 0; k < S; k++)
+            if (sm.place[k] == lane) G += sm.grad[k];
+    const int64_t ranks = (int64_t)dp * replicas;
+    const bool has_ar = dev && t1 > t0 && ranks > 1 && G > 0;
+    const int64_t AR = has_ar ? allreduce_ns(cl, ranks, G) : 0;
+    const int64_t endL = double_to_i64(own);
+    if (DUMP) {
+        if (has_ar) { dump.ar_start[lane] = endL; dump.ar_end[lane] = endL + AR; }
+        return;
+    }
+    const int64_t batch = group_max(dev ? endL + AR : 0, kWave);
+    const int64_t nar = group_count(has_ar, kWave);
+    const int64_t sends = group_sum(dev ? nsend : 0, kWave);
+    const int64_t base = ev.stage_pos[c];
+    if (dev && base >= 0) {
+        out.comp_busy[base + lane] = comp;
+        out.comm_busy[base + lane] = comm + AR;
+        if (out.util) out.util[base + lane] = batch > 0 ? (double)comp / (double)batch : 0.0;
+    }
+    if (lane == 0) {
+        out.batch_ns[c] = batch;
+        ev.num_events[c] = ntask + sends + nar;
+    }
+}
+
 __global__ __launch_bounds__(kWave) void k_simulate_explicit(CostsDev co, ClusterDev cl, CandDev ca, Workspace ws,
                                                              EventsDev ev, SimOut out, int64_t C) {
     __shared__ ExplicitLds sm;
-    const int lane = threadIdx.x;
-    const int L = co.L;
     for (int64_t pos = blockIdx.x; pos < C; pos += gridDim.x) {
         // descriptors beyond the valid candidates were never written: the class table bounds them
         if (pos >= ws.hdr[H_CLASS_START + kClasses]) break;
         const Desc ds = ws.desc[pos];
         if (!is_explicit(ds) || (ds.meta & 0xff) == 0) continue;          // uniform: one descriptor per wavefront
-        __syncthreads();                                                  // the previous candidate's LDS is free
-        const int pp = ds.meta & 0xff, v = ds.meta >> 16, m = ds.m, dp = ds.dp;
-        const int tp = (int)(uint32_t)ds.spare;
-        const int64_t id = ds.spare >> 32, c = ds.cand;
-        auto invalid = [&]() {
-            if (lane == 0) { ev.status[c] = 1; ev.num_events[c] = 0; out.batch_ns[c] = INT64_MAX; }
-        };
-        // k_decode has checked the head of the block (pp, m, S, nparts, replicas, S * m)
-        const int64_t woff = ca.schedule_off[id], nwords = ca.schedule_off[id + 1] - woff;
-        const int32_t* w = ca.schedule_words + woff;
-        const int S = w[1], nparts = w[3], replicas = w[4];
-        const int32_t* dev_off = w + 5;
-        const int64_t ntask = dev_off[pp];
-        bool bad = dev_off[0] != 0 || ntask < 0 || ntask > 2ll * S * m || nwords != 5 + pp + 1 + 3ll * S + ntask;
-        const int t0 = lane < pp ? dev_off[lane] : 0, t1 = lane < pp ? dev_off[lane + 1] : 0;      // this device's list
-        bad = bad || __builtin_amdgcn_ballot_w64(t1 < t0) != 0;
-        if (bad) { invalid(); continue; }
-        const int32_t* st = dev_off + pp + 1;
-        const int32_t* tasks = st + 3 * S;
+        const ExplicitCand xc{ds.meta & 0xff, ds.meta >> 16, ds.m, ds.dp, (int)(uint32_t)ds.spare, ds.spare >> 32, ds.poff,
+                              ds.cand};
+        explicit_candidate<false>(co, cl, ca, ws, ev, out, xc, VirtDump{}, sm);
+    }
+}
 
-        // the stages (lane = virtual stage)
-        const bool isk = lane < S;
-        int place = 0, part = 0, prev = -1;
-        if (isk) { place = st[3 * lane]; part = st[3 * lane + 1]; prev = st[3 * lane + 2]; }
-        bool kbad = isk && (place < 0 || place >= pp || part < 0 || part >= nparts || prev < -1 || prev >= S || prev == lane);
-        sm.succ[lane] = 0;
-        sm.next[lane] = -1;
-        __syncthreads();
-        if (isk && !kbad && prev >= 0) atomicAdd(&sm.succ[prev], 1);
-        __syncthreads();
-        kbad = kbad || (isk && sm.succ[lane] > 1);                        // at most one stage after any stage
-        // the partition (lane = part): 0 = b0 < b1 < ... = L
-        int plo = 0, phi = 0;
-        if (lane < nparts) {
-            if (ds.poff >= 0) { plo = ca.part_pool[ds.poff + lane]; phi = ca.part_pool[ds.poff + lane + 1]; }
-            else { plo = (int)(((int64_t)lane * L) / nparts); phi = (int)(((int64_t)(lane + 1) * L) / nparts); }
-            if (phi <= plo || phi > L || (lane == 0 && plo != 0) || (lane == nparts - 1 && phi != L)) kbad = true;
-        }
-        if (__builtin_amdgcn_ballot_w64(kbad) != 0) { invalid(); continue; }
-        if (isk && prev >= 0) sm.next[prev] = lane;
-        if (isk) { sm.place[lane] = place; sm.prev[lane] = prev; }
-        __syncthreads();
-
-        // every task at most once, on the device of its stage
-        const int slots = S * m;
-        for (int i = lane; i < slots; i += kWave) { sm.endF[i] = kNotListed; sm.endB[i] = kNotListed; }
-        __syncthreads();
-        bool lbad = false;
-        for (int i = t0; i < t1; i++) {
-            const uint32_t x = (uint32_t)tasks[i];
-            const int kd = x >> 31, k = (x >> 16) & 0x7fff, j = x & 0xffff;
-            if (k >= S || j >= m || sm.place[k] != lane) { lbad = true; break; }
-            double* e = (kd ? sm.endB : sm.endF) + k * m + j;               // only this lane holds stage k
-            if (*e != kNotListed) { lbad = true; break; }
-            *e = kListed;
-        }
-        if (__builtin_amdgcn_ballot_w64(lbad) != 0) { invalid(); continue; }
-        __syncthreads();
-
-
-        // composed events of every stage's part, p2p events of the edges
-        const int64_t tpdp = (int64_t)tp * dp;
-        auto node_of = [&](int dev) -> int64_t {
-            return tpdp >= cl.gpus_per_node ? dev : (int64_t)node_of_position(cl, dev, (int)tpdp);
-        };
-        const int64_t* row = ws.comb + (size_t)((v * kMaxPP + pp - 1) * (L + 1)) * kCombWords;
-        const size_t vr = (size_t)v * (L + 1);
-        int64_t FT = 0, BT = 0, PB = 0, share = 0;
-        sm.sendF[lane] = 0;
-        __syncthreads();
-        if (isk) {
-            int lo, hi;
-            if (ds.poff >= 0) { lo = ca.part_pool[ds.poff + part]; hi = ca.part_pool[ds.poff + part + 1]; }
-            else { lo = (int)(((int64_t)part * L) / nparts); hi = (int)(((int64_t)(part + 1) * L) / nparts); }
-            const int64_t* eh = row + hi * kCombWords;
-            const int64_t* el = row + lo * kCombWords;
-            FT = eh[0] - el[0]; BT = eh[1] - el[1];
-            const int64_t fcp = ws.pfc[vr + hi] - ws.pfc[vr + lo], bcp = ws.pbc[vr + hi] - ws.pbc[vr + lo];
-            sm.compF[lane] = fcp; sm.compB[lane] = bcp;
-            sm.commF[lane] = FT - fcp; sm.commB[lane] = BT - bcp;
-            sm.grad[lane] = eh[3] - el[3];
-            if (prev >= 0) {
-                // the activation that leaves the part of the stage before: entry of the layer after it
-                const int pq = st[3 * prev + 1];
-                int qhi;
-                if (ds.poff >= 0) qhi = ca.part_pool[ds.poff + pq + 1];
-                else qhi = (int)(((int64_t)(pq + 1) * L) / nparts);
-                const int inter = node_of(sm.place[prev]) != node_of(place) ? 1 : 0;
-                PB = row[qhi * kCombWords + 4 + inter];
-                sm.sendF[prev] = PB;                                     // the same event, sent forwards by the stage before
-            }
-            sm.sendB[lane] = PB;
-        }
-        __syncthreads();
-        if (isk) share = FT + BT + sm.sendF[lane] + PB;
-        if (stage_out_of_range(isk ? share : 0, m, kWave)) {
-            if (lane == 0) { ev.status[c] = 2; ev.num_events[c] = 0; out.batch_ns[c] = INT64_MAX; }
-            continue;
-        }
-        if (isk) {
-            const int64_t pf_task = cl.blocking == 1 ? sm.sendF[lane] : 0, pb_task = cl.blocking == 1 ? PB : 0;
-            sm.durF[lane] = (double)(FT + pf_task);
-            sm.durB[lane] = (double)(BT + pb_task);
-        }
-        __syncthreads();
-        if (isk) {
-            const int nx = sm.next[lane];
-            sm.latF[lane] = prev >= 0 && cl.blocking != 1 ? (double)sm.sendF[prev] : 0.0;
-            sm.latB[lane] = nx >= 0 && cl.blocking != 1 ? (double)sm.sendB[nx] : 0.0;
-        }
-        __syncthreads();
-        // the rounds
-        int i = t0;
-        double own = 0.0;
-        int64_t comp = 0, comm = 0, nsend = 0;
-        bool stuck = false;
-        for (int64_t round = 0; round <= ntask; round++) {
-            const bool todo = i < t1;
-            if (__builtin_amdgcn_ballot_w64(todo) == 0) break;
-            bool ran = false;
-            int kd = 0, k = 0, j = 0;
-            double arrive = 0.0;
-            if (todo) {
-                const uint32_t x = (uint32_t)tasks[i];
-                kd = x >> 31; k = (x >> 16) & 0x7fff; j = x & 0xffff;
-                if (kd == 0) {
-                    const int p = sm.prev[k];
-                    if (p < 0) ran = true;
-                    else { const double e = sm.endF[p * m + j]; ran = e >= 0.0; arrive = e + sm.latF[k]; }
-                } else {
-                    const int nx = sm.next[k];
-                    if (nx < 0) ran = sm.endF[k * m + j] >= 0.0;         // its own forward; this device ran it
-                    else { const double e = sm.endB[nx * m + j]; ran = e >= 0.0; arrive = e + sm.latB[k]; }
-                }
-            }
-            __syncthreads();                                             // all reads of this round before its writes
-            if (ran) {
-                const double start = arrive > own ? arrive : own;
-                own = start + (kd ? sm.durB[k] : sm.durF[k]);
-                (kd ? sm.endB : sm.endF)[k * m + j] = own;
-                comp += kd ? sm.compB[k] : sm.compF[k];
-                const int64_t snd = kd ? sm.sendB[k] : sm.sendF[k];
-                comm += (kd ? sm.commB[k] : sm.commF[k]) + snd;
-                nsend += kd ? (sm.prev[k] >= 0 ? 1 : 0) : (sm.next[k] >= 0 ? 1 : 0);
-                i++;
-            }
-            if (__builtin_amdgcn_ballot_w64(ran) == 0) { stuck = true; break; }
-            __syncthreads();
-        }
-        if (stuck || __builtin_amdgcn_ballot_w64(i < t1) != 0) { invalid(); continue; }
-
-        // data-parallel modelling per device: one all-reduce after its list, over the bytes of all its stages
-        const bool dev = lane < pp;
-        int64_t G = 0;
-        if (dev)
-            for (int k = 0; k < S; k++)
-                if (sm.place[k] == lane) G += sm.grad[k];
-        const int64_t ranks = (int64_t)dp * replicas;
-        const bool has_ar = dev && t1 > t0 && ranks > 1 && G > 0;
-        const int64_t AR = has_ar ? allreduce_ns(cl, ranks, G) : 0;
-        const int64_t endL = double_to_i64(own);
-        const int64_t batch = group_max(dev ? endL + AR : 0, kWave);
-        const int64_t nar = group_count(has_ar, kWave);
-        const int64_t sends = group_sum(dev ? nsend : 0, kWave);
-        const int64_t base = ev.stage_pos[c];
-        if (dev && base >= 0) {
-            out.comp_busy[base + lane] = comp;
-            out.comm_busy[base + lane] = comm + AR;
-            if (out.util) out.util[base + lane] = batch > 0 ? (double)comp / (double)batch : 0.0;
-        }
-        if (lane == 0) {
-            out.batch_ns[c] = batch;
-            ev.num_events[c] = ntask + sends + nar;
-        }
+// Timeline dump of the selected candidates that have an explicit schedule; one wavefront per
+// selection.  The block of candidate sel[q] holds 2 * S * m entries laid out [kind][virtual stage]
+// [micro-batch]; the all-reduce windows are per device.  Runs after k_timeline, which has set
+// every all-reduce window to -1 and skipped these candidates.
+__global__ __launch_bounds__(kWave) void k_timeline_explicit(CostsDev co, ClusterDev cl, CandDev ca, Workspace ws,
+                                                             const int32_t* status, int64_t C, int64_t n,
+                                                             const int64_t* sel, const int64_t* task_off,
+                                                             int64_t* start_ns, int64_t* end_ns, int64_t* ar_start,
+                                                             int64_t* ar_end) {
+    __shared__ ExplicitLds sm;
+    for (int64_t q = blockIdx.x; q < n; q += gridDim.x) {
+        const int64_t c = sel[q];
+        if (c < 0 || c >= C || status[c] != 0 || ca.schedule[c] != 4 || !ca.chunks) continue;
+        const int tp = ca.tp[c];
+        int v = -1;
+        for (int i = 0; i < co.V; i++)
+            if (co.variant_tp[i] == tp) { v = i; break; }
+        if (v < 0) continue;                                              // cannot be: the status is OK
+        const ExplicitCand xc{ca.pp[c], v, ca.m[c], ca.dp[c], tp, ca.chunks[c], ca.part_off[c], c};
+        const int64_t off = task_off[q];
+        const VirtDump dump{start_ns + off, end_ns + off, ar_start + q * kMaxPP, ar_end + q * kMaxPP};
+        explicit_candidate<true>(co, cl, ca, ws, EventsDev{}, SimOut{}, xc, dump, sm);
     }
 }
 

@@ -286,6 +286,7 @@ __global__ __launch_bounds__(kTlWaves * kWave) void k_timeline(CostsDev co, Clus
 //           F(s,j) after F(s,j-1) for j <= w, after B(s,j-w-1) for j > w;
 //           B(s,j) after F(s,w+j) for j < m-w, else after B(s,j-1) (after F(s,m-1) if j = 0)
 //   interleaved  the same order over slots; entries [kind][virtual stage][micro-batch]
+//   explicit     the order of the device's list; entries of tasks that are not listed stay untouched
 // One workgroup per selected candidate; entries in the layout of the dump, [kind][stage][micro-batch].
 __global__ __launch_bounds__(256) void k_bubbles(CandDev ca, const int32_t* __restrict__ status, int64_t C, int64_t n,
                                                  const int64_t* __restrict__ sel, const int64_t* __restrict__ task_off,
@@ -297,7 +298,25 @@ __global__ __launch_bounds__(256) void k_bubbles(CandDev ca, const int32_t* __re
     if (c < 0 || c >= C || status[c] != 0) return;
     const int pp = ca.pp[c], m = ca.m[c], sched = ca.schedule[c];
     const int64_t off = task_off[q];
-    if (sched > 3) return;
+    if (sched == 4) {
+        // Explicit schedule: the lists are the device order; thread d walks the list of device d.
+        if (!ca.chunks || !ca.schedule_off || !ca.schedule_words) return;
+        const int32_t* w = ca.schedule_words + ca.schedule_off[ca.chunks[c]];     // checked when the candidate got status OK
+        const int S = w[1];
+        const int32_t* dev_off = w + 5;
+        const int32_t* tasks = dev_off + pp + 1 + 3 * S;
+        if ((int)threadIdx.x < pp) {
+            int64_t before = 0;
+            for (int i = dev_off[threadIdx.x]; i < dev_off[threadIdx.x + 1]; i++) {
+                const uint32_t x = (uint32_t)tasks[i];
+                const int64_t e = off + ((int64_t)(x >> 31) * S + ((x >> 16) & 0x7fff)) * m + (x & 0xffff);
+                idle[e] = start[e] - before;
+                before = end[e];
+            }
+        }
+        return;
+    }
+    if (sched > 4) return;
     if (sched == 3) {
         // Interleaved: device d = k mod pp runs slots, not micro-batches, in the Dapple order with
         // W warm-up forwards.  Slot i of a direction <-> (chunk, micro-batch) and slot <-> position

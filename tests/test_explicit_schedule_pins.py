@@ -103,7 +103,7 @@ def longest_path(S, m, place, prev, lists, Fd, Bd, pf, pb, blocking):
             if val != start[n]:
                 start[n] = val
                 changed = True
-    return {n: start[n] + dur(n) for n in preds}
+    return {n: start[n] + dur(n) for n in preds}, start
 
 
 def random_schedule(rng, pp, S, m):
@@ -156,7 +156,7 @@ def test_random_schedules_against_the_task_graph(oracle_mod):
         cl = mk_cluster(dp * pp, g=g, alpha=(2, 7), beta=(5, 1), blocking=blocking)
         blk = pack_schedule(pp, list(zip(place, part, prev)), m, nparts, replicas, lists)
         w = with_schedules(mk(costs, cl, [(dp, 1, pp, m, 4, bnd, 0)]), [blk], [0])
-        r = oracle_mod.simulate(w)
+        r = oracle_mod.simulate(w, timeline=True)
         assert r["status"][0] == 0, trial
         Fd = [sum(fc[bnd[part[k]]:bnd[part[k] + 1]]) for k in range(S)]
         Bd = [sum(bc[bnd[part[k]]:bnd[part[k] + 1]]) for k in range(S)]
@@ -168,7 +168,16 @@ def test_random_schedules_against_the_task_graph(oracle_mod):
                 cls = 0 if node(place[q]) == node(place[k]) else 1
                 t = (2, 7)[cls] + act[bnd[part[q] + 1] - 1] // (5, 1)[cls]
                 pf[q], pb[k] = t, t
-        end = longest_path(S, m, place, prev, lists, Fd, Bd, pf, pb, blocking)
+        end, start = longest_path(S, m, place, prev, lists, Fd, Bd, pf, pb, blocking)
+        # the dump: every listed task with its start and end, the others untouched
+        assert r["start"].shape == (2, S, m)
+        for kd in (FWD, BWD):
+            for k in range(S):
+                for j in range(m):
+                    if (kd, k, j) in end:
+                        assert r["end"][kd, k, j] == end[(kd, k, j)] and r["start"][kd, k, j] == start[(kd, k, j)], (trial, kd, k, j)
+                    else:
+                        assert r["end"][kd, k, j] == -1 and r["start"][kd, k, j] == -1
         n = dp * replicas
         has_next = {prev[q] for q in range(S) if prev[q] >= 0}
         fin, comp, comm, nar = [], [], [], 0
@@ -181,6 +190,8 @@ def test_random_schedules_against_the_task_graph(oracle_mod):
                 ar = (2, 7)[cls] + (2 * (n - 1) * G) // (n * (5, 1)[cls])
                 nar += 1
             fin.append(last + ar)
+            assert r["ar_window"][0][d] == (last if ar or (lists[d] and n > 1 and G > 0) else -1)
+            assert r["ar_window"][1][d] == (last + ar if ar or (lists[d] and n > 1 and G > 0) else -1)
             comp.append(sum(Fd[k] if kd == FWD else Bd[k] for kd, k, _ in lists[d]))
             sends = sum((pf[k] if kd == FWD else pb[k]) for kd, k, _ in lists[d])
             comm.append(sends + ar)

@@ -164,10 +164,17 @@ def _timeline_parity(H, oracle_mod, w, idx):
     out = ds.alloc_outputs(c, ev)
     ds.distsim_simulate(c, dw.cluster, ev, out)
     idx = np.asarray(idx, np.int64)
-    vch = np.ones(w.C, np.int64)
+    vch = np.ones(w.C, np.int64)                      # rows per device: chunks, or S / pp for explicit schedules (as a fraction)
+    rows_of_c = w.cand["pp"].astype(np.int64).copy()  # rows of the dump: stages or virtual stages
     if w.cand.get("chunks") is not None:
         vch = np.where(w.cand["schedule"] == 3, w.cand["chunks"], 1).astype(np.int64)
-    sizes = 2 * w.cand["pp"][idx].astype(np.int64) * vch[idx] * w.cand["m"][idx]
+        rows_of_c = rows_of_c * vch
+        if w.cand.get("schedule_off") is not None:
+            for cc in np.nonzero(w.cand["schedule"] == 4)[0]:
+                sid = int(w.cand["chunks"][cc])
+                if 0 <= sid < len(w.cand["schedule_off"]) - 1:
+                    rows_of_c[cc] = int(w.cand["schedule_words"][int(w.cand["schedule_off"][sid]) + 1])
+    sizes = 2 * rows_of_c[idx] * w.cand["m"][idx]
     off = np.concatenate([[0], np.cumsum(sizes)])
     dev = c.device
     start = torch.full((int(off[-1]),), -7, dtype=torch.int64, device=dev)
@@ -189,8 +196,20 @@ def _timeline_parity(H, oracle_mod, w, idx):
             assert (start[off[k]:off[k + 1]] == -7).all() and (ar0[k] == -1).all()
             assert (idle[off[k]:off[k + 1]] == -7).all()
             continue
-        S = pp * int(vch[i])                              # rows: stages, or virtual stages
-        want_idle = idle_before(r["start"], r["end"], int(w.cand["schedule"][i]), int(vch[i]))
+        S = int(rows_of_c[i])                             # rows: stages, or virtual stages
+        if int(w.cand["schedule"][i]) == 4:
+            from oracle.bubbles import idle_before_lists
+            from workloads.schedules import unpack_schedule
+            sid = int(w.cand["chunks"][i])
+            o0, o1 = int(w.cand["schedule_off"][sid]), int(w.cand["schedule_off"][sid + 1])
+            lists = unpack_schedule(w.cand["schedule_words"][o0:o1])[5]
+            want_idle = idle_before_lists(r["start"], r["end"], lists)
+            listed = r["start"] >= 0
+            got = idle[off[k]:off[k + 1]].reshape(2, S, m)
+            assert np.array_equal(got[listed], want_idle[listed]) and (got[~listed] == -7).all(), (i, "idle")
+            idle[off[k]:off[k + 1]] = want_idle.reshape(-1)          # checked; let the common line below pass
+        else:
+            want_idle = idle_before(r["start"], r["end"], int(w.cand["schedule"][i]), int(vch[i]))
         assert np.array_equal(idle[off[k]:off[k + 1]].reshape(2, S, m), want_idle), (i, "idle")
         assert np.array_equal(start[off[k]:off[k + 1]].reshape(2, S, m), r["start"]), (i, "start")
         assert np.array_equal(end[off[k]:off[k + 1]].reshape(2, S, m), r["end"]), (i, "end")
@@ -609,6 +628,10 @@ def test_explicit_schedules(H, oracle_mod):
     ora = oracle_mod.simulate(w, nthreads=NT)
     assert (ora["status"][w.cand["schedule"] == 4] == 1).all()
     H.assert_same(H.run_hip(w, table=False), ora, what="explicit without tables")
+    # dump and bubbles of explicit candidates next to the others
+    w = mk(costs, mk_cluster(N, blocking=1), rows, name="explicit dump")
+    w.cand["schedule_off"], w.cand["schedule_words"] = off, words
+    _timeline_parity(H, oracle_mod, w, np.arange(0, w.C, 2))
 
 
 def test_invalid_range_and_capacity_status(H, oracle_mod):

@@ -288,9 +288,11 @@ def make_workload(name: str, **kw) -> Workload:
 
 
 def subset(w: Workload, idx) -> Workload:
-    """The same tables with only the candidates ``idx`` (partition pool shared, offsets kept)."""
+    """The same tables with only the candidates ``idx`` (partition pool and explicit schedules shared,
+    offsets kept)."""
     idx = np.asarray(idx, dtype=np.int64)
-    cand = {k: (v if k == "part_pool" else v[idx].copy()) for k, v in w.cand.items()}
+    shared = ("part_pool", "schedule_off", "schedule_words")
+    cand = {k: (v if k in shared else v[idx].copy()) for k, v in w.cand.items()}
     return Workload(w.name + "[subset]", w.costs, dict(w.cluster), cand, w.notes, dict(w.meta))
 
 

@@ -33,6 +33,17 @@ def pack_schedule(pp: int, stages, m: int, nparts: int, replicas: int, lists) ->
     return np.ascontiguousarray(w)
 
 
+def unpack_schedule(words):
+    """Inverse of pack_schedule: (pp, stages, m, nparts, replicas, lists)."""
+    w = np.asarray(words).astype(np.int64)
+    pp, S, m, nparts, replicas = (int(x) for x in w[:5])
+    off = w[5:5 + pp + 1]
+    st = w[5 + pp + 1:5 + pp + 1 + 3 * S].reshape(S, 3)
+    tasks = w[5 + pp + 1 + 3 * S:] & 0xffffffff
+    lists = [[(int(x >> 31), int((x >> 16) & 0x7fff), int(x & 0xffff)) for x in tasks[off[d]:off[d + 1]]] for d in range(pp)]
+    return pp, [tuple(int(v) for v in r) for r in st], m, nparts, replicas, lists
+
+
 def pack_schedules(blocks):
     """Offsets [n + 1] and the word pool of several schedules."""
     off = np.zeros(len(blocks) + 1, np.int64)
