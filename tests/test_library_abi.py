@@ -51,3 +51,42 @@ def test_product_package_does_not_import_the_oracle():
             if f.endswith((".py", ".hip", ".hpp", ".h")):
                 txt = open(os.path.join(dirpath, f)).read()
                 assert "oracle" not in txt.lower(), os.path.join(dirpath, f)
+
+
+def test_binding_structs_match_the_header(tmp_path):
+    """The ctypes mirrors in the binding have the size and the field offsets that a C compiler
+    gives the structs of include/distsim.h."""
+    import ctypes
+    import subprocess
+    from paper_2306_08423_amd import binding as b
+    pairs = [("distsim_costs", b._Costs), ("distsim_cluster", b._Cluster), ("distsim_candidates", b._Cand),
+             ("distsim_events", b._Events)]
+    lines = ['#include <stdio.h>', '#include <stddef.h>', '#include "distsim.h"', 'int main(void) {']
+    for cname, cls in pairs:
+        lines.append(f'printf("{cname} %zu\\n", sizeof({cname}));')
+        for fname, _ in cls._fields_:
+            lines.append(f'printf("{cname}.{fname} %zu\\n", offsetof({cname}, {fname}));')
+    lines += ['return 0; }']
+    src = tmp_path / "layout.c"
+    src.write_text("\n".join(lines))
+    exe = tmp_path / "layout"
+    subprocess.check_call(["gcc", "-I", os.path.join(ROOT, "include"), "-o", str(exe), str(src)])
+    got = dict(l.split() for l in subprocess.check_output([str(exe)], text=True).splitlines())
+    for cname, cls in pairs:
+        assert int(got[cname]) == ctypes.sizeof(cls), cname
+        for fname, _ in cls._fields_:
+            assert int(got[f"{cname}.{fname}"]) == getattr(cls, fname).offset, (cname, fname)
+
+
+def test_kernel_names_of_library_and_binding_agree():
+    import ctypes
+    import paper_2306_08423_amd as ds
+    lib = ds.load_library()
+    lib.distsim_kernel_name.restype = ctypes.c_char_p
+    lib.distsim_kernel_name.argtypes = [ctypes.c_int]
+    names = [lib.distsim_kernel_name(k).decode() for k in range(len(ds.binding.KERNELS))]
+    assert names == list(ds.binding.KERNELS)
+    assert lib.distsim_kernel_name(len(names)).decode() == "?"
+    hdr = open(os.path.join(ROOT, "include", "distsim.h")).read()
+    ids = re.findall(r"DISTSIM_K_([A-Z_]+)", hdr[hdr.index("enum {"):hdr.index("DISTSIM_K_COUNT")])
+    assert len(ids) == len(names)
