@@ -32,7 +32,7 @@ def kernel_source_hash() -> str:
 
 
 def read_traffic(workload: str):
-    """HBM bytes per step of the two simulate launches (k_simulate + k_simulate_gpipe) from the
+    """HBM bytes per step of the two simulate kernels (k_simulate, k_simulate_gpipe) from the
     committed counter summary; None when the kernel sources changed after the counters were taken."""
     p = os.path.join(ROOT, "profiles", f"pmc_k_simulate_{workload}.txt")
     if not os.path.exists(p):
@@ -214,24 +214,25 @@ def main() -> int:
     m = w.cand["m"].astype(np.int64)
     pp = w.cand["pp"].astype(np.int64)
     tasks = int((2 * m * pp).sum())
-    # the sweep is two launches per step that share the candidates: k_simulate (everything but
-    # pairs of GPipe items) and k_simulate_gpipe; the roofline figure covers both
+    # the sweep is two kernels per step that share the candidates and run side by side: k_simulate
+    # (everything but pairs of GPipe items) and, on a stream of the library's context,
+    # k_simulate_gpipe; the library's timer of k_simulate spans both, and so does the roofline figure
     sim_ms, sim_n = kt["k_simulate"]
     gp_ms, gp_n = kt["k_simulate_gpipe"]
-    sim_avg_s = (sim_ms / max(sim_n, 1) + gp_ms / max(gp_n, 1)) / 1e3
+    sim_avg_s = sim_ms / max(sim_n, 1) / 1e3
     # algorithmic HBM bytes of k_simulate per launch: descriptor in (32 B), batch_ns and num_events
     # out (16 B) per candidate; partition byte in (1 B) and comp/comm/util out (24 B) per stage
     sim_bytes = C * (32 + 16) + S * (1 + 24)
     roofline = {
-        "kernel": "k_simulate + k_simulate_gpipe", "bound": "alu",
+        "kernel": "k_simulate || k_simulate_gpipe", "bound": "alu",
         "achieved": FLOPS_PER_TASK * tasks / sim_avg_s / 1e12, "peak": ALU_PEAK_TFLOPS, "unit": "TFLOP/s",
         "traffic": read_traffic(args.workload),
         "avg_launch_ms": sim_avg_s * 1e3, "launches": sim_n,
-        "launch_ms": {"k_simulate": sim_ms / max(sim_n, 1), "k_simulate_gpipe": gp_ms / max(gp_n, 1)},
+        "launch_ms": {"span": sim_ms / max(sim_n, 1), "k_simulate_gpipe": gp_ms / max(gp_n, 1)},
     }
     roofline["frac"] = roofline["achieved"] / roofline["peak"]
     roofline_hbm = {
-        "kernel": "k_simulate + k_simulate_gpipe", "bound": "hbm", "achieved": sim_bytes / sim_avg_s / 1e9, "peak": HBM_PEAK_GBS,
+        "kernel": "k_simulate || k_simulate_gpipe", "bound": "hbm", "achieved": sim_bytes / sim_avg_s / 1e9, "peak": HBM_PEAK_GBS,
         "unit": "GB/s", "algorithmic_bytes_per_launch": sim_bytes,
     }
     roofline_hbm["frac"] = roofline_hbm["achieved"] / HBM_PEAK_GBS

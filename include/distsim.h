@@ -99,10 +99,13 @@ extern "C" {
 
 typedef struct distsim_ctx distsim_ctx;   /* opaque; host-side state only (device id, error text, timers) */
 
-/* Create / destroy a context bound to HIP device `hip_device`.  Host memory only.
+/* Create / destroy a context bound to HIP device `hip_device`: host memory, one HIP stream of
+ * default priority and two events (distsim_simulate runs a second kernel next to the first on
+ * that stream, forked from and joined to the caller's stream; that is safe under stream capture).
+ * A context serves one host thread at a time.
  * One tuning knob is read from the environment here: DISTSIM_SPLIT_MIN_ITEMS, the number of
  * 64-lane groups of stages from which distsim_simulate gives the GPipe candidates a launch of
- * their own (default 98304; 0 = always).  Results do not depend on it. */
+ * their own (default 16384; 0 = always).  Results do not depend on it. */
 int         distsim_create(distsim_ctx **out, int hip_device);
 void        distsim_destroy(distsim_ctx *ctx);
 /* Text of the last error on this context; valid until the next call on it. */
@@ -351,6 +354,8 @@ int distsim_comm_event_times(distsim_ctx *ctx, int64_t n, const int32_t *kind, c
  * Optional kernel timing with HIP events recorded on the caller's stream around each kernel
  * launch.  distsim_timing_read blocks until the recorded launches have finished and returns
  * the accumulated time and launch count of one kernel, then clears that kernel's record.
+ * DISTSIM_K_SIMULATE spans the whole sweep of distsim_simulate, i.e. also the kernel that runs
+ * beside it on the context's stream (DISTSIM_K_SIMULATE_GPIPE, timed there on its own).
  */
 enum {
     DISTSIM_K_LAYER_TABLES = 0, DISTSIM_K_DECODE, DISTSIM_K_BINS, DISTSIM_K_SCATTER,

@@ -26,6 +26,10 @@ struct distsim_ctx {
     int device = 0;
     int num_cus = 256;
     int64_t split_min_items = kSplitMinItems;   // lists of fewer wave-items go through k_simulate alone
+    // k_simulate_gpipe runs next to k_simulate on a stream of the context (default priority),
+    // forked from and joined to the caller's stream with the two events
+    hipStream_t side = nullptr;
+    hipEvent_t fork = nullptr, join = nullptr;
     std::string err;
     bool timing = false;
     std::vector<TimedLaunch> rec[DISTSIM_K_COUNT];
@@ -137,6 +141,14 @@ int distsim_create(distsim_ctx** out, int hip_device) {
     hipDeviceProp_t prop;
     if (hipGetDeviceProperties(&prop, hip_device) == hipSuccess && prop.multiProcessorCount > 0)
         ctx->num_cus = prop.multiProcessorCount;
+    int prev = 0;
+    const bool had = hipGetDevice(&prev) == hipSuccess;
+    const bool made = hipSetDevice(hip_device) == hipSuccess &&
+                      hipStreamCreateWithFlags(&ctx->side, hipStreamNonBlocking) == hipSuccess &&
+                      hipEventCreateWithFlags(&ctx->fork, hipEventDisableTiming) == hipSuccess &&
+                      hipEventCreateWithFlags(&ctx->join, hipEventDisableTiming) == hipSuccess;
+    if (had) (void)hipSetDevice(prev);
+    if (!made) { distsim_destroy(ctx); return DISTSIM_EHIP; }
     if (const char* e = getenv("DISTSIM_SPLIT_MIN_ITEMS")) {
         char* end = nullptr;
         const long long v = strtoll(e, &end, 10);
@@ -150,6 +162,9 @@ void distsim_destroy(distsim_ctx* ctx) {
     if (!ctx) return;
     for (auto& v : ctx->rec) for (auto& t : v) { (void)hipEventDestroy(t.start); (void)hipEventDestroy(t.stop); }
     for (auto& t : ctx->pool) { (void)hipEventDestroy(t.start); (void)hipEventDestroy(t.stop); }
+    if (ctx->fork) (void)hipEventDestroy(ctx->fork);
+    if (ctx->join) (void)hipEventDestroy(ctx->join);
+    if (ctx->side) (void)hipStreamDestroy(ctx->side);
     delete ctx;
 }
 
@@ -267,19 +282,29 @@ int distsim_simulate(distsim_ctx* ctx, const distsim_cluster* cluster, const dis
         Timer t(ctx, st, DISTSIM_K_SIM_INIT);
         hipLaunchKernelGGL(k_sim_init, dim3((int)((C + 255) / 256)), dim3(256), 0, st, events->status, C, batch_ns);
     }
-    {
+    if (cl.blocking == 2) {
         Timer t(ctx, st, DISTSIM_K_SIMULATE);
-        if (cl.blocking == 2)
-            hipLaunchKernelGGL(k_simulate_links, dim3(simulate_grid(ctx, C)), dim3(256), 0, st, co, cl, ca, ws, ev, out);
-        else
-            hipLaunchKernelGGL(k_simulate, dim3(general_grid(ctx, C)), dim3(256), 0, st, co, cl, ca, ws, ev, out,
-                               ctx->split_min_items);
-    }
-    if (cl.blocking != 2 && C >= ctx->split_min_items) {     // the pairs of GPipe items that k_simulate leaves out (none in a
-                                                       // list of fewer wave-items than that, and an item holds a candidate)
-        Timer t(ctx, st, DISTSIM_K_SIMULATE_GPIPE);
-        hipLaunchKernelGGL(k_simulate_gpipe, dim3(gpipe_grid(ctx, C)), dim3(256), 0, st, co, cl, ca, ws, ev, out,
+        hipLaunchKernelGGL(k_simulate_links, dim3(simulate_grid(ctx, C)), dim3(256), 0, st, co, cl, ca, ws, ev, out);
+    } else if (C < ctx->split_min_items) {
+        // a list of fewer candidates than that has fewer wave-items too: k_simulate takes all of it
+        Timer t(ctx, st, DISTSIM_K_SIMULATE);
+        hipLaunchKernelGGL(k_simulate, dim3(general_grid(ctx, C)), dim3(256), 0, st, co, cl, ca, ws, ev, out,
                            ctx->split_min_items);
+    } else {
+        // k_simulate and, for the pairs of GPipe items that it leaves out, k_simulate_gpipe, side
+        // by side: they write different rows.  The timer of k_simulate spans both.
+        Timer t(ctx, st, DISTSIM_K_SIMULATE);
+        HIP_TRY(hipEventRecord(ctx->fork, st));
+        HIP_TRY(hipStreamWaitEvent(ctx->side, ctx->fork, 0));
+        hipLaunchKernelGGL(k_simulate, dim3(general_grid(ctx, C)), dim3(256), 0, st, co, cl, ca, ws, ev, out,
+                           ctx->split_min_items);
+        {
+            Timer tg(ctx, ctx->side, DISTSIM_K_SIMULATE_GPIPE);
+            hipLaunchKernelGGL(k_simulate_gpipe, dim3(gpipe_grid(ctx, C)), dim3(256), 0, ctx->side, co, cl, ca, ws, ev, out,
+                               ctx->split_min_items);
+        }
+        HIP_TRY(hipEventRecord(ctx->join, ctx->side));
+        HIP_TRY(hipStreamWaitEvent(st, ctx->join, 0));
     }
     if (cd->chunks) {       // candidates of the interleaved schedule, if the caller has any
         Timer t(ctx, st, DISTSIM_K_SIMULATE_VIRTUAL);

@@ -565,7 +565,7 @@ __device__ __forceinline__ void simulate_items(const ClusterDev& cl, const CandD
 // the grid (about one pair per wavefront for large lists: the hardware's dispatch order is the
 // load balancing, and the items of the widest class, the longest, go first).
 
-constexpr int64_t kSplitMinItems = 98304;      // default of the threshold below
+constexpr int64_t kSplitMinItems = 16384;      // default of the threshold below
 
 // Item number t of one launch's share -> its place in visiting order.
 struct OwnedItem {

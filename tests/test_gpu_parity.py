@@ -280,14 +280,16 @@ def test_async_schedule(H, oracle_mod):
     H.assert_same(hip, oracle_mod.simulate(w, nthreads=NT), what=w.name)
 
 
-def test_graph_capture_and_replay(H, oracle_mod):
+@pytest.mark.parametrize("split", [False, True])
+def test_graph_capture_and_replay(H, oracle_mod, split):
     """The three calls allocate nothing and never synchronise, so a caller can record them into a
-    HIP graph; every replay (with eager work and synchronisation in between) must give the eager result."""
+    HIP graph; every replay (with eager work and synchronisation in between) must give the eager
+    result.  split: with the second sweep kernel forked onto the context's stream and joined."""
     import torch
     import paper_2306_08423_amd as ds
-    _say("[case] graph capture")
+    _say(f"[case] graph capture split={split}")
     w = make_workload("gpt48")
-    c = H.ctx()
+    c = H.ctx_split() if split else H.ctx()
     dw = ds.upload(w, c.device)
     ev = ds.alloc_events(c, dw.L, dw.V, dw.C, ds.stage_entries(w.cand["pp"]), table=False)
     out = ds.alloc_outputs(c, ev, util=True)
