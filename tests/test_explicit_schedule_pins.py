@@ -264,3 +264,46 @@ def test_invalid_explicit_schedules(oracle_mod):
     assert status(pack_schedule(pp, stages, 1, pp, 1, cyc), row=(1, 1, pp, 1, 4, None, 0)) == 1
     okl = [[(FWD, 0, 0), (FWD, 3, 0), (BWD, 3, 0), (BWD, 0, 0)], [(FWD, 2, 0), (FWD, 1, 0), (BWD, 1, 0), (BWD, 2, 0)]]
     assert status(pack_schedule(pp, stages, 1, pp, 1, okl), row=(1, 1, pp, 1, 4, None, 0)) == 0
+
+
+def test_pack_and_unpack_are_inverse():
+    from workloads.schedules import unpack_schedule
+    rng = np.random.default_rng(3)
+    for _ in range(50):
+        pp, S, m = int(rng.integers(1, 9)), int(rng.integers(1, 20)), int(rng.integers(1, 9))
+        place, prev, lists = random_schedule(rng, pp, S, m)
+        stages = [(place[k], int(rng.integers(0, 4)), prev[k]) for k in range(S)]
+        blk = pack_schedule(pp, stages, m, 4, 2, lists)
+        assert blk.dtype == np.int32
+        got = unpack_schedule(blk)
+        assert got == (pp, stages, m, 4, 2, lists)
+
+
+def test_generated_lists_are_complete_and_run_to_their_end(oracle_mod):
+    """Every generator lists each of its tasks once, on the device that holds the stage, and the
+    oracle runs the schedule to its end for every shape tried."""
+    for pp in (1, 2, 3, 4, 5, 8, 13, 16):
+        for m in (1, 2, 3, 7, 16):
+            cases = [(chain(pp), gpipe_lists(pp, m), 1, pp, set(range(m))), (chain(pp), dapple_lists(pp, m), 1, pp, set(range(m)))]
+            if pp % 2 == 0:
+                cases.append((bidirectional_stages(pp), bidirectional_lists(pp, m), 2, pp, None))
+            for v in (1, 2, 3):
+                if m % pp == 0 and pp * v <= 16:
+                    cases.append((interleaved_stages(pp, v), interleaved_lists(pp, v, m), 1, pp * v, set(range(m))))
+            for stages, lists, replicas, nparts, mbs in cases:
+                seen = set()
+                for d, lst in enumerate(lists):
+                    for t in lst:
+                        assert t not in seen and stages[t[1]][0] == d
+                        seen.add(t)
+                if mbs is not None:
+                    assert seen == {(kd, k, j) for kd in (FWD, BWD) for k in range(len(stages)) for j in mbs}
+                else:                                   # two pipelines: every micro-batch through exactly one of them
+                    for j in range(m):
+                        pipes = {k // pp for kd, k, jj in seen if jj == j}
+                        assert len(pipes) == 1
+                L = max(nparts, 2)
+                costs = mk_costs([7] * L, [11] * L, act=[64] * L, grad=[100] * L)
+                w = with_schedules(mk(costs, mk_cluster(pp), [(1, 1, pp, m, 4, None, 0)]),
+                                   [pack_schedule(pp, stages, m, nparts, replicas, lists)], [0])
+                assert int(oracle_mod.simulate(w)["status"][0]) == 0, (pp, m, len(stages))
