@@ -271,6 +271,8 @@ def main() -> int:
                    "candidates": C, "valid": status_ok},
         "events_per_s": nev * args.steps / dt, "stage_tasks_per_s": tasks * args.steps / dt,
         "kernel_ms": {k: (v[0] / max(v[1], 1)) * (v[1] / args.steps) for k, v in kt.items()},
+        "kernel_ms_note": "k_simulate is the span of the two sweep kernels, which run side by side "
+                          "(k_simulate_gpipe on a stream of the library's context); the other entries are single kernels",
         "roofline": roofline, "roofline_hbm": roofline_hbm,
         "graph_replay": graph, "timeline": timeline, "ingest": ingest, "cpu_baseline": cpu_baseline, "parity": parity,
     }
