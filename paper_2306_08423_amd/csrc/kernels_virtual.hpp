@@ -102,10 +102,13 @@ __device__ __forceinline__ void virtual_candidate(const CostsDev& co, const Clus
 
     // the rounds
     const int64_t n = (int64_t)m * vch;                       // slots per direction
-    const int group = pp * vch;                               // slots per group of pp micro-batches
     int64_t W = 2ll * (pp - d - 1) + (int64_t)(vch - 1) * pp; // warm-up forwards
     if (W > n) W = n;
     int64_t iF = 0, iB = 0;
+    // slot i of a direction = group (i / (pp vch)), position of the chunk (i mod (pp vch)) / pp,
+    // place in the chunk i mod pp; kept as counters: r, c and the group's first micro-batch
+    int rF = 0, cF = 0, rB = 0, cB = 0;
+    int64_t jF0 = 0, jB0 = 0;
     double own = 0.0;
     bool stuck = false;
     const int64_t max_rounds = 4 * n + 8 * pp + 64;
@@ -118,8 +121,8 @@ __device__ __forceinline__ void virtual_candidate(const CostsDev& co, const Clus
         if (todo) {
             const bool fwd = iF < W || (iF < n && iF - W == iB);
             const int64_t i = fwd ? iF : iB;
-            const int w = (int)(i % group);
-            const int cch = fwd ? w / pp : vch - 1 - w / pp;
+            // chunk and micro-batch of the slot, from the counters kept with iF / iB
+            const int cch = fwd ? cF : vch - 1 - cB;
             const int k = cch * pp + d;
             bool ok = true;
             double arrive = 0.0;
@@ -150,10 +153,15 @@ __device__ __forceinline__ void virtual_candidate(const CostsDev& co, const Clus
             if (ok) {
                 const double t0 = arrive > own ? arrive : own;
                 own = t0 + (fwd ? sm.durF[k] : sm.durB[k]);
-                if (fwd) { sm.ringF[d][i & (kVirtRing - 1)] = own; iF++; }
-                else { sm.ringB[d][i & (kVirtRing - 1)] = own; iB++; }
+                const int64_t j = fwd ? jF0 + rF : jB0 + rB;                    // micro-batch of the slot
+                if (fwd) {
+                    sm.ringF[d][i & (kVirtRing - 1)] = own; iF++;
+                    if (++rF == pp) { rF = 0; if (++cF == vch) { cF = 0; jF0 += pp; } }
+                } else {
+                    sm.ringB[d][i & (kVirtRing - 1)] = own; iB++;
+                    if (++rB == pp) { rB = 0; if (++cB == vch) { cB = 0; jB0 += pp; } }
+                }
                 if (DUMP) {
-                    const int64_t j = (i / group) * pp + w % pp;                 // micro-batch of the slot
                     const int64_t e = ((int64_t)(fwd ? 0 : 1) * S + k) * m + j;
                     dump.start[e] = double_to_i64(t0);
                     dump.end[e] = double_to_i64(own);
