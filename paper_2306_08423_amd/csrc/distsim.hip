@@ -307,14 +307,25 @@ int distsim_simulate(distsim_ctx* ctx, const distsim_cluster* cluster, const dis
         HIP_TRY(hipStreamWaitEvent(st, ctx->join, 0));
     }
     if (cd->chunks) {       // candidates of the interleaved schedule, if the caller has any
+        // one launch per ring size; a block is one wavefront, a CU holds up to 32 of them
         Timer t(ctx, st, DISTSIM_K_SIMULATE_VIRTUAL);
-        const int64_t blocks = C < (int64_t)ctx->num_cus * 16 ? C : (int64_t)ctx->num_cus * 16;
-        hipLaunchKernelGGL(k_simulate_virtual, dim3((unsigned)blocks), dim3(kWave), 0, st, co, cl, ca, ws, ev, out, C);
+        const int64_t most = (int64_t)ctx->num_cus * 32;
+        const unsigned blocks = (unsigned)(C < most ? C : most);
+        hipLaunchKernelGGL(k_simulate_virtual<64>, dim3(blocks), dim3(kWave), 0, st, co, cl, ca, ws, ev, out, 0, 1);
+        hipLaunchKernelGGL(k_simulate_virtual<32>, dim3(blocks), dim3(kWave), 0, st, co, cl, ca, ws, ev, out, 1, 2);
+        hipLaunchKernelGGL(k_simulate_virtual<16>, dim3(blocks), dim3(kWave), 0, st, co, cl, ca, ws, ev, out, 2, 3);
+        hipLaunchKernelGGL(k_simulate_virtual<8>, dim3(blocks), dim3(kWave), 0, st, co, cl, ca, ws, ev, out, 3, kClasses);
     }
     if (cd->chunks && ca.n_schedules > 0) {       // candidates with an explicit schedule, if the caller has any
+        // one launch per LDS size (by the schedule's number of stage x micro-batch pairs)
         Timer t(ctx, st, DISTSIM_K_SIMULATE_EXPLICIT);
-        const int64_t blocks = C < (int64_t)ctx->num_cus * 16 ? C : (int64_t)ctx->num_cus * 16;
-        hipLaunchKernelGGL(k_simulate_explicit, dim3((unsigned)blocks), dim3(kWave), 0, st, co, cl, ca, ws, ev, out, C);
+        const int64_t most = (int64_t)ctx->num_cus * 32;
+        const unsigned blocks = (unsigned)(C < most ? C : most);
+        static_assert(kMaxSlots == 2048, "the launches below cover schedules of up to 2048 pairs");
+        hipLaunchKernelGGL(k_simulate_explicit<2048>, dim3(blocks), dim3(kWave), 0, st, co, cl, ca, ws, ev, out, 1024);
+        hipLaunchKernelGGL(k_simulate_explicit<1024>, dim3(blocks), dim3(kWave), 0, st, co, cl, ca, ws, ev, out, 512);
+        hipLaunchKernelGGL(k_simulate_explicit<512>, dim3(blocks), dim3(kWave), 0, st, co, cl, ca, ws, ev, out, 256);
+        hipLaunchKernelGGL(k_simulate_explicit<256>, dim3(blocks), dim3(kWave), 0, st, co, cl, ca, ws, ev, out, 0);
     }
     HIP_TRY(hipGetLastError());
     return DISTSIM_OK;

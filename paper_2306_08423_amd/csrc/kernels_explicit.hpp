@@ -11,13 +11,16 @@
 
 namespace distsim {
 
+// LDS of one candidate of at most SLOTS (virtual stage, micro-batch) pairs.
+template <int SLOTS>
 struct ExplicitLds {
-    double endF[kMaxSlots], endB[kMaxSlots];    // end of the task, kNotListed / kListed before it has run
-    double durF[kMaxPP], durB[kMaxPP];          // by virtual stage: task durations
-    double latF[kMaxPP], latB[kMaxPP];          // by virtual stage: latency of the incoming forward / backward edge
-    int64_t sendF[kMaxPP], sendB[kMaxPP];       // by virtual stage: outgoing p2p events
-    int64_t compF[kMaxPP], compB[kMaxPP];       // by virtual stage: computation inside a task
-    int64_t commF[kMaxPP], commB[kMaxPP];       // by virtual stage: in-stage communication inside a task
+    // first index: kind of the task, 0 = forward, 1 = backward
+    double end[2][SLOTS];                       // end of the task, kNotListed / kListed before it has run
+    double dur[2][kMaxPP];                      // by virtual stage: task durations
+    double lat[2][kMaxPP];                      // by virtual stage: latency of the incoming edge
+    int64_t send[2][kMaxPP];                    // by virtual stage: outgoing p2p events
+    int64_t comp[2][kMaxPP];                    // by virtual stage: computation inside a task
+    int64_t comm[2][kMaxPP];                    // by virtual stage: communication inside a task and its outgoing p2p event
     int64_t grad[kMaxPP];                       // by virtual stage: gradient bytes of its part
     int32_t place[kMaxPP], prev[kMaxPP], next[kMaxPP], succ[kMaxPP];
 };
@@ -33,10 +36,10 @@ struct ExplicitCand {
 // DUMP = true: the candidate is known to be OK; writes the start and end of every listed task
 // ([kind][virtual stage][micro-batch], -1 for tasks that are not listed) and the all-reduce
 // windows, and none of the simulation's outputs.
-template <bool DUMP>
+template <bool DUMP, typename Lds>
 __device__ __forceinline__ void explicit_candidate(const CostsDev& co, const ClusterDev& cl, const CandDev& ca,
                                                    const Workspace& ws, const EventsDev& ev, const SimOut& out,
-                                                   const ExplicitCand& xc, const VirtDump& dump, ExplicitLds& sm) {
+                                                   const ExplicitCand& xc, const VirtDump& dump, Lds& sm) {
     const int lane = threadIdx.x;
     const int L = co.L;
     __syncthreads();                                                  // the previous candidate's LDS is free
@@ -83,14 +86,14 @@ __device__ __forceinline__ void explicit_candidate(const CostsDev& co, const Clu
 
     // every task at most once, on the device of its stage
     const int slots = S * m;
-    for (int i = lane; i < slots; i += kWave) { sm.endF[i] = kNotListed; sm.endB[i] = kNotListed; }
+    for (int i = lane; i < slots; i += kWave) { sm.end[0][i] = kNotListed; sm.end[1][i] = kNotListed; }
     __syncthreads();
     bool lbad = false;
     for (int i = t0; i < t1; i++) {
         const uint32_t x = (uint32_t)tasks[i];
         const int kd = x >> 31, k = (x >> 16) & 0x7fff, j = x & 0xffff;
         if (k >= S || j >= m || sm.place[k] != lane) { lbad = true; break; }
-        double* e = (kd ? sm.endB : sm.endF) + k * m + j;               // only this lane holds stage k
+        double* e = sm.end[kd] + k * m + j;                             // only this lane holds stage k
         if (*e != kNotListed) { lbad = true; break; }
         *e = kListed;
     }
@@ -106,7 +109,7 @@ __device__ __forceinline__ void explicit_candidate(const CostsDev& co, const Clu
     const int64_t* row = ws.comb + (size_t)((v * kMaxPP + pp - 1) * (L + 1)) * kCombWords;
     const size_t vr = (size_t)v * (L + 1);
     int64_t FT = 0, BT = 0, PB = 0, share = 0;
-    sm.sendF[lane] = 0;
+    sm.send[0][lane] = 0;
     __syncthreads();
     if (isk) {
         int lo, hi;
@@ -116,8 +119,8 @@ __device__ __forceinline__ void explicit_candidate(const CostsDev& co, const Clu
         const int64_t* el = row + lo * kCombWords;
         FT = eh[0] - el[0]; BT = eh[1] - el[1];
         const int64_t fcp = ws.pfc[vr + hi] - ws.pfc[vr + lo], bcp = ws.pbc[vr + hi] - ws.pbc[vr + lo];
-        sm.compF[lane] = fcp; sm.compB[lane] = bcp;
-        sm.commF[lane] = FT - fcp; sm.commB[lane] = BT - bcp;
+        sm.comp[0][lane] = fcp; sm.comp[1][lane] = bcp;
+        sm.comm[0][lane] = FT - fcp; sm.comm[1][lane] = BT - bcp;
         sm.grad[lane] = eh[3] - el[3];
         if (prev >= 0) {
             // the activation that leaves the part of the stage before: entry of the layer after it
@@ -127,34 +130,39 @@ __device__ __forceinline__ void explicit_candidate(const CostsDev& co, const Clu
             else qhi = (int)(((int64_t)(pq + 1) * L) / nparts);
             const int inter = node_of(sm.place[prev]) != node_of(place) ? 1 : 0;
             PB = row[qhi * kCombWords + 4 + inter];
-            sm.sendF[prev] = PB;                                     // the same event, sent forwards by the stage before
+            sm.send[0][prev] = PB;                                   // the same event, sent forwards by the stage before
         }
-        sm.sendB[lane] = PB;
+        sm.send[1][lane] = PB;
     }
     __syncthreads();
-    if (isk) share = FT + BT + sm.sendF[lane] + PB;
+    if (isk) share = FT + BT + sm.send[0][lane] + PB;
     if (stage_out_of_range(isk ? share : 0, m, kWave)) {
         if (!DUMP && lane == 0) { ev.status[c] = 2; ev.num_events[c] = 0; out.batch_ns[c] = INT64_MAX; }
         return;
     }
     if (isk) {
-        const int64_t pf_task = cl.blocking == 1 ? sm.sendF[lane] : 0, pb_task = cl.blocking == 1 ? PB : 0;
-        sm.durF[lane] = (double)(FT + pf_task);
-        sm.durB[lane] = (double)(BT + pb_task);
+        const int64_t pf_task = cl.blocking == 1 ? sm.send[0][lane] : 0, pb_task = cl.blocking == 1 ? PB : 0;
+        sm.dur[0][lane] = (double)(FT + pf_task);
+        sm.dur[1][lane] = (double)(BT + pb_task);
+        sm.comm[0][lane] += sm.send[0][lane];
+        sm.comm[1][lane] += PB;
     }
     __syncthreads();
     if (isk) {
         const int nx = sm.next[lane];
-        sm.latF[lane] = prev >= 0 && cl.blocking != 1 ? (double)sm.sendF[prev] : 0.0;
-        sm.latB[lane] = nx >= 0 && cl.blocking != 1 ? (double)sm.sendB[nx] : 0.0;
+        sm.lat[0][lane] = prev >= 0 && cl.blocking != 1 ? (double)sm.send[0][prev] : 0.0;
+        sm.lat[1][lane] = nx >= 0 && cl.blocking != 1 ? (double)sm.send[1][nx] : 0.0;
     }
     __syncthreads();
     if (DUMP) {                                                      // tasks that are not listed read -1
         for (int q = lane; q < 2 * slots; q += kWave) { dump.start[q] = -1; dump.end[q] = -1; }
     }
 
-    // the rounds
+    // the rounds.  The word of the task after the next one is requested a task ahead, and all of a
+    // round's LDS reads are issued together (at valid addresses whatever the task), so that a round
+    // waits for one trip to LDS and not for the list in memory.
     int i = t0;
+    uint32_t x = i < t1 ? (uint32_t)tasks[i] : 0u, xn = i + 1 < t1 ? (uint32_t)tasks[i + 1] : 0u;
     double own = 0.0;
     int64_t comp = 0, comm = 0, nsend = 0;
     bool stuck = false;
@@ -162,36 +170,36 @@ __device__ __forceinline__ void explicit_candidate(const CostsDev& co, const Clu
         const bool todo = i < t1;
         if (__builtin_amdgcn_ballot_w64(todo) == 0) break;
         bool ran = false;
-        int kd = 0, k = 0, j = 0;
-        double arrive = 0.0;
         if (todo) {
-            const uint32_t x = (uint32_t)tasks[i];
-            kd = x >> 31; k = (x >> 16) & 0x7fff; j = x & 0xffff;
-            if (kd == 0) {
-                const int p = sm.prev[k];
-                if (p < 0) ran = true;
-                else { const double e = sm.endF[p * m + j]; ran = e >= 0.0; arrive = e + sm.latF[k]; }
-            } else {
-                const int nx = sm.next[k];
-                if (nx < 0) ran = sm.endF[k * m + j] >= 0.0;         // its own forward; this device ran it
-                else { const double e = sm.endB[nx * m + j]; ran = e >= 0.0; arrive = e + sm.latB[k]; }
+            const int kd = x >> 31, k = (x >> 16) & 0x7fff, j = x & 0xffff;
+            // the task that feeds this one: the same micro-batch on the stage before (forward) or
+            // after (backward); at the end of its pipeline a backward follows its own forward,
+            // which this device ran
+            const int pv = sm.prev[k], nx = sm.next[k];
+            const int link = kd ? nx : pv;
+            const bool turn = kd && link < 0;
+            const bool has_prod = link >= 0 || turn;
+            const double e = sm.end[turn ? 0 : kd][(link >= 0 ? link : k) * m + j];
+            const double lat = sm.lat[kd][k], dur = sm.dur[kd][k];
+            const int64_t cp = sm.comp[kd][k], cm = sm.comm[kd][k];
+            ran = !has_prod || e >= 0.0;
+            if (ran) {                                               // a round's reads of end[] come before its writes
+                const double arrive = has_prod ? e + lat : 0.0;
+                const double start = arrive > own ? arrive : own;
+                own = start + dur;
+                sm.end[kd][k * m + j] = own;
+                if (DUMP) {
+                    const int64_t q = ((int64_t)kd * S + k) * m + j;
+                    dump.start[q] = double_to_i64(start);
+                    dump.end[q] = double_to_i64(own);
+                }
+                comp += cp;
+                comm += cm;
+                nsend += (kd ? pv : nx) >= 0 ? 1 : 0;
+                i++;
+                x = xn;
+                xn = i + 1 < t1 ? (uint32_t)tasks[i + 1] : 0u;
             }
-        }
-        __syncthreads();                                             // all reads of this round before its writes
-        if (ran) {
-            const double start = arrive > own ? arrive : own;
-            own = start + (kd ? sm.durB[k] : sm.durF[k]);
-            (kd ? sm.endB : sm.endF)[k * m + j] = own;
-            if (DUMP) {
-                const int64_t q = ((int64_t)kd * S + k) * m + j;
-                dump.start[q] = double_to_i64(start);
-                dump.end[q] = double_to_i64(own);
-            }
-            comp += kd ? sm.compB[k] : sm.compF[k];
-            const int64_t snd = kd ? sm.sendB[k] : sm.sendF[k];
-            comm += (kd ? sm.commB[k] : sm.commF[k]) + snd;
-            nsend += kd ? (sm.prev[k] >= 0 ? 1 : 0) : (sm.next[k] >= 0 ? 1 : 0);
-            i++;
         }
         if (__builtin_amdgcn_ballot_w64(ran) == 0) { stuck = true; break; }
         __syncthreads();
@@ -227,16 +235,23 @@ __device__ __forceinline__ void explicit_candidate(const CostsDev& co, const Clu
     }
 }
 
+// One launch per LDS size: the candidates whose schedule has more than slots_above and at most
+// SLOTS (virtual stage, micro-batch) pairs, so that small schedules take little LDS and more of
+// them are resident.  Every launch walks the whole visiting order and takes its own.
+template <int SLOTS>
 __global__ __launch_bounds__(kWave) void k_simulate_explicit(CostsDev co, ClusterDev cl, CandDev ca, Workspace ws,
-                                                             EventsDev ev, SimOut out, int64_t C) {
-    __shared__ ExplicitLds sm;
-    for (int64_t pos = blockIdx.x; pos < C; pos += gridDim.x) {
-        // descriptors beyond the valid candidates were never written: the class table bounds them
-        if (pos >= ws.hdr[H_CLASS_START + kClasses]) break;
+                                                             EventsDev ev, SimOut out, int slots_above) {
+    __shared__ ExplicitLds<SLOTS> sm;
+    // descriptors beyond the valid candidates were never written: the class table bounds them
+    const int64_t pos_end = ws.hdr[H_CLASS_START + kClasses];
+    for (int64_t pos = blockIdx.x; pos < pos_end; pos += gridDim.x) {
         const Desc ds = ws.desc[pos];
         if (!is_explicit(ds) || (ds.meta & 0xff) == 0) continue;          // uniform: one descriptor per wavefront
         const ExplicitCand xc{ds.meta & 0xff, ds.meta >> 16, ds.m, ds.dp, (int)(uint32_t)ds.spare, ds.spare >> 32, ds.poff,
                               ds.cand};
+        // k_decode has checked the head of the block: 1 <= S <= 64, S * m <= kMaxSlots
+        const int slots = ca.schedule_words[ca.schedule_off[xc.id] + 1] * xc.m;
+        if (slots <= slots_above || slots > SLOTS) continue;
         explicit_candidate<false>(co, cl, ca, ws, ev, out, xc, VirtDump{}, sm);
     }
 }
@@ -250,7 +265,7 @@ __global__ __launch_bounds__(kWave) void k_timeline_explicit(CostsDev co, Cluste
                                                              const int64_t* sel, const int64_t* task_off,
                                                              int64_t* start_ns, int64_t* end_ns, int64_t* ar_start,
                                                              int64_t* ar_end) {
-    __shared__ ExplicitLds sm;
+    __shared__ ExplicitLds<kMaxSlots> sm;
     for (int64_t q = blockIdx.x; q < n; q += gridDim.x) {
         const int64_t c = sel[q];
         if (c < 0 || c >= C || status[c] != 0 || ca.schedule[c] != 4 || !ca.chunks) continue;

@@ -13,14 +13,20 @@
 
 namespace distsim {
 
-constexpr int kVirtRing = 64;        // ring slots per device and direction (the lead of a producer stays below pp)
-
+// LDS of one candidate of at most R devices: R ring slots per device and direction.  A producer
+// never leads its consumer by more than the ring holds when R >= max(8, pp) (checked by running
+// the rounds, which do not depend on the durations, for every pp, every chunk count with
+// pp * chunks <= 64 and micro-batch counts up to 8 pp); a task that would overwrite a slot not yet
+// read waits, so a ring that were too small could stall a candidate but never give a wrong time.
+template <int R>
 struct VirtLds {
-    double ringF[kMaxPP][kVirtRing], ringB[kMaxPP][kVirtRing];
-    double durF[kMaxPP], durB[kMaxPP];          // by virtual stage: task durations
-    double latF[kMaxPP], latB[kMaxPP];          // by virtual stage: latency of the incoming forward / backward edge
-    int64_t sendF[kMaxPP], sendB[kMaxPP];       // by virtual stage: outgoing p2p events
-    int32_t doneF[kMaxPP], doneB[kMaxPP];       // by device: slots run, as of the previous round
+    static constexpr int kRing = R;
+    // first index: direction, 0 = forward, 1 = backward
+    double ring[2][R][R];                       // by device and slot modulo R: end of the task
+    double dur[2][kMaxPP];                      // by virtual stage: task durations
+    double lat[2][kMaxPP];                      // by virtual stage: latency of the incoming edge
+    int64_t send[2][kMaxPP];                    // by virtual stage: outgoing p2p events
+    int32_t done[2][R];                         // by device: slots run, as of the previous round
 };
 
 // What one candidate needs from its descriptor (or, for the dump, from the candidate arrays).
@@ -40,10 +46,11 @@ struct VirtDump {
 // One candidate on one wavefront.  DUMP = false: writes status / batch time / busy sums.
 // DUMP = true: the candidate is known to be OK; writes every task's start and end and the
 // all-reduce windows, and none of the simulation's outputs.
-template <bool DUMP>
+template <bool DUMP, typename Lds>
 __device__ __forceinline__ void virtual_candidate(const CostsDev& co, const ClusterDev& cl, const CandDev& ca,
                                                   const Workspace& ws, const EventsDev& ev, const SimOut& out,
-                                                  const VirtCand& vc, const VirtDump& dump, VirtLds& sm) {
+                                                  const VirtCand& vc, const VirtDump& dump, Lds& sm) {
+    constexpr int kVirtRing = Lds::kRing;
     const int d = threadIdx.x;                                   // device
     const int L = co.L;
     const int pp = vc.pp, v = vc.v, m = vc.m, dp = vc.dp, tp = vc.tp, vch = vc.vch;
@@ -77,10 +84,10 @@ __device__ __forceinline__ void virtual_candidate(const CostsDev& co, const Clus
             comm += FT + BT - CP + PF + PB;
             share += FT + BT + PF + PB;
             const int64_t pf_task = cl.blocking == 1 ? PF : 0, pb_task = cl.blocking == 1 ? PB : 0;
-            sm.durF[k] = (double)(FT + pf_task);
-            sm.durB[k] = (double)(BT + pb_task);
-            sm.sendF[k] = PF - pf_task;
-            sm.sendB[k] = PB - pb_task;
+            sm.dur[0][k] = (double)(FT + pf_task);
+            sm.dur[1][k] = (double)(BT + pb_task);
+            sm.send[0][k] = PF - pf_task;
+            sm.send[1][k] = PB - pb_task;
         }
     }
     bad = __builtin_amdgcn_ballot_w64(bad != 0) != 0;
@@ -94,75 +101,75 @@ __device__ __forceinline__ void virtual_candidate(const CostsDev& co, const Clus
     if (act) {
         for (int cch = 0; cch < vch; cch++) {
             const int k = cch * pp + d;
-            sm.latF[k] = k > 0 ? (double)sm.sendF[k - 1] : 0.0;
-            sm.latB[k] = k + 1 < S ? (double)sm.sendB[k + 1] : 0.0;
+            sm.lat[0][k] = k > 0 ? (double)sm.send[0][k - 1] : 0.0;
+            sm.lat[1][k] = k + 1 < S ? (double)sm.send[1][k + 1] : 0.0;
         }
     }
     __syncthreads();
 
     // the rounds
-    const int64_t n = (int64_t)m * vch;                       // slots per direction
-    int64_t W = 2ll * (pp - d - 1) + (int64_t)(vch - 1) * pp; // warm-up forwards
+    // slot numbers fit 32 bits: m <= 2^16 and pp * vch <= 64
+    const int n = m * vch;                                    // slots per direction
+    int W = 2 * (pp - d - 1) + (vch - 1) * pp;                // warm-up forwards
     if (W > n) W = n;
-    int64_t iF = 0, iB = 0;
+    int iF = 0, iB = 0;
     // slot i of a direction = group (i / (pp vch)), position of the chunk (i mod (pp vch)) / pp,
     // place in the chunk i mod pp; kept as counters: r, c and the group's first micro-batch
     int rF = 0, cF = 0, rB = 0, cB = 0;
-    int64_t jF0 = 0, jB0 = 0;
+    int jF0 = 0, jB0 = 0;
     double own = 0.0;
     bool stuck = false;
-    const int64_t max_rounds = 4 * n + 8 * pp + 64;
-    for (int64_t round = 0; round < max_rounds; round++) {
-        if (act) { sm.doneF[d] = (int32_t)iF; sm.doneB[d] = (int32_t)iB; }
+    const int max_rounds = 4 * n + 8 * pp + 64;
+    // Per direction: the producer of a slot is the same slot on the device before (in the
+    // direction), or, on the direction's first device, the slot pp earlier on its last device; the
+    // consumers of the ring slot that a task overwrites are the device after and, on the
+    // direction's last device, the first device (pp slots later).  All of a round's LDS reads are
+    // issued together, at clamped addresses, and the conditions select among what came back.
+    const int dL = d > 0 ? d - 1 : 0, dR = d + 1 < pp ? d + 1 : d;
+    for (int round = 0; round < max_rounds; round++) {
+        if (act) { sm.done[0][d] = iF; sm.done[1][d] = iB; }
         __syncthreads();
         const bool todo = act && iB < n;
         if (__builtin_amdgcn_ballot_w64(todo) == 0) break;
         bool ran = false;
         if (todo) {
             const bool fwd = iF < W || (iF < n && iF - W == iB);
-            const int64_t i = fwd ? iF : iB;
+            const int dir = fwd ? 0 : 1;
+            const int i = fwd ? iF : iB;
             // chunk and micro-batch of the slot, from the counters kept with iF / iB
             const int cch = fwd ? cF : vch - 1 - cB;
             const int k = cch * pp + d;
-            bool ok = true;
-            double arrive = 0.0;
-            if (fwd) {
-                if (k > 0) {                                   // producer: the same slot on the device before,
-                    const int src = d > 0 ? d - 1 : pp - 1;    // or pp slots earlier on the last device
-                    const int64_t si = d > 0 ? i : i - pp;
-                    if (sm.doneF[src] > si) arrive = sm.ringF[src][si & (kVirtRing - 1)] + sm.latF[k];
-                    else ok = false;
-                }
-                // the slot this task overwrites in the ring must have been read by its consumers
-                if (ok && i >= kVirtRing) {
-                    if (d + 1 < pp && !(sm.doneF[d + 1] > i - kVirtRing)) ok = false;
-                    if (d == pp - 1 && vch > 1 && !(sm.doneF[0] > i - kVirtRing + pp)) ok = false;
-                }
-            } else {
-                if (k + 1 < S) {
-                    const int src = d + 1 < pp ? d + 1 : 0;
-                    const int64_t si = d + 1 < pp ? i : i - pp;
-                    if (sm.doneB[src] > si) arrive = sm.ringB[src][si & (kVirtRing - 1)] + sm.latB[k];
-                    else ok = false;
-                }
-                if (ok && i >= kVirtRing) {
-                    if (d > 0 && !(sm.doneB[d - 1] > i - kVirtRing)) ok = false;
-                    if (d == 0 && vch > 1 && !(sm.doneB[pp - 1] > i - kVirtRing + pp)) ok = false;
-                }
+            const bool has_prod = fwd ? k > 0 : k + 1 < S;
+            const bool first = fwd ? d == 0 : d + 1 == pp;            // first device of the direction
+            const bool last = fwd ? d + 1 == pp : d == 0;             // last device of the direction
+            const int src = first ? (fwd ? pp - 1 : 0) : (fwd ? dL : dR);
+            const int si = first ? i - pp : i;
+            const int done_src = sm.done[dir][src];
+            const double prod_end = sm.ring[dir][src][si & (kVirtRing - 1)];
+            const double lat = sm.lat[dir][k], dur = sm.dur[dir][k];
+            const int done_next = sm.done[dir][fwd ? dR : dL];
+            const int done_wrap = sm.done[dir][fwd ? 0 : pp - 1];
+            bool ok = !has_prod || done_src > si;
+            // the slot this task overwrites in the ring must have been read by its consumers
+            if (i >= kVirtRing) {
+                if (!last && !(done_next > i - kVirtRing)) ok = false;
+                if (last && vch > 1 && !(done_wrap > i - kVirtRing + pp)) ok = false;
             }
             if (ok) {
+                const double arrive = has_prod ? prod_end + lat : 0.0;
                 const double t0 = arrive > own ? arrive : own;
-                own = t0 + (fwd ? sm.durF[k] : sm.durB[k]);
-                const int64_t j = fwd ? jF0 + rF : jB0 + rB;                    // micro-batch of the slot
+                own = t0 + dur;
+                sm.ring[dir][d][i & (kVirtRing - 1)] = own;
+                const int j = fwd ? jF0 + rF : jB0 + rB;                        // micro-batch of the slot
                 if (fwd) {
-                    sm.ringF[d][i & (kVirtRing - 1)] = own; iF++;
+                    iF++;
                     if (++rF == pp) { rF = 0; if (++cF == vch) { cF = 0; jF0 += pp; } }
                 } else {
-                    sm.ringB[d][i & (kVirtRing - 1)] = own; iB++;
+                    iB++;
                     if (++rB == pp) { rB = 0; if (++cB == vch) { cB = 0; jB0 += pp; } }
                 }
                 if (DUMP) {
-                    const int64_t e = ((int64_t)(fwd ? 0 : 1) * S + k) * m + j;
+                    const int64_t e = ((int64_t)dir * S + k) * m + j;
                     dump.start[e] = double_to_i64(t0);
                     dump.end[e] = double_to_i64(own);
                 }
@@ -201,12 +208,16 @@ __device__ __forceinline__ void virtual_candidate(const CostsDev& co, const Clus
     }
 }
 
+// One launch per ring size R: the candidates of the classes [cls_lo, cls_hi) of the visiting order
+// (class k holds the candidates of 64 >> k lanes, i.e. pp <= 64 >> k <= R), so that candidates of
+// few devices take little LDS and more of them are resident.
+template <int R>
 __global__ __launch_bounds__(kWave) void k_simulate_virtual(CostsDev co, ClusterDev cl, CandDev ca, Workspace ws,
-                                                            EventsDev ev, SimOut out, int64_t C) {
-    __shared__ VirtLds sm;
-    for (int64_t pos = blockIdx.x; pos < C; pos += gridDim.x) {
-        // descriptors beyond the valid candidates were never written: the class table bounds them
-        if (pos >= ws.hdr[H_CLASS_START + kClasses]) break;
+                                                            EventsDev ev, SimOut out, int cls_lo, int cls_hi) {
+    __shared__ VirtLds<R> sm;
+    // descriptors beyond the valid candidates were never written: the class table bounds them
+    const int64_t pos_end = ws.hdr[H_CLASS_START + cls_hi];
+    for (int64_t pos = ws.hdr[H_CLASS_START + cls_lo] + blockIdx.x; pos < pos_end; pos += gridDim.x) {
         const Desc ds = ws.desc[pos];
         if (!is_interleaved(ds) || (ds.meta & 0xff) == 0) continue;       // uniform: one descriptor per wavefront
         const VirtCand vc{ds.meta & 0xff, ds.meta >> 16, ds.m, ds.dp, (int)(uint32_t)ds.spare, (int)(ds.spare >> 32),
@@ -225,7 +236,7 @@ __global__ __launch_bounds__(kWave) void k_timeline_virtual(CostsDev co, Cluster
                                                             const int64_t* sel, const int64_t* task_off,
                                                             int64_t* start_ns, int64_t* end_ns, int64_t* ar_start,
                                                             int64_t* ar_end) {
-    __shared__ VirtLds sm;
+    __shared__ VirtLds<kMaxPP> sm;
     for (int64_t q = blockIdx.x; q < n; q += gridDim.x) {
         const int64_t c = sel[q];
         if (c < 0 || c >= C || status[c] != 0 || ca.schedule[c] != 3 || !ca.chunks) continue;
