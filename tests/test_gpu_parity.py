@@ -636,6 +636,32 @@ def test_explicit_schedules(H, oracle_mod):
     _timeline_parity(H, oracle_mod, w, np.arange(0, w.C, 2))
 
 
+def test_maximum_micro_batch_count(H, oracle_mod):
+    """The largest micro-batch count the interface takes (2^16) with the deepest pipeline (64
+    stages, 131 198 levels), with few stages and with one; every schedule of the level sweeps; one
+    more micro-batch is invalid.  Also blocking p2p, buckets, the serialised links and the dump of
+    a candidate of 655 360 stage-tasks."""
+    _say("[case] maximum micro-batch count")
+    rng = np.random.default_rng(3)
+    L = 96
+    costs = mk_costs(rng.integers(0, 5000, (2, L)).tolist(), rng.integers(0, 9000, (2, L)).tolist(),
+                     fa=rng.integers(0, 300, (2, L)).tolist(), ba=rng.integers(0, 300, (2, L)).tolist(),
+                     act=(rng.integers(0, 100, (2, L)) * 64).tolist(), grad=rng.integers(0, 1 << 20, (2, L)).tolist(),
+                     tps=(1, 2))
+    N, M = 64 * 15, 1 << 16
+    rows = [(N // 64, 1, 64, M, 0, None), (N // 64, 1, 64, M, 1, None), (N // 64, 1, 64, M, 2, None),
+            (N // 10, 2, 5, M, 1, None), (N, 1, 1, M, 0, None), (N // 64, 1, 64, M + 1, 1, None),
+            (N // 3, 1, 3, M - 1, 0, None), (N // 64, 1, 64, M, 0, None)]
+    for blocking, bucket in ((0, 0), (1, 1 << 18), (2, 0)):
+        w = mk(costs, mk_cluster(N, blocking=blocking, bucket=bucket), rows)
+        ora = oracle_mod.simulate(w, nthreads=NT)
+        assert ora["status"].tolist() == [0, 0, 0, 0, 0, 1, 0, 0]
+        H.assert_same(H.run_hip(w), ora, what=f"m = 2^16, blocking={blocking} bucket={bucket}")
+        H.assert_same(H.run_hip(w, table=False, split=True), ora, what=f"m = 2^16, blocking={blocking}, GPipe launch")
+    w = mk(costs, mk_cluster(N), rows)
+    _timeline_parity(H, oracle_mod, w, [3])
+
+
 def test_invalid_range_and_capacity_status(H, oracle_mod):
     _say("[case] status codes")
     costs = mk_costs([10] * 4, [20] * 4, tps=(1,))
