@@ -112,6 +112,18 @@ __device__ __forceinline__ int64_t double_to_i64(double d) {
     return (int64_t)(((uint64_t)hi << 32) | lo);
 }
 
+// Boundary s of the uniform partition of L layers into `parts` parts: floor(s L / parts) for
+// 0 <= s <= parts <= 64 and L <= 255.  The product is below 2^15, so the fp32 quotient (reciprocal
+// and product, a few units in the last place) is off by at most one; the remainder corrects it.
+__device__ __forceinline__ int uniform_bound(int s, int L, int parts) {
+    const int x = s * L;
+    int q = (int)__fdividef((float)x, (float)parts);
+    const int r = x - q * parts;
+    if (r < 0) q--;
+    else if (r >= parts) q++;
+    return q;
+}
+
 // Truncating unsigned division.  Operands below 2^53 (the usual case) go through one
 // correctly rounded fp64 division and an exact integer fix-up of the quotient; anything
 // larger takes the generic 64-bit path.

@@ -426,7 +426,7 @@ __device__ __forceinline__ void stage_fetch_bounds(const CandDev& ca, int L, Sta
     x.lo = 0; x.hi = 0;
     if (x.s < pp) {
         if (x.d.poff >= 0) { x.lo = ca.part_pool[x.d.poff + x.s]; x.hi = ca.part_pool[x.d.poff + x.s + 1]; }
-        else { x.lo = (int)(((int64_t)x.s * L) / pp); x.hi = (int)(((int64_t)(x.s + 1) * L) / pp); }
+        else { x.lo = uniform_bound(x.s, L, pp); x.hi = uniform_bound((x.s + 1), L, pp); }
     }
 }
 

@@ -76,7 +76,7 @@ __device__ __forceinline__ void explicit_candidate(const CostsDev& co, const Clu
     int plo = 0, phi = 0;
     if (lane < nparts) {
         if (xc.poff >= 0) { plo = ca.part_pool[xc.poff + lane]; phi = ca.part_pool[xc.poff + lane + 1]; }
-        else { plo = (int)(((int64_t)lane * L) / nparts); phi = (int)(((int64_t)(lane + 1) * L) / nparts); }
+        else { plo = uniform_bound(lane, L, nparts); phi = uniform_bound((lane + 1), L, nparts); }
         if (phi <= plo || phi > L || (lane == 0 && plo != 0) || (lane == nparts - 1 && phi != L)) kbad = true;
     }
     if (__builtin_amdgcn_ballot_w64(kbad) != 0) { invalid(); return; }
@@ -114,7 +114,7 @@ __device__ __forceinline__ void explicit_candidate(const CostsDev& co, const Clu
     if (isk) {
         int lo, hi;
         if (xc.poff >= 0) { lo = ca.part_pool[xc.poff + part]; hi = ca.part_pool[xc.poff + part + 1]; }
-        else { lo = (int)(((int64_t)part * L) / nparts); hi = (int)(((int64_t)(part + 1) * L) / nparts); }
+        else { lo = uniform_bound(part, L, nparts); hi = uniform_bound((part + 1), L, nparts); }
         const int64_t* eh = row + hi * kCombWords;
         const int64_t* el = row + lo * kCombWords;
         FT = eh[0] - el[0]; BT = eh[1] - el[1];
@@ -127,7 +127,7 @@ __device__ __forceinline__ void explicit_candidate(const CostsDev& co, const Clu
             const int pq = st[3 * prev + 1];
             int qhi;
             if (xc.poff >= 0) qhi = ca.part_pool[xc.poff + pq + 1];
-            else qhi = (int)(((int64_t)(pq + 1) * L) / nparts);
+            else qhi = uniform_bound((pq + 1), L, nparts);
             const int inter = node_of(sm.place[prev]) != node_of(place) ? 1 : 0;
             PB = row[qhi * kCombWords + 4 + inter];
             sm.send[0][prev] = PB;                                   // the same event, sent forwards by the stage before

@@ -318,7 +318,7 @@ __device__ __forceinline__ void simulate_items(const ClusterDev& cl, const CandD
         int lo = 0, hi = 0;
         if (actv[u]) {
             if (d[u].poff >= 0) { lo = ca.part_pool[d[u].poff + s]; hi = ca.part_pool[d[u].poff + s + 1]; }
-            else { lo = (int)(((int64_t)s * L) / ppv[u]); hi = (int)(((int64_t)(s + 1) * L) / ppv[u]); }
+            else { lo = uniform_bound(s, L, ppv[u]); hi = uniform_bound((s + 1), L, ppv[u]); }
         }
         StageSums r;
         const int drop = stage_sums(cl, ws, L, width, s, ppv[u], v, d[u].m, dp, (int)d[u].spare, lo, hi, r);

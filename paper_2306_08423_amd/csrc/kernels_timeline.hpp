@@ -116,7 +116,7 @@ __global__ __launch_bounds__(kTlWaves * kWave) void k_timeline(CostsDev co, Clus
         int lo = 0, hi = 0;
         if (act) {
             if (poff >= 0) { lo = ca.part_pool[poff + s]; hi = ca.part_pool[poff + s + 1]; }
-            else { lo = (int)(((int64_t)s * L) / pp); hi = (int)(((int64_t)(s + 1) * L) / pp); }
+            else { lo = uniform_bound(s, L, pp); hi = uniform_bound((s + 1), L, pp); }
         }
         StageRow r;
         // a candidate whose partition or range check fails gets no entries

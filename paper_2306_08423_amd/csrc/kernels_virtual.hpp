@@ -72,7 +72,7 @@ __device__ __forceinline__ void virtual_candidate(const CostsDev& co, const Clus
             const int k = cch * pp + d;
             int lo, hi;
             if (vc.poff >= 0) { lo = ca.part_pool[vc.poff + k]; hi = ca.part_pool[vc.poff + k + 1]; }
-            else { lo = (int)(((int64_t)k * L) / S); hi = (int)(((int64_t)(k + 1) * L) / S); }
+            else { lo = uniform_bound(k, L, S); hi = uniform_bound((k + 1), L, S); }
             if (hi <= lo || hi > L || (k == 0 && lo != 0) || (k == S - 1 && hi != L)) { bad = 1; break; }
             const int64_t* eh = row + hi * kCombWords;
             const int64_t* el = row + lo * kCombWords;
