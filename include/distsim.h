@@ -100,12 +100,13 @@ extern "C" {
 typedef struct distsim_ctx distsim_ctx;   /* opaque; host-side state only (device id, error text, timers) */
 
 /* Create / destroy a context bound to HIP device `hip_device`: host memory, one HIP stream of
- * default priority and two events (distsim_simulate runs a second kernel next to the first on
- * that stream, forked from and joined to the caller's stream; that is safe under stream capture).
+ * default priority and two events (for long lists distsim_build_events and distsim_simulate run
+ * some kernels on that stream next to those on the caller's, forked from and joined to the
+ * caller's stream inside the call; that is safe under stream capture).
  * A context serves one host thread at a time.
- * One tuning knob is read from the environment here: DISTSIM_SPLIT_MIN_ITEMS, the number of
- * 64-lane groups of stages from which distsim_simulate gives the GPipe candidates a launch of
- * their own (default 16384; 0 = always).  Results do not depend on it. */
+ * One tuning knob is read from the environment here: DISTSIM_SPLIT_MIN_ITEMS, the list length
+ * from which the two calls use the second stream and distsim_simulate gives the GPipe
+ * candidates a launch of their own (default 16384; 0 = always).  Results do not depend on it. */
 int         distsim_create(distsim_ctx **out, int hip_device);
 void        distsim_destroy(distsim_ctx *ctx);
 /* Text of the last error on this context; valid until the next call on it. */

@@ -217,7 +217,19 @@ int distsim_build_events(distsim_ctx* ctx, const distsim_costs* costs, const dis
     out->cand = *cand;
 
     const int cblocks = (int)((C + 255) / 256);
-    {
+    // The layer tables do not depend on the candidates and nothing before k_stage_events reads
+    // them: for a long list they are built on the context's stream next to decode / bins / scatter.
+    const bool beside = C >= ctx->split_min_items;
+    if (beside) {
+        HIP_TRY(hipEventRecord(ctx->fork, st));
+        HIP_TRY(hipStreamWaitEvent(ctx->side, ctx->fork, 0));
+        {
+            Timer t(ctx, ctx->side, DISTSIM_K_LAYER_TABLES);
+            hipLaunchKernelGGL(k_layer_tables, dim3(costs->V * kMaxPP), dim3(kWave), 0, ctx->side, co, cl, ws);
+        }
+        HIP_TRY(hipEventRecord(ctx->join, ctx->side));
+        hipLaunchKernelGGL(k_clear_bins, dim3((kBins + 255) / 256), dim3(256), 0, st, ws);
+    } else {
         Timer t(ctx, st, DISTSIM_K_LAYER_TABLES);
         hipLaunchKernelGGL(k_layer_tables, dim3(costs->V * kMaxPP), dim3(kWave), 0, st, co, cl, ws);
         hipLaunchKernelGGL(k_clear_bins, dim3((kBins + 255) / 256), dim3(256), 0, st, ws);
@@ -232,10 +244,11 @@ int distsim_build_events(distsim_ctx* ctx, const distsim_costs* costs, const dis
         hipLaunchKernelGGL(k_bins, dim3(1), dim3(kBinsBlock), 0, st, ws, out->stage_cap);
     }
     if (C > 0) {
-        {
-            Timer t(ctx, st, DISTSIM_K_SCATTER);
-            hipLaunchKernelGGL(k_scatter, dim3(cblocks), dim3(256), 0, st, ca, C, ws, ev);
-        }
+        Timer t(ctx, st, DISTSIM_K_SCATTER);
+        hipLaunchKernelGGL(k_scatter, dim3(cblocks), dim3(256), 0, st, ca, C, ws, ev);
+    }
+    if (beside) HIP_TRY(hipStreamWaitEvent(st, ctx->join, 0));       // what follows on the caller's stream sees the tables
+    if (C > 0) {
         if (out->stage_tab && out->stage_cap > 0) {
             Timer t(ctx, st, DISTSIM_K_STAGE_EVENTS);
             hipLaunchKernelGGL(k_stage_events, dim3(item_grid(ctx, C)), dim3(256), 0, st, co, cl, ca, ws, ev);
@@ -278,7 +291,10 @@ int distsim_simulate(distsim_ctx* ctx, const distsim_cluster* cluster, const dis
     EventsDev ev{events->stage_cap, events->status, events->stage_pos, events->stage_tab, events->stage_layers,
                  events->num_events};
     SimOut out{batch_ns, comp_busy_ns, comm_busy_ns, util};
-    {
+    // k_sim_init marks the candidates that k_decode rejected; the sweeps write the others' results,
+    // so it may run beside them
+    const bool beside = cl.blocking != 2 && C >= ctx->split_min_items;
+    if (!beside) {
         Timer t(ctx, st, DISTSIM_K_SIM_INIT);
         hipLaunchKernelGGL(k_sim_init, dim3((int)((C + 255) / 256)), dim3(256), 0, st, events->status, C, batch_ns);
     }
@@ -298,6 +314,10 @@ int distsim_simulate(distsim_ctx* ctx, const distsim_cluster* cluster, const dis
         HIP_TRY(hipStreamWaitEvent(ctx->side, ctx->fork, 0));
         hipLaunchKernelGGL(k_simulate, dim3(general_grid(ctx, C)), dim3(256), 0, st, co, cl, ca, ws, ev, out,
                            ctx->split_min_items);
+        {
+            Timer ti(ctx, ctx->side, DISTSIM_K_SIM_INIT);
+            hipLaunchKernelGGL(k_sim_init, dim3((int)((C + 255) / 256)), dim3(256), 0, ctx->side, events->status, C, batch_ns);
+        }
         {
             Timer tg(ctx, ctx->side, DISTSIM_K_SIMULATE_GPIPE);
             hipLaunchKernelGGL(k_simulate_gpipe, dim3(gpipe_grid(ctx, C)), dim3(256), 0, ctx->side, co, cl, ca, ws, ev, out,
