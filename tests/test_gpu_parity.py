@@ -636,6 +636,26 @@ def test_explicit_schedules(H, oracle_mod):
     _timeline_parity(H, oracle_mod, w, np.arange(0, w.C, 2))
 
 
+def test_uniform_partition_every_shape(H, oracle_mod):
+    """The uniform partition rule floor(s L / pp) for every layer count 1..255 and every stage count
+    it admits (up to 64), through the level sweeps and, with 2 and 3 chunks, the interleaved kernel."""
+    _say("[case] uniform partitions, every (L, pp)")
+    rng = np.random.default_rng(9)
+    n = 0
+    for L in range(1, 256):
+        costs = mk_costs(rng.integers(1, 1000, (1, L)).tolist(), rng.integers(1, 1000, (1, L)).tolist(),
+                         act=(rng.integers(1, 9, (1, L)) * 64).tolist(), grad=rng.integers(1, 99, (1, L)).tolist())
+        for pp in range(1, min(L, 64) + 1):
+            rows = [(1, 1, pp, 3, 1, None), (1, 1, pp, 2, 0, None)]
+            rows += [(1, 1, pp, pp, 3, None, v) for v in (2, 3) if pp * v <= min(L, 64)]
+            w = mk(costs, mk_cluster(pp), rows)
+            ora = oracle_mod.simulate(w)
+            assert (ora["status"] == 0).all(), (L, pp)
+            H.assert_same(H.run_hip(w, table=(pp % 7 == 0)), ora, what=f"uniform L={L} pp={pp}")
+            n += 1
+    assert n == 14304
+
+
 def test_maximum_micro_batch_count(H, oracle_mod):
     """The largest micro-batch count the interface takes (2^16) with the deepest pipeline (64
     stages, 131 198 levels), with few stages and with one; every schedule of the level sweeps; one
