@@ -50,6 +50,95 @@ def read_traffic(workload: str):
         return None
 
 
+def variant_workloads(w, n):
+    """A seeded sample of n candidates of the workload, once per reading of the p2p events and per
+    further schedule: (name, workload, kernel that does the variant's work, mask of the candidates
+    that kernel simulates)."""
+    import numpy as np
+    from workloads import Workload, subset
+    from workloads.schedules import chain, dapple_lists, gpipe_lists, pack_schedule, pack_schedules
+
+    idx = np.sort(np.random.default_rng(11).choice(len(w.cand["pp"]), n, replace=False))
+    base = subset(w, idx)
+    L = int(w.costs["L"])
+    everyone = np.ones(n, bool)
+
+    def copy_cand():
+        return {k: v.copy() for k, v in base.cand.items()}
+
+    yield "default", base, "k_simulate", everyone
+    for name, blocking in (("p2p_blocking_1", 1), ("serialised_links", 2)):
+        cl = dict(base.cluster)
+        cl["p2p_blocking"] = blocking
+        yield name, Workload(base.name, base.costs, cl, base.cand), "k_simulate", everyone
+    cand = copy_cand()
+    cand["schedule"] = np.where(cand["schedule"] == 1, 2, cand["schedule"]).astype(np.uint8)
+    yield "asynchronous", Workload(base.name, base.costs, dict(base.cluster), cand), "k_simulate", cand["schedule"] == 2
+    # interleaved: two chunks per device, uniform partition, m rounded up to a multiple of pp
+    cand = copy_cand()
+    pp, m = base.cand["pp"].astype(np.int64), base.cand["m"].astype(np.int64)
+    take = (pp >= 2) & (2 * pp <= min(L, 64))
+    cand["m"] = np.where(take, ((m + pp - 1) // pp) * pp, m).astype(np.int32)
+    cand["schedule"] = np.where(take, 3, cand["schedule"]).astype(np.uint8)
+    cand["part_off"] = np.where(take, -1, cand["part_off"]).astype(np.int64)
+    cand["chunks"] = np.where(take, 2, 1).astype(np.int32)
+    yield "interleaved_2_chunks", Workload(base.name, base.costs, dict(base.cluster), cand), "k_simulate_virtual", take
+    # explicit lists: the two built-in orders written out, for a few (pp, m) shapes
+    cand = copy_cand()
+    shapes = {4: 16, 8: 32, 16: 64}
+    blocks, ids = [], np.zeros((65, 2), np.int32)
+    for p_, m_ in shapes.items():
+        for sc in (0, 1):
+            ids[p_, sc] = len(blocks)
+            blocks.append(pack_schedule(p_, chain(p_), m_, p_, 1, gpipe_lists(p_, m_) if sc == 0 else dapple_lists(p_, m_)))
+    take = np.isin(pp, list(shapes)) & (base.cand["schedule"] <= 1)
+    m_of = np.zeros(65, np.int64)
+    for p_, m_ in shapes.items():
+        m_of[p_] = m_
+    cand["m"] = np.where(take, m_of[pp], m).astype(np.int32)
+    cand["chunks"] = np.where(take, ids[pp, np.minimum(base.cand["schedule"], 1)], 0).astype(np.int32)
+    cand["schedule"] = np.where(take, 4, cand["schedule"]).astype(np.uint8)
+    cand["schedule_off"], cand["schedule_words"] = pack_schedules(blocks)
+    yield "explicit_lists", Workload(base.name, base.costs, dict(base.cluster), cand), "k_simulate_explicit", take
+
+
+def time_variants(ds, ctx, w, n):
+    """The three calls on every workload of variant_workloads: ms per step and the time of the
+    kernel that does the variant's work (HIP events of the library)."""
+    import torch
+
+    res = {"sample": f"{n} seeded candidates of {w.name}"}
+    for name, wv, kernel, counted in variant_workloads(w, n):
+        dwv = ds.upload(wv, ctx.device)
+        evv = ds.alloc_events(ctx, dwv.L, dwv.V, dwv.C, ds.stage_entries(wv.cand["pp"]), table=False)
+        outv = ds.alloc_outputs(ctx, evv, util=True)
+        bestv, scr = ds.alloc_search(ctx, dwv.C)
+
+        def stepv():
+            ds.distsim_build_events(ctx, dwv, evv)
+            ds.distsim_simulate(ctx, dwv.cluster, evv, outv)
+            ds.distsim_search(ctx, outv.batch_ns, dwv.C, bestv, scr)
+        stepv()
+        torch.cuda.synchronize()
+        ctx.timing_enable(True)
+        t0 = time.perf_counter()
+        for _ in range(5):
+            stepv()
+        torch.cuda.synchronize()
+        dt = (time.perf_counter() - t0) / 5
+        ktv = ctx.timing_read()
+        ctx.timing_enable(False)
+        ms, cnt = ktv[kernel]
+        ok = (evv.status[:dwv.C] == 0).cpu().numpy()
+        n_counted = int((ok & counted).sum())
+        k_ms = ms / max(cnt, 1)
+        res[name] = {"candidates": int(dwv.C), "valid": int(ok.sum()), "ms_per_step": dt * 1e3, "kernel": kernel,
+                     "kernel_ms": k_ms, "kernel_candidates": n_counted,
+                     "kernel_candidates_per_s": n_counted / (k_ms / 1e3) if k_ms > 0 else None}
+        del dwv, evv, outv, bestv, scr
+    return res
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -64,6 +153,9 @@ def main() -> int:
     ap.add_argument("--ingest", type=int, default=4_000_000,
                     help="also time the steps in front of event generation (operator dedup, communication "
                          "event times) on this many seeded records (0 = skip)")
+    ap.add_argument("--variants", type=int, default=100_000,
+                    help="also time the other readings and schedules (blocking p2p, serialised links, asynchronous, "
+                         "interleaved, explicit lists) on this many seeded candidates of the workload (0 = skip)")
     ap.add_argument("--no-graph", action="store_true", help="skip the HIP-graph replay of the step")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one 1 GiB device-to-device copy (known traffic, for scaling HBM counters)")
@@ -201,6 +293,10 @@ def main() -> int:
                                        "frac": ct_bytes / ct_s / 1e9 / HBM_PEAK_GBS}}
         del d_rec, eid, rep, wsp, prof, elapsed
 
+    variants = None
+    if args.variants > 0:
+        variants = time_variants(ds, ctx, w, min(args.variants, dw.C))
+
     if args.calib_copy:
         src = torch.empty(1 << 30, dtype=torch.uint8, device=ctx.device)
         dst = torch.empty_like(src)
@@ -274,7 +370,8 @@ def main() -> int:
         "kernel_ms_note": "k_simulate is the span of the two sweep kernels, which run side by side "
                           "(k_simulate_gpipe on a stream of the library's context); the other entries are single kernels",
         "roofline": roofline, "roofline_hbm": roofline_hbm,
-        "graph_replay": graph, "timeline": timeline, "ingest": ingest, "cpu_baseline": cpu_baseline, "parity": parity,
+        "graph_replay": graph, "timeline": timeline, "ingest": ingest, "variants": variants,
+        "cpu_baseline": cpu_baseline, "parity": parity,
     }
     print(json.dumps(line))
     return 0
