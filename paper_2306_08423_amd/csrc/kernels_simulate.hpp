@@ -572,7 +572,10 @@ struct OwnedItem {
     Item it;
     int64_t w;          // wave-item index (rows w * 64 .. of the per-stage arrays)
 };
-__device__ __forceinline__ OwnedItem owned_item(const int64_t* __restrict__ hdr, int64_t t, bool gpipe, bool split) {
+// The header is read through the constant address space: nothing writes it while a sweep runs,
+// and a wave-uniform index then makes every read a scalar load that needs no vector register.
+typedef const __attribute__((address_space(4))) int64_t* HdrPtr;
+__device__ __forceinline__ OwnedItem owned_item(HdrPtr hdr, int64_t t, bool gpipe, bool split) {
     int k = 0;
     int64_t first = 0;                                  // first owned item of the class, relative to the class
     for (; k < kClasses - 1; k++) {
@@ -595,8 +598,10 @@ __device__ __forceinline__ void simulate_all(const CostsDev& co, const ClusterDe
                                              const Workspace& ws, const EventsDev& ev, const SimOut& out,
                                              Park& park, double* xp, int64_t split_min_items) {
     const int lane = lane_id();
-    const int64_t* __restrict__ hdr = ws.hdr;
-    const int64_t wave0 = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / kWave;
+    const HdrPtr hdr = (HdrPtr)ws.hdr;
+    // the wavefront's number as a scalar: the header words and the item ranges then come through
+    // scalar loads, all requested at once, instead of a chain of dependent vector loads
+    const int64_t wave0 = __builtin_amdgcn_readfirstlane((int)(((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / kWave));
     const int64_t nwaves = ((int64_t)gridDim.x * blockDim.x) / kWave;
     int64_t W = hdr[H_NUM_ITEMS];                       // items that have room in the per-stage arrays
     if (W * kWave > ev.stage_cap) W = ev.stage_cap / kWave;
@@ -668,7 +673,7 @@ __global__ __launch_bounds__(kSimBlock, 6) void k_simulate_gpipe(CostsDev co, Cl
 __global__ __launch_bounds__(kSimBlock) void k_simulate_links(CostsDev co, ClusterDev cl, CandDev ca, Workspace ws,
                                                               EventsDev ev, SimOut out) {
     const int lane = lane_id();
-    const int64_t wave0 = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / kWave;
+    const int64_t wave0 = __builtin_amdgcn_readfirstlane((int)(((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / kWave));
     const int64_t nwaves = ((int64_t)gridDim.x * blockDim.x) / kWave;
     int64_t W = ws.hdr[H_NUM_ITEMS];
     if (W * kWave > ev.stage_cap) W = ev.stage_cap / kWave;
