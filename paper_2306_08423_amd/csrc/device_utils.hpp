@@ -160,13 +160,15 @@ struct ClusterDev {
     int64_t bucket;
     int32_t blocking;          // 1: p2p events occupy the sender; 2: sends queue on their link
     double inv_gpus_per_node;  // 1 / gpus_per_node (set on the host)
+    double gpus_per_node_f;    // gpus_per_node as a double (set on the host: a kernel argument stays in scalar registers)
+    double inv_bucket;         // 1 / bucket, 0 when there are no buckets (set on the host)
 };
 
 // Node of the first rank of pipeline position s when a position spans tpdp < gpus_per_node
 // ranks: floor(s * tpdp / gpus_per_node) for s < 64.  The product is exact in fp64 and the
 // quotient is below 64, so one multiplication by the reciprocal and an exact remainder give it.
 __device__ __forceinline__ int node_of_position(const ClusterDev& cl, int s, int tpdp) {
-    const double x = (double)s * (double)tpdp, g = (double)cl.gpus_per_node;
+    const double x = (double)s * (double)tpdp, g = cl.gpus_per_node_f;
     int q = (int)(x * cl.inv_gpus_per_node);
     const double r = __fma_rn(-(double)q, g, x);
     if (r < 0.0) q--;

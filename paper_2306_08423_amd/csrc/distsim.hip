@@ -88,6 +88,8 @@ ClusterDev to_dev(const distsim_cluster& c) {
     d.bucket = c.dp_bucket_bytes;
     d.blocking = c.p2p_blocking;
     d.inv_gpus_per_node = 1.0 / (double)c.gpus_per_node;
+    d.gpus_per_node_f = (double)c.gpus_per_node;
+    d.inv_bucket = c.dp_bucket_bytes > 0 ? 1.0 / (double)c.dp_bucket_bytes : 0.0;
     return d;
 }
 

@@ -516,13 +516,12 @@ __device__ __forceinline__ void simulate_items(const ClusterDev& cl, const CandD
             const int64_t startB = endB - (int64_t)sw[u].Bd;
             const int64_t tot_hi = row[hi * kCombWords + 1];
             const int64_t ar_cap = allreduce_ns(cl, dp, cl.bucket);
-            const double inv_bucket = 1.0 / (double)cl.bucket;
             int64_t acc = 0, t = 0;
             ar_busy = 0; nar = 0;
             for (int l = hi - 1; l >= lo; l--) {
                 const int64_t ready = startB + (tot_hi - row[l * kCombWords + 1]);
                 acc += row[(l + 1) * kCombWords + 3] - row[l * kCombWords + 3];
-                const int64_t kk = (int64_t)udiv64_by((uint64_t)acc, (uint64_t)cl.bucket, inv_bucket);
+                const int64_t kk = (int64_t)udiv64_by((uint64_t)acc, (uint64_t)cl.bucket, cl.inv_bucket);
                 if (kk > 0) {
                     t = (t > ready ? t : ready) + kk * ar_cap;
                     ar_busy += kk * ar_cap;
