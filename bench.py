@@ -156,6 +156,9 @@ def main() -> int:
     ap.add_argument("--variants", type=int, default=100_000,
                     help="also time the other readings and schedules (blocking p2p, serialised links, asynchronous, "
                          "interleaved, explicit lists) on this many seeded candidates of the workload (0 = skip)")
+    ap.add_argument("--search", type=int, default=1 << 27,
+                    help="also time the argmin alone over this many seeded batch times, a list long enough for "
+                         "HBM to bound it (0 = skip)")
     ap.add_argument("--no-graph", action="store_true", help="skip the HIP-graph replay of the step")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one 1 GiB device-to-device copy (known traffic, for scaling HBM counters)")
@@ -293,6 +296,38 @@ def main() -> int:
                                        "frac": ct_bytes / ct_s / 1e9 / HBM_PEAK_GBS}}
         del d_rec, eid, rep, wsp, prof, elapsed
 
+    search = None
+    if args.search > 0:
+        n_s = int(args.search)
+        gen = torch.Generator(device=ctx.device)
+        gen.manual_seed(2306084230 + 13)
+        times = torch.randint(1 << 20, 1 << 50, (n_s,), dtype=torch.int64, device=ctx.device, generator=gen)
+        times[::977] = torch.iinfo(torch.int64).max                       # candidates that are not valid
+        wgt = torch.randint(1, 1 << 12, (n_s,), dtype=torch.int64, device=ctx.device, generator=gen)
+        best_s, scr_s = ds.alloc_search(ctx, n_s)
+        ds.distsim_search(ctx, times, n_s, best_s, scr_s)                  # warm-up
+        torch.cuda.synchronize()
+        lo = torch.min(times)
+        first = int(torch.nonzero(times == lo)[0].item())
+        ok = best_s.cpu().tolist() == [first, int(lo.item())]
+        ctx.timing_enable(True)
+        for _ in range(10):
+            ds.distsim_search(ctx, times, n_s, best_s, scr_s)
+        torch.cuda.synchronize()
+        ms0, n0 = ctx.timing_read()["k_search"]
+        for _ in range(10):
+            ds.distsim_search(ctx, times, n_s, best_s, scr_s, weight=wgt, objective=1)
+        torch.cuda.synchronize()
+        ms1, n1 = ctx.timing_read()["k_search"]
+        ctx.timing_enable(False)
+        s0, s1 = ms0 / max(n0, 1) / 1e3, ms1 / max(n1, 1) / 1e3
+        search = {"candidates": n_s, "matches_torch_min": bool(ok),
+                  "min": {"ms": s0 * 1e3, "bound": "hbm", "achieved": n_s * 8 / s0 / 1e9, "peak": HBM_PEAK_GBS,
+                          "unit": "GB/s", "frac": n_s * 8 / s0 / 1e9 / HBM_PEAK_GBS},
+                  "weighted": {"ms": s1 * 1e3, "bound": "hbm", "achieved": n_s * 16 / s1 / 1e9, "peak": HBM_PEAK_GBS,
+                               "unit": "GB/s", "frac": n_s * 16 / s1 / 1e9 / HBM_PEAK_GBS}}
+        del times, wgt, best_s, scr_s
+
     variants = None
     if args.variants > 0:
         variants = time_variants(ds, ctx, w, min(args.variants, dw.C))
@@ -370,7 +405,7 @@ def main() -> int:
         "kernel_ms_note": "k_simulate is the span of the two sweep kernels, which run side by side "
                           "(k_simulate_gpipe on a stream of the library's context); the other entries are single kernels",
         "roofline": roofline, "roofline_hbm": roofline_hbm,
-        "graph_replay": graph, "timeline": timeline, "ingest": ingest, "variants": variants,
+        "graph_replay": graph, "timeline": timeline, "ingest": ingest, "search": search, "variants": variants,
         "cpu_baseline": cpu_baseline, "parity": parity,
     }
     print(json.dumps(line))
