@@ -743,7 +743,7 @@ def test_search_parity(H, oracle_mod):
     import paper_2306_08423_amd as ds
     c = H.ctx()
     rng = np.random.default_rng(8)
-    for n in (1, 2, 63, 64, 65, 1000, 4097, 300_000):
+    for n in (1, 2, 63, 64, 65, 1000, 4097, 300_000, 3_000_001):        # the last: several turns of the grid's loop
         b = rng.integers(1, 1 << 52, n)
         b[rng.integers(0, n, n // 3 + 1)] = b[n // 2]
         b[rng.random(n) < 0.1] = INT64_MAX
