@@ -1,35 +1,43 @@
 // Interleaved one-forward-one-backward schedule: every device holds several model chunks, so a
 // device's tasks belong to several virtual stages and the producer of a task is no longer "the
-// neighbour's latest task".  One wavefront per candidate, lane = device.  Each lane walks its own
-// task list (closed forms of the slot numbers, see distsim.h) and keeps the end times of its
-// latest forward and backward slots in LDS rings; in every round a lane runs its next task if the
-// producing slot on the neighbouring device (the device before for forwards, after for backwards,
-// with the edge from the last device back to the first one chunk apart) has been run, reading its
-// end time from that device's ring.  Rounds repeat until every list is done; a round in which no
-// lane can run ends the loop (it cannot happen for a valid schedule) and the candidate is reported
+// neighbour's latest task".  A wavefront is cut into groups of R lanes, one candidate per group,
+// lane = device.  Each lane walks its own task list (closed forms of the slot numbers, see
+// distsim.h) and keeps the end times of its latest forward and backward slots in LDS rings; in
+// every round a lane runs its next task if the producing slot on the neighbouring device (the
+// device before for forwards, after for backwards, with the edge from the last device back to
+// the first one chunk apart) has been run, reading its end time from that device's ring.  Rounds
+// repeat until every list of the wavefront is done; a round in which no lane can run ends the
+// loop (it cannot happen for a valid schedule) and the candidates still unfinished are reported
 // invalid.  Same arithmetic as the level sweep: fp64 values that are integers below 2^53.
 #pragma once
 #include "kernels_simulate.hpp"
 
 namespace distsim {
 
-// LDS of one candidate of at most R devices: R ring slots per device and direction.  A producer
-// never leads its consumer by more than the ring holds when R >= max(8, pp) (checked by running
-// the rounds, which do not depend on the durations, for every pp, every chunk count with
-// pp * chunks <= 64 and micro-batch counts up to 8 pp); a task that would overwrite a slot not yet
-// read waits, so a ring that were too small could stall a candidate but never give a wrong time.
+// LDS of one wavefront: 64 / R candidates of at most R devices each, R ring slots per device and
+// direction.  A producer never leads its consumer by more than the ring holds when R >= max(8, pp)
+// (checked by running the rounds, which do not depend on the durations, for every pp, every chunk
+// count with pp * chunks <= 64 and micro-batch counts up to 8 pp); a task that would overwrite a
+// slot not yet read waits, so a ring that were too small could stall a candidate but never give
+// a wrong time.
 template <int R>
 struct VirtLds {
-    static constexpr int kRing = R;
+    static_assert(R >= 8 && R <= kWave && (R & (R - 1)) == 0, "ring sizes are powers of two from 8 to 64");
+    static constexpr int kRing = R, kGroups = kWave / R;
     // first index: direction, 0 = forward, 1 = backward
-    double ring[2][R][R];                       // by device and slot modulo R: end of the task
-    double dur[2][kMaxPP];                      // by virtual stage: task durations
-    double lat[2][kMaxPP];                      // by virtual stage: latency of the incoming edge
-    int64_t send[2][kMaxPP];                    // by virtual stage: outgoing p2p events
-    int32_t done[2][R];                         // by device: slots run, as of the previous round
+    union {
+        double ring[2][kWave][R];               // by lane and slot modulo R: end of the task
+        // by group and virtual stage: outgoing p2p events; needed only while the latencies are
+        // set up, before the first round writes the rings (64 R >= (64 / R) 64 entries for R >= 8)
+        int64_t send[2][kGroups][kMaxPP];
+    };
+    double dur[2][kGroups][kMaxPP];             // by group and virtual stage: task durations
+    double lat[2][kGroups][kMaxPP];             // by group and virtual stage: latency of the incoming edge
+    int32_t done[2][kWave];                     // by lane: slots run, as of the previous round
 };
 
-// What one candidate needs from its descriptor (or, for the dump, from the candidate arrays).
+// What one candidate needs from its descriptor (or, for the dump, from the candidate arrays); the
+// lanes of a group hold the same values.  pp == 0: the group has no candidate.
 struct VirtCand {
     int pp, v, m, dp, tp, vch;
     int64_t poff, c;
@@ -43,25 +51,26 @@ struct VirtDump {
     int64_t* ar_end;
 };
 
-// One candidate on one wavefront.  DUMP = false: writes status / batch time / busy sums.
-// DUMP = true: the candidate is known to be OK; writes every task's start and end and the
-// all-reduce windows, and none of the simulation's outputs.
+// The candidates of one wavefront, one per group of Lds::kRing lanes.  DUMP = false: writes status
+// / batch time / busy sums.  DUMP = true: the candidates are known to be OK; writes every task's
+// start and end and the all-reduce windows, and none of the simulation's outputs.
 template <bool DUMP, typename Lds>
-__device__ __forceinline__ void virtual_candidate(const CostsDev& co, const ClusterDev& cl, const CandDev& ca,
-                                                  const Workspace& ws, const EventsDev& ev, const SimOut& out,
-                                                  const VirtCand& vc, const VirtDump& dump, Lds& sm) {
-    constexpr int kVirtRing = Lds::kRing;
-    const int d = threadIdx.x;                                   // device
+__device__ __forceinline__ void virtual_groups(const CostsDev& co, const ClusterDev& cl, const CandDev& ca,
+                                               const Workspace& ws, const EventsDev& ev, const SimOut& out,
+                                               const VirtCand& vc, const VirtDump& dump, Lds& sm) {
+    constexpr int R = Lds::kRing;
+    const int lane = threadIdx.x;
+    const int g = lane / R, d = lane % R, g0 = g * R;            // group, device, first lane of the group
     const int L = co.L;
     const int pp = vc.pp, v = vc.v, m = vc.m, dp = vc.dp, tp = vc.tp, vch = vc.vch;
     const int64_t c = vc.c;
     const int S = pp * vch;
-    const bool act = d < pp;
+    bool act = d < pp;                                           // pp == 0: nothing to do in this group
     const int64_t tpdp = (int64_t)tp * dp;
     auto node_of = [&](int dev) -> int64_t {
         return tpdp >= cl.gpus_per_node ? dev : (int64_t)node_of_position(cl, dev, (int)tpdp);
     };
-    const int64_t* row = ws.comb + (size_t)((v * kMaxPP + pp - 1) * (L + 1)) * kCombWords;
+    const int64_t* row = ws.comb + (size_t)((v * kMaxPP + (pp > 0 ? pp - 1 : 0)) * (L + 1)) * kCombWords;
 
     // composed events of this device's chunks
     int bad = 0;
@@ -84,32 +93,32 @@ __device__ __forceinline__ void virtual_candidate(const CostsDev& co, const Clus
             comm += FT + BT - CP + PF + PB;
             share += FT + BT + PF + PB;
             const int64_t pf_task = cl.blocking == 1 ? PF : 0, pb_task = cl.blocking == 1 ? PB : 0;
-            sm.dur[0][k] = (double)(FT + pf_task);
-            sm.dur[1][k] = (double)(BT + pb_task);
-            sm.send[0][k] = PF - pf_task;
-            sm.send[1][k] = PB - pb_task;
+            sm.dur[0][g][k] = (double)(FT + pf_task);
+            sm.dur[1][g][k] = (double)(BT + pb_task);
+            sm.send[0][g][k] = PF - pf_task;
+            sm.send[1][g][k] = PB - pb_task;
         }
     }
-    bad = __builtin_amdgcn_ballot_w64(bad != 0) != 0;
-    const bool range = !bad && stage_out_of_range(act ? share : 0, m, kWave);
-    if (bad || range) {
-        if (!DUMP && d == 0) { ev.status[c] = bad ? 1 : 2; ev.num_events[c] = 0; out.batch_ns[c] = INT64_MAX; }
-        return;
+    const bool gbad = group_any(bad != 0, R);
+    const bool range = stage_out_of_range(act && !gbad ? share : 0, m, R);
+    if (gbad || range) {
+        if (!DUMP && act && d == 0) { ev.status[c] = gbad ? 1 : 2; ev.num_events[c] = 0; out.batch_ns[c] = INT64_MAX; }
+        act = false;
     }
     __syncthreads();
     // latency of the edge into virtual stage k: the send of k - 1 (forward), of k + 1 (backward)
     if (act) {
         for (int cch = 0; cch < vch; cch++) {
             const int k = cch * pp + d;
-            sm.lat[0][k] = k > 0 ? (double)sm.send[0][k - 1] : 0.0;
-            sm.lat[1][k] = k + 1 < S ? (double)sm.send[1][k + 1] : 0.0;
+            sm.lat[0][g][k] = k > 0 ? (double)sm.send[0][g][k - 1] : 0.0;
+            sm.lat[1][g][k] = k + 1 < S ? (double)sm.send[1][g][k + 1] : 0.0;
         }
     }
     __syncthreads();
 
     // the rounds
     // slot numbers fit 32 bits: m <= 2^16 and pp * vch <= 64
-    const int n = m * vch;                                    // slots per direction
+    const int n = act ? m * vch : 0;                          // slots per direction
     int W = 2 * (pp - d - 1) + (vch - 1) * pp;                // warm-up forwards
     if (W > n) W = n;
     int iF = 0, iB = 0;
@@ -118,16 +127,16 @@ __device__ __forceinline__ void virtual_candidate(const CostsDev& co, const Clus
     int rF = 0, cF = 0, rB = 0, cB = 0;
     int jF0 = 0, jB0 = 0;
     double own = 0.0;
-    bool stuck = false;
-    const int max_rounds = 4 * n + 8 * pp + 64;
+    const int max_rounds = wave_max_i32(act ? 4 * n + 8 * pp + 64 : 0);
     // Per direction: the producer of a slot is the same slot on the device before (in the
     // direction), or, on the direction's first device, the slot pp earlier on its last device; the
     // consumers of the ring slot that a task overwrites are the device after and, on the
     // direction's last device, the first device (pp slots later).  All of a round's LDS reads are
     // issued together, at clamped addresses, and the conditions select among what came back.
-    const int dL = d > 0 ? d - 1 : 0, dR = d + 1 < pp ? d + 1 : d;
+    const int dL = g0 + (d > 0 ? d - 1 : 0), dR = g0 + (d + 1 < pp ? d + 1 : d);      // neighbouring lanes
+    const int dFirst = g0, dLast = g0 + (pp > 0 ? pp - 1 : 0);
     for (int round = 0; round < max_rounds; round++) {
-        if (act) { sm.done[0][d] = iF; sm.done[1][d] = iB; }
+        if (act) { sm.done[0][lane] = iF; sm.done[1][lane] = iB; }
         __syncthreads();
         const bool todo = act && iB < n;
         if (__builtin_amdgcn_ballot_w64(todo) == 0) break;
@@ -142,24 +151,24 @@ __device__ __forceinline__ void virtual_candidate(const CostsDev& co, const Clus
             const bool has_prod = fwd ? k > 0 : k + 1 < S;
             const bool first = fwd ? d == 0 : d + 1 == pp;            // first device of the direction
             const bool last = fwd ? d + 1 == pp : d == 0;             // last device of the direction
-            const int src = first ? (fwd ? pp - 1 : 0) : (fwd ? dL : dR);
+            const int src = first ? (fwd ? dLast : dFirst) : (fwd ? dL : dR);
             const int si = first ? i - pp : i;
             const int done_src = sm.done[dir][src];
-            const double prod_end = sm.ring[dir][src][si & (kVirtRing - 1)];
-            const double lat = sm.lat[dir][k], dur = sm.dur[dir][k];
+            const double prod_end = sm.ring[dir][src][si & (R - 1)];
+            const double lat = sm.lat[dir][g][k], dur = sm.dur[dir][g][k];
             const int done_next = sm.done[dir][fwd ? dR : dL];
-            const int done_wrap = sm.done[dir][fwd ? 0 : pp - 1];
+            const int done_wrap = sm.done[dir][fwd ? dFirst : dLast];
             bool ok = !has_prod || done_src > si;
             // the slot this task overwrites in the ring must have been read by its consumers
-            if (i >= kVirtRing) {
-                if (!last && !(done_next > i - kVirtRing)) ok = false;
-                if (last && vch > 1 && !(done_wrap > i - kVirtRing + pp)) ok = false;
+            if (i >= R) {
+                if (!last && !(done_next > i - R)) ok = false;
+                if (last && vch > 1 && !(done_wrap > i - R + pp)) ok = false;
             }
             if (ok) {
                 const double arrive = has_prod ? prod_end + lat : 0.0;
                 const double t0 = arrive > own ? arrive : own;
                 own = t0 + dur;
-                sm.ring[dir][d][i & (kVirtRing - 1)] = own;
+                sm.ring[dir][lane][i & (R - 1)] = own;
                 const int j = fwd ? jF0 + rF : jB0 + rB;                        // micro-batch of the slot
                 if (fwd) {
                     iF++;
@@ -176,13 +185,14 @@ __device__ __forceinline__ void virtual_candidate(const CostsDev& co, const Clus
                 ran = true;
             }
         }
-        if (__builtin_amdgcn_ballot_w64(ran) == 0) { stuck = true; break; }
+        if (__builtin_amdgcn_ballot_w64(ran) == 0) break;               // nothing can run any more
         __syncthreads();
     }
     __syncthreads();
-    if (stuck || __builtin_amdgcn_ballot_w64(act && iB < n) != 0) {
-        if (!DUMP && d == 0) { ev.status[c] = 1; ev.num_events[c] = 0; out.batch_ns[c] = INT64_MAX; }
-        return;
+    // a candidate with a list that did not end: its schedule cannot be run
+    if (group_any(act && iB < n, R)) {
+        if (!DUMP && act && d == 0) { ev.status[c] = 1; ev.num_events[c] = 0; out.batch_ns[c] = INT64_MAX; }
+        act = false;
     }
 
     // data-parallel modelling per device: one trailing all-reduce over the bytes of all its chunks
@@ -193,36 +203,45 @@ __device__ __forceinline__ void virtual_candidate(const CostsDev& co, const Clus
         if (has_ar) { dump.ar_start[d] = endB; dump.ar_end[d] = endB + AR; }
         return;
     }
-    const int64_t batch = group_max(act ? endB + AR : 0, kWave);
-    const int64_t nar = group_count(has_ar, kWave);
-    const int64_t base = ev.stage_pos[c];
-    if (act && base >= 0) {
-        const int64_t cb = (int64_t)m * comp, mb = (int64_t)m * comm + AR;
-        out.comp_busy[base + d] = cb;
-        out.comm_busy[base + d] = mb;
-        if (out.util) out.util[base + d] = batch > 0 ? (double)cb / (double)batch : 0.0;
-    }
-    if (d == 0) {
-        out.batch_ns[c] = batch;
-        ev.num_events[c] = 2ll * m * S + 2ll * m * (S - 1) + nar;
+    const int64_t batch = group_max(act ? endB + AR : 0, R);
+    const int64_t nar = group_count(has_ar, R);
+    if (act) {
+        const int64_t base = ev.stage_pos[c];
+        if (base >= 0) {
+            const int64_t cb = (int64_t)m * comp, mb = (int64_t)m * comm + AR;
+            out.comp_busy[base + d] = cb;
+            out.comm_busy[base + d] = mb;
+            if (out.util) out.util[base + d] = batch > 0 ? (double)cb / (double)batch : 0.0;
+        }
+        if (d == 0) {
+            out.batch_ns[c] = batch;
+            ev.num_events[c] = 2ll * m * S + 2ll * m * (S - 1) + nar;
+        }
     }
 }
 
 // One launch per ring size R: the candidates of the classes [cls_lo, cls_hi) of the visiting order
-// (class k holds the candidates of 64 >> k lanes, i.e. pp <= 64 >> k <= R), so that candidates of
-// few devices take little LDS and more of them are resident.
+// (class k holds the candidates of 64 >> k lanes, i.e. pp <= 64 >> k <= R), 64 / R consecutive
+// ones per wavefront, so that candidates of few devices share a wavefront and take little LDS.
+// Neighbours in visiting order have about the same number of micro-batches, hence lists of about
+// the same length when their chunk counts agree.
 template <int R>
 __global__ __launch_bounds__(kWave) void k_simulate_virtual(CostsDev co, ClusterDev cl, CandDev ca, Workspace ws,
                                                             EventsDev ev, SimOut out, int cls_lo, int cls_hi) {
+    constexpr int kGroups = kWave / R;
     __shared__ VirtLds<R> sm;
+    const int g = threadIdx.x / R;
     // descriptors beyond the valid candidates were never written: the class table bounds them
     const int64_t pos_end = ws.hdr[H_CLASS_START + cls_hi];
-    for (int64_t pos = ws.hdr[H_CLASS_START + cls_lo] + blockIdx.x; pos < pos_end; pos += gridDim.x) {
-        const Desc ds = ws.desc[pos];
-        if (!is_interleaved(ds) || (ds.meta & 0xff) == 0) continue;       // uniform: one descriptor per wavefront
+    for (int64_t pos0 = ws.hdr[H_CLASS_START + cls_lo] + (int64_t)blockIdx.x * kGroups; pos0 < pos_end;
+         pos0 += (int64_t)gridDim.x * kGroups) {
+        Desc ds{};
+        if (pos0 + g < pos_end) ds = ws.desc[pos0 + g];
+        if (!is_interleaved(ds)) ds.meta = 0;
+        if (__builtin_amdgcn_ballot_w64((ds.meta & 0xff) != 0) == 0) continue;
         const VirtCand vc{ds.meta & 0xff, ds.meta >> 16, ds.m, ds.dp, (int)(uint32_t)ds.spare, (int)(ds.spare >> 32),
                           ds.poff, ds.cand};
-        virtual_candidate<false>(co, cl, ca, ws, ev, out, vc, VirtDump{}, sm);
+        virtual_groups<false>(co, cl, ca, ws, ev, out, vc, VirtDump{}, sm);
         __syncthreads();
     }
 }
@@ -248,7 +267,7 @@ __global__ __launch_bounds__(kWave) void k_timeline_virtual(CostsDev co, Cluster
         const VirtCand vc{ca.pp[c], v, ca.m[c], ca.dp[c], tp, ca.chunks[c], ca.part_off[c], c};
         const int64_t off = task_off[q];
         const VirtDump dump{start_ns + off, end_ns + off, ar_start + q * kMaxPP, ar_end + q * kMaxPP};
-        virtual_candidate<true>(co, cl, ca, ws, EventsDev{}, SimOut{}, vc, dump, sm);
+        virtual_groups<true>(co, cl, ca, ws, EventsDev{}, SimOut{}, vc, dump, sm);
         __syncthreads();
     }
 }
