@@ -36,6 +36,7 @@ def _load():
         _lib = ctypes.CDLL(build())
         _lib.oracle_simulate.restype = ctypes.c_int
         _lib.oracle_search.restype = ctypes.c_int
+        _lib.oracle_stage_table.restype = ctypes.c_int
     return _lib
 
 
@@ -78,6 +79,7 @@ def simulate(w, nthreads: int = 1, timeline: bool = False) -> Dict[str, np.ndarr
     xlen = int(xwords.size) if xwords is not None else 0
     if xwords is not None and xwords.size == 0:
         xwords = np.zeros(1, np.int32)
+    pool_len = int(pool.size)
     if pool.size == 0:
         pool = np.zeros(1, np.uint8)
     C = dp.shape[0]
@@ -96,7 +98,7 @@ def simulate(w, nthreads: int = 1, timeline: bool = False) -> Dict[str, np.ndarr
         if sched[0] == 4 and chunks is not None and xoff is not None and 0 <= int(chunks[0]) < xn:
             o = int(xoff[int(chunks[0])])
             if 0 <= o and o + 5 <= xlen:
-                rows = max(1, min(64, int(xwords[o + 1])))     # S of its schedule block
+                rows = max(1, int(xwords[o + 1]))     # S of its schedule block
         tls = np.full((2, rows, int(m[0])), -1, np.int64)
         tle = np.full((2, rows, int(m[0])), -1, np.int64)
         tar = np.full((2, int(pp[0])), -1, np.int64)
@@ -104,7 +106,7 @@ def simulate(w, nthreads: int = 1, timeline: bool = False) -> Dict[str, np.ndarr
         ctypes.c_int32(L), ctypes.c_int32(V), _p(vt), *[_p(a) for a in cols],
         ctypes.c_int32(int(cl["num_devices"])), ctypes.c_int32(int(cl["gpus_per_node"])),
         _p(alpha), _p(beta), ctypes.c_int64(int(cl["dp_bucket_bytes"])), ctypes.c_int32(int(cl.get("p2p_blocking", 0))),
-        ctypes.c_int64(C), _p(dp), _p(tp), _p(pp), _p(m), _p(sched), _p(chunks), _p(poff), _p(pool),
+        ctypes.c_int64(C), _p(dp), _p(tp), _p(pp), _p(m), _p(sched), _p(chunks), _p(poff), _p(pool), ctypes.c_int64(pool_len),
         ctypes.c_int64(xn), _p(xoff), _p(xwords), ctypes.c_int64(xlen),
         _p(status), _p(batch), _p(nev), _p(soff), _p(comp), _p(comm), _p(util),
         _p(tls), _p(tle), _p(tar), ctypes.c_int32(int(nthreads)))
@@ -128,3 +130,41 @@ def search(batch_ns, weight=None, objective: int = 0):
     best = np.zeros(2, np.int64)
     lib.oracle_search(_p(b), _p(wt), ctypes.c_int64(b.shape[0]), ctypes.c_int32(objective), _p(best))
     return int(best[0]), int(best[1])
+
+
+def stage_table(w, sim) -> Dict[str, np.ndarray]:
+    """The composed events of every stage of the candidates that ``sim`` (a result of ``simulate`` on
+    the same workload) reports as OK, from plain loops over each stage's layers: ``tab`` [8][n] with
+    the columns FC, FA, BC, BA, PF, PB, G, AR and ``layer_lo`` / ``layer_hi`` [n], n = stage_off[C],
+    entry stage_off[c] + s.  Candidates of the schedules 3 and 4 keep zeros."""
+    lib = _load()
+    co, cl, ca = w.costs, w.cluster, w.cand
+    L, V = int(co["L"]), int(co["V"])
+    vt = _c(co["variant_tp"], np.int32)
+    cols = [_c(co[k], np.int64) for k in
+            ("fwd_comp_ns", "bwd_comp_ns", "fwd_comm_ns", "bwd_comm_ns", "act_bytes", "grad_bytes", "a2a_bytes")]
+    alpha = _c(cl["alpha_ns"], np.int64)
+    beta = _c(cl["beta_bytes_per_ns"], np.int64)
+    dp, tp, pp = (_c(ca[k], np.int32) for k in ("dp", "tp", "pp"))
+    sched = _c(ca["schedule"], np.uint8)
+    poff = _c(ca["part_off"], np.int64)
+    pool = _c(ca["part_pool"], np.uint8)
+    if pool.size == 0:
+        pool = np.zeros(1, np.uint8)
+    C = dp.shape[0]
+    status = _c(sim["status"], np.int32)
+    soff = _c(sim["stage_off"], np.int64)
+    n = int(soff[C])
+    tab = np.zeros((8, max(n, 1)), np.int64)
+    lo = np.zeros(max(n, 1), np.int32)
+    hi = np.zeros(max(n, 1), np.int32)
+    rc = lib.oracle_stage_table(
+        ctypes.c_int32(L), ctypes.c_int32(V), _p(vt), *[_p(a) for a in cols],
+        ctypes.c_int32(int(cl["num_devices"])), ctypes.c_int32(int(cl["gpus_per_node"])), _p(alpha), _p(beta),
+        ctypes.c_int64(C), _p(dp), _p(tp), _p(pp), _p(sched), _p(poff), _p(pool), _p(status), _p(soff),
+        _p(tab), _p(lo), _p(hi))
+    if rc != 0:
+        raise ValueError(f"oracle_stage_table rejected its arguments (rc={rc})")
+    if n == 0:
+        return {"tab": tab[:, :0], "layer_lo": lo[:0], "layer_hi": hi[:0]}
+    return {"tab": tab, "layer_lo": lo, "layer_hi": hi}

@@ -65,9 +65,9 @@
 #define ST_OK 0
 #define ST_INVALID 1
 #define ST_RANGE 2
-#define MAX_PP 64        /* interface limits of the evaluated library: a candidate beyond */
-#define MAX_M (1 << 16)  /* them is reported invalid                                      */
-#define MAX_SLOTS 2048   /* (virtual stage, micro-batch) pairs of an explicit schedule    */
+#define MAX_PP 64        /* devices of one pipeline: the interface's bound on pp (a candidate beyond it is
+                            invalid).  Nothing else is bounded here: any micro-batch count, any number of
+                            virtual stages and any schedule length is simulated.                      */
 
 enum { EV_TASK_DONE = 0, EV_ARRIVE_F = 1, EV_ARRIVE_B = 2, EV_GRAD_READY = 3, EV_AR_DONE = 4 };
 
@@ -190,7 +190,7 @@ static void build_schedule(int pp, int m, int sched, uint8_t *kind, int32_t *mb)
 
 static void simulate_one(const costs_t *co, const cluster_t *cl,
                          int32_t dp, int32_t tp, int32_t pp, int32_t m, int sched,
-                         const uint8_t *bnd_in /* NULL = uniform */,
+                         const uint8_t *bnd_in /* NULL = uniform */, int64_t bnd_avail /* entries readable at bnd_in */,
                          scratch_t *sc, result_t *res,
                          int64_t *comp_busy, int64_t *comm_busy, double *util, /* [pp] or NULL */
                          int64_t *tl_start, int64_t *tl_end /* [2][pp][m] or NULL */,
@@ -201,14 +201,15 @@ static void simulate_one(const costs_t *co, const cluster_t *cl,
     res->num_events = 0;
 
     /* --- validation ("unreachable" configurations, Sec. 6) --- */
-    if (dp < 1 || tp < 1 || pp < 1 || m < 1 || m > MAX_M || (sched != 0 && sched != 1 && sched != 2)) return;
+    if (dp < 1 || tp < 1 || pp < 1 || m < 1 || (sched != 0 && sched != 1 && sched != 2)) return;
     if ((int64_t)dp * tp * pp != cl->num_devices) return;
     if (pp > L || pp > MAX_PP) return;
     int v = -1;
     for (int i = 0; i < co->V; i++) if (co->variant_tp[i] == tp) { v = i; break; }
     if (v < 0) return;
-    int bnd[257];
+    int bnd[MAX_PP + 1];
     if (bnd_in) {
+        if (bnd_avail < pp + 1) return;               /* the partition would run off the pool */
         for (int s = 0; s <= pp; s++) bnd[s] = bnd_in[s];
         if (bnd[0] != 0 || bnd[pp] != L) return;
         for (int s = 0; s < pp; s++) if (bnd[s + 1] <= bnd[s]) return;
@@ -426,30 +427,37 @@ static void simulate_one(const costs_t *co, const cluster_t *cl,
  * the last device back to the first included), a backward the backward of k + 1; the last
  * virtual stage turns a micro-batch around on its own device.  One gradient all-reduce per device
  * over the bytes of all its chunks follows its last backward (buckets are not modelled for this
- * schedule; link serialisation is not either: such a candidate is invalid).
+ * schedule).  With p2p_blocking == 2 a link is an ordered pair (sending device, receiving device)
+ * and carries one transfer at a time, whatever chunks the transfers belong to.
  * Timeline arrays, if given, are [2][S][m] (virtual stage, not device).
  */
 static void simulate_interleaved(const costs_t *co, const cluster_t *cl,
                                  int32_t dp, int32_t tp, int32_t pp, int32_t m, int32_t vch,
-                                 const uint8_t *bnd_in, scratch_t *sc, result_t *res,
+                                 const uint8_t *bnd_in, int64_t bnd_avail, scratch_t *sc, result_t *res,
                                  int64_t *comp_busy, int64_t *comm_busy, double *util,
                                  int64_t *tl_start, int64_t *tl_end, int64_t *tl_ar) {
     const int L = co->L;
     res->status = ST_INVALID;
     res->batch_ns = INT64_MAX;
     res->num_events = 0;
-    if (dp < 1 || tp < 1 || pp < 1 || m < 1 || m > MAX_M || vch < 1) return;
+    if (dp < 1 || tp < 1 || pp < 1 || pp > MAX_PP || m < 1 || vch < 1) return;
     if ((int64_t)dp * tp * pp != cl->num_devices) return;
-    if ((int64_t)pp * vch > MAX_PP || (int64_t)pp * vch > L || m % pp != 0 || cl->p2p_blocking == 2) return;
+    if ((int64_t)pp * vch > L || m % pp != 0) return;
     const int S = pp * vch;
+    if (bnd_in && bnd_avail < S + 1) return;
     int v = -1;
     for (int i = 0; i < co->V; i++) if (co->variant_tp[i] == tp) { v = i; break; }
     if (v < 0) return;
-    int bnd[257];
+    int *bnd = (int *)malloc((size_t)(S + 1) * sizeof(int));
+    int64_t *pf = (int64_t *)calloc((size_t)S, sizeof(int64_t)), *pb = (int64_t *)calloc((size_t)S, sizeof(int64_t));
+    int64_t *link_free = (int64_t *)calloc((size_t)pp * pp, sizeof(int64_t));   /* [sender][receiver]: free again at */
+#define FREE_I() do { free(bnd); free(pf); free(pb); free(link_free); } while (0)
     if (bnd_in) {
+        int okp = 1;
         for (int k = 0; k <= S; k++) bnd[k] = bnd_in[k];
-        if (bnd[0] != 0 || bnd[S] != L) return;
-        for (int k = 0; k < S; k++) if (bnd[k + 1] <= bnd[k]) return;
+        if (bnd[0] != 0 || bnd[S] != L) okp = 0;
+        for (int k = 0; k < S && okp; k++) if (bnd[k + 1] <= bnd[k]) okp = 0;
+        if (!okp) { FREE_I(); return; }
     } else {
         for (int k = 0; k <= S; k++) bnd[k] = (int)(((int64_t)k * L) / S);
     }
@@ -459,9 +467,7 @@ static void simulate_interleaved(const costs_t *co, const cluster_t *cl,
     const int64_t *a2a = co->a2a + (int64_t)v * L;
 
     /* p2p events of every boundary between virtual stages, by the nodes of the two devices */
-    int64_t pf[256], pb[256];
     const int64_t g = cl->gpus_per_node;
-    for (int k = 0; k < S; k++) { pf[k] = 0; pb[k] = 0; }
     for (int k = 0; k + 1 < S; k++) {
         int64_t na = ((int64_t)(k % pp) * tp * dp) / g, nb = ((int64_t)((k + 1) % pp) * tp * dp) / g;
         int cls = na == nb ? 0 : 1;
@@ -479,7 +485,7 @@ static void simulate_interleaved(const costs_t *co, const cluster_t *cl,
             }
             t1 += (unsigned __int128)(pf[k] + pb[k]);
         }
-        if (t1 * (unsigned __int128)m >= ((unsigned __int128)1 << 53)) { res->status = ST_RANGE; return; }
+        if (t1 * (unsigned __int128)m >= ((unsigned __int128)1 << 53)) { res->status = ST_RANGE; FREE_I(); return; }
     }
     res->status = ST_OK;
 
@@ -498,19 +504,20 @@ static void simulate_interleaved(const costs_t *co, const cluster_t *cl,
     }
     memset(sc->arrF, 0, (size_t)narr);
     memset(sc->arrB, 0, (size_t)narr);
-    uint8_t *task_vs = (uint8_t *)malloc((size_t)ntask);
+    int32_t *task_vs = (int32_t *)malloc((size_t)ntask * sizeof(int32_t));
     const int64_t nslot = (int64_t)m * vch;
     for (int d = 0; d < pp; d++) {
-        uint8_t *kk = sc->task_kind + d * per_dev, *vs = task_vs + d * per_dev;
+        uint8_t *kk = sc->task_kind + d * per_dev;
+        int32_t *vs = task_vs + d * per_dev;
         int32_t *jj = sc->task_mb + d * per_dev;
         int64_t W = 2ll * (pp - d - 1) + (int64_t)(vch - 1) * pp;
         if (W > nslot) W = nslot;
         int64_t n = 0, f = 0, b = 0;
 #define PUT_F(i_) do { int64_t i__ = (i_), w__ = i__ % ((int64_t)pp * vch);                              \
-            kk[n] = 0; vs[n] = (uint8_t)((w__ / pp) * pp + d);                                            \
+            kk[n] = 0; vs[n] = (int32_t)((w__ / pp) * pp + d);                                            \
             jj[n] = (int32_t)((i__ / ((int64_t)pp * vch)) * pp + w__ % pp); n++; } while (0)
 #define PUT_B(i_) do { int64_t i__ = (i_), w__ = i__ % ((int64_t)pp * vch);                              \
-            kk[n] = 1; vs[n] = (uint8_t)((vch - 1 - w__ / pp) * pp + d);                                  \
+            kk[n] = 1; vs[n] = (int32_t)((vch - 1 - w__ / pp) * pp + d);                                  \
             jj[n] = (int32_t)((i__ / ((int64_t)pp * vch)) * pp + w__ % pp); n++; } while (0)
         for (; f < W; f++) PUT_F(f);
         while (f < nslot) { PUT_F(f); f++; PUT_B(b); b++; }
@@ -576,12 +583,28 @@ static void simulate_interleaved(const costs_t *co, const cluster_t *cl,
             busy[d] = 0;
             next[d]++;
             if (kd == 0 && k + 1 < S) {
-                heap_push(h, now + (cl->p2p_blocking == 1 ? 0 : pf[k]), EV_ARRIVE_F, k + 1, j, 0);
+                int64_t arrive = now + pf[k];
+                if (cl->p2p_blocking == 1) arrive = now;
+                if (cl->p2p_blocking == 2) {         /* the link to the next device carries one transfer at a time */
+                    int64_t *lf = &link_free[(int64_t)d * pp + (k + 1) % pp];
+                    int64_t depart = now > *lf ? now : *lf;
+                    arrive = depart + pf[k];
+                    *lf = arrive;
+                }
+                heap_push(h, arrive, EV_ARRIVE_F, k + 1, j, 0);
                 mb_[d] += pf[k]; nev++;
             }
             if (kd == 0 && k + 1 == S) sc->arrB[(int64_t)k * m + j] = 1;     /* turn-around on the last virtual stage */
             if (kd == 1 && k > 0) {
-                heap_push(h, now + (cl->p2p_blocking == 1 ? 0 : pb[k]), EV_ARRIVE_B, k - 1, j, 0);
+                int64_t arrive = now + pb[k];
+                if (cl->p2p_blocking == 1) arrive = now;
+                if (cl->p2p_blocking == 2) {
+                    int64_t *lf = &link_free[(int64_t)d * pp + (k - 1) % pp];
+                    int64_t depart = now > *lf ? now : *lf;
+                    arrive = depart + pb[k];
+                    *lf = arrive;
+                }
+                heap_push(h, arrive, EV_ARRIVE_B, k - 1, j, 0);
                 mb_[d] += pb[k]; nev++;
             }
             if (next[d] == per_dev && dp > 1) {       /* trailing gradient all-reduce of the device */
@@ -613,6 +636,8 @@ static void simulate_interleaved(const costs_t *co, const cluster_t *cl,
     }
 #undef TRY_START_I
     free(task_vs);
+    FREE_I();
+#undef FREE_I
     res->batch_ns = now;
     res->num_events = nev;
     for (int d = 0; d < pp; d++) {
@@ -635,11 +660,13 @@ static void simulate_interleaved(const costs_t *co, const cluster_t *cl,
  * or, on a stage without successor, its own F(k, j).  A device runs its list in order; a task
  * starts when the device is free and its input has arrived.  One gradient all-reduce per device
  * after its list, over the bytes of the parts of all stages it holds.  A schedule that cannot be
- * run to its end (an input that never arrives) is invalid, as is any malformed block.
+ * run to its end (an input that never arrives) is invalid, as is any malformed block.  With
+ * p2p_blocking == 2 a link is an ordered pair (sending device, receiving device) and carries one
+ * transfer at a time.
  * Per-stage outputs are per device. */
 static void simulate_explicit(const costs_t *co, const cluster_t *cl,
                               int32_t dp, int32_t tp, int32_t pp, int32_t m,
-                              const int32_t *w, int64_t nwords, const uint8_t *bnd_in,
+                              const int32_t *w, int64_t nwords, const uint8_t *bnd_in, int64_t bnd_avail,
                               scratch_t *sc, result_t *res,
                               int64_t *comp_busy, int64_t *comm_busy, double *util,
                               int64_t *tl_start, int64_t *tl_end /* [2][S][m] or NULL; tasks not listed keep what is there */,
@@ -648,35 +675,42 @@ static void simulate_explicit(const costs_t *co, const cluster_t *cl,
     res->status = ST_INVALID;
     res->batch_ns = INT64_MAX;
     res->num_events = 0;
-    if (dp < 1 || tp < 1 || pp < 1 || pp > MAX_PP || m < 1 || m > MAX_M) return;
-    if ((int64_t)dp * tp * pp != cl->num_devices || cl->p2p_blocking == 2) return;
+    if (dp < 1 || tp < 1 || pp < 1 || pp > MAX_PP || m < 1) return;
+    if ((int64_t)dp * tp * pp != cl->num_devices) return;
     if (!w || nwords < 5 + pp + 1) return;
     const int S = w[1], nparts = w[3], replicas = w[4];
-    if (w[0] != pp || w[2] != m || S < 1 || S > MAX_PP || nparts < 1 || nparts > MAX_PP || nparts > L || replicas < 1)
-        return;
-    if ((int64_t)S * m > MAX_SLOTS) return;
+    if (w[0] != pp || w[2] != m || S < 1 || nparts < 1 || nparts > L || replicas < 1) return;
+    if (bnd_in && bnd_avail < (int64_t)nparts + 1) return;
     const int32_t *dev_off = w + 5;
     const int64_t ntask = dev_off[pp];
     if (dev_off[0] != 0 || ntask < 0 || ntask > 2ll * S * m) return;
     for (int d = 0; d < pp; d++) if (dev_off[d + 1] < dev_off[d]) return;
-    if (nwords != 5 + pp + 1 + 3ll * S + ntask) return;
-    const int32_t *st = dev_off + pp + 1, *tasks = st + 3 * S;
-    int place[64], part[64], prev[64], next[64];
-    for (int k = 0; k < S; k++) next[k] = -1;
-    for (int k = 0; k < S; k++) {
-        place[k] = st[3 * k]; part[k] = st[3 * k + 1]; prev[k] = st[3 * k + 2];
-        if (place[k] < 0 || place[k] >= pp || part[k] < 0 || part[k] >= nparts || prev[k] < -1 || prev[k] >= S || prev[k] == k)
-            return;
-    }
-    for (int k = 0; k < S; k++) if (prev[k] >= 0) { if (next[prev[k]] >= 0) return; next[prev[k]] = k; }
+    if (nwords != 5 + pp + 1 + 3ll * S + ntask) return;           /* bounds S by the block's length */
+    const int32_t *st = dev_off + pp + 1, *tasks = st + 3 * (int64_t)S;
     int v = -1;
     for (int i = 0; i < co->V; i++) if (co->variant_tp[i] == tp) { v = i; break; }
     if (v < 0) return;
-    int bnd[65];
+    /* by virtual stage: device, part, the stage before and after it in its pipeline, outgoing p2p events */
+    int *place = (int *)malloc((size_t)S * 4 * sizeof(int)), *part = place + S, *prev = part + S, *next = prev + S;
+    int64_t *pf = (int64_t *)calloc((size_t)S * 2, sizeof(int64_t)), *pb = pf + S;
+    int *bnd = (int *)malloc((size_t)(nparts + 1) * sizeof(int));
+    int64_t *link_free = (int64_t *)calloc((size_t)pp * pp, sizeof(int64_t));   /* [sender][receiver]: free again at */
+    uint8_t *seen = NULL;
+#define FREE_X() do { free(place); free(pf); free(bnd); free(link_free); free(seen); } while (0)
+    for (int k = 0; k < S; k++) next[k] = -1;
+    for (int k = 0; k < S; k++) {
+        place[k] = st[3 * k]; part[k] = st[3 * k + 1]; prev[k] = st[3 * k + 2];
+        if (place[k] < 0 || place[k] >= pp || part[k] < 0 || part[k] >= nparts || prev[k] < -1 || prev[k] >= S || prev[k] == k) {
+            FREE_X(); return;
+        }
+    }
+    for (int k = 0; k < S; k++) if (prev[k] >= 0) { if (next[prev[k]] >= 0) { FREE_X(); return; } next[prev[k]] = k; }
     if (bnd_in) {
+        int okp = 1;
         for (int q = 0; q <= nparts; q++) bnd[q] = bnd_in[q];
-        if (bnd[0] != 0 || bnd[nparts] != L) return;
-        for (int q = 0; q < nparts; q++) if (bnd[q + 1] <= bnd[q]) return;
+        if (bnd[0] != 0 || bnd[nparts] != L) okp = 0;
+        for (int q = 0; q < nparts && okp; q++) if (bnd[q + 1] <= bnd[q]) okp = 0;
+        if (!okp) { FREE_X(); return; }
     } else {
         for (int q = 0; q <= nparts; q++) bnd[q] = (int)(((int64_t)q * L) / nparts);
     }
@@ -687,7 +721,7 @@ static void simulate_explicit(const costs_t *co, const cluster_t *cl,
         sc->arrF = (uint8_t *)realloc(sc->arrF, (size_t)narr);
         sc->arrB = (uint8_t *)realloc(sc->arrB, (size_t)narr);
     }
-    uint8_t *seen = (uint8_t *)calloc((size_t)(2 * narr), 1);
+    seen = (uint8_t *)calloc((size_t)(2 * narr), 1);
     int okl = 1;
     for (int d = 0; d < pp && okl; d++)
         for (int64_t i = dev_off[d]; i < dev_off[d + 1]; i++) {
@@ -696,16 +730,14 @@ static void simulate_explicit(const costs_t *co, const cluster_t *cl,
             if (k >= S || j >= m || place[k] != d || seen[((int64_t)kd * S + k) * m + j]) { okl = 0; break; }
             seen[((int64_t)kd * S + k) * m + j] = 1;
         }
-    if (!okl) { free(seen); return; }
+    if (!okl) { FREE_X(); return; }
 
     const int64_t *fc = co->fc + (int64_t)v * L, *bc = co->bc + (int64_t)v * L;
     const int64_t *fa = co->fa + (int64_t)v * L, *ba = co->ba + (int64_t)v * L;
     const int64_t *act = co->act + (int64_t)v * L, *grad = co->grad + (int64_t)v * L;
     const int64_t *a2a = co->a2a + (int64_t)v * L;
     /* p2p event on the edge prev[k] -> k, both directions: the activation that leaves prev[k] */
-    int64_t pf[64], pb[64];
     const int64_t g = cl->gpus_per_node;
-    for (int k = 0; k < S; k++) { pf[k] = 0; pb[k] = 0; }
     for (int k = 0; k < S; k++) if (prev[k] >= 0) {
         int q = prev[k];
         int64_t na = ((int64_t)place[q] * tp * dp) / g, nb = ((int64_t)place[k] * tp * dp) / g;
@@ -723,7 +755,7 @@ static void simulate_explicit(const costs_t *co, const cluster_t *cl,
             }
             t1 += (unsigned __int128)(pf[k] + pb[k]);
         }
-        if (t1 * (unsigned __int128)m >= ((unsigned __int128)1 << 53)) { free(seen); res->status = ST_RANGE; return; }
+        if (t1 * (unsigned __int128)m >= ((unsigned __int128)1 << 53)) { FREE_X(); res->status = ST_RANGE; return; }
     }
 
     memset(sc->arrF, 0, (size_t)narr);
@@ -789,11 +821,27 @@ static void simulate_explicit(const costs_t *co, const cluster_t *cl,
             if (kd == 0) {
                 doneF[(int64_t)k * m + j] = 1;
                 if (next[k] >= 0) {
-                    heap_push(h, now + (cl->p2p_blocking == 1 ? 0 : pf[k]), EV_ARRIVE_F, next[k], j, 0);
+                    int64_t arrive = now + pf[k];
+                    if (cl->p2p_blocking == 1) arrive = now;
+                    if (cl->p2p_blocking == 2) {     /* one transfer at a time from this device to that one */
+                        int64_t *lf = &link_free[(int64_t)d * pp + place[next[k]]];
+                        int64_t depart = now > *lf ? now : *lf;
+                        arrive = depart + pf[k];
+                        *lf = arrive;
+                    }
+                    heap_push(h, arrive, EV_ARRIVE_F, next[k], j, 0);
                     mb_[d] += pf[k]; nev++;
                 }
             } else if (prev[k] >= 0) {
-                heap_push(h, now + (cl->p2p_blocking == 1 ? 0 : pb[k]), EV_ARRIVE_B, prev[k], j, 0);
+                int64_t arrive = now + pb[k];
+                if (cl->p2p_blocking == 1) arrive = now;
+                if (cl->p2p_blocking == 2) {
+                    int64_t *lf = &link_free[(int64_t)d * pp + place[prev[k]]];
+                    int64_t depart = now > *lf ? now : *lf;
+                    arrive = depart + pb[k];
+                    *lf = arrive;
+                }
+                heap_push(h, arrive, EV_ARRIVE_B, prev[k], j, 0);
                 mb_[d] += pb[k]; nev++;
             }
             if (nxt[d] == dev_off[d + 1] && (int64_t)dp * replicas > 1) {      /* the device's gradient all-reduce */
@@ -824,7 +872,8 @@ static void simulate_explicit(const costs_t *co, const cluster_t *cl,
         }
     }
 #undef TRY_START_X
-    free(seen);
+    FREE_X();
+#undef FREE_X
     if (ran != ntask) return;                  /* some list could not be run to its end */
     res->status = ST_OK;
     res->batch_ns = now;
@@ -846,7 +895,7 @@ int oracle_simulate(int32_t L, int32_t V, const int32_t *variant_tp,
                     const int64_t *alpha2, const int64_t *beta2, int64_t bucket, int32_t p2p_blocking,
                     int64_t C, const int32_t *dp, const int32_t *tp, const int32_t *pp, const int32_t *m,
                     const uint8_t *schedule, const int32_t *chunks /* or NULL */, const int64_t *part_off,
-                    const uint8_t *part_pool,
+                    const uint8_t *part_pool, int64_t part_pool_len,
                     int64_t n_sched, const int64_t *sched_off /* [n_sched+1] or NULL */, const int32_t *sched_words,
                     int64_t sched_words_len,
                     int32_t *status, int64_t *batch_ns, int64_t *num_events, int64_t *stage_off,
@@ -871,7 +920,15 @@ int oracle_simulate(int32_t L, int32_t V, const int32_t *variant_tp,
             int64_t *buf = NULL;
             if (p >= 1 && p <= MAX_PP) buf = (int64_t *)malloc((size_t)p * 3 * sizeof(int64_t));
             result_t r;
-            const uint8_t *b = part_off[c] >= 0 ? part_pool + part_off[c] : NULL;
+            /* part_off: -1 = uniform split, else an offset into the pool; anything else is no strategy */
+            const int64_t po = part_off[c];
+            const uint8_t *b = po >= 0 && po < part_pool_len ? part_pool + po : NULL;
+            const int64_t avail = b ? part_pool_len - po : 0;
+            if (po < -1 || (po >= 0 && !b)) {
+                status[c] = ST_INVALID; batch_ns[c] = INT64_MAX; num_events[c] = 0; slots[c] = 0;
+                free(buf);
+                continue;
+            }
             if (schedule[c] == 4) {
                 const int32_t *blk = NULL;
                 int64_t nw = 0;
@@ -881,15 +938,15 @@ int oracle_simulate(int32_t L, int32_t V, const int32_t *variant_tp,
                     blk = sched_words + sched_off[chunks[c]];
                     nw = sched_off[chunks[c] + 1] - sched_off[chunks[c]];
                 }
-                simulate_explicit(&co, &cl, dp[c], tp[c], p, m[c], blk, nw, b, &sc, &r,
+                simulate_explicit(&co, &cl, dp[c], tp[c], p, m[c], blk, nw, b, avail, &sc, &r,
                                   buf, buf ? buf + p : NULL, buf ? (double *)(buf + 2 * p) : NULL,
                                   C == 1 ? tl_start : NULL, C == 1 ? tl_end : NULL, C == 1 ? tl_ar : NULL);
             } else if (schedule[c] == 3)
-                simulate_interleaved(&co, &cl, dp[c], tp[c], p, m[c], chunks ? chunks[c] : 0 /* no chunk counts: invalid */, b, &sc, &r,
+                simulate_interleaved(&co, &cl, dp[c], tp[c], p, m[c], chunks ? chunks[c] : 0 /* no chunk counts: invalid */, b, avail, &sc, &r,
                                      buf, buf ? buf + p : NULL, buf ? (double *)(buf + 2 * p) : NULL,
                                      C == 1 ? tl_start : NULL, C == 1 ? tl_end : NULL, C == 1 ? tl_ar : NULL);
             else
-                simulate_one(&co, &cl, dp[c], tp[c], p, m[c], schedule[c], b, &sc, &r,
+                simulate_one(&co, &cl, dp[c], tp[c], p, m[c], schedule[c], b, avail, &sc, &r,
                              buf, buf ? buf + p : NULL, buf ? (double *)(buf + 2 * p) : NULL,
                              C == 1 ? tl_start : NULL, C == 1 ? tl_end : NULL, C == 1 ? tl_ar : NULL);
             status[c] = r.status;
@@ -916,6 +973,67 @@ int oracle_simulate(int32_t L, int32_t V, const int32_t *variant_tp,
     stage_off[C] = off;
     free(tmp_c);
     free(slots);
+    return 0;
+}
+
+/* The composed events of every pipeline stage, written out from their definitions with plain loops
+ * over the stage's layers (Sec. 4.3: a layer is a computation event, plus an all-reduce event when
+ * MP > 1; a stage is the list of its layers' events).  For the candidates with status[c] == 0 and
+ * one of the schedules 0..2, entry i = stage_off[c] + s of the columns
+ *   0 FC, 2 BC  forward / backward computation of the stage's layers
+ *   1 FA, 3 BA  communication inside the stage: the layers' all-reduce events (tp > 1) and
+ *               all-to-all events over the dp group
+ *   4 PF, 5 PB  p2p event towards stage s+1 / s-1: the activation that crosses that boundary
+ *   6 G         gradient bytes, 7 AR the ring all-reduce of G over dp ranks (Sec. 4.2 volume; 0 for
+ *               the asynchronous schedule, which has no such event)
+ * and layer_lo / layer_hi = the stage's layers [lo, hi).  Candidates of the schedules 3 and 4 keep
+ * zeros (their outputs are per device).  tab is [8][n] with n = stage_off[C]. */
+int oracle_stage_table(int32_t L, int32_t V, const int32_t *variant_tp,
+                       const int64_t *fc, const int64_t *bc, const int64_t *fa, const int64_t *ba,
+                       const int64_t *act, const int64_t *grad, const int64_t *a2a,
+                       int32_t num_devices, int32_t gpus_per_node,
+                       const int64_t *alpha2, const int64_t *beta2,
+                       int64_t C, const int32_t *dp, const int32_t *tp, const int32_t *pp,
+                       const uint8_t *schedule, const int64_t *part_off, const uint8_t *part_pool,
+                       const int32_t *status, const int64_t *stage_off,
+                       int64_t *tab, int32_t *layer_lo, int32_t *layer_hi) {
+    if (L < 1 || V < 1 || C < 0) return -1;
+    cluster_t cl = { num_devices, gpus_per_node, { alpha2[0], alpha2[1] }, { beta2[0], beta2[1] }, 0, 0 };
+    const int64_t n = stage_off[C];
+    memset(tab, 0, (size_t)(8 * n) * sizeof(int64_t));
+    memset(layer_lo, 0, (size_t)n * sizeof(int32_t));
+    memset(layer_hi, 0, (size_t)n * sizeof(int32_t));
+    for (int64_t c = 0; c < C; c++) {
+        if (status[c] != ST_OK || schedule[c] > 2) continue;
+        const int P = pp[c];
+        int v = -1;
+        for (int i = 0; i < V; i++) if (variant_tp[i] == tp[c]) { v = i; break; }
+        if (v < 0) return -2;
+        for (int s = 0; s < P; s++) {
+            const int lo = part_off[c] >= 0 ? part_pool[part_off[c] + s] : (int)(((int64_t)s * L) / P);
+            const int hi = part_off[c] >= 0 ? part_pool[part_off[c] + s + 1] : (int)(((int64_t)(s + 1) * L) / P);
+            const int64_t i = stage_off[c] + s;
+            int64_t FC = 0, FA = 0, BC = 0, BA = 0, G = 0;
+            for (int l = lo; l < hi; l++) {
+                const int64_t x = (int64_t)v * L + l;
+                FC += fc[x];
+                BC += bc[x];
+                if (tp[c] > 1) { FA += fa[x]; BA += ba[x]; }
+                FA += alltoall_ns(&cl, dp[c], a2a[x]);
+                BA += alltoall_ns(&cl, dp[c], a2a[x]);
+                G += grad[x];
+            }
+            /* ranks ordered tp fastest, then dp, then pp: node of the first rank of a pipeline position */
+            const int64_t per = (int64_t)tp[c] * dp[c], g = gpus_per_node;
+            int64_t PF = 0, PB = 0;
+            if (s + 1 < P) PF = p2p_ns(&cl, act[(int64_t)v * L + hi - 1], (s * per) / g == ((s + 1) * per) / g ? 0 : 1);
+            if (s > 0) PB = p2p_ns(&cl, act[(int64_t)v * L + lo - 1], ((s - 1) * per) / g == (s * per) / g ? 0 : 1);
+            tab[0 * n + i] = FC; tab[1 * n + i] = FA; tab[2 * n + i] = BC; tab[3 * n + i] = BA;
+            tab[4 * n + i] = PF; tab[5 * n + i] = PB; tab[6 * n + i] = G;
+            tab[7 * n + i] = schedule[c] == 2 ? 0 : allreduce_ns(&cl, dp[c], G);
+            layer_lo[i] = lo; layer_hi[i] = hi;
+        }
+    }
     return 0;
 }
 

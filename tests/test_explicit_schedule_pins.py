@@ -43,7 +43,7 @@ def same_result(a, b, ia, ib, what):
 
 def test_builtin_schedules_written_out_as_lists(oracle_mod):
     rng = np.random.default_rng(5)
-    for trial in range(120):
+    for trial in range(180):
         pp = int(rng.integers(1, 7))
         v = int(rng.integers(1, 4))
         m = pp * int(rng.integers(1, 4)) if trial % 3 == 2 else int(rng.integers(1, 9))
@@ -51,8 +51,10 @@ def test_builtin_schedules_written_out_as_lists(oracle_mod):
         dp = int(rng.choice([1, 2, 3]))
         L = pp * v + int(rng.integers(0, 5))
         costs = rand_costs(rng, L, tps=(1, 2))
-        blocking = int(rng.integers(0, 2))
+        blocking = int(rng.integers(0, 3))          # latency on the edge, send on the device, sends queue on their link
         cl = mk_cluster(dp * tp * pp, g=int(rng.choice([1, 2, 4, 64])), alpha=(3, 11), beta=(5, 2), blocking=blocking)
+        if blocking == 2:                           # transfers long enough to queue
+            costs["act_bytes"] = costs["act_bytes"] * 20
         if trial % 3 == 2:                          # interleaved
             S = pp * v
             bnd = [0] + sorted(rng.choice(np.arange(1, L), S - 1, replace=False).tolist()) + [L]
@@ -202,6 +204,93 @@ def test_random_schedules_against_the_task_graph(oracle_mod):
         assert r["num_events"][0] == ntask + nsend + nar, trial
 
 
+def test_serialised_links_against_graph_with_send_nodes(oracle_mod):
+    """p2p_blocking = 2 for explicit schedules: the sender goes on, every transfer is a node of its own.
+    A link is an ordered pair (sending device, receiving device) and carries one transfer at a time:
+    a send starts when its task has ended and the send before it on that link (in the order of the
+    sending device's list) has arrived; the consumer waits for the arrival.  Solved by relaxation."""
+    rng = np.random.default_rng(414)
+    queued = 0
+    for trial in range(200):
+        pp = int(rng.integers(1, 5))
+        S = int(rng.integers(1, 9))
+        m = int(rng.integers(1, 5))
+        nparts = int(rng.integers(1, 5))
+        L = nparts + int(rng.integers(0, 4))
+        bnd = [0] + sorted(rng.choice(np.arange(1, L), nparts - 1, replace=False).tolist()) + [L]
+        place, prev, lists = random_schedule(rng, pp, S, m)
+        part = [int(rng.integers(0, nparts)) for _ in range(S)]
+        fc, bc = rng.integers(0, 30, L).tolist(), rng.integers(0, 30, L).tolist()
+        act = (rng.integers(0, 40, L) * 5).tolist()              # transfers often longer than the tasks
+        costs = mk_costs(fc, bc, act=act)
+        g = int(rng.choice([1, 2, 1 << 20]))
+        blk = pack_schedule(pp, list(zip(place, part, prev)), m, nparts, 1, lists)
+        w = with_schedules(mk(costs, mk_cluster(pp, g=g, alpha=(2, 7), beta=(5, 1), blocking=2), [(1, 1, pp, m, 4, bnd, 0)]), [blk], [0])
+        r = oracle_mod.simulate(w, timeline=True)
+        assert r["status"][0] == 0, trial
+        Fd = [sum(fc[bnd[part[k]]:bnd[part[k] + 1]]) for k in range(S)]
+        Bd = [sum(bc[bnd[part[k]]:bnd[part[k] + 1]]) for k in range(S)]
+        nxt = {prev[k]: k for k in range(S) if prev[k] >= 0}
+        pf, pb = [0] * S, [0] * S
+        for k in range(S):
+            if prev[k] >= 0:
+                q = prev[k]
+                cls = 0 if place[q] // g == place[k] // g else 1
+                t = (2, 7)[cls] + act[bnd[part[q] + 1] - 1] // (5, 1)[cls]
+                pf[q], pb[k] = t, t
+        dur = lambda n: Fd[n[1]] if n[0] == FWD else Bd[n[1]]
+        # where the transfer after a task goes, and how long it takes (None: the task sends nothing)
+        def send_of(n):
+            kd, k, _ = n
+            if kd == FWD and k in nxt:
+                return place[nxt[k]], pf[k]
+            if kd == BWD and prev[k] >= 0:
+                return place[prev[k]], pb[k]
+            return None
+        preds = {}                     # node -> [(node before it, time from that node's START to this node's start)]
+        for d, lst in enumerate(lists):
+            last_on_link = {}
+            for i, t in enumerate(lst):
+                kd, k, j = t
+                p = [(("T",) + lst[i - 1], dur(lst[i - 1]))] if i > 0 else []
+                if kd == FWD and prev[k] >= 0:
+                    p.append((("S", FWD, prev[k], j), pf[prev[k]]))
+                if kd == BWD:
+                    p.append((("S", BWD, nxt[k], j), pb[nxt[k]]) if k in nxt else (("T", FWD, k, j), Fd[k]))
+                preds[("T",) + t] = p
+                sd = send_of(t)
+                if sd is not None:
+                    q = [(("T",) + t, dur(t))]
+                    if sd[0] in last_on_link:
+                        before = last_on_link[sd[0]]
+                        q.append((("S",) + before, send_of(before)[1]))
+                    preds[("S",) + t] = q
+                    last_on_link[sd[0]] = t
+        start = {n: 0 for n in preds}
+        changed, rounds = True, 0
+        while changed:
+            changed = False
+            rounds += 1
+            assert rounds < 20 * len(preds) + 10
+            for n, ps in preds.items():
+                val = max([start[q] + wgt for q, wgt in ps], default=0)
+                if val != start[n]:
+                    start[n] = val
+                    changed = True
+        for n, val in start.items():
+            if n[0] == "T":
+                assert r["start"][n[1], n[2], n[3]] == val, (trial, n)
+                assert r["end"][n[1], n[2], n[3]] == val + dur(n[1:]), (trial, n)
+        assert r["batch_ns"][0] == max(start[("T",) + t] + dur(t) for lst in lists for t in lst), trial
+        for d, lst in enumerate(lists):
+            assert r["comm_busy_ns"][d] == sum(send_of(t)[1] for t in lst if send_of(t) is not None)
+        w.cluster["p2p_blocking"] = 0
+        free = oracle_mod.simulate(w)
+        assert r["batch_ns"][0] >= free["batch_ns"][0]
+        queued += int(r["batch_ns"][0] > free["batch_ns"][0])
+    assert queued > 10                 # the queueing really delays a good number of the cases
+
+
 def test_bidirectional_lists_run_and_use_both_directions(oracle_mod):
     """Two pipelines in opposite directions: every device list is a merge of the two early-backward
     orders; the run ends, both replicas' gradients are reduced over dp * 2 ranks, and with equal
@@ -240,7 +329,7 @@ def test_invalid_explicit_schedules(oracle_mod):
     assert status(good) == 0
     assert status(good, ids=(1,)) == 1 and status(good, ids=(-1,)) == 1            # no such schedule
     assert status(good, row=(1, 1, pp, 3, 4, None, 0)) == 1                          # m differs
-    assert status(good, cluster=mk_cluster(pp, blocking=2)) == 1                     # no link queues
+    assert status(good, cluster=mk_cluster(pp, blocking=2)) == 0                     # link queues are modelled
     lists = dapple_lists(pp, m)
     swapped = [lists[0], [lists[1][1], lists[1][0]] + lists[1][2:]]                  # B(1,0) before F(1,0): never ready
     assert status(pack_schedule(pp, chain(pp), m, pp, 1, swapped)) == 1

@@ -10,6 +10,7 @@ import pytest
 import oracle
 import test_explicit_schedule_pins as xpins
 import test_oracle_pins as pins
+import test_stage_table_pins as spins
 
 SRC = os.path.join(os.path.dirname(os.path.abspath(oracle.__file__)), "distsim_oracle.c")
 
@@ -40,7 +41,7 @@ MUTANTS = [
     ("GPipe backward before the last forward", "for (int i = 0; i < m; i++) { k[n] = 0; j[n++] = i; }\n            for (int i = 0; i < m; i++) { k[n] = 1; j[n++] = i; }",
      "for (int i = 0; i < m - 1; i++) { k[n] = 0; j[n++] = i; }\n            k[n] = 1; j[n++] = 0; k[n] = 0; j[n++] = m - 1;\n            for (int i = 1; i < m; i++) { k[n] = 1; j[n++] = i; }"),
     ("interleaved: warm-up of the plain schedule", "int64_t W = 2ll * (pp - d - 1) + (int64_t)(vch - 1) * pp;", "int64_t W = (pp - d - 1) + (int64_t)(vch - 1) * pp;"),
-    ("interleaved: backward chunks not mirrored", "kk[n] = 1; vs[n] = (uint8_t)((vch - 1 - w__ / pp) * pp + d);", "kk[n] = 1; vs[n] = (uint8_t)((w__ / pp) * pp + d);"),
+    ("interleaved: backward chunks not mirrored", "kk[n] = 1; vs[n] = (int32_t)((vch - 1 - w__ / pp) * pp + d);", "kk[n] = 1; vs[n] = (int32_t)((w__ / pp) * pp + d);"),
     ("interleaved: micro-batch groups ignored", "jj[n] = (int32_t)((i__ / ((int64_t)pp * vch)) * pp + w__ % pp); n++; } while (0)\n#define PUT_B", "jj[n] = (int32_t)(w__ % pp); n++; } while (0)\n#define PUT_B"),
     ("interleaved: link class by virtual stage", "int64_t na = ((int64_t)(k % pp) * tp * dp) / g, nb = ((int64_t)((k + 1) % pp) * tp * dp) / g;", "int64_t na = ((int64_t)k * tp * dp) / g, nb = ((int64_t)(k + 1) * tp * dp) / g;"),
     ("interleaved: all-reduce of one chunk only", "for (int c = 0; c < vch; c++)\n                    for (int l = bnd[c * pp + d]; l < bnd[c * pp + d + 1]; l++) G += grad[l];", "for (int c = 0; c < 1; c++)\n                    for (int l = bnd[c * pp + d]; l < bnd[c * pp + d + 1]; l++) G += grad[l];"),
@@ -49,7 +50,21 @@ MUTANTS = [
     ("explicit: link class by stage number", "int64_t na = ((int64_t)place[q] * tp * dp) / g, nb = ((int64_t)place[k] * tp * dp) / g;", "int64_t na = ((int64_t)q * tp * dp) / g, nb = ((int64_t)k * tp * dp) / g;"),
     ("explicit: all-reduce ignores the replicas", "int64_t dd = allreduce_ns(cl, (int64_t)dp * replicas, G);", "int64_t dd = allreduce_ns(cl, (int64_t)dp, G);"),
     ("explicit: gradient bytes of every stage on every device", "for (int q = 0; q < S; q++) if (place[q] == d)\n                    for (int l = bnd[part[q]]", "for (int q = 0; q < S; q++)\n                    for (int l = bnd[part[q]]"),
-    ("explicit: backward gradient goes to the stage after", "heap_push(h, now + (cl->p2p_blocking == 1 ? 0 : pb[k]), EV_ARRIVE_B, prev[k], j, 0);\n                mb_[d] += pb[k]; nev++;\n            }\n            if (nxt[d] == dev_off[d + 1]", "heap_push(h, now, EV_ARRIVE_B, prev[k], j, 0);\n                mb_[d] += pb[k]; nev++;\n            }\n            if (nxt[d] == dev_off[d + 1]"),
+    ("explicit: latency of the backward edge dropped", "int64_t arrive = now + pb[k];\n                if (cl->p2p_blocking == 1) arrive = now;\n                if (cl->p2p_blocking == 2) {\n                    int64_t *lf = &link_free[(int64_t)d * pp + place[prev[k]]];",
+     "int64_t arrive = now;\n                if (cl->p2p_blocking == 1) arrive = now;\n                if (cl->p2p_blocking == 2) {\n                    int64_t *lf = &link_free[(int64_t)d * pp + place[prev[k]]];"),
+    ("explicit: links do not serialise", "int64_t *lf = &link_free[(int64_t)d * pp + place[next[k]]];\n                        int64_t depart = now > *lf ? now : *lf;",
+     "int64_t *lf = &link_free[(int64_t)d * pp + place[next[k]]];\n                        int64_t depart = now;"),
+    ("explicit: one queue per sending device, whatever the receiver", "int64_t *lf = &link_free[(int64_t)d * pp + place[prev[k]]];", "int64_t *lf = &link_free[(int64_t)d * pp];"),
+    ("explicit: one queue per receiving device, whatever the sender", "int64_t *lf = &link_free[(int64_t)d * pp + place[next[k]]];", "int64_t *lf = &link_free[place[next[k]]];"),
+    ("interleaved: links do not serialise", "int64_t *lf = &link_free[(int64_t)d * pp + (k + 1) % pp];\n                    int64_t depart = now > *lf ? now : *lf;",
+     "int64_t *lf = &link_free[(int64_t)d * pp + (k + 1) % pp];\n                    int64_t depart = now;"),
+    ("interleaved: a queue per chunk boundary instead of per pair of devices", "int64_t *lf = &link_free[(int64_t)d * pp + (k - 1) % pp];", "int64_t *lf = &link_free[(int64_t)(k % (pp * pp))];"),
+    ("stage table: p2p bytes of the next stage's first layer", "PF = p2p_ns(&cl, act[(int64_t)v * L + hi - 1],", "PF = p2p_ns(&cl, act[(int64_t)v * L + (hi < L ? hi : L - 1)],"),
+    ("stage table: backward p2p with the class of the other boundary", "((s - 1) * per) / g == (s * per) / g ? 0 : 1", "(s * per) / g == ((s + 1) * per) / g ? 0 : 1"),
+    ("stage table: all-reduce column for the asynchronous schedule", "tab[7 * n + i] = schedule[c] == 2 ? 0 : allreduce_ns(&cl, dp[c], G);", "tab[7 * n + i] = allreduce_ns(&cl, dp[c], G);"),
+    ("stage table: all-reduce events of a tp = 1 layer", "if (tp[c] > 1) { FA += fa[x]; BA += ba[x]; }", "{ FA += fa[x]; BA += ba[x]; }"),
+    ("stage table: all-to-all in the forward pass only", "                BA += alltoall_ns(&cl, dp[c], a2a[x]);\n", ""),
+    ("stage table: stage bounds of the uniform split rounded up", "(int)(((int64_t)(s + 1) * L) / P);\n            const int64_t i", "(int)(((int64_t)(s + 1) * L + P - 1) / P);\n            const int64_t i"),
     ("utilisation from communication", "util[s] = now > 0 ? (double)cb[s] / (double)now : 0.0;", "util[s] = now > 0 ? (double)mb_[s] / (double)now : 0.0;"),
 ]
 
@@ -79,8 +94,12 @@ PINS = [
     pins.test_interleaved_link_classes_follow_the_devices,
     xpins.test_builtin_schedules_written_out_as_lists,
     xpins.test_random_schedules_against_the_task_graph,
+    xpins.test_serialised_links_against_graph_with_send_nodes,
     xpins.test_bidirectional_lists_run_and_use_both_directions,
     xpins.test_invalid_explicit_schedules,
+    spins.test_tiny_golden_stage_events,
+    spins.test_every_column_against_discrete_event_timelines,
+    lambda o: spins.test_busy_time_identities(o, "gpt24"),
 ]
 
 
@@ -112,6 +131,7 @@ def test_planted_mistake_is_caught(oracle_mod, tmp_path, name, old, new):
     mutant = ctypes.CDLL(str(so))
     mutant.oracle_simulate.restype = ctypes.c_int
     mutant.oracle_search.restype = ctypes.c_int
+    mutant.oracle_stage_table.restype = ctypes.c_int
     oracle._lib = mutant
     try:
         assert _caught(oracle_mod), f"no pin notices: {name}"

@@ -793,8 +793,14 @@ def test_interleaved_validity_rules(oracle_mod):
     assert ok((1, 1, 4, 8, 3, None, 0)) == 1
     assert ok((1, 1, 4, 8, 3, list(range(13)), 3)) == 0
     assert ok((1, 1, 4, 8, 3, [0, 3, 6, 9, 12], 3)) == 1     # boundaries of 4 parts where 12 are needed
-    cl2 = mk_cluster(4, g=1 << 20, blocking=2)
-    assert int(one(oracle_mod, costs, cl2, (1, 1, 4, 8, 3, None, 3))["status"][0]) == 1
+    cl2 = mk_cluster(4, g=1 << 20, blocking=2)                  # link queues are modelled for this schedule too
+    assert int(one(oracle_mod, costs, cl2, (1, 1, 4, 8, 3, None, 3))["status"][0]) == 0
+    # nothing but the layer count bounds the number of virtual stages, nothing bounds the micro-batches
+    many = mk_costs([5] * 200, [7] * 200)
+    assert int(one(oracle_mod, many, cl, (1, 1, 4, 8, 3, None, 50))["status"][0]) == 0      # 200 virtual stages
+    assert int(one(oracle_mod, many, cl, (1, 1, 4, 8, 3, None, 51))["status"][0]) == 1      # 204 > 200 layers
+    r = one(oracle_mod, costs, mk_cluster(1), (1, 1, 1, (1 << 16) + 3, 1, None))
+    assert int(r["status"][0]) == 0 and int(r["batch_ns"][0]) == ((1 << 16) + 3) * 12 * 12
     # one chunk per device is a valid degenerate case: Dapple's order with a warm-up twice as deep,
     # which hides the p2p latencies that Dapple's steady state leaves exposed
     a = one(oracle_mod, costs, cl, (1, 1, 4, 8, 3, None, 1))
