@@ -116,7 +116,7 @@ def time_variants(ds, ctx, w, n):
 
         def stepv():
             ds.distsim_build_events(ctx, dwv, evv)
-            ds.distsim_simulate(ctx, dwv.cluster, evv, outv)
+            ds.distsim_simulate(ctx, dwv, evv, outv)
             ds.distsim_search(ctx, outv.batch_ns, dwv.C, bestv, scr)
         stepv()
         torch.cuda.synchronize()
@@ -187,7 +187,7 @@ def main() -> int:
 
     def step():
         ds.distsim_build_events(ctx, dw, ev)
-        ds.distsim_simulate(ctx, dw.cluster, ev, out)
+        ds.distsim_simulate(ctx, dw, ev, out)
         ds.distsim_search(ctx, out.batch_ns, dw.C, best, scratch)
 
     for _ in range(args.warmup):
@@ -237,15 +237,15 @@ def main() -> int:
         t_end = torch.empty_like(t_start)
         ar0 = torch.empty((nsel, 64), dtype=torch.int64, device=ctx.device)
         ar1 = torch.empty_like(ar0)
-        ds.distsim_timeline(ctx, dw.cluster, ev, d_sel, d_off, t_start, t_end, ar0, ar1)      # warm-up
+        ds.distsim_timeline(ctx, dw, ev, d_sel, d_off, t_start, t_end, ar0, ar1)      # warm-up
         torch.cuda.synchronize()
         ctx.timing_enable(True)
         for _ in range(5):
-            ds.distsim_timeline(ctx, dw.cluster, ev, d_sel, d_off, t_start, t_end, ar0, ar1)
+            ds.distsim_timeline(ctx, dw, ev, d_sel, d_off, t_start, t_end, ar0, ar1)
         torch.cuda.synchronize()
         t_idle = torch.empty_like(t_start)
         for _ in range(5):
-            ds.distsim_bubbles(ctx, ev, d_sel, d_off, t_start, t_end, t_idle)
+            ds.distsim_bubbles(ctx, dw, ev, d_sel, d_off, t_start, t_end, t_idle)
         torch.cuda.synchronize()
         kt3 = ctx.timing_read()
         tl_ms, tl_n = kt3["k_timeline"]

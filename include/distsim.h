@@ -10,6 +10,8 @@
  * search of Sec. 6 picks the best candidate.
  *
  * Conventions that hold for every call
+ *  - Every call makes the context's device current for its own duration and restores the
+ *    caller's current device before it returns.
  *  - "device pointer" = memory of the HIP device the context was created on, owned by the
  *    caller (e.g. a PyTorch tensor).  The library never frees or reallocates caller memory
  *    and allocates no device memory itself; everything it needs beyond the inputs and
@@ -20,9 +22,10 @@
  *  - All times are int64 nanoseconds, all sizes int64 bytes.
  *  - Return value: DISTSIM_OK, or a negative code; text via distsim_last_error().
  *    A *candidate* that is not a valid strategy is not a call error: see `status`.
- *  - Preconditions on table entries (not checked): 0 <= time < 2^40 ns, 0 <= bytes < 2^40,
- *    0 <= alpha < 2^40, 1 <= beta < 2^32, num_devices <= 2^14, so that no product in the
- *    collective formulas below leaves 63 bits.
+ *  - Preconditions on table entries (device memory, not checked): 0 <= time < 2^40 ns,
+ *    0 <= bytes < 2^40.  The cluster description (host memory) is checked: 0 <= alpha < 2^40,
+ *    1 <= beta < 2^32, num_devices <= 2^22, bucket bytes < 2^53, else DISTSIM_ERANGE.  Together
+ *    they keep every product in the collective formulas below within 63 bits.
  */
 #ifndef DISTSIM_H
 #define DISTSIM_H
@@ -35,9 +38,16 @@ extern "C" {
 #endif
 
 #define DISTSIM_OK       0
-#define DISTSIM_EINVAL  (-1)   /* null pointer, negative size, unsupported shape            */
-#define DISTSIM_ERANGE  (-2)   /* a size exceeds a documented limit                          */
+#define DISTSIM_EINVAL  (-1)   /* null pointer, negative size, inconsistent arguments        */
+#define DISTSIM_ERANGE  (-2)   /* a cost or bound of the cluster description would let the
+                                  collective formulas leave their integer range: alpha >= 2^40,
+                                  beta >= 2^32, bucket bytes >= 2^53 or more than 2^22 devices
+                                  (table entries live in device memory and are not inspected by
+                                  the host; times that would pass 2^53 are caught per candidate,
+                                  see DISTSIM_ST_RANGE)                                        */
 #define DISTSIM_EHIP    (-3)   /* HIP runtime error                                          */
+#define DISTSIM_ELIMIT  (-4)   /* a size is beyond a documented limit of this library (C, L, V,
+                                  n, K)                                                        */
 
 #define DISTSIM_MAX_PP   64    /* pipeline stages per candidate (one 64-lane wavefront)      */
 #define DISTSIM_MAX_L    255   /* layers (partition boundaries are bytes)                    */
@@ -51,7 +61,8 @@ extern "C" {
                                   chunks[c] model chunks; virtual stage k = chunk * pp + device
                                   owns the k-th of pp * chunks parts of the layers (part_pool
                                   then holds pp * chunks + 1 boundaries).  Needs m % pp == 0,
-                                  pp * chunks <= min(64, L), p2p_blocking != 2.  Forward slot i
+                                  pp * chunks <= L (more than 64 virtual stages, or p2p_blocking
+                                  == 2, is DISTSIM_ST_UNSUPPORTED).  Forward slot i
                                   of a device: chunk (i mod (pp chunks)) / pp, micro-batch
                                   (i / (pp chunks)) pp + i mod pp; backward slot i: the mirrored
                                   chunk.  Device d runs 2 (pp-d-1) + (chunks-1) pp forwards,
@@ -78,10 +89,11 @@ extern "C" {
                                   needs B(next k, j) and its p2p event, or on a stage without successor
                                   its own F(k, j).  A device runs its list in order.  One gradient
                                   all-reduce per device after its list, over the bytes of the parts of
-                                  all its stages.  pp and m must equal the candidate's, S * m <=
-                                  DISTSIM_MAX_SLOTS, p2p_blocking != 2.  A schedule that cannot be run
-                                  to its end is invalid, as is a malformed block.  Per-stage outputs
-                                  are per device; no stage table.                                 */
+                                  all its stages.  pp and m must equal the candidate's.  A schedule that
+                                  cannot be run to its end is invalid, as is a malformed block; one with
+                                  S > 64, nparts > 64, S * m > DISTSIM_MAX_SLOTS or under p2p_blocking ==
+                                  2 is DISTSIM_ST_UNSUPPORTED.  Per-stage outputs are per device; no
+                                  stage table.                                                     */
 #define DISTSIM_MAX_SLOTS 2048 /* (virtual stage, micro-batch) pairs of an explicit schedule       */
 #define DISTSIM_1F1B_ASYNC 2   /* asynchronous pipeline (Sec. 7, discussion of new algorithms):
                                   the Dapple order without the global synchronisation event, i.e.
@@ -91,11 +103,17 @@ extern "C" {
 #define DISTSIM_ST_OK       0
 #define DISTSIM_MAX_M    65536 /* micro-batches per candidate                                 */
 #define DISTSIM_ST_INVALID  1  /* "unreachable" strategy (Sec. 6): dp*tp*pp != devices, pp > L,
-                                  pp > DISTSIM_MAX_PP, m < 1, m > DISTSIM_MAX_M, no table variant
-                                  for tp, unknown schedule, or a partition that is not
-                                  0 = b0 < b1 < ... < bpp = L                                    */
+                                  pp > DISTSIM_MAX_PP, m < 1, no table variant for tp, unknown
+                                  schedule, or a partition that is not 0 = b0 < b1 < ... < bpp = L */
 #define DISTSIM_ST_RANGE    2  /* m * (sum of all stage-task and p2p durations) >= 2^53        */
 #define DISTSIM_ST_NOROOM   3  /* valid, but its stages do not fit stage_cap                    */
+#define DISTSIM_ST_UNSUPPORTED 4 /* passes every check that takes O(1) per candidate, but lies beyond
+                                  what the kernels of this library simulate: m > DISTSIM_MAX_M; an
+                                  interleaved candidate with pp * chunks > 64; an explicit schedule
+                                  with S > 64, nparts > 64 or S * m > DISTSIM_MAX_SLOTS; p2p_blocking
+                                  == 2 with an interleaved or explicit schedule.  Not a statement
+                                  about the strategy: the method itself has no such bounds.  Treated
+                                  like an invalid candidate by every call (batch_ns = INT64_MAX).  */
 
 typedef struct distsim_ctx distsim_ctx;   /* opaque; host-side state only (device id, error text, timers) */
 
@@ -204,9 +222,10 @@ enum {
  * stage_pos[c] .. stage_pos[c] + pp - 1.  A candidate occupies pp rounded up to a power of
  * two entries and candidates of equal rounded size are packed 64 entries to a wavefront, so
  *   stage_cap >= distsim_stage_entries(C)   (= 64 C + 448, always enough), or any tighter
- *   bound >= 64 * sum over k of ceil(n_k 2^k / 64) with n_k = candidates whose rounded pp is 2^k;
- * candidates that do not fit get DISTSIM_ST_NOROOM.  Entries not owned by any candidate are
- * written as zero.
+ *   bound >= U = 64 * sum over k of ceil(n_k 2^k / 64) with n_k = candidates whose rounded pp is 2^k;
+ * candidates that do not fit get DISTSIM_ST_NOROOM.  Of the first min(U, stage_cap rounded down
+ * to a multiple of 64) entries, those not owned by any candidate are written as zero; entries
+ * from there on are not touched.
  *
  * The stage table is an optional product: the events proper are the shared layer-event tables
  * kept in the workspace (every candidate that generates an event reuses its time, Sec. 3.2),
@@ -229,23 +248,38 @@ typedef struct {
     size_t   workspace_bytes;
     int64_t  num_candidates; /* C of the call that produced the events; filled in by
                                 distsim_build_events, checked by distsim_simulate / _timeline     */
-    distsim_costs      costs;   /* copies of the inputs' pointers, filled in by distsim_build_events: */
-    distsim_candidates cand;    /* the arrays they point to must stay alive until distsim_simulate    */
 } distsim_events;
+/* The struct holds nothing of the caller's inputs: the calls that follow distsim_build_events take
+ * the candidate arrays again as an argument and find everything they need of the cost table in
+ * the workspace, so the cost table may be released once distsim_build_events has run. */
 
 /* A stage_cap that is always enough for C candidates. */
 int64_t distsim_stage_entries(int64_t C);
 
-/* Bytes of distsim_events.workspace needed for tables of (L, V) and C candidates. */
+/* Bytes of distsim_events.workspace needed for tables of (L, V) and C candidates; 0 if a size is
+ * outside its limit. */
 size_t distsim_workspace_bytes(int32_t L, int32_t V, int64_t C);
+
+/*
+ * One allocation for all arrays of a distsim_events.  distsim_events_bytes: device bytes needed for
+ * status, stage_pos, num_events and the workspace of C candidates of a cost table of shape
+ * (costs->L, costs->V; its pointers are not read), plus stage_tab and stage_layers of stage_cap
+ * entries when with_stage_table != 0; every array starts on a 256-byte boundary.  0 if a size is
+ * outside its limit.  distsim_events_bind: fills *ev (every field) with pointers into `memory`
+ * (device, 256-byte aligned, at least distsim_events_bytes() bytes) laid out that way; host-side
+ * pointer arithmetic only.  Errors: EINVAL, ELIMIT.
+ */
+size_t distsim_events_bytes(const distsim_costs *costs, int64_t C, int64_t stage_cap, int with_stage_table);
+int    distsim_events_bind(distsim_events *ev, void *memory, size_t memory_bytes, const distsim_costs *costs,
+                           int64_t C, int64_t stage_cap, int with_stage_table);
 
 /*
  * Event-flow generation (Sec. 4.1 events -> Sec. 4.3 composed events).  For every candidate:
  * validate, map layers to composed events, evaluate collective events, reduce the layer
  * events of each stage (segmented sums over the layer axis) and write the stage table.
  * Also prepares, inside the workspace, the order in which distsim_simulate visits candidates.
- * Errors: EINVAL (null pointers, workspace too small, stage_cap < 0), ERANGE (C, L or V
- * outside their limits), EHIP.  C == 0 is valid.
+ * Errors: EINVAL (null pointers, workspace too small, stage_cap < 0), ERANGE (cluster), ELIMIT
+ * (C, L or V outside their limits), EHIP.  C == 0 is valid.
  */
 int distsim_build_events(distsim_ctx *ctx, const distsim_costs *costs, const distsim_cluster *cluster,
                          const distsim_candidates *cand, int64_t C, distsim_events *out,
@@ -262,12 +296,12 @@ int distsim_build_events(distsim_ctx *ctx, const distsim_costs *costs, const dis
  * = comp_busy / batch as fp64; entries not owned by an OK candidate are written as zero.
  * Also writes num_events[c], and the status of candidates whose partition is invalid or
  * whose times would leave the 2^53 range (final values; distsim_build_events has already
- * written the same ones if it was asked for the stage table).  `events` must come from distsim_build_events with the same
- * cluster and C.  Errors: EINVAL, EHIP.
+ * written the same ones if it was asked for the stage table).  `events` must come from
+ * distsim_build_events with the same cluster, candidates and C.  Errors: EINVAL, ERANGE, ELIMIT, EHIP.
  */
-int distsim_simulate(distsim_ctx *ctx, const distsim_cluster *cluster, const distsim_events *events,
-                     int64_t C, int64_t *batch_ns, int64_t *comp_busy_ns, int64_t *comm_busy_ns,
-                     double *util, void *hip_stream);
+int distsim_simulate(distsim_ctx *ctx, const distsim_cluster *cluster, const distsim_candidates *cand,
+                     const distsim_events *events, int64_t C, int64_t *batch_ns, int64_t *comp_busy_ns,
+                     int64_t *comm_busy_ns, double *util, void *hip_stream);
 
 /*
  * Strategy search (Sec. 6): best[0] = index of the best candidate, best[1] = its batch_ns
@@ -299,10 +333,11 @@ int distsim_search(distsim_ctx *ctx, const int64_t *batch_ns, const int64_t *wei
  *                all-reduce event on each stage's device (interleaved: each device), -1 where
  *                there is none.
  * p2p events follow from the table: the one after task (kind, s, j) starts at that task's end
- * (its compute end) and lasts stage_tab[PF or PB].  Errors: EINVAL, ERANGE, EHIP.
+ * (its compute end) and lasts stage_tab[PF or PB].  `cand`: the candidates of the
+ * distsim_build_events call.  Errors: EINVAL, ERANGE, ELIMIT, EHIP.
  */
-int distsim_timeline(distsim_ctx *ctx, const distsim_cluster *cluster, const distsim_events *events,
-                     int64_t n, const int64_t *sel, const int64_t *task_off,
+int distsim_timeline(distsim_ctx *ctx, const distsim_cluster *cluster, const distsim_candidates *cand,
+                     const distsim_events *events, int64_t n, const int64_t *sel, const int64_t *task_off,
                      int64_t *start_ns, int64_t *end_ns, int64_t *ar_start_ns, int64_t *ar_end_ns,
                      void *hip_stream);
 
@@ -313,10 +348,10 @@ int distsim_timeline(distsim_ctx *ctx, const distsim_cluster *cluster, const dis
  * idle_before_ns gets, in the same [kind][stage][micro-batch] layout, the time the stage's device
  * was idle in front of each stage-task: its start minus the end of the task the device ran before
  * it in the schedule's order (minus 0 for the device's first task).  Candidates that got no
- * timeline get nothing, nor do tasks that an explicit schedule does not list.  Errors: EINVAL, ERANGE, EHIP.
+ * timeline get nothing, nor do tasks that an explicit schedule does not list.  Errors: EINVAL, ELIMIT, EHIP.
  */
-int distsim_bubbles(distsim_ctx *ctx, const distsim_events *events, int64_t n, const int64_t *sel,
-                    const int64_t *task_off, const int64_t *start_ns, const int64_t *end_ns,
+int distsim_bubbles(distsim_ctx *ctx, const distsim_candidates *cand, const distsim_events *events, int64_t n,
+                    const int64_t *sel, const int64_t *task_off, const int64_t *start_ns, const int64_t *end_ns,
                     int64_t *idle_before_ns, void *hip_stream);
 
 /*
@@ -330,7 +365,7 @@ int distsim_bubbles(distsim_ctx *ctx, const distsim_events *events, int64_t n, c
  *                  e < *num_events (the rest is left untouched)
  *   num_events     device out, one int64
  *   workspace      device memory of distsim_dedup_workspace_bytes(n) bytes
- * n <= 2^28.  Errors: EINVAL, ERANGE, EHIP.
+ * n <= 2^28.  Errors: EINVAL, ELIMIT, EHIP.
  */
 size_t distsim_dedup_workspace_bytes(int64_t n);
 int distsim_dedup_events(distsim_ctx *ctx, const int64_t *records, int64_t n, int32_t K,

@@ -18,7 +18,7 @@ LIB_PATH = os.path.join(_HERE, "libdistsim_hip.so")
 
 EXPORTS = (
     "distsim_create", "distsim_destroy", "distsim_last_error", "distsim_workspace_bytes", "distsim_stage_entries",
-    "distsim_build_events", "distsim_simulate", "distsim_search_scratch_bytes", "distsim_search",
+    "distsim_events_bytes", "distsim_events_bind", "distsim_build_events", "distsim_simulate", "distsim_search_scratch_bytes", "distsim_search",
     "distsim_timeline", "distsim_bubbles", "distsim_dedup_workspace_bytes", "distsim_dedup_events", "distsim_comm_event_times",
     "distsim_timing_enable", "distsim_timing_read", "distsim_kernel_name",
 )
@@ -30,6 +30,8 @@ KERNELS = ("k_layer_tables", "k_decode", "k_bins", "k_scatter", "k_stage_events"
            "k_timeline_virtual", "k_simulate_gpipe", "k_simulate_explicit",
            "k_timeline_explicit")
 INT64_MAX = (1 << 63) - 1
+ST_OK, ST_INVALID, ST_RANGE, ST_NOROOM, ST_UNSUPPORTED = 0, 1, 2, 3, 4
+MAX_PP, MAX_M, MAX_SLOTS = 64, 1 << 16, 2048
 
 
 class _Costs(C.Structure):
@@ -57,8 +59,7 @@ class _Events(C.Structure):
     _fields_ = [("stage_cap", C.c_int64), ("L", C.c_int32), ("V", C.c_int32),
                 ("status", C.c_void_p), ("stage_pos", C.c_void_p), ("stage_tab", C.c_void_p),
                 ("stage_layers", C.c_void_p), ("num_events", C.c_void_p),
-                ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t), ("num_candidates", C.c_int64),
-                ("costs", _Costs), ("cand", _Cand)]
+                ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t), ("num_candidates", C.c_int64)]
 
 
 _lib = None
@@ -85,7 +86,12 @@ def load_library():
     lib.distsim_build_events.argtypes = [C.c_void_p, C.POINTER(_Costs), C.POINTER(_Cluster), C.POINTER(_Cand),
                                          C.c_int64, C.POINTER(_Events), C.c_void_p]
     lib.distsim_build_events.restype = C.c_int
-    lib.distsim_simulate.argtypes = [C.c_void_p, C.POINTER(_Cluster), C.POINTER(_Events), C.c_int64,
+    lib.distsim_events_bytes.argtypes = [C.POINTER(_Costs), C.c_int64, C.c_int64, C.c_int]
+    lib.distsim_events_bytes.restype = C.c_size_t
+    lib.distsim_events_bind.argtypes = [C.POINTER(_Events), C.c_void_p, C.c_size_t, C.POINTER(_Costs), C.c_int64,
+                                        C.c_int64, C.c_int]
+    lib.distsim_events_bind.restype = C.c_int
+    lib.distsim_simulate.argtypes = [C.c_void_p, C.POINTER(_Cluster), C.POINTER(_Cand), C.POINTER(_Events), C.c_int64,
                                      C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
     lib.distsim_simulate.restype = C.c_int
     lib.distsim_search_scratch_bytes.argtypes = [C.c_int64]
@@ -93,9 +99,9 @@ def load_library():
     lib.distsim_search.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int, C.c_void_p,
                                    C.c_void_p, C.c_void_p]
     lib.distsim_search.restype = C.c_int
-    lib.distsim_timeline.argtypes = [C.c_void_p, C.POINTER(_Cluster), C.POINTER(_Events), C.c_int64] + [C.c_void_p] * 7
+    lib.distsim_timeline.argtypes = [C.c_void_p, C.POINTER(_Cluster), C.POINTER(_Cand), C.POINTER(_Events), C.c_int64] + [C.c_void_p] * 7
     lib.distsim_timeline.restype = C.c_int
-    lib.distsim_bubbles.argtypes = [C.c_void_p, C.POINTER(_Events), C.c_int64] + [C.c_void_p] * 6
+    lib.distsim_bubbles.argtypes = [C.c_void_p, C.POINTER(_Cand), C.POINTER(_Events), C.c_int64] + [C.c_void_p] * 6
     lib.distsim_bubbles.restype = C.c_int
     lib.distsim_dedup_workspace_bytes.argtypes = [C.c_int64]
     lib.distsim_dedup_workspace_bytes.restype = C.c_size_t
@@ -266,8 +272,33 @@ def alloc_events(ctx: Context, L: int, V: int, Cn: int, stage_cap: Optional[int]
     # torch's caching allocator hands out 512-byte aligned blocks
     workspace = torch.empty(nbytes, dtype=torch.uint8, device=dev)
     st = _Events(cap, 0, 0, _ptr(status), _ptr(stage_pos), _ptr(stage_tab), _ptr(stage_layers), _ptr(num_events),
-                 _ptr(workspace), nbytes, 0, _Costs(), _Cand())
+                 _ptr(workspace), nbytes, 0)
     return Events(Cn, cap, status, stage_pos, stage_tab, stage_layers, num_events, workspace, st)
+
+
+def alloc_events_bound(ctx: Context, dw: DeviceWorkload, stage_cap: int, table: bool = True) -> Events:
+    """The same arrays carved out of ONE device allocation by distsim_events_bind."""
+    co = dw.costs_struct()
+    nbytes = ctx.lib.distsim_events_bytes(C.byref(co), dw.C, int(stage_cap), int(table))
+    if nbytes == 0:
+        raise DistSimError("distsim_events_bytes rejected its arguments")
+    blob = torch.empty(nbytes, dtype=torch.uint8, device=ctx.device)
+    st = _Events()
+    rc = ctx.lib.distsim_events_bind(C.byref(st), _ptr(blob), nbytes, C.byref(co), dw.C, int(stage_cap), int(table))
+    if rc != 0:
+        raise DistSimError(f"distsim_events_bind failed ({rc})")
+    base = blob.data_ptr()
+
+    def view(ptr, n, dtype, shape=None):
+        if not ptr:
+            return None
+        size = torch.empty(0, dtype=dtype).element_size()
+        t = blob[ptr - base: ptr - base + n * size].view(dtype)
+        return t if shape is None else t.view(shape)
+    Cn, cap = max(dw.C, 1), max(int(stage_cap), 1)
+    return Events(dw.C, int(stage_cap), view(st.status, Cn, torch.int32), view(st.stage_pos, Cn, torch.int64),
+                  view(st.stage_tab, NCOLS * cap, torch.int64, (NCOLS, cap)), view(st.stage_layers, cap, torch.int32),
+                  view(st.num_events, Cn, torch.int64), blob, st)
 
 
 def distsim_build_events(ctx: Context, dw: DeviceWorkload, ev: Events) -> None:
@@ -293,9 +324,9 @@ def alloc_outputs(ctx: Context, ev: Events, util: bool = True) -> SimOutputs:
                       torch.empty(n, dtype=torch.float64, device=dev) if util else None)
 
 
-def distsim_simulate(ctx: Context, cluster, ev: Events, out: SimOutputs) -> None:
-    cl = cluster_struct(cluster)
-    ctx.check(ctx.lib.distsim_simulate(ctx.h, C.byref(cl), C.byref(ev.struct), ev.C, _ptr(out.batch_ns),
+def distsim_simulate(ctx: Context, dw: DeviceWorkload, ev: Events, out: SimOutputs) -> None:
+    cl, ca = dw.cluster_struct(), dw.cand_struct()
+    ctx.check(ctx.lib.distsim_simulate(ctx.h, C.byref(cl), C.byref(ca), C.byref(ev.struct), ev.C, _ptr(out.batch_ns),
                                        _ptr(out.comp_busy_ns), _ptr(out.comm_busy_ns), _ptr(out.util), _stream()))
 
 
@@ -311,17 +342,18 @@ def distsim_search(ctx: Context, batch_ns: torch.Tensor, Cn: int, best: torch.Te
                                      _stream()))
 
 
-def distsim_timeline(ctx: Context, cluster, ev: Events, sel: torch.Tensor, task_off: torch.Tensor,
+def distsim_timeline(ctx: Context, dw: DeviceWorkload, ev: Events, sel: torch.Tensor, task_off: torch.Tensor,
                      start_ns: torch.Tensor, end_ns: torch.Tensor, ar_start_ns: torch.Tensor,
                      ar_end_ns: torch.Tensor) -> None:
-    cl = cluster_struct(cluster)
-    ctx.check(ctx.lib.distsim_timeline(ctx.h, C.byref(cl), C.byref(ev.struct), sel.numel(), _ptr(sel), _ptr(task_off),
+    cl, ca = dw.cluster_struct(), dw.cand_struct()
+    ctx.check(ctx.lib.distsim_timeline(ctx.h, C.byref(cl), C.byref(ca), C.byref(ev.struct), sel.numel(), _ptr(sel), _ptr(task_off),
                                        _ptr(start_ns), _ptr(end_ns), _ptr(ar_start_ns), _ptr(ar_end_ns), _stream()))
 
 
-def distsim_bubbles(ctx: Context, ev: Events, sel: torch.Tensor, task_off: torch.Tensor, start_ns: torch.Tensor,
-                    end_ns: torch.Tensor, idle_before_ns: torch.Tensor) -> None:
-    ctx.check(ctx.lib.distsim_bubbles(ctx.h, C.byref(ev.struct), sel.numel(), _ptr(sel), _ptr(task_off),
+def distsim_bubbles(ctx: Context, dw: DeviceWorkload, ev: Events, sel: torch.Tensor, task_off: torch.Tensor,
+                    start_ns: torch.Tensor, end_ns: torch.Tensor, idle_before_ns: torch.Tensor) -> None:
+    ca = dw.cand_struct()
+    ctx.check(ctx.lib.distsim_bubbles(ctx.h, C.byref(ca), C.byref(ev.struct), sel.numel(), _ptr(sel), _ptr(task_off),
                                       _ptr(start_ns), _ptr(end_ns), _ptr(idle_before_ns), _stream()))
 
 

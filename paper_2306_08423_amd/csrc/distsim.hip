@@ -99,6 +99,66 @@ bool cluster_ok(const distsim_cluster* c) {
            c->p2p_blocking >= 0 && c->p2p_blocking <= 2;
 }
 
+// Bounds that keep every product of the collective formulas within 63 bits (with table entries
+// below 2^40) and every bucket count exact in fp64.
+bool cluster_in_range(const distsim_cluster* c) {
+    const int64_t a = (int64_t)1 << 40, b = (int64_t)1 << 32;
+    return c->num_devices <= (1 << 22) && c->alpha_ns[0] < a && c->alpha_ns[1] < a && c->beta_bytes_per_ns[0] < b &&
+           c->beta_bytes_per_ns[1] < b && c->dp_bucket_bytes < ((int64_t)1 << 53);
+}
+
+// Makes the context's device current for the duration of a call and restores the caller's.
+struct DeviceScope {
+    int prev = -1;
+    hipError_t err;
+    explicit DeviceScope(int device) {
+        if (hipGetDevice(&prev) != hipSuccess) prev = -1;
+        err = prev == device ? hipSuccess : hipSetDevice(device);
+        if (prev == device) prev = -1;                           // nothing to restore
+    }
+    ~DeviceScope() { if (prev >= 0) (void)hipSetDevice(prev); }
+};
+
+CandDev cand_dev(const distsim_candidates* cand) {
+    return CandDev{cand->dp, cand->tp, cand->pp, cand->m, cand->schedule, cand->part_off, cand->part_pool,
+                   cand->part_pool ? cand->part_pool_len : 0, cand->chunks,
+                   cand->schedule_off && cand->schedule_words ? cand->n_schedules : 0, cand->schedule_off,
+                   cand->schedule_words, cand->schedule_words_len};
+}
+
+bool cand_arrays_ok(const distsim_candidates* cand) {
+    return cand->dp && cand->tp && cand->pp && cand->m && cand->schedule && cand->part_off;
+}
+
+// What the calls after event generation know of the cost table: its shape and, through the copy in
+// the workspace, the tensor-parallel size of every variant.
+CostsDev costs_after_build(const distsim_events* ev, const Workspace& ws) {
+    return CostsDev{ev->L, ev->V, ws.vtp, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
+}
+
+// Layout of the single allocation of distsim_events_bind; base may be null (size query).
+size_t carve_events(distsim_events* ev, void* base, int32_t L, int32_t V, int64_t C, int64_t stage_cap, bool table) {
+    size_t off = 0;
+    char* b = (char*)base;
+    auto take = [&](size_t bytes) { void* p = b ? (void*)(b + off) : nullptr; off += align256(bytes); return p; };
+    const size_t Cc = (size_t)(C > 0 ? C : 1), cap = (size_t)(stage_cap > 0 ? stage_cap : 1);
+    Workspace w;
+    const size_t wbytes = carve(w, nullptr, L, V, C);
+    void* status = take(Cc * 4);
+    void* pos = take(Cc * 8);
+    void* nev = take(Cc * 8);
+    void* wsp = take(wbytes);
+    void* tab = table ? take(cap * DISTSIM_NCOLS * 8) : nullptr;
+    void* lay = table ? take(cap * 4) : nullptr;
+    if (ev) {
+        ev->stage_cap = stage_cap; ev->L = L; ev->V = V;
+        ev->status = (int32_t*)status; ev->stage_pos = (int64_t*)pos; ev->num_events = (int64_t*)nev;
+        ev->stage_tab = (int64_t*)tab; ev->stage_layers = (int32_t*)lay;
+        ev->workspace = wsp; ev->workspace_bytes = wbytes; ev->num_candidates = 0;
+    }
+    return off;
+}
+
 // Waves that sweep the wave-items: enough to fill every SIMD, never more than one per candidate.
 // Grid of k_simulate: a wavefront takes two items per turn and items differ a lot in length, so
 // the grid is many times what is resident at once and the dispatcher evens the load out.
@@ -175,9 +235,24 @@ const char* distsim_last_error(const distsim_ctx* ctx) { return ctx ? ctx->err.c
 int64_t distsim_stage_entries(int64_t C) { return C < 0 ? 0 : C * kWave + (kClasses * kWave); }
 
 size_t distsim_workspace_bytes(int32_t L, int32_t V, int64_t C) {
-    if (L < 1 || L > DISTSIM_MAX_L || V < 1 || V > DISTSIM_MAX_V || C < 0) return 0;
+    if (L < 1 || L > DISTSIM_MAX_L || V < 1 || V > DISTSIM_MAX_V || C < 0 || C > 0x7fffffff) return 0;
     Workspace w;
     return carve(w, nullptr, L, V, C);
+}
+
+size_t distsim_events_bytes(const distsim_costs* costs, int64_t C, int64_t stage_cap, int with_stage_table) {
+    if (!costs || stage_cap < 0 || distsim_workspace_bytes(costs->L, costs->V, C) == 0) return 0;
+    return carve_events(nullptr, nullptr, costs->L, costs->V, C, stage_cap, with_stage_table != 0);
+}
+
+int distsim_events_bind(distsim_events* ev, void* memory, size_t memory_bytes, const distsim_costs* costs, int64_t C,
+                        int64_t stage_cap, int with_stage_table) {
+    if (!ev || !memory || !costs || stage_cap < 0 || C < 0 || ((uintptr_t)memory & 255) != 0) return DISTSIM_EINVAL;
+    const size_t need = distsim_events_bytes(costs, C, stage_cap, with_stage_table);
+    if (need == 0) return DISTSIM_ELIMIT;
+    if (memory_bytes < need) return DISTSIM_EINVAL;
+    (void)carve_events(ev, memory, costs->L, costs->V, C, stage_cap, with_stage_table != 0);
+    return DISTSIM_OK;
 }
 
 int distsim_build_events(distsim_ctx* ctx, const distsim_costs* costs, const distsim_cluster* cluster,
@@ -185,9 +260,11 @@ int distsim_build_events(distsim_ctx* ctx, const distsim_costs* costs, const dis
     if (!ctx) return DISTSIM_EINVAL;
     if (!costs || !cluster || !cand || !out) return fail(ctx, DISTSIM_EINVAL, "null argument");
     if (costs->L < 1 || costs->L > DISTSIM_MAX_L || costs->V < 1 || costs->V > DISTSIM_MAX_V)
-        return fail(ctx, DISTSIM_ERANGE, "cost table shape outside 1 <= L <= 255, 1 <= V <= 16");
-    if (C < 0 || C > 0x7fffffff) return fail(ctx, DISTSIM_ERANGE, "candidate count outside [0, 2^31)");
+        return fail(ctx, DISTSIM_ELIMIT, "cost table shape outside 1 <= L <= 255, 1 <= V <= 16");
+    if (C < 0) return fail(ctx, DISTSIM_EINVAL, "negative candidate count");
+    if (C > 0x7fffffff) return fail(ctx, DISTSIM_ELIMIT, "candidate count outside [0, 2^31)");
     if (!cluster_ok(cluster)) return fail(ctx, DISTSIM_EINVAL, "cluster description out of range");
+    if (!cluster_in_range(cluster)) return fail(ctx, DISTSIM_ERANGE, "cluster: alpha >= 2^40, beta >= 2^32, bucket >= 2^53 or more than 2^22 devices");
     if (!costs->variant_tp || !costs->fwd_comp_ns || !costs->bwd_comp_ns || !costs->fwd_comm_ns ||
         !costs->bwd_comm_ns || !costs->act_bytes || !costs->grad_bytes)
         return fail(ctx, DISTSIM_EINVAL, "null cost column");
@@ -202,21 +279,17 @@ int distsim_build_events(distsim_ctx* ctx, const distsim_costs* costs, const dis
     const size_t need = carve(ws, out->workspace, costs->L, costs->V, C);
     if (out->workspace_bytes < need) return fail(ctx, DISTSIM_EINVAL, "workspace too small");
 
-    HIP_TRY(hipSetDevice(ctx->device));
+    DeviceScope dev(ctx->device);
+    HIP_TRY(dev.err);
     hipStream_t st = (hipStream_t)hip_stream;
     CostsDev co{costs->L, costs->V, costs->variant_tp, costs->fwd_comp_ns, costs->bwd_comp_ns, costs->fwd_comm_ns,
                 costs->bwd_comm_ns, costs->act_bytes, costs->grad_bytes, costs->a2a_bytes};
     const ClusterDev cl = to_dev(*cluster);
-    CandDev ca{cand->dp, cand->tp, cand->pp, cand->m, cand->schedule, cand->part_off, cand->part_pool,
-               cand->part_pool ? cand->part_pool_len : 0, cand->chunks,
-               cand->schedule_off && cand->schedule_words ? cand->n_schedules : 0, cand->schedule_off,
-               cand->schedule_words, cand->schedule_words_len};
+    const CandDev ca = cand_dev(cand);
     EventsDev ev{out->stage_cap, out->status, out->stage_pos, out->stage_tab, out->stage_layers, out->num_events};
     out->L = costs->L;
     out->V = costs->V;
     out->num_candidates = C;
-    out->costs = *costs;
-    out->cand = *cand;
 
     const int cblocks = (int)((C + 255) / 256);
     // The layer tables do not depend on the candidates and nothing before k_stage_events reads
@@ -260,35 +333,30 @@ int distsim_build_events(distsim_ctx* ctx, const distsim_costs* costs, const dis
     return DISTSIM_OK;
 }
 
-int distsim_simulate(distsim_ctx* ctx, const distsim_cluster* cluster, const distsim_events* events, int64_t C,
-                     int64_t* batch_ns, int64_t* comp_busy_ns, int64_t* comm_busy_ns, double* util,
-                     void* hip_stream) {
+int distsim_simulate(distsim_ctx* ctx, const distsim_cluster* cluster, const distsim_candidates* cd,
+                     const distsim_events* events, int64_t C, int64_t* batch_ns, int64_t* comp_busy_ns,
+                     int64_t* comm_busy_ns, double* util, void* hip_stream) {
     if (!ctx) return DISTSIM_EINVAL;
-    if (!cluster || !events) return fail(ctx, DISTSIM_EINVAL, "null argument");
+    if (!cluster || !events || !cd) return fail(ctx, DISTSIM_EINVAL, "null argument");
     if (!cluster_ok(cluster)) return fail(ctx, DISTSIM_EINVAL, "cluster description out of range");
-    if (C < 0 || C > 0x7fffffff) return fail(ctx, DISTSIM_ERANGE, "candidate count outside [0, 2^31)");
+    if (!cluster_in_range(cluster)) return fail(ctx, DISTSIM_ERANGE, "cluster: alpha >= 2^40, beta >= 2^32, bucket >= 2^53 or more than 2^22 devices");
+    if (C < 0) return fail(ctx, DISTSIM_EINVAL, "negative candidate count");
+    if (C > 0x7fffffff) return fail(ctx, DISTSIM_ELIMIT, "candidate count outside [0, 2^31)");
     if (C != events->num_candidates) return fail(ctx, DISTSIM_EINVAL, "C differs from the distsim_build_events call");
     if (C == 0) return DISTSIM_OK;
-    if (!batch_ns || !events->status || !events->num_events || !events->workspace ||
+    if (!batch_ns || !events->status || !events->num_events || !events->workspace || !cand_arrays_ok(cd) ||
         (events->stage_cap > 0 && (!comp_busy_ns || !comm_busy_ns)))
-        return fail(ctx, DISTSIM_EINVAL, "null output or events array");
-    HIP_TRY(hipSetDevice(ctx->device));
-    hipStream_t st = (hipStream_t)hip_stream;
+        return fail(ctx, DISTSIM_EINVAL, "null output, candidate or events array");
     if (events->L < 1 || events->L > DISTSIM_MAX_L || events->V < 1 || events->V > DISTSIM_MAX_V)
         return fail(ctx, DISTSIM_EINVAL, "events were not produced by distsim_build_events");
     Workspace ws;
     if (events->workspace_bytes < carve(ws, events->workspace, events->L, events->V, C))
         return fail(ctx, DISTSIM_EINVAL, "workspace too small for C");
-    const distsim_costs* cs = &events->costs;
-    const distsim_candidates* cd = &events->cand;
-    if (!cs->variant_tp || !cs->act_bytes || cs->L != events->L || cs->V != events->V)
-        return fail(ctx, DISTSIM_EINVAL, "events were not produced by distsim_build_events");
-    CostsDev co{cs->L, cs->V, cs->variant_tp, cs->fwd_comp_ns, cs->bwd_comp_ns, cs->fwd_comm_ns, cs->bwd_comm_ns,
-                cs->act_bytes, cs->grad_bytes, cs->a2a_bytes};
-    CandDev ca{cd->dp, cd->tp, cd->pp, cd->m, cd->schedule, cd->part_off, cd->part_pool,
-               cd->part_pool ? cd->part_pool_len : 0, cd->chunks,
-               cd->schedule_off && cd->schedule_words ? cd->n_schedules : 0, cd->schedule_off, cd->schedule_words,
-               cd->schedule_words_len};
+    DeviceScope dev(ctx->device);
+    HIP_TRY(dev.err);
+    hipStream_t st = (hipStream_t)hip_stream;
+    const CostsDev co = costs_after_build(events, ws);
+    const CandDev ca = cand_dev(cd);
     const ClusterDev cl = to_dev(*cluster);
     EventsDev ev{events->stage_cap, events->status, events->stage_pos, events->stage_tab, events->stage_layers,
                  events->num_events};
@@ -300,13 +368,15 @@ int distsim_simulate(distsim_ctx* ctx, const distsim_cluster* cluster, const dis
         Timer t(ctx, st, DISTSIM_K_SIM_INIT);
         hipLaunchKernelGGL(k_sim_init, dim3((int)((C + 255) / 256)), dim3(256), 0, st, events->status, C, batch_ns);
     }
+    // The sweep kernels below set EXEC by hand (DISTSIM_STEP*): blocks of kSimBlock threads, whole
+    // wavefronts only, never a partial block.
     if (cl.blocking == 2) {
         Timer t(ctx, st, DISTSIM_K_SIMULATE);
-        hipLaunchKernelGGL(k_simulate_links, dim3(simulate_grid(ctx, C)), dim3(256), 0, st, co, cl, ca, ws, ev, out);
+        hipLaunchKernelGGL(k_simulate_links, dim3(simulate_grid(ctx, C)), dim3(kSimBlock), 0, st, co, cl, ca, ws, ev, out);
     } else if (C < ctx->split_min_items) {
         // a list of fewer candidates than that has fewer wave-items too: k_simulate takes all of it
         Timer t(ctx, st, DISTSIM_K_SIMULATE);
-        hipLaunchKernelGGL(k_simulate, dim3(general_grid(ctx, C)), dim3(256), 0, st, co, cl, ca, ws, ev, out,
+        hipLaunchKernelGGL(k_simulate, dim3(general_grid(ctx, C)), dim3(kSimBlock), 0, st, co, cl, ca, ws, ev, out,
                            ctx->split_min_items);
     } else {
         // k_simulate and, for the pairs of GPipe items that it leaves out, k_simulate_gpipe, side
@@ -314,7 +384,7 @@ int distsim_simulate(distsim_ctx* ctx, const distsim_cluster* cluster, const dis
         Timer t(ctx, st, DISTSIM_K_SIMULATE);
         HIP_TRY(hipEventRecord(ctx->fork, st));
         HIP_TRY(hipStreamWaitEvent(ctx->side, ctx->fork, 0));
-        hipLaunchKernelGGL(k_simulate, dim3(general_grid(ctx, C)), dim3(256), 0, st, co, cl, ca, ws, ev, out,
+        hipLaunchKernelGGL(k_simulate, dim3(general_grid(ctx, C)), dim3(kSimBlock), 0, st, co, cl, ca, ws, ev, out,
                            ctx->split_min_items);
         {
             Timer ti(ctx, ctx->side, DISTSIM_K_SIM_INIT);
@@ -322,7 +392,7 @@ int distsim_simulate(distsim_ctx* ctx, const distsim_cluster* cluster, const dis
         }
         {
             Timer tg(ctx, ctx->side, DISTSIM_K_SIMULATE_GPIPE);
-            hipLaunchKernelGGL(k_simulate_gpipe, dim3(gpipe_grid(ctx, C)), dim3(256), 0, ctx->side, co, cl, ca, ws, ev, out,
+            hipLaunchKernelGGL(k_simulate_gpipe, dim3(gpipe_grid(ctx, C)), dim3(kSimBlock), 0, ctx->side, co, cl, ca, ws, ev, out,
                                ctx->split_min_items);
         }
         HIP_TRY(hipEventRecord(ctx->join, ctx->side));
@@ -353,34 +423,32 @@ int distsim_simulate(distsim_ctx* ctx, const distsim_cluster* cluster, const dis
     return DISTSIM_OK;
 }
 
-int distsim_timeline(distsim_ctx* ctx, const distsim_cluster* cluster, const distsim_events* events, int64_t n,
-                     const int64_t* sel, const int64_t* task_off, int64_t* start_ns, int64_t* end_ns,
-                     int64_t* ar_start_ns, int64_t* ar_end_ns, void* hip_stream) {
+int distsim_timeline(distsim_ctx* ctx, const distsim_cluster* cluster, const distsim_candidates* cd,
+                     const distsim_events* events, int64_t n, const int64_t* sel, const int64_t* task_off,
+                     int64_t* start_ns, int64_t* end_ns, int64_t* ar_start_ns, int64_t* ar_end_ns, void* hip_stream) {
     if (!ctx) return DISTSIM_EINVAL;
-    if (!cluster || !events) return fail(ctx, DISTSIM_EINVAL, "null argument");
+    if (!cluster || !events || !cd) return fail(ctx, DISTSIM_EINVAL, "null argument");
     if (!cluster_ok(cluster)) return fail(ctx, DISTSIM_EINVAL, "cluster description out of range");
-    if (n < 0 || n > 0x7fffffff) return fail(ctx, DISTSIM_ERANGE, "selection size outside [0, 2^31)");
+    if (!cluster_in_range(cluster)) return fail(ctx, DISTSIM_ERANGE, "cluster: alpha >= 2^40, beta >= 2^32, bucket >= 2^53 or more than 2^22 devices");
+    if (n < 0) return fail(ctx, DISTSIM_EINVAL, "negative selection size");
+    if (n > 0x7fffffff) return fail(ctx, DISTSIM_ELIMIT, "selection size outside [0, 2^31)");
     if (n == 0) return DISTSIM_OK;
     if (!sel || !task_off || !start_ns || !end_ns || !ar_start_ns || !ar_end_ns || !events->status ||
-        !events->workspace)
+        !events->workspace || !cand_arrays_ok(cd))
         return fail(ctx, DISTSIM_EINVAL, "null array");
-    const distsim_costs* cs = &events->costs;
-    const distsim_candidates* cd = &events->cand;
-    if (!cs->variant_tp || !cs->act_bytes || cs->L != events->L || cs->V != events->V || events->L < 1 ||
-        events->L > DISTSIM_MAX_L || events->V < 1 || events->V > DISTSIM_MAX_V)
+    if (events->L < 1 || events->L > DISTSIM_MAX_L || events->V < 1 || events->V > DISTSIM_MAX_V)
         return fail(ctx, DISTSIM_EINVAL, "events were not produced by distsim_build_events");
     Workspace ws;
-    (void)carve(ws, events->workspace, events->L, events->V, 0);     // table addresses do not depend on C
-    HIP_TRY(hipSetDevice(ctx->device));
+    if (events->workspace_bytes < carve(ws, events->workspace, events->L, events->V, events->num_candidates))
+        return fail(ctx, DISTSIM_EINVAL, "events were not produced by distsim_build_events");
+    DeviceScope dev(ctx->device);
+    HIP_TRY(dev.err);
     hipStream_t st = (hipStream_t)hip_stream;
-    CostsDev co{cs->L, cs->V, cs->variant_tp, cs->fwd_comp_ns, cs->bwd_comp_ns, cs->fwd_comm_ns, cs->bwd_comm_ns,
-                cs->act_bytes, cs->grad_bytes, cs->a2a_bytes};
-    CandDev ca{cd->dp, cd->tp, cd->pp, cd->m, cd->schedule, cd->part_off, cd->part_pool,
-               cd->part_pool ? cd->part_pool_len : 0, cd->chunks,
-               cd->schedule_off && cd->schedule_words ? cd->n_schedules : 0, cd->schedule_off, cd->schedule_words,
-               cd->schedule_words_len};
+    const CostsDev co = costs_after_build(events, ws);
+    const CandDev ca = cand_dev(cd);
     TimelineOut out{sel, task_off, start_ns, end_ns, ar_start_ns, ar_end_ns};
     {
+        // k_timeline uses the DISTSIM_STEP* macros: blocks of kTlWaves whole wavefronts
         Timer t(ctx, st, DISTSIM_K_TIMELINE);
         hipLaunchKernelGGL(k_timeline, dim3((unsigned)((n + kTlChunk - 1) / kTlChunk)), dim3(kTlWaves * kWave), 0, st,
                            co, cl_dev(*cluster), ca, ws, events->status, events->num_candidates, n, out);
@@ -414,8 +482,9 @@ int distsim_search(distsim_ctx* ctx, const int64_t* batch_ns, const int64_t* wei
     if (!best || !scratch || (C > 0 && !batch_ns)) return fail(ctx, DISTSIM_EINVAL, "null argument");
     if (objective != 0 && objective != 1) return fail(ctx, DISTSIM_EINVAL, "objective must be 0 or 1");
     if (objective == 1 && C > 0 && !weight) return fail(ctx, DISTSIM_EINVAL, "objective 1 needs weights");
-    if (C < 0) return fail(ctx, DISTSIM_ERANGE, "negative candidate count");
-    HIP_TRY(hipSetDevice(ctx->device));
+    if (C < 0) return fail(ctx, DISTSIM_EINVAL, "negative candidate count");
+    DeviceScope dev(ctx->device);
+    HIP_TRY(dev.err);
     hipStream_t st = (hipStream_t)hip_stream;
     Best* partial = (Best*)scratch;
     int64_t nb = (C + kSearchBlock * 4 - 1) / (kSearchBlock * 4);
@@ -433,23 +502,21 @@ int distsim_search(distsim_ctx* ctx, const int64_t* batch_ns, const int64_t* wei
     return DISTSIM_OK;
 }
 
-int distsim_bubbles(distsim_ctx* ctx, const distsim_events* events, int64_t n, const int64_t* sel,
-                    const int64_t* task_off, const int64_t* start_ns, const int64_t* end_ns, int64_t* idle_before_ns,
-                    void* hip_stream) {
+int distsim_bubbles(distsim_ctx* ctx, const distsim_candidates* cd, const distsim_events* events, int64_t n,
+                    const int64_t* sel, const int64_t* task_off, const int64_t* start_ns, const int64_t* end_ns,
+                    int64_t* idle_before_ns, void* hip_stream) {
     if (!ctx) return DISTSIM_EINVAL;
-    if (!events) return fail(ctx, DISTSIM_EINVAL, "null argument");
-    if (n < 0 || n > 0x7fffffff) return fail(ctx, DISTSIM_ERANGE, "selection size outside [0, 2^31)");
+    if (!events || !cd) return fail(ctx, DISTSIM_EINVAL, "null argument");
+    if (n < 0) return fail(ctx, DISTSIM_EINVAL, "negative selection size");
+    if (n > 0x7fffffff) return fail(ctx, DISTSIM_ELIMIT, "selection size outside [0, 2^31)");
     if (n == 0) return DISTSIM_OK;
-    const distsim_candidates* cd = &events->cand;
     if (!sel || !task_off || !start_ns || !end_ns || !idle_before_ns || !events->status || !cd->pp || !cd->m ||
         !cd->schedule)
         return fail(ctx, DISTSIM_EINVAL, "null array");
-    HIP_TRY(hipSetDevice(ctx->device));
+    DeviceScope dev(ctx->device);
+    HIP_TRY(dev.err);
     hipStream_t st = (hipStream_t)hip_stream;
-    CandDev ca{cd->dp, cd->tp, cd->pp, cd->m, cd->schedule, cd->part_off, cd->part_pool,
-               cd->part_pool ? cd->part_pool_len : 0, cd->chunks,
-               cd->schedule_off && cd->schedule_words ? cd->n_schedules : 0, cd->schedule_off, cd->schedule_words,
-               cd->schedule_words_len};
+    const CandDev ca = cand_dev(cd);
     {
         Timer t(ctx, st, DISTSIM_K_BUBBLES);
         hipLaunchKernelGGL(k_bubbles, dim3((unsigned)n), dim3(256), 0, st, ca, events->status, events->num_candidates,
@@ -496,11 +563,12 @@ int distsim_dedup_events(distsim_ctx* ctx, const int64_t* records, int64_t n, in
                          void* hip_stream) {
     if (!ctx) return DISTSIM_EINVAL;
     if (n < 0 || K < 1 || !num_events) return fail(ctx, DISTSIM_EINVAL, "bad size or null num_events");
-    if (K > kMaxRecordWords || n > kMaxDedupRecords) return fail(ctx, DISTSIM_ERANGE, "K above 16 or n above 2^28");
+    if (K > kMaxRecordWords || n > kMaxDedupRecords) return fail(ctx, DISTSIM_ELIMIT, "K above 16 or n above 2^28");
     if (n > 0 && (!records || !event_id || !rep || !workspace)) return fail(ctx, DISTSIM_EINVAL, "null argument");
     DedupSpace d;
     if (workspace_bytes < carve_dedup(d, workspace, n) && n > 0) return fail(ctx, DISTSIM_EINVAL, "workspace too small");
-    HIP_TRY(hipSetDevice(ctx->device));
+    DeviceScope dev(ctx->device);
+    HIP_TRY(dev.err);
     hipStream_t st = (hipStream_t)hip_stream;
     Timer t(ctx, st, DISTSIM_K_DEDUP);
     const int64_t nb = (n + kScanBlock - 1) / kScanBlock;
@@ -527,7 +595,8 @@ int distsim_comm_event_times(distsim_ctx* ctx, int64_t n, const int32_t* kind, c
     if (n < 0) return fail(ctx, DISTSIM_EINVAL, "negative size");
     if (n == 0) return DISTSIM_OK;
     if (!kind || !ranks || !t_a || !t_b || !elapsed_ns) return fail(ctx, DISTSIM_EINVAL, "null argument");
-    HIP_TRY(hipSetDevice(ctx->device));
+    DeviceScope dev(ctx->device);
+    HIP_TRY(dev.err);
     hipStream_t st = (hipStream_t)hip_stream;
     Timer t(ctx, st, DISTSIM_K_COMM_TIMES);
     hipLaunchKernelGGL(k_comm_event_times, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, n, kind, ranks, t_a,

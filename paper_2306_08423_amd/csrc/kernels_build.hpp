@@ -84,6 +84,7 @@ __global__ __launch_bounds__(64) void k_layer_tables(CostsDev co, ClusterDev cl,
     int64_t* pg = ws.pg + (size_t)v * (L + 1);
     int64_t* comb = ws.comb + (size_t)row * (L + 1) * kCombWords;
     int64_t c_fa = 0, c_ba = 0, c_fc = 0, c_bc = 0, c_g = 0;
+    if (row == 0 && lane < co.V) ws.vtp[lane] = co.variant_tp[lane];
     if (lane == 0) {
         pfa[0] = 0; pba[0] = 0;
         if (base) { pfc[0] = 0; pbc[0] = 0; pg[0] = 0; }
@@ -134,10 +135,7 @@ __global__ void k_clear_bins(Workspace ws) {
 // only the non-empty bins go to the global counters (one atomic each), which hands the
 // workgroup its base rank in every bin.  rank[c] is the candidate's position inside its bin.
 constexpr int kDecodeBlock = 1024;
-#ifndef DISTSIM_DECODE_PER
-#define DISTSIM_DECODE_PER 4
-#endif
-constexpr int kDecodePer = DISTSIM_DECODE_PER;
+constexpr int kDecodePer = 4;                 // candidates per thread
 constexpr int kDecodeChunk = kDecodeBlock * kDecodePer;
 
 __global__ __launch_bounds__(kDecodeBlock) void k_decode(CostsDev co, ClusterDev cl, CandDev ca, int64_t C,
@@ -155,25 +153,28 @@ __global__ __launch_bounds__(kDecodeBlock) void k_decode(CostsDev co, ClusterDev
         const int32_t dp = ca.dp[c], tp = ca.tp[c], pp = ca.pp[c], m = ca.m[c];
         const int sched = ca.schedule[c];
         const int64_t poff = ca.part_off[c];
-        bool ok = dp >= 1 && tp >= 1 && pp >= 1 && m >= 1 && m <= kMaxM && sched <= 4 && pp <= co.L && pp <= kMaxPP;
+        // ok: a strategy as far as O(1) checks can tell; sup: within what the kernels of this library take
+        bool ok = dp >= 1 && tp >= 1 && pp >= 1 && m >= 1 && sched <= 4 && pp <= co.L && pp <= kMaxPP;
+        bool sup = m <= kMaxM;
         ok = ok && (int64_t)dp * tp * pp == (int64_t)cl.num_devices;
         int64_t parts = pp;                      // parts of the layer partition
         if (ok && sched == 3) {                  // interleaved: pp * chunks virtual stages
             const int64_t vch = ca.chunks ? ca.chunks[c] : 0;      // no chunk counts: invalid
             parts = (int64_t)pp * vch;
-            ok = vch >= 1 && parts <= kMaxPP && parts <= co.L && m % pp == 0 && cl.blocking != 2;
+            ok = vch >= 1 && parts <= co.L && m % pp == 0;
+            sup = sup && parts <= kMaxPP && cl.blocking != 2;
         }
         if (ok && sched == 4) {                  // explicit: the head of its schedule block; the kernel checks the rest
             const int64_t id = ca.chunks ? ca.chunks[c] : -1;
-            ok = id >= 0 && id < ca.n_schedules && ca.schedule_off && ca.schedule_words && cl.blocking != 2;
+            ok = id >= 0 && id < ca.n_schedules && ca.schedule_off && ca.schedule_words;
             if (ok) {
                 const int64_t o = ca.schedule_off[id], n = ca.schedule_off[id + 1] - o;
                 ok = o >= 0 && n >= 5 + pp + 1 && o + n <= ca.schedule_words_len;
                 if (ok) {
                     const int32_t* w = ca.schedule_words + o;
                     parts = w[3];
-                    ok = w[0] == pp && w[2] == m && w[1] >= 1 && w[1] <= kMaxPP && parts >= 1 && parts <= kMaxPP &&
-                         parts <= co.L && w[4] >= 1 && (int64_t)w[1] * m <= kMaxSlots;
+                    ok = w[0] == pp && w[2] == m && w[1] >= 1 && parts >= 1 && parts <= co.L && w[4] >= 1;
+                    sup = sup && w[1] <= kMaxPP && parts <= kMaxPP && (int64_t)w[1] * m <= kMaxSlots && cl.blocking != 2;
                 }
             }
         }
@@ -183,7 +184,7 @@ __global__ __launch_bounds__(kDecodeBlock) void k_decode(CostsDev co, ClusterDev
             for (int i = co.V - 1; i >= 0; i--) if (co.variant_tp[i] == tp) v = i;
             ok = v >= 0;
         }
-        if (ok) {
+        if (ok && sup) {
             int k = 0;                               // class 0 = 64 lanes ... class 6 = 1 lane
             while (k < 6 && (32 >> k) >= pp) k++;
             const int mb = (m < kMBins ? m : kMBins) - 1;
@@ -194,7 +195,7 @@ __global__ __launch_bounds__(kDecodeBlock) void k_decode(CostsDev co, ClusterDev
             ev.num_events[c] = 0;
             ev.stage_pos[c] = -1;
         }
-        ev.status[c] = ok ? 0 : 1;
+        ev.status[c] = ok ? (sup ? 0 : 4) : 1;
     }
     __syncthreads();
     for (int b = threadIdx.x; b < kBins; b += kDecodeBlock) {

@@ -188,6 +188,9 @@ struct Sweep {
 };
 
 constexpr int kSimBlock = 256;
+// The DISTSIM_STEP* macros set EXEC themselves and put it back to all ones: every kernel that uses
+// them must run whole 64-lane wavefronts and call them from wave-uniform control flow only.
+static_assert(kSimBlock % kWave == 0, "the sweep kernels need whole wavefronts");
 
 // What only the epilogue of an item needs waits here during the sweep, one slot per lane of the
 // workgroup and per item of a lockstep pair (one block, so that one address register serves).

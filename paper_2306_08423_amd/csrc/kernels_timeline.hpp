@@ -18,20 +18,12 @@ struct TimelineOut {
 
 // A row of the staging ring takes the entries of kTlFlush levels plus what the last flush left
 // behind because it did not fill an aligned group of kTlFlush entries (32 bytes).
-#ifndef DISTSIM_TL_FLUSH
-#define DISTSIM_TL_FLUSH 4
-#endif
-constexpr int kTlFlush = DISTSIM_TL_FLUSH;   // levels between two flushes = entries per aligned write
+constexpr int kTlFlush = 4;              // levels between two flushes = entries per aligned write
 constexpr int kTlRing = 2 * kTlFlush;    // ring capacity per row
 constexpr int kTlRow = kTlRing + 1;      // padded: consecutive stages start in different LDS banks
-#ifndef DISTSIM_TL_CHUNK
-#define DISTSIM_TL_CHUNK 16
-#endif
-#ifndef DISTSIM_TL_WAVES
-#define DISTSIM_TL_WAVES 4
-#endif
-constexpr int kTlChunk = DISTSIM_TL_CHUNK;   // selected candidates per workgroup (at most 64)
-constexpr int kTlWaves = DISTSIM_TL_WAVES;
+constexpr int kTlChunk = 16;             // selected candidates per workgroup (at most 64)
+constexpr int kTlWaves = 4;
+static_assert(kTlChunk <= kWave && kTlWaves >= 1, "one wavefront sorts a chunk; blocks are kTlWaves whole wavefronts");
 
 // Per-wavefront staging area.
 struct TlRowMeta { int64_t base, dur; };     // index of the row's entry 0 in start / end; task duration

@@ -7,6 +7,7 @@ namespace distsim {
 
 constexpr int kMaxPP = 64;
 constexpr int kMaxM = 1 << 16;
+constexpr int kMaxV = 16;                   // tensor-parallel variants of a cost table
 constexpr int kMaxSlots = 2048;             // (virtual stage, micro-batch) pairs of an explicit schedule
 constexpr int kClasses = 7;                 // lanes per candidate: 64, 32, 16, 8, 4, 2, 1
 constexpr int kMBins = 1024;                // micro-batch count is clamped to this for ordering only
@@ -48,6 +49,8 @@ struct Workspace {
     int32_t *bin_start;            // [kBins+1]
     int32_t *rank;                 // [C] position of the candidate inside its bin
     int64_t *hdr;                  // [H_WORDS]
+    int32_t *vtp;                  // [kMaxV] the cost table's variant -> tensor-parallel size (a copy: the calls
+                                   //         after event generation do not see the cost table any more)
     Desc *desc;                    // [C] candidates in visiting order
 };
 
@@ -72,6 +75,7 @@ inline size_t carve(Workspace& w, void* base, int32_t L, int32_t V, int64_t C) {
     w.bin_start = (int32_t*)take((size_t)(kBins + 1) * 4);
     w.rank = (int32_t*)take(Cc * 4);
     w.hdr = (int64_t*)take(H_WORDS * 8);
+    w.vtp = (int32_t*)take(kMaxV * 4);
     w.desc = (Desc*)take(Cc * sizeof(Desc));
     return off;
 }

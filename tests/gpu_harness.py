@@ -53,7 +53,7 @@ def run_hip(w, stage_cap=None, util=True, search=None, table=True, split=False):
     out.batch_ns.fill_(-7); out.comp_busy_ns.fill_(-7); out.comm_busy_ns.fill_(-7)
     if util:
         out.util.fill_(-7.0)
-    ds.distsim_simulate(c, dw.cluster, ev, out)
+    ds.distsim_simulate(c, dw, ev, out)
     res = {}
     if search is not None:
         obj, wgt = search
@@ -72,6 +72,7 @@ def run_hip(w, stage_cap=None, util=True, search=None, table=True, split=False):
         "comp_busy_ns": out.comp_busy_ns.cpu().numpy()[:cap],
         "comm_busy_ns": out.comm_busy_ns.cpu().numpy()[:cap],
         "pp": w.cand["pp"].astype(np.int64),
+        "workload": w,
     })
     if util:
         res["util"] = out.util.cpu().numpy()[:cap]
@@ -86,22 +87,89 @@ def rows_of(hip, sel):
     return ds.stage_rows(hip["status"][sel], hip["stage_pos"][sel], hip["pp"][sel])
 
 
-def assert_same(hip, ora, idx=None, what=""):
+def beyond_limits(w):
+    """Per candidate: does it lie beyond what this library's kernels take (include/distsim.h,
+    DISTSIM_ST_UNSUPPORTED)?  From the inputs alone; says nothing about validity."""
+    ca = w.cand
+    C = len(ca["pp"])
+    pp, m, sc = ca["pp"].astype(np.int64), ca["m"].astype(np.int64), ca["schedule"]
+    blocking = int(w.cluster.get("p2p_blocking", 0))
+    out = m > ds.binding.MAX_M
+    ch = ca.get("chunks")
+    if ch is not None:
+        ch = ch.astype(np.int64)
+        out = out | ((sc == 3) & ((pp * ch > ds.binding.MAX_PP) | (blocking == 2)))
+        off, words = ca.get("schedule_off"), ca.get("schedule_words")
+        if off is not None and words is not None:
+            n = len(off) - 1
+            for c in np.nonzero(sc == 4)[0]:
+                sid = int(ch[c])
+                if not (0 <= sid < n):
+                    continue
+                o, e = int(off[sid]), int(off[sid + 1])
+                if o < 0 or e - o < 5 or e > len(words):
+                    continue
+                S, nparts = int(words[o + 1]), int(words[o + 3])
+                if S > ds.binding.MAX_PP or nparts > ds.binding.MAX_PP or S * int(m[c]) > ds.binding.MAX_SLOTS or blocking == 2:
+                    out[c] = True
+    return out
+
+
+def assert_same(hip, ora, idx=None, what="", w=None):
     """Bit-exact on every integer output; utilisation (fp64 quotient of two exact integers,
-    one IEEE division on both sides) within 1e-12 relative.  idx: the oracle ran on w[idx]."""
+    one IEEE division on both sides) within 1e-12 relative.  idx: the oracle ran on w[idx].
+    w: the workload (default: the one run_hip was given).  Candidates of it that lie beyond the
+    library's limits must come back as DISTSIM_ST_UNSUPPORTED (unless they fail an O(1) validity check, which both
+    sides report as invalid) and are left out of the comparison of results; no other candidate may."""
     C = len(ora["status"])
     sel = np.arange(C) if idx is None else np.asarray(idx)
-    assert np.array_equal(hip["status"][sel], ora["status"]), what + " status"
-    assert np.array_equal(hip["batch_ns"][sel], ora["batch_ns"]), what + " batch_ns"
-    assert np.array_equal(hip["num_events"][sel], ora["num_events"]), what + " num_events"
+    w = hip.get("workload") if w is None else w
+    hs, os_ = hip["status"][sel], ora["status"]
+    unsup = hs == ds.binding.ST_UNSUPPORTED
+    if w is None:
+        assert not unsup.any(), what + " unsupported candidates in a workload within the limits"
+    else:
+        beyond = beyond_limits(w)[sel]
+        assert not (unsup & ~beyond).any(), what + " unsupported without a limit being passed"
+        assert np.isin(hs[beyond], (ds.binding.ST_INVALID, ds.binding.ST_UNSUPPORTED)).all(), what + " beyond the limits but simulated"
+        assert (hs[beyond & (os_ != 1)] == ds.binding.ST_UNSUPPORTED).all(), what + " valid beyond the limits, not reported as such"
+        assert (hip["batch_ns"][sel][unsup] == np.iinfo(np.int64).max).all() and (hip["num_events"][sel][unsup] == 0).all()
+        assert (hip["stage_pos"][sel][unsup] == -1).all()
+    keep = ~unsup
+    assert np.array_equal(hs[keep], os_[keep]), what + " status"
+    assert np.array_equal(hip["batch_ns"][sel][keep], ora["batch_ns"][keep]), what + " batch_ns"
+    assert np.array_equal(hip["num_events"][sel][keep], ora["num_events"][keep]), what + " num_events"
     rows, cnt_h = rows_of(hip, sel)
     oo = ora["stage_off"]
-    assert np.array_equal(cnt_h, oo[1:] - oo[:-1]), what + " stage counts"
+    cnt_o = (oo[1:] - oo[:-1]) * keep                       # the oracle's rows of the candidates the library took
+    assert np.array_equal(cnt_h, cnt_o), what + " stage counts"
+    orow = np.repeat(oo[:-1], cnt_o) + (np.arange(int(cnt_o.sum())) - np.repeat(np.cumsum(cnt_o) - cnt_o, cnt_o))
     if len(rows):
         assert rows.min() >= 0 and rows.max() < len(hip["comp_busy_ns"]), what + " stage_pos range"
         assert len(np.unique(rows)) == len(rows), what + " overlapping stage blocks"
     for key in ("comp_busy_ns", "comm_busy_ns"):
-        assert np.array_equal(hip[key][rows], ora[key]), what + " " + key
+        assert np.array_equal(hip[key][rows], ora[key][orow]), what + " " + key
     if "util" in hip:
-        a, b = hip["util"][rows], ora["util"]
+        a, b = hip["util"][rows], ora["util"][orow]
         assert np.all(np.abs(a - b) <= 1e-12 * np.abs(b)), what + " util"
+    if "stage_tab" in hip and "stage_table" in ora:
+        # every column of the materialised stage table and the layer ranges, against the per-stage
+        # sums that the oracle forms with plain loops over each stage's layers
+        t = ora["stage_table"]
+        names = ("FC", "FA", "BC", "BA", "PF", "PB", "G", "AR")
+        for col, nm in enumerate(names):
+            assert np.array_equal(hip["stage_tab"][col, rows], t["tab"][col, orow]), what + " stage_tab " + nm
+        lay = hip["stage_layers"][rows]
+        assert np.array_equal(lay & 0xff, t["layer_lo"][orow]) and np.array_equal(lay >> 8, t["layer_hi"][orow]), what + " stage_layers"
+        # entries of the rows in use that belong to no candidate are zero (whole lists only)
+        used = (int(rows.max()) // 64 + 1) * 64 if len(rows) and idx is None else 0
+        free = np.ones(used, bool)
+        free[rows[rows < used]] = False
+        assert not hip["stage_tab"][:, :used][:, free].any() and not hip["stage_layers"][:used][free].any(), what + " free rows"
+
+
+def oracle_with_table(oracle_mod, w, nthreads=1):
+    """The oracle's results plus its stage table (the yardstick of stage_tab / stage_layers)."""
+    ora = oracle_mod.simulate(w, nthreads=nthreads)
+    ora["stage_table"] = oracle_mod.stage_table(w, ora)
+    return ora

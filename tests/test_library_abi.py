@@ -17,6 +17,48 @@ def test_header_declares_the_three_calls():
     names = _declared()
     for n in ("distsim_build_events", "distsim_simulate", "distsim_search"):
         assert n in names
+    # the rest of the boundary: context, error text, sizing of the caller's buffers
+    for n in ("distsim_create", "distsim_destroy", "distsim_last_error", "distsim_events_bytes"):
+        assert n in names
+    hdr = open(os.path.join(ROOT, "include", "distsim.h")).read()
+    # simulate takes the candidates itself (nothing of the caller's is kept inside distsim_events)
+    sig = re.search(r"int distsim_simulate\(([^;]*)\);", hdr).group(1)
+    assert "const distsim_candidates *cand" in sig and "const distsim_cluster *cluster" in sig
+    ev = hdr[hdr.index("typedef struct {\n    int64_t  stage_cap;"):hdr.index("} distsim_events;")]
+    assert "distsim_costs" not in ev and "distsim_candidates" not in ev
+    for code in ("DISTSIM_EINVAL  (-1)", "DISTSIM_ERANGE  (-2)", "DISTSIM_EHIP    (-3)", "DISTSIM_ELIMIT  (-4)"):
+        assert code in hdr
+
+
+def test_events_sizing_and_binding_need_no_gpu():
+    """distsim_events_bytes / distsim_events_bind are host-side arithmetic: the arrays they lay out are
+    256-byte aligned, inside the block, disjoint, and large enough."""
+    import ctypes as C
+    import paper_2306_08423_amd as ds
+    from paper_2306_08423_amd import binding as b
+    lib = ds.load_library()
+    co = b._Costs(64, 4, None, None, None, None, None, None, None, None)
+    Cn, cap = 1000, 4096
+    small = lib.distsim_events_bytes(C.byref(co), Cn, cap, 0)
+    big = lib.distsim_events_bytes(C.byref(co), Cn, cap, 1)
+    assert 0 < small < big and big - small >= cap * (8 * 8 + 4)
+    assert lib.distsim_events_bytes(C.byref(b._Costs(300, 4)), Cn, cap, 0) == 0          # L beyond its limit
+    assert lib.distsim_events_bytes(C.byref(co), -1, cap, 0) == 0
+    ev = b._Events()
+    base = 1 << 30                                                                        # any 256-byte aligned address
+    assert lib.distsim_events_bind(C.byref(ev), C.c_void_p(base), big, C.byref(co), Cn, cap, 1) == 0
+    spans = [(ev.status, Cn * 4), (ev.stage_pos, Cn * 8), (ev.num_events, Cn * 8), (ev.workspace, ev.workspace_bytes),
+             (ev.stage_tab, cap * 64), (ev.stage_layers, cap * 4)]
+    assert ev.stage_cap == cap and ev.L == 64 and ev.V == 4
+    assert ev.workspace_bytes == lib.distsim_workspace_bytes(64, 4, Cn)
+    spans.sort()
+    for (p, n), (q, _) in zip(spans, spans[1:] + [(base + big, 0)]):
+        assert p % 256 == 0 and p >= base and p + n <= q
+    assert lib.distsim_events_bind(C.byref(ev), C.c_void_p(base), big - 1, C.byref(co), Cn, cap, 1) == -1
+    assert lib.distsim_events_bind(C.byref(ev), C.c_void_p(base + 8), big, C.byref(co), Cn, cap, 1) == -1
+    assert lib.distsim_events_bind(C.byref(ev), C.c_void_p(base), big, C.byref(b._Costs(64, 40)), Cn, cap, 1) == -4
+    assert lib.distsim_events_bind(C.byref(ev), C.c_void_p(base), small, C.byref(co), Cn, cap, 0) == 0
+    assert not ev.stage_tab and not ev.stage_layers
 
 
 def test_library_exports_every_declared_symbol():
