@@ -317,6 +317,23 @@ int distsim_search(distsim_ctx *ctx, const int64_t *batch_ns, const int64_t *wei
                    int objective, int64_t *best, void *scratch, void *hip_stream);
 
 /*
+ * distsim_search for callers that cannot allocate device memory or hand any over: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, results and
+ * errors as distsim_search, minus `scratch`: the per-workgroup partial results live in a device
+ * array inside the library, DISTSIM_SEARCH_STATIC_SCRATCH_BYTES (48 KiB) on every GPU the library
+ * is used on, held until the process ends; its address was taken when the context was created.
+ * The call allocates nothing (no device memory, no events, no host-side growth) and never
+ * synchronises; it is not timed by distsim_timing_enable.  At most DISTSIM_SEARCH_STATIC_MAX_C
+ * candidates, else ELIMIT.  All calls on one GPU share the array: two that may overlap in time
+ * (different streams, threads or contexts of that GPU) race; calls on one stream are ordered
+ * and every call overwrites what it reads, so nothing has to be cleared in between.
+ */
+#define DISTSIM_SEARCH_STATIC_SCRATCH_BYTES (2048 * 24)
+#define DISTSIM_SEARCH_STATIC_MAX_C 2147483647LL
+int distsim_search_static(distsim_ctx *ctx, const int64_t *batch_ns, const int64_t *weight, int64_t C,
+                          int objective, int64_t *best, void *hip_stream);
+
+/*
  * Timeline dump for selected candidates: the per-device event lists that Algorithm 1 builds,
  * reduced to their stage-tasks (Sec. 3.2: the timeline says when which device computes and
  * communicates; Sec. 5.3 / 5.4 compare exactly these start and end timestamps).

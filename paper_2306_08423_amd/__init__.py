@@ -6,6 +6,6 @@ PyTorch device tensors into those calls.
 """
 from .binding import (  # noqa: F401
     Context, DeviceWorkload, DistSimError, Events, SimOutputs, EXPORTS, KERNELS, COL, LIB_PATH,
-    alloc_dedup, alloc_events, alloc_events_bound, alloc_outputs, alloc_search, distsim_bubbles, distsim_comm_event_times, distsim_dedup_events, distsim_build_events, distsim_search, distsim_simulate, distsim_timeline,
+    alloc_dedup, alloc_events, alloc_events_bound, alloc_outputs, alloc_search, distsim_bubbles, distsim_comm_event_times, distsim_dedup_events, distsim_build_events, distsim_search, distsim_search_static, distsim_simulate, distsim_timeline,
     load_library, stage_entries, stage_rows, upload,
 )

@@ -18,7 +18,7 @@ LIB_PATH = os.path.join(_HERE, "libdistsim_hip.so")
 
 EXPORTS = (
     "distsim_create", "distsim_destroy", "distsim_last_error", "distsim_workspace_bytes", "distsim_stage_entries",
-    "distsim_events_bytes", "distsim_events_bind", "distsim_build_events", "distsim_simulate", "distsim_search_scratch_bytes", "distsim_search",
+    "distsim_events_bytes", "distsim_events_bind", "distsim_build_events", "distsim_simulate", "distsim_search_scratch_bytes", "distsim_search", "distsim_search_static",
     "distsim_timeline", "distsim_bubbles", "distsim_dedup_workspace_bytes", "distsim_dedup_events", "distsim_comm_event_times",
     "distsim_timing_enable", "distsim_timing_read", "distsim_kernel_name",
 )
@@ -99,6 +99,8 @@ def load_library():
     lib.distsim_search.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int, C.c_void_p,
                                    C.c_void_p, C.c_void_p]
     lib.distsim_search.restype = C.c_int
+    lib.distsim_search_static.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int, C.c_void_p, C.c_void_p]
+    lib.distsim_search_static.restype = C.c_int
     lib.distsim_timeline.argtypes = [C.c_void_p, C.POINTER(_Cluster), C.POINTER(_Cand), C.POINTER(_Events), C.c_int64] + [C.c_void_p] * 7
     lib.distsim_timeline.restype = C.c_int
     lib.distsim_bubbles.argtypes = [C.c_void_p, C.POINTER(_Cand), C.POINTER(_Events), C.c_int64] + [C.c_void_p] * 6
@@ -340,6 +342,12 @@ def distsim_search(ctx: Context, batch_ns: torch.Tensor, Cn: int, best: torch.Te
                    weight: Optional[torch.Tensor] = None, objective: int = 0) -> None:
     ctx.check(ctx.lib.distsim_search(ctx.h, _ptr(batch_ns), _ptr(weight), Cn, objective, _ptr(best), _ptr(scratch),
                                      _stream()))
+
+
+def distsim_search_static(ctx: Context, batch_ns: torch.Tensor, Cn: int, best: torch.Tensor,
+                          weight: Optional[torch.Tensor] = None, objective: int = 0) -> None:
+    """distsim_search with the partial results in the library's own device array: no scratch argument."""
+    ctx.check(ctx.lib.distsim_search_static(ctx.h, _ptr(batch_ns), _ptr(weight), Cn, objective, _ptr(best), _stream()))
 
 
 def distsim_timeline(ctx: Context, dw: DeviceWorkload, ev: Events, sel: torch.Tensor, task_off: torch.Tensor,

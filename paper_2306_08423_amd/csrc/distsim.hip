@@ -18,6 +18,12 @@
 
 using namespace distsim;
 
+// Scratch of distsim_search_static: the per-workgroup partial results of the argmin, in a device
+// array of the library itself, so that this entry point needs no memory from anybody.  In host code
+// the name is only a handle: the array's device address comes from hipGetSymbolAddress, once per
+// context (with the context's device current), and only that pointer is handed to kernels.
+static __device__ __align__(256) unsigned char scratch[kSearchMaxBlocks * sizeof(Best)];
+
 struct TimedLaunch {
     hipEvent_t start, stop;
 };
@@ -30,6 +36,8 @@ struct distsim_ctx {
     // forked from and joined to the caller's stream with the two events
     hipStream_t side = nullptr;
     hipEvent_t fork = nullptr, join = nullptr;
+    void* static_scratch = nullptr;          // device address of `scratch` on this context's device
+    std::string static_scratch_err;          // why it could not be taken (empty = taken)
     std::string err;
     bool timing = false;
     std::vector<TimedLaunch> rec[DISTSIM_K_COUNT];
@@ -209,6 +217,13 @@ int distsim_create(distsim_ctx** out, int hip_device) {
                       hipStreamCreateWithFlags(&ctx->side, hipStreamNonBlocking) == hipSuccess &&
                       hipEventCreateWithFlags(&ctx->fork, hipEventDisableTiming) == hipSuccess &&
                       hipEventCreateWithFlags(&ctx->join, hipEventDisableTiming) == hipSuccess;
+    if (made) {
+        // every device holds its own copy of the array at its own address
+        void* p = nullptr;
+        const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e == hipSuccess && p) ctx->static_scratch = p;
+        else ctx->static_scratch_err = std::string("hipGetSymbolAddress(scratch): ") + hipGetErrorString(e);
+    }
     if (had) (void)hipSetDevice(prev);
     if (!made) { distsim_destroy(ctx); return DISTSIM_EHIP; }
     if (const char* e = getenv("DISTSIM_SPLIT_MIN_ITEMS")) {
@@ -476,21 +491,14 @@ size_t distsim_search_scratch_bytes(int64_t C) {
     return (size_t)kSearchMaxBlocks * sizeof(Best);
 }
 
-int distsim_search(distsim_ctx* ctx, const int64_t* batch_ns, const int64_t* weight, int64_t C, int objective,
-                   int64_t* best, void* scratch, void* hip_stream) {
-    if (!ctx) return DISTSIM_EINVAL;
-    if (!best || !scratch || (C > 0 && !batch_ns)) return fail(ctx, DISTSIM_EINVAL, "null argument");
-    if (objective != 0 && objective != 1) return fail(ctx, DISTSIM_EINVAL, "objective must be 0 or 1");
-    if (objective == 1 && C > 0 && !weight) return fail(ctx, DISTSIM_EINVAL, "objective 1 needs weights");
-    if (C < 0) return fail(ctx, DISTSIM_EINVAL, "negative candidate count");
-    DeviceScope dev(ctx->device);
-    HIP_TRY(dev.err);
-    hipStream_t st = (hipStream_t)hip_stream;
-    Best* partial = (Best*)scratch;
+namespace {
+
+// The two launches of the argmin; `partial` holds one Best per workgroup of the first.
+int launch_search(distsim_ctx* ctx, const int64_t* batch_ns, const int64_t* weight, int64_t C, int objective,
+                  int64_t* best, Best* partial, hipStream_t st) {
     int64_t nb = (C + kSearchBlock * 4 - 1) / (kSearchBlock * 4);
     if (nb > kSearchMaxBlocks) nb = kSearchMaxBlocks;
     if (nb < 1) nb = 1;
-    Timer t(ctx, st, DISTSIM_K_SEARCH);
     if (objective == 0) {
         hipLaunchKernelGGL(k_search_partial<0>, dim3((int)nb), dim3(kSearchBlock), 0, st, batch_ns, weight, C, partial);
         hipLaunchKernelGGL(k_search_final<0>, dim3(1), dim3(kSearchBlock), 0, st, partial, (int)nb, best);
@@ -500,6 +508,39 @@ int distsim_search(distsim_ctx* ctx, const int64_t* batch_ns, const int64_t* wei
     }
     HIP_TRY(hipGetLastError());
     return DISTSIM_OK;
+}
+
+}  // namespace
+
+int distsim_search(distsim_ctx* ctx, const int64_t* batch_ns, const int64_t* weight, int64_t C, int objective,
+                   int64_t* best, void* scratch_mem, void* hip_stream) {
+    if (!ctx) return DISTSIM_EINVAL;
+    if (!best || !scratch_mem || (C > 0 && !batch_ns)) return fail(ctx, DISTSIM_EINVAL, "null argument");
+    if (objective != 0 && objective != 1) return fail(ctx, DISTSIM_EINVAL, "objective must be 0 or 1");
+    if (objective == 1 && C > 0 && !weight) return fail(ctx, DISTSIM_EINVAL, "objective 1 needs weights");
+    if (C < 0) return fail(ctx, DISTSIM_EINVAL, "negative candidate count");
+    DeviceScope dev(ctx->device);
+    HIP_TRY(dev.err);
+    hipStream_t st = (hipStream_t)hip_stream;
+    Timer t(ctx, st, DISTSIM_K_SEARCH);
+    return launch_search(ctx, batch_ns, weight, C, objective, best, (Best*)scratch_mem, st);
+}
+
+int distsim_search_static(distsim_ctx* ctx, const int64_t* batch_ns, const int64_t* weight, int64_t C, int objective,
+                          int64_t* best, void* hip_stream) {
+    if (!ctx) return DISTSIM_EINVAL;
+    if (!best || (C > 0 && !batch_ns)) return fail(ctx, DISTSIM_EINVAL, "null argument");
+    if (objective != 0 && objective != 1) return fail(ctx, DISTSIM_EINVAL, "objective must be 0 or 1");
+    if (objective == 1 && C > 0 && !weight) return fail(ctx, DISTSIM_EINVAL, "objective 1 needs weights");
+    if (C < 0) return fail(ctx, DISTSIM_EINVAL, "negative candidate count");
+    if (C > DISTSIM_SEARCH_STATIC_MAX_C)
+        return fail(ctx, DISTSIM_ELIMIT, "distsim_search_static: more than DISTSIM_SEARCH_STATIC_MAX_C (2^31 - 1) candidates");
+    if (!ctx->static_scratch) return fail(ctx, DISTSIM_EHIP, ctx->static_scratch_err.empty() ? "no static scratch" : ctx->static_scratch_err);
+    static_assert(sizeof(scratch) == DISTSIM_SEARCH_STATIC_SCRATCH_BYTES, "header and array disagree");
+    DeviceScope dev(ctx->device);
+    HIP_TRY(dev.err);
+    // no timer here: its events would be created on first use, and this call creates nothing
+    return launch_search(ctx, batch_ns, weight, C, objective, best, (Best*)ctx->static_scratch, (hipStream_t)hip_stream);
 }
 
 int distsim_bubbles(distsim_ctx* ctx, const distsim_candidates* cd, const distsim_events* events, int64_t n,
