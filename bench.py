@@ -139,6 +139,109 @@ def time_variants(ds, ctx, w, n):
     return res
 
 
+def replicated_events(w, num_events, status) -> int:
+    """Events of the full timeline that Algorithm 1 and the data-parallel modelling step build: the pp
+    distinct device lists are appended to all tp devices of a stage and duplicated dp times."""
+    import numpy as np
+    ok = status == 0
+    rep = w.cand["tp"].astype(np.int64) * w.cand["dp"].astype(np.int64)
+    return int((num_events[ok] * rep[ok]).sum())
+
+
+def measure(ds, torch, ctx, w, steps, warmup, table=False):
+    """One workload through the three calls: `steps` timed steps with the library's per-kernel timers
+    off (the headline), then the same number with them on (per-kernel times, span of the two sweep
+    kernels).  Returns the figures and the device buffers (for the later sections)."""
+    import numpy as np
+    from workloads import total_stages
+    dw = ds.upload(w, ctx.device)
+    ev = ds.alloc_events(ctx, dw.L, dw.V, dw.C, ds.stage_entries(w.cand["pp"]), table=table)
+    out = ds.alloc_outputs(ctx, ev, util=True)
+    best, scratch = ds.alloc_search(ctx, dw.C)
+
+    def step():
+        ds.distsim_build_events(ctx, dw, ev)
+        ds.distsim_simulate(ctx, dw, ev, out)
+        ds.distsim_search(ctx, out.batch_ns, dw.C, best, scratch)
+
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    # second pass, same launches: HIP events of the library around every kernel, on the stream it runs on
+    ctx.timing_enable(True)
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    kt = ctx.timing_read()
+    ctx.timing_enable(False)
+    C, S = dw.C, total_stages(w)
+    m, pp = w.cand["m"].astype(np.int64), w.cand["pp"].astype(np.int64)
+    tasks = int((2 * m * pp).sum())
+    status = ev.status[:C].cpu().numpy()
+    num_events = ev.num_events[:C].cpu().numpy()
+    sim_ms, sim_n = kt["k_simulate"]
+    gp_ms, gp_n = kt["k_simulate_gpipe"]
+    sim_avg_s = sim_ms / max(sim_n, 1) / 1e3
+    # algorithmic HBM bytes of the sweep per launch: descriptor in (32 B), batch_ns and num_events out
+    # (16 B) per candidate; partition byte in (1 B) and comp / comm / util out (24 B) per stage
+    sim_bytes = C * (32 + 16) + S * (1 + 24)
+    res = {
+        "C": C, "S": S, "tasks": tasks, "dt": dt, "kt": kt, "valid": int((status == 0).sum()),
+        "events": int(num_events.sum()), "events_replicated": replicated_events(w, num_events, status),
+        "sim_avg_s": sim_avg_s, "sim_launches": sim_n, "gpipe_ms": gp_ms / max(gp_n, 1), "sim_bytes": sim_bytes,
+    }
+    return res, (dw, ev, out, best, scratch, step)
+
+
+def sweep_rooflines(r, traffic, copy_gbs):
+    """The two views of the sweep kernels (k_simulate and k_simulate_gpipe side by side)."""
+    hbm = {
+        "kernel": "k_simulate || k_simulate_gpipe", "bound": "hbm",
+        "achieved": r["sim_bytes"] / r["sim_avg_s"] / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+        "traffic": traffic, "algorithmic_bytes_per_launch": r["sim_bytes"],
+        "avg_launch_ms": r["sim_avg_s"] * 1e3, "launches": r["sim_launches"],
+        "launch_ms": {"span": r["sim_avg_s"] * 1e3, "k_simulate_gpipe": r["gpipe_ms"]},
+        "note": "span of the two sweep kernels from HIP events on the caller's stream around fork and join, "
+                "taken in a second pass of the same steps with the library's timers on; the sweep is bound by "
+                "VALU issue, not by HBM (see roofline_alu)",
+    }
+    hbm["frac"] = hbm["achieved"] / HBM_PEAK_GBS
+    if copy_gbs:
+        hbm["frac_of_measured_copy"] = hbm["achieved"] / copy_gbs
+    alu = {
+        "kernel": "k_simulate || k_simulate_gpipe", "bound": "alu",
+        "achieved": FLOPS_PER_TASK * r["tasks"] / r["sim_avg_s"] / 1e12, "peak": ALU_PEAK_TFLOPS, "unit": "TFLOP/s",
+        "derivation": "3 fp64 operations per stage-task (producer end + p2p, max with the device's previous end, "
+                      "+ duration) against 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz = 39.3 T non-FMA fp64 "
+                      "operations/s (the published 78.6 TFLOP/s counts an FMA as two)",
+    }
+    alu["frac"] = alu["achieved"] / alu["peak"]
+    alu["frac_of_published_fp64_peak"] = alu["achieved"] / 78.6
+    return hbm, alu
+
+
+def copy_bandwidth(torch, device, nbytes=1 << 30, reps=10):
+    """Device-to-device copy of nbytes, timed with HIP events: read + write bytes per second in GB/s."""
+    src = torch.empty(nbytes, dtype=torch.uint8, device=device)
+    dst = torch.empty_like(src)
+    dst.copy_(src)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        dst.copy_(src)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / reps
+    del src, dst
+    return 2 * nbytes / (ms / 1e3) / 1e9
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -160,8 +263,12 @@ def main() -> int:
                     help="also time the argmin alone over this many seeded batch times, a list long enough for "
                          "HBM to bound it (0 = skip)")
     ap.add_argument("--no-graph", action="store_true", help="skip the HIP-graph replay of the step")
-    ap.add_argument("--calib-copy", action="store_true",
-                    help="also run one 1 GiB device-to-device copy (known traffic, for scaling HBM counters)")
+    ap.add_argument("--no-copy", action="store_true",
+                    help="skip the timed 1 GiB device-to-device copy (the HBM bandwidth this box reaches; its "
+                         "known traffic also scales the HBM counters of a profiler run)")
+    ap.add_argument("--second", default="gpt96",
+                    help="also time the three calls on this workload, the one with the most work per candidate "
+                         "(none = skip)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: the library evaluates candidates on ONE GPU; --gpus must be 1 "
@@ -172,35 +279,17 @@ def main() -> int:
     import numpy as np
     import torch
     import paper_2306_08423_amd as ds
-    from workloads import make_workload, subset, total_stages
+    from workloads import make_workload, subset
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         return 3
     w = make_workload(args.workload)
     ctx = ds.Context(0)
-    dw = ds.upload(w, ctx.device)
-    S = total_stages(w)
-    ev = ds.alloc_events(ctx, dw.L, dw.V, dw.C, ds.stage_entries(w.cand["pp"]), table=not args.no_stage_table)
-    out = ds.alloc_outputs(ctx, ev, util=True)
-    best, scratch = ds.alloc_search(ctx, dw.C)
-
-    def step():
-        ds.distsim_build_events(ctx, dw, ev)
-        ds.distsim_simulate(ctx, dw, ev, out)
-        ds.distsim_search(ctx, out.batch_ns, dw.C, best, scratch)
-
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    ctx.timing_enable(True)
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    kt = ctx.timing_read()
-    ctx.timing_enable(False)
+    res, (dw, ev, out, best, scratch, step) = measure(ds, torch, ctx, w, args.steps, args.warmup,
+                                                       table=not args.no_stage_table)
+    S, dt, kt = res["S"], res["dt"], res["kt"]
+    copy_gbs = copy_bandwidth(torch, ctx.device) if not args.no_copy else None
 
     # the same step recorded once into a HIP graph and replayed (the calls allocate nothing and never
     # synchronise): what a caller in a tight loop pays when launch overhead matters
@@ -332,41 +421,22 @@ def main() -> int:
     if args.variants > 0:
         variants = time_variants(ds, ctx, w, min(args.variants, dw.C))
 
-    if args.calib_copy:
-        src = torch.empty(1 << 30, dtype=torch.uint8, device=ctx.device)
-        dst = torch.empty_like(src)
-        dst.copy_(src)
-        torch.cuda.synchronize()
-        del src, dst
-
     C = dw.C
-    nev = int(ev.num_events[:C].sum().item())
-    status_ok = int((ev.status[:C] == 0).sum().item())
-    m = w.cand["m"].astype(np.int64)
-    pp = w.cand["pp"].astype(np.int64)
-    tasks = int((2 * m * pp).sum())
-    # the sweep is two kernels per step that share the candidates and run side by side: k_simulate
-    # (everything but pairs of GPipe items) and, on a stream of the library's context,
-    # k_simulate_gpipe; the library's timer of k_simulate spans both, and so does the roofline figure
-    sim_ms, sim_n = kt["k_simulate"]
-    gp_ms, gp_n = kt["k_simulate_gpipe"]
-    sim_avg_s = sim_ms / max(sim_n, 1) / 1e3
-    # algorithmic HBM bytes of k_simulate per launch: descriptor in (32 B), batch_ns and num_events
-    # out (16 B) per candidate; partition byte in (1 B) and comp/comm/util out (24 B) per stage
-    sim_bytes = C * (32 + 16) + S * (1 + 24)
-    roofline = {
-        "kernel": "k_simulate || k_simulate_gpipe", "bound": "alu",
-        "achieved": FLOPS_PER_TASK * tasks / sim_avg_s / 1e12, "peak": ALU_PEAK_TFLOPS, "unit": "TFLOP/s",
-        "traffic": read_traffic(args.workload),
-        "avg_launch_ms": sim_avg_s * 1e3, "launches": sim_n,
-        "launch_ms": {"span": sim_ms / max(sim_n, 1), "k_simulate_gpipe": gp_ms / max(gp_n, 1)},
-    }
-    roofline["frac"] = roofline["achieved"] / roofline["peak"]
-    roofline_hbm = {
-        "kernel": "k_simulate || k_simulate_gpipe", "bound": "hbm", "achieved": sim_bytes / sim_avg_s / 1e9, "peak": HBM_PEAK_GBS,
-        "unit": "GB/s", "algorithmic_bytes_per_launch": sim_bytes,
-    }
-    roofline_hbm["frac"] = roofline_hbm["achieved"] / HBM_PEAK_GBS
+    tasks = res["tasks"]
+    roofline, roofline_alu = sweep_rooflines(res, read_traffic(args.workload), copy_gbs)
+
+    second = None
+    if args.second and args.second != "none" and args.second != args.workload:
+        w2 = make_workload(args.second)
+        r2, bufs2 = measure(ds, torch, ctx, w2, max(args.steps // 2, 3), 2)
+        hbm2, alu2 = sweep_rooflines(r2, read_traffic(args.second), copy_gbs)
+        second = {"workload": f"{args.second}: {r2['C']} candidates, {r2['S']} stages, {r2['tasks']} stage-tasks",
+                  "value": r2["C"] * max(args.steps // 2, 3) / r2["dt"], "unit": "strategies/s",
+                  "ms_per_step": r2["dt"] / max(args.steps // 2, 3) * 1e3,
+                  "events_per_s": r2["events"] * max(args.steps // 2, 3) / r2["dt"],
+                  "stage_tasks_per_s": r2["tasks"] * max(args.steps // 2, 3) / r2["dt"],
+                  "sweep_span_ms": r2["sim_avg_s"] * 1e3, "roofline_hbm_frac": hbm2["frac"], "roofline_alu_frac": alu2["frac"]}
+        del bufs2
 
     cpu_baseline = None
     parity = None
@@ -399,12 +469,20 @@ def main() -> int:
         "data": "synthetic",
         "config": {"workload": f"{args.workload}: {C} candidates, L={dw.L}, V={dw.V}, "
                                f"{w.cluster['num_devices']} simulated devices, {S} stages, {tasks} stage-tasks",
-                   "candidates": C, "valid": status_ok},
-        "events_per_s": nev * args.steps / dt, "stage_tasks_per_s": tasks * args.steps / dt,
+                   "candidates": C, "valid": res["valid"]},
+        "events_per_s": res["events"] * args.steps / dt, "stage_tasks_per_s": tasks * args.steps / dt,
+        "events_replicated_per_s": res["events_replicated"] * args.steps / dt,
+        "events_note": "events_per_s counts the events on the pp distinct device timelines of every candidate; "
+                       "events_replicated_per_s multiplies each candidate's count by tp x dp, the size of the full "
+                       "timeline of Algorithm 1 and the data-parallel modelling step (never the headline)",
+        "timing_note": "value / ms_per_step: `steps` steps with the library's per-kernel timers off; kernel_ms and "
+                       "the rooflines: a second pass of the same steps with the timers on",
         "kernel_ms": {k: (v[0] / max(v[1], 1)) * (v[1] / args.steps) for k, v in kt.items()},
         "kernel_ms_note": "k_simulate is the span of the two sweep kernels, which run side by side "
                           "(k_simulate_gpipe on a stream of the library's context); the other entries are single kernels",
-        "roofline": roofline, "roofline_hbm": roofline_hbm,
+        "roofline": roofline, "roofline_alu": roofline_alu,
+        "hbm_copy_measured_GBs": copy_gbs,
+        "second_workload": second,
         "graph_replay": graph, "timeline": timeline, "ingest": ingest, "search": search, "variants": variants,
         "cpu_baseline": cpu_baseline, "parity": parity,
     }
