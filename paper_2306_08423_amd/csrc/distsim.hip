@@ -32,6 +32,7 @@ struct distsim_ctx {
     int device = 0;
     int num_cus = 256;
     int64_t split_min_items = kSplitMinItems;   // lists of fewer wave-items go through k_simulate alone
+    int64_t grid_per_cu = 128;                  // workgroups per CU of the sweep launches (at most)
     // k_simulate_gpipe runs next to k_simulate on a stream of the context (default priority),
     // forked from and joined to the caller's stream with the two events
     hipStream_t side = nullptr;
@@ -171,7 +172,7 @@ size_t carve_events(distsim_events* ev, void* base, int32_t L, int32_t V, int64_
 // Grid of k_simulate: a wavefront takes two items per turn and items differ a lot in length, so
 // the grid is many times what is resident at once and the dispatcher evens the load out.
 int simulate_grid(const distsim_ctx* ctx, int64_t C) {
-    const int64_t want = (int64_t)ctx->num_cus * 128;
+    const int64_t want = (int64_t)ctx->num_cus * ctx->grid_per_cu;
     const int64_t need = (C + 7) / 8;                         // blocks of 4 waves, 2 items per wave
     return (int)(need < want ? (need < 1 ? 1 : need) : want);
 }
@@ -230,6 +231,11 @@ int distsim_create(distsim_ctx** out, int hip_device) {
         char* end = nullptr;
         const long long v = strtoll(e, &end, 10);
         if (end != e && v >= 0) ctx->split_min_items = v;
+    }
+    if (const char* e = getenv("DISTSIM_GRID_PER_CU")) {
+        char* end = nullptr;
+        const long long v = strtoll(e, &end, 10);
+        if (end != e && v >= 1 && v <= 1024) ctx->grid_per_cu = v;
     }
     *out = ctx;
     return DISTSIM_OK;
@@ -306,7 +312,6 @@ int distsim_build_events(distsim_ctx* ctx, const distsim_costs* costs, const dis
     out->V = costs->V;
     out->num_candidates = C;
 
-    const int cblocks = (int)((C + 255) / 256);
     // The layer tables do not depend on the candidates and nothing before k_stage_events reads
     // them: for a long list they are built on the context's stream next to decode / bins / scatter.
     const bool beside = C >= ctx->split_min_items;
@@ -333,9 +338,12 @@ int distsim_build_events(distsim_ctx* ctx, const distsim_costs* costs, const dis
         Timer t(ctx, st, DISTSIM_K_BINS);
         hipLaunchKernelGGL(k_bins, dim3(1), dim3(kBinsBlock), 0, st, ws, out->stage_cap);
     }
-    if (C > 0) {
+    {
+        // also for C == 0: the first threads fill the order tables of the sweep kernels (their totals)
         Timer t(ctx, st, DISTSIM_K_SCATTER);
-        hipLaunchKernelGGL(k_scatter, dim3(cblocks), dim3(256), 0, st, ca, C, ws, ev);
+        const int64_t threads = C > ws.order_cap ? C : ws.order_cap;
+        hipLaunchKernelGGL(k_scatter, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st, ca, C, ws, ev,
+                           ctx->split_min_items);
     }
     if (beside) HIP_TRY(hipStreamWaitEvent(st, ctx->join, 0));       // what follows on the caller's stream sees the tables
     if (C > 0) {
@@ -391,24 +399,21 @@ int distsim_simulate(distsim_ctx* ctx, const distsim_cluster* cluster, const dis
     } else if (C < ctx->split_min_items) {
         // a list of fewer candidates than that has fewer wave-items too: k_simulate takes all of it
         Timer t(ctx, st, DISTSIM_K_SIMULATE);
-        hipLaunchKernelGGL(k_simulate, dim3(general_grid(ctx, C)), dim3(kSimBlock), 0, st, co, cl, ca, ws, ev, out,
-                           ctx->split_min_items);
+        hipLaunchKernelGGL(k_simulate, dim3(general_grid(ctx, C)), dim3(kSimBlock), 0, st, co, cl, ca, ws, ev, out);
     } else {
         // k_simulate and, for the pairs of GPipe items that it leaves out, k_simulate_gpipe, side
         // by side: they write different rows.  The timer of k_simulate spans both.
         Timer t(ctx, st, DISTSIM_K_SIMULATE);
         HIP_TRY(hipEventRecord(ctx->fork, st));
         HIP_TRY(hipStreamWaitEvent(ctx->side, ctx->fork, 0));
-        hipLaunchKernelGGL(k_simulate, dim3(general_grid(ctx, C)), dim3(kSimBlock), 0, st, co, cl, ca, ws, ev, out,
-                           ctx->split_min_items);
+        hipLaunchKernelGGL(k_simulate, dim3(general_grid(ctx, C)), dim3(kSimBlock), 0, st, co, cl, ca, ws, ev, out);
         {
             Timer ti(ctx, ctx->side, DISTSIM_K_SIM_INIT);
             hipLaunchKernelGGL(k_sim_init, dim3((int)((C + 255) / 256)), dim3(256), 0, ctx->side, events->status, C, batch_ns);
         }
         {
             Timer tg(ctx, ctx->side, DISTSIM_K_SIMULATE_GPIPE);
-            hipLaunchKernelGGL(k_simulate_gpipe, dim3(gpipe_grid(ctx, C)), dim3(kSimBlock), 0, ctx->side, co, cl, ca, ws, ev, out,
-                               ctx->split_min_items);
+            hipLaunchKernelGGL(k_simulate_gpipe, dim3(gpipe_grid(ctx, C)), dim3(kSimBlock), 0, ctx->side, co, cl, ca, ws, ev, out);
         }
         HIP_TRY(hipEventRecord(ctx->join, ctx->side));
         HIP_TRY(hipStreamWaitEvent(st, ctx->join, 0));

@@ -260,9 +260,85 @@ __global__ __launch_bounds__(kBinsBlock) void k_bins(Workspace ws, int64_t stage
     }
 }
 
-// Scatter candidates into visiting order and hand each its block of per-stage entries.
-__global__ __launch_bounds__(256) void k_scatter(CandDev ca, int64_t C, Workspace ws, EventsDev ev) {
+// ---------------------------------------------------------------------------------------
+// Order in which the sweep kernels take the pairs of their wave-items.  Two launches share the
+// items: in every class the leading items that hold only GPipe candidates (hdr[H_GPIPE_ITEMS +
+// class], an even number) belong to k_simulate_gpipe, all others to k_simulate; a list of fewer
+// than split_min_items wave-items is not worth two launches and goes to k_simulate whole.
+// Inside a class the items are sorted by micro-batch count, longest sweep first, but the classes
+// follow one another, so in visiting order the lengths form a saw-tooth: taken in that order the
+// long items of the narrower classes would start late and a launch would end with a few long
+// sweeps on an empty machine.  So every class is cut into kOrderGroups groups of consecutive pairs
+// and a launch takes group 0 of every class, then group 1 of every class, and so on (the last
+// group also holds the up to kOrderGroups - 1 pairs that the even split leaves over): pairs at the
+// same relative position of their class, which have about the same micro-batch count, run at
+// about the same time.  A pair never straddles two classes.
+constexpr int kOrderShift = 6, kOrderGroups = 1 << kOrderShift;
+
+// The items of class k that a launch owns: the first of them (relative to the class) and how many.
+// Items past the room in the per-stage arrays (wave-item index >= item_limit) own nothing and are
+// dropped from the class's end.
+__device__ __forceinline__ void owned_range(const int64_t* __restrict__ hdr, int k, bool gpipe, bool split,
+                                            int64_t item_limit, int32_t& first, int32_t& own) {
+    const int64_t n = hdr[H_ITEM_START + k + 1] - hdr[H_ITEM_START + k], g = split ? hdr[H_GPIPE_ITEMS + k] : 0;
+    const int64_t f = gpipe || !split ? 0 : g;
+    int64_t o = gpipe ? g : n - g;
+    const int64_t room = item_limit - hdr[H_ITEM_START + k] - f;
+    if (o > room) o = room > 0 ? room : 0;
+    first = (int32_t)f;
+    own = (int32_t)o;
+}
+
+// Entry q of both order tables (called by thread q of k_scatter, whose grid covers order_cap).
+__device__ __forceinline__ void pair_order_entry(const Workspace& ws, int32_t q, int64_t stage_cap, int64_t split_min_items) {
+    const int64_t* __restrict__ hdr = ws.hdr;
+    int64_t W = hdr[H_NUM_ITEMS];                       // items that have room in the per-stage arrays
+    if (W * kWave > stage_cap) W = stage_cap / kWave;
+    const bool split = hdr[H_NUM_ITEMS] >= split_min_items;
+    for (int which = 0; which < 2; which++) {           // 0: k_simulate's pairs, 1: k_simulate_gpipe's
+        const bool gpipe = which == 1;
+        int32_t first[kClasses], own[kClasses], pairs[kClasses];
+        int32_t group_total = 0, total = 0;
+#pragma unroll
+        for (int k = 0; k < kClasses; k++) {
+            owned_range(hdr, k, gpipe, split, W, first[k], own[k]);       // without the split k_simulate_gpipe owns nothing
+            pairs[k] = (own[k] + 1) >> 1;
+            group_total += pairs[k] >> kOrderShift;
+            total += pairs[k];
+        }
+        if (q == 0) ws.hdr[H_PAIRS + which] = total;
+        if (q >= total || q >= ws.order_cap) continue;
+        int32_t g = kOrderGroups - 1;
+        if (group_total > 0) {
+            g = q / group_total;
+            if (g > kOrderGroups - 1) g = kOrderGroups - 1;
+        }
+        const bool last = g == kOrderGroups - 1;
+        int32_t r = q - g * group_total;
+        int32_t item = 0, has_two = 0;
+        bool found = false;
+#pragma unroll
+        for (int k = 0; k < kClasses; k++) {
+            const int32_t per = pairs[k] >> kOrderShift;
+            const int32_t sz = last ? pairs[k] - g * per : per;
+            if (!found && r < sz) {
+                found = true;
+                const int32_t j = g * per + r;
+                item = (int32_t)hdr[H_ITEM_START + k] + first[k] + 2 * j;
+                has_two = 2 * j + 1 < own[k];
+            }
+            if (!found) r -= sz;
+        }
+        ws.order[which][q] = item | (has_two ? (int32_t)0x80000000 : 0);
+    }
+}
+
+// Scatter candidates into visiting order and hand each its block of per-stage entries; the first
+// order_cap threads also fill the order tables of the sweep kernels.
+__global__ __launch_bounds__(256) void k_scatter(CandDev ca, int64_t C, Workspace ws, EventsDev ev,
+                                                 int64_t split_min_items) {
     const int64_t c = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (c < ws.order_cap) pair_order_entry(ws, (int32_t)c, ev.stage_cap, split_min_items);
     if (c >= C) return;
     const int kv = ws.key[c];
     if (kv < 0) return;

@@ -513,32 +513,50 @@ __device__ __forceinline__ void simulate_items(const ClusterDev& cl, const CandD
         const bool has_ar = (misc >> 16) & 1, dropped = (misc >> 17) & 1;
         int64_t finish = endB + AR, ar_busy = AR, nar = has_ar ? 1 : 0;
         if (has_ar && cl.bucket > 0) {
+            // Bucketed gradient all-reduce behind the last micro-batch's backward: layer l (taken from
+            // hi - 1 down to lo) is ready at r_l = start of that backward + its events from hi - 1
+            // down to l, the open bucket then holds the bytes of the layers l..hi-1 modulo the bucket
+            // size, every full bucket is issued at once and the events queue on the device's
+            // communication stream, t <- max(t, r_l) + (buckets issued at l) * ar_cap; the rest goes
+            // after the stage's first layer.  Unrolled, that max-plus chain is
+            //   t = max over l of  r_l + (events issued at the layers l, l-1, ..., lo)
+            // and the number of full buckets issued by the layers above l is floor(bytes above l /
+            // bucket size), so every term stands on its own: no chain through the layers, and their
+            // table reads are independent.  (A layer that issues nothing adds a term that the next
+            // issuing layer below it, or the end of the backward itself, dominates.)
             const int lo = misc & 0xff, hi = (misc >> 8) & 0xff, v = misc >> 18, dp = park.dp[u][slot];
-            // per layer: backward time up to the layer (word 1) and gradient bytes (word 3)
+            // per layer boundary: backward time of the layers below it (word 1), their gradient bytes (word 3)
             const int64_t* row = ws.comb + (size_t)((v * kMaxPP + ppv[u] - 1) * (L + 1)) * kCombWords;
             const int64_t startB = endB - (int64_t)sw[u].Bd;
-            const int64_t tot_hi = row[hi * kCombWords + 1];
+            const int64_t tot_hi = row[hi * kCombWords + 1], g_hi = row[hi * kCombWords + 3];
             const int64_t ar_cap = allreduce_ns(cl, dp, cl.bucket);
-            int64_t acc = 0, t = 0;
-            ar_busy = 0; nar = 0;
-            for (int l = hi - 1; l >= lo; l--) {
-                const int64_t ready = startB + (tot_hi - row[l * kCombWords + 1]);
-                acc += row[(l + 1) * kCombWords + 3] - row[l * kCombWords + 3];
-                const int64_t kk = (int64_t)udiv64_by((uint64_t)acc, (uint64_t)cl.bucket, cl.inv_bucket);
-                if (kk > 0) {
-                    t = (t > ready ? t : ready) + kk * ar_cap;
-                    ar_busy += kk * ar_cap;
-                    nar += kk;
-                    acc -= kk * cl.bucket;
+            const int64_t G = g_hi - row[lo * kCombWords + 3];
+            const int64_t full = (int64_t)udiv64_by((uint64_t)G, (uint64_t)cl.bucket, cl.inv_bucket);
+            const int64_t rest = G - full * cl.bucket;
+            const int64_t dlast = rest > 0 ? allreduce_ns(cl, dp, rest) : 0;
+            ar_busy = full * ar_cap + dlast;
+            nar = full + (rest > 0 ? 1 : 0);
+            const int64_t all = startB + tot_hi + ar_busy;          // r_l + events from l down = all - (time below l) - (events above l)
+            int64_t t = endB;
+            // four layers at a time, their table entries requested together (at clamped, always valid
+            // addresses): a trip to memory per four layers instead of one per layer
+            constexpr int kBatch = 4;
+            for (int l0 = lo; l0 < hi; l0 += kBatch) {
+                int64_t gb[kBatch], tb[kBatch];
+#pragma unroll
+                for (int i = 0; i < kBatch; i++) {
+                    const int l = l0 + i < hi ? l0 + i : hi - 1;
+                    gb[i] = row[(l + 1) * kCombWords + 3];
+                    tb[i] = row[l * kCombWords + 1];
                 }
-                if (l == lo && acc > 0) {
-                    const int64_t dlast = allreduce_ns(cl, dp, acc);
-                    t = (t > ready ? t : ready) + dlast;
-                    ar_busy += dlast;
-                    nar += 1;
+#pragma unroll
+                for (int i = 0; i < kBatch; i++) {
+                    const int64_t above = (int64_t)udiv64_by((uint64_t)(g_hi - gb[i]), (uint64_t)cl.bucket, cl.inv_bucket);
+                    const int64_t term = all - tb[i] - above * ar_cap;      // a clamped entry repeats the last layer's term
+                    t = term > t ? term : t;
                 }
             }
-            finish = t > endB ? t : endB;
+            finish = t;
         }
         // one event per stage that has one, or the stages' bucket counts
         nar = cl.bucket > 0 ? group_sum(nar, width) : group_count(has_ar, width);
@@ -563,42 +581,35 @@ __device__ __forceinline__ void simulate_items(const ClusterDev& cl, const CandD
 // candidates (hdr[H_GPIPE_ITEMS + class], an even number) belong to k_simulate_gpipe, which
 // sweeps them two at a time with the stages regrouped two to a lane; all other items belong to
 // k_simulate.  Two kernels, so that each gets registers allotted for its own sweep.  Either
-// launch numbers its own items and a wavefront takes them two at a time, with the stride of
-// the grid (about one pair per wavefront for large lists: the hardware's dispatch order is the
-// load balancing, and the items of the widest class, the longest, go first).
+// launch numbers the pairs of its own items and a wavefront takes them with the stride of the grid
+// (about one pair per wavefront for large lists: the hardware's dispatch order is the load
+// balancing, so the order of the pairs is longest first, see PairOrder).
 
-constexpr int64_t kSplitMinItems = 16384;      // default of the threshold below
+constexpr int64_t kSplitMinItems = 16384;      // default list length (wave-items) from which two launches share the items
 
-// Item number t of one launch's share -> its place in visiting order.
-struct OwnedItem {
-    Item it;
-    int64_t w;          // wave-item index (rows w * 64 .. of the per-stage arrays)
-};
 // The header is read through the constant address space: nothing writes it while a sweep runs,
 // and a wave-uniform index then makes every read a scalar load that needs no vector register.
 typedef const __attribute__((address_space(4))) int64_t* HdrPtr;
-__device__ __forceinline__ OwnedItem owned_item(HdrPtr hdr, int64_t t, bool gpipe, bool split) {
+__device__ __forceinline__ Item decode_item_c(HdrPtr hdr, int64_t w) {
     int k = 0;
-    int64_t first = 0;                                  // first owned item of the class, relative to the class
-    for (; k < kClasses - 1; k++) {
-        const int64_t n = hdr[H_ITEM_START + k + 1] - hdr[H_ITEM_START + k], g = split ? hdr[H_GPIPE_ITEMS + k] : 0;
-        const int64_t mine = gpipe ? g : n - g;
-        if (t < mine) break;
-        t -= mine;
-    }
-    first = gpipe || !split ? 0 : hdr[H_GPIPE_ITEMS + k];
-    OwnedItem o;
-    o.w = hdr[H_ITEM_START + k] + first + t;
-    o.it.sh = 6 - k;
-    o.it.pos0 = hdr[H_CLASS_START + k] + ((first + t) << k);
-    o.it.class_end = hdr[H_CLASS_START + k + 1];
-    return o;
+#pragma unroll
+    for (int i = 1; i < kClasses; i++) k += (w >= hdr[H_ITEM_START + i]) ? 1 : 0;
+    Item it;
+    it.sh = 6 - k;
+    it.pos0 = hdr[H_CLASS_START + k] + ((w - hdr[H_ITEM_START + k]) << k);
+    it.class_end = hdr[H_CLASS_START + k + 1];
+    return it;
 }
+
+// The order in which a launch takes its pairs is a table in the workspace (k_pair_order): entry q
+// names the pair's first wave-item and says whether the next item belongs to the pair.  A pair
+// never straddles two classes.
+typedef const __attribute__((address_space(4))) int32_t* OrderPtr;
 
 template <bool GPIPE_PAIRS>
 __device__ __forceinline__ void simulate_all(const CostsDev& co, const ClusterDev& cl, const CandDev& ca,
                                              const Workspace& ws, const EventsDev& ev, const SimOut& out,
-                                             Park& park, double* xp, int64_t split_min_items) {
+                                             Park& park, double* xp) {
     const int lane = lane_id();
     const HdrPtr hdr = (HdrPtr)ws.hdr;
     // the wavefront's number as a scalar: the header words and the item ranges then come through
@@ -607,21 +618,23 @@ __device__ __forceinline__ void simulate_all(const CostsDev& co, const ClusterDe
     const int64_t nwaves = ((int64_t)gridDim.x * blockDim.x) / kWave;
     int64_t W = hdr[H_NUM_ITEMS];                       // items that have room in the per-stage arrays
     if (W * kWave > ev.stage_cap) W = ev.stage_cap / kWave;
-    // A short list is not worth two launches (two ramps and two tails on a machine that neither
-    // fills): below split_min_items wave-items k_simulate takes everything, GPipe pairs included.
-    const bool split = hdr[H_NUM_ITEMS] >= split_min_items;
-    int64_t gp_items = 0;
-    for (int k = 0; k < kClasses; k++) gp_items += split ? hdr[H_GPIPE_ITEMS + k] : 0;
-    int64_t mine = GPIPE_PAIRS ? gp_items : hdr[H_NUM_ITEMS] - gp_items;
-    // items past the room in the per-stage arrays are skipped anyway
-    if (mine > ev.stage_cap + kClasses) mine = ev.stage_cap + kClasses;
-    const int64_t pairs = (mine + 1) / 2;
+    const OrderPtr order = (OrderPtr)ws.order[GPIPE_PAIRS ? 1 : 0];
+    const int64_t pairs = hdr[H_PAIRS + (GPIPE_PAIRS ? 1 : 0)];
     const int L = co.L;
-    for (int64_t q = wave0; q < pairs; q += nwaves) {
-        const bool pair = 2 * q + 1 < mine;
-        const OwnedItem oa = owned_item(hdr, 2 * q, GPIPE_PAIRS, split);
-        const OwnedItem ob = owned_item(hdr, pair ? 2 * q + 1 : 2 * q, GPIPE_PAIRS, split);
-        const Item ia = oa.it, ib = ob.it;
+    // Rounds of nwaves pairs, taken back and forth: a wavefront's pairs are w, 2n-1-w, 2n+w, ...  With
+    // the pairs in order of falling length that gives every wavefront about the same total, so a
+    // grid that is resident all at once ends together; with more wavefronts than pairs it is just
+    // pair number = wavefront number and the hardware's dispatch order balances the load.
+    for (int64_t r0 = 0; r0 < pairs; r0 += 2 * nwaves)
+    for (int half = 0; half < 2; half++) {
+        const int64_t q = half == 0 ? r0 + wave0 : r0 + 2 * nwaves - 1 - wave0;
+        if (q >= pairs) continue;
+        const int32_t e = order[q];
+        const bool pair = e < 0;
+        struct { int64_t w; } oa{e & 0x7fffffff}, ob{pair ? oa.w + 1 : oa.w};
+        const Item ia = decode_item_c(hdr, oa.w);
+        Item ib = ia;                                   // the same class: the next 64 >> sh candidates
+        if (pair) ib.pos0 += (int64_t)1 << (6 - ia.sh);
         const int64_t posa = ia.pos0 + (lane >> ia.sh), posb = ib.pos0 + (lane >> ib.sh);
         Desc da{}, db{};
         if (posa < ia.class_end) da = ws.desc[posa];
@@ -629,14 +642,14 @@ __device__ __forceinline__ void simulate_all(const CostsDev& co, const ClusterDe
         if (has_own_kernel(da)) da = Desc{};          // those candidates have a kernel of their own
         if (has_own_kernel(db)) db = Desc{};
         if constexpr (GPIPE_PAIRS) {
-            // an even number of items per class and room for all of them: always two, side by side
+            // an even number of items per class and room for all of them (k_bins): always two, side by side
             const Desc two[2] = {da, db};
             simulate_items<2, false, true>(cl, ca, ws, ev, out, L, oa.w, ia.sh, two, lane, park, xp);
         } else {
             const bool okA = oa.w < W, okB = pair && ob.w < W;
             // simulated together when every lane sees the same shape (pp, m, schedule) in both,
             // which neighbours in visiting order mostly do, else one after the other
-            const bool same = okA && okB && ob.w == oa.w + 1 && ia.sh == ib.sh &&
+            const bool same = okA && okB &&
                               __builtin_amdgcn_ballot_w64(((da.meta ^ db.meta) & 0xffff) != 0 || da.m != db.m) == 0;
             if (same) {
                 const Desc two[2] = {da, db};
@@ -656,18 +669,18 @@ __device__ __forceinline__ void simulate_all(const CostsDev& co, const ClusterDe
 }
 
 __global__ __launch_bounds__(kSimBlock, 6) void k_simulate(CostsDev co, ClusterDev cl, CandDev ca, Workspace ws,
-                                                           EventsDev ev, SimOut out, int64_t split_min_items) {
+                                                           EventsDev ev, SimOut out) {
     // What only the epilogue needs is parked in LDS during the sweep (each lane its own slot),
     // so that the sweep runs in few enough registers for six wavefronts per SIMD.
     __shared__ Park park;
-    simulate_all<false>(co, cl, ca, ws, ev, out, park, nullptr, split_min_items);
+    simulate_all<false>(co, cl, ca, ws, ev, out, park, nullptr);
 }
 
 __global__ __launch_bounds__(kSimBlock, 6) void k_simulate_gpipe(CostsDev co, ClusterDev cl, CandDev ca, Workspace ws,
-                                                                 EventsDev ev, SimOut out, int64_t split_min_items) {
+                                                                 EventsDev ev, SimOut out) {
     __shared__ Park park;
     __shared__ __align__(16) double regroup[kSimBlock / kWave][2 * kWave];     // 1 KB per wavefront
-    simulate_all<true>(co, cl, ca, ws, ev, out, park, regroup[threadIdx.x / kWave], split_min_items);
+    simulate_all<true>(co, cl, ca, ws, ev, out, park, regroup[threadIdx.x / kWave]);
 }
 
 // Same contract as k_simulate for p2p_blocking = 2 (sends queue on their link): one item per

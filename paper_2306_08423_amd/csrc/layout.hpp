@@ -22,6 +22,7 @@ enum {
     H_NUM_ITEMS = 16,              // total wave-items
     H_GPIPE_ITEMS = 17,            // [kClasses] leading wave-items of each class that hold only GPipe candidates
                                    //            (an even number; zero for the class of one lane per candidate)
+    H_PAIRS = 24,                  // [2] pairs of wave-items that k_simulate / k_simulate_gpipe take (entries of Workspace::order)
     H_WORDS = 32
 };
 
@@ -52,6 +53,11 @@ struct Workspace {
     int32_t *vtp;                  // [kMaxV] the cost table's variant -> tensor-parallel size (a copy: the calls
                                    //         after event generation do not see the cost table any more)
     Desc *desc;                    // [C] candidates in visiting order
+    // Order in which the sweep kernels take pairs of wave-items, longest sweeps first (k_pair_order):
+    // entry = index of the pair's first wave-item | 1 << 31 when the next item belongs to the pair too;
+    // order[0]: k_simulate's pairs, order[1]: k_simulate_gpipe's.
+    int32_t *order[2];             // [order_cap] each
+    int64_t order_cap;
 };
 
 inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
@@ -77,6 +83,9 @@ inline size_t carve(Workspace& w, void* base, int32_t L, int32_t V, int64_t C) {
     w.hdr = (int64_t*)take(H_WORDS * 8);
     w.vtp = (int32_t*)take(kMaxV * 4);
     w.desc = (Desc*)take(Cc * sizeof(Desc));
+    w.order_cap = (int64_t)(Cc / 2 + kClasses + 1);       // a class of n items has (n + 1) / 2 pairs
+    w.order[0] = (int32_t*)take((size_t)w.order_cap * 4);
+    w.order[1] = (int32_t*)take((size_t)w.order_cap * 4);
     return off;
 }
 
