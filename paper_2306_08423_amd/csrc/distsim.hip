@@ -466,12 +466,26 @@ int distsim_timeline(distsim_ctx* ctx, const distsim_cluster* cluster, const dis
     hipStream_t st = (hipStream_t)hip_stream;
     const CostsDev co = costs_after_build(events, ws);
     const CandDev ca = cand_dev(cd);
-    TimelineOut out{sel, task_off, start_ns, end_ns, ar_start_ns, ar_end_ns};
     {
-        // k_timeline uses the DISTSIM_STEP* macros: blocks of kTlWaves whole wavefronts
+        // k_timeline uses the DISTSIM_STEP* macros: blocks of one whole wavefront.  The selection is
+        // packed into wave-items first (counting sort by width class); the sorted entry numbers and
+        // the counters sit in workspace arrays that only distsim_build_events uses otherwise (the
+        // ordering keys, one int32 per candidate, and the bin counters), so a selection longer than
+        // the candidate list goes in several rounds.
         Timer t(ctx, st, DISTSIM_K_TIMELINE);
-        hipLaunchKernelGGL(k_timeline, dim3((unsigned)((n + kTlChunk - 1) / kTlChunk)), dim3(kTlWaves * kWave), 0, st,
-                           co, cl_dev(*cluster), ca, ws, events->status, events->num_candidates, n, out);
+        const int64_t room = events->num_candidates > 0 ? events->num_candidates : 1;
+        for (int64_t at = 0; at < n; at += room) {
+            const int64_t nn = n - at < room ? n - at : room;
+            const TimelineOut out{sel + at, task_off + at, start_ns, end_ns, ar_start_ns + at * kMaxPP, ar_end_ns + at * kMaxPP};
+            const unsigned pb = (unsigned)((nn + 255) / 256);
+            hipLaunchKernelGGL(k_timeline_clear, dim3(1), dim3(kWave), 0, st, ws.bin_count);
+            hipLaunchKernelGGL(k_timeline_pack<0>, dim3(pb), dim3(256), 0, st, ca, events->status, events->num_candidates, nn,
+                               out.sel, ws.bin_count, ws.key, out.ar_start, out.ar_end);
+            hipLaunchKernelGGL(k_timeline_pack<1>, dim3(pb), dim3(256), 0, st, ca, events->status, events->num_candidates, nn,
+                               out.sel, ws.bin_count, ws.key, out.ar_start, out.ar_end);
+            hipLaunchKernelGGL(k_timeline, dim3((unsigned)nn), dim3(kWave), 0, st, co, cl_dev(*cluster), ca, ws,
+                               events->status, events->num_candidates, nn, ws.bin_count, ws.key, out);
+        }
     }
     if (cd->chunks) {          // interleaved candidates among the selected ones: one wavefront each
         Timer t(ctx, st, DISTSIM_K_TIMELINE_VIRTUAL);

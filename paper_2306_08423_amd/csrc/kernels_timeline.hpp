@@ -16,88 +16,116 @@ struct TimelineOut {
     int64_t* ar_end;            // [n][kMaxPP] end of its last one
 };
 
-// A row of the staging ring takes the entries of kTlFlush levels plus what the last flush left
-// behind because it did not fill an aligned group of kTlFlush entries (32 bytes).
-constexpr int kTlFlush = 4;              // levels between two flushes = entries per aligned write
-constexpr int kTlRing = 2 * kTlFlush;    // ring capacity per row
-constexpr int kTlRow = kTlRing + 1;      // padded: consecutive stages start in different LDS banks
-constexpr int kTlChunk = 16;             // selected candidates per workgroup (at most 64)
-constexpr int kTlWaves = 4;
-static_assert(kTlChunk <= kWave && kTlWaves >= 1, "one wavefront sorts a chunk; blocks are kTlWaves whole wavefronts");
+// Start times wait in LDS, per (kind, lane), until a 64-byte aligned run of their row of the output
+// is complete: a ring that takes what the last flush left behind (fewer than kTlRun entries) plus
+// the entries of the kTlRun levels up to the next flush (at most one task of a kind per level).
+constexpr int kTlRun = 8;                // entries per aligned run (64 bytes) = levels between two flushes
+constexpr int kTlRing = 2 * kTlRun;      // ring capacity per (kind, lane)
+constexpr int kTlRowPad = kTlRing + 1;   // padded: the rows of neighbouring lanes start in different LDS banks
 
 // Per-wavefront staging area.
-struct TlRowMeta { int64_t base, dur; };     // index of the row's entry 0 in start / end; task duration
+struct TlRowMeta { int64_t at, dur_cnt; };   // index in start / end of the first entry to write | its ring slot << 56; task duration (below 2^53) | entries to write << 56
 struct TlStage {
-    double ring[2][kWave][kTlRow];           // start times of the newest tasks, [kind][lane][micro-batch mod kTlRing]
+    double buf[2][kWave][kTlRowPad];     // [kind][lane][entry number modulo kTlRing]
     TlRowMeta meta[2][kWave];
-    int2 span[2][kWave];                     // entries [x, y) of the row that the running flush writes
 };
 
-// A workgroup takes kTlChunk consecutive entries of the selection, sorts them by the number of
-// lanes they need (64, 32, ... 1) and packs them into wave-items like simulate does, so that
-// candidates with few stages share a wavefront; its four wavefronts take the items in turn.
-// The sweep is the level sweep of kernels_simulate.hpp (same level functions, bit patterns and
-// task step) with one addition: after each step the lanes that ran a task put its start time
-// into an LDS ring, one row per (kind, lane).  A stage's tasks of one kind come in micro-batch
-// order, so what a row gains between two flushes is one run of consecutive micro-batches; every
-// kTlFlush levels the wavefront writes out, per row, the entries up to the last 32-byte boundary
-// of the output arrays (the rest waits for the next flush; the last flush writes everything),
-// kTlFlush lanes per row and 64 / kTlFlush rows per store: whole aligned sectors instead of one
-// partial cache line per lane.  The end time is the start plus the row's task duration.  The staging area belongs to one
-// wavefront, whose LDS instructions execute in order: between its writes and the reads by other
-// lanes only the compiler has to be kept from reordering (wavefront-scope fences).
-__global__ __launch_bounds__(kTlWaves * kWave) void k_timeline(CostsDev co, ClusterDev cl, CandDev ca, Workspace ws,
-                                                               const int32_t* __restrict__ status, int64_t C,
-                                                               int64_t n, TimelineOut out) {
-    __shared__ TlStage stage_mem[kTlWaves];
-    __shared__ int32_t order[kTlChunk];
-    __shared__ int32_t cls_start[kClasses + 1], cls_count[kClasses], item_start[kClasses + 1];
-    const int lane = lane_id(), wave = threadIdx.x / kWave;
-    const int64_t q0 = (int64_t)blockIdx.x * kTlChunk;
-    const int L = co.L;
+// Width class of selection entry q for the level-sweep dump (0: 64 lanes ... 6: one lane), -1 when the
+// entry gets no dump from k_timeline: index outside the list, candidate not OK, or a schedule that
+// has a dump kernel of its own.
+__device__ __forceinline__ int timeline_class(const CandDev& ca, const int32_t* __restrict__ status, int64_t C, int64_t c) {
+    if (c < 0 || c >= C || status[c] != 0 || ca.schedule[c] >= 3) return -1;
+    const int pp = ca.pp[c];
+    int sh = 0;
+    while ((1 << sh) < pp) sh++;
+    return 6 - sh;
+}
 
-    // all-reduce windows default to "none"
-    for (int i = threadIdx.x; i < kTlChunk * kMaxPP; i += blockDim.x) {
-        const int64_t q = q0 + i / kMaxPP;
-        if (q < n) { out.ar_start[q * kMaxPP + i % kMaxPP] = -1; out.ar_end[q * kMaxPP + i % kMaxPP] = -1; }
-    }
-    // counting sort of the chunk by width class (first wavefront)
-    if (wave == 0) {
-        const int64_t q = q0 + lane;
-        int k = -1;
-        if (lane < kTlChunk && q < n) {
-            const int64_t c = out.sel[q];
-            if (c >= 0 && c < C && status[c] == 0 && ca.schedule[c] < 3) {       // the interleaved schedule has a dump of its own, explicit ones none
-                const int pp = ca.pp[c];
-                int sh = 0;
-                while ((1 << sh) < pp) sh++;
-                k = 6 - sh;
-            }
+// Packing of the selection into wave-items, over the whole selection: a counting sort by width
+// class (two passes over the selection), so that the candidates of few stages share wavefronts
+// whatever their place in the selection, and every item becomes a wavefront of its own.  Counters:
+// cnt[0..6] entries per class, cnt[8..14] the scatter pass's cursors.
+constexpr int kTlCounters = 16;
+__global__ __launch_bounds__(64) void k_timeline_clear(int32_t* __restrict__ cnt) {
+    if (threadIdx.x < kTlCounters) cnt[threadIdx.x] = 0;
+}
+
+// PASS 0: counts the entries of every class and sets all all-reduce windows of the selection to
+// "none".  PASS 1: hands every entry its place among the entries of its class (a block adds its
+// own counts to the cursors once per class) and writes the entry's number there.
+template <int PASS>
+__global__ __launch_bounds__(256) void k_timeline_pack(CandDev ca, const int32_t* __restrict__ status, int64_t C, int64_t n,
+                                                       const int64_t* __restrict__ sel, int32_t* __restrict__ cnt,
+                                                       int32_t* __restrict__ sorted, int64_t* __restrict__ ar_start,
+                                                       int64_t* __restrict__ ar_end) {
+    __shared__ int32_t hist[kClasses], base[kClasses];
+    if (threadIdx.x < kClasses) hist[threadIdx.x] = 0;
+    __syncthreads();
+    const int64_t q = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int k = q < n ? timeline_class(ca, status, C, sel[q]) : -1;
+    int rank = 0;
+    if (k >= 0) rank = atomicAdd(&hist[k], 1);
+    if (PASS == 0) {
+        const int64_t q_first = (int64_t)blockIdx.x * blockDim.x;
+        for (int i = threadIdx.x; i < (int)blockDim.x * kMaxPP; i += blockDim.x) {
+            const int64_t e = q_first * kMaxPP + i;
+            if (e < n * kMaxPP) { ar_start[e] = -1; ar_end[e] = -1; }
         }
-        int at = 0, items = 0;
-        for (int kk = 0; kk < kClasses; kk++) {
-            const uint64_t b = __builtin_amdgcn_ballot_w64(k == kk);
-            const int cnt = __popcll(b);
-            if (k == kk) order[at + __popcll(b & ((1ull << lane) - 1))] = lane;
-            if (lane == 0) { cls_start[kk] = at; cls_count[kk] = cnt; item_start[kk] = items; }
-            at += cnt;
-            items += (cnt + (1 << kk) - 1) >> kk;
-        }
-        if (lane == 0) { cls_start[kClasses] = at; item_start[kClasses] = items; }
     }
     __syncthreads();
+    if (threadIdx.x < kClasses && hist[threadIdx.x] > 0)
+        base[threadIdx.x] = atomicAdd(&cnt[(PASS == 0 ? 0 : 8) + threadIdx.x], hist[threadIdx.x]);
+    if (PASS == 0) return;
+    __syncthreads();
+    if (k >= 0) {
+        int start = 0;                                   // entries of the wider classes come first
+        for (int i = 0; i < k; i++) start += cnt[i];
+        sorted[start + base[k] + rank] = (int32_t)q;
+    }
+}
 
-    TlStage& sm = stage_mem[wave];
-    const double ninf = -__builtin_huge_val();
+// One wavefront per wave-item of the packed selection (64 >> k entries of class k, 1 << (6 - k)
+// lanes each), widest class -- the longest sweeps -- first.
+// The sweep is the level sweep of kernels_simulate.hpp (same level functions, bit patterns and
+// task step) with one addition: after each step the lanes that ran a task put its start time
+// into their row of the staging area.  A stage's tasks of one kind come in micro-batch order and
+// their entries are consecutive in the output ([kind][stage][micro-batch]).  Every kTlRun levels the
+// wavefront writes out, per row, the entries up to the last 64-byte boundary of the output arrays
+// (the rest waits for the next flush; the last flush writes everything), with the lanes regrouped:
+// four neighbouring lanes take one row, two entries each, so that one store instruction writes 16
+// rows and the four lanes of a row write one whole aligned 64-byte run (one full-width request to
+// memory instead of one per lane); end = start + the row's task duration.  The staging area
+// belongs to one wavefront, whose LDS instructions execute in order: between its writes and the
+// reads by other lanes only the compiler has to be kept from reordering (wavefront-scope fences).
+__global__ __launch_bounds__(kWave) void k_timeline(CostsDev co, ClusterDev cl, CandDev ca, Workspace ws,
+                                                    const int32_t* __restrict__ status, int64_t C, int64_t n,
+                                                    const int32_t* __restrict__ cnt, const int32_t* __restrict__ sorted,
+                                                    TimelineOut out) {
+    __shared__ TlStage stage_mem;
+    const int lane = lane_id();
+    const int L = co.L;
+    // class and item ranges from the counts (wave-uniform)
+    int cls_start[kClasses + 1], item_start[kClasses + 1];
+    cls_start[0] = 0; item_start[0] = 0;
+#pragma unroll
+    for (int kk = 0; kk < kClasses; kk++) {
+        const int c_k = cnt[kk];
+        cls_start[kk + 1] = cls_start[kk] + c_k;
+        item_start[kk + 1] = item_start[kk] + ((c_k + (1 << kk) - 1) >> kk);
+    }
     const int total_items = item_start[kClasses];
-    for (int w = wave; w < total_items; w += kTlWaves) {
-        int k = 0;
-        while (w >= item_start[k + 1]) k++;
+    TlStage& sm = stage_mem;
+    const double ninf = -__builtin_huge_val();
+    for (int w = blockIdx.x; w < total_items; w += gridDim.x) {
+        int k = 0, first_item = 0, first_entry = 0, class_entries = 0;
+#pragma unroll
+        for (int kk = 0; kk < kClasses; kk++)
+            if (w >= item_start[kk]) { k = kk; first_item = item_start[kk]; first_entry = cls_start[kk]; class_entries = cls_start[kk + 1] - cls_start[kk]; }
         const int sh = 6 - k, width = 1 << sh;
         const int g = lane >> sh, s = lane & (width - 1);
-        const int slot = ((w - item_start[k]) << k) + g;          // position inside the class
-        const bool have = slot < cls_count[k];
-        const int64_t q = q0 + (have ? order[cls_start[k] + slot] : 0);
+        const int slot = ((w - first_item) << k) + g;             // position inside the class
+        const bool have = slot < class_entries;
+        const int64_t q = have ? sorted[first_entry + slot] : 0;
         const int64_t c = have ? out.sel[q] : 0;
         int pp = 0, m = 0, dp = 1, tp = 1, sched = 0;
         int64_t poff = -1;
@@ -122,8 +150,6 @@ __global__ __launch_bounds__(kTlWaves * kWave) void k_timeline(CostsDev co, Clus
         if (!(act && s + 1 < pp)) pbR = ninf;
         const int64_t off = act ? out.task_off[q] : 0;
         const int64_t baseF = off + (int64_t)s * m, baseB = off + ((int64_t)pp + s) * m;   // rows [kind][stage][0]
-        sm.meta[0][lane] = TlRowMeta{baseF, Fd_i};
-        sm.meta[1][lane] = TlRowMeta{baseB, Bd_i};
 
         // level windows of this lane on x = level - s (see kernels_simulate.hpp)
         int f1hi, f2lo = 1, f2hi = 0, blo, bhi;
@@ -141,7 +167,7 @@ __global__ __launch_bounds__(kTlWaves * kWave) void k_timeline(CostsDev co, Clus
         double linkF = 0.0, linkB = 0.0;                      // p2p_blocking = 2: arrival of the lane's latest sends
         const double sendF = (double)r.PF, sendB = (double)r.PB;
         const bool hasL = act && s > 0, hasR = act && s + 1 < pp;
-        int nF = 0, nB = 0, fF = 0, fB = 0;                   // tasks run / written out, per kind
+        int nF = 0, nB = 0, cF = 0, cB = 0;                   // tasks written out / staged since the last flush, per kind
         uint64_t kmask = 0, kmask2 = 0;
         for (int l0 = 0; l0 < nlev; l0 += 32) {
             const int x0 = l0 - s;
@@ -184,48 +210,53 @@ __global__ __launch_bounds__(kTlWaves * kWave) void k_timeline(CostsDev co, Clus
                     DISTSIM_STEP1(PBb, own, tr, pbR, Bd);
                     ranB = (kmask >> lane) & 1; tB = tr;
                 }
-                if (ranF) { sm.ring[0][lane][nF & (kTlRing - 1)] = tF; nF++; }
-                if (ranB) { sm.ring[1][lane][nB & (kTlRing - 1)] = tB; nB++; }
+                if (ranF) { sm.buf[0][lane][(nF + cF) & (kTlRing - 1)] = tF; cF++; }
+                if (ranB) { sm.buf[1][lane][(nB + cB) & (kTlRing - 1)] = tB; cB++; }
                 const bool last = l0 + kk == nlev - 1;
-                if ((kk & (kTlFlush - 1)) != kTlFlush - 1 && !last) continue;
-                // flush: per row the entries [flushed, upto), upto = done rounded down to a sector
-                // boundary of the output (done itself in the last flush, which may take two rounds)
-                constexpr int kGroups = kTlFlush, kRowsPer = kWave / kTlFlush;   // stores per kind, rows per store
+                if ((kk & (kTlRun - 1)) != kTlRun - 1 && !last) continue;
+                // flush: per kind and row the staged entries up to the last 64-byte boundary of the
+                // output (all of them in the last flush, which may take two rounds)
+                for (int kind = 0; kind < 2; kind++)
                 for (int round = 0; round < (last ? 2 : 1); round++) {
-                    int upF = last ? nF : nF - (int)((baseF + nF) & (kTlFlush - 1));
-                    int upB = last ? nB : nB - (int)((baseB + nB) & (kTlFlush - 1));
-                    if (upF > fF + kTlFlush) upF = fF + kTlFlush;
-                    if (upB > fB + kTlFlush) upB = fB + kTlFlush;
-                    sm.span[0][lane] = make_int2(fF, upF);
-                    sm.span[1][lane] = make_int2(fB, upB);
+                    const int64_t at = kind ? baseB + nB : baseF + nF;
+                    const int staged = kind ? cB : cF;
+                    int wr = last ? staged : staged - (int)((at + staged) & (kTlRun - 1));
+                    wr = wr < 0 ? 0 : (wr > kTlRun ? kTlRun : wr);
+                    if (__builtin_amdgcn_ballot_w64(wr > 0) == 0) continue;
+                    const int slot0 = (kind ? nB : nF) & (kTlRing - 1);
+                    sm.meta[kind][lane] = TlRowMeta{at | ((int64_t)slot0 << 56), (kind ? Bd_i : Fd_i) | ((int64_t)wr << 56)};
                     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-                    const int rsub = lane / kTlFlush, e = lane & (kTlFlush - 1);
-                    for (int kind = 0; kind < 2; kind++) {
-                        if (__builtin_amdgcn_ballot_w64(kind ? upB > fB : upF > fF) == 0) continue;
-                        // all LDS reads of the kGroups stores first, then the stores
-                        int2 sp[kGroups];
-                        TlRowMeta mt[kGroups];
-                        double val[kGroups];
+                    constexpr int kLanesPerRow = kTlRun / 2, kRowsPer = kWave / kLanesPerRow;      // 4 lanes x 2 entries; 16 rows per store
+                    constexpr int kStores = kWave / kRowsPer;
+                    const int rsub = lane / kLanesPerRow, e = 2 * (lane % kLanesPerRow);
+                    // all LDS reads of the four stores first, then the stores
+                    TlRowMeta mt[kStores];
+                    double v0[kStores], v1[kStores];
 #pragma unroll
-                        for (int gi = 0; gi < kGroups; gi++) {
-                            sp[gi] = sm.span[kind][gi * kRowsPer + rsub];
-                            mt[gi] = sm.meta[kind][gi * kRowsPer + rsub];
-                        }
+                    for (int gi = 0; gi < kStores; gi++) mt[gi] = sm.meta[kind][gi * kRowsPer + rsub];
 #pragma unroll
-                        for (int gi = 0; gi < kGroups; gi++)
-                            val[gi] = sm.ring[kind][gi * kRowsPer + rsub][(sp[gi].x + e) & (kTlRing - 1)];
+                    for (int gi = 0; gi < kStores; gi++) {
+                        const int r = gi * kRowsPer + rsub, sl = (int)(mt[gi].at >> 56) + e;
+                        v0[gi] = sm.buf[kind][r][sl & (kTlRing - 1)];
+                        v1[gi] = sm.buf[kind][r][(sl + 1) & (kTlRing - 1)];
+                    }
 #pragma unroll
-                        for (int gi = 0; gi < kGroups; gi++) {
-                            const int j = sp[gi].x + e;
-                            if (j < sp[gi].y) {
-                                const int64_t t0 = double_to_i64(val[gi]);
-                                out.start[mt[gi].base + j] = t0;
-                                out.end[mt[gi].base + j] = t0 + mt[gi].dur;
+                    for (int gi = 0; gi < kStores; gi++) {
+                        const int n_row = (int)(mt[gi].dur_cnt >> 56);
+                        const int64_t dur = mt[gi].dur_cnt & (((int64_t)1 << 56) - 1);
+                        if (e < n_row) {
+                            const int64_t a = double_to_i64(v0[gi]), b = double_to_i64(v1[gi]);
+                            const int64_t idx = (mt[gi].at & (((int64_t)1 << 56) - 1)) + e;
+                            if (e + 1 < n_row) {
+                                *reinterpret_cast<longlong2*>(out.start + idx) = longlong2{a, b};
+                                *reinterpret_cast<longlong2*>(out.end + idx) = longlong2{a + dur, b + dur};
+                            } else {
+                                out.start[idx] = a;
+                                out.end[idx] = a + dur;
                             }
                         }
                     }
-                    if (upF > fF) fF = upF;
-                    if (upB > fB) fB = upB;
+                    if (kind) { nB += wr; cB -= wr; } else { nF += wr; cF -= wr; }
                     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
                 }
             }
