@@ -61,8 +61,8 @@ extern "C" {
                                   chunks[c] model chunks; virtual stage k = chunk * pp + device
                                   owns the k-th of pp * chunks parts of the layers (part_pool
                                   then holds pp * chunks + 1 boundaries).  Needs m % pp == 0,
-                                  pp * chunks <= L (more than 64 virtual stages, or p2p_blocking
-                                  == 2, is DISTSIM_ST_UNSUPPORTED).  Forward slot i
+                                  pp * chunks <= L (more than 64 virtual stages is
+                                  DISTSIM_ST_UNSUPPORTED).  Forward slot i
                                   of a device: chunk (i mod (pp chunks)) / pp, micro-batch
                                   (i / (pp chunks)) pp + i mod pp; backward slot i: the mirrored
                                   chunk.  Device d runs 2 (pp-d-1) + (chunks-1) pp forwards,
@@ -91,9 +91,9 @@ extern "C" {
                                   all-reduce per device after its list, over the bytes of the parts of
                                   all its stages.  pp and m must equal the candidate's.  A schedule that
                                   cannot be run to its end is invalid, as is a malformed block; one with
-                                  S > 64, nparts > 64, S * m > DISTSIM_MAX_SLOTS or under p2p_blocking ==
-                                  2 is DISTSIM_ST_UNSUPPORTED.  Per-stage outputs are per device; no
-                                  stage table.                                                     */
+                                  S > 64, nparts > 64 or S * m > DISTSIM_MAX_SLOTS is
+                                  DISTSIM_ST_UNSUPPORTED.  Per-stage outputs are per device; no stage
+                                  table.                                                           */
 #define DISTSIM_MAX_SLOTS 2048 /* (virtual stage, micro-batch) pairs of an explicit schedule       */
 #define DISTSIM_1F1B_ASYNC 2   /* asynchronous pipeline (Sec. 7, discussion of new algorithms):
                                   the Dapple order without the global synchronisation event, i.e.
@@ -110,8 +110,7 @@ extern "C" {
 #define DISTSIM_ST_UNSUPPORTED 4 /* passes every check that takes O(1) per candidate, but lies beyond
                                   what the kernels of this library simulate: m > DISTSIM_MAX_M; an
                                   interleaved candidate with pp * chunks > 64; an explicit schedule
-                                  with S > 64, nparts > 64 or S * m > DISTSIM_MAX_SLOTS; p2p_blocking
-                                  == 2 with an interleaved or explicit schedule.  Not a statement
+                                  with S > 64, nparts > 64 or S * m > DISTSIM_MAX_SLOTS.  Not a statement
                                   about the strategy: the method itself has no such bounds.  Treated
                                   like an invalid candidate by every call (batch_ns = INT64_MAX).  */
 
@@ -177,7 +176,10 @@ typedef struct {
                                         boundary carries one transfer per direction at a time, a
                                         send starts when its task has ended and the previous send
                                         over that link has arrived (slower kernel; an extension,
-                                        the paper models no contention)                          */
+                                        the paper models no contention).  A link is an ordered pair
+                                        (sending device, receiving device): with several virtual
+                                        stages per device (interleaved, explicit schedules) all
+                                        transfers between the same two devices share its queue    */
 } distsim_cluster;
 
 /* Candidate strategies "xM xP xD" (Sec. 5.1) x micro-batches x schedule x partition.

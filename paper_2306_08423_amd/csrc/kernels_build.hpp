@@ -162,7 +162,7 @@ __global__ __launch_bounds__(kDecodeBlock) void k_decode(CostsDev co, ClusterDev
             const int64_t vch = ca.chunks ? ca.chunks[c] : 0;      // no chunk counts: invalid
             parts = (int64_t)pp * vch;
             ok = vch >= 1 && parts <= co.L && m % pp == 0;
-            sup = sup && parts <= kMaxPP && cl.blocking != 2;
+            sup = sup && parts <= kMaxPP;
         }
         if (ok && sched == 4) {                  // explicit: the head of its schedule block; the kernel checks the rest
             const int64_t id = ca.chunks ? ca.chunks[c] : -1;
@@ -174,7 +174,7 @@ __global__ __launch_bounds__(kDecodeBlock) void k_decode(CostsDev co, ClusterDev
                     const int32_t* w = ca.schedule_words + o;
                     parts = w[3];
                     ok = w[0] == pp && w[2] == m && w[1] >= 1 && parts >= 1 && parts <= co.L && w[4] >= 1;
-                    sup = sup && w[1] <= kMaxPP && parts <= kMaxPP && (int64_t)w[1] * m <= kMaxSlots && cl.blocking != 2;
+                    sup = sup && w[1] <= kMaxPP && parts <= kMaxPP && (int64_t)w[1] * m <= kMaxSlots;
                 }
             }
         }

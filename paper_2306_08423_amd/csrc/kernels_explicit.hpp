@@ -23,6 +23,14 @@ struct ExplicitLds {
     int64_t comm[2][kMaxPP];                    // by virtual stage: communication inside a task and its outgoing p2p event
     int64_t grad[kMaxPP];                       // by virtual stage: gradient bytes of its part
     int32_t place[kMaxPP], prev[kMaxPP], next[kMaxPP], succ[kMaxPP];
+    // p2p_blocking = 2: a link is an ordered pair (sending device, receiving device) and carries one
+    // transfer at a time.  link[kind][k]: the queue that the send after a task of (kind, stage k)
+    // uses = the lowest-numbered edge between the same two devices (kind * kMaxPP + stage);
+    // link_free[queue]: arrival of the latest transfer on it.  Only the sending device's lane
+    // touches a queue.
+    int32_t link[2][kMaxPP];
+    double link_free[2 * kMaxPP];
+    double send_d[2][kMaxPP];                   // outgoing p2p events as doubles
 };
 constexpr double kNotListed = -1.0, kListed = -2.0;
 
@@ -150,9 +158,31 @@ __device__ __forceinline__ void explicit_candidate(const CostsDev& co, const Clu
     __syncthreads();
     if (isk) {
         const int nx = sm.next[lane];
-        sm.lat[0][lane] = prev >= 0 && cl.blocking != 1 ? (double)sm.send[0][prev] : 0.0;
-        sm.lat[1][lane] = nx >= 0 && cl.blocking != 1 ? (double)sm.send[1][nx] : 0.0;
+        // latency of the incoming edge; none when the send is part of the sender's task (1) or when
+        // the consumer reads the transfer's arrival time instead of the task's end (2)
+        sm.lat[0][lane] = prev >= 0 && cl.blocking == 0 ? (double)sm.send[0][prev] : 0.0;
+        sm.lat[1][lane] = nx >= 0 && cl.blocking == 0 ? (double)sm.send[1][nx] : 0.0;
+        sm.send_d[0][lane] = (double)sm.send[0][lane];
+        sm.send_d[1][lane] = (double)sm.send[1][lane];
+        if (cl.blocking == 2) {
+            // the queue of each of the stage's two outgoing edges: forward to next, backward to prev
+            const int dst_f = nx >= 0 ? sm.place[nx] : -1, dst_b = prev >= 0 ? sm.place[prev] : -1;
+            int qf = lane, qb = kMaxPP + lane;
+            for (int k2 = 0; k2 < S; k2++) {
+                if (sm.place[k2] != place) continue;
+                const int n2 = sm.next[k2], p2 = sm.prev[k2];
+                const int d2f = n2 >= 0 ? sm.place[n2] : -1, d2b = p2 >= 0 ? sm.place[p2] : -1;
+                if (d2f >= 0 && d2f == dst_f && k2 < qf) qf = k2;
+                if (d2f >= 0 && d2f == dst_b && k2 < qb) qb = k2;
+                if (d2b >= 0 && d2b == dst_f && kMaxPP + k2 < qf) qf = kMaxPP + k2;
+                if (d2b >= 0 && d2b == dst_b && kMaxPP + k2 < qb) qb = kMaxPP + k2;
+            }
+            sm.link[0][lane] = qf;
+            sm.link[1][lane] = qb;
+        }
     }
+    sm.link_free[lane] = 0.0;
+    sm.link_free[kMaxPP + lane] = 0.0;
     __syncthreads();
     if (DUMP) {                                                      // tasks that are not listed read -1
         for (int q = lane; q < 2 * slots; q += kWave) { dump.start[q] = -1; dump.end[q] = -1; }
@@ -182,12 +212,20 @@ __device__ __forceinline__ void explicit_candidate(const CostsDev& co, const Clu
             const double e = sm.end[turn ? 0 : kd][(link >= 0 ? link : k) * m + j];
             const double lat = sm.lat[kd][k], dur = sm.dur[kd][k];
             const int64_t cp = sm.comp[kd][k], cm = sm.comm[kd][k];
+            const bool sends = (kd ? pv : nx) >= 0;                  // the task is followed by a transfer
+            const int queue = sm.link[kd][k];
+            const double free_at = sm.link_free[cl.blocking == 2 && sends ? queue : 0], send = sm.send_d[kd][k];
             ran = !has_prod || e >= 0.0;
             if (ran) {                                               // a round's reads of end[] come before its writes
                 const double arrive = has_prod ? e + lat : 0.0;
                 const double start = arrive > own ? arrive : own;
                 own = start + dur;
-                sm.end[kd][k * m + j] = own;
+                double seen = own;                                   // what the consuming task reads
+                if (cl.blocking == 2 && sends) {                     // the transfer queues on its link
+                    seen = (own > free_at ? own : free_at) + send;
+                    sm.link_free[queue] = seen;
+                }
+                sm.end[kd][k * m + j] = seen;
                 if (DUMP) {
                     const int64_t q = ((int64_t)kd * S + k) * m + j;
                     dump.start[q] = double_to_i64(start);

@@ -127,6 +127,11 @@ __device__ __forceinline__ void virtual_groups(const CostsDev& co, const Cluster
     int rF = 0, cF = 0, rB = 0, cB = 0;
     int jF0 = 0, jB0 = 0;
     double own = 0.0;
+    // p2p_blocking = 2: a link is an ordered pair (sending device, receiving device) and carries one
+    // transfer at a time.  A device sends forwards to the device after it and backwards to the one
+    // before it (both modulo pp): two queues, which are one and the same for pp <= 2.
+    double link_f = 0.0, link_b = 0.0;
+    const bool one_queue = pp <= 2;
     const int max_rounds = wave_max_i32(act ? 4 * n + 8 * pp + 64 : 0);
     // Per direction: the producer of a slot is the same slot on the device before (in the
     // direction), or, on the direction's first device, the slot pp earlier on its last device; the
@@ -156,6 +161,8 @@ __device__ __forceinline__ void virtual_groups(const CostsDev& co, const Cluster
             const int done_src = sm.done[dir][src];
             const double prod_end = sm.ring[dir][src][si & (R - 1)];
             const double lat = sm.lat[dir][g][k], dur = sm.dur[dir][g][k];
+            const bool sends = fwd ? k + 1 < S : k > 0;                // the task is followed by a transfer ...
+            const double send = sm.lat[dir][g][sends ? (fwd ? k + 1 : k - 1) : k];      // ... which is the consumer's edge
             const int done_next = sm.done[dir][fwd ? dR : dL];
             const int done_wrap = sm.done[dir][fwd ? dFirst : dLast];
             bool ok = !has_prod || done_src > si;
@@ -165,10 +172,18 @@ __device__ __forceinline__ void virtual_groups(const CostsDev& co, const Cluster
                 if (last && vch > 1 && !(done_wrap > i - R + pp)) ok = false;
             }
             if (ok) {
-                const double arrive = has_prod ? prod_end + lat : 0.0;
+                // with queues on the links the producer has stored the transfer's arrival time
+                const double arrive = has_prod ? prod_end + (cl.blocking == 2 ? 0.0 : lat) : 0.0;
                 const double t0 = arrive > own ? arrive : own;
                 own = t0 + dur;
-                sm.ring[dir][lane][i & (R - 1)] = own;
+                double seen = own;                                     // what the consuming task reads
+                if (cl.blocking == 2 && sends) {
+                    const bool q_f = fwd || one_queue;
+                    const double free_at = q_f ? link_f : link_b;
+                    seen = (own > free_at ? own : free_at) + send;
+                    if (q_f) link_f = seen; else link_b = seen;
+                }
+                sm.ring[dir][lane][i & (R - 1)] = seen;
                 const int j = fwd ? jF0 + rF : jB0 + rB;                        // micro-batch of the slot
                 if (fwd) {
                     iF++;

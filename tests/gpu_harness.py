@@ -93,12 +93,11 @@ def beyond_limits(w):
     ca = w.cand
     C = len(ca["pp"])
     pp, m, sc = ca["pp"].astype(np.int64), ca["m"].astype(np.int64), ca["schedule"]
-    blocking = int(w.cluster.get("p2p_blocking", 0))
     out = m > ds.binding.MAX_M
     ch = ca.get("chunks")
     if ch is not None:
         ch = ch.astype(np.int64)
-        out = out | ((sc == 3) & ((pp * ch > ds.binding.MAX_PP) | (blocking == 2)))
+        out = out | ((sc == 3) & (pp * ch > ds.binding.MAX_PP))
         off, words = ca.get("schedule_off"), ca.get("schedule_words")
         if off is not None and words is not None:
             n = len(off) - 1
@@ -110,7 +109,7 @@ def beyond_limits(w):
                 if o < 0 or e - o < 5 or e > len(words):
                     continue
                 S, nparts = int(words[o + 1]), int(words[o + 3])
-                if S > ds.binding.MAX_PP or nparts > ds.binding.MAX_PP or S * int(m[c]) > ds.binding.MAX_SLOTS or blocking == 2:
+                if S > ds.binding.MAX_PP or nparts > ds.binding.MAX_PP or S * int(m[c]) > ds.binding.MAX_SLOTS:
                     out[c] = True
     return out
 
