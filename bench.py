@@ -242,6 +242,23 @@ def copy_bandwidth(torch, device, nbytes=1 << 30, reps=10):
     return 2 * nbytes / (ms / 1e3) / 1e9
 
 
+def fill_bandwidth(torch, device, nbytes=1 << 30, reps=10):
+    """A plain fill of nbytes of device memory, timed with HIP events: written bytes per second in
+    GB/s, the rate this machine reaches for a kernel that only writes (the timeline dump is one)."""
+    dst = torch.empty(nbytes // 8, dtype=torch.int64, device=device)
+    dst.fill_(1)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        dst.fill_(1)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / reps
+    del dst
+    return nbytes / (ms / 1e3) / 1e9
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -264,8 +281,9 @@ def main() -> int:
                          "HBM to bound it (0 = skip)")
     ap.add_argument("--no-graph", action="store_true", help="skip the HIP-graph replay of the step")
     ap.add_argument("--no-copy", action="store_true",
-                    help="skip the timed 1 GiB device-to-device copy (the HBM bandwidth this box reaches; its "
-                         "known traffic also scales the HBM counters of a profiler run)")
+                    help="skip the timed 1 GiB device-to-device copy and 1 GiB fill (the HBM bandwidth this box reaches "
+                         "for read + write and for writes alone; the copy's known traffic also scales the HBM "
+                         "counters of a profiler run)")
     ap.add_argument("--second", default="gpt96",
                     help="also time the three calls on this workload, the one with the most work per candidate "
                          "(none = skip)")
@@ -290,6 +308,7 @@ def main() -> int:
                                                        table=not args.no_stage_table)
     S, dt, kt = res["S"], res["dt"], res["kt"]
     copy_gbs = copy_bandwidth(torch, ctx.device) if not args.no_copy else None
+    fill_gbs = fill_bandwidth(torch, ctx.device) if not args.no_copy else None
 
     # the same step recorded once into a HIP graph and replayed (the calls allocate nothing and never
     # synchronise): what a caller in a tight loop pays when launch overhead matters
@@ -346,6 +365,8 @@ def main() -> int:
                     "stage_tasks_per_s": int(off[-1]) / tl_s, "bound": "hbm",
                     "achieved": tl_bytes / tl_s / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                     "frac": tl_bytes / tl_s / 1e9 / HBM_PEAK_GBS}
+        if fill_gbs:
+            timeline["frac_of_measured_fill"] = tl_bytes / tl_s / 1e9 / fill_gbs
         bb_s = bb_ms / max(bb_n, 1) / 1e3
         bb_bytes = int(off[-1]) * 24                       # start and predecessor's end in, idle time out
         timeline["bubbles"] = {"ms": bb_s * 1e3, "bound": "hbm", "achieved": bb_bytes / bb_s / 1e9,
@@ -482,6 +503,7 @@ def main() -> int:
                           "(k_simulate_gpipe on a stream of the library's context); the other entries are single kernels",
         "roofline": roofline, "roofline_alu": roofline_alu,
         "hbm_copy_measured_GBs": copy_gbs,
+        "hbm_fill_measured_GBs": fill_gbs,
         "second_workload": second,
         "graph_replay": graph, "timeline": timeline, "ingest": ingest, "search": search, "variants": variants,
         "cpu_baseline": cpu_baseline, "parity": parity,

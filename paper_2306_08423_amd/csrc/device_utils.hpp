@@ -112,6 +112,11 @@ __device__ __forceinline__ int64_t double_to_i64(double d) {
     return (int64_t)(((uint64_t)hi << 32) | lo);
 }
 
+// The same for an integer of [0, 2^52): adding 2^52 puts the integer into the low mantissa bits.
+__device__ __forceinline__ int64_t small_double_to_i64(double d) {
+    return __double_as_longlong(d + 4503599627370496.0) & 0xfffffffffffffll;
+}
+
 // Boundary s of the uniform partition of L layers into `parts` parts: floor(s L / parts) for
 // 0 <= s <= parts <= 64 and L <= 255.  The product is below 2^15, so the fp32 quotient (reciprocal
 // and product, a few units in the last place) is off by at most one; the remainder corrects it.

@@ -405,8 +405,8 @@ __device__ __forceinline__ bool stage_out_of_range(int64_t per_stage, int m, int
     // lane, so does m * (sum of the shares); only otherwise the sum itself is formed
     const uint64_t v = (uint64_t)per_stage;
     const bool small = (v >> 32) == 0 && (uint64_t)(uint32_t)v * (uint32_t)(m * width) < (1ull << 53);
-    uint64_t t1 = 0;
-    if (__builtin_amdgcn_ballot_w64(!small) != 0) t1 = (uint64_t)group_sum(per_stage, width);
+    if (__builtin_amdgcn_ballot_w64(!small) == 0) return false;     // the usual case, decided for the whole wavefront
+    const uint64_t t1 = (uint64_t)group_sum(per_stage, width);
     return __umul64hi(t1, (uint64_t)m) != 0 || t1 * (uint64_t)m >= (1ull << 53);
 }
 
@@ -458,7 +458,10 @@ __device__ __forceinline__ int stage_sums(const ClusterDev& cl, const Workspace&
     }
     const bool range = stage_out_of_range(r.FT + r.BT + r.PF + r.PB, m, width);
     const int drop = bad ? 1 : (range ? 2 : 0);
-    if (drop) r = StageSums{0, 0, 0, 0, 0, 0};
+    // rare: the branch is taken by the whole wavefront or not at all
+    if (__builtin_amdgcn_ballot_w64(drop != 0) != 0) {
+        if (drop) r = StageSums{0, 0, 0, 0, 0, 0};
+    }
     return drop;
 }
 

@@ -572,7 +572,8 @@ __device__ __forceinline__ void simulate_items(const ClusterDev& cl, const CandD
         if (live && s == 0) {
             const int64_t cc = park.cand[u][slot];
             out.batch_ns[cc] = batch;
-            ev.num_events[cc] = 2ll * mv[u] * ppv[u] + 2ll * mv[u] * (ppv[u] - 1) + nar;
+            // m (2 pp + 2 (pp - 1)) stage-tasks and p2p events: below 2^24 for m <= 2^16, pp <= 64
+            ev.num_events[cc] = (int64_t)(2 * mv[u] * (2 * ppv[u] - 1)) + nar;
         }
     }
 }

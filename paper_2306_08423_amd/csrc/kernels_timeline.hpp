@@ -21,12 +21,12 @@ struct TimelineOut {
 // the entries of the kTlRun levels up to the next flush (at most one task of a kind per level).
 constexpr int kTlRun = 8;                // entries per aligned run (64 bytes) = levels between two flushes
 constexpr int kTlRing = 2 * kTlRun;      // ring capacity per (kind, lane)
-constexpr int kTlRowPad = kTlRing + 1;   // padded: the rows of neighbouring lanes start in different LDS banks
+constexpr int kTlRowPad = kTlRing + 2;   // padded: the rows of neighbouring lanes start in different LDS banks, every row 16-byte aligned
 
 // Per-wavefront staging area.
-struct TlRowMeta { int64_t at, dur_cnt; };   // index in start / end of the first entry to write | its ring slot << 56; task duration (below 2^53) | entries to write << 56
+struct TlRowMeta { int64_t at, dur_cnt; };   // index in start / end of the first entry to write; task duration (below 2^53) | entries to write << 56
 struct TlStage {
-    double buf[2][kWave][kTlRowPad];     // [kind][lane][entry number modulo kTlRing]
+    alignas(16) double buf[2][kWave][kTlRowPad];     // [kind][lane][index of the entry in the output modulo kTlRing]
     TlRowMeta meta[2][kWave];
 };
 
@@ -168,6 +168,7 @@ __global__ __launch_bounds__(kWave) void k_timeline(CostsDev co, ClusterDev cl, 
         const double sendF = (double)r.PF, sendB = (double)r.PB;
         const bool hasL = act && s > 0, hasR = act && s + 1 < pp;
         int nF = 0, nB = 0, cF = 0, cB = 0;                   // tasks written out / staged since the last flush, per kind
+        const int ringF = (int)baseF & (kTlRing - 1), ringB = (int)baseB & (kTlRing - 1);      // ring slot of the row's first entry
         uint64_t kmask = 0, kmask2 = 0;
         for (int l0 = 0; l0 < nlev; l0 += 32) {
             const int x0 = l0 - s;
@@ -210,21 +211,26 @@ __global__ __launch_bounds__(kWave) void k_timeline(CostsDev co, ClusterDev cl, 
                     DISTSIM_STEP1(PBb, own, tr, pbR, Bd);
                     ranB = (kmask >> lane) & 1; tB = tr;
                 }
-                if (ranF) { sm.buf[0][lane][(nF + cF) & (kTlRing - 1)] = tF; cF++; }
-                if (ranB) { sm.buf[1][lane][(nB + cB) & (kTlRing - 1)] = tB; cB++; }
+                // an entry's ring slot is its index in the output modulo the ring: runs that are aligned
+                // in the output are aligned in the ring too
+                if (ranF) { sm.buf[0][lane][(ringF + nF + cF) & (kTlRing - 1)] = tF; cF++; }
+                if (ranB) { sm.buf[1][lane][(ringB + nB + cB) & (kTlRing - 1)] = tB; cB++; }
                 const bool last = l0 + kk == nlev - 1;
                 if ((kk & (kTlRun - 1)) != kTlRun - 1 && !last) continue;
                 // flush: per kind and row the staged entries up to the last 64-byte boundary of the
                 // output (all of them in the last flush, which may take two rounds)
+                // every time of the item so far is at most some lane's `own`: below 2^52 they convert with one addition
+                const bool small = __builtin_amdgcn_ballot_w64(own >= 4503599627370496.0) == 0;
                 for (int kind = 0; kind < 2; kind++)
                 for (int round = 0; round < (last ? 2 : 1); round++) {
                     const int64_t at = kind ? baseB + nB : baseF + nF;
                     const int staged = kind ? cB : cF;
-                    int wr = last ? staged : staged - (int)((at + staged) & (kTlRun - 1));
+                    int wr = last ? staged : staged - (((int)at + staged) & (kTlRun - 1));
                     wr = wr < 0 ? 0 : (wr > kTlRun ? kTlRun : wr);
                     if (__builtin_amdgcn_ballot_w64(wr > 0) == 0) continue;
-                    const int slot0 = (kind ? nB : nF) & (kTlRing - 1);
-                    sm.meta[kind][lane] = TlRowMeta{at | ((int64_t)slot0 << 56), (kind ? Bd_i : Fd_i) | ((int64_t)wr << 56)};
+                    // whole aligned runs only (the usual flush): pairs of entries are 16-byte aligned in the ring and in the output
+                    const bool whole = __builtin_amdgcn_ballot_w64(wr > 0 && (wr != kTlRun || ((int)at & (kTlRun - 1)) != 0)) == 0;
+                    sm.meta[kind][lane] = TlRowMeta{at, (kind ? Bd_i : Fd_i) | ((int64_t)wr << 56)};
                     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
                     constexpr int kLanesPerRow = kTlRun / 2, kRowsPer = kWave / kLanesPerRow;      // 4 lanes x 2 entries; 16 rows per store
                     constexpr int kStores = kWave / kRowsPer;
@@ -234,25 +240,44 @@ __global__ __launch_bounds__(kWave) void k_timeline(CostsDev co, ClusterDev cl, 
                     double v0[kStores], v1[kStores];
 #pragma unroll
                     for (int gi = 0; gi < kStores; gi++) mt[gi] = sm.meta[kind][gi * kRowsPer + rsub];
+                    if (whole && small) {
 #pragma unroll
-                    for (int gi = 0; gi < kStores; gi++) {
-                        const int r = gi * kRowsPer + rsub, sl = (int)(mt[gi].at >> 56) + e;
-                        v0[gi] = sm.buf[kind][r][sl & (kTlRing - 1)];
-                        v1[gi] = sm.buf[kind][r][(sl + 1) & (kTlRing - 1)];
-                    }
+                        for (int gi = 0; gi < kStores; gi++) {
+                            const int r = gi * kRowsPer + rsub, sl = ((int)mt[gi].at + e) & (kTlRing - 1);      // even
+                            const double2 v = *reinterpret_cast<const double2*>(&sm.buf[kind][r][sl]);
+                            v0[gi] = v.x; v1[gi] = v.y;
+                        }
 #pragma unroll
-                    for (int gi = 0; gi < kStores; gi++) {
-                        const int n_row = (int)(mt[gi].dur_cnt >> 56);
-                        const int64_t dur = mt[gi].dur_cnt & (((int64_t)1 << 56) - 1);
-                        if (e < n_row) {
-                            const int64_t a = double_to_i64(v0[gi]), b = double_to_i64(v1[gi]);
-                            const int64_t idx = (mt[gi].at & (((int64_t)1 << 56) - 1)) + e;
-                            if (e + 1 < n_row) {
+                        for (int gi = 0; gi < kStores; gi++) {
+                            if ((mt[gi].dur_cnt >> 56) != 0) {
+                                const int64_t dur = mt[gi].dur_cnt & (((int64_t)1 << 56) - 1);
+                                const int64_t a = small_double_to_i64(v0[gi]), b = small_double_to_i64(v1[gi]);
+                                const int64_t idx = mt[gi].at + e;
                                 *reinterpret_cast<longlong2*>(out.start + idx) = longlong2{a, b};
                                 *reinterpret_cast<longlong2*>(out.end + idx) = longlong2{a + dur, b + dur};
-                            } else {
-                                out.start[idx] = a;
-                                out.end[idx] = a + dur;
+                            }
+                        }
+                    } else {
+#pragma unroll
+                        for (int gi = 0; gi < kStores; gi++) {
+                            const int r = gi * kRowsPer + rsub, sl = (int)mt[gi].at + e;
+                            v0[gi] = sm.buf[kind][r][sl & (kTlRing - 1)];
+                            v1[gi] = sm.buf[kind][r][(sl + 1) & (kTlRing - 1)];
+                        }
+#pragma unroll
+                        for (int gi = 0; gi < kStores; gi++) {
+                            const int n_row = (int)(mt[gi].dur_cnt >> 56);
+                            const int64_t dur = mt[gi].dur_cnt & (((int64_t)1 << 56) - 1);
+                            if (e < n_row) {
+                                const int64_t a = double_to_i64(v0[gi]), b = double_to_i64(v1[gi]);
+                                const int64_t idx = mt[gi].at + e;
+                                if (e + 1 < n_row) {
+                                    *reinterpret_cast<longlong2*>(out.start + idx) = longlong2{a, b};
+                                    *reinterpret_cast<longlong2*>(out.end + idx) = longlong2{a + dur, b + dur};
+                                } else {
+                                    out.start[idx] = a;
+                                    out.end[idx] = a + dur;
+                                }
                             }
                         }
                     }
