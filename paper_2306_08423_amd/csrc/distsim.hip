@@ -342,8 +342,12 @@ int distsim_build_events(distsim_ctx* ctx, const distsim_costs* costs, const dis
         // also for C == 0: the first threads fill the order tables of the sweep kernels (their totals)
         Timer t(ctx, st, DISTSIM_K_SCATTER);
         const int64_t threads = C > ws.order_cap ? C : ws.order_cap;
+        // with a bucketed all-reduce: the classes whose stages hold 16 layers or more go first (their epilogues are long)
+        int first_whole = kClasses;
+        if (cluster->dp_bucket_bytes > 0)
+            for (int k = kClasses - 1; k >= 0 && ((int64_t)costs->L << k) >= 16 * kWave; k--) first_whole = k;
         hipLaunchKernelGGL(k_scatter, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st, ca, C, ws, ev,
-                           ctx->split_min_items);
+                           ctx->split_min_items, first_whole);
     }
     if (beside) HIP_TRY(hipStreamWaitEvent(st, ctx->join, 0));       // what follows on the caller's stream sees the tables
     if (C > 0) {

@@ -290,7 +290,12 @@ __device__ __forceinline__ void owned_range(const int64_t* __restrict__ hdr, int
 }
 
 // Entry q of both order tables (called by thread q of k_scatter, whose grid covers order_cap).
-__device__ __forceinline__ void pair_order_entry(const Workspace& ws, int32_t q, int64_t stage_cap, int64_t split_min_items) {
+// first_whole: the classes from this one on (the narrow ones) are taken first and whole, widest last;
+// kClasses = none.  With a bucketed all-reduce the epilogue of an item walks the layers of a stage,
+// so a short sweep of a stage that holds many layers is a long item all the same and must not wait
+// for the end of the launch.
+__device__ __forceinline__ void pair_order_entry(const Workspace& ws, int32_t q, int64_t stage_cap, int64_t split_min_items,
+                                                 int first_whole) {
     const int64_t* __restrict__ hdr = ws.hdr;
     int64_t W = hdr[H_NUM_ITEMS];                       // items that have room in the per-stage arrays
     if (W * kWave > stage_cap) W = stage_cap / kWave;
@@ -298,36 +303,53 @@ __device__ __forceinline__ void pair_order_entry(const Workspace& ws, int32_t q,
     for (int which = 0; which < 2; which++) {           // 0: k_simulate's pairs, 1: k_simulate_gpipe's
         const bool gpipe = which == 1;
         int32_t first[kClasses], own[kClasses], pairs[kClasses];
-        int32_t group_total = 0, total = 0;
+        int32_t group_total = 0, total = 0, whole_total = 0;
 #pragma unroll
         for (int k = 0; k < kClasses; k++) {
             owned_range(hdr, k, gpipe, split, W, first[k], own[k]);       // without the split k_simulate_gpipe owns nothing
             pairs[k] = (own[k] + 1) >> 1;
-            group_total += pairs[k] >> kOrderShift;
+            if (k >= first_whole) whole_total += pairs[k];
+            else group_total += pairs[k] >> kOrderShift;
             total += pairs[k];
         }
         if (q == 0) ws.hdr[H_PAIRS + which] = total;
         if (q >= total || q >= ws.order_cap) continue;
-        int32_t g = kOrderGroups - 1;
-        if (group_total > 0) {
-            g = q / group_total;
-            if (g > kOrderGroups - 1) g = kOrderGroups - 1;
-        }
-        const bool last = g == kOrderGroups - 1;
-        int32_t r = q - g * group_total;
         int32_t item = 0, has_two = 0;
         bool found = false;
+        if (q < whole_total) {
+            int32_t r = q;
 #pragma unroll
-        for (int k = 0; k < kClasses; k++) {
-            const int32_t per = pairs[k] >> kOrderShift;
-            const int32_t sz = last ? pairs[k] - g * per : per;
-            if (!found && r < sz) {
-                found = true;
-                const int32_t j = g * per + r;
-                item = (int32_t)hdr[H_ITEM_START + k] + first[k] + 2 * j;
-                has_two = 2 * j + 1 < own[k];
+            for (int k = kClasses - 1; k >= 0; k--) {
+                if (k < first_whole) continue;
+                if (!found && r < pairs[k]) {
+                    found = true;
+                    item = (int32_t)hdr[H_ITEM_START + k] + first[k] + 2 * r;
+                    has_two = 2 * r + 1 < own[k];
+                }
+                if (!found) r -= pairs[k];
             }
-            if (!found) r -= sz;
+        } else {
+            const int32_t q2 = q - whole_total;
+            int32_t g = kOrderGroups - 1;
+            if (group_total > 0) {
+                g = q2 / group_total;
+                if (g > kOrderGroups - 1) g = kOrderGroups - 1;
+            }
+            const bool last = g == kOrderGroups - 1;
+            int32_t r = q2 - g * group_total;
+#pragma unroll
+            for (int k = 0; k < kClasses; k++) {
+                if (k >= first_whole) continue;
+                const int32_t per = pairs[k] >> kOrderShift;
+                const int32_t sz = last ? pairs[k] - g * per : per;
+                if (!found && r < sz) {
+                    found = true;
+                    const int32_t j = g * per + r;
+                    item = (int32_t)hdr[H_ITEM_START + k] + first[k] + 2 * j;
+                    has_two = 2 * j + 1 < own[k];
+                }
+                if (!found) r -= sz;
+            }
         }
         ws.order[which][q] = item | (has_two ? (int32_t)0x80000000 : 0);
     }
@@ -336,9 +358,9 @@ __device__ __forceinline__ void pair_order_entry(const Workspace& ws, int32_t q,
 // Scatter candidates into visiting order and hand each its block of per-stage entries; the first
 // order_cap threads also fill the order tables of the sweep kernels.
 __global__ __launch_bounds__(256) void k_scatter(CandDev ca, int64_t C, Workspace ws, EventsDev ev,
-                                                 int64_t split_min_items) {
+                                                 int64_t split_min_items, int first_whole) {
     const int64_t c = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (c < ws.order_cap) pair_order_entry(ws, (int32_t)c, ev.stage_cap, split_min_items);
+    if (c < ws.order_cap) pair_order_entry(ws, (int32_t)c, ev.stage_cap, split_min_items, first_whole);
     if (c >= C) return;
     const int kv = ws.key[c];
     if (kv < 0) return;
