@@ -27,7 +27,8 @@
  *      of each device's list (Sec. 4.3, "Data Parallelism Modeling").  With a
  *      bucket size the gradient all-reduce is split into buckets that start as
  *      soon as the last micro-batch's backward has produced their bytes
- *      (extension; bucket = 0 gives the paper's single trailing event).
+ *      (extension; bucket = 0 gives the paper's single trailing event; the interleaved and
+ *      the explicit schedules fill the buckets per device, see there).
  *      Schedule 2 is the asynchronous pipeline of the paper's discussion of new
  *      algorithms (Sec. 7): the Dapple order minus the global synchronisation
  *      event, i.e. no gradient all-reduce event is appended.
@@ -426,8 +427,12 @@ static void simulate_one(const costs_t *co, const cluster_t *cl,
  * A forward of virtual stage k needs the forward of k - 1 for that micro-batch (the edge from
  * the last device back to the first included), a backward the backward of k + 1; the last
  * virtual stage turns a micro-batch around on its own device.  One gradient all-reduce per device
- * over the bytes of all its chunks follows its last backward (buckets are not modelled for this
- * schedule).  With p2p_blocking == 2 a link is an ordered pair (sending device, receiving device)
+ * over the bytes of all its chunks follows its last backward.  With a bucket size (extension, as
+ * for the built-in schedules): a chunk's gradients are complete in its backward of the last
+ * micro-batch, layer by layer from its last layer to its first; the device fills its buckets in
+ * that order across its chunks, every full bucket is reduced at once, the events queue on the
+ * device's communication stream, and what is left after the device's last gradient goes as one more
+ * event.  With p2p_blocking == 2 a link is an ordered pair (sending device, receiving device)
  * and carries one transfer at a time, whatever chunks the transfers belong to.
  * Timeline arrays, if given, are [2][S][m] (virtual stage, not device).
  */
@@ -531,9 +536,14 @@ static void simulate_interleaved(const costs_t *co, const cluster_t *cl,
     int64_t next[64];
     uint8_t busy[64];
     int64_t cb[64], mb_[64];
-    for (int d = 0; d < pp; d++) { next[d] = 0; busy[d] = 0; cb[d] = 0; mb_[d] = 0; }
+    int64_t comm_free[64], acc[64], pend[64];     /* DP communication stream, open bucket bytes, gradients still to come */
+    for (int d = 0; d < pp; d++) {
+        next[d] = 0; busy[d] = 0; cb[d] = 0; mb_[d] = 0; comm_free[d] = 0; acc[d] = 0; pend[d] = 0;
+        for (int c = 0; c < vch; c++) pend[d] += bnd[c * pp + d + 1] - bnd[c * pp + d];
+    }
     int64_t nev = 0, now = 0;
     if (tl_ar) for (int d = 0; d < 2 * pp; d++) tl_ar[d] = -1;
+    const int64_t cap = cl->bucket;
 
 #define TRY_START_I(d_) do {                                                            \
         int d__ = (d_);                                                                 \
@@ -559,6 +569,8 @@ static void simulate_interleaved(const costs_t *co, const cluster_t *cl,
                         if (tp > 1) { t += ba[l]; mb_[d__] += ba[l]; }                  \
                         int64_t x = alltoall_ns(cl, dp, a2a[l]);                        \
                         t += x; mb_[d__] += x;                                          \
+                        if (j == m - 1 && cap > 0 && dp > 1)                            \
+                            heap_push(h, t, EV_GRAD_READY, k, j, l);                    \
                     }                                                                   \
                 }                                                                       \
                 if (cl->p2p_blocking == 1) {                                            \
@@ -607,7 +619,7 @@ static void simulate_interleaved(const costs_t *co, const cluster_t *cl,
                 heap_push(h, arrive, EV_ARRIVE_B, k - 1, j, 0);
                 mb_[d] += pb[k]; nev++;
             }
-            if (next[d] == per_dev && dp > 1) {       /* trailing gradient all-reduce of the device */
+            if (next[d] == per_dev && dp > 1 && cap == 0) {       /* trailing gradient all-reduce of the device */
                 int64_t G = 0;
                 for (int c = 0; c < vch; c++)
                     for (int l = bnd[c * pp + d]; l < bnd[c * pp + d + 1]; l++) G += grad[l];
@@ -629,6 +641,21 @@ static void simulate_interleaved(const costs_t *co, const cluster_t *cl,
             sc->arrB[(int64_t)k * m + e.mb] = 1;
             TRY_START_I(d);
             break;
+        case EV_GRAD_READY: {                        /* bucketed, overlapped gradient all-reduce of device d */
+            acc[d] += grad[e.layer];
+            pend[d]--;
+            while (acc[d] >= cap || (pend[d] == 0 && acc[d] > 0)) {
+                int64_t bytes = acc[d] >= cap ? cap : acc[d];
+                int64_t dd = allreduce_ns(cl, dp, bytes);
+                int64_t st = comm_free[d] > now ? comm_free[d] : now;
+                comm_free[d] = st + dd;
+                heap_push(h, comm_free[d], EV_AR_DONE, k, 0, 0);
+                mb_[d] += dd;
+                if (tl_ar) { if (tl_ar[d] < 0) tl_ar[d] = st; tl_ar[pp + d] = comm_free[d]; }
+                acc[d] -= bytes;
+            }
+            break;
+        }
         case EV_AR_DONE:
             nev++;
             break;
@@ -659,7 +686,12 @@ static void simulate_interleaved(const costs_t *co, const cluster_t *cl,
  * F(k, j) needs F(prev[k], j) and its p2p event; B(k, j) needs B(next[k], j) and its p2p event,
  * or, on a stage without successor, its own F(k, j).  A device runs its list in order; a task
  * starts when the device is free and its input has arrived.  One gradient all-reduce per device
- * after its list, over the bytes of the parts of all stages it holds.  A schedule that cannot be
+ * after its list, over the bytes of the parts of all stages it holds.  With a bucket size
+ * (extension): the gradients of a stage are complete in the last backward task of that stage on the
+ * device's list, layer by layer from the last layer of its part to the first; the device fills its
+ * buckets in that order, full buckets are reduced at once and queue on the device's communication
+ * stream, what is left after the device's last gradient goes as one more event; a stage without a
+ * backward task on the list produces no gradient.  A schedule that cannot be
  * run to its end (an input that never arrives) is invalid, as is any malformed block.  With
  * p2p_blocking == 2 a link is an ordered pair (sending device, receiving device) and carries one
  * transfer at a time.
@@ -696,7 +728,8 @@ static void simulate_explicit(const costs_t *co, const cluster_t *cl,
     int *bnd = (int *)malloc((size_t)(nparts + 1) * sizeof(int));
     int64_t *link_free = (int64_t *)calloc((size_t)pp * pp, sizeof(int64_t));   /* [sender][receiver]: free again at */
     uint8_t *seen = NULL;
-#define FREE_X() do { free(place); free(pf); free(bnd); free(link_free); free(seen); } while (0)
+    int64_t *last_bwd = NULL;
+#define FREE_X() do { free(place); free(pf); free(bnd); free(link_free); free(seen); free(last_bwd); } while (0)
     for (int k = 0; k < S; k++) next[k] = -1;
     for (int k = 0; k < S; k++) {
         place[k] = st[3 * k]; part[k] = st[3 * k + 1]; prev[k] = st[3 * k + 2];
@@ -767,9 +800,19 @@ static void simulate_explicit(const costs_t *co, const cluster_t *cl,
     int64_t nxt[64];
     uint8_t busy[64];
     int64_t cb[64], mb_[64];
-    for (int d = 0; d < pp; d++) { nxt[d] = dev_off[d]; busy[d] = 0; cb[d] = 0; mb_[d] = 0; }
+    int64_t comm_free[64], acc[64], pend[64];     /* DP communication stream, open bucket bytes, gradients still to come */
+    for (int d = 0; d < pp; d++) { nxt[d] = dev_off[d]; busy[d] = 0; cb[d] = 0; mb_[d] = 0; comm_free[d] = 0; acc[d] = 0; pend[d] = 0; }
     int64_t nev = 0, now = 0, ran = 0;
     if (tl_ar) for (int d = 0; d < 2 * pp; d++) tl_ar[d] = -1;
+    const int64_t cap = cl->bucket, ranks = (int64_t)dp * replicas;
+    /* by stage: the last backward task of the stage on its device's list, -1 = none */
+    last_bwd = (int64_t *)malloc((size_t)S * sizeof(int64_t));
+    for (int q = 0; q < S; q++) last_bwd[q] = -1;
+    for (int64_t i = 0; i < ntask; i++) {
+        uint32_t x = (uint32_t)tasks[i];
+        if (x >> 31) last_bwd[(x >> 16) & 0x7fff] = i;
+    }
+    for (int q = 0; q < S; q++) if (last_bwd[q] >= 0) pend[place[q]] += bnd[part[q] + 1] - bnd[part[q]];
 
 #define TRY_START_X(d_) do {                                                            \
         int d__ = (d_);                                                                 \
@@ -795,6 +838,8 @@ static void simulate_explicit(const costs_t *co, const cluster_t *cl,
                         if (tp > 1) { t += ba[l]; mb_[d__] += ba[l]; }                  \
                         int64_t y = alltoall_ns(cl, dp, a2a[l]);                        \
                         t += y; mb_[d__] += y;                                          \
+                        if (nxt[d__] == last_bwd[k] && cap > 0 && ranks > 1)            \
+                            heap_push(h, t, EV_GRAD_READY, k, j, l);                    \
                     }                                                                   \
                 }                                                                       \
                 if (cl->p2p_blocking == 1) {                                            \
@@ -844,7 +889,7 @@ static void simulate_explicit(const costs_t *co, const cluster_t *cl,
                 heap_push(h, arrive, EV_ARRIVE_B, prev[k], j, 0);
                 mb_[d] += pb[k]; nev++;
             }
-            if (nxt[d] == dev_off[d + 1] && (int64_t)dp * replicas > 1) {      /* the device's gradient all-reduce */
+            if (nxt[d] == dev_off[d + 1] && ranks > 1 && cap == 0) {      /* the device's gradient all-reduce */
                 int64_t G = 0;
                 for (int q = 0; q < S; q++) if (place[q] == d)
                     for (int l = bnd[part[q]]; l < bnd[part[q] + 1]; l++) G += grad[l];
@@ -866,6 +911,21 @@ static void simulate_explicit(const costs_t *co, const cluster_t *cl,
             sc->arrB[(int64_t)k * m + e.mb] = 1;
             TRY_START_X(d);
             break;
+        case EV_GRAD_READY: {                        /* bucketed, overlapped gradient all-reduce of device d */
+            acc[d] += grad[e.layer];
+            pend[d]--;
+            while (acc[d] >= cap || (pend[d] == 0 && acc[d] > 0)) {
+                int64_t bytes = acc[d] >= cap ? cap : acc[d];
+                int64_t dd = allreduce_ns(cl, ranks, bytes);
+                int64_t st = comm_free[d] > now ? comm_free[d] : now;
+                comm_free[d] = st + dd;
+                heap_push(h, comm_free[d], EV_AR_DONE, k, 0, 0);
+                mb_[d] += dd;
+                if (tl_ar) { if (tl_ar[d] < 0) tl_ar[d] = st; tl_ar[pp + d] = comm_free[d]; }
+                acc[d] -= bytes;
+            }
+            break;
+        }
         case EV_AR_DONE:
             nev++;
             break;

@@ -8,6 +8,7 @@ import subprocess
 import pytest
 
 import oracle
+import test_device_buckets_pins as bpins
 import test_explicit_schedule_pins as xpins
 import test_oracle_pins as pins
 import test_stage_table_pins as spins
@@ -65,6 +66,17 @@ MUTANTS = [
     ("stage table: all-reduce events of a tp = 1 layer", "if (tp[c] > 1) { FA += fa[x]; BA += ba[x]; }", "{ FA += fa[x]; BA += ba[x]; }"),
     ("stage table: all-to-all in the forward pass only", "                BA += alltoall_ns(&cl, dp[c], a2a[x]);\n", ""),
     ("stage table: stage bounds of the uniform split rounded up", "(int)(((int64_t)(s + 1) * L) / P);\n            const int64_t i", "(int)(((int64_t)(s + 1) * L + P - 1) / P);\n            const int64_t i"),
+    ("device buckets: gradients of every micro-batch", "if (j == m - 1 && cap > 0 && dp > 1)", "if (cap > 0 && dp > 1)"),
+    ("device buckets: gradients of the first micro-batch", "if (j == m - 1 && cap > 0 && dp > 1)", "if (j == 0 && cap > 0 && dp > 1)"),
+    ("device buckets: what is left after the last gradient is dropped", "while (acc[d] >= cap || (pend[d] == 0 && acc[d] > 0)) {", "while (acc[d] >= cap) {"),
+    ("device buckets: what is left goes after every chunk", "            pend[d]--;\n            while (acc[d] >= cap || (pend[d] == 0 && acc[d] > 0)) {",
+     "            pend[d] = e.layer == bnd[k] ? 0 : 1;\n            while (acc[d] >= cap || (pend[d] == 0 && acc[d] > 0)) {"),
+    ("device buckets: events do not queue", "int64_t st = comm_free[d] > now ? comm_free[d] : now;", "int64_t st = now;"),
+    ("device buckets: the trailing event stays", "if (next[d] == per_dev && dp > 1 && cap == 0) {", "if (next[d] == per_dev && dp > 1) {"),
+    ("device buckets, explicit: the first backward of a stage instead of the last", "if (x >> 31) last_bwd[(x >> 16) & 0x7fff] = i;",
+     "if ((x >> 31) && last_bwd[(x >> 16) & 0x7fff] < 0) last_bwd[(x >> 16) & 0x7fff] = i;"),
+    ("device buckets, explicit: the replicas are forgotten", "int64_t dd = allreduce_ns(cl, ranks, bytes);", "int64_t dd = allreduce_ns(cl, dp, bytes);"),
+    ("device buckets, explicit: stages without backward keep the device waiting", "if (last_bwd[q] >= 0) pend[place[q]] +=", "pend[place[q]] +="),
     ("utilisation from communication", "util[s] = now > 0 ? (double)cb[s] / (double)now : 0.0;", "util[s] = now > 0 ? (double)mb_[s] / (double)now : 0.0;"),
 ]
 
@@ -97,6 +109,11 @@ PINS = [
     xpins.test_serialised_links_against_graph_with_send_nodes,
     xpins.test_bidirectional_lists_run_and_use_both_directions,
     xpins.test_invalid_explicit_schedules,
+    bpins.test_two_chunks_on_one_device_by_hand,
+    bpins.test_lists_of_the_built_in_schedules_with_buckets,
+    bpins.test_bucket_chain_of_interleaved_candidates_from_the_dump,
+    bpins.test_a_stage_without_backward_gives_no_gradient_with_buckets,
+    bpins.test_replicas_enter_the_bucket_events,
     spins.test_tiny_golden_stage_events,
     spins.test_every_column_against_discrete_event_timelines,
     lambda o: spins.test_busy_time_identities(o, "gpt24"),
