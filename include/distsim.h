@@ -67,8 +67,11 @@ extern "C" {
                                   (i / (pp chunks)) pp + i mod pp; backward slot i: the mirrored
                                   chunk.  Device d runs 2 (pp-d-1) + (chunks-1) pp forwards,
                                   then forward / backward in turn, then the backwards left.
-                                  One trailing gradient all-reduce per device (no buckets).
-                                  Per-stage outputs are per device; no stage table.            */
+                                  One trailing gradient all-reduce per device; with a bucket
+                                  size the device fills its buckets across its chunks (a chunk's
+                                  gradients are complete in its backward of micro-batch m - 1,
+                                  last layer first).  Per-stage outputs are per device; no
+                                  stage table.                                                  */
 #define DISTSIM_EXPLICIT 4     /* the schedule S of Algorithm 1 given by the caller (Sec. 4.3: which device
                                   runs which stage-task of which micro-batch, in which order; Sec. 7: a
                                   new pipeline algorithm enters through its schedule).  chunks[c] names
@@ -89,7 +92,10 @@ extern "C" {
                                   needs B(next k, j) and its p2p event, or on a stage without successor
                                   its own F(k, j).  A device runs its list in order.  One gradient
                                   all-reduce per device after its list, over the bytes of the parts of
-                                  all its stages.  pp and m must equal the candidate's.  A schedule that
+                                  all its stages; with a bucket size the device fills its buckets across
+                                  its stages (a stage's gradients are complete in its last backward task
+                                  on the list, last layer first; a stage without a backward task adds
+                                  nothing).  pp and m must equal the candidate's.  A schedule that
                                   cannot be run to its end is invalid, as is a malformed block; one with
                                   S > 64, nparts > 64 or S * m > DISTSIM_MAX_SLOTS is
                                   DISTSIM_ST_UNSUPPORTED.  Per-stage outputs are per device; no stage

@@ -92,9 +92,12 @@ __device__ __forceinline__ void explicit_candidate(const CostsDev& co, const Clu
     if (isk) { sm.place[lane] = place; sm.prev[lane] = prev; }
     __syncthreads();
 
-    // every task at most once, on the device of its stage
+    // every task at most once, on the device of its stage; succ[] has done its work and now takes,
+    // by stage, the place in the list of the stage's last backward task (-1 = none): that is the
+    // task in which the stage's gradients are complete (bucketed all-reduce)
     const int slots = S * m;
     for (int i = lane; i < slots; i += kWave) { sm.end[0][i] = kNotListed; sm.end[1][i] = kNotListed; }
+    sm.succ[lane] = -1;
     __syncthreads();
     bool lbad = false;
     for (int i = t0; i < t1; i++) {
@@ -104,6 +107,7 @@ __device__ __forceinline__ void explicit_candidate(const CostsDev& co, const Clu
         double* e = sm.end[kd] + k * m + j;                             // only this lane holds stage k
         if (*e != kNotListed) { lbad = true; break; }
         *e = kListed;
+        if (kd) sm.succ[k] = i;
     }
     if (__builtin_amdgcn_ballot_w64(lbad) != 0) { invalid(); return; }
     __syncthreads();
@@ -226,6 +230,9 @@ __device__ __forceinline__ void explicit_candidate(const CostsDev& co, const Clu
                     sm.link_free[queue] = seen;
                 }
                 sm.end[kd][k * m + j] = seen;
+                // bucketed all-reduce: the start of the stage's last backward takes the place of its
+                // duration, which no later task needs
+                if (kd && cl.bucket > 0 && i == sm.succ[k]) sm.dur[1][k] = start;
                 if (DUMP) {
                     const int64_t q = ((int64_t)kd * S + k) * m + j;
                     dump.start[q] = double_to_i64(start);
@@ -244,22 +251,65 @@ __device__ __forceinline__ void explicit_candidate(const CostsDev& co, const Clu
     }
     if (stuck || __builtin_amdgcn_ballot_w64(i < t1) != 0) { invalid(); return; }
 
-    // data-parallel modelling per device: one all-reduce after its list, over the bytes of all its stages
+    // data-parallel modelling per device: one all-reduce after its list, over the bytes of all its
+    // stages; or, with a bucket size, the device's buckets: a stage's gradients are complete in its
+    // last backward task on the list, layer by layer from the last layer of its part down, each at the
+    // start of that task + the backward events down to the layer; the device walks its list once more
+    // to take those tasks in order; full buckets are issued at once and queue, the rest goes after the
+    // device's last gradient; a stage without a backward task adds nothing.
     const bool dev = lane < pp;
-    int64_t G = 0;
-    if (dev)
-        for (int k = 0; k < S; k++)
-            if (sm.place[k] == lane) G += sm.grad[k];
     const int64_t ranks = (int64_t)dp * replicas;
-    const bool has_ar = dev && t1 > t0 && ranks > 1 && G > 0;
-    const int64_t AR = has_ar ? allreduce_ns(cl, ranks, G) : 0;
     const int64_t endL = double_to_i64(own);
+    int64_t AR = 0, ar_first = endL, ar_last = endL, nar_dev = 0;                   // AR: busy time of the all-reduce events
+    bool has_ar = false;
+    if (cl.bucket <= 0) {
+        int64_t G = 0;
+        if (dev)
+            for (int k = 0; k < S; k++)
+                if (sm.place[k] == lane) G += sm.grad[k];
+        has_ar = dev && t1 > t0 && ranks > 1 && G > 0;
+        if (has_ar) { AR = allreduce_ns(cl, ranks, G); ar_last = endL + AR; nar_dev = 1; }
+    } else if (dev && ranks > 1) {
+        const int64_t ar_cap = allreduce_ns(cl, ranks, cl.bucket);
+        int64_t t_free = 0, acc = 0, ready = 0;
+        ar_first = -1;
+        for (int q = t0; q < t1; q++) {
+            const uint32_t y = (uint32_t)tasks[q];
+            const int k = (y >> 16) & 0x7fff;
+            if (!(y >> 31) || sm.succ[k] != q) continue;
+            const int part_k = st[3 * k + 1];
+            int lo, hi;
+            if (xc.poff >= 0) { lo = ca.part_pool[xc.poff + part_k]; hi = ca.part_pool[xc.poff + part_k + 1]; }
+            else { lo = uniform_bound(part_k, L, nparts); hi = uniform_bound((part_k + 1), L, nparts); }
+            const int64_t startB = double_to_i64(sm.dur[1][k]), tot_hi = row[hi * kCombWords + 1];
+            for (int l = hi - 1; l >= lo; l--) {
+                ready = startB + (tot_hi - row[l * kCombWords + 1]);
+                acc += row[(l + 1) * kCombWords + 3] - row[l * kCombWords + 3];
+                const int64_t kb = (int64_t)udiv64_by((uint64_t)acc, (uint64_t)cl.bucket, cl.inv_bucket);
+                if (kb > 0) {
+                    const int64_t b0 = t_free > ready ? t_free : ready;
+                    if (ar_first < 0) ar_first = b0;
+                    t_free = b0 + kb * ar_cap;
+                    acc -= kb * cl.bucket;
+                    AR += kb * ar_cap; nar_dev += kb;
+                }
+            }
+        }
+        if (acc > 0) {
+            const int64_t b0 = t_free > ready ? t_free : ready, dd = allreduce_ns(cl, ranks, acc);
+            if (ar_first < 0) ar_first = b0;
+            t_free = b0 + dd;
+            AR += dd; nar_dev++;
+        }
+        has_ar = nar_dev > 0;
+        if (has_ar) ar_last = t_free;
+    }
     if (DUMP) {
-        if (has_ar) { dump.ar_start[lane] = endL; dump.ar_end[lane] = endL + AR; }
+        if (has_ar) { dump.ar_start[lane] = ar_first; dump.ar_end[lane] = ar_last; }
         return;
     }
-    const int64_t batch = group_max(dev ? endL + AR : 0, kWave);
-    const int64_t nar = group_count(has_ar, kWave);
+    const int64_t batch = group_max(dev ? (ar_last > endL ? ar_last : endL) : 0, kWave);
+    const int64_t nar = group_sum(dev ? nar_dev : 0, kWave);
     const int64_t sends = group_sum(dev ? nsend : 0, kWave);
     const int64_t base = ev.stage_pos[c];
     if (dev && base >= 0) {

@@ -185,6 +185,9 @@ __device__ __forceinline__ void virtual_groups(const CostsDev& co, const Cluster
                 }
                 sm.ring[dir][lane][i & (R - 1)] = seen;
                 const int j = fwd ? jF0 + rF : jB0 + rB;                        // micro-batch of the slot
+                // bucketed all-reduce: the chunk's gradients are complete in this task; its duration is
+                // not needed again (the chunk has no later backward), so the start time takes its place
+                if (!fwd && j == m - 1 && cl.bucket > 0) sm.dur[1][g][k] = t0;
                 if (fwd) {
                     iF++;
                     if (++rF == pp) { rF = 0; if (++cF == vch) { cF = 0; jF0 += pp; } }
@@ -210,16 +213,55 @@ __device__ __forceinline__ void virtual_groups(const CostsDev& co, const Cluster
         act = false;
     }
 
-    // data-parallel modelling per device: one trailing all-reduce over the bytes of all its chunks
+    // data-parallel modelling per device: one trailing all-reduce over the bytes of all its chunks,
+    // or, with a bucket size, the device's buckets: the chunks' gradients arrive in the order of
+    // their backwards of the last micro-batch (chunk vch - 1 first), layer by layer from a chunk's
+    // last layer down, each at the start of that backward + the backward events down to the layer;
+    // full buckets are issued at once and queue, the rest goes after the device's last gradient.
     const int64_t endB = double_to_i64(own);
     const bool has_ar = act && dp > 1 && G > 0;
-    const int64_t AR = has_ar ? allreduce_ns(cl, dp, G) : 0;
+    int64_t AR = 0, ar_first = endB, finish = endB, nar_dev = has_ar ? 1 : 0;       // AR: busy time of the all-reduce events
+    if (has_ar && cl.bucket <= 0) {
+        AR = allreduce_ns(cl, dp, G);
+        finish = endB + AR;
+    } else if (has_ar) {
+        const int64_t ar_cap = allreduce_ns(cl, dp, cl.bucket);
+        int64_t t_free = 0, acc = 0, ready = 0;
+        ar_first = -1; nar_dev = 0;
+        for (int cch = vch - 1; cch >= 0; cch--) {
+            const int k = cch * pp + d;
+            int lo, hi;
+            if (vc.poff >= 0) { lo = ca.part_pool[vc.poff + k]; hi = ca.part_pool[vc.poff + k + 1]; }
+            else { lo = uniform_bound(k, L, S); hi = uniform_bound((k + 1), L, S); }
+            const int64_t startB = double_to_i64(sm.dur[1][g][k]), tot_hi = row[hi * kCombWords + 1];
+            for (int l = hi - 1; l >= lo; l--) {
+                ready = startB + (tot_hi - row[l * kCombWords + 1]);
+                acc += row[(l + 1) * kCombWords + 3] - row[l * kCombWords + 3];
+                const int64_t kb = (int64_t)udiv64_by((uint64_t)acc, (uint64_t)cl.bucket, cl.inv_bucket);
+                if (kb > 0) {
+                    const int64_t b0 = t_free > ready ? t_free : ready;
+                    if (ar_first < 0) ar_first = b0;
+                    t_free = b0 + kb * ar_cap;
+                    acc -= kb * cl.bucket;
+                    AR += kb * ar_cap; nar_dev += kb;
+                }
+            }
+        }
+        if (acc > 0) {
+            const int64_t b0 = t_free > ready ? t_free : ready, dd = allreduce_ns(cl, dp, acc);
+            if (ar_first < 0) ar_first = b0;
+            t_free = b0 + dd;
+            AR += dd; nar_dev++;
+        }
+        finish = t_free > endB ? t_free : endB;
+        if (DUMP) { dump.ar_start[d] = ar_first; dump.ar_end[d] = t_free; return; }
+    }
     if (DUMP) {
         if (has_ar) { dump.ar_start[d] = endB; dump.ar_end[d] = endB + AR; }
         return;
     }
-    const int64_t batch = group_max(act ? endB + AR : 0, R);
-    const int64_t nar = group_count(has_ar, R);
+    const int64_t batch = group_max(act ? finish : 0, R);
+    const int64_t nar = group_sum(nar_dev, R);
     if (act) {
         const int64_t base = ev.stage_pos[c];
         if (base >= 0) {

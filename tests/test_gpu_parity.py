@@ -365,6 +365,16 @@ def test_interleaved_schedule(H, oracle_mod):
     assert (ora["batch_ns"][ok3] > free["batch_ns"][ok3]).sum() > 100
     H.assert_same(H.run_hip(w, table=False), ora, what=w.name)
     _timeline_parity(H, oracle_mod, w, np.nonzero(ok3)[0][::25])
+    # bucketed all-reduce: a device fills its buckets across its chunks (results, all-reduce windows)
+    for bucket, blocking in ((8 << 20, 0), (1 << 20, 1), (64 << 20, 2)):
+        cl = dict(w0.cluster); cl["dp_bucket_bytes"] = bucket; cl["p2p_blocking"] = blocking
+        w = Workload(f"gpt48+interleaved bucket={bucket} blocking={blocking}", w0.costs, cl, cand)
+        ora = H.oracle_with_table(oracle_mod, w, NT)
+        plain = oracle_mod.simulate(Workload("trailing", w0.costs, dict(cl, dp_bucket_bytes=0), cand), nthreads=NT)
+        ok3 = (ora["status"] == 0) & (cand["schedule"] == 3)
+        assert (ora["num_events"][ok3] > plain["num_events"][ok3]).sum() > 100          # the buckets are events of their own
+        H.assert_same(H.run_hip(w, table=False), ora, what=w.name)
+        _timeline_parity(H, oracle_mod, w, np.nonzero(ok3)[0][::20])
     # without chunk counts an interleaved candidate is invalid
     nc = {k: v for k, v in cand.items() if k != "chunks"}
     w = Workload("gpt48+interleaved no chunks", w0.costs, w0.cluster, nc)
@@ -640,6 +650,19 @@ def test_explicit_schedules(H, oracle_mod):
         hip = H.run_hip(w, table=False)
         H.assert_same(hip, ora, what=w.name)
         H.assert_same(H.run_hip(w, split=True), ora, what=w.name + ", table, GPipe launch")
+    # bucketed all-reduce: a device fills its buckets across its stages (results, all-reduce windows)
+    gmean = int(np.asarray(costs["grad_bytes"]).mean())
+    for bucket, blocking in ((max(1, gmean // 2), 0), (max(1, 3 * gmean), 1), (max(1, gmean // 7), 2)):
+        w = mk(costs, mk_cluster(N, blocking=blocking, bucket=bucket), rows, name=f"explicit bucket={bucket} blocking={blocking}")
+        w.cand["schedule_off"], w.cand["schedule_words"] = off, words
+        ora = H.oracle_with_table(oracle_mod, w, NT)
+        wp = mk(costs, mk_cluster(N, blocking=blocking), rows)
+        wp.cand["schedule_off"], wp.cand["schedule_words"] = off, words
+        plain = oracle_mod.simulate(wp, nthreads=NT)
+        x4 = (w.cand["schedule"] == 4) & (ora["status"] == 0)
+        assert (ora["num_events"][x4] != plain["num_events"][x4]).sum() > 50
+        H.assert_same(H.run_hip(w, table=False), ora, what=w.name)
+        _timeline_parity(H, oracle_mod, w, np.nonzero(x4)[0][::3])
     # without the tables an explicit candidate is invalid
     w = mk(costs, mk_cluster(N), rows[:8])
     ora = H.oracle_with_table(oracle_mod, w, NT)
