@@ -232,11 +232,6 @@ int distsim_create(distsim_ctx** out, int hip_device) {
         const long long v = strtoll(e, &end, 10);
         if (end != e && v >= 0) ctx->split_min_items = v;
     }
-    if (const char* e = getenv("DISTSIM_GRID_PER_CU")) {
-        char* end = nullptr;
-        const long long v = strtoll(e, &end, 10);
-        if (end != e && v >= 1 && v <= 1024) ctx->grid_per_cu = v;
-    }
     *out = ctx;
     return DISTSIM_OK;
 }
