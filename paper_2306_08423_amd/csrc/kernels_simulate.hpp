@@ -162,6 +162,24 @@ __device__ __forceinline__ double from_lanes(double x, int byte_addr) {
         : [oa] "+v"(o1st), [ob] "+v"(o2nd), [t_] "+v"(t), [p] "+v"(bits), [k] "=&s"(kmask) \
         : [ca] "v"(lat1st), [da] "v"(dur1st), [cb] "v"(lat2nd), [db] "v"(dur2nd))
 
+// One level of the sweep with queues on the links (p2p_blocking = 2), for the lanes whose pattern bit
+// is set: the task starts at max(own, arrival of the neighbour's latest send) -- `gate` is 0 for a
+// lane that has that neighbour and -inf for one that has not --, and its own send leaves when the
+// task has ended and the link is free: own = max(own, arr + gate) + dur; link = max(own, link) + send.
+#define DISTSIM_LSTEP(bits, o, t, link, gate, dur, send)                       \
+    asm volatile(                                                              \
+        "v_add_co_u32_e64 %[p], %[k], %[p], %[p]\n\t"                        \
+        "s_mov_b64 exec, %[k]\n\t"                                            \
+        "v_add_f64 %[t0], %[t0], %[g0]\n\t"                                   \
+        "v_max_f64 %[t0], %[t0], %[o0]\n\t"                                   \
+        "v_add_f64 %[o0], %[t0], %[d0]\n\t"                                   \
+        "v_max_f64 %[t0], %[o0], %[l0]\n\t"                                   \
+        "v_add_f64 %[l0], %[t0], %[s0]\n\t"                                   \
+        "s_mov_b64 exec, -1\n\t"                                              \
+        "s_nop 0"                                                              \
+        : [o0] "+v"(o), [t0] "+v"(t), [l0] "+v"(link), [p] "+v"(bits), [k] "=&s"(kmask) \
+        : [g0] "v"(gate), [d0] "v"(dur), [s0] "v"(send))
+
 // Level windows of a lane that holds stage s, expressed on x = level - s:
 //   forward  x in [0, f1hi]  and  even x in [f2lo, f2hi]
 //   backward x in [blo, bhi], every x (GPipe) or every second x (1F1B)
@@ -357,8 +375,11 @@ __device__ __forceinline__ void simulate_items(const ClusterDev& cl, const CandD
         // of the task.  Plain per-level form of the sweep, one item at a time.
         static_assert(U == 1, "the serialised sweep takes one item at a time");
         const int nlev = wave_max_i32(act ? 2 * (m + pp - 1) : 0);
-        const bool hasL = act && s > 0, hasR = act && s + 1 < pp;
+        // a lane without that neighbour never looks at what the lane beside it sends (another
+        // candidate's stage); the link time of a lane without a receiver is never looked at either
+        const double gateL = act && s > 0 ? 0.0 : ninf, gateR = act && s + 1 < pp ? 0.0 : ninf;
         double own = 0.0, linkF = 0.0, linkB = 0.0;
+        uint64_t kmask;
         for (int l0 = 0; l0 < nlev; l0 += 32) {
             const int x0 = l0 - s;
             const uint32_t even_x = (x0 & 1) ? 0x55555555u : 0xaaaaaaaau;
@@ -366,20 +387,22 @@ __device__ __forceinline__ void simulate_items(const ClusterDev& cl, const CandD
             uint32_t PBb = level_bits(blo - x0, bhi - x0);
             if (sched != 0) PBb &= ((blo - x0) & 1) ? 0x55555555u : 0xaaaaaaaau;
             if (!act) { PFb = 0; PBb = 0; }
+            const bool anyF = wave_or_u32(PFb) != 0, anyB = wave_or_u32(PBb) != 0;
             const int kend = nlev - l0 < 32 ? nlev - l0 : 32;
+            // a lane runs at most one task per level, and a level's tasks read only what the level
+            // before left: the backward step may follow the forward step, which changes neither the
+            // backward lanes' end times nor any backward link
             for (int k = 0; k < kend; k++) {
-                const double arrL = from_prev_lane(linkF), arrR = from_next_lane(linkB);
-                if (PFb >> 31) {
-                    const double t0 = hasL && arrL > own ? arrL : own;
-                    own = t0 + sw[0].Fd;
-                    if (hasR) linkF = (own > linkF ? own : linkF) + sendF[0];
-                } else if (PBb >> 31) {
-                    const double t0 = hasR && arrR > own ? arrR : own;
-                    own = t0 + sw[0].Bd;
-                    if (hasL) linkB = (own > linkB ? own : linkB) + sendB[0];
+                if (anyF) {
+                    double arrL = from_prev_lane(linkF);
+                    DISTSIM_LSTEP(PFb, own, arrL, linkF, gateL, sw[0].Fd, sendF[0]);
                 }
-                PFb <<= 1; PBb <<= 1;
+                if (anyB) {
+                    double arrR = from_next_lane(linkB);
+                    DISTSIM_LSTEP(PBb, own, arrR, linkB, gateR, sw[0].Bd, sendB[0]);
+                }
             }
+            (void)kmask;
         }
         sw[0].own = own;
     } else if constexpr (GPIPE_PAIR) {
