@@ -2,38 +2,63 @@
 // device's tasks belong to several virtual stages and the producer of a task is no longer "the
 // neighbour's latest task".  A wavefront is cut into groups of R lanes, one candidate per group,
 // lane = device.  Each lane walks its own task list (closed forms of the slot numbers, see
-// distsim.h) and keeps the end times of its latest forward and backward slots in LDS rings; in
-// every round a lane runs its next task if the producing slot on the neighbouring device (the
-// device before for forwards, after for backwards, with the edge from the last device back to
-// the first one chunk apart) has been run, reading its end time from that device's ring.  Rounds
-// repeat until every list of the wavefront is done; a round in which no lane can run ends the
-// loop (it cannot happen for a valid schedule) and the candidates still unfinished are reported
-// invalid.  Same arithmetic as the level sweep: fp64 values that are integers below 2^53.
+// distsim.h) and keeps the end times of its latest forward and backward slots in short LDS rings.
+// A round is a forward step and a backward step: in the forward step the lanes whose next task is
+// a forward run it if the producing slot on the neighbouring device (the device before for
+// forwards, after for backwards) has been run, reading its end time from that device's ring; the
+// backward step does the same for the lanes whose next task is then a backward, so a device in
+// the steady phase runs both tasks of a pair in one round, each in code that knows its direction.
+// The edge from the last device back to the first joins slots one chunk (pp slots) apart and has
+// a longer ring of its own.  Rounds repeat until every list of the wavefront is done; a round in
+// which no lane can run ends the loop (it cannot happen for a valid schedule) and the candidates
+// still unfinished are reported invalid.  Same arithmetic as the level sweep: fp64 values that
+// are integers below 2^53.
 #pragma once
+#include <cstddef>
+#include <type_traits>
+
 #include "kernels_simulate.hpp"
 
 namespace distsim {
 
-// LDS of one wavefront: 64 / R candidates of at most R devices each, R ring slots per device and
-// direction.  A producer never leads its consumer by more than the ring holds when R >= max(8, pp)
-// (checked by running the rounds, which do not depend on the durations, for every pp, every chunk
-// count with pp * chunks <= 64 and micro-batch counts up to 8 pp); a task that would overwrite a
-// slot not yet read waits, so a ring that were too small could stall a candidate but never give
-// a wrong time.
+// LDS of one wavefront: 64 / R candidates of at most R devices each.  Two kinds of ring hold task
+// ends, both per direction: one of kDepth slots per device, read by the next device of the
+// direction at the same slot number, and one of R slots per candidate, written by the
+// direction's last device and read by its first device pp slots later.  The steps do not
+// depend on the durations, so running them on the CPU settles the depths (every pp, every chunk
+// count with pp * chunks <= 64, micro-batch counts up to 8 pp): a device leads the next one by at
+// most 2 slots, the last device leads the first by up to pp / 2 slots on top of the pp between
+// them, and with these depths no schedule waits for a slot to become free (2 m chunks + about
+// 2 pp steps in all).  A task that would overwrite a slot not yet read waits, so a ring that were
+// too small could stall a candidate but never give a wrong time.
+struct VirtStage {                              // one virtual stage: task durations, latencies of the incoming edges
+    double dur_f, lat_f, dur_b, lat_b;
+};
 template <int R>
 struct VirtLds {
-    static_assert(R >= 8 && R <= kWave && (R & (R - 1)) == 0, "ring sizes are powers of two from 8 to 64");
-    static constexpr int kRing = R, kGroups = kWave / R;
-    // first index: direction, 0 = forward, 1 = backward
-    union {
-        double ring[2][kWave][R];               // by lane and slot modulo R: end of the task
-        // by group and virtual stage: outgoing p2p events; needed only while the latencies are
-        // set up, before the first round writes the rings (64 R >= (64 / R) 64 entries for R >= 8)
-        int64_t send[2][kGroups][kMaxPP];
-    };
-    double dur[2][kGroups][kMaxPP];             // by group and virtual stage: task durations
-    double lat[2][kGroups][kMaxPP];             // by group and virtual stage: latency of the incoming edge
-    int32_t done[2][kWave];                     // by lane: slots run, as of the previous round
+    static_assert(R >= 8 && R <= kWave && (R & (R - 1)) == 0, "group sizes are powers of two from 8 to 64");
+    static constexpr int kLanes = R, kGroups = kWave / R, kDepth = 4;
+    // first index of the rings and counters: direction, 0 = forward, 1 = backward
+    double ring[2][kDepth][kWave];              // by slot modulo kDepth and lane: what the next device reads
+    double wrap[2][kGroups][R];                 // by group and slot modulo R: the same from the direction's last device
+    alignas(32) VirtStage st[kGroups][kMaxPP];  // by group and virtual stage
+    int32_t done[2][kWave];                     // by lane: slots run
+};
+
+// What a lane needs for its tasks of one direction.  Places in LDS are byte offsets from the start
+// of the wavefront's VirtLds.
+struct VirtDir {
+    int a_done_src, a_done_cons, a_done_own;    // slot counters of the producing device, of the consuming device, of this one
+    int p_base, p_off, p_mask, p_sh;            // the producer's end of slot i: p_base + (((i - p_off) & p_mask) << p_sh)
+    int m_base, m_mask, m_sh;                   // where this lane's end of slot i goes: m_base + ((i & m_mask) << m_sh)
+    int g_min, g_off;                           // slot i may go there if i < g_min or the consumer has run more than i - g_off slots
+    int k_first, k_last;                        // virtual stages without a producer / without a consumer (direction's ends)
+    int k_start, k_step;                        // stage of the first chunk in this direction's order, step to the next chunk
+};
+// The slot a lane is at in one direction: slot i = round of pp * chunks slots (first micro-batch
+// j0), chunk position cp in the direction's order, place r in the chunk; k = virtual stage.
+struct VirtPos {
+    int i, r, cp, j0, k;
 };
 
 // What one candidate needs from its descriptor (or, for the dump, from the candidate arrays); the
@@ -51,14 +76,14 @@ struct VirtDump {
     int64_t* ar_end;
 };
 
-// The candidates of one wavefront, one per group of Lds::kRing lanes.  DUMP = false: writes status
+// The candidates of one wavefront, one per group of Lds::kLanes lanes.  DUMP = false: writes status
 // / batch time / busy sums.  DUMP = true: the candidates are known to be OK; writes every task's
 // start and end and the all-reduce windows, and none of the simulation's outputs.
 template <bool DUMP, typename Lds>
 __device__ __forceinline__ void virtual_groups(const CostsDev& co, const ClusterDev& cl, const CandDev& ca,
                                                const Workspace& ws, const EventsDev& ev, const SimOut& out,
                                                const VirtCand& vc, const VirtDump& dump, Lds& sm) {
-    constexpr int R = Lds::kRing;
+    constexpr int R = Lds::kLanes, D = Lds::kDepth;
     const int lane = threadIdx.x;
     const int g = lane / R, d = lane % R, g0 = g * R;            // group, device, first lane of the group
     const int L = co.L;
@@ -93,10 +118,15 @@ __device__ __forceinline__ void virtual_groups(const CostsDev& co, const Cluster
             comm += FT + BT - CP + PF + PB;
             share += FT + BT + PF + PB;
             const int64_t pf_task = cl.blocking == 1 ? PF : 0, pb_task = cl.blocking == 1 ? PB : 0;
-            sm.dur[0][g][k] = (double)(FT + pf_task);
-            sm.dur[1][g][k] = (double)(BT + pb_task);
-            sm.send[0][g][k] = PF - pf_task;
-            sm.send[1][g][k] = PB - pb_task;
+            VirtStage vs;
+            vs.dur_f = (double)(FT + pf_task);
+            vs.dur_b = (double)(BT + pb_task);
+            // A boundary's p2p event is the same in both directions, so the latency of the edge into
+            // this stage equals the stage's own transfer across that boundary the other way: the
+            // forward edge comes over the boundary that the backward send crosses, and vice versa.
+            vs.lat_f = (double)(PB - pb_task);
+            vs.lat_b = (double)(PF - pf_task);
+            sm.st[g][k] = vs;
         }
     }
     const bool gbad = group_any(bad != 0, R);
@@ -105,107 +135,118 @@ __device__ __forceinline__ void virtual_groups(const CostsDev& co, const Cluster
         if (!DUMP && act && d == 0) { ev.status[c] = gbad ? 1 : 2; ev.num_events[c] = 0; out.batch_ns[c] = INT64_MAX; }
         act = false;
     }
-    __syncthreads();
-    // latency of the edge into virtual stage k: the send of k - 1 (forward), of k + 1 (backward)
-    if (act) {
-        for (int cch = 0; cch < vch; cch++) {
-            const int k = cch * pp + d;
-            sm.lat[0][g][k] = k > 0 ? (double)sm.send[0][g][k - 1] : 0.0;
-            sm.lat[1][g][k] = k + 1 < S ? (double)sm.send[1][g][k + 1] : 0.0;
-        }
-    }
-    __syncthreads();
+    // (a lane reads only its own stages' entries: no barrier is needed for them)
 
     // the rounds
     // slot numbers fit 32 bits: m <= 2^16 and pp * vch <= 64
     const int n = act ? m * vch : 0;                          // slots per direction
     int W = 2 * (pp - d - 1) + (vch - 1) * pp;                // warm-up forwards
     if (W > n) W = n;
-    int iF = 0, iB = 0;
-    // slot i of a direction = group (i / (pp vch)), position of the chunk (i mod (pp vch)) / pp,
-    // place in the chunk i mod pp; kept as counters: r, c and the group's first micro-batch
-    int rF = 0, cF = 0, rB = 0, cB = 0;
-    int jF0 = 0, jB0 = 0;
+    // Per direction: the producer of a slot is the same slot on the device before (in the
+    // direction), or, on the direction's first device, the slot pp earlier on its last device,
+    // which sits in the candidate's wrap ring; the consumer of the ring slot that a task
+    // overwrites is the device after or, on the direction's last device, the first device (pp
+    // slots later).
+    char* const lds = reinterpret_cast<char*>(&sm);
+    const int dLast = pp > 0 ? pp - 1 : 0;
+    auto dir_consts = [&](int dir) {
+        const bool fwd = dir == 0;
+        const bool first = fwd ? d == 0 : d == dLast, last = fwd ? d == dLast : d == 0;
+        const int before = fwd ? (d > 0 ? d - 1 : 0) : (d < dLast ? d + 1 : d);       // clamped: unused at the ends
+        const int after = fwd ? (d < dLast ? d + 1 : d) : (d > 0 ? d - 1 : 0);
+        const int src = g0 + (first ? (fwd ? dLast : 0) : before), cons = g0 + (last ? (fwd ? 0 : dLast) : after);
+        const int ring0 = (int)offsetof(Lds, ring) + dir * D * kWave * 8, wrap0 = (int)offsetof(Lds, wrap) + (dir * kWave + g0) * 8;
+        const int done0 = (int)offsetof(Lds, done) + dir * kWave * 4;
+        VirtDir dc;
+        dc.a_done_src = done0 + src * 4; dc.a_done_cons = done0 + cons * 4; dc.a_done_own = done0 + lane * 4;
+        dc.p_base = first ? wrap0 : ring0 + src * 8; dc.p_off = first ? pp : 0;
+        dc.p_mask = first ? R - 1 : D - 1; dc.p_sh = first ? 3 : 9;
+        dc.m_base = last ? wrap0 : ring0 + lane * 8; dc.m_mask = last ? R - 1 : D - 1; dc.m_sh = last ? 3 : 9;
+        dc.g_min = last ? (vch > 1 ? R : INT32_MAX) : D; dc.g_off = last ? R - pp : D;
+        dc.k_first = fwd ? 0 : S - 1; dc.k_last = fwd ? S - 1 : 0;
+        dc.k_start = fwd ? d : (vch - 1) * pp + d; dc.k_step = fwd ? pp : -pp;
+        return dc;
+    };
+    static_assert(kWave * 8 == 1 << 9, "a ring slot is 64 doubles apart from the next");
+    const VirtDir dcF = dir_consts(0), dcB = dir_consts(1);
+    VirtPos pF{0, 0, 0, 0, dcF.k_start}, pB{0, 0, 0, 0, dcB.k_start};
     double own = 0.0;
     // p2p_blocking = 2: a link is an ordered pair (sending device, receiving device) and carries one
     // transfer at a time.  A device sends forwards to the device after it and backwards to the one
     // before it (both modulo pp): two queues, which are one and the same for pp <= 2.
     double link_f = 0.0, link_b = 0.0;
     const bool one_queue = pp <= 2;
-    const int max_rounds = wave_max_i32(act ? 4 * n + 8 * pp + 64 : 0);
-    // Per direction: the producer of a slot is the same slot on the device before (in the
-    // direction), or, on the direction's first device, the slot pp earlier on its last device; the
-    // consumers of the ring slot that a task overwrites are the device after and, on the
-    // direction's last device, the first device (pp slots later).  All of a round's LDS reads are
-    // issued together, at clamped addresses, and the conditions select among what came back.
-    const int dL = g0 + (d > 0 ? d - 1 : 0), dR = g0 + (d + 1 < pp ? d + 1 : d);      // neighbouring lanes
-    const int dFirst = g0, dLast = g0 + (pp > 0 ? pp - 1 : 0);
-    for (int round = 0; round < max_rounds; round++) {
-        if (act) { sm.done[0][lane] = iF; sm.done[1][lane] = iB; }
-        __syncthreads();
-        const bool todo = act && iB < n;
-        if (__builtin_amdgcn_ballot_w64(todo) == 0) break;
+    if (act) {
+        *reinterpret_cast<int32_t*>(lds + dcF.a_done_own) = 0;
+        *reinterpret_cast<int32_t*>(lds + dcB.a_done_own) = 0;
+    }
+    __syncthreads();
+    // One step: the lanes in `want` try their next task of the direction.  All LDS reads come
+    // before the writes, so what a lane sees does not depend on the order of the lanes.
+    auto step = [&](auto dir_tag, const VirtDir& dc, VirtPos& p, double& link, bool want) -> bool {
+        constexpr int dir = decltype(dir_tag)::value;
         bool ran = false;
-        if (todo) {
-            const bool fwd = iF < W || (iF < n && iF - W == iB);
-            const int dir = fwd ? 0 : 1;
-            const int i = fwd ? iF : iB;
-            // chunk and micro-batch of the slot, from the counters kept with iF / iB
-            const int cch = fwd ? cF : vch - 1 - cB;
-            const int k = cch * pp + d;
-            const bool has_prod = fwd ? k > 0 : k + 1 < S;
-            const bool first = fwd ? d == 0 : d + 1 == pp;            // first device of the direction
-            const bool last = fwd ? d + 1 == pp : d == 0;             // last device of the direction
-            const int src = first ? (fwd ? dLast : dFirst) : (fwd ? dL : dR);
-            const int si = first ? i - pp : i;
-            const int done_src = sm.done[dir][src];
-            const double prod_end = sm.ring[dir][src][si & (R - 1)];
-            const double lat = sm.lat[dir][g][k], dur = sm.dur[dir][g][k];
-            const bool sends = fwd ? k + 1 < S : k > 0;                // the task is followed by a transfer ...
-            const double send = sm.lat[dir][g][sends ? (fwd ? k + 1 : k - 1) : k];      // ... which is the consumer's edge
-            const int done_next = sm.done[dir][fwd ? dR : dL];
-            const int done_wrap = sm.done[dir][fwd ? dFirst : dLast];
-            bool ok = !has_prod || done_src > si;
-            // the slot this task overwrites in the ring must have been read by its consumers
-            if (i >= R) {
-                if (!last && !(done_next > i - R)) ok = false;
-                if (last && vch > 1 && !(done_wrap > i - R + pp)) ok = false;
-            }
+        if (want) {
+            const int i = p.i, si = i - dc.p_off;
+            const int done_src = *reinterpret_cast<const int32_t*>(lds + dc.a_done_src);
+            const int done_cons = *reinterpret_cast<const int32_t*>(lds + dc.a_done_cons);
+            const double prod_end = *reinterpret_cast<const double*>(lds + dc.p_base + ((si & dc.p_mask) << dc.p_sh));
+            const VirtStage* stg = &sm.st[g][p.k];
+            const double dur = dir == 0 ? stg->dur_f : stg->dur_b, lat = dir == 0 ? stg->lat_f : stg->lat_b;
+            const bool has_prod = p.k != dc.k_first;
+            // the producer has run, and the slot this task overwrites in its ring has been read
+            // (no short-circuit: all reads are issued before the first wait)
+            const bool ok = (!has_prod | (done_src > si)) & ((i < dc.g_min) | (done_cons > i - dc.g_off));
             if (ok) {
                 // with queues on the links the producer has stored the transfer's arrival time
                 const double arrive = has_prod ? prod_end + (cl.blocking == 2 ? 0.0 : lat) : 0.0;
-                const double t0 = arrive > own ? arrive : own;
+                const double t0 = __builtin_fmax(arrive, own);
                 own = t0 + dur;
                 double seen = own;                                     // what the consuming task reads
-                if (cl.blocking == 2 && sends) {
-                    const bool q_f = fwd || one_queue;
-                    const double free_at = q_f ? link_f : link_b;
-                    seen = (own > free_at ? own : free_at) + send;
-                    if (q_f) link_f = seen; else link_b = seen;
+                if (cl.blocking == 2 && p.k != dc.k_last) {
+                    // the transfer crosses the boundary of the opposite edge into this stage
+                    const double send = dir == 0 ? stg->lat_b : stg->lat_f;
+                    seen = __builtin_fmax(own, link) + send;
+                    link = seen;
                 }
-                sm.ring[dir][lane][i & (R - 1)] = seen;
-                const int j = fwd ? jF0 + rF : jB0 + rB;                        // micro-batch of the slot
+                *reinterpret_cast<double*>(lds + dc.m_base + ((i & dc.m_mask) << dc.m_sh)) = seen;
+                *reinterpret_cast<int32_t*>(lds + dc.a_done_own) = i + 1;
+                const int j = p.j0 + p.r;                              // micro-batch of the slot
                 // bucketed all-reduce: the chunk's gradients are complete in this task; its duration is
                 // not needed again (the chunk has no later backward), so the start time takes its place
-                if (!fwd && j == m - 1 && cl.bucket > 0) sm.dur[1][g][k] = t0;
-                if (fwd) {
-                    iF++;
-                    if (++rF == pp) { rF = 0; if (++cF == vch) { cF = 0; jF0 += pp; } }
-                } else {
-                    iB++;
-                    if (++rB == pp) { rB = 0; if (++cB == vch) { cB = 0; jB0 += pp; } }
-                }
+                if (dir == 1 && cl.bucket > 0 && j == m - 1) sm.st[g][p.k].dur_b = t0;
                 if (DUMP) {
-                    const int64_t e = ((int64_t)dir * S + k) * m + j;
+                    const int64_t e = ((int64_t)dir * S + p.k) * m + j;
                     dump.start[e] = double_to_i64(t0);
                     dump.end[e] = double_to_i64(own);
+                }
+                p.i = i + 1;
+                if (++p.r == pp) {
+                    p.r = 0; p.k += dc.k_step;
+                    if (++p.cp == vch) { p.cp = 0; p.k = dc.k_start; p.j0 += pp; }
                 }
                 ran = true;
             }
         }
+        return ran;
+    };
+    const int max_rounds = wave_max_i32(act ? 4 * n + 8 * pp + 64 : 0);
+    for (int round = 0; round < max_rounds; round++) {
+        const bool todo = act && pB.i < n;
+        if (__builtin_amdgcn_ballot_w64(todo) == 0) break;
+        bool ran = false;
+        const bool wantF = todo && (pF.i < W || (pF.i < n && pF.i - W == pB.i));
+        if (__builtin_amdgcn_ballot_w64(wantF) != 0)
+            ran = step(std::integral_constant<int, 0>{}, dcF, pF, link_f, wantF);
+        const bool wantB = todo && !(pF.i < W || (pF.i < n && pF.i - W == pB.i));
+        if (__builtin_amdgcn_ballot_w64(wantB) != 0) {
+            double link = one_queue ? link_f : link_b;
+            ran |= step(std::integral_constant<int, 1>{}, dcB, pB, link, wantB);
+            if (cl.blocking == 2) { if (one_queue) link_f = link; else link_b = link; }
+        }
         if (__builtin_amdgcn_ballot_w64(ran) == 0) break;               // nothing can run any more
-        __syncthreads();
     }
+    const int iB = pB.i;
     __syncthreads();
     // a candidate with a list that did not end: its schedule cannot be run
     if (group_any(act && iB < n, R)) {
@@ -233,7 +274,7 @@ __device__ __forceinline__ void virtual_groups(const CostsDev& co, const Cluster
             int lo, hi;
             if (vc.poff >= 0) { lo = ca.part_pool[vc.poff + k]; hi = ca.part_pool[vc.poff + k + 1]; }
             else { lo = uniform_bound(k, L, S); hi = uniform_bound((k + 1), L, S); }
-            const int64_t startB = double_to_i64(sm.dur[1][g][k]), tot_hi = row[hi * kCombWords + 1];
+            const int64_t startB = double_to_i64(sm.st[g][k].dur_b), tot_hi = row[hi * kCombWords + 1];
             for (int l = hi - 1; l >= lo; l--) {
                 ready = startB + (tot_hi - row[l * kCombWords + 1]);
                 acc += row[(l + 1) * kCombWords + 3] - row[l * kCombWords + 3];
@@ -277,9 +318,9 @@ __device__ __forceinline__ void virtual_groups(const CostsDev& co, const Cluster
     }
 }
 
-// One launch per ring size R: the candidates of the classes [cls_lo, cls_hi) of the visiting order
+// One launch per group size R: the candidates of the classes [cls_lo, cls_hi) of the visiting order
 // (class k holds the candidates of 64 >> k lanes, i.e. pp <= 64 >> k <= R), 64 / R consecutive
-// ones per wavefront, so that candidates of few devices share a wavefront and take little LDS.
+// ones per wavefront, so that candidates of few devices share a wavefront.
 // Neighbours in visiting order have about the same number of micro-batches, hence lists of about
 // the same length when their chunk counts agree.
 template <int R>
