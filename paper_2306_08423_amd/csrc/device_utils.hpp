@@ -105,6 +105,14 @@ __device__ __forceinline__ int64_t wave_inclusive_sum(int64_t v) {
     return v;
 }
 
+// max of two doubles that are known not to be NaN: one instruction (the builtin first rewrites
+// each operand that it cannot prove canonical)
+__device__ __forceinline__ double max_f64(double a, double b) {
+    double r;
+    asm("v_max_f64 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+    return r;
+}
+
 // Exact conversion of a double that holds an integer of [0, 2^53) (five instructions).
 __device__ __forceinline__ int64_t double_to_i64(double d) {
     const uint32_t hi = (uint32_t)(d * (1.0 / 4294967296.0));              // truncates

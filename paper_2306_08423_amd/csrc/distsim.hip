@@ -418,14 +418,12 @@ int distsim_simulate(distsim_ctx* ctx, const distsim_cluster* cluster, const dis
         HIP_TRY(hipStreamWaitEvent(st, ctx->join, 0));
     }
     if (cd->chunks) {       // candidates of the interleaved schedule, if the caller has any
-        // one launch per ring size; a block is one wavefront, a CU holds up to 32 of them
+        // one launch for all classes; a block is one wavefront with 9.5 KB of LDS, 16 fit a CU; four
+        // times as many blocks as fit, so that the order in which they start evens out their lengths
         Timer t(ctx, st, DISTSIM_K_SIMULATE_VIRTUAL);
-        const int64_t most = (int64_t)ctx->num_cus * 32;
+        const int64_t most = (int64_t)ctx->num_cus * 64;
         const unsigned blocks = (unsigned)(C < most ? C : most);
-        hipLaunchKernelGGL(k_simulate_virtual<64>, dim3(blocks), dim3(kWave), 0, st, co, cl, ca, ws, ev, out, 0, 1);
-        hipLaunchKernelGGL(k_simulate_virtual<32>, dim3(blocks), dim3(kWave), 0, st, co, cl, ca, ws, ev, out, 1, 2);
-        hipLaunchKernelGGL(k_simulate_virtual<16>, dim3(blocks), dim3(kWave), 0, st, co, cl, ca, ws, ev, out, 2, 3);
-        hipLaunchKernelGGL(k_simulate_virtual<8>, dim3(blocks), dim3(kWave), 0, st, co, cl, ca, ws, ev, out, 3, kClasses);
+        hipLaunchKernelGGL(k_simulate_virtual, dim3(blocks), dim3(kWave), 0, st, co, cl, ca, ws, ev, out);
     }
     if (cd->chunks && ca.n_schedules > 0) {       // candidates with an explicit schedule, if the caller has any
         // one launch per LDS size (by the schedule's number of stage x micro-batch pairs)

@@ -21,27 +21,28 @@
 
 namespace distsim {
 
-// LDS of one wavefront: 64 / R candidates of at most R devices each.  Two kinds of ring hold task
-// ends, both per direction: one of kDepth slots per device, read by the next device of the
-// direction at the same slot number, and one of R slots per candidate, written by the
-// direction's last device and read by its first device pp slots later.  The steps do not
-// depend on the durations, so running them on the CPU settles the depths (every pp, every chunk
-// count with pp * chunks <= 64, micro-batch counts up to 8 pp): a device leads the next one by at
-// most 2 slots, the last device leads the first by up to pp / 2 slots on top of the pp between
-// them, and with these depths no schedule waits for a slot to become free (2 m chunks + about
-// 2 pp steps in all).  A task that would overwrite a slot not yet read waits, so a ring that were
-// too small could stall a candidate but never give a wrong time.
+// LDS of one wavefront, which holds 64 / R candidates of at most R devices each (R a power of
+// two, 2 to 64).  Two kinds of ring hold task ends, both per direction: one of kDepth slots per
+// device, read by the next device of the direction at the same slot number, and one of R slots
+// per candidate, written by the direction's last device and read by its first device pp slots
+// later.  The steps do not depend on the durations, so running them on the CPU settles the
+// depths (every pp, every chunk count with pp * chunks <= 64, micro-batch counts up to 8 pp): a
+// device leads the next one by at most 2 slots, the last device leads the first by up to pp / 2
+// slots on top of the pp between them, and with these depths no schedule waits for a slot to
+// become free (2 m chunks + about 2 pp steps in all).  A task that would overwrite a slot not
+// yet read waits, so a ring that were too small could stall a candidate but never give a wrong
+// time.  The table of virtual stages is shared by the wavefront's candidates: each takes pp *
+// chunks entries, and candidates that do not fit wait for a further pass (none do with up to
+// 128 / (64 / R) virtual stages each, e.g. two chunks per device).
 struct VirtStage {                              // one virtual stage: task durations, latencies of the incoming edges
     double dur_f, lat_f, dur_b, lat_b;
 };
-template <int R>
 struct VirtLds {
-    static_assert(R >= 8 && R <= kWave && (R & (R - 1)) == 0, "group sizes are powers of two from 8 to 64");
-    static constexpr int kLanes = R, kGroups = kWave / R, kDepth = 4;
+    static constexpr int kDepth = 4, kStages = 2 * kWave;
     // first index of the rings and counters: direction, 0 = forward, 1 = backward
     double ring[2][kDepth][kWave];              // by slot modulo kDepth and lane: what the next device reads
-    double wrap[2][kGroups][R];                 // by group and slot modulo R: the same from the direction's last device
-    alignas(32) VirtStage st[kGroups][kMaxPP];  // by group and virtual stage
+    double wrap[2][kWave];                      // R slots per candidate, slot modulo R: the same from the direction's last device
+    alignas(32) VirtStage st[kStages];          // the candidates' virtual stages, one candidate after the other
     int32_t done[2][kWave];                     // by lane: slots run
 };
 
@@ -65,6 +66,7 @@ struct VirtPos {
 // lanes of a group hold the same values.  pp == 0: the group has no candidate.
 struct VirtCand {
     int pp, v, m, dp, tp, vch;
+    int st0;             // first entry of the candidate in the table of virtual stages
     int64_t poff, c;
 };
 
@@ -76,14 +78,17 @@ struct VirtDump {
     int64_t* ar_end;
 };
 
-// The candidates of one wavefront, one per group of Lds::kLanes lanes.  DUMP = false: writes status
+// The candidates of one wavefront, one per group of R lanes.  DUMP = false: writes status
 // / batch time / busy sums.  DUMP = true: the candidates are known to be OK; writes every task's
 // start and end and the all-reduce windows, and none of the simulation's outputs.
-template <bool DUMP, typename Lds>
+template <bool DUMP, int R>
 __device__ __forceinline__ void virtual_groups(const CostsDev& co, const ClusterDev& cl, const CandDev& ca,
                                                const Workspace& ws, const EventsDev& ev, const SimOut& out,
-                                               const VirtCand& vc, const VirtDump& dump, Lds& sm) {
-    constexpr int R = Lds::kLanes, D = Lds::kDepth;
+                                               const VirtCand& vc, const VirtDump& dump, VirtLds& sm) {
+    static_assert(R >= 2 && R <= kWave && (R & (R - 1)) == 0, "group sizes are powers of two from 2 to 64");
+    constexpr int D = VirtLds::kDepth;
+    using Lds = VirtLds;
+    VirtStage* const st = sm.st + vc.st0;                         // this candidate's virtual stages
     const int lane = threadIdx.x;
     const int g = lane / R, d = lane % R, g0 = g * R;            // group, device, first lane of the group
     const int L = co.L;
@@ -126,7 +131,7 @@ __device__ __forceinline__ void virtual_groups(const CostsDev& co, const Cluster
             // forward edge comes over the boundary that the backward send crosses, and vice versa.
             vs.lat_f = (double)(PB - pb_task);
             vs.lat_b = (double)(PF - pf_task);
-            sm.st[g][k] = vs;
+            st[k] = vs;
         }
     }
     const bool gbad = group_any(bad != 0, R);
@@ -183,30 +188,34 @@ __device__ __forceinline__ void virtual_groups(const CostsDev& co, const Cluster
     __syncthreads();
     // One step: the lanes in `want` try their next task of the direction.  All LDS reads come
     // before the writes, so what a lane sees does not depend on the order of the lanes.
-    auto step = [&](auto dir_tag, const VirtDir& dc, VirtPos& p, double& link, bool want) -> bool {
+    auto step = [&](auto dir_tag, auto links_tag, const VirtDir& dc, VirtPos& p, double& link, bool want) -> bool {
         constexpr int dir = decltype(dir_tag)::value;
+        constexpr bool LINKS = decltype(links_tag)::value;               // p2p_blocking = 2
         bool ran = false;
         if (want) {
             const int i = p.i, si = i - dc.p_off;
             const int done_src = *reinterpret_cast<const int32_t*>(lds + dc.a_done_src);
             const int done_cons = *reinterpret_cast<const int32_t*>(lds + dc.a_done_cons);
             const double prod_end = *reinterpret_cast<const double*>(lds + dc.p_base + ((si & dc.p_mask) << dc.p_sh));
-            const VirtStage* stg = &sm.st[g][p.k];
+            const VirtStage* stg = st + p.k;
             const double dur = dir == 0 ? stg->dur_f : stg->dur_b, lat = dir == 0 ? stg->lat_f : stg->lat_b;
             const bool has_prod = p.k != dc.k_first;
+            // one wait for the four reads: without this the compiler moves two of them behind the
+            // test below and a step waits for LDS twice
+            asm volatile("" : : "v"(prod_end), "v"(dur), "v"(lat), "v"(done_src), "v"(done_cons));
             // the producer has run, and the slot this task overwrites in its ring has been read
             // (no short-circuit: all reads are issued before the first wait)
             const bool ok = (!has_prod | (done_src > si)) & ((i < dc.g_min) | (done_cons > i - dc.g_off));
             if (ok) {
                 // with queues on the links the producer has stored the transfer's arrival time
-                const double arrive = has_prod ? prod_end + (cl.blocking == 2 ? 0.0 : lat) : 0.0;
-                const double t0 = __builtin_fmax(arrive, own);
+                const double arrive = has_prod ? (LINKS ? prod_end : prod_end + lat) : 0.0;
+                const double t0 = max_f64(arrive, own);
                 own = t0 + dur;
                 double seen = own;                                     // what the consuming task reads
-                if (cl.blocking == 2 && p.k != dc.k_last) {
+                if (LINKS && p.k != dc.k_last) {
                     // the transfer crosses the boundary of the opposite edge into this stage
                     const double send = dir == 0 ? stg->lat_b : stg->lat_f;
-                    seen = __builtin_fmax(own, link) + send;
+                    seen = max_f64(own, link) + send;
                     link = seen;
                 }
                 *reinterpret_cast<double*>(lds + dc.m_base + ((i & dc.m_mask) << dc.m_sh)) = seen;
@@ -214,7 +223,7 @@ __device__ __forceinline__ void virtual_groups(const CostsDev& co, const Cluster
                 const int j = p.j0 + p.r;                              // micro-batch of the slot
                 // bucketed all-reduce: the chunk's gradients are complete in this task; its duration is
                 // not needed again (the chunk has no later backward), so the start time takes its place
-                if (dir == 1 && cl.bucket > 0 && j == m - 1) sm.st[g][p.k].dur_b = t0;
+                if (dir == 1 && cl.bucket > 0 && j == m - 1) st[p.k].dur_b = t0;
                 if (DUMP) {
                     const int64_t e = ((int64_t)dir * S + p.k) * m + j;
                     dump.start[e] = double_to_i64(t0);
@@ -231,21 +240,24 @@ __device__ __forceinline__ void virtual_groups(const CostsDev& co, const Cluster
         return ran;
     };
     const int max_rounds = wave_max_i32(act ? 4 * n + 8 * pp + 64 : 0);
-    for (int round = 0; round < max_rounds; round++) {
-        const bool todo = act && pB.i < n;
-        if (__builtin_amdgcn_ballot_w64(todo) == 0) break;
-        bool ran = false;
-        const bool wantF = todo && (pF.i < W || (pF.i < n && pF.i - W == pB.i));
-        if (__builtin_amdgcn_ballot_w64(wantF) != 0)
-            ran = step(std::integral_constant<int, 0>{}, dcF, pF, link_f, wantF);
-        const bool wantB = todo && !(pF.i < W || (pF.i < n && pF.i - W == pB.i));
-        if (__builtin_amdgcn_ballot_w64(wantB) != 0) {
-            double link = one_queue ? link_f : link_b;
-            ran |= step(std::integral_constant<int, 1>{}, dcB, pB, link, wantB);
-            if (cl.blocking == 2) { if (one_queue) link_f = link; else link_b = link; }
+    // The loop exists twice, with and without the queues on the links, so that neither pays for the other.
+    auto rounds = [&](auto links_tag) {
+        constexpr bool LINKS = decltype(links_tag)::value;
+        for (int round = 0; round < max_rounds; round++) {
+            // A device's next task is a forward while it has run at most W forwards more than backwards
+            // (W of them in the warm-up, then one before every backward) and forwards are left.  A step
+            // that no lane wants is skipped by the branch around its body.  (n = 0 in idle lanes.)
+            const bool wantF = pF.i < n && pF.i - pB.i <= W;
+            bool ran = step(std::integral_constant<int, 0>{}, links_tag, dcF, pF, link_f, wantF);
+            if (LINKS && one_queue) link_b = link_f;
+            const bool wantB = pB.i < n && !(pF.i < n && pF.i - pB.i <= W);
+            ran |= step(std::integral_constant<int, 1>{}, links_tag, dcB, pB, link_b, wantB);
+            if (LINKS && one_queue) link_f = link_b;
+            if (__builtin_amdgcn_ballot_w64(ran) == 0) break;           // all lists are done, or nothing can run any more
         }
-        if (__builtin_amdgcn_ballot_w64(ran) == 0) break;               // nothing can run any more
-    }
+    };
+    if (cl.blocking == 2) rounds(std::true_type{});
+    else rounds(std::false_type{});
     const int iB = pB.i;
     __syncthreads();
     // a candidate with a list that did not end: its schedule cannot be run
@@ -274,7 +286,7 @@ __device__ __forceinline__ void virtual_groups(const CostsDev& co, const Cluster
             int lo, hi;
             if (vc.poff >= 0) { lo = ca.part_pool[vc.poff + k]; hi = ca.part_pool[vc.poff + k + 1]; }
             else { lo = uniform_bound(k, L, S); hi = uniform_bound((k + 1), L, S); }
-            const int64_t startB = double_to_i64(sm.st[g][k].dur_b), tot_hi = row[hi * kCombWords + 1];
+            const int64_t startB = double_to_i64(st[k].dur_b), tot_hi = row[hi * kCombWords + 1];
             for (int l = hi - 1; l >= lo; l--) {
                 ready = startB + (tot_hi - row[l * kCombWords + 1]);
                 acc += row[(l + 1) * kCombWords + 3] - row[l * kCombWords + 3];
@@ -318,30 +330,60 @@ __device__ __forceinline__ void virtual_groups(const CostsDev& co, const Cluster
     }
 }
 
-// One launch per group size R: the candidates of the classes [cls_lo, cls_hi) of the visiting order
-// (class k holds the candidates of 64 >> k lanes, i.e. pp <= 64 >> k <= R), 64 / R consecutive
-// ones per wavefront, so that candidates of few devices share a wavefront.
-// Neighbours in visiting order have about the same number of micro-batches, hence lists of about
-// the same length when their chunk counts agree.
+// One unit of work: the 64 / R consecutive candidates of the visiting order from pos0 on, one per
+// group of R lanes.  Neighbours in visiting order have about the same number of micro-batches,
+// hence lists of about the same length when their chunk counts agree.
 template <int R>
-__global__ __launch_bounds__(kWave) void k_simulate_virtual(CostsDev co, ClusterDev cl, CandDev ca, Workspace ws,
-                                                            EventsDev ev, SimOut out, int cls_lo, int cls_hi) {
+__device__ __forceinline__ void virtual_unit(const CostsDev& co, const ClusterDev& cl, const CandDev& ca,
+                                             const Workspace& ws, const EventsDev& ev, const SimOut& out,
+                                             int64_t pos0, int64_t pos_end, VirtLds& sm) {
     constexpr int kGroups = kWave / R;
-    __shared__ VirtLds<R> sm;
-    const int g = threadIdx.x / R;
+    const int lane = threadIdx.x, g = lane / R;
     // descriptors beyond the valid candidates were never written: the class table bounds them
-    const int64_t pos_end = ws.hdr[H_CLASS_START + cls_hi];
-    for (int64_t pos0 = ws.hdr[H_CLASS_START + cls_lo] + (int64_t)blockIdx.x * kGroups; pos0 < pos_end;
-         pos0 += (int64_t)gridDim.x * kGroups) {
-        Desc ds{};
-        if (pos0 + g < pos_end) ds = ws.desc[pos0 + g];
-        if (!is_interleaved(ds)) ds.meta = 0;
-        if (__builtin_amdgcn_ballot_w64((ds.meta & 0xff) != 0) == 0) continue;
-        const VirtCand vc{ds.meta & 0xff, ds.meta >> 16, ds.m, ds.dp, (int)(uint32_t)ds.spare, (int)(ds.spare >> 32),
-                          ds.poff, ds.cand};
-        virtual_groups<false>(co, cl, ca, ws, ev, out, vc, VirtDump{}, sm);
-        __syncthreads();
+    Desc ds{};
+    if (pos0 + g < pos_end) ds = ws.desc[pos0 + g];
+    if (!is_interleaved(ds)) ds.meta = 0;
+    const int pp = ds.meta & 0xff, vch = (int)(ds.spare >> 32);
+    bool pending = pp != 0;
+    // Passes: the pending candidates, in order, for as long as their virtual stages fit the table
+    // (the first always does: a candidate has at most 64).
+    for (int pass = 0; pass < kGroups && __builtin_amdgcn_ballot_w64(pending) != 0; pass++) {
+        int upto = pending && lane % R == 0 ? pp * vch : 0;        // becomes: stages of the pending candidates up to this one
+        for (int sh = 1; sh < kWave; sh <<= 1) {
+            const int o = __shfl_up(upto, sh, kWave);
+            if (lane >= sh) upto += o;
+        }
+        const bool now = pending && upto <= VirtLds::kStages;
+        const VirtCand vc{now ? pp : 0, ds.meta >> 16, ds.m, ds.dp, (int)(uint32_t)ds.spare, vch,
+                          now ? upto - pp * vch : 0, ds.poff, ds.cand};
+        virtual_groups<false, R>(co, cl, ca, ws, ev, out, vc, VirtDump{}, sm);
+        pending = pending && !now;
     }
+}
+
+// Class k of the visiting order holds the candidates of 64 >> k lanes (pp <= 64 >> k), so that a
+// wavefront takes 1, 2, 4, 8, 16 or 32 of them (the candidates of one device share the groups of
+// two lanes).  The units of all classes are numbered in one sequence, widest class first, and
+// dealt to the blocks in turn; a block is one wavefront.
+__global__ __launch_bounds__(kWave, 4) void k_simulate_virtual(CostsDev co, ClusterDev cl, CandDev ca, Workspace ws,
+                                                            EventsDev ev, SimOut out) {
+    __shared__ VirtLds sm;
+    int64_t next = blockIdx.x;                    // this block's next unit, counted from the first unit of the current classes
+    auto classes = [&](auto width_tag, int cls_lo, int cls_hi) {
+        constexpr int R = decltype(width_tag)::value, kGroups = kWave / R;
+        const int64_t pos_lo = ws.hdr[H_CLASS_START + cls_lo], pos_end = ws.hdr[H_CLASS_START + cls_hi];
+        const int64_t units = (pos_end - pos_lo + kGroups - 1) / kGroups;
+        for (; next < units; next += gridDim.x)
+            virtual_unit<R>(co, cl, ca, ws, ev, out, pos_lo + next * kGroups, pos_end, sm);
+        next -= units;
+    };
+    static_assert(kClasses == 7, "one call per class below, the last for the two narrowest");
+    classes(std::integral_constant<int, 64>{}, 0, 1);
+    classes(std::integral_constant<int, 32>{}, 1, 2);
+    classes(std::integral_constant<int, 16>{}, 2, 3);
+    classes(std::integral_constant<int, 8>{}, 3, 4);
+    classes(std::integral_constant<int, 4>{}, 4, 5);
+    classes(std::integral_constant<int, 2>{}, 5, 7);
 }
 
 // Timeline dump of the selected candidates that use the interleaved schedule; one wavefront per
@@ -353,7 +395,7 @@ __global__ __launch_bounds__(kWave) void k_timeline_virtual(CostsDev co, Cluster
                                                             const int64_t* sel, const int64_t* task_off,
                                                             int64_t* start_ns, int64_t* end_ns, int64_t* ar_start,
                                                             int64_t* ar_end) {
-    __shared__ VirtLds<kMaxPP> sm;
+    __shared__ VirtLds sm;
     for (int64_t q = blockIdx.x; q < n; q += gridDim.x) {
         const int64_t c = sel[q];
         if (c < 0 || c >= C || status[c] != 0 || ca.schedule[c] != 3 || !ca.chunks) continue;
@@ -362,10 +404,10 @@ __global__ __launch_bounds__(kWave) void k_timeline_virtual(CostsDev co, Cluster
         for (int i = 0; i < co.V; i++)
             if (co.variant_tp[i] == tp) { v = i; break; }
         if (v < 0) continue;                                              // cannot be: the status is OK
-        const VirtCand vc{ca.pp[c], v, ca.m[c], ca.dp[c], tp, ca.chunks[c], ca.part_off[c], c};
+        const VirtCand vc{ca.pp[c], v, ca.m[c], ca.dp[c], tp, ca.chunks[c], 0, ca.part_off[c], c};
         const int64_t off = task_off[q];
         const VirtDump dump{start_ns + off, end_ns + off, ar_start + q * kMaxPP, ar_end + q * kMaxPP};
-        virtual_groups<true>(co, cl, ca, ws, EventsDev{}, SimOut{}, vc, dump, sm);
+        virtual_groups<true, kWave>(co, cl, ca, ws, EventsDev{}, SimOut{}, vc, dump, sm);
         __syncthreads();
     }
 }

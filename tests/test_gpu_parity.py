@@ -416,6 +416,20 @@ def test_interleaved_schedule(H, oracle_mod):
     assert hip["status"][-2:].tolist() == [4, 1]
     H.assert_same(hip, ora, what="interleaved ragged")
     _timeline_parity(H, oracle_mod, w, np.arange(0, w.C, 3))
+    # many candidates of few devices and many chunks: the candidates that share a wavefront have more
+    # virtual stages than its table holds, so it takes them in several passes
+    rows = []
+    for pp in (1, 2, 3, 4, 5, 8):
+        for v in (6, 8, 12, 16, 21, 32, 64):
+            if pp * v > 64:
+                continue
+            for groups in (1, 2, 3, 4, 7):
+                rows.append((N // pp, 1, pp, pp * groups, 3, None, v))
+    w = mk(costs, mk_cluster(N), rows)
+    ora = H.oracle_with_table(oracle_mod, w, NT)
+    assert (ora["status"] == 0).sum() > 100
+    H.assert_same(H.run_hip(w, table=False), ora, what="interleaved, many chunks on few devices")
+    _timeline_parity(H, oracle_mod, w, np.arange(0, w.C, 7))
 
 
 def test_runs_are_deterministic(H):
