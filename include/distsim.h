@@ -423,7 +423,7 @@ enum {
     DISTSIM_K_STAGE_EVENTS, DISTSIM_K_SIM_INIT, DISTSIM_K_SIMULATE, DISTSIM_K_SEARCH, DISTSIM_K_TIMELINE,
     DISTSIM_K_DEDUP, DISTSIM_K_COMM_TIMES, DISTSIM_K_BUBBLES, DISTSIM_K_SIMULATE_VIRTUAL,
     DISTSIM_K_TIMELINE_VIRTUAL, DISTSIM_K_SIMULATE_GPIPE, DISTSIM_K_SIMULATE_EXPLICIT,
-    DISTSIM_K_TIMELINE_EXPLICIT, DISTSIM_K_COUNT
+    DISTSIM_K_TIMELINE_EXPLICIT, DISTSIM_K_COMPILE_SCHEDULES, DISTSIM_K_COUNT
 };
 int distsim_timing_enable(distsim_ctx *ctx, int on);
 int distsim_timing_read(distsim_ctx *ctx, int kernel, double *total_ms, int64_t *launches);

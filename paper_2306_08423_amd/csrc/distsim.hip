@@ -12,6 +12,7 @@
 #include "kernels_ingest.hpp"
 #include "kernels_search.hpp"
 #include "kernels_explicit.hpp"
+#include "kernels_schedule.hpp"
 #include "kernels_simulate.hpp"
 #include "kernels_timeline.hpp"
 #include "kernels_virtual.hpp"
@@ -50,6 +51,7 @@ static const char* kKernelNames[DISTSIM_K_COUNT] = {
     "k_stage_events", "k_sim_init", "k_simulate", "k_search", "k_timeline",
     "k_dedup", "k_comm_event_times", "k_bubbles", "k_simulate_virtual",
     "k_timeline_virtual", "k_simulate_gpipe", "k_simulate_explicit", "k_timeline_explicit",
+    "k_compile_schedules",
 };
 
 static int fail(distsim_ctx* ctx, int code, const std::string& msg) {
@@ -310,6 +312,14 @@ int distsim_build_events(distsim_ctx* ctx, const distsim_costs* costs, const dis
     // The layer tables do not depend on the candidates and nothing before k_stage_events reads
     // them: for a long list they are built on the context's stream next to decode / bins / scatter.
     const bool beside = C >= ctx->split_min_items;
+    // The explicit schedules are turned into programs once, for all the candidates that use them
+    // (after k_layer_tables on the same stream, which clears the count of schedules without one).
+    auto compile_schedules = [&](hipStream_t s) {
+        if (!cand->chunks || ca.n_schedules <= 0) return;
+        Timer t(ctx, s, DISTSIM_K_COMPILE_SCHEDULES);
+        const int64_t ids = ca.n_schedules < kSchedCap ? ca.n_schedules : kSchedCap;
+        hipLaunchKernelGGL(k_compile_schedules, dim3((unsigned)ids), dim3(kWave), 0, s, ca, ws);
+    };
     if (beside) {
         HIP_TRY(hipEventRecord(ctx->fork, st));
         HIP_TRY(hipStreamWaitEvent(ctx->side, ctx->fork, 0));
@@ -317,12 +327,14 @@ int distsim_build_events(distsim_ctx* ctx, const distsim_costs* costs, const dis
             Timer t(ctx, ctx->side, DISTSIM_K_LAYER_TABLES);
             hipLaunchKernelGGL(k_layer_tables, dim3(costs->V * kMaxPP), dim3(kWave), 0, ctx->side, co, cl, ws);
         }
+        compile_schedules(ctx->side);
         HIP_TRY(hipEventRecord(ctx->join, ctx->side));
         hipLaunchKernelGGL(k_clear_bins, dim3((kBins + 255) / 256), dim3(256), 0, st, ws);
     } else {
         Timer t(ctx, st, DISTSIM_K_LAYER_TABLES);
         hipLaunchKernelGGL(k_layer_tables, dim3(costs->V * kMaxPP), dim3(kWave), 0, st, co, cl, ws);
         hipLaunchKernelGGL(k_clear_bins, dim3((kBins + 255) / 256), dim3(256), 0, st, ws);
+        compile_schedules(st);
     }
     if (C > 0) {
         Timer t(ctx, st, DISTSIM_K_DECODE);
@@ -426,8 +438,16 @@ int distsim_simulate(distsim_ctx* ctx, const distsim_cluster* cluster, const dis
         hipLaunchKernelGGL(k_simulate_virtual, dim3(blocks), dim3(kWave), 0, st, co, cl, ca, ws, ev, out);
     }
     if (cd->chunks && ca.n_schedules > 0) {       // candidates with an explicit schedule, if the caller has any
-        // one launch per LDS size (by the schedule's number of stage x micro-batch pairs)
         Timer t(ctx, st, DISTSIM_K_SIMULATE_EXPLICIT);
+        {
+            // those whose schedule has a program: one launch for all classes, a block is one wavefront
+            // with 18 KB of LDS; four times as many blocks as fit, as for the interleaved schedule
+            const int64_t most = (int64_t)ctx->num_cus * 32;
+            const unsigned blocks = (unsigned)(C < most ? C : most);
+            hipLaunchKernelGGL(k_simulate_scheduled, dim3(blocks), dim3(kWave), 0, st, co, cl, ca, ws, ev, out);
+        }
+        // the others (none as a rule: every block ends at once then): one launch per LDS size (by the
+        // schedule's number of stage x micro-batch pairs)
         const int64_t most = (int64_t)ctx->num_cus * 32;
         const unsigned blocks = (unsigned)(C < most ? C : most);
         static_assert(kMaxSlots == 2048, "the launches below cover schedules of up to 2048 pairs");

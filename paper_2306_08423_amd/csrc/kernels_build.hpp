@@ -71,6 +71,7 @@ __global__ __launch_bounds__(64) void k_layer_tables(CostsDev co, ClusterDev cl,
     const int row = blockIdx.x;
     const int v = row / kMaxPP, pp = row % kMaxPP + 1;
     const int lane = threadIdx.x;
+    if (row == 0 && lane == 0) ws.hdr[H_SCHED_TABLE] = 0;             // counted up by k_compile_schedules, which follows
     const int L = co.L;
     const int tp = co.variant_tp[v];
     int64_t dp = 1;

@@ -330,6 +330,8 @@ template <int SLOTS>
 __global__ __launch_bounds__(kWave) void k_simulate_explicit(CostsDev co, ClusterDev cl, CandDev ca, Workspace ws,
                                                              EventsDev ev, SimOut out, int slots_above) {
     __shared__ ExplicitLds<SLOTS> sm;
+    // only the candidates of schedules that k_compile_schedules left to this kernel
+    if (ws.hdr[H_SCHED_TABLE] == 0) return;
     // descriptors beyond the valid candidates were never written: the class table bounds them
     const int64_t pos_end = ws.hdr[H_CLASS_START + kClasses];
     for (int64_t pos = blockIdx.x; pos < pos_end; pos += gridDim.x) {
@@ -337,6 +339,7 @@ __global__ __launch_bounds__(kWave) void k_simulate_explicit(CostsDev co, Cluste
         if (!is_explicit(ds) || (ds.meta & 0xff) == 0) continue;          // uniform: one descriptor per wavefront
         const ExplicitCand xc{ds.meta & 0xff, ds.meta >> 16, ds.m, ds.dp, (int)(uint32_t)ds.spare, ds.spare >> 32, ds.poff,
                               ds.cand};
+        if (xc.id < kSchedCap && ws.sched_hdr[xc.id].state != 0) continue;      // 0: no program
         // k_decode has checked the head of the block: 1 <= S <= 64, S * m <= kMaxSlots
         const int slots = ca.schedule_words[ca.schedule_off[xc.id] + 1] * xc.m;
         if (slots <= slots_above || slots > SLOTS) continue;

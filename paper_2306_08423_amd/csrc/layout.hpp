@@ -9,6 +9,17 @@ constexpr int kMaxPP = 64;
 constexpr int kMaxM = 1 << 16;
 constexpr int kMaxV = 16;                   // tensor-parallel variants of a cost table
 constexpr int kMaxSlots = 2048;             // (virtual stage, micro-batch) pairs of an explicit schedule
+// Compiled explicit schedules (k_compile_schedules): the first kSchedCap schedules, as far as their
+// blocks lie in the first kSchedOpsCap words of the schedule array, get a program; a program's ring
+// pool has at most kSchedMaxPool entries, the candidates of a wavefront share kSchedWavePool.
+constexpr int kSchedCap = 4096;
+constexpr int64_t kSchedOpsCap = 1 << 17;
+constexpr int kSchedMaxPool = 512, kSchedWavePool = 512;
+struct SchedHdr {
+    int32_t state;                 // kSchedTable / kSchedCompiled / kSchedInvalid
+    int32_t n_rounds, depth;       // rounds of the program, entries per ring
+    int32_t n_send;                // tasks that are followed by a transfer
+};
 constexpr int kClasses = 7;                 // lanes per candidate: 64, 32, 16, 8, 4, 2, 1
 constexpr int kMBins = 1024;                // micro-batch count is clamped to this for ordering only
 constexpr int kBinsPerClass = 2 * kMBins;   // schedule x m
@@ -23,6 +34,7 @@ enum {
     H_GPIPE_ITEMS = 17,            // [kClasses] leading wave-items of each class that hold only GPipe candidates
                                    //            (an even number; zero for the class of one lane per candidate)
     H_PAIRS = 24,                  // [2] pairs of wave-items that k_simulate / k_simulate_gpipe take (entries of Workspace::order)
+    H_SCHED_TABLE = 26,            // explicit schedules without a compiled program (k_simulate_explicit takes their candidates)
     H_WORDS = 32
 };
 
@@ -58,6 +70,8 @@ struct Workspace {
     // order[0]: k_simulate's pairs, order[1]: k_simulate_gpipe's.
     int32_t *order[2];             // [order_cap] each
     int64_t order_cap;
+    int64_t *sched_ops;            // [kSchedOpsCap + 8] programs of the explicit schedules, word for word beside schedule_words
+    SchedHdr *sched_hdr;           // [kSchedCap]
 };
 
 inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
@@ -86,6 +100,8 @@ inline size_t carve(Workspace& w, void* base, int32_t L, int32_t V, int64_t C) {
     w.order_cap = (int64_t)(Cc / 2 + kClasses + 1);       // a class of n items has (n + 1) / 2 pairs
     w.order[0] = (int32_t*)take((size_t)w.order_cap * 4);
     w.order[1] = (int32_t*)take((size_t)w.order_cap * 4);
+    w.sched_ops = (int64_t*)take((size_t)(kSchedOpsCap + 8) * 8);
+    w.sched_hdr = (SchedHdr*)take((size_t)kSchedCap * sizeof(SchedHdr));
     return off;
 }
 

@@ -700,6 +700,61 @@ def test_explicit_schedules(H, oracle_mod):
     _timeline_parity(H, oracle_mod, w, np.arange(1, w.C, 3))
 
 
+def test_explicit_schedules_without_a_program(H, oracle_mod):
+    """Schedules that the library does not turn into a program and runs with the table of all task
+    ends instead: a stage whose ends pile up (its consumer's device is busy with another pipeline
+    first: more than 16 ends wait), blocks that lie beyond the first 2^17 words of the schedule array;
+    next to schedules that do get a program.  And the order of the checks: lists that cannot be run to
+    their ends are no strategy, but a candidate's own range check comes first."""
+    _say("[case] explicit schedules without a program")
+    from workloads.schedules import chain, dapple_lists, gpipe_lists, pack_schedule, pack_schedules
+    rng = np.random.default_rng(77)
+    L = 48
+    costs = mk_costs(rng.integers(1, 5000, (2, L)).tolist(), rng.integers(1, 9000, (2, L)).tolist(),
+                     fa=rng.integers(0, 300, (2, L)).tolist(), ba=rng.integers(0, 300, (2, L)).tolist(),
+                     act=(rng.integers(1, 100, (2, L)) * 64).tolist(), grad=rng.integers(1, 1 << 20, (2, L)).tolist(),
+                     tps=(1, 2))
+    N = 64 * 9
+    blocks, rows = [], []
+
+    def add(blk, pp, m, tp=1, bnd=None):
+        blocks.append(blk)
+        rows.append((N // (pp * tp), tp, pp, m, 4, bnd, len(blocks) - 1))
+    # stage 0 (device 0) feeds stage 1 (device 1), which starts only after device 1 has run all of
+    # stage 2, a pipeline of its own
+    for m in (3, 17, 40, 200):
+        stages = [(0, 0, -1), (1, 1, 0), (1, 2, -1)]
+        dev0 = [(0, 0, j) for j in range(m)] + [(1, 0, j) for j in range(m)]
+        dev1 = [(0, 2, j) for j in range(m)] + [(1, 2, j) for j in range(m)] + [(0, 1, j) for j in range(m)] + [(1, 1, j) for j in range(m)]
+        add(pack_schedule(2, stages, m, 3, 1, [dev0, dev1]), 2, m, 1, [0, 10, 30, L])
+        add(pack_schedule(2, stages, m, 3, 2, [dev0, dev1]), 2, m, 2, None)
+    # enough large blocks to pass 2^17 words; candidates on every one of them
+    for q in range(36):
+        pp, m = (16, 128) if q % 2 == 0 else (8, 256)
+        lists = gpipe_lists(pp, m) if q % 3 == 0 else dapple_lists(pp, m)
+        add(pack_schedule(pp, chain(pp), m, pp, 1, lists), pp, m, 1 + q % 2)
+    off, words = pack_schedules(blocks)
+    assert off[-1] > (1 << 17) + 8000 and off[8 + 20] < (1 << 17)
+    # lists that cannot be run (device 1 wants stage 1's backward first), also with times out of range
+    stuck = pack_schedule(2, chain(2), 2, 2, 1, [dapple_lists(2, 2)[0], dapple_lists(2, 2)[1][::-1]])
+    blocks.append(stuck)
+    rows.append((N // 2, 1, 2, 2, 4, None, len(blocks) - 1))
+    off, words = pack_schedules(blocks)
+    for blocking, bucket in ((0, 0), (2, 0), (1, 1 << 20)):
+        w = mk(costs, mk_cluster(N, blocking=blocking, bucket=bucket), rows, name=f"no program, blocking={blocking} bucket={bucket}")
+        w.cand["schedule_off"], w.cand["schedule_words"] = off, words
+        ora = H.oracle_with_table(oracle_mod, w, NT)
+        assert (ora["status"][:-1] == 0).all() and ora["status"][-1] == 1
+        H.assert_same(H.run_hip(w, table=False), ora, what=w.name)
+        _timeline_parity(H, oracle_mod, w, np.arange(0, w.C - 1, 5))
+    huge = dict(costs); huge["fwd_comp_ns"] = costs["fwd_comp_ns"] * (1 << 40)
+    w = mk(huge, mk_cluster(N), rows[:4] + rows[-1:], name="no program, out of range")
+    w.cand["schedule_off"], w.cand["schedule_words"] = off, words
+    ora = H.oracle_with_table(oracle_mod, w, NT)
+    assert (ora["status"] == 2).all()
+    H.assert_same(H.run_hip(w, table=False), ora, what=w.name)
+
+
 def test_uniform_partition_every_shape(H, oracle_mod):
     """The uniform partition rule floor(s L / pp) for every layer count 1..255 and every stage count
     it admits (up to 64), through the level sweeps and, with 2 and 3 chunks, the interleaved kernel."""
