@@ -99,7 +99,13 @@ extern "C" {
                                   cannot be run to its end is invalid, as is a malformed block; one with
                                   S > 64, nparts > 64 or S * m > DISTSIM_MAX_SLOTS is
                                   DISTSIM_ST_UNSUPPORTED.  Per-stage outputs are per device; no stage
-                                  table.                                                           */
+                                  table.  distsim_build_events turns every schedule into a program
+                                  once (the order of the tasks does not depend on the durations) and
+                                  distsim_simulate runs the candidates from it; the schedules after the
+                                  first 4096, those whose blocks reach beyond the first 2^17 words of
+                                  schedule_words and those in which more than 16 ends of one stage wait
+                                  for their consumers at a time take a slower path with the same
+                                  results.                                                         */
 #define DISTSIM_MAX_SLOTS 2048 /* (virtual stage, micro-batch) pairs of an explicit schedule       */
 #define DISTSIM_1F1B_ASYNC 2   /* asynchronous pipeline (Sec. 7, discussion of new algorithms):
                                   the Dapple order without the global synchronisation event, i.e.
