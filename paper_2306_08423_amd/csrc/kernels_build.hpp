@@ -47,6 +47,15 @@ __device__ __forceinline__ bool is_interleaved(const Desc& d) { return ((d.meta 
 // ... and the explicit schedules (k_simulate_explicit); either kind is skipped by the level sweeps.
 __device__ __forceinline__ bool is_explicit(const Desc& d) { return ((d.meta >> 8) & 0xff) == 4; }
 __device__ __forceinline__ bool has_own_kernel(const Desc& d) { return ((d.meta >> 8) & 0xff) >= 3; }
+// Positions in visiting order of class k's interleaved candidates / of those with an explicit schedule.
+__device__ __forceinline__ void interleaved_range(const Workspace& ws, int k, int64_t& lo, int64_t& hi) {
+    lo = ws.bin_start[k * kBinsPerClass + kMBins + kSubVirtual];
+    hi = ws.bin_start[k * kBinsPerClass + kMBins + kSubExplicit];
+}
+__device__ __forceinline__ void explicit_range(const Workspace& ws, int k, int64_t& lo, int64_t& hi) {
+    lo = ws.bin_start[k * kBinsPerClass + kMBins + kSubExplicit];
+    hi = ws.bin_start[(k + 1) * kBinsPerClass];
+}
 
 __device__ __forceinline__ Item decode_item(const int64_t* __restrict__ hdr, int64_t w) {
     int k = 0;
@@ -159,8 +168,10 @@ __global__ __launch_bounds__(kDecodeBlock) void k_decode(CostsDev co, ClusterDev
         bool sup = m <= kMaxM;
         ok = ok && (int64_t)dp * tp * pp == (int64_t)cl.num_devices;
         int64_t parts = pp;                      // parts of the layer partition
+        int64_t slots3 = 0;                      // interleaved: slots per direction of a device's list
         if (ok && sched == 3) {                  // interleaved: pp * chunks virtual stages
             const int64_t vch = ca.chunks ? ca.chunks[c] : 0;      // no chunk counts: invalid
+            slots3 = (int64_t)m * vch;
             parts = (int64_t)pp * vch;
             ok = vch >= 1 && parts <= co.L && m % pp == 0;
             sup = sup && parts <= kMaxPP;
@@ -189,7 +200,11 @@ __global__ __launch_bounds__(kDecodeBlock) void k_decode(CostsDev co, ClusterDev
             int k = 0;                               // class 0 = 64 lanes ... class 6 = 1 lane
             while (k < 6 && (32 >> k) >= pp) k++;
             const int mb = (m < kMBins ? m : kMBins) - 1;
-            const int bin = k * kBinsPerClass + (sched != 0 ? kMBins : 0) + (kMBins - 1 - mb);   // ordered by sweep shape
+            int sub = kMBins - 1 - mb;               // place in its half of the class's bins, longest first
+            if (sched == 3) sub = kSubVirtual + 127 - (int)((slots3 < 2048 ? slots3 : 2047) >> 4);
+            else if (sched == 4) sub = kSubExplicit + 127 - ((m < 2048 ? m : 2047) >> 4);
+            else if (sched != 0) sub = m >= 1024 ? 0 : m > 512 ? (1025 - m) >> 1 : 256 + 512 - m;
+            const int bin = k * kBinsPerClass + (sched != 0 ? kMBins : 0) + sub;   // ordered by sweep shape
             rank[j] = atomicAdd(&hist[bin], 1);
             key[j] = bin | (v << 24);
         } else {

@@ -515,26 +515,29 @@ __device__ __forceinline__ void scheduled_unit(const CostsDev& co, const Cluster
 }
 
 // All classes in one launch, as k_simulate_virtual: class k of the visiting order holds the
-// candidates of 64 >> k lanes; a block is one wavefront.
+// candidates of 64 >> k lanes and keeps those with an explicit schedule side by side; a block is
+// one wavefront.
 __global__ __launch_bounds__(kWave, 4) void k_simulate_scheduled(CostsDev co, ClusterDev cl, CandDev ca, Workspace ws,
                                                                  EventsDev ev, SimOut out) {
     __shared__ SchedLds sm;
-    int64_t next = blockIdx.x;                    // this block's next unit, counted from the first unit of the current classes
-    auto classes = [&](auto width_tag, int cls_lo, int cls_hi) {
+    int64_t next = blockIdx.x;                    // this block's next unit, counted from the first unit of the current class
+    auto one_class = [&](auto width_tag, int cls) {
         constexpr int R = decltype(width_tag)::value, kGroups = kWave / R;
-        const int64_t pos_lo = ws.hdr[H_CLASS_START + cls_lo], pos_end = ws.hdr[H_CLASS_START + cls_hi];
+        int64_t pos_lo, pos_end;
+        explicit_range(ws, cls, pos_lo, pos_end);
         const int64_t units = (pos_end - pos_lo + kGroups - 1) / kGroups;
         for (; next < units; next += gridDim.x)
             scheduled_unit<R>(co, cl, ca, ws, ev, out, pos_lo + next * kGroups, pos_end, sm);
         next -= units;
     };
-    static_assert(kClasses == 7, "one call per class below, the last for the two narrowest");
-    classes(std::integral_constant<int, 64>{}, 0, 1);
-    classes(std::integral_constant<int, 32>{}, 1, 2);
-    classes(std::integral_constant<int, 16>{}, 2, 3);
-    classes(std::integral_constant<int, 8>{}, 3, 4);
-    classes(std::integral_constant<int, 4>{}, 4, 5);
-    classes(std::integral_constant<int, 2>{}, 5, 7);
+    static_assert(kClasses == 7, "one call per class below");
+    one_class(std::integral_constant<int, 64>{}, 0);
+    one_class(std::integral_constant<int, 32>{}, 1);
+    one_class(std::integral_constant<int, 16>{}, 2);
+    one_class(std::integral_constant<int, 8>{}, 3);
+    one_class(std::integral_constant<int, 4>{}, 4);
+    one_class(std::integral_constant<int, 2>{}, 5);
+    one_class(std::integral_constant<int, 2>{}, 6);
 }
 
 }  // namespace distsim

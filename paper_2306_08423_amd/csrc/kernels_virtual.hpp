@@ -362,28 +362,31 @@ __device__ __forceinline__ void virtual_unit(const CostsDev& co, const ClusterDe
 }
 
 // Class k of the visiting order holds the candidates of 64 >> k lanes (pp <= 64 >> k), so that a
-// wavefront takes 1, 2, 4, 8, 16 or 32 of them (the candidates of one device share the groups of
-// two lanes).  The units of all classes are numbered in one sequence, widest class first, and
-// dealt to the blocks in turn; a block is one wavefront.
+// wavefront takes 1, 2, 4, 8, 16 or 32 of them (the candidates of one device use groups of two
+// lanes), and a class keeps its interleaved candidates side by side, longest lists first.  The
+// units of all classes are numbered in one sequence, widest class first, and dealt to the blocks
+// in turn; a block is one wavefront.
 __global__ __launch_bounds__(kWave, 4) void k_simulate_virtual(CostsDev co, ClusterDev cl, CandDev ca, Workspace ws,
                                                             EventsDev ev, SimOut out) {
     __shared__ VirtLds sm;
-    int64_t next = blockIdx.x;                    // this block's next unit, counted from the first unit of the current classes
-    auto classes = [&](auto width_tag, int cls_lo, int cls_hi) {
+    int64_t next = blockIdx.x;                    // this block's next unit, counted from the first unit of the current class
+    auto one_class = [&](auto width_tag, int cls) {
         constexpr int R = decltype(width_tag)::value, kGroups = kWave / R;
-        const int64_t pos_lo = ws.hdr[H_CLASS_START + cls_lo], pos_end = ws.hdr[H_CLASS_START + cls_hi];
+        int64_t pos_lo, pos_end;
+        interleaved_range(ws, cls, pos_lo, pos_end);
         const int64_t units = (pos_end - pos_lo + kGroups - 1) / kGroups;
         for (; next < units; next += gridDim.x)
             virtual_unit<R>(co, cl, ca, ws, ev, out, pos_lo + next * kGroups, pos_end, sm);
         next -= units;
     };
-    static_assert(kClasses == 7, "one call per class below, the last for the two narrowest");
-    classes(std::integral_constant<int, 64>{}, 0, 1);
-    classes(std::integral_constant<int, 32>{}, 1, 2);
-    classes(std::integral_constant<int, 16>{}, 2, 3);
-    classes(std::integral_constant<int, 8>{}, 3, 4);
-    classes(std::integral_constant<int, 4>{}, 4, 5);
-    classes(std::integral_constant<int, 2>{}, 5, 7);
+    static_assert(kClasses == 7, "one call per class below");
+    one_class(std::integral_constant<int, 64>{}, 0);
+    one_class(std::integral_constant<int, 32>{}, 1);
+    one_class(std::integral_constant<int, 16>{}, 2);
+    one_class(std::integral_constant<int, 8>{}, 3);
+    one_class(std::integral_constant<int, 4>{}, 4);
+    one_class(std::integral_constant<int, 2>{}, 5);
+    one_class(std::integral_constant<int, 2>{}, 6);
 }
 
 // Timeline dump of the selected candidates that use the interleaved schedule; one wavefront per

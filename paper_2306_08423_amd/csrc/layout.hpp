@@ -23,6 +23,11 @@ struct SchedHdr {
 constexpr int kClasses = 7;                 // lanes per candidate: 64, 32, 16, 8, 4, 2, 1
 constexpr int kMBins = 1024;                // micro-batch count is clamped to this for ordering only
 constexpr int kBinsPerClass = 2 * kMBins;   // schedule x m
+// The second half of a class's bins (schedules other than GPipe), longest lists first in each part:
+// the level sweeps' schedules by m (pairs of m share a bin above 512), then the interleaved
+// candidates by m * chunks / 16, then those with an explicit schedule by m / 16 -- so that the
+// kernels of the last two find their candidates side by side.
+constexpr int kSubVirtual = 768, kSubExplicit = 896;
 constexpr int kBins = kClasses * kBinsPerClass;
 constexpr int kCombWords = 6;               // int64 words per entry of Workspace::comb
 
