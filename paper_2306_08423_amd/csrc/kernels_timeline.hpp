@@ -253,8 +253,10 @@ __global__ __launch_bounds__(kWave) void k_timeline(CostsDev co, ClusterDev cl, 
                                 const int64_t dur = mt[gi].dur_cnt & (((int64_t)1 << 56) - 1);
                                 const int64_t a = small_double_to_i64(v0[gi]), b = small_double_to_i64(v1[gi]);
                                 const int64_t idx = mt[gi].at + e;
-                                *reinterpret_cast<longlong2*>(out.start + idx) = longlong2{a, b};
-                                *reinterpret_cast<longlong2*>(out.end + idx) = longlong2{a + dur, b + dur};
+                                // written once and not read again by this kernel: streaming stores
+                                typedef long long i64x2 __attribute__((ext_vector_type(2)));
+                                __builtin_nontemporal_store(i64x2{a, b}, reinterpret_cast<i64x2*>(out.start + idx));
+                                __builtin_nontemporal_store(i64x2{a + dur, b + dur}, reinterpret_cast<i64x2*>(out.end + idx));
                             }
                         }
                     } else {
