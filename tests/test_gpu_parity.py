@@ -755,6 +755,19 @@ def test_explicit_schedules_without_a_program(H, oracle_mod):
     H.assert_same(H.run_hip(w, table=False), ora, what=w.name)
 
 
+def test_bench_variants_parity(H, oracle_mod):
+    """The variant workloads that bench.py times (other p2p readings, asynchronous, interleaved and
+    explicit schedules on a seeded sample of hetero64), in the launch shapes of the benchmark: every
+    group of every wavefront of the interleaved and the explicit kernels is filled."""
+    _say("[case] bench variants")
+    import bench
+    w0 = make_workload("hetero64")
+    for name, wv, kernel, counted in bench.variant_workloads(w0, 20000):
+        ora = oracle_mod.simulate(wv, nthreads=NT)
+        assert (ora["status"][counted] == 0).all(), name
+        H.assert_same(H.run_hip(wv, table=False), ora, what="bench variant " + name)
+
+
 def test_uniform_partition_every_shape(H, oracle_mod):
     """The uniform partition rule floor(s L / pp) for every layer count 1..255 and every stage count
     it admits (up to 64), through the level sweeps and, with 2 and 3 chunks, the interleaved kernel."""
