@@ -281,16 +281,29 @@ def test_async_schedule(H, oracle_mod):
     H.assert_same(hip, H.oracle_with_table(oracle_mod, w, NT), what=w.name)
 
 
-@pytest.mark.parametrize("split", [False, True])
+@pytest.mark.parametrize("split", [False, True, "schedules", "schedules, split"])
 def test_graph_capture_and_replay(H, oracle_mod, split):
     """The three calls allocate nothing and never synchronise, so a caller can record them into a
     HIP graph; every replay (with eager work and synchronisation in between) must give the eager
-    result.  split: with the second sweep kernel forked onto the context's stream and joined."""
+    result.  split: with the second sweep kernel forked onto the context's stream and joined.
+    schedules: a list with explicit schedules (compiled inside distsim_build_events, on the
+    context's stream when split) and, in a second list, interleaved candidates."""
     import torch
     import paper_2306_08423_amd as ds
     _say(f"[case] graph capture split={split}")
     w = make_workload("gpt48")
-    c = H.ctx_split() if split else H.ctx()
+    if isinstance(split, str):
+        import bench
+        ws = {name: wv for name, wv, _, _ in bench.variant_workloads(w, 600)}
+        for name in ("explicit_lists", "interleaved_2_chunks"):
+            _graph_replay_case(H, oracle_mod, ws[name], H.ctx_split() if "split" in split.split(", ")[1:] else H.ctx())
+        return
+    _graph_replay_case(H, oracle_mod, w, H.ctx_split() if split else H.ctx())
+
+
+def _graph_replay_case(H, oracle_mod, w, c):
+    import torch
+    import paper_2306_08423_amd as ds
     dw = ds.upload(w, c.device)
     ev = ds.alloc_events(c, dw.L, dw.V, dw.C, ds.stage_entries(w.cand["pp"]), table=False)
     out = ds.alloc_outputs(c, ev, util=True)
@@ -301,9 +314,16 @@ def test_graph_capture_and_replay(H, oracle_mod, split):
         ds.distsim_simulate(c, dw, ev, out)
         ds.distsim_search(c, out.batch_ns, dw.C, best, scratch)
 
+    def results():
+        # per-stage entries by candidate: where a candidate's block lies may differ between runs
+        # (the order of candidates that share an ordering bin), what it holds may not
+        rows, _ = ds.stage_rows(ev.status.cpu().numpy()[:dw.C], ev.stage_pos.cpu().numpy()[:dw.C], w.cand["pp"])
+        rows = torch.as_tensor(rows, device=out.comp_busy_ns.device)
+        return (out.batch_ns.clone(), out.comp_busy_ns[rows].clone(), out.comm_busy_ns[rows].clone(), best.clone())
+
     step()
     torch.cuda.synchronize()
-    want = (out.batch_ns.clone(), out.comp_busy_ns.clone(), out.comm_busy_ns.clone(), best.clone())
+    want = results()
     side = torch.cuda.Stream()
     side.wait_stream(torch.cuda.current_stream())
     with torch.cuda.stream(side):
@@ -319,8 +339,7 @@ def test_graph_capture_and_replay(H, oracle_mod, split):
         torch.cuda.synchronize()
         g.replay()
         torch.cuda.synchronize()
-        got = (out.batch_ns, out.comp_busy_ns, out.comm_busy_ns, best)
-        for a, b in zip(got, want):
+        for a, b in zip(results(), want):
             assert torch.equal(a, b), rep
         step()                                             # eager work between replays
         torch.cuda.synchronize()
