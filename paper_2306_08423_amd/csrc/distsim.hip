@@ -446,15 +446,10 @@ int distsim_simulate(distsim_ctx* ctx, const distsim_cluster* cluster, const dis
             const unsigned blocks = (unsigned)(C < most ? C : most);
             hipLaunchKernelGGL(k_simulate_scheduled, dim3(blocks), dim3(kWave), 0, st, co, cl, ca, ws, ev, out);
         }
-        // the others (none as a rule: every block ends at once then): one launch per LDS size (by the
-        // schedule's number of stage x micro-batch pairs)
-        const int64_t most = (int64_t)ctx->num_cus * 32;
+        // the others (none as a rule: every block ends at once then)
+        const int64_t most = (int64_t)ctx->num_cus * 16;
         const unsigned blocks = (unsigned)(C < most ? C : most);
-        static_assert(kMaxSlots == 2048, "the launches below cover schedules of up to 2048 pairs");
-        hipLaunchKernelGGL(k_simulate_explicit<2048>, dim3(blocks), dim3(kWave), 0, st, co, cl, ca, ws, ev, out, 1024);
-        hipLaunchKernelGGL(k_simulate_explicit<1024>, dim3(blocks), dim3(kWave), 0, st, co, cl, ca, ws, ev, out, 512);
-        hipLaunchKernelGGL(k_simulate_explicit<512>, dim3(blocks), dim3(kWave), 0, st, co, cl, ca, ws, ev, out, 256);
-        hipLaunchKernelGGL(k_simulate_explicit<256>, dim3(blocks), dim3(kWave), 0, st, co, cl, ca, ws, ev, out, 0);
+        hipLaunchKernelGGL(k_simulate_explicit, dim3(blocks), dim3(kWave), 0, st, co, cl, ca, ws, ev, out);
     }
     HIP_TRY(hipGetLastError());
     return DISTSIM_OK;

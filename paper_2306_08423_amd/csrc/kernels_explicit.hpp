@@ -5,7 +5,8 @@
 // its list and runs it if its input is there: start = max(device free, end of the producing task
 // + p2p event), the rule of Algorithm 1.  A round in which no lane can run a task ends the loop:
 // the schedule cannot be run to its end and the candidate is invalid.  Same arithmetic as the
-// level sweeps: fp64 values that are integers below 2^53.  The slow path: generality, not speed.
+// level sweeps: fp64 values that are integers below 2^53.  The slow path: generality, not speed
+// (the schedules that get a program, nearly all, run through kernels_schedule.hpp instead).
 #pragma once
 #include "kernels_virtual.hpp"
 
@@ -323,14 +324,12 @@ __device__ __forceinline__ void explicit_candidate(const CostsDev& co, const Clu
     }
 }
 
-// One launch per LDS size: the candidates whose schedule has more than slots_above and at most
-// SLOTS (virtual stage, micro-batch) pairs, so that small schedules take little LDS and more of
-// them are resident.  Every launch walks the whole visiting order and takes its own.
-template <int SLOTS>
+// The candidates whose schedule k_compile_schedules left without a program (none as a rule: every
+// block ends at once then); one wavefront per candidate, LDS for the largest schedule.  Walks the
+// whole visiting order.
 __global__ __launch_bounds__(kWave) void k_simulate_explicit(CostsDev co, ClusterDev cl, CandDev ca, Workspace ws,
-                                                             EventsDev ev, SimOut out, int slots_above) {
-    __shared__ ExplicitLds<SLOTS> sm;
-    // only the candidates of schedules that k_compile_schedules left to this kernel
+                                                             EventsDev ev, SimOut out) {
+    __shared__ ExplicitLds<kMaxSlots> sm;
     if (ws.hdr[H_SCHED_TABLE] == 0) return;
     // descriptors beyond the valid candidates were never written: the class table bounds them
     const int64_t pos_end = ws.hdr[H_CLASS_START + kClasses];
@@ -341,8 +340,6 @@ __global__ __launch_bounds__(kWave) void k_simulate_explicit(CostsDev co, Cluste
                               ds.cand};
         if (xc.id < kSchedCap && ws.sched_hdr[xc.id].state != 0) continue;      // 0: no program
         // k_decode has checked the head of the block: 1 <= S <= 64, S * m <= kMaxSlots
-        const int slots = ca.schedule_words[ca.schedule_off[xc.id] + 1] * xc.m;
-        if (slots <= slots_above || slots > SLOTS) continue;
         explicit_candidate<false>(co, cl, ca, ws, ev, out, xc, VirtDump{}, sm);
     }
 }
