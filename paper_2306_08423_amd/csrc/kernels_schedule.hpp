@@ -517,7 +517,7 @@ __device__ __forceinline__ void scheduled_unit(const CostsDev& co, const Cluster
 // All classes in one launch, as k_simulate_virtual: class k of the visiting order holds the
 // candidates of 64 >> k lanes and keeps those with an explicit schedule side by side; a block is
 // one wavefront.
-__global__ __launch_bounds__(kWave, 4) void k_simulate_scheduled(CostsDev co, ClusterDev cl, CandDev ca, Workspace ws,
+__global__ __launch_bounds__(kWave, 3) void k_simulate_scheduled(CostsDev co, ClusterDev cl, CandDev ca, Workspace ws,
                                                                  EventsDev ev, SimOut out) {
     __shared__ SchedLds sm;
     int64_t next = blockIdx.x;                    // this block's next unit, counted from the first unit of the current class
