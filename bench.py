@@ -135,6 +135,12 @@ def time_variants(ds, ctx, w, n):
         res[name] = {"candidates": int(dwv.C), "valid": int(ok.sum()), "ms_per_step": dt * 1e3, "kernel": kernel,
                      "kernel_ms": k_ms, "kernel_candidates": n_counted,
                      "kernel_candidates_per_s": n_counted / (k_ms / 1e3) if k_ms > 0 else None}
+        if name == "explicit_lists":
+            # the schedules are turned into programs once per distsim_build_events (k_simulate_explicit's
+            # timer spans the kernel that runs the candidates from them and the one for schedules without)
+            cms, ccnt = ktv["k_compile_schedules"]
+            res[name]["compile_schedules_ms"] = cms / max(ccnt, 1)
+            res[name]["schedules"] = int(len(wv.cand["schedule_off"]) - 1)
         del dwv, evv, outv, bestv, scr
     return res
 
