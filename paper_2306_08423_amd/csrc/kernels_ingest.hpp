@@ -27,40 +27,82 @@ __global__ __launch_bounds__(256) void k_dedup_clear(int32_t* __restrict__ table
 // record that finds it empty; records with equal words join the slot and lower its entry to the
 // smallest index among them, records with other words probe on.  The table has at least 2n
 // slots, so every probe sequence meets an empty slot within `size` steps.
-__global__ __launch_bounds__(256) void k_dedup_insert(const int64_t* __restrict__ rec, int64_t n, int K,
-                                                      int32_t* table, int64_t size, int32_t* __restrict__ slot_of) {
-    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= n) return;
+// Equal records are merged inside the workgroup first (a small table in LDS over the workgroup's
+// own records, same probing): only one record per distinct operator of the workgroup, carrying the
+// smallest index among its equals, goes to the table in memory, and the others take its slot.  A
+// popular operator is in nearly every wavefront; without the merge all of them would read the same
+// slot and the same representative record, one L2 channel serving them one after the other.
+constexpr int kDedupBlock = 512, kDedupLocal = 2 * kDedupBlock;
+__global__ __launch_bounds__(kDedupBlock) void k_dedup_insert(const int64_t* __restrict__ rec, int64_t n, int K,
+                                                              int32_t* table, int64_t size, int32_t* __restrict__ slot_of) {
+    __shared__ int32_t local[kDedupLocal];      // thread that claimed the local slot | bits of its hash << 9, -1 = empty
+    __shared__ int32_t lowest[kDedupBlock];     // by claiming thread: smallest record index among its equals
+    __shared__ int32_t global_slot[kDedupBlock];
+    const int tid = threadIdx.x;
+    const int64_t base = (int64_t)blockIdx.x * kDedupBlock, i = base + tid;
+    for (int q = tid; q < kDedupLocal; q += kDedupBlock) local[q] = -1;
+    lowest[tid] = INT32_MAX;
+    __syncthreads();
     int64_t w[kMaxRecordWords];
     uint64_t h = 0;
+    int leader = -1;
+    if (i < n) {
 #pragma unroll
-    for (int k = 0; k < kMaxRecordWords; k++) {
-        if (k < K) { w[k] = rec[i * K + k]; h = mix64(h ^ (uint64_t)w[k]); }
-    }
-    int64_t slot = (int64_t)(h & (uint64_t)(size - 1));
-    int32_t found = -1;
-    for (int64_t probe = 0; probe < size && found < 0; probe++) {
-        // look before locking: popular operators are met millions of times, and a record that
-        // finds its slot already held by an equal record of lower index has nothing to write
-        // (an ordinary load: a stale value only costs an atomic that changes nothing, because
-        // a slot goes from empty to an index and then only to lower indices of equal records)
-        int32_t cur = table[slot];
-        if (cur == -1) {
-            cur = atomicCAS(&table[slot], -1, (int32_t)i);
-            if (cur == -1) { found = (int32_t)slot; break; }
+        for (int k = 0; k < kMaxRecordWords; k++) {
+            if (k < K) { w[k] = rec[i * K + k]; h = mix64(h ^ (uint64_t)w[k]); }
         }
-        bool same = true;
+        // the workgroup's own table: other bits of the hash than the table in memory uses
+        // an entry is the claiming thread and 22 more bits of its hash, so that records are compared
+        // word for word only when those agree
+        static_assert(kDedupBlock == 512, "nine bits for the thread");
+        int pos = (int)(h >> 40) & (kDedupLocal - 1);
+        const int32_t mine = (int32_t)((h >> 8 & 0x3fffff) << 9) | tid;
+        for (int probe = 0; probe < kDedupLocal && leader < 0; probe++) {
+            int32_t cur = local[pos];
+            if (cur == -1) {
+                cur = atomicCAS(&local[pos], -1, mine);
+                if (cur == -1) { leader = tid; break; }
+            }
+            bool same = (cur >> 9) == (mine >> 9);
+            if (same) {
 #pragma unroll
-        for (int k = 0; k < kMaxRecordWords; k++)
-            if (k < K && rec[(int64_t)cur * K + k] != w[k]) same = false;
-        if (same) {
-            if (cur > (int32_t)i) atomicMin(&table[slot], (int32_t)i);
-            found = (int32_t)slot;
-        } else {
-            slot = (slot + 1) & (size - 1);
+                for (int k = 0; k < kMaxRecordWords; k++)
+                    if (k < K && rec[(base + (cur & 511)) * K + k] != w[k]) same = false;
+            }
+            if (same) leader = cur & 511;
+            else pos = (pos + 1) & (kDedupLocal - 1);
         }
+        if (leader >= 0) atomicMin(&lowest[leader], (int32_t)i);
     }
-    slot_of[i] = found;
+    __syncthreads();
+    if (i < n && leader == tid) {
+        const int32_t first = lowest[tid];          // stands for all its equals in the workgroup
+        int64_t slot = (int64_t)(h & (uint64_t)(size - 1));
+        int32_t found = -1;
+        for (int64_t probe = 0; probe < size && found < 0; probe++) {
+            // look before locking (an ordinary load: a stale value only costs an atomic that changes
+            // nothing, because a slot goes from empty to an index and then only to lower indices of
+            // equal records)
+            int32_t cur = table[slot];
+            if (cur == -1) {
+                cur = atomicCAS(&table[slot], -1, first);
+                if (cur == -1) { found = (int32_t)slot; break; }
+            }
+            bool same = true;
+#pragma unroll
+            for (int k = 0; k < kMaxRecordWords; k++)
+                if (k < K && rec[(int64_t)cur * K + k] != w[k]) same = false;
+            if (same) {
+                if (cur > first) atomicMin(&table[slot], first);
+                found = (int32_t)slot;
+            } else {
+                slot = (slot + 1) & (size - 1);
+            }
+        }
+        global_slot[tid] = found;
+    }
+    __syncthreads();
+    if (i < n) slot_of[i] = leader >= 0 ? global_slot[leader] : -1;
 }
 
 // Exclusive prefix count of the first occurrences (records that are their slot's entry), per
