@@ -582,15 +582,16 @@ __global__ __launch_bounds__(256) void k_stage_events(CostsDev co, ClusterDev cl
         nar = group_sum(nar, width);
         const int lo_w = drop ? 0 : cur.lo, hi_w = drop ? 0 : cur.hi;
         const int64_t i = w * kWave + lane;
-        ev.stage_tab[0 * cap + i] = r.FC;
-        ev.stage_tab[1 * cap + i] = r.FA;
-        ev.stage_tab[2 * cap + i] = r.BC;
-        ev.stage_tab[3 * cap + i] = r.BA;
-        ev.stage_tab[4 * cap + i] = r.PF;
-        ev.stage_tab[5 * cap + i] = r.PB;
-        ev.stage_tab[6 * cap + i] = r.G;
-        ev.stage_tab[7 * cap + i] = AR;
-        ev.stage_layers[i] = lo_w | (hi_w << 8);
+        // written once and not read again by the library: streaming stores
+        __builtin_nontemporal_store(r.FC, &ev.stage_tab[0 * cap + i]);
+        __builtin_nontemporal_store(r.FA, &ev.stage_tab[1 * cap + i]);
+        __builtin_nontemporal_store(r.BC, &ev.stage_tab[2 * cap + i]);
+        __builtin_nontemporal_store(r.BA, &ev.stage_tab[3 * cap + i]);
+        __builtin_nontemporal_store(r.PF, &ev.stage_tab[4 * cap + i]);
+        __builtin_nontemporal_store(r.PB, &ev.stage_tab[5 * cap + i]);
+        __builtin_nontemporal_store(r.G, &ev.stage_tab[6 * cap + i]);
+        __builtin_nontemporal_store(AR, &ev.stage_tab[7 * cap + i]);
+        __builtin_nontemporal_store((int32_t)(lo_w | (hi_w << 8)), &ev.stage_layers[i]);
         if (act && s == 0) {
             const int64_t c = d.cand;
             if (drop) {
