@@ -41,9 +41,10 @@ __device__ __forceinline__ Best wave_best(Best a) {
 
 constexpr int kSearchBlock = 256;
 // Eight workgroups per CU, i.e. every wavefront slot of the chip once: a list long enough for HBM
-// to matter (2^27 candidates) streams at 5.0 TB/s that way, against 3.3 TB/s with half as many
-// workgroups and 4.4 to 4.8 TB/s with two or four times as many; several loads per thread and
-// turn (strided) were slower than one (4.7 TB/s).
+// to matter (2^27 candidates) streams at 5.0 TB/s that way with one 8-byte load per candidate,
+// against 3.3 TB/s with half as many workgroups and 4.4 to 4.8 TB/s with two or four times as many;
+// several loads per thread and turn (strided) were slower than one (4.7 TB/s); two neighbouring
+// candidates per 16-byte non-temporal load: 6.4 TB/s.
 constexpr int kSearchMaxBlocks = 2048;
 
 template <int OBJ>
@@ -66,11 +67,28 @@ __global__ __launch_bounds__(kSearchBlock) void k_search_partial(const int64_t* 
     // candidates meet does not matter (ties go to the lowest index inside better())
     Best a{-1, INT64_MAX, 1};
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-    for (int64_t c = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; c < C; c += stride) {
-        Best b{c, batch_ns[c], 1};
-        if (b.val == INT64_MAX) continue;
-        if (OBJ == 1) { b.wgt = weight[c]; if (b.wgt <= 0) continue; }
+    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    auto take = [&](int64_t c, int64_t val, int64_t wgt) {
+        Best b{c, val, wgt};
+        if (b.val == INT64_MAX) return;
+        if (OBJ == 1 && b.wgt <= 0) return;
         if (better<OBJ>(b, a)) a = b;
+    };
+    typedef long long i64x2 __attribute__((ext_vector_type(2)));
+    const bool wide = (((uintptr_t)batch_ns | (OBJ == 1 ? (uintptr_t)weight : 0)) & 15) == 0;
+    if (wide) {
+        // two candidates per load, read once and never again: 16-byte streaming loads
+        const int64_t pairs = C / 2;
+        for (int64_t q = t; q < pairs; q += stride) {
+            const i64x2 v = __builtin_nontemporal_load(reinterpret_cast<const i64x2*>(batch_ns) + q);
+            i64x2 g{1, 1};
+            if (OBJ == 1) g = __builtin_nontemporal_load(reinterpret_cast<const i64x2*>(weight) + q);
+            take(2 * q, v.x, g.x);
+            take(2 * q + 1, v.y, g.y);
+        }
+        if ((C & 1) && t == 0) take(C - 1, batch_ns[C - 1], OBJ == 1 ? weight[C - 1] : 1);
+    } else {
+        for (int64_t c = t; c < C; c += stride) take(c, batch_ns[c], OBJ == 1 ? weight[c] : 1);
     }
     a = block_best<OBJ>(a);
     if (threadIdx.x == 0) partial[blockIdx.x] = a;
