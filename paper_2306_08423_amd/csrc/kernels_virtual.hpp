@@ -38,7 +38,7 @@ struct VirtStage {                              // one virtual stage: task durat
     double dur_f, lat_f, dur_b, lat_b;
 };
 struct VirtLds {
-    static constexpr int kDepth = 4, kStages = 2 * kWave;
+    static constexpr int kDepth = 2, kStages = 2 * kWave;
     // first index of the rings and counters: direction, 0 = forward, 1 = backward
     double ring[2][kDepth][kWave];              // by slot modulo kDepth and lane: what the next device reads
     double wrap[2][kWave];                      // R slots per candidate, slot modulo R: the same from the direction's last device
@@ -366,7 +366,7 @@ __device__ __forceinline__ void virtual_unit(const CostsDev& co, const ClusterDe
 // lanes), and a class keeps its interleaved candidates side by side, longest lists first.  The
 // units of all classes are numbered in one sequence, widest class first, and dealt to the blocks
 // in turn; a block is one wavefront.
-__global__ __launch_bounds__(kWave, 4) void k_simulate_virtual(CostsDev co, ClusterDev cl, CandDev ca, Workspace ws,
+__global__ __launch_bounds__(kWave, 5) void k_simulate_virtual(CostsDev co, ClusterDev cl, CandDev ca, Workspace ws,
                                                             EventsDev ev, SimOut out) {
     __shared__ VirtLds sm;
     int64_t next = blockIdx.x;                    // this block's next unit, counted from the first unit of the current class
