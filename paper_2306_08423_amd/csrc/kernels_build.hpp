@@ -181,7 +181,7 @@ __global__ __launch_bounds__(kDecodeBlock) void k_decode(CostsDev co, ClusterDev
             ok = id >= 0 && id < ca.n_schedules && ca.schedule_off && ca.schedule_words;
             if (ok) {
                 const int64_t o = ca.schedule_off[id], n = ca.schedule_off[id + 1] - o;
-                ok = o >= 0 && n >= 5 + pp + 1 && o + n <= ca.schedule_words_len;
+                ok = o >= 0 && n >= 5 + pp + 1 && o <= ca.schedule_words_len && n <= ca.schedule_words_len - o;      // (no sum that could wrap)
                 if (ok) {
                     const int32_t* w = ca.schedule_words + o;
                     parts = w[3];

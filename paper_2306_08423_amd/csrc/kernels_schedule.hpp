@@ -72,7 +72,10 @@ __global__ __launch_bounds__(kWave) void k_compile_schedules(CandDev ca, Workspa
         };
         const int64_t woff = ca.schedule_off[id], nwords = ca.schedule_off[id + 1] - woff;
         // a block that is not there, or has no room for a head: no candidate passes k_decode with it
-        if (woff < 0 || nwords < 6 || woff + nwords > ca.schedule_words_len) { state = kSchedInvalid; done(); continue; }
+        // (written so that offsets near 2^63 cannot wrap the sum)
+        if (woff < 0 || nwords < 6 || woff > ca.schedule_words_len || nwords > ca.schedule_words_len - woff) {
+            state = kSchedInvalid; done(); continue;
+        }
         const int32_t* w = ca.schedule_words + woff;
         const int pp = w[0], S = w[1], m = w[2], nparts = w[3];
         // beyond the program's limits (k_decode reports such candidates as beyond the library anyway)
