@@ -103,9 +103,9 @@ extern "C" {
                                   once (the order of the tasks does not depend on the durations) and
                                   distsim_simulate runs the candidates from it; the schedules after the
                                   first 4096, those whose blocks reach beyond the first 2^17 words of
-                                  schedule_words and those in which more than 16 ends of one stage wait
-                                  for their consumers at a time take a slower path with the same
-                                  results.                                                         */
+                                  schedule_words and those in which more than min(16, 128 / S) ends of
+                                  one stage wait for their consumers at a time take a slower path with
+                                  the same results.                                                */
 #define DISTSIM_MAX_SLOTS 2048 /* (virtual stage, micro-batch) pairs of an explicit schedule       */
 #define DISTSIM_1F1B_ASYNC 2   /* asynchronous pipeline (Sec. 7, discussion of new algorithms):
                                   the Dapple order without the global synchronisation event, i.e.

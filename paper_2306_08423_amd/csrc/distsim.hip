@@ -441,7 +441,7 @@ int distsim_simulate(distsim_ctx* ctx, const distsim_cluster* cluster, const dis
         Timer t(ctx, st, DISTSIM_K_SIMULATE_EXPLICIT);
         {
             // those whose schedule has a program: one launch for all classes, a block is one wavefront
-            // with 18 KB of LDS; four times as many blocks as fit, as for the interleaved schedule
+            // with 12 KB of LDS; more blocks than fit, so that the order in which they start evens out their lengths
             const int64_t most = (int64_t)ctx->num_cus * 32;
             const unsigned blocks = (unsigned)(C < most ? C : most);
             hipLaunchKernelGGL(k_simulate_scheduled, dim3(blocks), dim3(kWave), 0, st, co, cl, ca, ws, ev, out);

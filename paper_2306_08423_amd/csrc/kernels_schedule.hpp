@@ -225,7 +225,7 @@ struct SchedStage {                             // task durations; the latency a
     double dur_f, add_f, dur_b, add_b;          // or, with link queues, the transfer that follows the task
 };
 struct SchedLds {
-    static constexpr int kStages = 2 * kWave, kRing = 8, kBatch = 4;
+    static constexpr int kStages = kWave, kRing = 8, kBatch = 4;
     double pool[kSchedWavePool];                // ring entries: ends of tasks, as their consumers see them
     alignas(32) SchedStage st[kStages];
     int64_t own_p2p[kStages];                   // by stage: p2p event of the edge from its prev (set-up only)

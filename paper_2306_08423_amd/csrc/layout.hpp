@@ -14,7 +14,7 @@ constexpr int kMaxSlots = 2048;             // (virtual stage, micro-batch) pair
 // pool has at most kSchedMaxPool entries, the candidates of a wavefront share kSchedWavePool.
 constexpr int kSchedCap = 4096;
 constexpr int64_t kSchedOpsCap = 1 << 17;
-constexpr int kSchedMaxPool = 512, kSchedWavePool = 512;
+constexpr int kSchedMaxPool = 256, kSchedWavePool = 256;
 struct SchedHdr {
     int32_t state;                 // kSchedTable / kSchedCompiled / kSchedInvalid
     int32_t n_rounds, depth;       // rounds of the program, entries per ring
