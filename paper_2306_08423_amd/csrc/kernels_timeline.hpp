@@ -402,7 +402,8 @@ __global__ __launch_bounds__(256) void k_bubbles(CandDev ca, const int32_t* __re
         return;
     }
     const int per_kind = pp * m;                          // <= 64 * 65536
-    for (int t = threadIdx.x; t < 2 * per_kind; t += blockDim.x) {
+    // the task in front of task t on its device: index into start / end, -1 = none
+    auto predecessor = [&](int t) -> int64_t {
         const int kind = t >= per_kind ? 1 : 0;
         const int r = t - kind * per_kind;
         const int s = r / m, j = r - s * m;
@@ -421,8 +422,26 @@ __global__ __launch_bounds__(256) void k_bubbles(CandDev ca, const int32_t* __re
                 else { pk = 0; pj = m - 1; }
             }
         }
-        const int64_t before = pk < 0 ? 0 : end[off + ((int64_t)pk * pp + s) * m + pj];
-        idle[off + t] = start[off + t] - before;
+        return pk < 0 ? -1 : off + ((int64_t)pk * pp + s) * m + pj;
+    };
+    // four tasks per thread and turn, all their loads before the first store: the kernel waits for
+    // memory, not for arithmetic
+    constexpr int kPer = 4;
+    const int total = 2 * per_kind;
+    for (int t0 = threadIdx.x; t0 < total; t0 += kPer * blockDim.x) {
+        int64_t st[kPer], before[kPer];
+#pragma unroll
+        for (int u = 0; u < kPer; u++) {
+            const int t = t0 + u * blockDim.x;
+            const int64_t p = t < total ? predecessor(t) : -1;
+            st[u] = t < total ? start[off + t] : 0;
+            before[u] = p >= 0 ? end[p] : 0;
+        }
+#pragma unroll
+        for (int u = 0; u < kPer; u++) {
+            const int t = t0 + u * blockDim.x;
+            if (t < total) idle[off + t] = st[u] - before[u];
+        }
     }
 }
 
