@@ -113,6 +113,34 @@ __device__ __forceinline__ double max_f64(double a, double b) {
     return r;
 }
 
+// Sum / maximum of doubles over aligned groups of `width` lanes, as group_reduce does for integers.
+template <int CTRL>
+__device__ __forceinline__ double dpp_f64(double v) {
+    return __longlong_as_double(dpp_i64<CTRL>(__double_as_longlong(v)));
+}
+__device__ __forceinline__ double readlane_f64(double v, int l) {
+    return __longlong_as_double(readlane_i64(__double_as_longlong(v), l));
+}
+template <typename Op>
+__device__ __forceinline__ double group_reduce_f64(double v, int width, Op op) {
+    if (width >= 2) v = op(v, dpp_f64<kDppXor1>(v));
+    if (width >= 4) v = op(v, dpp_f64<kDppXor2>(v));
+    if (width >= 8) v = op(v, dpp_f64<kDppHalfMirror>(v));
+    if (width >= 16) v = op(v, dpp_f64<kDppMirror>(v));
+    if (width >= 32) {
+        const double a = op(readlane_f64(v, 0), readlane_f64(v, 16));
+        const double b = op(readlane_f64(v, 32), readlane_f64(v, 48));
+        v = width == 64 ? op(a, b) : ((threadIdx.x & 32) ? b : a);
+    }
+    return v;
+}
+__device__ __forceinline__ double group_sum_f64(double v, int width) {
+    return group_reduce_f64(v, width, [](double x, double y) { return x + y; });
+}
+__device__ __forceinline__ double group_max_f64(double v, int width) {
+    return group_reduce_f64(v, width, [](double x, double y) { return max_f64(x, y); });
+}
+
 // Exact conversion of a double that holds an integer of [0, 2^53) (five instructions).
 __device__ __forceinline__ int64_t double_to_i64(double d) {
     const uint32_t hi = (uint32_t)(d * (1.0 / 4294967296.0));              // truncates

@@ -144,24 +144,6 @@ __device__ __forceinline__ double from_lanes(double x, int byte_addr) {
         : [o_] "+v"(o), [tl_] "+v"(tl), [tr_] "+v"(tr)                        \
         : [kf] "s"(kmask), [kb] "s"(kmask2), [cl__] "v"(cl_), [cr__] "v"(cr_), [df_] "v"(df), [db_] "v"(db))
 
-// Two chained tasks of one lane at one level: the first takes its operand from a neighbour lane
-// (t), the second from the first (two stages of one candidate held by one lane).  Both run under
-// the one mask taken from the pattern.
-#define DISTSIM_DSTEP(bits, o1st, o2nd, t, lat1st, dur1st, lat2nd, dur2nd)     \
-    asm volatile(                                                              \
-        "v_add_co_u32_e64 %[p], %[k], %[p], %[p]\n\t"                        \
-        "s_mov_b64 exec, %[k]\n\t"                                            \
-        "v_add_f64 %[t_], %[t_], %[ca]\n\t"                                   \
-        "v_max_f64 %[t_], %[t_], %[oa]\n\t"                                   \
-        "v_add_f64 %[oa], %[t_], %[da]\n\t"                                   \
-        "v_add_f64 %[t_], %[oa], %[cb]\n\t"                                   \
-        "v_max_f64 %[t_], %[t_], %[ob]\n\t"                                   \
-        "v_add_f64 %[ob], %[t_], %[db]\n\t"                                   \
-        "s_mov_b64 exec, -1\n\t"                                              \
-        "s_nop 0"                                                              \
-        : [oa] "+v"(o1st), [ob] "+v"(o2nd), [t_] "+v"(t), [p] "+v"(bits), [k] "=&s"(kmask) \
-        : [ca] "v"(lat1st), [da] "v"(dur1st), [cb] "v"(lat2nd), [db] "v"(dur2nd))
-
 // One level of the sweep with queues on the links (p2p_blocking = 2), for the lanes whose pattern bit
 // is set: the task starts at max(own, arrival of the neighbour's latest send) -- `gate` is 0 for a
 // lane that has that neighbour and -inf for one that has not --, and its own send leaves when the
@@ -221,97 +203,61 @@ struct Park {
     int32_t misc[2][kSimBlock];        // layer bounds, flags, variant
 };
 
-// GPipe sweep of two items of one shape with the stages regrouped two to a lane.  In the usual
-// layout item u, lane l holds one stage and every level moves the neighbour's value across
-// lanes.  Here lane x holds the stages of the linear positions 2x and 2x + 1 (position = 64 u +
-// l), i.e. two neighbouring stages of one candidate (candidates take an even number of lanes:
-// sh >= 1), and a level runs both: forwards F(2i, j) then F(2i+1, j), whose operand is the
-// lane's own first result; backwards B(2i+1, j) then B(2i, j).  Levels, for pair i of a
-// candidate with I = ceil(pp / 2) pairs: forwards i + j, backwards (m + I - 1) + (I - 1 - i) + j.
-// One cross-lane move serves two stage-tasks and the ramps are half as long.  Edges that do not
-// exist carry -inf, stages that do not exist have zero durations, as in the usual layout.
-// The two items may differ in shape (pp, m of a lane's candidate); they share the lanes per
-// candidate.  xp: 128 doubles of LDS owned by this wavefront.
-__device__ __forceinline__ void sweep_gpipe_pair(Sweep (&sw)[2], int sh, int lane, const int (&pp)[2],
-                                                 const int (&m)[2], double* xp) {
-    auto regroup = [&](double a, double b, double& x0, double& x1) {
-        xp[lane] = a;
-        xp[kWave + lane] = b;
-        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-        const double2 v = reinterpret_cast<const double2*>(xp)[lane];
-        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");       // read before the next overwrite
-        x0 = v.x; x1 = v.y;
-    };
-    double F0, F1, B0, B1, pl0, pl1, pr0, pr1;
-    regroup(sw[0].Fd, sw[1].Fd, F0, F1);
-    regroup(sw[0].Bd, sw[1].Bd, B0, B1);
-    regroup(sw[0].pfL, sw[1].pfL, pl0, pl1);
-    regroup(sw[0].pbR, sw[1].pbR, pr0, pr1);
-    // shape of the candidate whose stages this lane now holds
-    const int src = 2 * (lane & 31);
-    const int mp0 = __shfl(m[0] | (pp[0] << 24), src, kWave), mp1 = __shfl(m[1] | (pp[1] << 24), src, kWave);
-    const int mp = lane < 32 ? mp0 : mp1;
-    const int mm = mp & 0xffffff, I = ((mp >> 24) + 1) >> 1;       // mm = 0: no candidate here
-    const int i = (src & ((1 << sh) - 1)) >> 1;
-    const bool on = mm > 0;
-    const int blo = mm + 2 * I - 2 - 2 * i, bhi = blo + mm - 1;    // on x = level - i
-    const int gLastF = wave_max_i32(on ? i + mm - 1 : -1);
-    const int gFirstB = -wave_max_i32(on ? -(i + blo) : -(1 << 30));
-    const int gLastB = wave_max_i32(on ? i + bhi : -1);
-    const int nlev = gLastB + 1;
-    double own0 = 0.0, own1 = 0.0;
-    uint64_t kmask;
-    for (int l0 = 0; l0 < nlev; l0 += 32) {
-        const int x0 = l0 - i;
-        uint32_t PFb = on ? level_bits(-x0, mm - 1 - x0) : 0u;
-        uint32_t PBb = on ? level_bits(blo - x0, bhi - x0) : 0u;
-        // chunk-relative levels with forwards [0, lastF] and with backwards [firstB, lastB]
-        const bool anyF = gLastF >= l0, anyB = gFirstB < l0 + 32;
-        const int lastF = anyF ? (gLastF - l0 < 31 ? gLastF - l0 : 31) : -1;
-        const int firstB = anyB ? (gFirstB > l0 ? gFirstB - l0 : 0) : 64;
-        const int lastB = anyB ? (gLastB - l0 < 31 ? gLastB - l0 : 31) : -1;
-        // forwards only, then levels that have both kinds (candidates of different length in one
-        // wavefront), then backwards only; a pattern is shifted up to the level of its first use
-        const int onlyF = lastF + 1 < firstB ? lastF + 1 : firstB;
-        int k = 0;
-        for (; k < onlyF; k++) {
-            double t = from_prev_lane(own1);
-            DISTSIM_DSTEP(PFb, own0, own1, t, pl0, F0, pl1, F1);
-        }
-        if (k <= lastF) {
-            PBb = shl32(PBb, k);
-            for (; k <= lastF; k++) {
-                double t = from_prev_lane(own1), r = from_next_lane(own0);
-                DISTSIM_DSTEP(PFb, own0, own1, t, pl0, F0, pl1, F1);
-                DISTSIM_DSTEP(PBb, own1, own0, r, pr1, B1, pr0, B0);
-            }
-        } else {
-            k = firstB > k ? firstB : k;
-            PBb = shl32(PBb, k);
-        }
-        for (; k <= lastB; k++) {
-            double r = from_next_lane(own0);
-            DISTSIM_DSTEP(PBb, own1, own0, r, pr1, B1, pr0, B0);
+// GPipe without a sweep.  The events of a stage are the same for every micro-batch (Sec. 4.3: the
+// stage's event list is built once and replayed), so under GPipe the m forwards, and then the m
+// backwards, pass the stages as identical jobs pass the machines of a flow shop, and the recurrence
+// start = max(end of the device's previous task, end of the producer + p2p) solves exactly:
+//   end F(s, j) = sum_{i<=s} (F_i + pf_i) + j max_{i<=s} F_i
+// (induction on s and j: of the two operands of the max, the producer's wins when an earlier stage
+// is the longest, the device's own previous task when stage s is), and for the backwards, which
+// the last stage starts when its last forward has ended at R = end F(pp-1, m-1),
+//   end B(s, j) = R + sum_{i>=s} (B_i + pb_i) + j max_{i>=s} B_i
+// (the same induction from the last stage down; a path that starts at the end of an earlier
+// stage's forwards instead is never longer, since R, the sums and the maxima only grow towards
+// the last stage).  F_i, B_i: duration of a stage-task on its device, the send included when the
+// sender is occupied by it; pf_i, pb_i: latency of the edge into stage i, zero for the first
+// stage of either direction.  What the epilogue needs is the end of each stage's last backward:
+// one reduction over the candidate's lanes and two suffix scans, in exact fp64 (every partial
+// sum is an integer below 2^53 by the range check).  Lanes with on[u] unset contribute nothing.
+template <int U>
+__device__ __forceinline__ void gpipe_finish(const Sweep (&sw)[U], const bool (&on)[U], const int (&m)[U],
+                                             int s, int width, int lane, double (&fin)[U]) {
+    double fs[U], fm[U], T[U], M[U];
+#pragma unroll
+    for (int u = 0; u < U; u++) {
+        // an edge that does not exist carries -inf
+        fs[u] = on[u] ? sw[u].Fd + max_f64(sw[u].pfL, 0.0) : 0.0;
+        fm[u] = on[u] ? sw[u].Fd : 0.0;
+        T[u] = on[u] ? sw[u].Bd + max_f64(sw[u].pbR, 0.0) : 0.0;
+        M[u] = on[u] ? sw[u].Bd : 0.0;
+        fs[u] = group_sum_f64(fs[u], width);
+        fm[u] = group_max_f64(fm[u], width);
+    }
+    // inclusive suffix sum / suffix maximum over the candidate's lanes; a lane whose partner would
+    // lie outside the candidate reads itself, which leaves a maximum as it is
+    for (int d = 1; d < width; d <<= 1) {
+        const bool ok = s + d < width;
+        const int adr = (ok ? lane + d : lane) * 4;
+#pragma unroll
+        for (int u = 0; u < U; u++) {
+            const double t = from_lanes(T[u], adr), x = from_lanes(M[u], adr);
+            T[u] += ok ? t : 0.0;
+            M[u] = max_f64(M[u], x);
         }
     }
-    (void)kmask;
-    // back to one stage per lane
-    reinterpret_cast<double2*>(xp)[lane] = double2{own0, own1};
-    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-    sw[0].own = xp[lane];
-    sw[1].own = xp[kWave + lane];
-    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+#pragma unroll
+    for (int u = 0; u < U; u++) fin[u] = fs[u] + T[u] + (double)(m[u] - 1) * (fm[u] + M[u]);
 }
 
 // Simulates U wave-items at once.  For U = 2 the two items must have the same shape in every
-// lane (pp, m, schedule): then they share patterns, masks and control flow.  GPIPE_PAIR: the two
-// items hold GPipe candidates of at least two lanes each and are swept with the stages regrouped
-// two to a lane (sweep_gpipe_pair); the caller has checked that.
+// lane (pp, m, schedule): then they share patterns, masks and control flow.  GPipe candidates take
+// no part in the sweep: their end times have a closed form (gpipe_finish).  GPIPE_PAIR: the two
+// items hold nothing but GPipe candidates, of any shapes; the caller has checked that.
 template <int U, bool LINKS = false, bool GPIPE_PAIR = false>
 __device__ __forceinline__ void simulate_items(const ClusterDev& cl, const CandDev& ca, const Workspace& ws,
                                                const EventsDev& ev, const SimOut& out, int L, int64_t w0,
                                                int sh, const Desc (&d)[U], int lane,
-                                               Park& park, double* xp = nullptr) {
+                                               Park& park) {
     const double ninf = -__builtin_huge_val();
     const int slot = threadIdx.x;
     const int width = 1 << sh;
@@ -406,25 +352,29 @@ __device__ __forceinline__ void simulate_items(const ClusterDev& cl, const CandD
         }
         sw[0].own = own;
     } else if constexpr (GPIPE_PAIR) {
-        static_assert(U == 2, "the regrouped sweep takes two items");
-        sweep_gpipe_pair(sw, sh, lane, ppv, mv, xp);
+        double fin[U];
+        gpipe_finish<U>(sw, actv, mv, s, width, lane, fin);
+#pragma unroll
+        for (int u = 0; u < U; u++) sw[u].own = fin[u];
     } else {
         const LevelWindows lw(sched, m, pp, s);
+        const bool gpipe = act && sched == 0;       // closed form below
+        const bool swept = act && sched != 0;
         const int f1hi = lw.f1hi, f2lo = lw.f2lo, f2hi = lw.f2hi, blo = lw.blo, bhi = lw.bhi;
         // Levels at which some lane of the wavefront has a forward / a backward task: forwards from
         // level 0 to gLastF, backwards from gFirstB to gLastB (the last level of the sweep).
         const int lastFx = (f2lo <= f2hi && f2hi > f1hi) ? f2hi : f1hi;
-        const int gLastF = wave_max_i32(act ? s + lastFx : -1);
-        const int gFirstB = -wave_max_i32(act ? -(s + blo) : -(1 << 30));
-        const int gLastB = wave_max_i32(act ? s + bhi : -1);
+        const int gLastF = wave_max_i32(swept ? s + lastFx : -1);
+        const int gFirstB = -wave_max_i32(swept ? -(s + blo) : -(1 << 30));
+        const int gLastB = wave_max_i32(swept ? s + bhi : -1);
         const int nlev = gLastB + 1;
 
         // 1F1B past its warm-up runs forwards on even x and backwards on odd x.  When every
         // candidate of the wavefront is 1F1B with one pp, a level that has both kinds therefore
         // splits the lanes by parity, and one merged operand (previous lane for the forward
         // lanes, next lane for the backward lanes) feeds a single task step.
-        const int ppu = wave_max_i32(pp);
-        const bool par_ok = width >= 2 && __builtin_amdgcn_ballot_w64(act && (sched == 0 || pp != ppu)) == 0;
+        const int ppu = wave_max_i32(swept ? pp : 0);
+        const bool par_ok = width >= 2 && __builtin_amdgcn_ballot_w64(swept && pp != ppu) == 0;
         const bool even_s = (s & 1) == 0;
         const int adrE = (even_s ? lane - 1 : lane + 1) * 4;
 
@@ -433,8 +383,8 @@ __device__ __forceinline__ void simulate_items(const ClusterDev& cl, const CandD
             const uint32_t even_x = (x0 & 1) ? 0x55555555u : 0xaaaaaaaau;       // levels with even x
             uint32_t PFb = level_bits(-x0, f1hi - x0) | (level_bits(f2lo - x0, f2hi - x0) & even_x);
             uint32_t PBb = level_bits(blo - x0, bhi - x0);
-            if (sched != 0) PBb &= ((blo - x0) & 1) ? 0x55555555u : 0xaaaaaaaau;   // x - blo even
-            if (!act) { PFb = 0; PBb = 0; }
+            PBb &= ((blo - x0) & 1) ? 0x55555555u : 0xaaaaaaaau;                   // x - blo even
+            if (!swept) { PFb = 0; PBb = 0; }
             // chunk-relative level ranges in which a lane may have a forward / a backward task
             const bool anyF = gLastF >= l0, anyB = gFirstB < l0 + 32;
             const int firstF = anyF ? 0 : 64, lastF = anyF ? (gLastF - l0 < 31 ? gLastF - l0 : 31) : -1;
@@ -525,6 +475,16 @@ __device__ __forceinline__ void simulate_items(const ClusterDev& cl, const CandD
             }
             (void)kmask; (void)kmask2;
         }
+        if (__builtin_amdgcn_ballot_w64(gpipe) != 0) {
+            bool on[U];
+            int mg[U];
+            double fin[U];
+#pragma unroll
+            for (int u = 0; u < U; u++) { on[u] = gpipe; mg[u] = m; }
+            gpipe_finish<U>(sw, on, mg, s, width, lane, fin);
+#pragma unroll
+            for (int u = 0; u < U; u++) if (gpipe) sw[u].own = fin[u];
+        }
     }
 
 #pragma unroll
@@ -603,8 +563,8 @@ __device__ __forceinline__ void simulate_items(const ClusterDev& cl, const CandD
 
 // Two launches share the wave-items.  In every class the leading items that hold only GPipe
 // candidates (hdr[H_GPIPE_ITEMS + class], an even number) belong to k_simulate_gpipe, which
-// sweeps them two at a time with the stages regrouped two to a lane; all other items belong to
-// k_simulate.  Two kernels, so that each gets registers allotted for its own sweep.  Either
+// takes them two at a time and has no sweep at all (gpipe_finish); all other items belong to
+// k_simulate.  Two kernels, so that the one without a sweep gets by with fewer registers.  Either
 // launch numbers the pairs of its own items and a wavefront takes them with the stride of the grid
 // (about one pair per wavefront for large lists: the hardware's dispatch order is the load
 // balancing, so the order of the pairs is longest first, see PairOrder).
@@ -633,7 +593,7 @@ typedef const __attribute__((address_space(4))) int32_t* OrderPtr;
 template <bool GPIPE_PAIRS>
 __device__ __forceinline__ void simulate_all(const CostsDev& co, const ClusterDev& cl, const CandDev& ca,
                                              const Workspace& ws, const EventsDev& ev, const SimOut& out,
-                                             Park& park, double* xp) {
+                                             Park& park) {
     const int lane = lane_id();
     const HdrPtr hdr = (HdrPtr)ws.hdr;
     // the wavefront's number as a scalar: the header words and the item ranges then come through
@@ -668,7 +628,7 @@ __device__ __forceinline__ void simulate_all(const CostsDev& co, const ClusterDe
         if constexpr (GPIPE_PAIRS) {
             // an even number of items per class and room for all of them (k_bins): always two, side by side
             const Desc two[2] = {da, db};
-            simulate_items<2, false, true>(cl, ca, ws, ev, out, L, oa.w, ia.sh, two, lane, park, xp);
+            simulate_items<2, false, true>(cl, ca, ws, ev, out, L, oa.w, ia.sh, two, lane, park);
         } else {
             const bool okA = oa.w < W, okB = pair && ob.w < W;
             // simulated together when every lane sees the same shape (pp, m, schedule) in both,
@@ -697,14 +657,13 @@ __global__ __launch_bounds__(kSimBlock, 6) void k_simulate(CostsDev co, ClusterD
     // What only the epilogue needs is parked in LDS during the sweep (each lane its own slot),
     // so that the sweep runs in few enough registers for six wavefronts per SIMD.
     __shared__ Park park;
-    simulate_all<false>(co, cl, ca, ws, ev, out, park, nullptr);
+    simulate_all<false>(co, cl, ca, ws, ev, out, park);
 }
 
 __global__ __launch_bounds__(kSimBlock, 6) void k_simulate_gpipe(CostsDev co, ClusterDev cl, CandDev ca, Workspace ws,
                                                                  EventsDev ev, SimOut out) {
     __shared__ Park park;
-    __shared__ __align__(16) double regroup[kSimBlock / kWave][2 * kWave];     // 1 KB per wavefront
-    simulate_all<true>(co, cl, ca, ws, ev, out, park, regroup[threadIdx.x / kWave]);
+    simulate_all<true>(co, cl, ca, ws, ev, out, park);
 }
 
 // Same contract as k_simulate for p2p_blocking = 2 (sends queue on their link): one item per
