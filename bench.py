@@ -379,6 +379,10 @@ def main() -> int:
                     "frac": tl_bytes / tl_s / 1e9 / HBM_PEAK_GBS}
         if fill_gbs:
             timeline["frac_of_measured_fill"] = tl_bytes / tl_s / 1e9 / fill_gbs
+        gp_ms, gp_n = kt3["k_timeline_gpipe"]
+        timeline["gpipe_kernel_ms"] = gp_ms / max(gp_n, 1)
+        timeline["note"] = ("ms spans the packing of the selection, the level-sweep dump (k_timeline) and the closed-form "
+                            "dump of the GPipe candidates (k_timeline_gpipe, also given on its own)")
         bb_s = bb_ms / max(bb_n, 1) / 1e3
         bb_bytes = int(off[-1]) * 24                       # start and predecessor's end in, idle time out
         timeline["bubbles"] = {"ms": bb_s * 1e3, "bound": "hbm", "achieved": bb_bytes / bb_s / 1e9,

@@ -422,14 +422,16 @@ int distsim_comm_event_times(distsim_ctx *ctx, int64_t n, const int32_t *kind, c
  * launch.  distsim_timing_read blocks until the recorded launches have finished and returns
  * the accumulated time and launch count of one kernel, then clears that kernel's record.
  * DISTSIM_K_SIMULATE spans the whole sweep of distsim_simulate, i.e. also the kernel that runs
- * beside it on the context's stream (DISTSIM_K_SIMULATE_GPIPE, timed there on its own).
+ * beside it on the context's stream (DISTSIM_K_SIMULATE_GPIPE, timed there on its own);
+ * DISTSIM_K_TIMELINE spans the packing of the selection and both dump kernels of the built-in
+ * schedules (DISTSIM_K_TIMELINE_GPIPE is the second of them, timed on its own as well).
  */
 enum {
     DISTSIM_K_LAYER_TABLES = 0, DISTSIM_K_DECODE, DISTSIM_K_BINS, DISTSIM_K_SCATTER,
     DISTSIM_K_STAGE_EVENTS, DISTSIM_K_SIM_INIT, DISTSIM_K_SIMULATE, DISTSIM_K_SEARCH, DISTSIM_K_TIMELINE,
     DISTSIM_K_DEDUP, DISTSIM_K_COMM_TIMES, DISTSIM_K_BUBBLES, DISTSIM_K_SIMULATE_VIRTUAL,
     DISTSIM_K_TIMELINE_VIRTUAL, DISTSIM_K_SIMULATE_GPIPE, DISTSIM_K_SIMULATE_EXPLICIT,
-    DISTSIM_K_TIMELINE_EXPLICIT, DISTSIM_K_COMPILE_SCHEDULES, DISTSIM_K_COUNT
+    DISTSIM_K_TIMELINE_EXPLICIT, DISTSIM_K_COMPILE_SCHEDULES, DISTSIM_K_TIMELINE_GPIPE, DISTSIM_K_COUNT
 };
 int distsim_timing_enable(distsim_ctx *ctx, int on);
 int distsim_timing_read(distsim_ctx *ctx, int kernel, double *total_ms, int64_t *launches);

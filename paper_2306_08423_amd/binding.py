@@ -28,7 +28,7 @@ COL = {"FC": 0, "FA": 1, "BC": 2, "BA": 3, "PF": 4, "PB": 5, "G": 6, "AR": 7}
 KERNELS = ("k_layer_tables", "k_decode", "k_bins", "k_scatter", "k_stage_events",
            "k_sim_init", "k_simulate", "k_search", "k_timeline", "k_dedup", "k_comm_event_times", "k_bubbles", "k_simulate_virtual",
            "k_timeline_virtual", "k_simulate_gpipe", "k_simulate_explicit",
-           "k_timeline_explicit", "k_compile_schedules")
+           "k_timeline_explicit", "k_compile_schedules", "k_timeline_gpipe")
 INT64_MAX = (1 << 63) - 1
 ST_OK, ST_INVALID, ST_RANGE, ST_NOROOM, ST_UNSUPPORTED = 0, 1, 2, 3, 4
 MAX_PP, MAX_M, MAX_SLOTS = 64, 1 << 16, 2048

@@ -51,7 +51,7 @@ static const char* kKernelNames[DISTSIM_K_COUNT] = {
     "k_stage_events", "k_sim_init", "k_simulate", "k_search", "k_timeline",
     "k_dedup", "k_comm_event_times", "k_bubbles", "k_simulate_virtual",
     "k_timeline_virtual", "k_simulate_gpipe", "k_simulate_explicit", "k_timeline_explicit",
-    "k_compile_schedules",
+    "k_compile_schedules", "k_timeline_gpipe",
 };
 
 static int fail(distsim_ctx* ctx, int code, const std::string& msg) {
@@ -455,6 +455,10 @@ int distsim_simulate(distsim_ctx* ctx, const distsim_cluster* cluster, const dis
     return DISTSIM_OK;
 }
 
+// Selection length from which the closed-form dump of the GPipe candidates runs beside the
+// level-sweep dump on the context's stream; below it the fork and the join cost more than they bring.
+static const int64_t kTimelineForkMin = 2048;
+
 int distsim_timeline(distsim_ctx* ctx, const distsim_cluster* cluster, const distsim_candidates* cd,
                      const distsim_events* events, int64_t n, const int64_t* sel, const int64_t* task_off,
                      int64_t* start_ns, int64_t* end_ns, int64_t* ar_start_ns, int64_t* ar_end_ns, void* hip_stream) {
@@ -485,6 +489,8 @@ int distsim_timeline(distsim_ctx* ctx, const distsim_cluster* cluster, const dis
         // ordering keys, one int32 per candidate, and the bin counters), so a selection longer than
         // the candidate list goes in several rounds.
         Timer t(ctx, st, DISTSIM_K_TIMELINE);
+        // GPipe candidates have a dump kernel of their own unless sends queue on their links
+        const int gpipe_apart = cluster->p2p_blocking != 2 ? 1 : 0;
         const int64_t room = events->num_candidates > 0 ? events->num_candidates : 1;
         for (int64_t at = 0; at < n; at += room) {
             const int64_t nn = n - at < room ? n - at : room;
@@ -492,11 +498,32 @@ int distsim_timeline(distsim_ctx* ctx, const distsim_cluster* cluster, const dis
             const unsigned pb = (unsigned)((nn + 255) / 256);
             hipLaunchKernelGGL(k_timeline_clear, dim3(1), dim3(kWave), 0, st, ws.bin_count);
             hipLaunchKernelGGL(k_timeline_pack<0>, dim3(pb), dim3(256), 0, st, ca, events->status, events->num_candidates, nn,
-                               out.sel, ws.bin_count, ws.key, out.ar_start, out.ar_end);
+                               out.sel, ws.bin_count, ws.key, out.ar_start, out.ar_end, gpipe_apart);
+            // The dump of the GPipe candidates goes behind the first pack, which sets all all-reduce
+            // windows to "none"; for a long selection on the context's stream, beside the second pack
+            // and the level-sweep dump (they write different entries).
+            const bool beside = gpipe_apart && nn >= kTimelineForkMin;
+            const hipStream_t sg = beside ? ctx->side : st;
+            auto dump_gpipe = [&]() {
+                Timer tg(ctx, sg, DISTSIM_K_TIMELINE_GPIPE);
+                hipLaunchKernelGGL(k_timeline_gpipe, dim3((unsigned)nn), dim3(kTlGpipeBlock), 0, sg, co, cl_dev(*cluster), ca, ws,
+                                   events->status, events->num_candidates, nn, out);     // a workgroup per entry of the selection
+            };
+            if (beside) {
+                HIP_TRY(hipEventRecord(ctx->fork, st));
+                HIP_TRY(hipStreamWaitEvent(ctx->side, ctx->fork, 0));
+                dump_gpipe();
+            }
             hipLaunchKernelGGL(k_timeline_pack<1>, dim3(pb), dim3(256), 0, st, ca, events->status, events->num_candidates, nn,
-                               out.sel, ws.bin_count, ws.key, out.ar_start, out.ar_end);
+                               out.sel, ws.bin_count, ws.key, out.ar_start, out.ar_end, gpipe_apart);
             hipLaunchKernelGGL(k_timeline, dim3((unsigned)nn), dim3(kWave), 0, st, co, cl_dev(*cluster), ca, ws,
                                events->status, events->num_candidates, nn, ws.bin_count, ws.key, out);
+            if (beside) {
+                HIP_TRY(hipEventRecord(ctx->join, ctx->side));
+                HIP_TRY(hipStreamWaitEvent(st, ctx->join, 0));
+            } else if (gpipe_apart) {
+                dump_gpipe();
+            }
         }
     }
     if (cd->chunks) {          // interleaved candidates among the selected ones: one wavefront each

@@ -32,9 +32,11 @@ struct TlStage {
 
 // Width class of selection entry q for the level-sweep dump (0: 64 lanes ... 6: one lane), -1 when the
 // entry gets no dump from k_timeline: index outside the list, candidate not OK, or a schedule that
-// has a dump kernel of its own.
-__device__ __forceinline__ int timeline_class(const CandDev& ca, const int32_t* __restrict__ status, int64_t C, int64_t c) {
+// has a dump kernel of its own (GPipe when gpipe_apart is set: k_timeline_gpipe).
+__device__ __forceinline__ int timeline_class(const CandDev& ca, const int32_t* __restrict__ status, int64_t C, int64_t c,
+                                              int gpipe_apart) {
     if (c < 0 || c >= C || status[c] != 0 || ca.schedule[c] >= 3) return -1;
+    if (gpipe_apart && ca.schedule[c] == 0) return -1;
     const int pp = ca.pp[c];
     int sh = 0;
     while ((1 << sh) < pp) sh++;
@@ -57,12 +59,12 @@ template <int PASS>
 __global__ __launch_bounds__(256) void k_timeline_pack(CandDev ca, const int32_t* __restrict__ status, int64_t C, int64_t n,
                                                        const int64_t* __restrict__ sel, int32_t* __restrict__ cnt,
                                                        int32_t* __restrict__ sorted, int64_t* __restrict__ ar_start,
-                                                       int64_t* __restrict__ ar_end) {
+                                                       int64_t* __restrict__ ar_end, int gpipe_apart) {
     __shared__ int32_t hist[kClasses], base[kClasses];
     if (threadIdx.x < kClasses) hist[threadIdx.x] = 0;
     __syncthreads();
     const int64_t q = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    const int k = q < n ? timeline_class(ca, status, C, sel[q]) : -1;
+    const int k = q < n ? timeline_class(ca, status, C, sel[q], gpipe_apart) : -1;
     int rank = 0;
     if (k >= 0) rank = atomicAdd(&hist[k], 1);
     if (PASS == 0) {
@@ -82,6 +84,42 @@ __global__ __launch_bounds__(256) void k_timeline_pack(CandDev ca, const int32_t
         for (int i = 0; i < k; i++) start += cnt[i];
         sorted[start + base[k] + rank] = (int32_t)q;
     }
+}
+
+// Data-parallel modelling for the dump: window of the gradient all-reduce events on the device of
+// stage s (entry q of the selection), which has dp > 1 replicas and G > 0 gradient bytes.  endB: end
+// of the stage's last backward, Bd_i: its duration.
+__device__ __forceinline__ void allreduce_window(const ClusterDev& cl, const Workspace& ws, int L, int v, int pp, int dp,
+                                                 int lo, int hi, int64_t G, int64_t endB, int64_t Bd_i,
+                                                 const TimelineOut& out, int64_t q, int s) {
+    if (cl.bucket <= 0) {
+        out.ar_start[q * kMaxPP + s] = endB;
+        out.ar_end[q * kMaxPP + s] = endB + allreduce_ns(cl, dp, G);
+        return;
+    }
+    const size_t vr = (size_t)v * (L + 1), rr = (size_t)(v * kMaxPP + pp - 1) * (L + 1);
+    const int64_t startB = endB - Bd_i;
+    const int64_t tot_hi = ws.pbc[vr + hi] + ws.pba[rr + hi];
+    const int64_t ar_cap = allreduce_ns(cl, dp, cl.bucket);
+    int64_t acc = 0, t = 0, first = -1;
+    for (int l = hi - 1; l >= lo; l--) {
+        const int64_t ready = startB + (tot_hi - (ws.pbc[vr + l] + ws.pba[rr + l]));
+        acc += ws.pg[vr + l + 1] - ws.pg[vr + l];
+        const int64_t kb = (int64_t)udiv64((uint64_t)acc, (uint64_t)cl.bucket);
+        if (kb > 0) {
+            const int64_t b0 = t > ready ? t : ready;
+            if (first < 0) first = b0;
+            t = b0 + kb * ar_cap;
+            acc -= kb * cl.bucket;
+        }
+        if (l == lo && acc > 0) {
+            const int64_t b0 = t > ready ? t : ready;
+            if (first < 0) first = b0;
+            t = b0 + allreduce_ns(cl, dp, acc);
+        }
+    }
+    out.ar_start[q * kMaxPP + s] = first;
+    out.ar_end[q * kMaxPP + s] = t;
 }
 
 // One wavefront per wave-item of the packed selection (64 >> k entries of class k, 1 << (6 - k)
@@ -290,39 +328,112 @@ __global__ __launch_bounds__(kWave) void k_timeline(CostsDev co, ClusterDev cl, 
         }
         (void)kmask; (void)kmask2;
 
-        // data-parallel modelling: window of the gradient all-reduce events on this device
-        if (act && dp > 1 && r.G > 0 && sched != 2) {
-            const int64_t endB = double_to_i64(own);
-            if (cl.bucket <= 0) {
-                out.ar_start[q * kMaxPP + s] = endB;
-                out.ar_end[q * kMaxPP + s] = endB + allreduce_ns(cl, dp, r.G);
-            } else {
-                const size_t vr = (size_t)v * (L + 1), rr = (size_t)(v * kMaxPP + pp - 1) * (L + 1);
-                const int64_t startB = endB - Bd_i;
-                const int64_t tot_hi = ws.pbc[vr + hi] + ws.pba[rr + hi];
-                const int64_t ar_cap = allreduce_ns(cl, dp, cl.bucket);
-                int64_t acc = 0, t = 0, first = -1;
-                for (int l = hi - 1; l >= lo; l--) {
-                    const int64_t ready = startB + (tot_hi - (ws.pbc[vr + l] + ws.pba[rr + l]));
-                    acc += ws.pg[vr + l + 1] - ws.pg[vr + l];
-                    const int64_t kb = (int64_t)udiv64((uint64_t)acc, (uint64_t)cl.bucket);
-                    if (kb > 0) {
-                        const int64_t b0 = t > ready ? t : ready;
-                        if (first < 0) first = b0;
-                        t = b0 + kb * ar_cap;
-                        acc -= kb * cl.bucket;
-                    }
-                    if (l == lo && acc > 0) {
-                        const int64_t b0 = t > ready ? t : ready;
-                        if (first < 0) first = b0;
-                        t = b0 + allreduce_ns(cl, dp, acc);
-                    }
-                }
-                out.ar_start[q * kMaxPP + s] = first;
-                out.ar_end[q * kMaxPP + s] = t;
+        if (act && dp > 1 && r.G > 0 && sched != 2)
+            allreduce_window(cl, ws, L, v, pp, dp, lo, hi, r.G, double_to_i64(own), Bd_i, out, q, s);
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");   // the staging area is reused by the next item
+    }
+}
+
+// The GPipe candidates of the selection, without a sweep: every task's end has the closed form
+// that gpipe_finish (kernels_simulate.hpp) derives,
+//   end F(s, j) = sum_{i<=s} (F_i + pf_i) + j max_{i<=s} F_i
+//   end B(s, j) = end F(pp-1, m-1) + sum_{i>=s} (B_i + pb_i) + j max_{i>=s} B_i
+// and start = end - duration.  One workgroup per selected candidate: lane s of its first wavefront
+// forms the four scans of stage s and leaves (end of the first task, step per micro-batch,
+// duration) of its two rows in LDS; then all threads write the candidate's block entry by entry,
+// consecutive threads consecutive entries, every wavefront 512 contiguous bytes of each array per
+// store instruction.  Not for p2p_blocking = 2 (sends queue on their links; those candidates stay
+// with k_timeline).
+constexpr int kTlGpipeBlock = 256;
+struct alignas(16) TlGpipeRow { double end0, step, dur, spare; };
+__global__ __launch_bounds__(kTlGpipeBlock) void k_timeline_gpipe(CostsDev co, ClusterDev cl, CandDev ca, Workspace ws,
+                                                                  const int32_t* __restrict__ status, int64_t C, int64_t n,
+                                                                  TimelineOut out) {
+    __shared__ TlGpipeRow tab[2 * kWave];
+    __shared__ int verdict;                 // 0: no entries for this candidate, 1: times below 2^52, 2: above
+    const int lane = lane_id(), s = lane;
+    const bool first_wave = threadIdx.x < kWave;
+    const int L = co.L;
+    // q, hence everything that decides whether an entry of the selection is taken, is the same in
+    // all threads of the workgroup
+    for (int64_t q = blockIdx.x; q < n; q += gridDim.x) {
+        const int64_t c = out.sel[q];
+        if (c < 0 || c >= C) continue;
+        if (status[c] != 0 || ca.schedule[c] != 0) continue;
+        const int pp = __builtin_amdgcn_readfirstlane(ca.pp[c]), m = __builtin_amdgcn_readfirstlane(ca.m[c]);
+        if (first_wave) {
+            const int dp = ca.dp[c], tp = ca.tp[c];
+            const int64_t poff = ca.part_off[c];
+            int v = 0;
+            for (int i = co.V - 1; i >= 0; i--) if (co.variant_tp[i] == tp) v = i;
+            const bool in = s < pp;
+            int lo = 0, hi = 0;
+            if (in) {
+                if (poff >= 0) { lo = ca.part_pool[poff + s]; hi = ca.part_pool[poff + s + 1]; }
+                else { lo = uniform_bound(s, L, pp); hi = uniform_bound((s + 1), L, pp); }
+            }
+            StageRow r;
+            // a candidate whose partition or range check fails gets no entries
+            const bool ok = stage_row(cl, ws, L, kWave, s, pp, v, m, dp, tp, lo, hi, r) == 0;
+            const int64_t pf_task = cl.blocking == 1 ? r.PF : 0, pb_task = cl.blocking == 1 ? r.PB : 0;
+            const int64_t Fd_i = r.FC + r.FA + pf_task, Bd_i = r.BC + r.BA + pb_task;
+            const double Fd = (double)Fd_i, Bd = (double)Bd_i;              // zero in lanes without a stage
+            // latency of the edge into the stage (the neighbour's outgoing event), zero without one
+            double pfL = from_prev_lane((double)(r.PF - pf_task)), pbR = from_next_lane((double)(r.PB - pb_task));
+            if (!(in && s > 0)) pfL = 0.0;
+            if (!(in && s + 1 < pp)) pbR = 0.0;
+            // prefix sum and maximum over the stages up to s, suffix sum and maximum over those from s on
+            double A = Fd + pfL, MF = Fd, T = Bd + pbR, MB = Bd;
+            for (int d = 1; d < kWave; d <<= 1) {
+                const bool up = lane >= d, dn = lane + d < kWave;
+                const int au = (up ? lane - d : lane) * 4, ad = (dn ? lane + d : lane) * 4;
+                const double a = from_lanes(A, au), f = from_lanes(MF, au), t = from_lanes(T, ad), b = from_lanes(MB, ad);
+                A += up ? a : 0.0;
+                MF = max_f64(MF, f);
+                T += dn ? t : 0.0;
+                MB = max_f64(MB, b);
+            }
+            const double mm1 = (double)(m - 1);
+            const double R = readlane_f64(A, pp - 1) + mm1 * readlane_f64(MF, pp - 1);   // end of the last stage's last forward
+            if (in) {
+                tab[s] = TlGpipeRow{A, MF, Fd, 0.0};
+                tab[kWave + s] = TlGpipeRow{R + T, MB, Bd, 0.0};
+            }
+            // the last task of all ends at stage 0: below 2^52 every time converts with one addition
+            const bool small = R + readlane_f64(T, 0) + mm1 * readlane_f64(MB, 0) < 4503599627370496.0;
+            if (lane == 0) verdict = ok ? (small ? 1 : 2) : 0;
+            if (ok && in && dp > 1 && r.G > 0)
+                allreduce_window(cl, ws, L, v, pp, dp, lo, hi, r.G, double_to_i64(R + T + mm1 * MB), Bd_i, out, q, s);
+        }
+        __syncthreads();
+        const int vd = verdict;
+        if (vd != 0) {
+            const bool small = vd == 1;
+            const int64_t off = out.task_off[q];
+            const int total = 2 * pp * m;                       // [kind][stage][micro-batch], row = kind * pp + stage
+            // a step of one workgroup's worth of entries, in rows and micro-batches
+            const int qs = kTlGpipeBlock / m, rs = kTlGpipeBlock - qs * m;
+            // the 64 entries of a store instruction start at a 128-byte boundary of the output: whole
+            // lines but for the two ends of the block.  A thread whose first entry would lie in front
+            // of the block starts one turn later, with the row and micro-batch of that later entry.
+            const int skew = (int)((reinterpret_cast<uintptr_t>(out.start + off) >> 3) & 15);
+            int e = (int)threadIdx.x - skew;
+            const int e_first = e < 0 ? e + kTlGpipeBlock : e;
+            int row = e_first / m, j = e_first - row * m;
+            for (int base = -skew; base < total; base += kTlGpipeBlock, e += kTlGpipeBlock) {
+                if (e < 0 || e >= total) continue;
+                const TlGpipeRow t = tab[row < pp ? row : row + (kWave - pp)];
+                const double en = t.end0 + (double)j * t.step, st = en - t.dur;
+                const int64_t a = small ? small_double_to_i64(st) : double_to_i64(st);
+                const int64_t b = small ? small_double_to_i64(en) : double_to_i64(en);
+                // written once and not read again by this kernel: streaming stores
+                __builtin_nontemporal_store(a, out.start + off + e);
+                __builtin_nontemporal_store(b, out.end + off + e);
+                j += rs; row += qs;
+                if (j >= m) { j -= m; row++; }
             }
         }
-        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");   // the staging area is reused by the next item
+        __syncthreads();                    // the rows are reused by the next entry
     }
 }
 
