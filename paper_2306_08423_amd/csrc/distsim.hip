@@ -489,8 +489,6 @@ int distsim_timeline(distsim_ctx* ctx, const distsim_cluster* cluster, const dis
         // ordering keys, one int32 per candidate, and the bin counters), so a selection longer than
         // the candidate list goes in several rounds.
         Timer t(ctx, st, DISTSIM_K_TIMELINE);
-        // GPipe candidates have a dump kernel of their own unless sends queue on their links
-        const int gpipe_apart = cluster->p2p_blocking != 2 ? 1 : 0;
         const int64_t room = events->num_candidates > 0 ? events->num_candidates : 1;
         for (int64_t at = 0; at < n; at += room) {
             const int64_t nn = n - at < room ? n - at : room;
@@ -498,11 +496,11 @@ int distsim_timeline(distsim_ctx* ctx, const distsim_cluster* cluster, const dis
             const unsigned pb = (unsigned)((nn + 255) / 256);
             hipLaunchKernelGGL(k_timeline_clear, dim3(1), dim3(kWave), 0, st, ws.bin_count);
             hipLaunchKernelGGL(k_timeline_pack<0>, dim3(pb), dim3(256), 0, st, ca, events->status, events->num_candidates, nn,
-                               out.sel, ws.bin_count, ws.key, out.ar_start, out.ar_end, gpipe_apart);
+                               out.sel, ws.bin_count, ws.key, out.ar_start, out.ar_end);
             // The dump of the GPipe candidates goes behind the first pack, which sets all all-reduce
             // windows to "none"; for a long selection on the context's stream, beside the second pack
             // and the level-sweep dump (they write different entries).
-            const bool beside = gpipe_apart && nn >= kTimelineForkMin;
+            const bool beside = nn >= kTimelineForkMin;
             const hipStream_t sg = beside ? ctx->side : st;
             auto dump_gpipe = [&]() {
                 Timer tg(ctx, sg, DISTSIM_K_TIMELINE_GPIPE);
@@ -515,13 +513,13 @@ int distsim_timeline(distsim_ctx* ctx, const distsim_cluster* cluster, const dis
                 dump_gpipe();
             }
             hipLaunchKernelGGL(k_timeline_pack<1>, dim3(pb), dim3(256), 0, st, ca, events->status, events->num_candidates, nn,
-                               out.sel, ws.bin_count, ws.key, out.ar_start, out.ar_end, gpipe_apart);
+                               out.sel, ws.bin_count, ws.key, out.ar_start, out.ar_end);
             hipLaunchKernelGGL(k_timeline, dim3((unsigned)nn), dim3(kWave), 0, st, co, cl_dev(*cluster), ca, ws,
                                events->status, events->num_candidates, nn, ws.bin_count, ws.key, out);
             if (beside) {
                 HIP_TRY(hipEventRecord(ctx->join, ctx->side));
                 HIP_TRY(hipStreamWaitEvent(st, ctx->join, 0));
-            } else if (gpipe_apart) {
+            } else {
                 dump_gpipe();
             }
         }

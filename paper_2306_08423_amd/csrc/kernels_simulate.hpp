@@ -19,10 +19,10 @@ __global__ __launch_bounds__(256) void k_sim_init(const int32_t* __restrict__ st
 
 // Lane (g, s) of a wave-item owns stage s of one candidate and keeps a single running value:
 // the end time of the most recent stage-task on that device.  Tasks are visited in levels
-// chosen such that every dependency of a level-l task lies in a lower level:
-//   GPipe  F(s,j): s + j                         B(s,j): (m + pp - 1) + (pp - 1 - s) + j
-//   1F1B   F(s,j): s + j        (j <= w_s)       B(s,j): 2 pp - 1 - s + 2 j
-//                  s + 2 j      (j >  w_s)       w_s = min(pp - 1 - s, m) warm-up forwards
+// chosen such that every dependency of a level-l task lies in a lower level; for 1F1B and the
+// asynchronous schedule, which shares its order (GPipe candidates are not swept, see gpipe_finish):
+//   F(s,j): s + j        (j <= w_s)       B(s,j): 2 pp - 1 - s + 2 j
+//           s + 2 j      (j >  w_s)       w_s = min(pp - 1 - s, m) warm-up forwards
 // In that order the most recent task of the producing neighbour at the time a task runs is
 // exactly its producer (forward: F(s-1,j) on the previous lane; backward: B(s+1,j) on the next
 // lane), so the cross-stage operand is the neighbour lane's register, read with a DPP shift.
@@ -164,19 +164,14 @@ __device__ __forceinline__ double from_lanes(double x, int byte_addr) {
 
 // Level windows of a lane that holds stage s, expressed on x = level - s:
 //   forward  x in [0, f1hi]  and  even x in [f2lo, f2hi]
-//   backward x in [blo, bhi], every x (GPipe) or every second x (1F1B)
+//   backward x in [blo, bhi], every second x
 struct LevelWindows {
     int f1hi, f2lo = 1, f2hi = 0, blo, bhi;
-    __device__ __forceinline__ LevelWindows(int sched, int m, int pp, int s) {
-        if (sched == 0) {
-            f1hi = m - 1;
-            blo = m + 2 * pp - 2 - 2 * s; bhi = blo + m - 1;
-        } else {
-            int wq = pp - 1 - s; if (wq > m) wq = m;
-            f1hi = wq < m - 1 ? wq : m - 1;
-            f2lo = 2 * wq + 2; f2hi = 2 * m - 2;
-            blo = 2 * pp - 1 - 2 * s; bhi = blo + 2 * m - 2;
-        }
+    __device__ __forceinline__ LevelWindows(int m, int pp, int s) {
+        int wq = pp - 1 - s; if (wq > m) wq = m;
+        f1hi = wq < m - 1 ? wq : m - 1;
+        f2lo = 2 * wq + 2; f2hi = 2 * m - 2;
+        blo = 2 * pp - 1 - 2 * s; bhi = blo + 2 * m - 2;
     }
 };
 
@@ -216,20 +211,23 @@ struct Park {
 // stage's forwards instead is never longer, since R, the sums and the maxima only grow towards
 // the last stage).  F_i, B_i: duration of a stage-task on its device, the send included when the
 // sender is occupied by it; pf_i, pb_i: latency of the edge into stage i, zero for the first
-// stage of either direction.  What the epilogue needs is the end of each stage's last backward:
+// stage of either direction.  LINKS (sends queue on their link, one transfer at a time): a link is
+// one more machine of the shop, between its two stages, so its transfer time also enters the two
+// maxima.  What the epilogue needs is the end of each stage's last backward:
 // one reduction over the candidate's lanes and two suffix scans, in exact fp64 (every partial
 // sum is an integer below 2^53 by the range check).  Lanes with on[u] unset contribute nothing.
-template <int U>
+template <int U, bool LINKS = false>
 __device__ __forceinline__ void gpipe_finish(const Sweep (&sw)[U], const bool (&on)[U], const int (&m)[U],
                                              int s, int width, int lane, double (&fin)[U]) {
     double fs[U], fm[U], T[U], M[U];
 #pragma unroll
     for (int u = 0; u < U; u++) {
         // an edge that does not exist carries -inf
-        fs[u] = on[u] ? sw[u].Fd + max_f64(sw[u].pfL, 0.0) : 0.0;
-        fm[u] = on[u] ? sw[u].Fd : 0.0;
-        T[u] = on[u] ? sw[u].Bd + max_f64(sw[u].pbR, 0.0) : 0.0;
-        M[u] = on[u] ? sw[u].Bd : 0.0;
+        const double eF = max_f64(sw[u].pfL, 0.0), eB = max_f64(sw[u].pbR, 0.0);
+        fs[u] = on[u] ? sw[u].Fd + eF : 0.0;
+        fm[u] = on[u] ? (LINKS ? max_f64(sw[u].Fd, eF) : sw[u].Fd) : 0.0;
+        T[u] = on[u] ? sw[u].Bd + eB : 0.0;
+        M[u] = on[u] ? (LINKS ? max_f64(sw[u].Bd, eB) : sw[u].Bd) : 0.0;
         fs[u] = group_sum_f64(fs[u], width);
         fm[u] = group_max_f64(fm[u], width);
     }
@@ -313,14 +311,16 @@ __device__ __forceinline__ void simulate_items(const ClusterDev& cl, const CandD
     }
 
     if constexpr (LINKS) {
-        const LevelWindows lw(sched, m, pp, s);
+        const LevelWindows lw(m, pp, s);
         const int f1hi = lw.f1hi, f2lo = lw.f2lo, f2hi = lw.f2hi, blo = lw.blo, bhi = lw.bhi;
         // Sends queue on their link (p2p_blocking = 2): every lane keeps the arrival time of its
         // latest forward send and of its latest backward send; a send starts when its task has
         // ended and the link is free, and the neighbour reads the arrival time instead of the end
         // of the task.  Plain per-level form of the sweep, one item at a time.
         static_assert(U == 1, "the serialised sweep takes one item at a time");
-        const int nlev = wave_max_i32(act ? 2 * (m + pp - 1) : 0);
+        const bool gpipe = act && sched == 0;       // closed form below
+        const bool swept = act && sched != 0;
+        const int nlev = wave_max_i32(swept ? 2 * (m + pp - 1) : 0);
         // a lane without that neighbour never looks at what the lane beside it sends (another
         // candidate's stage); the link time of a lane without a receiver is never looked at either
         const double gateL = act && s > 0 ? 0.0 : ninf, gateR = act && s + 1 < pp ? 0.0 : ninf;
@@ -331,8 +331,8 @@ __device__ __forceinline__ void simulate_items(const ClusterDev& cl, const CandD
             const uint32_t even_x = (x0 & 1) ? 0x55555555u : 0xaaaaaaaau;
             uint32_t PFb = level_bits(-x0, f1hi - x0) | (level_bits(f2lo - x0, f2hi - x0) & even_x);
             uint32_t PBb = level_bits(blo - x0, bhi - x0);
-            if (sched != 0) PBb &= ((blo - x0) & 1) ? 0x55555555u : 0xaaaaaaaau;
-            if (!act) { PFb = 0; PBb = 0; }
+            PBb &= ((blo - x0) & 1) ? 0x55555555u : 0xaaaaaaaau;
+            if (!swept) { PFb = 0; PBb = 0; }
             const bool anyF = wave_or_u32(PFb) != 0, anyB = wave_or_u32(PBb) != 0;
             const int kend = nlev - l0 < 32 ? nlev - l0 : 32;
             // a lane runs at most one task per level, and a level's tasks read only what the level
@@ -351,15 +351,33 @@ __device__ __forceinline__ void simulate_items(const ClusterDev& cl, const CandD
             (void)kmask;
         }
         sw[0].own = own;
+        if (__builtin_amdgcn_ballot_w64(gpipe) != 0) {
+            const bool on[1] = {gpipe};
+            const int mg[1] = {m};
+            double fin[1];
+            gpipe_finish<1, true>(sw, on, mg, s, width, lane, fin);
+            if (gpipe) sw[0].own = fin[0];
+        }
     } else if constexpr (GPIPE_PAIR) {
         double fin[U];
         gpipe_finish<U>(sw, actv, mv, s, width, lane, fin);
 #pragma unroll
         for (int u = 0; u < U; u++) sw[u].own = fin[u];
     } else {
-        const LevelWindows lw(sched, m, pp, s);
+        const LevelWindows lw(m, pp, s);
         const bool gpipe = act && sched == 0;       // closed form below
         const bool swept = act && sched != 0;
+        // GPipe lanes first: the sweep below never touches them (their patterns are empty)
+        if (__builtin_amdgcn_ballot_w64(gpipe) != 0) {
+            bool on[U];
+            int mg[U];
+            double fin[U];
+#pragma unroll
+            for (int u = 0; u < U; u++) { on[u] = gpipe; mg[u] = m; }
+            gpipe_finish<U>(sw, on, mg, s, width, lane, fin);
+#pragma unroll
+            for (int u = 0; u < U; u++) if (gpipe) sw[u].own = fin[u];
+        }
         const int f1hi = lw.f1hi, f2lo = lw.f2lo, f2hi = lw.f2hi, blo = lw.blo, bhi = lw.bhi;
         // Levels at which some lane of the wavefront has a forward / a backward task: forwards from
         // level 0 to gLastF, backwards from gFirstB to gLastB (the last level of the sweep).
@@ -474,16 +492,6 @@ __device__ __forceinline__ void simulate_items(const ClusterDev& cl, const CandD
                 k = e;
             }
             (void)kmask; (void)kmask2;
-        }
-        if (__builtin_amdgcn_ballot_w64(gpipe) != 0) {
-            bool on[U];
-            int mg[U];
-            double fin[U];
-#pragma unroll
-            for (int u = 0; u < U; u++) { on[u] = gpipe; mg[u] = m; }
-            gpipe_finish<U>(sw, on, mg, s, width, lane, fin);
-#pragma unroll
-            for (int u = 0; u < U; u++) if (gpipe) sw[u].own = fin[u];
         }
     }
 

@@ -32,11 +32,9 @@ struct TlStage {
 
 // Width class of selection entry q for the level-sweep dump (0: 64 lanes ... 6: one lane), -1 when the
 // entry gets no dump from k_timeline: index outside the list, candidate not OK, or a schedule that
-// has a dump kernel of its own (GPipe when gpipe_apart is set: k_timeline_gpipe).
-__device__ __forceinline__ int timeline_class(const CandDev& ca, const int32_t* __restrict__ status, int64_t C, int64_t c,
-                                              int gpipe_apart) {
-    if (c < 0 || c >= C || status[c] != 0 || ca.schedule[c] >= 3) return -1;
-    if (gpipe_apart && ca.schedule[c] == 0) return -1;
+// has a dump kernel of its own (GPipe: k_timeline_gpipe; interleaved and explicit schedules).
+__device__ __forceinline__ int timeline_class(const CandDev& ca, const int32_t* __restrict__ status, int64_t C, int64_t c) {
+    if (c < 0 || c >= C || status[c] != 0 || ca.schedule[c] >= 3 || ca.schedule[c] == 0) return -1;
     const int pp = ca.pp[c];
     int sh = 0;
     while ((1 << sh) < pp) sh++;
@@ -59,12 +57,12 @@ template <int PASS>
 __global__ __launch_bounds__(256) void k_timeline_pack(CandDev ca, const int32_t* __restrict__ status, int64_t C, int64_t n,
                                                        const int64_t* __restrict__ sel, int32_t* __restrict__ cnt,
                                                        int32_t* __restrict__ sorted, int64_t* __restrict__ ar_start,
-                                                       int64_t* __restrict__ ar_end, int gpipe_apart) {
+                                                       int64_t* __restrict__ ar_end) {
     __shared__ int32_t hist[kClasses], base[kClasses];
     if (threadIdx.x < kClasses) hist[threadIdx.x] = 0;
     __syncthreads();
     const int64_t q = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    const int k = q < n ? timeline_class(ca, status, C, sel[q], gpipe_apart) : -1;
+    const int k = q < n ? timeline_class(ca, status, C, sel[q]) : -1;
     int rank = 0;
     if (k >= 0) rank = atomicAdd(&hist[k], 1);
     if (PASS == 0) {
@@ -190,16 +188,8 @@ __global__ __launch_bounds__(kWave) void k_timeline(CostsDev co, ClusterDev cl, 
         const int64_t baseF = off + (int64_t)s * m, baseB = off + ((int64_t)pp + s) * m;   // rows [kind][stage][0]
 
         // level windows of this lane on x = level - s (see kernels_simulate.hpp)
-        int f1hi, f2lo = 1, f2hi = 0, blo, bhi;
-        if (sched == 0) {
-            f1hi = m - 1;
-            blo = m + 2 * pp - 2 - 2 * s; bhi = blo + m - 1;
-        } else {
-            int wq = pp - 1 - s; if (wq > m) wq = m;
-            f1hi = wq < m - 1 ? wq : m - 1;
-            f2lo = 2 * wq + 2; f2hi = 2 * m - 2;
-            blo = 2 * pp - 1 - 2 * s; bhi = blo + 2 * m - 2;
-        }
+        const LevelWindows lw(m, pp, s);
+        const int f1hi = lw.f1hi, f2lo = lw.f2lo, f2hi = lw.f2hi, blo = lw.blo, bhi = lw.bhi;
         const int nlev = wave_max_i32(act ? 2 * (m + pp - 1) : 0);
         double own = 0.0;
         double linkF = 0.0, linkB = 0.0;                      // p2p_blocking = 2: arrival of the lane's latest sends
@@ -213,7 +203,7 @@ __global__ __launch_bounds__(kWave) void k_timeline(CostsDev co, ClusterDev cl, 
             const uint32_t even_x = (x0 & 1) ? 0x55555555u : 0xaaaaaaaau;
             uint32_t PFb = level_bits(-x0, f1hi - x0) | (level_bits(f2lo - x0, f2hi - x0) & even_x);
             uint32_t PBb = level_bits(blo - x0, bhi - x0);
-            if (sched != 0) PBb &= ((blo - x0) & 1) ? 0x55555555u : 0xaaaaaaaau;
+            PBb &= ((blo - x0) & 1) ? 0x55555555u : 0xaaaaaaaau;
             if (!act) { PFb = 0; PBb = 0; }
             const bool anyF = wave_or_u32(PFb) != 0, anyB = wave_or_u32(PBb) != 0;
             const int kend = nlev - l0 < 32 ? nlev - l0 : 32;
@@ -342,8 +332,8 @@ __global__ __launch_bounds__(kWave) void k_timeline(CostsDev co, ClusterDev cl, 
 // forms the four scans of stage s and leaves (end of the first task, step per micro-batch,
 // duration) of its two rows in LDS; then all threads write the candidate's block entry by entry,
 // consecutive threads consecutive entries, every wavefront 512 contiguous bytes of each array per
-// store instruction.  Not for p2p_blocking = 2 (sends queue on their links; those candidates stay
-// with k_timeline).
+// store instruction.  With p2p_blocking = 2 (sends queue on their links) a link is one more machine
+// of the flow shop and its transfer time enters the two maxima.
 constexpr int kTlGpipeBlock = 256;
 struct alignas(16) TlGpipeRow { double end0, step, dur, spare; };
 __global__ __launch_bounds__(kTlGpipeBlock) void k_timeline_gpipe(CostsDev co, ClusterDev cl, CandDev ca, Workspace ws,
@@ -384,6 +374,7 @@ __global__ __launch_bounds__(kTlGpipeBlock) void k_timeline_gpipe(CostsDev co, C
             if (!(in && s + 1 < pp)) pbR = 0.0;
             // prefix sum and maximum over the stages up to s, suffix sum and maximum over those from s on
             double A = Fd + pfL, MF = Fd, T = Bd + pbR, MB = Bd;
+            if (cl.blocking == 2) { MF = max_f64(Fd, pfL); MB = max_f64(Bd, pbR); }
             for (int d = 1; d < kWave; d <<= 1) {
                 const bool up = lane >= d, dn = lane + d < kWave;
                 const int au = (up ? lane - d : lane) * 4, ad = (dn ? lane + d : lane) * 4;

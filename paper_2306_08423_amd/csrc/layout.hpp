@@ -16,7 +16,7 @@ constexpr int kSchedCap = 4096;
 constexpr int64_t kSchedOpsCap = 1 << 17;
 constexpr int kSchedMaxPool = 256, kSchedWavePool = 256;
 struct SchedHdr {
-    int32_t state;                 // kSchedTable / kSchedCompiled / kSchedInvalid
+    int32_t state;                 // kSchedTable / kSchedCompiled / kSchedInvalid / kSchedStuck
     int32_t n_rounds, depth;       // rounds of the program, entries per ring
     int32_t n_send;                // tasks that are followed by a transfer
 };

@@ -213,11 +213,13 @@ def test_gpipe_flow_shop_closed_form(oracle_mod):
         assert r["batch_ns"][0] == batch, (trial, pp, m, bnd)
 
 
-@pytest.mark.parametrize("blocking", [0, 1])
+@pytest.mark.parametrize("blocking", [0, 1, 2])
 def test_gpipe_flow_shop_every_task(oracle_mod, blocking):
     """The same flow shop, task by task: end F(s, j) = sum_{i<=s} (F_i + pf_i) + j max_{i<=s} F_i and
-    end B(s, j) = end F(pp-1, m-1) + sum_{i>=s} (B_i + pb_i) + j max_{i>=s} B_i, where a sender that is
-    occupied by its send (p2p_blocking = 1) has the send in its task and the edge costs nothing."""
+    end B(s, j) = end F(pp-1, m-1) + sum_{i>=s} (B_i + pb_i) + j max_{i>=s} B_i.  A sender that is
+    occupied by its send (p2p_blocking = 1) has the send in its task and the edge costs nothing; a link
+    that carries one transfer at a time (p2p_blocking = 2) is one more machine between its two stages,
+    so its transfer time is among the maxima."""
     rng = np.random.default_rng(12)
     L = 16
     for trial in range(200):
@@ -227,20 +229,21 @@ def test_gpipe_flow_shop_every_task(oracle_mod, blocking):
         bnd = [0] + cuts + [L]
         fc = rng.integers(0, 1000, L).tolist()
         bc = rng.integers(0, 2000, L).tolist()
-        act = (rng.integers(0, 50, L) * 200).tolist()
+        act = (rng.integers(0, 400, L) * 200).tolist()                          # transfers as long as stage-tasks
         alpha = int(rng.integers(0, 300))
         costs = mk_costs(fc, bc, act=act)
         cl = mk_cluster(pp, g=1 << 20, alpha=(alpha, 0), beta=(200, 1), blocking=blocking)
         r = one(oracle_mod, costs, cl, (1, 1, pp, m, 0, bnd), timeline=True)
         F, B = _stage_sums(fc, bnd), _stage_sums(bc, bnd)
         edge = [alpha + act[bnd[s + 1] - 1] // 200 for s in range(pp - 1)]      # between s and s + 1
-        if blocking:
+        if blocking == 1:
             F = [F[s] + (edge[s] if s + 1 < pp else 0) for s in range(pp)]
             B = [B[s] + (edge[s - 1] if s > 0 else 0) for s in range(pp)]
             edge = [0] * (pp - 1)
-        endF = lambda s, j: sum(F[:s + 1]) + sum(edge[:s]) + j * max(F[:s + 1])
+        queue = blocking == 2
+        endF = lambda s, j: sum(F[:s + 1]) + sum(edge[:s]) + j * max(F[:s + 1] + (edge[:s] if queue else []))
         R = endF(pp - 1, m - 1)
-        endB = lambda s, j: R + sum(B[s:]) + sum(edge[s:]) + j * max(B[s:])
+        endB = lambda s, j: R + sum(B[s:]) + sum(edge[s:]) + j * max(B[s:] + (edge[s:] if queue else []))
         for s in range(pp):
             for j in range(m):
                 assert r["end"][0, s, j] == endF(s, j), (trial, "F", s, j)
