@@ -508,12 +508,13 @@ def test_ragged_shapes_and_odd_stage_counts(H, oracle_mod):
     H.assert_same(H.run_hip(w), H.oracle_with_table(oracle_mod, w), what="zeros")
 
 
-def test_gpipe_items_regrouped_two_stages_to_a_lane(H, oracle_mod):
-    """GPipe candidates are swept in pairs of wave-items with two stages to a lane (for long lists;
-    the harness's second context does so for any list).  Items of one
-    class that differ in pp and in m, odd numbers of GPipe items per class (the odd one goes the
-    usual way), odd pp (a lane with a single stage), m = 1, other schedules next to them, blocking
-    p2p, bucketed all-reduce, and per-stage arrays too small for all of them."""
+def test_gpipe_closed_form_items(H, oracle_mod):
+    """GPipe candidates get their end times from the closed form of the recurrence, not from a sweep:
+    in a kernel of their own, in pairs of wave-items (for long lists; the harness's second context
+    does so for any list), and as lanes left out of the sweep elsewhere.  Items of one class that
+    differ in pp and in m, odd numbers of GPipe items per class (the odd one goes the usual way), stage
+    counts that are not powers of two, m = 1, other schedules next to them in one wave-item, all three
+    readings of the p2p events, bucketed all-reduce, and per-stage arrays too small for all of them."""
     _say("[case] GPipe pairs")
     rng = np.random.default_rng(123)
     L = 80
@@ -533,7 +534,7 @@ def test_gpipe_items_regrouped_two_stages_to_a_lane(H, oracle_mod):
         if rng.random() < 0.5:
             bnd = [0] + np.sort(rng.choice(np.arange(1, L), pp - 1, replace=False)).tolist() + [L]
         rows.append((N // (pp * tp), tp, pp, m, sc, bnd))
-    for blocking, bucket in ((0, 0), (1, 0), (0, 1 << 19)):
+    for blocking, bucket in ((2, 0), (0, 0), (1, 0), (0, 1 << 19)):
         w = mk(costs, mk_cluster(N, blocking=blocking, bucket=bucket), rows)
         ora = H.oracle_with_table(oracle_mod, w, NT)
         assert ((ora["status"] == 0) & (w.cand["schedule"] == 0)).sum() > 700
