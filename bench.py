@@ -208,7 +208,28 @@ def measure(ds, torch, ctx, w, steps, warmup, table=False):
     return res, (dw, ev, out, best, scratch, step)
 
 
-def sweep_rooflines(r, traffic, copy_gbs):
+def read_valu_instructions(workload: str):
+    """VALU wave-instructions per step of the two simulate kernels from the committed counter summary
+    (profiles/pmc_sq_bench_<workload>.txt); None when there is none or the kernel sources changed since."""
+    p = os.path.join(ROOT, "profiles", f"pmc_sq_bench_{workload}.txt")
+    if not os.path.exists(p):
+        return None
+    kernel, total, ok = None, 0.0, False
+    for line in open(p):
+        if line.startswith("# kernel_source_sha256_16:"):
+            ok = line.split(":", 1)[1].strip() == kernel_source_hash()
+        elif line.startswith("#"):
+            continue
+        elif not line.startswith(" "):
+            kernel = line.strip()
+        elif kernel in ("k_simulate", "k_simulate_gpipe"):
+            f = line.split()
+            if len(f) == 2 and f[0] == "SQ_INSTS_VALU":
+                total += float(f[1])
+    return total if ok and total > 0 else None
+
+
+def sweep_rooflines(r, traffic, copy_gbs, valu=None):
     """The two views of the sweep kernels (k_simulate and k_simulate_gpipe side by side)."""
     hbm = {
         "kernel": "k_simulate || k_simulate_gpipe", "bound": "hbm",
@@ -234,6 +255,11 @@ def sweep_rooflines(r, traffic, copy_gbs):
     }
     alu["frac"] = alu["achieved"] / alu["peak"]
     alu["frac_of_published_fp64_peak"] = alu["achieved"] / 78.6
+    if valu:
+        # how full the vector issue slots are, whatever the instructions do: counted wave-instructions of
+        # both kernels x 4 cycles each against 1024 SIMDs x 2.4 GHz over the span
+        alu["valu_instructions_per_launch"] = valu
+        alu["valu_issue_frac"] = valu * 4 / (1024 * 2.4e9 * r["sim_avg_s"])
     return hbm, alu
 
 
@@ -460,7 +486,7 @@ def main() -> int:
 
     C = dw.C
     tasks = res["tasks"]
-    roofline, roofline_alu = sweep_rooflines(res, read_traffic(args.workload), copy_gbs)
+    roofline, roofline_alu = sweep_rooflines(res, read_traffic(args.workload), copy_gbs, read_valu_instructions(args.workload))
 
     second = None
     if args.second and args.second != "none" and args.second != args.workload:
