@@ -379,10 +379,36 @@ __device__ __forceinline__ void simulate_items(const ClusterDev& cl, const CandD
             for (int u = 0; u < U; u++) if (gpipe) sw[u].own = fin[u];
         }
         const int f1hi = lw.f1hi, f2lo = lw.f2lo, f2hi = lw.f2hi, blo = lw.blo, bhi = lw.bhi;
-        // Levels at which some lane of the wavefront has a forward / a backward task: forwards from
-        // level 0 to gLastF, backwards from gFirstB to gLastB (the last level of the sweep).
-        const int lastFx = (f2lo <= f2hi && f2hi > f1hi) ? f2hi : f1hi;
-        const int gLastF = wave_max_i32(swept ? s + lastFx : -1);
+        // The warm-up without a sweep.  The forwards in front of a stage's first backward, F(s, j) with
+        // j <= f1hi, depend on F(s-1, j) and F(s, j-1) only, and both lie in the warm-up as well (an
+        // earlier stage warms up at least as long): on that set the recurrence is the flow shop of
+        // gpipe_finish, end F(s, j) = sum_{i<=s} (F_i + pf_i) + j max_{i<=s} F_i.  Every lane starts the
+        // sweep with the end of its last warm-up forward, which is the state the level sweep reaches
+        // at the candidate's first backward (level pp); the levels in front of it are not visited.
+        // One prefix sum and one prefix maximum over the candidate's lanes, exact in fp64.
+        if (__builtin_amdgcn_ballot_w64(swept) != 0) {
+            double acc[U], top[U];
+#pragma unroll
+            for (int u = 0; u < U; u++) {
+                acc[u] = swept ? sw[u].Fd + max_f64(sw[u].pfL, 0.0) : 0.0;     // an edge that does not exist carries -inf
+                top[u] = swept ? sw[u].Fd : 0.0;
+            }
+            for (int dd = 1; dd < width; dd <<= 1) {
+                const bool ok = s >= dd;
+                const int adr = (ok ? lane - dd : lane) * 4;
+#pragma unroll
+                for (int u = 0; u < U; u++) {
+                    const double t = from_lanes(acc[u], adr), x = from_lanes(top[u], adr);
+                    acc[u] += ok ? t : 0.0;
+                    top[u] = max_f64(top[u], x);
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < U; u++) if (swept) sw[u].own = __fma_rn((double)f1hi, top[u], acc[u]);
+        }
+        // Levels at which some lane of the wavefront has a task left: forwards behind the warm-up up to
+        // gLastF, backwards from gFirstB (the first level of the sweep) to gLastB (its last).
+        const int gLastF = wave_max_i32(swept && f2lo <= f2hi ? s + f2hi : -1);
         const int gFirstB = -wave_max_i32(swept ? -(s + blo) : -(1 << 30));
         const int gLastB = wave_max_i32(swept ? s + bhi : -1);
         const int nlev = gLastB + 1;
@@ -396,10 +422,10 @@ __device__ __forceinline__ void simulate_items(const ClusterDev& cl, const CandD
         const bool even_s = (s & 1) == 0;
         const int adrE = (even_s ? lane - 1 : lane + 1) * 4;
 
-        for (int l0 = 0; l0 < nlev; l0 += 32) {
+        for (int l0 = gFirstB; l0 < nlev; l0 += 32) {
             const int x0 = l0 - s;
             const uint32_t even_x = (x0 & 1) ? 0x55555555u : 0xaaaaaaaau;       // levels with even x
-            uint32_t PFb = level_bits(-x0, f1hi - x0) | (level_bits(f2lo - x0, f2hi - x0) & even_x);
+            uint32_t PFb = level_bits(f2lo - x0, f2hi - x0) & even_x;            // the forwards behind the warm-up
             uint32_t PBb = level_bits(blo - x0, bhi - x0);
             PBb &= ((blo - x0) & 1) ? 0x55555555u : 0xaaaaaaaau;                   // x - blo even
             if (!swept) { PFb = 0; PBb = 0; }

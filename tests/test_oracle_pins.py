@@ -250,6 +250,37 @@ def test_gpipe_flow_shop_every_task(oracle_mod, blocking):
                 assert r["end"][1, s, j] == endB(s, j), (trial, "B", s, j)
 
 
+@pytest.mark.parametrize("blocking", [0, 1])
+@pytest.mark.parametrize("sched", [1, 2])
+def test_early_backward_warm_up_is_a_flow_shop(oracle_mod, sched, blocking):
+    """The forwards that a stage of the early-backward schedule runs in front of its first backward,
+    F(s, j) with j <= min(pp - 1 - s, m - 1), depend only on forwards of the same set, so they pass the
+    stages as identical jobs pass the machines of a flow shop:
+    end F(s, j) = sum_{i<=s} (F_i + pf_i) + j max_{i<=s} F_i, whatever the backwards behind them do."""
+    rng = np.random.default_rng(21)
+    L = 16
+    for trial in range(200):
+        pp = int(rng.integers(1, 12))
+        m = int(rng.integers(1, 14))
+        cuts = sorted(rng.choice(np.arange(1, L), size=pp - 1, replace=False).tolist())
+        bnd = [0] + cuts + [L]
+        fc = rng.integers(0, 1000, L).tolist()
+        bc = rng.integers(0, 2000, L).tolist()
+        act = (rng.integers(0, 400, L) * 200).tolist()
+        alpha = int(rng.integers(0, 300))
+        costs = mk_costs(fc, bc, act=act)
+        cl = mk_cluster(pp, g=1 << 20, alpha=(alpha, 0), beta=(200, 1), blocking=blocking)
+        r = one(oracle_mod, costs, cl, (1, 1, pp, m, sched, bnd), timeline=True)
+        F = _stage_sums(fc, bnd)
+        edge = [alpha + act[bnd[s + 1] - 1] // 200 for s in range(pp - 1)]      # between s and s + 1
+        if blocking == 1:
+            F = [F[s] + (edge[s] if s + 1 < pp else 0) for s in range(pp)]
+            edge = [0] * (pp - 1)
+        for s in range(pp):
+            for j in range(min(pp - 1 - s, m - 1) + 1):
+                assert r["end"][0, s, j] == sum(F[:s + 1]) + sum(edge[:s]) + j * max(F[:s + 1]), (trial, s, j)
+
+
 @pytest.mark.parametrize("sched", [0, 1])
 def test_degenerate_cases(oracle_mod, sched):
     L = 6
