@@ -325,11 +325,32 @@ __device__ __forceinline__ void simulate_items(const ClusterDev& cl, const CandD
         // candidate's stage); the link time of a lane without a receiver is never looked at either
         const double gateL = act && s > 0 ? 0.0 : ninf, gateR = act && s + 1 < pp ? 0.0 : ninf;
         double own = 0.0, linkF = 0.0, linkB = 0.0;
+        // The warm-up forwards in closed form, as in the sweep without queues (below): with a link that
+        // carries one transfer at a time the shop has one more machine between two stages, the link.
+        // end F(s, j) = (sum + j max) over the stages up to s and the links in front of s; the arrival
+        // of stage s's latest send adds its own link to both.
+        {
+            const double before = from_prev_lane(sendF[0]);
+            const double inL = swept && s > 0 ? before : 0.0;              // transfer on the link into this stage
+            double acc = swept ? sw[0].Fd + inL : 0.0, top = swept ? max_f64(sw[0].Fd, inL) : 0.0;
+            for (int dd = 1; dd < width; dd <<= 1) {
+                const bool ok = s >= dd;
+                const int adr = (ok ? lane - dd : lane) * 4;
+                const double t = from_lanes(acc, adr), x = from_lanes(top, adr);
+                acc += ok ? t : 0.0;
+                top = max_f64(top, x);
+            }
+            if (swept) {
+                own = __fma_rn((double)f1hi, top, acc);
+                linkF = __fma_rn((double)f1hi, max_f64(top, sendF[0]), acc + sendF[0]);
+            }
+        }
+        const int first = -wave_max_i32(swept ? -(s + blo) : -(1 << 30));      // level of the first backward
         uint64_t kmask;
-        for (int l0 = 0; l0 < nlev; l0 += 32) {
+        for (int l0 = first; l0 < nlev; l0 += 32) {
             const int x0 = l0 - s;
             const uint32_t even_x = (x0 & 1) ? 0x55555555u : 0xaaaaaaaau;
-            uint32_t PFb = level_bits(-x0, f1hi - x0) | (level_bits(f2lo - x0, f2hi - x0) & even_x);
+            uint32_t PFb = level_bits(f2lo - x0, f2hi - x0) & even_x;               // the forwards behind the warm-up
             uint32_t PBb = level_bits(blo - x0, bhi - x0);
             PBb &= ((blo - x0) & 1) ? 0x55555555u : 0xaaaaaaaau;
             if (!swept) { PFb = 0; PBb = 0; }

@@ -250,13 +250,14 @@ def test_gpipe_flow_shop_every_task(oracle_mod, blocking):
                 assert r["end"][1, s, j] == endB(s, j), (trial, "B", s, j)
 
 
-@pytest.mark.parametrize("blocking", [0, 1])
+@pytest.mark.parametrize("blocking", [0, 1, 2])
 @pytest.mark.parametrize("sched", [1, 2])
 def test_early_backward_warm_up_is_a_flow_shop(oracle_mod, sched, blocking):
     """The forwards that a stage of the early-backward schedule runs in front of its first backward,
     F(s, j) with j <= min(pp - 1 - s, m - 1), depend only on forwards of the same set, so they pass the
     stages as identical jobs pass the machines of a flow shop:
-    end F(s, j) = sum_{i<=s} (F_i + pf_i) + j max_{i<=s} F_i, whatever the backwards behind them do."""
+    end F(s, j) = sum_{i<=s} (F_i + pf_i) + j max_{i<=s} F_i, whatever the backwards behind them do
+    (with one transfer per link at a time, p2p_blocking = 2, the links in front of s join the maximum)."""
     rng = np.random.default_rng(21)
     L = 16
     for trial in range(200):
@@ -278,7 +279,8 @@ def test_early_backward_warm_up_is_a_flow_shop(oracle_mod, sched, blocking):
             edge = [0] * (pp - 1)
         for s in range(pp):
             for j in range(min(pp - 1 - s, m - 1) + 1):
-                assert r["end"][0, s, j] == sum(F[:s + 1]) + sum(edge[:s]) + j * max(F[:s + 1]), (trial, s, j)
+                top = max(F[:s + 1] + (edge[:s] if blocking == 2 else []))
+                assert r["end"][0, s, j] == sum(F[:s + 1]) + sum(edge[:s]) + j * top, (trial, s, j)
 
 
 @pytest.mark.parametrize("sched", [0, 1])
