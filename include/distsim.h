@@ -307,7 +307,9 @@ int distsim_build_events(distsim_ctx *ctx, const distsim_costs *costs, const dis
  * Outputs (device): batch_ns[C] = time of the last event (INT64_MAX unless status OK);
  * comp_busy_ns / comm_busy_ns [stage_cap] = sum of the durations of the computation /
  * communication events on each stage's device (index stage_pos[c] + s); util (may be NULL)
- * = comp_busy / batch as fp64; entries not owned by an OK candidate are written as zero.
+ * = comp_busy / batch as fp64; of the entries that the library lays candidates out in (the first
+ * min(U, stage_cap) of distsim_build_events' description), those not owned by an OK candidate are
+ * written as zero; entries from there on are not touched.
  * Also writes num_events[c], and the status of candidates whose partition is invalid or
  * whose times would leave the 2^53 range (final values; distsim_build_events has already
  * written the same ones if it was asked for the stage table).  `events` must come from
