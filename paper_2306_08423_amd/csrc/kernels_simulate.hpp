@@ -471,7 +471,7 @@ __device__ __forceinline__ void simulate_items(const ClusterDev& cl, const CandD
                     // roles by parity: on even levels the even stages run forwards, on odd levels
                     // the odd stages do
                     double latE[U], durE[U], latO[U], durO[U];
-    #pragma unroll
+#pragma unroll
                     for (int u = 0; u < U; u++) {
                         latE[u] = even_s ? sw[u].pfL : sw[u].pbR; durE[u] = even_s ? sw[u].Fd : sw[u].Bd;
                         latO[u] = even_s ? sw[u].pbR : sw[u].pfL; durO[u] = even_s ? sw[u].Bd : sw[u].Fd;
@@ -545,68 +545,81 @@ __device__ __forceinline__ void simulate_items(const ClusterDev& cl, const CandD
 #pragma unroll
     for (int u = 0; u < U; u++) {
         // data-parallel modelling: gradient all-reduce after (or overlapped with) the last backward
-        const int64_t endB = (int64_t)sw[u].own;
         const int64_t AR = park.ar[u][slot];
         const int misc = park.misc[u][slot];
         const bool has_ar = (misc >> 16) & 1, dropped = (misc >> 17) & 1;
-        int64_t finish = endB + AR, ar_busy = AR, nar = has_ar ? 1 : 0;
-        if (has_ar && cl.bucket > 0) {
-            // Bucketed gradient all-reduce behind the last micro-batch's backward: layer l (taken from
-            // hi - 1 down to lo) is ready at r_l = start of that backward + its events from hi - 1
-            // down to l, the open bucket then holds the bytes of the layers l..hi-1 modulo the bucket
-            // size, every full bucket is issued at once and the events queue on the device's
-            // communication stream, t <- max(t, r_l) + (buckets issued at l) * ar_cap; the rest goes
-            // after the stage's first layer.  Unrolled, that max-plus chain is
-            //   t = max over l of  r_l + (events issued at the layers l, l-1, ..., lo)
-            // and the number of full buckets issued by the layers above l is floor(bytes above l /
-            // bucket size), so every term stands on its own: no chain through the layers, and their
-            // table reads are independent.  (A layer that issues nothing adds a term that the next
-            // issuing layer below it, or the end of the backward itself, dominates.)
-            const int lo = misc & 0xff, hi = (misc >> 8) & 0xff, v = misc >> 18, dp = park.dp[u][slot];
-            // per layer boundary: backward time of the layers below it (word 1), their gradient bytes (word 3)
-            const int64_t* row = ws.comb + (size_t)((v * kMaxPP + ppv[u] - 1) * (L + 1)) * kCombWords;
-            const int64_t startB = endB - (int64_t)sw[u].Bd;
-            const int64_t tot_hi = row[hi * kCombWords + 1], g_hi = row[hi * kCombWords + 3];
-            const int64_t ar_cap = allreduce_ns(cl, dp, cl.bucket);
-            const int64_t G = g_hi - row[lo * kCombWords + 3];
-            const int64_t full = (int64_t)udiv64_by((uint64_t)G, (uint64_t)cl.bucket, cl.inv_bucket);
-            const int64_t rest = G - full * cl.bucket;
-            const int64_t dlast = rest > 0 ? allreduce_ns(cl, dp, rest) : 0;
-            ar_busy = full * ar_cap + dlast;
-            nar = full + (rest > 0 ? 1 : 0);
-            const int64_t all = startB + tot_hi + ar_busy;          // r_l + events from l down = all - (time below l) - (events above l)
-            int64_t t = endB;
-            // four layers at a time, their table entries requested together (at clamped, always valid
-            // addresses): a trip to memory per four layers instead of one per layer
-            constexpr int kBatch = 4;
-            for (int l0 = lo; l0 < hi; l0 += kBatch) {
-                int64_t gb[kBatch], tb[kBatch];
+        const bool live = actv[u] && !dropped;      // lanes outside a candidate and dropped candidates have zero rows
+        int64_t ar_busy = AR, nar = has_ar ? 1 : 0;
+        int64_t batch = 0;
+        double batch_d = 0.0;
+        // One trailing event: the end of the batch can stay in fp64.  Sums below 2^52 are exact (both
+        // terms are integers); a wavefront in which some lane's sum is not takes the integer path.
+        bool in_f64 = cl.bucket <= 0;
+        if (in_f64) {
+            batch_d = group_max_f64(live ? sw[u].own + (double)AR : 0.0, width);
+            in_f64 = __builtin_amdgcn_ballot_w64(!(batch_d < 4503599627370496.0)) == 0;
+            batch = small_double_to_i64(batch_d);
+        }
+        if (!in_f64) {
+            const int64_t endB = (int64_t)sw[u].own;
+            int64_t finish = endB + AR;
+            if (has_ar && cl.bucket > 0) {
+                // Bucketed gradient all-reduce behind the last micro-batch's backward: layer l (taken from
+                // hi - 1 down to lo) is ready at r_l = start of that backward + its events from hi - 1
+                // down to l, the open bucket then holds the bytes of the layers l..hi-1 modulo the bucket
+                // size, every full bucket is issued at once and the events queue on the device's
+                // communication stream, t <- max(t, r_l) + (buckets issued at l) * ar_cap; the rest goes
+                // after the stage's first layer.  Unrolled, that max-plus chain is
+                //   t = max over l of  r_l + (events issued at the layers l, l-1, ..., lo)
+                // and the number of full buckets issued by the layers above l is floor(bytes above l /
+                // bucket size), so every term stands on its own: no chain through the layers, and their
+                // table reads are independent.  (A layer that issues nothing adds a term that the next
+                // issuing layer below it, or the end of the backward itself, dominates.)
+                const int lo = misc & 0xff, hi = (misc >> 8) & 0xff, v = misc >> 18, dp = park.dp[u][slot];
+                // per layer boundary: backward time of the layers below it (word 1), their gradient bytes (word 3)
+                const int64_t* row = ws.comb + (size_t)((v * kMaxPP + ppv[u] - 1) * (L + 1)) * kCombWords;
+                const int64_t startB = endB - (int64_t)sw[u].Bd;
+                const int64_t tot_hi = row[hi * kCombWords + 1], g_hi = row[hi * kCombWords + 3];
+                const int64_t ar_cap = allreduce_ns(cl, dp, cl.bucket);
+                const int64_t G = g_hi - row[lo * kCombWords + 3];
+                const int64_t full = (int64_t)udiv64_by((uint64_t)G, (uint64_t)cl.bucket, cl.inv_bucket);
+                const int64_t rest = G - full * cl.bucket;
+                const int64_t dlast = rest > 0 ? allreduce_ns(cl, dp, rest) : 0;
+                ar_busy = full * ar_cap + dlast;
+                nar = full + (rest > 0 ? 1 : 0);
+                const int64_t all = startB + tot_hi + ar_busy;          // r_l + events from l down = all - (time below l) - (events above l)
+                int64_t t = endB;
+                // four layers at a time, their table entries requested together (at clamped, always valid
+                // addresses): a trip to memory per four layers instead of one per layer
+                constexpr int kBatch = 4;
+                for (int l0 = lo; l0 < hi; l0 += kBatch) {
+                    int64_t gb[kBatch], tb[kBatch];
 #pragma unroll
-                for (int i = 0; i < kBatch; i++) {
-                    const int l = l0 + i < hi ? l0 + i : hi - 1;
-                    gb[i] = row[(l + 1) * kCombWords + 3];
-                    tb[i] = row[l * kCombWords + 1];
-                }
+                    for (int i = 0; i < kBatch; i++) {
+                        const int l = l0 + i < hi ? l0 + i : hi - 1;
+                        gb[i] = row[(l + 1) * kCombWords + 3];
+                        tb[i] = row[l * kCombWords + 1];
+                    }
 #pragma unroll
-                for (int i = 0; i < kBatch; i++) {
-                    const int64_t above = (int64_t)udiv64_by((uint64_t)(g_hi - gb[i]), (uint64_t)cl.bucket, cl.inv_bucket);
-                    const int64_t term = all - tb[i] - above * ar_cap;      // a clamped entry repeats the last layer's term
-                    t = term > t ? term : t;
+                    for (int i = 0; i < kBatch; i++) {
+                        const int64_t above = (int64_t)udiv64_by((uint64_t)(g_hi - gb[i]), (uint64_t)cl.bucket, cl.inv_bucket);
+                        const int64_t term = all - tb[i] - above * ar_cap;      // a clamped entry repeats the last layer's term
+                        t = term > t ? term : t;
+                    }
                 }
+                finish = t;
             }
-            finish = t;
+            batch = group_max(live ? finish : 0, width);
+            batch_d = (double)batch;
         }
         // one event per stage that has one, or the stages' bucket counts
         nar = cl.bucket > 0 ? group_sum(nar, width) : group_count(has_ar, width);
-        const int64_t batch = group_max(actv[u] && !dropped ? finish : 0, width);
-        // lanes outside a candidate and dropped candidates have zero rows: they store zeros
-        const bool live = actv[u] && !dropped;
         const int64_t comp = live ? (int64_t)mv[u] * park.comp[u][slot] : 0;
         const int64_t comm = live ? (int64_t)mv[u] * park.comm[u][slot] + ar_busy : 0;
         const int64_t i = (w0 + u) * kWave + lane;
         out.comp_busy[i] = comp;
         out.comm_busy[i] = comm;
-        if (out.util) out.util[i] = batch > 0 ? (double)comp / (double)batch : 0.0;
+        if (out.util) out.util[i] = batch > 0 ? (double)comp / batch_d : 0.0;
         if (live && s == 0) {
             const int64_t cc = park.cand[u][slot];
             out.batch_ns[cc] = batch;
