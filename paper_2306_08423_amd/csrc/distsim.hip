@@ -396,7 +396,7 @@ int distsim_simulate(distsim_ctx* ctx, const distsim_cluster* cluster, const dis
                  events->num_events};
     SimOut out{batch_ns, comp_busy_ns, comm_busy_ns, util};
     // k_sim_init marks the candidates that k_decode rejected; the sweeps write the others' results,
-    // so it may run beside them
+    // so that work may run beside them: for a long list k_simulate_gpipe does it on its way in
     const bool beside = cl.blocking != 2 && C >= ctx->split_min_items;
     if (!beside) {
         Timer t(ctx, st, DISTSIM_K_SIM_INIT);
@@ -419,12 +419,9 @@ int distsim_simulate(distsim_ctx* ctx, const distsim_cluster* cluster, const dis
         HIP_TRY(hipStreamWaitEvent(ctx->side, ctx->fork, 0));
         hipLaunchKernelGGL(k_simulate, dim3(general_grid(ctx, C)), dim3(kSimBlock), 0, st, co, cl, ca, ws, ev, out);
         {
-            Timer ti(ctx, ctx->side, DISTSIM_K_SIM_INIT);
-            hipLaunchKernelGGL(k_sim_init, dim3((int)((C + 255) / 256)), dim3(256), 0, ctx->side, events->status, C, batch_ns);
-        }
-        {
+            // its first threads mark the rejected candidates (k_sim_init's work)
             Timer tg(ctx, ctx->side, DISTSIM_K_SIMULATE_GPIPE);
-            hipLaunchKernelGGL(k_simulate_gpipe, dim3(gpipe_grid(ctx, C)), dim3(kSimBlock), 0, ctx->side, co, cl, ca, ws, ev, out);
+            hipLaunchKernelGGL(k_simulate_gpipe, dim3(gpipe_grid(ctx, C)), dim3(kSimBlock), 0, ctx->side, co, cl, ca, ws, ev, out, C);
         }
         HIP_TRY(hipEventRecord(ctx->join, ctx->side));
         HIP_TRY(hipStreamWaitEvent(st, ctx->join, 0));

@@ -728,9 +728,13 @@ __global__ __launch_bounds__(kSimBlock, 6) void k_simulate(CostsDev co, ClusterD
     simulate_all<false>(co, cl, ca, ws, ev, out, park);
 }
 
+// init_C > 0: the launch also does k_sim_init's work for the candidates [0, init_C) first (it runs beside
+// k_simulate then, and one launch less stands in front of it on its stream).
 __global__ __launch_bounds__(kSimBlock, 6) void k_simulate_gpipe(CostsDev co, ClusterDev cl, CandDev ca, Workspace ws,
-                                                                 EventsDev ev, SimOut out) {
+                                                                 EventsDev ev, SimOut out, int64_t init_C) {
     __shared__ Park park;
+    for (int64_t c = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; c < init_C; c += (int64_t)gridDim.x * blockDim.x)
+        if (ev.status[c] != 0) out.batch_ns[c] = INT64_MAX;
     simulate_all<true>(co, cl, ca, ws, ev, out, park);
 }
 
