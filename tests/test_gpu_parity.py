@@ -881,6 +881,62 @@ def test_invalid_range_and_capacity_status(H, oracle_mod):
     assert H.run_hip(w4, stage_cap=0)["status"].tolist() == [3, 3, 3]
 
 
+def test_batch_ends_at_and_above_two_to_the_52(H, oracle_mod):
+    """With one trailing all-reduce event the kernels keep the end of the batch in fp64 as long as every
+    stage's end + event stays below 2^52 and take integers otherwise: ends between 2^52 and 2^53, events
+    that push the sum past 2^53 (odd sums there have no double), and small candidates beside them."""
+    _say("[case] batch ends at and above 2^52")
+    for sched in (0, 1, 2):
+        # pp = 2, m = 1: the first stage ends at 16 * 2^48 + 3 = 2^52 + 3
+        costs = mk_costs([3 << 48, (3 << 48) + 1, 3 << 48, 3 << 48], [1 << 48, 1 << 48, (1 << 48) + 2, 1 << 48],
+                         grad=[(1 << 52) + 1, 5, 1 << 40, 7], act=[0] * 4)
+        cl = mk_cluster(4, g=8, alpha=(0, 0), beta=(1, 1))
+        rows = [(2, 1, 2, 1, sched, [0, 2, 4]), (2, 1, 2, 1, sched, [0, 1, 4]), (4, 1, 1, 1, sched, None),
+                (2, 1, 2, 1, sched, [0, 3, 4])]
+        w = mk(costs, cl, rows)
+        hip, ora = H.run_hip(w), H.oracle_with_table(oracle_mod, w)
+        assert (ora["status"] == 0).all() and (ora["batch_ns"] >= 1 << 52).all()
+        assert (ora["batch_ns"] % 2 == 1).any() and (sched == 2 or ((ora["batch_ns"] > 1 << 53) & (ora["batch_ns"] % 2 == 1)).any())
+        H.assert_same(hip, ora, what=f"ends above 2^52, schedule {sched}")
+        H.assert_same(H.run_hip(w, table=False, split=True), ora, what=f"ends above 2^52, schedule {sched}, two launches")
+    # small and large candidates in one list (they share wavefronts of their class)
+    small = mk_costs([3, 4, 5, 6], [7, 8, 9, 10], grad=[1 << 52, 1, 1, 1], act=[0] * 4)
+    rows = [(2, 1, 2, m, sc, [0, 2, 4]) for m in (1, 2, 5) for sc in (0, 1)] + [(4, 1, 1, 3, 1, None)]
+    w = mk(small, mk_cluster(4, g=8, alpha=(0, 0), beta=(1, 1)), rows)
+    hip, ora = H.run_hip(w), H.oracle_with_table(oracle_mod, w)
+    assert (ora["status"] == 0).all() and (ora["batch_ns"] > 1 << 51).any()
+    H.assert_same(hip, ora, what="huge trailing events on short pipelines")
+
+
+def test_warm_up_shapes_of_the_early_backward_schedules(H, oracle_mod):
+    """The warm-up forwards of 1F1B and of the asynchronous schedule come from a closed form and the
+    sweep starts at the first backward: every relation of m to pp (m = 1, m < pp, m = pp, m = pp + 1,
+    m >> pp), stage counts that are not powers of two, all three readings of the p2p events, GPipe
+    candidates beside them, both ways of launching."""
+    _say("[case] warm-up shapes")
+    rng = np.random.default_rng(77)
+    L = 72
+    costs = mk_costs(rng.integers(1, 5000, (2, L)).tolist(), rng.integers(1, 9000, (2, L)).tolist(),
+                     fa=rng.integers(0, 300, (2, L)).tolist(), ba=rng.integers(0, 300, (2, L)).tolist(),
+                     act=(rng.integers(0, 300, (2, L)) * 200).tolist(), grad=rng.integers(0, 1 << 20, (2, L)).tolist(),
+                     tps=(1, 2))
+    N = 64 * 27 * 25 * 7 * 11
+    rows = []
+    for pp in (1, 2, 3, 4, 5, 7, 8, 9, 15, 16, 17, 31, 32, 33, 48, 63, 64):
+        if N % pp:
+            continue
+        for m in sorted({1, 2, max(1, pp - 1), pp, pp + 1, 2 * pp + 3, 150}):
+            for sc in (1, 2, 0):
+                bnd = [0] + np.sort(rng.choice(np.arange(1, L), pp - 1, replace=False)).tolist() + [L]
+                rows.append((N // pp, 1, pp, m, sc, bnd))
+    for blocking in (0, 1, 2):
+        w = mk(costs, mk_cluster(N, blocking=blocking), rows)
+        ora = H.oracle_with_table(oracle_mod, w, NT)
+        assert (ora["status"] == 0).all()
+        H.assert_same(H.run_hip(w, table=False), ora, what=f"warm-up shapes blocking={blocking}")
+        H.assert_same(H.run_hip(w, table=False, split=True), ora, what=f"warm-up shapes blocking={blocking}, two launches")
+
+
 def test_empty_candidate_list(H):
     _say("[case] C = 0")
     w = mk(mk_costs([1, 2], [3, 4]), mk_cluster(2), [])
