@@ -669,7 +669,10 @@ int distsim_dedup_events(distsim_ctx* ctx, const int64_t* records, int64_t n, in
     if (n > 0) {
         hipLaunchKernelGGL(k_dedup_clear, dim3((unsigned)((d.table_size + 255) / 256)), dim3(256), 0, st, d.table,
                            d.table_size);
-        hipLaunchKernelGGL(k_dedup_insert, dim3((unsigned)((n + kDedupBlock - 1) / kDedupBlock)), dim3(kDedupBlock), 0, st, records, n, (int)K,
+        // dynamic LDS: the workgroup's records (K words of 8 B for each of its threads), for records of up to
+        // kDedupStagedWords words; longer ones are compared through memory
+        hipLaunchKernelGGL(k_dedup_insert, dim3((unsigned)((n + kDedupBlock - 1) / kDedupBlock)), dim3(kDedupBlock),
+                           K <= kDedupStagedWords ? (size_t)K * kDedupBlock * sizeof(int64_t) : 0, st, records, n, (int)K,
                            d.table, d.table_size, d.slot_of);
         hipLaunchKernelGGL(k_dedup_scan_blocks, dim3((unsigned)nb), dim3(kScanBlock), 0, st, d.table, d.slot_of, n,
                            d.excl, d.block_tot);

@@ -33,11 +33,16 @@ __global__ __launch_bounds__(256) void k_dedup_clear(int32_t* __restrict__ table
 // popular operator is in nearly every wavefront; without the merge all of them would read the same
 // slot and the same representative record, one L2 channel serving them one after the other.
 constexpr int kDedupBlock = 512, kDedupLocal = 2 * kDedupBlock;
+constexpr int kDedupStagedWords = 12;        // records of up to that many words are staged in LDS (48 KB)
 __global__ __launch_bounds__(kDedupBlock) void k_dedup_insert(const int64_t* __restrict__ rec, int64_t n, int K,
                                                               int32_t* table, int64_t size, int32_t* __restrict__ slot_of) {
+    const bool in_lds = K <= kDedupStagedWords;     // the launch brings K * kDedupBlock * 8 bytes of dynamic LDS then
     __shared__ int32_t local[kDedupLocal];      // thread that claimed the local slot | bits of its hash << 9, -1 = empty
     __shared__ int32_t lowest[kDedupBlock];     // by claiming thread: smallest record index among its equals
     __shared__ int32_t global_slot[kDedupBlock];
+    // the workgroup's records, word k of thread t at staged[k * kDedupBlock + t]: a record that meets
+    // an equal one in the workgroup's table is compared with it here, not through memory
+    extern __shared__ int64_t staged[];
     const int tid = threadIdx.x;
     const int64_t base = (int64_t)blockIdx.x * kDedupBlock, i = base + tid;
     for (int q = tid; q < kDedupLocal; q += kDedupBlock) local[q] = -1;
@@ -49,8 +54,11 @@ __global__ __launch_bounds__(kDedupBlock) void k_dedup_insert(const int64_t* __r
     if (i < n) {
 #pragma unroll
         for (int k = 0; k < kMaxRecordWords; k++) {
-            if (k < K) { w[k] = rec[i * K + k]; h = mix64(h ^ (uint64_t)w[k]); }
+            if (k < K) { w[k] = rec[i * K + k]; h = mix64(h ^ (uint64_t)w[k]); if (in_lds) staged[k * kDedupBlock + tid] = w[k]; }
         }
+    }
+    __syncthreads();
+    if (i < n) {
         // the workgroup's own table: other bits of the hash than the table in memory uses
         // an entry is the claiming thread and 22 more bits of its hash, so that records are compared
         // word for word only when those agree
@@ -67,7 +75,7 @@ __global__ __launch_bounds__(kDedupBlock) void k_dedup_insert(const int64_t* __r
             if (same) {
 #pragma unroll
                 for (int k = 0; k < kMaxRecordWords; k++)
-                    if (k < K && rec[(base + (cur & 511)) * K + k] != w[k]) same = false;
+                    if (k < K && (in_lds ? staged[k * kDedupBlock + (cur & 511)] : rec[(base + (cur & 511)) * K + k]) != w[k]) same = false;
             }
             if (same) leader = cur & 511;
             else pos = (pos + 1) & (kDedupLocal - 1);

@@ -30,7 +30,7 @@ def _dedup_hip(H, rec):
 
 
 @pytest.mark.parametrize("n,distinct,K", [(1, 1, 1), (63, 5, 2), (1025, 40, 6), (4097, 4097, 3), (300_000, 7000, 6),
-                                          (70_000, 1, 16), (2048, 300, 5), (5000, 3, 1), (513, 513, 7), (100_000, 90_000, 4)])
+                                          (70_000, 1, 16), (30_000, 500, 12), (30_000, 500, 13), (2048, 300, 5), (5000, 3, 1), (513, 513, 7), (100_000, 90_000, 4)])
 def test_dedup_parity(H, n, distinct, K):
     from oracle.ingest import dedup_events
     from workloads import make_operator_records
