@@ -929,10 +929,15 @@ def test_warm_up_shapes_of_the_early_backward_schedules(H, oracle_mod):
             for sc in (1, 2, 0):
                 bnd = [0] + np.sort(rng.choice(np.arange(1, L), pp - 1, replace=False)).tolist() + [L]
                 rows.append((N // pp, 1, pp, m, sc, bnd))
+    # strategies that event generation rejects, in between: the launch that runs beside k_simulate marks them
+    nbad = 0
+    for at in (3, 40, 41, len(rows) - 1):
+        rows.insert(at, (7, 1, 5, 4, 1, None))          # dp tp pp is not the number of devices
+        nbad += 1
     for blocking in (0, 1, 2):
         w = mk(costs, mk_cluster(N, blocking=blocking), rows)
         ora = H.oracle_with_table(oracle_mod, w, NT)
-        assert (ora["status"] == 0).all()
+        assert (ora["status"] != 0).sum() == nbad and (ora["batch_ns"][ora["status"] != 0] == INT64_MAX).all()
         H.assert_same(H.run_hip(w, table=False), ora, what=f"warm-up shapes blocking={blocking}")
         H.assert_same(H.run_hip(w, table=False, split=True), ora, what=f"warm-up shapes blocking={blocking}, two launches")
 
