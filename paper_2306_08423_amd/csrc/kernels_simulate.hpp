@@ -617,9 +617,10 @@ __device__ __forceinline__ void simulate_items(const ClusterDev& cl, const CandD
         const int64_t comp = live ? (int64_t)mv[u] * park.comp[u][slot] : 0;
         const int64_t comm = live ? (int64_t)mv[u] * park.comm[u][slot] + ar_busy : 0;
         const int64_t i = (w0 + u) * kWave + lane;
-        out.comp_busy[i] = comp;
-        out.comm_busy[i] = comm;
-        if (out.util) out.util[i] = batch > 0 ? (double)comp / batch_d : 0.0;
+        // the rows are written once and not read again by the library: streaming stores
+        __builtin_nontemporal_store(comp, &out.comp_busy[i]);
+        __builtin_nontemporal_store(comm, &out.comm_busy[i]);
+        if (out.util) __builtin_nontemporal_store(batch > 0 ? (double)comp / batch_d : 0.0, &out.util[i]);
         if (live && s == 0) {
             const int64_t cc = park.cand[u][slot];
             out.batch_ns[cc] = batch;
