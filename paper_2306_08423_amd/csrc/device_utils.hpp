@@ -225,6 +225,12 @@ __device__ __forceinline__ int64_t allreduce_ns(const ClusterDev& cl, int64_t n,
     const int k = n <= cl.gpus_per_node ? 0 : 1;
     return cl.alpha[k] + (int64_t)udiv64(2ull * (uint64_t)(n - 1) * (uint64_t)bytes, (uint64_t)n * (uint64_t)cl.beta[k]);
 }
+// The same with the reciprocal of n * beta at hand (k_layer_tables keeps it per (variant, pp) row).
+__device__ __forceinline__ int64_t allreduce_ns_by(const ClusterDev& cl, int64_t n, int64_t bytes, double inv_den) {
+    if (n <= 1 || bytes <= 0) return 0;
+    const int k = n <= cl.gpus_per_node ? 0 : 1;
+    return cl.alpha[k] + (int64_t)udiv64_by(2ull * (uint64_t)(n - 1) * (uint64_t)bytes, (uint64_t)n * (uint64_t)cl.beta[k], inv_den);
+}
 __device__ __forceinline__ int64_t alltoall_ns(const ClusterDev& cl, int64_t n, int64_t bytes) {
     if (n <= 1 || bytes <= 0) return 0;
     const int k = n <= cl.gpus_per_node ? 0 : 1;

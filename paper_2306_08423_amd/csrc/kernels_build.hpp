@@ -98,7 +98,25 @@ __global__ __launch_bounds__(64) void k_layer_tables(CostsDev co, ClusterDev cl,
     if (lane == 0) {
         pfa[0] = 0; pba[0] = 0;
         if (base) { pfc[0] = 0; pbc[0] = 0; pg[0] = 0; }
-        for (int k = 0; k < kCombWords; k++) comb[k] = 0;
+        for (int k = 0; k < 4; k++) comb[k] = 0;
+        // what an all-reduce over this row's dp group divides by, as a reciprocal (word 5 of the row's
+        // first entry; word 4 follows below): dp * beta of the group's link class
+        const double den = (double)dp * (double)cl.beta[dp <= cl.gpus_per_node ? 0 : 1];
+        comb[5] = __double_as_longlong(1.0 / den);
+    }
+    {
+        // Link classes of this row's stage boundaries (word 4 of the row's first entry): bit s is set
+        // when the ranks of pipeline positions s and s + 1 start on different nodes.  Ranks are
+        // ordered tp fastest, then dp, then pp, so position s starts at rank s * (N / pp); a position
+        // of at least a node's worth of ranks starts on a node of its own.
+        bool inter = false;
+        if (cl.num_devices % pp == 0 && lane + 1 < pp) {
+            const int64_t span = cl.num_devices / pp, g = cl.gpus_per_node;
+            const int64_t a = span >= g ? lane : (lane * span) / g, b = span >= g ? lane + 1 : ((lane + 1) * span) / g;
+            inter = a != b;
+        }
+        const uint64_t mask = __builtin_amdgcn_ballot_w64(inter);
+        if (lane == 0) comb[4] = (int64_t)mask;
     }
     for (int l0 = 0; l0 < L; l0 += kWave) {
         const int l = l0 + lane;
@@ -420,19 +438,19 @@ struct StageRow {
 // (1 = not a partition, 2 = range); rows of dropped candidates and of idle lanes are zero.
 // Partition check and link classes of one stage: returns nonzero when the candidate's layer
 // bounds are not a partition of [0, L) (a reduction over the candidate's lanes); inter_next /
-// inter_prev say whether the p2p to the next / previous stage crosses nodes.
-__device__ __forceinline__ int stage_check(const ClusterDev& cl, int L, int width, int s, int pp, int dp, int tp,
+// inter_prev say whether the p2p to the next / previous stage crosses nodes, read off the row's
+// mask of inter-node boundaries (k_layer_tables; row0 = first entry of the candidate's (variant, pp)
+// row of Workspace::comb, looked at by the lanes that hold a stage only).
+__device__ __forceinline__ int stage_check(const int64_t* row0, int L, int width, int s, int pp,
                                            int lo, int hi, int& inter_next, int& inter_prev) {
     int bad = 0;
-    int node = 0;               // node of the stage's first rank (ranks ordered tp fastest, then dp, then pp)
+    inter_next = 0; inter_prev = 0;
     if (s < pp) {
         bad = (hi <= lo) || (hi > L) || (s == 0 && lo != 0) || (s == pp - 1 && hi != L);
-        // a stage of at least a node's worth of ranks starts on a node of its own
-        const int64_t tpdp = (int64_t)tp * dp;
-        node = tpdp >= cl.gpus_per_node ? s : node_of_position(cl, s, (int)tpdp);
+        const uint64_t mask = (uint64_t)row0[4];
+        inter_next = (int)((mask >> s) & 1);
+        inter_prev = (int)(((mask << 1) >> s) & 1);
     }
-    inter_next = node != __builtin_amdgcn_update_dpp(0, node, kDppWaveShl1, 0xf, 0xf, true);
-    inter_prev = node != __builtin_amdgcn_update_dpp(0, node, kDppWaveShr1, 0xf, 0xf, true);
     return group_any(bad != 0, width) ? 1 : 0;
 }
 
@@ -452,7 +470,8 @@ __device__ __forceinline__ int stage_row(const ClusterDev& cl, const Workspace& 
                                          int pp, int v, int m, int dp, int tp, int lo, int hi, StageRow& r) {
     r = StageRow{0, 0, 0, 0, 0, 0, 0};
     int inter_next, inter_prev;
-    const int bad = stage_check(cl, L, width, s, pp, dp, tp, lo, hi, inter_next, inter_prev);
+    const int bad = stage_check(ws.comb + (size_t)((v * kMaxPP + pp - 1) * (L + 1)) * kCombWords, L, width, s, pp, lo, hi,
+                                inter_next, inter_prev);
     if (s < pp && !bad) {
         const size_t vr = (size_t)v * (L + 1), rr = (size_t)(v * kMaxPP + pp - 1) * (L + 1);
         r.FC = ws.pfc[vr + hi] - ws.pfc[vr + lo];
@@ -475,15 +494,17 @@ __device__ __forceinline__ int stage_row(const ClusterDev& cl, const Workspace& 
 // Workspace::comb.
 struct StageSums {
     int64_t FT, BT, CP, G, PF, PB;
+    double inv_ar;              // 1 / (dp * beta) of the gradient all-reduce over the row's dp group
 };
 
 __device__ __forceinline__ int stage_sums(const ClusterDev& cl, const Workspace& ws, int L, int width, int s,
                                           int pp, int v, int m, int dp, int tp, int lo, int hi, StageSums& r) {
-    r = StageSums{0, 0, 0, 0, 0, 0};
+    r = StageSums{0, 0, 0, 0, 0, 0, 0.0};
     int inter_next, inter_prev;
-    const int bad = stage_check(cl, L, width, s, pp, dp, tp, lo, hi, inter_next, inter_prev);
+    const int64_t* row = ws.comb + (size_t)((v * kMaxPP + pp - 1) * (L + 1)) * kCombWords;
+    const int bad = stage_check(row, L, width, s, pp, lo, hi, inter_next, inter_prev);
     if (s < pp && !bad) {
-        const int64_t* row = ws.comb + (size_t)((v * kMaxPP + pp - 1) * (L + 1)) * kCombWords;
+        r.inv_ar = __longlong_as_double(row[5]);
         const longlong2* e_hi = (const longlong2*)(row + hi * kCombWords);
         const longlong2* e_lo = (const longlong2*)(row + lo * kCombWords);
         const longlong2 h0 = e_hi[0], h1 = e_hi[1], l0 = e_lo[0], l1 = e_lo[1];
@@ -498,7 +519,7 @@ __device__ __forceinline__ int stage_sums(const ClusterDev& cl, const Workspace&
     const int drop = bad ? 1 : (range ? 2 : 0);
     // rare: the branch is taken by the whole wavefront or not at all
     if (__builtin_amdgcn_ballot_w64(drop != 0) != 0) {
-        if (drop) r = StageSums{0, 0, 0, 0, 0, 0};
+        if (drop) r = StageSums{0, 0, 0, 0, 0, 0, 0.0};
     }
     return drop;
 }

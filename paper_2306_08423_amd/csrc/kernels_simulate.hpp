@@ -304,7 +304,7 @@ __device__ __forceinline__ void simulate_items(const ClusterDev& cl, const CandD
         // what only the epilogue needs waits in LDS
         park.comp[u][slot] = r.CP;                                         // computation per micro-batch
         park.comm[u][slot] = r.FT + r.BT - r.CP + r.PF + r.PB;             // communication per micro-batch
-        park.ar[u][slot] = (cl.bucket > 0 || !has_ar) ? 0 : allreduce_ns(cl, dp, r.G);  // single trailing all-reduce
+        park.ar[u][slot] = (cl.bucket > 0 || !has_ar) ? 0 : allreduce_ns_by(cl, dp, r.G, r.inv_ar);  // single trailing all-reduce
         park.cand[u][slot] = (int32_t)c;
         park.dp[u][slot] = dp;
         park.misc[u][slot] = lo | (hi << 8) | ((int)has_ar << 16) | ((drop ? 1 : 0) << 17) | (v << 18);

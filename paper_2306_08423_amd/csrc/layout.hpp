@@ -59,8 +59,11 @@ struct Workspace {
     int64_t *p2p;                  // [(variant*L + l)*2 + link class]: p2p event of the activation after layer l
     // The same sums arranged for simulate, row = variant*kMaxPP + (pp-1), six words per entry l:
     //   pfc+pfa, pbc+pba | pfc+pbc, pg | p2p event (intra-, inter-node) of the activation that
-    //   enters layer l (zero at l = 0)
-    // so that a stage's composed events come from two neighbouring-in-memory places.
+    //   enters layer l
+    // so that a stage's composed events come from two neighbouring-in-memory places.  No activation
+    // enters layer 0: the last two words of a row's first entry hold the row's mask of inter-node
+    // stage boundaries (bit s: positions s and s + 1 start on different nodes) and, as a double, the
+    // reciprocal of dp * beta of the gradient all-reduce over the row's dp group.
     int64_t *comb;
     int32_t *key;                  // [C] ordering bin | variant << 24, -1 = not simulated
     int32_t *bin_count;            // [kBins]
