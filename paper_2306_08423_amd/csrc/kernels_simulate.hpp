@@ -76,6 +76,17 @@ __device__ __forceinline__ double from_lanes(double x, int byte_addr) {
     return __hiloint2double(hi, lo);
 }
 
+// Value held by the next / previous lane of the wavefront, the 64 lanes taken as a ring.
+template <int CTRL>
+__device__ __forceinline__ double dpp_move_f64(double x) {
+    int lo = __double2loint(x), hi = __double2hiint(x);
+    lo = __builtin_amdgcn_update_dpp(0, lo, CTRL, 0xf, 0xf, true);
+    hi = __builtin_amdgcn_update_dpp(0, hi, CTRL, 0xf, 0xf, true);
+    return __hiloint2double(hi, lo);
+}
+constexpr int kDppWaveRol1 = 0x134;   // lane i reads lane i+1, lane 63 reads lane 0
+constexpr int kDppWaveRor1 = 0x13C;   // lane i reads lane i-1, lane 0 reads lane 63
+
 // One level for the lanes whose pattern bit is set: own = max(own, nb + lat) + dur.
 // Requires EXEC == all ones on entry (wave-uniform control flow, full wavefronts) and leaves
 // it so.  The trailing s_nop keeps two wait states between the write of `own` and the DPP
@@ -523,6 +534,50 @@ __device__ __forceinline__ void simulate_items(const ClusterDev& cl, const CandD
                     }
                     PBb = shl32(PBb, len);
                 } else if (inB) {
+                    bool packed = false;
+                    if constexpr (U == 2) {
+                        // The cool-down of two items in the lanes of one.  B(s, j) runs at level
+                        // 2 pp - 1 - s + 2 j: a lane has a backward only when level + s is odd, so at any
+                        // level every second lane idles.  The second item is rotated by one lane inside
+                        // each candidate's lanes (lane s holds its stage s - 1, the last stage wraps to
+                        // lane 0; width is even): its stage in lane s runs when level + s is even.  Each
+                        // lane then alternates between the two items level by level, and with the two
+                        // items' registers mixed by lane parity once (set O: what a lane runs on odd
+                        // levels, set E: on even levels) one task step serves both items: the operand of
+                        // an odd level is set E's end time of the next lane (the same item's next stage:
+                        // first item for even lanes, second for odd lanes), and the other way round.  A
+                        // lane without a next stage reads some value and adds -inf.  Six VALU
+                        // instructions per level for the pair instead of eleven.  For candidates that
+                        // fill the wavefront (64 lanes): the ring of lanes is then the DPP wave rotation.
+                        packed = width == kWave && len >= 8;
+                        if (packed) {
+                            const double rOwn = dpp_move_f64<kDppWaveRor1>(sw[1].own), rLat = dpp_move_f64<kDppWaveRor1>(sw[1].pbR),
+                                         rDur = dpp_move_f64<kDppWaveRor1>(sw[1].Bd);
+                            uint32_t PM = PBb | (uint32_t)__builtin_amdgcn_update_dpp(0, (int)PBb, kDppWaveRor1, 0xf, 0xf, true);
+                            double oOwn = even_s ? sw[0].own : rOwn, oLat = even_s ? sw[0].pbR : rLat, oDur = even_s ? sw[0].Bd : rDur;
+                            double eOwn = even_s ? rOwn : sw[0].own, eLat = even_s ? rLat : sw[0].pbR, eDur = even_s ? rDur : sw[0].Bd;
+                            int j = 0;
+                            if (((l0 + k) & 1) == 0) {
+                                double nb = dpp_move_f64<kDppWaveRol1>(oOwn);
+                                DISTSIM_STEP1(PM, eOwn, nb, eLat, eDur);
+                                j = 1;
+                            }
+                            for (; j + 1 < len; j += 2) {
+                                double na = dpp_move_f64<kDppWaveRol1>(eOwn);
+                                DISTSIM_STEP1(PM, oOwn, na, oLat, oDur);
+                                double nb = dpp_move_f64<kDppWaveRol1>(oOwn);
+                                DISTSIM_STEP1(PM, eOwn, nb, eLat, eDur);
+                            }
+                            if (j < len) {
+                                double na = dpp_move_f64<kDppWaveRol1>(eOwn);
+                                DISTSIM_STEP1(PM, oOwn, na, oLat, oDur);
+                            }
+                            sw[0].own = even_s ? oOwn : eOwn;
+                            sw[1].own = dpp_move_f64<kDppWaveRol1>(even_s ? eOwn : oOwn);
+                            PBb = shl32(PBb, len);
+                        }
+                    }
+                    if (!packed)
                     for (int j = 0; j < len; j++) {
                         if constexpr (U == 1) {
                             double fr = from_next_lane(sw[0].own);
