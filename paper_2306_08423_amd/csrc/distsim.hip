@@ -33,7 +33,7 @@ struct distsim_ctx {
     int device = 0;
     int num_cus = 256;
     int64_t split_min_items = kSplitMinItems;   // lists of fewer wave-items go through k_simulate alone
-    int64_t grid_per_cu = 128;                  // workgroups per CU of the sweep launches (at most)
+    int64_t grid_per_cu = 128;                  // groups of four wavefronts per CU of the sweep launches (at most)
     // k_simulate_gpipe runs next to k_simulate on a stream of the context (default priority),
     // forked from and joined to the caller's stream with the two events
     hipStream_t side = nullptr;
@@ -175,7 +175,7 @@ size_t carve_events(distsim_events* ev, void* base, int32_t L, int32_t V, int64_
 // the grid is many times what is resident at once and the dispatcher evens the load out.
 int simulate_grid(const distsim_ctx* ctx, int64_t C) {
     const int64_t want = (int64_t)ctx->num_cus * ctx->grid_per_cu;
-    const int64_t need = (C + 7) / 8;                         // blocks of 4 waves, 2 items per wave
+    const int64_t need = (C + 7) / 8;                         // in groups of 4 wavefronts (the launch multiplies by 256 / kSimBlock), 2 items per wavefront
     return (int)(need < want ? (need < 1 ? 1 : need) : want);
 }
 
@@ -406,22 +406,22 @@ int distsim_simulate(distsim_ctx* ctx, const distsim_cluster* cluster, const dis
     // wavefronts only, never a partial block.
     if (cl.blocking == 2) {
         Timer t(ctx, st, DISTSIM_K_SIMULATE);
-        hipLaunchKernelGGL(k_simulate_links, dim3(simulate_grid(ctx, C)), dim3(kSimBlock), 0, st, co, cl, ca, ws, ev, out);
+        hipLaunchKernelGGL(k_simulate_links, dim3(simulate_grid(ctx, C) * (256 / kSimBlock)), dim3(kSimBlock), 0, st, co, cl, ca, ws, ev, out);
     } else if (C < ctx->split_min_items) {
         // a list of fewer candidates than that has fewer wave-items too: k_simulate takes all of it
         Timer t(ctx, st, DISTSIM_K_SIMULATE);
-        hipLaunchKernelGGL(k_simulate, dim3(general_grid(ctx, C)), dim3(kSimBlock), 0, st, co, cl, ca, ws, ev, out);
+        hipLaunchKernelGGL(k_simulate, dim3(general_grid(ctx, C) * (256 / kSimBlock)), dim3(kSimBlock), 0, st, co, cl, ca, ws, ev, out);
     } else {
         // k_simulate and, for the pairs of GPipe items that it leaves out, k_simulate_gpipe, side
         // by side: they write different rows.  The timer of k_simulate spans both.
         Timer t(ctx, st, DISTSIM_K_SIMULATE);
         HIP_TRY(hipEventRecord(ctx->fork, st));
         HIP_TRY(hipStreamWaitEvent(ctx->side, ctx->fork, 0));
-        hipLaunchKernelGGL(k_simulate, dim3(general_grid(ctx, C)), dim3(kSimBlock), 0, st, co, cl, ca, ws, ev, out);
+        hipLaunchKernelGGL(k_simulate, dim3(general_grid(ctx, C) * (256 / kSimBlock)), dim3(kSimBlock), 0, st, co, cl, ca, ws, ev, out);
         {
             // its first threads mark the rejected candidates (k_sim_init's work)
             Timer tg(ctx, ctx->side, DISTSIM_K_SIMULATE_GPIPE);
-            hipLaunchKernelGGL(k_simulate_gpipe, dim3(gpipe_grid(ctx, C)), dim3(kSimBlock), 0, ctx->side, co, cl, ca, ws, ev, out, C);
+            hipLaunchKernelGGL(k_simulate_gpipe, dim3(gpipe_grid(ctx, C) * (256 / kSimBlock)), dim3(kSimBlock), 0, ctx->side, co, cl, ca, ws, ev, out, C);
         }
         HIP_TRY(hipEventRecord(ctx->join, ctx->side));
         HIP_TRY(hipStreamWaitEvent(st, ctx->join, 0));
