@@ -553,29 +553,40 @@ __device__ __forceinline__ void simulate_items(const ClusterDev& cl, const CandD
                         // fill the wavefront (64 lanes): the ring of lanes is then the DPP wave rotation.
                         packed = width == kWave && len >= 8;
                         if (packed) {
-                            const double rOwn = dpp_move_f64<kDppWaveRor1>(sw[1].own), rLat = dpp_move_f64<kDppWaveRor1>(sw[1].pbR),
-                                         rDur = dpp_move_f64<kDppWaveRor1>(sw[1].Bd);
+                            // mixed in place: item 0's registers become set O, item 1's set E
+                            {
+                                const double rOwn = dpp_move_f64<kDppWaveRor1>(sw[1].own), rLat = dpp_move_f64<kDppWaveRor1>(sw[1].pbR),
+                                             rDur = dpp_move_f64<kDppWaveRor1>(sw[1].Bd);
+                                sw[1].own = even_s ? rOwn : sw[0].own; sw[1].pbR = even_s ? rLat : sw[0].pbR; sw[1].Bd = even_s ? rDur : sw[0].Bd;
+                                sw[0].own = even_s ? sw[0].own : rOwn; sw[0].pbR = even_s ? sw[0].pbR : rLat; sw[0].Bd = even_s ? sw[0].Bd : rDur;
+                            }
                             uint32_t PM = PBb | (uint32_t)__builtin_amdgcn_update_dpp(0, (int)PBb, kDppWaveRor1, 0xf, 0xf, true);
-                            double oOwn = even_s ? sw[0].own : rOwn, oLat = even_s ? sw[0].pbR : rLat, oDur = even_s ? sw[0].Bd : rDur;
-                            double eOwn = even_s ? rOwn : sw[0].own, eLat = even_s ? rLat : sw[0].pbR, eDur = even_s ? rDur : sw[0].Bd;
                             int j = 0;
                             if (((l0 + k) & 1) == 0) {
-                                double nb = dpp_move_f64<kDppWaveRol1>(oOwn);
-                                DISTSIM_STEP1(PM, eOwn, nb, eLat, eDur);
+                                double nb = dpp_move_f64<kDppWaveRol1>(sw[0].own);
+                                DISTSIM_STEP1(PM, sw[1].own, nb, sw[1].pbR, sw[1].Bd);
                                 j = 1;
                             }
                             for (; j + 1 < len; j += 2) {
-                                double na = dpp_move_f64<kDppWaveRol1>(eOwn);
-                                DISTSIM_STEP1(PM, oOwn, na, oLat, oDur);
-                                double nb = dpp_move_f64<kDppWaveRol1>(oOwn);
-                                DISTSIM_STEP1(PM, eOwn, nb, eLat, eDur);
+                                double na = dpp_move_f64<kDppWaveRol1>(sw[1].own);
+                                DISTSIM_STEP1(PM, sw[0].own, na, sw[0].pbR, sw[0].Bd);
+                                double nb = dpp_move_f64<kDppWaveRol1>(sw[0].own);
+                                DISTSIM_STEP1(PM, sw[1].own, nb, sw[1].pbR, sw[1].Bd);
                             }
                             if (j < len) {
-                                double na = dpp_move_f64<kDppWaveRol1>(eOwn);
-                                DISTSIM_STEP1(PM, oOwn, na, oLat, oDur);
+                                double na = dpp_move_f64<kDppWaveRol1>(sw[1].own);
+                                DISTSIM_STEP1(PM, sw[0].own, na, sw[0].pbR, sw[0].Bd);
                             }
-                            sw[0].own = even_s ? oOwn : eOwn;
-                            sw[1].own = dpp_move_f64<kDppWaveRol1>(even_s ? eOwn : oOwn);
+                            // and apart again
+                            {
+                                const double aOwn = even_s ? sw[0].own : sw[1].own, aLat = even_s ? sw[0].pbR : sw[1].pbR,
+                                             aDur = even_s ? sw[0].Bd : sw[1].Bd;
+                                const double bOwn = even_s ? sw[1].own : sw[0].own, bLat = even_s ? sw[1].pbR : sw[0].pbR,
+                                             bDur = even_s ? sw[1].Bd : sw[0].Bd;
+                                sw[0].own = aOwn; sw[0].pbR = aLat; sw[0].Bd = aDur;
+                                sw[1].own = dpp_move_f64<kDppWaveRol1>(bOwn); sw[1].pbR = dpp_move_f64<kDppWaveRol1>(bLat);
+                                sw[1].Bd = dpp_move_f64<kDppWaveRol1>(bDur);
+                            }
                             PBb = shl32(PBb, len);
                         }
                     }
