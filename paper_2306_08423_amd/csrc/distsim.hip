@@ -419,9 +419,14 @@ int distsim_simulate(distsim_ctx* ctx, const distsim_cluster* cluster, const dis
         HIP_TRY(hipStreamWaitEvent(ctx->side, ctx->fork, 0));
         hipLaunchKernelGGL(k_simulate, dim3(general_grid(ctx, C) * (256 / kSimBlock)), dim3(kSimBlock), 0, st, co, cl, ca, ws, ev, out);
         {
-            // its first threads mark the rejected candidates (k_sim_init's work)
+            // its first threads mark the rejected candidates (k_sim_init's work).  Its items all cost about
+            // the same, so a wavefront may take several pairs in turn: a quarter of the wavefronts (measured:
+            // span -1.5 %, and a quarter of the spill stores, which every wavefront makes once) -- unless the
+            // all-reduce is bucketed: then an item's epilogue walks its layers with a trip to the tables
+            // every few of them, and the launch needs the wavefronts to hide those (measured: +3 % with fewer)
             Timer tg(ctx, ctx->side, DISTSIM_K_SIMULATE_GPIPE);
-            hipLaunchKernelGGL(k_simulate_gpipe, dim3(gpipe_grid(ctx, C) * (256 / kSimBlock)), dim3(kSimBlock), 0, ctx->side, co, cl, ca, ws, ev, out, C);
+            const int per_group = cl.bucket > 0 ? 256 / kSimBlock : 1;
+            hipLaunchKernelGGL(k_simulate_gpipe, dim3(gpipe_grid(ctx, C) * per_group), dim3(kSimBlock), 0, ctx->side, co, cl, ca, ws, ev, out, C);
         }
         HIP_TRY(hipEventRecord(ctx->join, ctx->side));
         HIP_TRY(hipStreamWaitEvent(st, ctx->join, 0));
