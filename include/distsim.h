@@ -135,7 +135,7 @@ typedef struct distsim_ctx distsim_ctx;   /* opaque; host-side state only (devic
  * A context serves one host thread at a time.
  * One tuning knob is read from the environment here: DISTSIM_SPLIT_MIN_ITEMS, the list length
  * from which the two calls use the second stream and distsim_simulate gives the GPipe
- * candidates a launch of their own (default 16384; 0 = always).  Results do not depend on it. */
+ * candidates a launch of their own (default 262144 candidates; 0 = always).  Results do not depend on it. */
 int         distsim_create(distsim_ctx **out, int hip_device);
 void        distsim_destroy(distsim_ctx *ctx);
 /* Text of the last error on this context; valid until the next call on it. */

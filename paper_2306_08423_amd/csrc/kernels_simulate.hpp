@@ -706,7 +706,7 @@ __device__ __forceinline__ void simulate_items(const ClusterDev& cl, const CandD
 // (about one pair per wavefront for large lists: the hardware's dispatch order is the load
 // balancing, so the order of the pairs is longest first, see PairOrder).
 
-constexpr int64_t kSplitMinItems = 16384;      // default list length (wave-items) from which two launches share the items
+constexpr int64_t kSplitMinItems = 262144;     // default list length (candidates) from which two launches share the items
 
 // The header is read through the constant address space: nothing writes it while a sweep runs,
 // and a wave-uniform index then makes every read a scalar load that needs no vector register.
