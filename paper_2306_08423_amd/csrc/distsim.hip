@@ -354,7 +354,7 @@ int distsim_build_events(distsim_ctx* ctx, const distsim_costs* costs, const dis
         if (cluster->dp_bucket_bytes > 0)
             for (int k = kClasses - 1; k >= 0 && ((int64_t)costs->L << k) >= 16 * kWave; k--) first_whole = k;
         hipLaunchKernelGGL(k_scatter, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st, ca, C, ws, ev,
-                           ctx->split_min_items, first_whole);
+                           C >= ctx->split_min_items ? 0 : INT64_MAX, first_whole);     // two launches: the same rule as distsim_simulate's, by candidates
     }
     if (beside) HIP_TRY(hipStreamWaitEvent(st, ctx->join, 0));       // what follows on the caller's stream sees the tables
     if (C > 0) {

@@ -298,7 +298,8 @@ __global__ __launch_bounds__(kBinsBlock) void k_bins(Workspace ws, int64_t stage
 // Order in which the sweep kernels take the pairs of their wave-items.  Two launches share the
 // items: in every class the leading items that hold only GPipe candidates (hdr[H_GPIPE_ITEMS +
 // class], an even number) belong to k_simulate_gpipe, all others to k_simulate; a list of fewer
-// than split_min_items wave-items is not worth two launches and goes to k_simulate whole.
+// than split_min_items wave-items is not worth two launches and goes to k_simulate whole (the host passes 0 or
+// the largest integer: it decides by the number of candidates, as it does when it launches the sweeps).
 // Inside a class the items are sorted by micro-batch count, longest sweep first, but the classes
 // follow one another, so in visiting order the lengths form a saw-tooth: taken in that order the
 // long items of the narrower classes would start late and a launch would end with a few long
