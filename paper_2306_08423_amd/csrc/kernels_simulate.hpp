@@ -648,11 +648,12 @@ __device__ __forceinline__ void simulate_items(const ClusterDev& cl, const CandD
                 const int64_t* row = ws.comb + (size_t)((v * kMaxPP + ppv[u] - 1) * (L + 1)) * kCombWords;
                 const int64_t startB = endB - (int64_t)sw[u].Bd;
                 const int64_t tot_hi = row[hi * kCombWords + 1], g_hi = row[hi * kCombWords + 3];
-                const int64_t ar_cap = allreduce_ns(cl, dp, cl.bucket);
+                const double inv_ar = __longlong_as_double(row[5]);      // 1 / (dp * beta) of the row's all-reduce group
+                const int64_t ar_cap = allreduce_ns_by(cl, dp, cl.bucket, inv_ar);
                 const int64_t G = g_hi - row[lo * kCombWords + 3];
                 const int64_t full = (int64_t)udiv64_by((uint64_t)G, (uint64_t)cl.bucket, cl.inv_bucket);
                 const int64_t rest = G - full * cl.bucket;
-                const int64_t dlast = rest > 0 ? allreduce_ns(cl, dp, rest) : 0;
+                const int64_t dlast = rest > 0 ? allreduce_ns_by(cl, dp, rest, inv_ar) : 0;
                 ar_busy = full * ar_cap + dlast;
                 nar = full + (rest > 0 ? 1 : 0);
                 const int64_t all = startB + tot_hi + ar_busy;          // r_l + events from l down = all - (time below l) - (events above l)
